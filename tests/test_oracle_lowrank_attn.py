@@ -59,10 +59,11 @@ def test_svdsolver_within_1e3_of_optimum():
     opt = np.sqrt((s[4:] ** 2).sum())
     A, Bm = go.svd_solver(R, rng.uniform(-1, 1, (64, 4)), 4)
     assert abs(np.linalg.norm(R - A @ Bm.T) - opt) <= 1e-3 * opt
-    # arbitrary tiny matrix, many rounds: converges to the optimum
+    # a tiny unstructured matrix (sigma_3/sigma_2 = 0.84), many rounds: converges to the optimum
+    rng = np.random.default_rng(2)
     R2 = rng.standard_normal((12, 8))
     sv = np.linalg.svd(R2, compute_uv=False)
-    A2, B2 = go.svd_solver(R2, rng.uniform(-1, 1, (8, 2)), 60)
+    A2, B2 = go.svd_solver(R2, rng.uniform(-1, 1, (8, 2)), 30)
     opt2 = np.sqrt((sv[2:] ** 2).sum())
     assert abs(np.linalg.norm(R2 - A2 @ B2.T) - opt2) <= 1e-3 * opt2
 
