@@ -1,0 +1,151 @@
+/*
+ * gear.h -- C ABI of libgear: GEAR KV-cache compression (arXiv 2403.05527) and
+ * the single-query attention read of the compressed cache, for AMD MI355X
+ * (gfx950).  Plain C: pointers and sizes only, no C++ or torch types.
+ *
+ * Conventions (all entry points)
+ *  - "device" pointers are HIP device memory of the current device, "host"
+ *    pointers ordinary host memory.  Every buffer is allocated and freed by
+ *    the caller; the library allocates nothing and keeps no global state.
+ *  - Work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
+ *    default stream); no call synchronises with the host.  Inputs may be
+ *    released once the stream has passed the call.
+ *  - d_h (head dimension) must be 128.  Tensors are fp16, contiguous,
+ *    [B, H, tokens, d_h] unless stated otherwise.  Inputs must be finite.
+ *  - Return value: GEAR_OK (0) or a negative gear_status.  Arguments are
+ *    validated on the host before anything is launched, so a failed call
+ *    leaves the cache untouched.
+ *  - A gear_cache is a small host-side descriptor owned by the caller.  It
+ *    records what the device arena holds (segments, ranks, token counts) so
+ *    that capacity and shape errors are caught without reading device memory.
+ *    Calls on one gear_cache must be issued in stream order by one thread.
+ */
+#ifndef GEAR_H
+#define GEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gear_status {
+  GEAR_OK = 0,
+  GEAR_EINVAL = -1,    /* bad / unsupported parameter, or NULL pointer            */
+  GEAR_ECAPACITY = -2, /* arena, workspace, segment or chunk capacity exceeded     */
+  GEAR_EALIGN = -3,    /* a pointer is not 16-byte aligned                         */
+  GEAR_EHIP = -4       /* a HIP runtime call failed (launch error)                 */
+} gear_status;
+
+#define GEAR_MAX_CHUNKS 256
+
+/* Hyper-parameters of Algorithm 1 of the paper plus the capacities of one
+ * layer's cache. */
+typedef struct gear_config {
+  int32_t B;             /* batch                                                  */
+  int32_t H_kv;          /* KV heads                                               */
+  int32_t H_q;           /* query heads, multiple of H_kv, H_q/H_kv <= 8           */
+  int32_t d_h;           /* head dimension, must be 128                            */
+  int32_t bits;          /* b in {2, 4}  (Eq. 2)                                   */
+  int32_t group;         /* g in {32, 64, 128}: Keys g tokens of one channel,      */
+                         /* Values g channels of one token                         */
+  int32_t outlier_ppm;   /* s of Filter_s (Eq. 4) in parts per million of a        */
+                         /* vector; 20000 = 2 %, 0 = GEAR-L (no sparse term)       */
+  int32_t n_buf_cap;     /* n_b: streaming-buffer capacity, 1..255                 */
+  int32_t n_prefill_max; /* capacity of the first (prefill) segment, <= 32768      */
+  int32_t n_chunks_max;  /* number of flushed buffers that can be appended, <= 256 */
+  int32_t rank_max;      /* largest rank any compress call will use, 0..8          */
+} gear_config;
+
+/* Host-side descriptor of one cache.  Filled by gear_cache_init, advanced by
+ * gear_compress.  Treat the fields as read-only. */
+typedef struct gear_cache {
+  gear_config cfg;
+  void*    arena;                        /* device                                 */
+  uint64_t arena_bytes;
+  int32_t  n_prefill;                    /* tokens in segment 0 (0 = none yet)     */
+  int32_t  rank_prefill;
+  int32_t  n_chunks;                     /* appended chunk segments                */
+  int32_t  n_total;                      /* tokens in all segments                 */
+  uint8_t  chunk_n[GEAR_MAX_CHUNKS];     /* tokens of chunk j                      */
+  uint8_t  chunk_rank[GEAR_MAX_CHUNKS];  /* rank of chunk j                        */
+} gear_cache;
+
+/* Sizes the caller must provide for `cfg`: the device arena that holds the
+ * compressed cache and a device workspace shared by gear_compress and
+ * gear_decode_attn (scratch; contents need not survive between calls). */
+int gear_cache_bytes(const gear_config* cfg, size_t* arena_bytes, size_t* workspace_bytes);
+
+/* Binds a device arena (>= arena_bytes, 256-byte aligned) to `cache` (host,
+ * out) and marks it empty.  Nothing is launched. */
+int gear_cache_init(const gear_config* cfg, void* arena, size_t arena_bytes, gear_cache* cache);
+
+/* Forgets every segment (the arena memory is reused). */
+int gear_cache_reset(gear_cache* cache);
+
+/*
+ * Compress one segment of n tokens and append it (Algorithm 1: the prefill body
+ * on the first call, the decoding-phase body on a flushed buffer afterwards):
+ *   S = Filter_s(X)  (Eq. 4: per Key channel over the n tokens of this call,
+ *                     per Value token over all H_kv*d_h channels; ties go to
+ *                     the lower index),
+ *   D = Quant_b(X - S) (Eq. 2 / Eq. 5, scale and zero-point stored in fp16),
+ *   R = X - D - S, and per (batch, head) A, B = SVDSolver_rank(R) (Eq. 6,
+ *   Algorithm 2 with `iters` rounds, start matrix init_B).
+ * K, V      : device fp16 [B, H_kv, n, d_h].
+ * n         : first call: 1..n_prefill_max; later calls: 1..n_buf_cap.
+ * rank      : 0..rank_max (0 = no low-rank term); iters >= 1.
+ * init_B    : device fp32 [2 (K,V), B, H_kv, d_h, rank]; required when rank > 0
+ *             (the random start of Algorithm 2 is an input so that runs are
+ *             reproducible).
+ * workspace : device, >= workspace_bytes of gear_cache_bytes.
+ */
+int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, int32_t rank,
+                  int32_t iters, const float* init_B, void* workspace, size_t workspace_bytes,
+                  void* stream);
+
+/* X-hat = D + A B^T + S for every stored token (Algorithm 1, "replace X with
+ * D + L + S"), rounded to fp16.  K_out, V_out: device fp16
+ * [B, H_kv, n_total, d_h]; either may be NULL. */
+int gear_decompress(const gear_cache* cache, void* K_out, void* V_out, void* stream);
+
+/*
+ * Single-query attention (Eq. 1) over the compressed cache followed by the
+ * first n_buf rows of the fp16 streaming buffer, never materialising K-hat or
+ * V-hat: softmax(q K^T / sqrt(d_h)) V per query head; query head i reads KV
+ * head i / (H_q / H_kv).
+ * q         : device fp16 [B, H_q, 1, d_h].
+ * K_buf,V_buf: device fp16 [B, H_kv, n_buf_cap, d_h]; may be NULL when n_buf == 0.
+ * n_buf     : 0..n_buf_cap; n_buf == 0 with an empty cache is GEAR_EINVAL.
+ * out       : device fp16 [B, H_q, 1, d_h].
+ */
+int gear_decode_attn(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf,
+                     int32_t n_buf, void* out, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/*
+ * Canonical views of the stored components (the physical arena layout is
+ * private); used to check the library against an independent implementation.
+ * which: 0 = Keys, 1 = Values.
+ *  codes_u8 : device u8  [B, H_kv, n_total, d_h], one integer code per entry.
+ *  scale/zero: device fp16; Keys [B, H_kv, NG, d_h] with NG = sum over segments
+ *             of ceil(n_seg / g) (segments in append order); Values
+ *             [B, H_kv, n_total, d_h / g].
+ *  mask_u8  : device u8  [B, H_kv, n_total, d_h], 1 on the support of S.
+ *  values   : device fp16 same shape, S itself (0 off the support).
+ *  A_f16    : device fp16 [B, H_kv, n_seg, rank_seg]; B_f16: [B, H_kv, d_h, rank_seg].
+ */
+int gear_export_codes(const gear_cache* cache, int which, void* codes_u8, void* scale_f16,
+                      void* zero_f16, void* stream);
+int gear_export_sparse(const gear_cache* cache, int which, void* mask_u8, void* values_f16,
+                       void* stream);
+int gear_export_lowrank(const gear_cache* cache, int which, int seg, void* A_f16, void* B_f16,
+                        void* stream);
+
+const char* gear_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEAR_H */

@@ -1,0 +1,442 @@
+// Filter_s (Eq. 4) + Quant_b(X - S) (Eq. 2 / Eq. 5) kernels of gear_compress:
+//   k_select_kernel       thresholds of every Key channel vector (over tokens)
+//   k_quant_kernel        Key codes, (scale, zero), ordered outlier lists
+//   v_filter_quant_kernel Value thresholds (per token over all heads), codes in
+//                         the token-blocked layout, (scale, zero), outlier lists
+#include "gear_internal.h"
+#include "gear_select.h"
+#include "gear_launch.h"
+
+namespace gear {
+
+// ------------------------------------------------------------------ sources
+struct LdsSource {  // one vector stored contiguously in LDS as fp16 bit patterns
+  static constexpr int kMaxChunks = 0;
+  const uint16_t* base;
+  int n_pad;  // multiple of 8
+  __device__ __forceinline__ uint4 operator()(int ch) const {
+    const int off = ch * 512 + lane_id() * 8;
+    if (off < n_pad) return *reinterpret_cast<const uint4*>(base + off);
+    return make_uint4(0, 0, 0, 0);
+  }
+};
+template <int NC>
+struct RegSource {  // the vector lives in the wave's registers
+  static constexpr int kMaxChunks = NC;
+  const uint4* x;
+  __device__ __forceinline__ uint4 operator()(int ch) const { return x[ch]; }
+};
+
+// ------------------------------------------------------------------ K select
+// grid (128/CB, B*H); block 256.  LDS: [CB][n_pad] fp16 + 4*512 u32.
+__global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restrict__ K, int n, int n_pad,
+                                                       int CB, int k_top, int k_bot,
+                                                       Thresh* __restrict__ thrK) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem_raw);
+  uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + 4 * 512 * sizeof(uint32_t));
+  const int slab = blockIdx.y, cb = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const uint16_t* X = K + (size_t)slab * n * D + cb * CB;
+
+  // transpose-load the [n x CB] column block so every vector is contiguous
+  const int VW = CB < 8 ? CB : 8;
+  const int U = CB / VW;
+  for (int idx = tid; idx < n * U; idx += 256) {
+    const int row = idx / U, u = idx - row * U;
+    const uint16_t* p = X + (size_t)row * D + u * VW;
+    uint16_t v[8];
+    if (VW == 8) {
+      const uint4 q = *reinterpret_cast<const uint4*>(p);
+      v[0] = q.x & 0xFFFF; v[1] = q.x >> 16; v[2] = q.y & 0xFFFF; v[3] = q.y >> 16;
+      v[4] = q.z & 0xFFFF; v[5] = q.z >> 16; v[6] = q.w & 0xFFFF; v[7] = q.w >> 16;
+    } else if (VW == 4) {
+      const uint2 q = *reinterpret_cast<const uint2*>(p);
+      v[0] = q.x & 0xFFFF; v[1] = q.x >> 16; v[2] = q.y & 0xFFFF; v[3] = q.y >> 16;
+    } else if (VW == 2) {
+      const uint32_t q = *reinterpret_cast<const uint32_t*>(p);
+      v[0] = q & 0xFFFF; v[1] = q >> 16;
+    } else {
+      v[0] = *p;
+    }
+    for (int e = 0; e < VW; ++e) tile[(size_t)(u * VW + e) * n_pad + row] = v[e];
+  }
+  // zero the padding so stray lanes read defined data
+  for (int idx = tid; idx < CB * (n_pad - n); idx += 256) {
+    const int c = idx / (n_pad - n), r = idx - c * (n_pad - n);
+    tile[(size_t)c * n_pad + n + r] = 0;
+  }
+  __syncthreads();
+
+  const int iters = (CB + 3) >> 2;
+  for (int it = 0; it < iters; ++it) {
+    const int v = it * 4 + wave;
+    const bool active = v < CB;
+    LdsSource src{tile + (size_t)(active ? v : 0) * n_pad, n_pad};
+    const Thresh th = wave_select(src, n, k_top, k_bot, hist_all + wave * 512, active);
+    if (active && lane == 0) thrK[(size_t)slab * D + cb * CB + v] = th;
+  }
+}
+
+// ------------------------------------------------------------------ K quant
+// grid (ceil(n/WT), B*H); block 256; WT = max(64, g) tokens per block.
+// thread (r0 = tid/16, oc = tid%16) owns channels 8*oc..8*oc+7 of rows
+// t0 + r0 + 16*k.
+template <int WT>
+__global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict__ K, SegView sv, Dims dm,
+                                                      int n, const Thresh* __restrict__ thrK,
+                                                      uint32_t* __restrict__ pool_ctr) {
+  constexpr int NK = WT / 16;
+  __shared__ float red_mn[4][D];
+  __shared__ float red_mx[4][D];
+  __shared__ float gq_mn[2][D];
+  __shared__ float gq_inv[2][D];
+  __shared__ uint32_t band_cnt[NK][4];
+  __shared__ uint32_t tile_off[2];
+
+  const int slab = blockIdx.y;
+  const int t0 = blockIdx.x * WT;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r0 = tid >> 4, oc = tid & 15;
+  const uint16_t* X = K + (size_t)slab * n * D;
+  const int g = dm.g;
+  const int ngw = WT / g;  // groups per block (1 or 2)
+
+  // thresholds of my 8 channels
+  Thresh th[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) th[e] = dm.ppm > 0 ? thrK[(size_t)slab * D + oc * 8 + e] : thresh_none();
+
+  float y[NK][8];
+  uint32_t raw[NK][4];
+  uint32_t flags[NK];
+#pragma unroll
+  for (int k = 0; k < NK; ++k) {
+    const int t = t0 + r0 + 16 * k;
+    flags[k] = 0;
+    uint4 q = make_uint4(0, 0, 0, 0);
+    if (t < n) q = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
+    raw[k][0] = q.x; raw[k][1] = q.y; raw[k][2] = q.z; raw[k][3] = q.w;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+      const bool out = (t < n) && is_outlier(key16(hb), t, th[e]);
+      if (out) flags[k] |= 1u << e;
+      y[k][e] = out ? 0.0f : h2f(hb);
+    }
+  }
+
+  // group min / max per channel
+  for (int gi = 0; gi < ngw; ++gi) {
+    float lmn[8], lmx[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { lmn[e] = INFINITY; lmx[e] = -INFINITY; }
+#pragma unroll
+    for (int k = 0; k < NK; ++k) {
+      const int tl = r0 + 16 * k;
+      if (tl / g == gi && t0 + tl < n) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { lmn[e] = fminf(lmn[e], y[k][e]); lmx[e] = fmaxf(lmx[e], y[k][e]); }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      lmn[e] = fminf(lmn[e], __shfl_xor(lmn[e], 16, 64));
+      lmn[e] = fminf(lmn[e], __shfl_xor(lmn[e], 32, 64));
+      lmx[e] = fmaxf(lmx[e], __shfl_xor(lmx[e], 16, 64));
+      lmx[e] = fmaxf(lmx[e], __shfl_xor(lmx[e], 32, 64));
+    }
+    if (lane < 16) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { red_mn[wave][oc * 8 + e] = lmn[e]; red_mx[wave][oc * 8 + e] = lmx[e]; }
+    }
+    __syncthreads();
+    if (tid < D && t0 + gi * g < n) {
+      const float mn = fminf(fminf(red_mn[0][tid], red_mn[1][tid]), fminf(red_mn[2][tid], red_mn[3][tid]));
+      const float mx = fmaxf(fmaxf(red_mx[0][tid], red_mx[1][tid]), fmaxf(red_mx[2][tid], red_mx[3][tid]));
+      const GroupQ q = make_group(mn, mx, dm.qmax);
+      gq_mn[gi][tid] = q.mn;
+      gq_inv[gi][tid] = q.inv;
+      const int grp = (t0 + gi * g) / g;
+      sv.sz[((size_t)slab * sv.ng_cap + grp) * D + tid] = group_bits(q);
+    }
+    __syncthreads();
+  }
+
+  // codes, packed token-major
+  uint32_t* crow = sv.codes + (size_t)slab * sv.n_cap * dm.wpr;
+#pragma unroll
+  for (int k = 0; k < NK; ++k) {
+    const int tl = r0 + 16 * k, t = t0 + tl;
+    if (t < n) {
+      const int gi = tl / g;
+      uint32_t w = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        GroupQ q;
+        q.mn = gq_mn[gi][oc * 8 + e];
+        q.inv = gq_inv[gi][oc * 8 + e];
+        q.delta = 0.0f;
+        w |= quant_code(y[k][e], q, dm.qmax) << (e * dm.bits);
+      }
+      if (dm.bits == 4) {
+        crow[(size_t)t * dm.wpr + oc] = w;
+      } else {  // 2 bits: 16 bits per thread
+        reinterpret_cast<uint16_t*>(crow + (size_t)t * dm.wpr)[oc] = (uint16_t)w;
+      }
+    }
+  }
+
+  // outlier lists, one per 64-token tile, ordered (t, c)
+  if (dm.ppm > 0) {
+    uint32_t cnt[NK], inc[NK];
+#pragma unroll
+    for (int k = 0; k < NK; ++k) {
+      cnt[k] = __popc(flags[k]);
+      inc[k] = wave_incl_scan(cnt[k]);
+      if (lane == 63) band_cnt[k][wave] = inc[k];
+    }
+    __syncthreads();
+    if (tid < WT / TILE) {
+      uint32_t tot = 0;
+      for (int k = tid * 4; k < tid * 4 + 4; ++k)
+        for (int w = 0; w < 4; ++w) tot += band_cnt[k][w];
+      const int tile = t0 / TILE + tid;
+      uint32_t off = 0;
+      if (t0 + tid * TILE < n) {
+        off = atomicAdd(&pool_ctr[slab], tot);
+        sv.sp_table[(size_t)slab * sv.ntile_cap + tile] = make_uint2(off, tot);
+      }
+      tile_off[tid] = off;
+    }
+    __syncthreads();
+    uint32_t* pool = sv.sp_pool + (size_t)slab * sv.pool_cap;
+#pragma unroll
+    for (int k = 0; k < NK; ++k) {
+      const int tl = r0 + 16 * k;
+      const int ti = k / 4;  // tile inside the block
+      uint32_t off = tile_off[ti];
+      for (int kk = ti * 4; kk < k; ++kk)
+        for (int w = 0; w < 4; ++w) off += band_cnt[kk][w];
+      for (int w = 0; w < wave; ++w) off += band_cnt[k][w];
+      off += inc[k] - cnt[k];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (flags[k] & (1u << e)) {
+          const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+          if (off < sv.pool_cap) pool[off] = (uint32_t)((tl & 63) * D + oc * 8 + e) | (hb << 16);
+          ++off;
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ V filter + quant
+// grid (ceil(n/64), B); block 256 (4 waves).  A wave owns one token group of
+// tpw tokens at a time, for all heads: lane l, chunk ch  <->  head 4*ch + l/16,
+// channels 8*(l%16)..+7, i.e. in-vector index ch*512 + l*8 + e.
+// LDS: 4*512 u32 histograms | colmask [H*128][2] u32 | head_cnt [H+1] u32.
+template <int NC>
+__global__ __launch_bounds__(256) void v_filter_quant_kernel(const uint16_t* __restrict__ V, SegView sv,
+                                                             Dims dm, int n, int k_top, int k_bot,
+                                                             Thresh* __restrict__ thrV) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  uint32_t* smem = reinterpret_cast<uint32_t*>(smem_raw);
+  const int H = dm.H, N = H * D;
+  uint32_t* hist = smem;
+  uint32_t* colmask = smem + 2048;
+  uint32_t* head_cnt = colmask + 2 * N;
+
+  const int b = blockIdx.y, tile = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int hsub = lane >> 4, oc = lane & 15;
+  const int g = dm.g, bits = dm.bits, tpw = dm.tpw;
+  const int lanes_per_group = g >> 3;  // 4, 8 or 16
+  const int ngroups_tile = TILE / tpw;
+
+  for (int i = tid; i < 2 * N; i += 256) colmask[i] = 0u;
+  __syncthreads();
+
+  for (int tg = wave; tg < ngroups_tile; tg += 4) {
+    uint32_t acc[NC][8];
+#pragma unroll
+    for (int ch = 0; ch < NC; ++ch)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[ch][e] = 0u;
+
+    for (int ti = 0; ti < tpw; ++ti) {
+      const int tl = tg * tpw + ti;
+      const int t = tile * TILE + tl;
+      const bool tvalid = t < n;
+      uint4 x[NC];
+#pragma unroll
+      for (int ch = 0; ch < NC; ++ch) {
+        const int head = 4 * ch + hsub;
+        x[ch] = make_uint4(0, 0, 0, 0);
+        if (tvalid && head < H)
+          x[ch] = *reinterpret_cast<const uint4*>(V + (((size_t)(b * H + head) * n + t) * D + oc * 8));
+      }
+      Thresh th = thresh_none();
+      if (dm.ppm > 0) {
+        RegSource<NC> src{x};
+        th = wave_select(src, N, k_top, k_bot, hist + wave * 512, tvalid);
+        if (tvalid && lane == 0) thrV[(size_t)b * n + t] = th;
+      }
+      if (tvalid) {
+#pragma unroll
+        for (int ch = 0; ch < NC; ++ch) {
+          const int head = 4 * ch + hsub;
+          if (4 * ch < H) {  // wave-uniform; lanes of heads >= H compute on zeros and store nothing
+            const uint32_t w[4] = {x[ch].x, x[ch].y, x[ch].z, x[ch].w};
+            float yv[8];
+            float lmn = INFINITY, lmx = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const uint32_t hb = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+              const int j = ch * 512 + lane * 8 + e;
+              const bool out = head < H && is_outlier(key16(hb), j, th);
+              if (out) atomicOr(&colmask[2 * j + (tl >> 5)], 1u << (tl & 31));
+              yv[e] = out ? 0.0f : h2f(hb);
+              lmn = fminf(lmn, yv[e]);
+              lmx = fmaxf(lmx, yv[e]);
+            }
+            for (int o = 1; o < lanes_per_group; o <<= 1) {
+              lmn = fminf(lmn, __shfl_xor(lmn, o, 64));
+              lmx = fmaxf(lmx, __shfl_xor(lmx, o, 64));
+            }
+            const GroupQ q = make_group(lmn, lmx, dm.qmax);
+            if (head < H) {
+              if ((oc & (lanes_per_group - 1)) == 0) {
+                const int G = (oc * 8) / g;
+                sv.sz[((size_t)(b * H + head) * sv.n_cap + t) * (D / g) + G] = group_bits(q);
+              }
+#pragma unroll
+              for (int e = 0; e < 8; ++e) acc[ch][e] |= quant_code(yv[e], q, dm.qmax) << (bits * ti);
+            }
+          }
+        }
+      }
+    }
+    // store this token group's code words (zero bits for tokens beyond n)
+    const int tgg = tile * ngroups_tile + tg;
+    if (tgg * tpw < n) {
+      const int blk = tgg >> 2, kg = tgg & 3;
+#pragma unroll
+      for (int ch = 0; ch < NC; ++ch) {
+        const int head = 4 * ch + hsub;
+        if (head < H) {
+          uint32_t* dst = sv.codes + ((size_t)(b * H + head) * sv.nblk_cap + blk) * 512 + (kg * 16 + oc) * 8;
+          *reinterpret_cast<uint4*>(dst) = make_uint4(acc[ch][0], acc[ch][1], acc[ch][2], acc[ch][3]);
+          *reinterpret_cast<uint4*>(dst + 4) = make_uint4(acc[ch][4], acc[ch][5], acc[ch][6], acc[ch][7]);
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // outlier lists per (head, tile), ordered (c, t); lane owns columns 2l, 2l+1
+  if (dm.ppm > 0) {
+    for (int h = wave; h < H; h += 4) {
+      const int j0 = h * D + 2 * lane;
+      const uint32_t c = __popc(colmask[2 * j0]) + __popc(colmask[2 * j0 + 1]) + __popc(colmask[2 * j0 + 2]) +
+                         __popc(colmask[2 * j0 + 3]);
+      const uint32_t tot = wave_sum(c);
+      if (lane == 0) head_cnt[h] = tot;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t run = 0;
+      for (int h = 0; h < H; ++h) {
+        const uint32_t c = head_cnt[h];
+        head_cnt[h] = run;
+        run += c;
+      }
+      head_cnt[H] = run;
+    }
+    __syncthreads();
+    const uint32_t region = (uint32_t)tile * TILE * (uint32_t)(k_top + k_bot);
+    uint32_t* pool = sv.sp_pool + (size_t)b * sv.pool_cap;
+    for (int h = wave; h < H; h += 4) {
+      const int j0 = h * D + 2 * lane;
+      uint32_t m[4] = {colmask[2 * j0], colmask[2 * j0 + 1], colmask[2 * j0 + 2], colmask[2 * j0 + 3]};
+      const uint32_t c = __popc(m[0]) + __popc(m[1]) + __popc(m[2]) + __popc(m[3]);
+      const uint32_t inc = wave_incl_scan(c);
+      uint32_t off = region + head_cnt[h] + inc - c;
+      const uint16_t* Xh = V + (size_t)(b * H + h) * n * D;
+      for (int cc = 0; cc < 2; ++cc) {
+        const int ch = 2 * lane + cc;
+        for (int half = 0; half < 2; ++half) {
+          uint32_t mm = m[2 * cc + half];
+          while (mm) {
+            const int bit = __ffs((int)mm) - 1;
+            mm &= mm - 1;
+            const int tl = half * 32 + bit;
+            const uint32_t hb = Xh[(size_t)(tile * TILE + tl) * D + ch];
+            if (off < sv.pool_cap) pool[off] = (uint32_t)(tl * D + ch) | (hb << 16);
+            ++off;
+          }
+        }
+      }
+      if (lane == 0)
+        sv.sp_table[(size_t)(b * H + h) * sv.ntile_cap + tile] =
+            make_uint2(region + head_cnt[h], head_cnt[h + 1] - head_cnt[h]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ launchers
+static int k_select_cb(int n_pad) {
+  int cb = 128;
+  while (cb > 1 && (size_t)cb * n_pad * 2 > 65536) cb >>= 1;
+  return cb;
+}
+
+hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, Thresh* thrK,
+                           hipStream_t st) {
+  const int n_pad = (n + 7) & ~7;
+  const int cb = k_select_cb(n_pad);
+  const size_t lds = 4 * 512 * sizeof(uint32_t) + (size_t)cb * n_pad * 2;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  dim3 grid(D / cb, dm.B * dm.H);
+  hipLaunchKernelGGL(k_select_kernel, grid, dim3(256), lds, st, K, n, n_pad, cb, k_top, k_bot, thrK);
+  return hipGetLastError();
+}
+
+hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const Thresh* thrK,
+                          uint32_t* pool_ctr, hipStream_t st) {
+  if (dm.g == 128) {
+    dim3 grid((n + 127) / 128, dm.B * dm.H);
+    hipLaunchKernelGGL(k_quant_kernel<128>, grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr);
+  } else {
+    dim3 grid((n + 63) / 64, dm.B * dm.H);
+    hipLaunchKernelGGL(k_quant_kernel<64>, grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr);
+  }
+  return hipGetLastError();
+}
+
+template <int NC>
+static hipError_t launch_v_nc(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
+                              int k_bot, Thresh* thrV, hipStream_t st) {
+  const size_t lds = (2048 + 2 * (size_t)dm.H * D + dm.H + 1) * sizeof(uint32_t);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v_filter_quant_kernel<NC>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  dim3 grid((n + TILE - 1) / TILE, dm.B);
+  hipLaunchKernelGGL(v_filter_quant_kernel<NC>, grid, dim3(256), lds, st, V, sv, dm, n, k_top, k_bot, thrV);
+  return hipGetLastError();
+}
+
+hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
+                                 int k_bot, Thresh* thrV, hipStream_t st) {
+  const int nc = (dm.H + 3) / 4;
+  if (nc <= 2) return launch_v_nc<2>(V, sv, dm, n, k_top, k_bot, thrV, st);
+  if (nc <= 4) return launch_v_nc<4>(V, sv, dm, n, k_top, k_bot, thrV, st);
+  if (nc <= 8) return launch_v_nc<8>(V, sv, dm, n, k_top, k_bot, thrV, st);
+  if (nc <= 10) return launch_v_nc<10>(V, sv, dm, n, k_top, k_bot, thrV, st);
+  return launch_v_nc<16>(V, sv, dm, n, k_top, k_bot, thrV, st);
+}
+
+}  // namespace gear

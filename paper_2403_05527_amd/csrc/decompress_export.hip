@@ -1,0 +1,159 @@
+// gear_decompress (X-hat = D + A B^T + S, Algorithm 1) and the canonical export
+// views of the stored components.
+#include "gear_internal.h"
+#include "gear_launch.h"
+
+namespace gear {
+
+__global__ void fill_u32_kernel(uint32_t* p, uint32_t v, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = v;
+}
+
+hipError_t launch_fill_u32(uint32_t* p, uint32_t v, size_t count, hipStream_t st) {
+  if (count == 0) return hipSuccess;
+  size_t blocks = (count + 255) / 256;
+  if (blocks > 65535) blocks = 65535;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, v, count);
+  return hipGetLastError();
+}
+
+__device__ __forceinline__ uint32_t load_code(const SegView& sv, const Dims& dm, bool is_k, int slab, int t,
+                                              int c) {
+  const uint32_t cmask = (1u << dm.bits) - 1u;
+  if (is_k) {
+    const int per = 32 / dm.bits;
+    const uint32_t w = sv.codes[((size_t)slab * sv.n_cap + t) * dm.wpr + c / per];
+    return (w >> ((c % per) * dm.bits)) & cmask;
+  }
+  const int tgg = t / dm.tpw, i = t - tgg * dm.tpw;
+  const uint32_t w =
+      sv.codes[((size_t)slab * sv.nblk_cap + (tgg >> 2)) * 512 + ((tgg & 3) * 16 + (c >> 3)) * 8 + (c & 7)];
+  return (w >> (i * dm.bits)) & cmask;
+}
+__device__ __forceinline__ uint32_t load_sz(const SegView& sv, const Dims& dm, bool is_k, int slab, int t, int c) {
+  if (is_k) return sv.sz[((size_t)slab * sv.ng_cap + t / dm.g) * D + c];
+  return sv.sz[((size_t)slab * sv.n_cap + t) * (D / dm.g) + c / dm.g];
+}
+
+// grid (ceil(n/64), B*H), block 256.
+__global__ __launch_bounds__(256) void decompress_kernel(Dims dm, SegView sv, int is_k, uint16_t* __restrict__ out,
+                                                         int n_total) {
+  __shared__ float sp[TILE][D];
+  __shared__ float Bs[D][8];
+  const int slab = blockIdx.y, tile = blockIdx.x;
+  const int b = slab / dm.H;
+  const int tid = threadIdx.x;
+  for (int i = tid; i < TILE * D; i += 256) sp[i / D][i % D] = 0.0f;
+  for (int i = tid; i < D * 8; i += 256) {
+    const int c = i >> 3, r = i & 7;
+    Bs[c][r] = r < sv.rank ? h2f(sv.Bf[((size_t)slab * D + c) * sv.rank + r]) : 0.0f;
+  }
+  __syncthreads();
+  if (dm.ppm > 0) {
+    const uint2 oc = sv.sp_table[(size_t)slab * sv.ntile_cap + tile];
+    const uint32_t* lst = sv.sp_pool + (size_t)(is_k ? slab : b) * sv.pool_cap + oc.x;
+    for (uint32_t e = tid; e < oc.y; e += 256) {
+      const uint32_t en = lst[e];
+      sp[(en & 0xFFFFu) >> 7][en & 127u] = h2f(en >> 16);
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < TILE * D; i += 256) {
+    const int tl = i / D, c = i % D, t = tile * TILE + tl;
+    if (t >= sv.n) break;
+    const uint32_t sb = load_sz(sv, dm, is_k, slab, t, c);
+    float v = (float)load_code(sv, dm, is_k, slab, t, c) * h2f(sb & 0xFFFFu) + h2f(sb >> 16);
+    float lr = 0.0f;
+    for (int r = 0; r < sv.rank; ++r) lr += h2f(sv.A[((size_t)slab * sv.n_cap + t) * sv.rank + r]) * Bs[c][r];
+    v = v + lr + sp[tl][c];
+    out[((size_t)slab * n_total + sv.t0 + t) * D + c] = (uint16_t)f2h(v);
+  }
+}
+
+// grid (ceil(n/64), B*H), block 256.
+__global__ __launch_bounds__(256) void export_codes_kernel(Dims dm, SegView sv, int is_k, uint8_t* __restrict__ codes,
+                                                           uint16_t* __restrict__ scale, uint16_t* __restrict__ zero,
+                                                           int n_total, int ng_total) {
+  const int slab = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+  for (int i = tid; i < TILE * D; i += 256) {
+    const int tl = i / D, c = i % D, t = tile * TILE + tl;
+    if (t >= sv.n) break;
+    codes[((size_t)slab * n_total + sv.t0 + t) * D + c] = (uint8_t)load_code(sv, dm, is_k, slab, t, c);
+    const uint32_t sb = load_sz(sv, dm, is_k, slab, t, c);
+    if (is_k) {
+      if (t % dm.g == 0) {
+        const size_t o = ((size_t)slab * ng_total + sv.g0 + t / dm.g) * D + c;
+        scale[o] = (uint16_t)(sb & 0xFFFFu);
+        zero[o] = (uint16_t)(sb >> 16);
+      }
+    } else if (c % dm.g == 0) {
+      const size_t o = ((size_t)slab * n_total + sv.t0 + t) * (D / dm.g) + c / dm.g;
+      scale[o] = (uint16_t)(sb & 0xFFFFu);
+      zero[o] = (uint16_t)(sb >> 16);
+    }
+  }
+}
+
+// grid (ceil(n/64), B*H), block 256.  Outputs must be zero-filled beforehand.
+__global__ __launch_bounds__(256) void export_sparse_kernel(Dims dm, SegView sv, int is_k, uint8_t* __restrict__ mask,
+                                                            uint16_t* __restrict__ vals, int n_total) {
+  const int slab = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+  const int b = slab / dm.H;
+  const uint2 oc = sv.sp_table[(size_t)slab * sv.ntile_cap + tile];
+  const uint32_t* lst = sv.sp_pool + (size_t)(is_k ? slab : b) * sv.pool_cap + oc.x;
+  for (uint32_t e = tid; e < oc.y; e += 256) {
+    const uint32_t en = lst[e];
+    const int t = tile * TILE + (int)((en & 0xFFFFu) >> 7), c = en & 127u;
+    if (t < sv.n) {
+      const size_t o = ((size_t)slab * n_total + sv.t0 + t) * D + c;
+      mask[o] = 1;
+      vals[o] = (uint16_t)(en >> 16);
+    }
+  }
+}
+
+__global__ void export_lowrank_kernel(SegView sv, uint16_t* __restrict__ A, uint16_t* __restrict__ Bf, int slabs) {
+  const size_t na = (size_t)slabs * sv.n * sv.rank, nb = (size_t)slabs * D * sv.rank;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < na + nb; i += (size_t)gridDim.x * blockDim.x) {
+    if (i < na) {
+      const size_t per = (size_t)sv.n * sv.rank;
+      const size_t slab = i / per, r = i - slab * per;
+      A[i] = sv.A[slab * sv.n_cap * sv.rank + r];
+    } else {
+      Bf[i - na] = sv.Bf[i - na];
+    }
+  }
+}
+
+hipError_t launch_decompress(const Dims& dm, const SegView& ks, const SegView& vs, uint16_t* Kout,
+                             uint16_t* Vout, int n_total, hipStream_t st) {
+  dim3 grid((ks.n + TILE - 1) / TILE, dm.B * dm.H);
+  if (Kout) hipLaunchKernelGGL(decompress_kernel, grid, dim3(256), 0, st, dm, ks, 1, Kout, n_total);
+  if (Vout) hipLaunchKernelGGL(decompress_kernel, grid, dim3(256), 0, st, dm, vs, 0, Vout, n_total);
+  return hipGetLastError();
+}
+
+hipError_t launch_export_codes(const Dims& dm, const SegView& sv, bool is_k, uint8_t* codes, uint16_t* scale,
+                               uint16_t* zero, int n_total, int ng_total, hipStream_t st) {
+  dim3 grid((sv.n + TILE - 1) / TILE, dm.B * dm.H);
+  hipLaunchKernelGGL(export_codes_kernel, grid, dim3(256), 0, st, dm, sv, is_k ? 1 : 0, codes, scale, zero,
+                     n_total, ng_total);
+  return hipGetLastError();
+}
+
+hipError_t launch_export_sparse(const Dims& dm, const SegView& sv, bool is_k, uint8_t* mask, uint16_t* vals,
+                                int n_total, hipStream_t st) {
+  if (dm.ppm == 0) return hipSuccess;
+  dim3 grid((sv.n + TILE - 1) / TILE, dm.B * dm.H);
+  hipLaunchKernelGGL(export_sparse_kernel, grid, dim3(256), 0, st, dm, sv, is_k ? 1 : 0, mask, vals, n_total);
+  return hipGetLastError();
+}
+
+hipError_t launch_export_lowrank(const Dims& dm, const SegView& sv, uint16_t* A, uint16_t* Bf, hipStream_t st) {
+  if (sv.rank == 0) return hipSuccess;
+  hipLaunchKernelGGL(export_lowrank_kernel, dim3(1024), dim3(256), 0, st, sv, A, Bf, dm.B * dm.H);
+  return hipGetLastError();
+}
+
+}  // namespace gear

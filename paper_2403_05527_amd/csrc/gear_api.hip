@@ -1,0 +1,404 @@
+// C ABI of libgear: argument validation, arena / workspace layout and the launch
+// sequences of the entry points declared in gear.h.
+#include <string.h>
+
+#include "gear_internal.h"
+#include "gear_launch.h"
+
+using namespace gear;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+inline int outlier_count(long long n_v, long long ppm) {  // ceil(ppm * n_v / 1e6), clamped
+  long long k = (ppm * n_v + 999999) / 1000000;
+  if (k > n_v) k = n_v;
+  if (k < 0) k = 0;
+  return (int)k;
+}
+
+struct Region {  // byte offsets of one tensor's arrays inside a segment region
+  size_t codes, sz, A, Bf, table, pool, bytes;
+  int n_cap, ng_cap, nblk_cap, ntile_cap;
+  uint32_t pool_cap;
+};
+
+Region region_layout(const gear_config& c, bool is_k, int n_cap) {
+  Region r;
+  const size_t slabs = (size_t)c.B * c.H_kv;
+  const int wpr = D * c.bits / 32, tpw = 32 / c.bits;
+  r.n_cap = n_cap;
+  r.ng_cap = (n_cap + c.group - 1) / c.group;
+  r.nblk_cap = (n_cap + 4 * tpw - 1) / (4 * tpw);
+  r.ntile_cap = (n_cap + TILE - 1) / TILE;
+  size_t o = 0;
+  r.codes = o;
+  o += up(is_k ? slabs * n_cap * wpr * 4 : slabs * (size_t)r.nblk_cap * 2048);
+  r.sz = o;
+  o += up(is_k ? slabs * (size_t)r.ng_cap * D * 4 : slabs * (size_t)n_cap * (D / c.group) * 4);
+  r.A = o;
+  o += up(slabs * (size_t)n_cap * (c.rank_max > 0 ? c.rank_max : 1) * 2);
+  r.Bf = o;
+  o += up(slabs * (size_t)D * (c.rank_max > 0 ? c.rank_max : 1) * 2);
+  r.table = o;
+  o += up(slabs * (size_t)r.ntile_cap * 8);
+  r.pool = o;
+  if (is_k) {
+    r.pool_cap = (uint32_t)D * outlier_count(n_cap, c.outlier_ppm);
+    o += up(slabs * (size_t)r.pool_cap * 4);
+  } else {
+    r.pool_cap = (uint32_t)n_cap * outlier_count((long long)c.H_kv * D, c.outlier_ppm);
+    o += up((size_t)c.B * r.pool_cap * 4);
+  }
+  r.bytes = o;
+  return r;
+}
+
+struct ArenaLayout {
+  Region kp, vp, kc, vc;   // prefill K/V, chunk K/V
+  size_t off_kp, off_vp, off_chunks, chunk_stride, bytes;
+};
+
+ArenaLayout arena_layout(const gear_config& c) {
+  ArenaLayout a;
+  a.kp = region_layout(c, true, c.n_prefill_max);
+  a.vp = region_layout(c, false, c.n_prefill_max);
+  a.kc = region_layout(c, true, c.n_buf_cap);
+  a.vc = region_layout(c, false, c.n_buf_cap);
+  a.off_kp = 0;
+  a.off_vp = a.kp.bytes;
+  a.off_chunks = a.off_vp + a.vp.bytes;
+  a.chunk_stride = a.kc.bytes + a.vc.bytes;
+  a.bytes = a.off_chunks + a.chunk_stride * (size_t)c.n_chunks_max;
+  return a;
+}
+
+struct WorkLayout {
+  size_t thrK, thrV, pool_ctr, Bcur, partial, Atmp, cmat, dec, bytes;
+};
+
+WorkLayout work_layout(const gear_config& c) {
+  WorkLayout w;
+  const size_t slabs = (size_t)c.B * c.H_kv;
+  const int n_max = c.n_prefill_max > c.n_buf_cap ? c.n_prefill_max : c.n_buf_cap;
+  const int npart = (n_max + 255) / 256;
+  const int R = 8;
+  size_t o = 0;
+  w.thrK = o; o += up(slabs * D * sizeof(Thresh));
+  w.thrV = o; o += up((size_t)c.B * n_max * sizeof(Thresh));
+  w.pool_ctr = o; o += up(slabs * 4);
+  w.Bcur = o; o += up(slabs * D * R * 4);
+  w.partial = o; o += up(slabs * (size_t)npart * (D * R + R * R) * 4);
+  w.Atmp = o; o += up(slabs * (size_t)n_max * R * 4);
+  w.cmat = o; o += up(slabs * R * R * 4);
+  const int nsplit = (c.n_prefill_max + DECODE_TS - 1) / DECODE_TS;
+  w.dec = o; o += up((size_t)c.B * c.H_q * (nsplit + 1) * DECODE_REC * 4);
+  w.bytes = o;
+  return w;
+}
+
+bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+int check_config(const gear_config* c) {
+  if (!c) return GEAR_EINVAL;
+  if (c->B < 1 || c->H_kv < 1 || c->H_kv > 64 || c->H_q < c->H_kv || c->H_q % c->H_kv) return GEAR_EINVAL;
+  const int gq = c->H_q / c->H_kv;
+  if (!pow2(gq) || gq > 8) return GEAR_EINVAL;
+  if (c->d_h != D) return GEAR_EINVAL;
+  if (c->bits != 2 && c->bits != 4) return GEAR_EINVAL;
+  if (c->group != 32 && c->group != 64 && c->group != 128) return GEAR_EINVAL;
+  if (c->outlier_ppm < 0 || c->outlier_ppm > 500000) return GEAR_EINVAL;
+  if (c->n_buf_cap < 1 || c->n_buf_cap > 255) return GEAR_EINVAL;
+  if (c->n_prefill_max < 1 || c->n_prefill_max > 32768) return GEAR_EINVAL;
+  if (c->n_chunks_max < 0 || c->n_chunks_max > GEAR_MAX_CHUNKS) return GEAR_EINVAL;
+  if (c->rank_max < 0 || c->rank_max > 8) return GEAR_EINVAL;
+  if ((long long)c->B * c->H_kv > 65535) return GEAR_EINVAL;  // grid.y
+  return GEAR_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+Dims make_dims(const gear_config& c) {
+  Dims d;
+  d.B = c.B; d.H = c.H_kv; d.Hq = c.H_q;
+  d.bits = c.bits; d.g = c.group; d.ppm = c.outlier_ppm;
+  d.wpr = D * c.bits / 32;
+  d.tpw = 32 / c.bits;
+  d.qmax = (float)((1 << c.bits) - 1);
+  return d;
+}
+
+SegView make_view(char* base, const Region& r, int n, int rank, int t0, int g0) {
+  SegView v;
+  v.codes = reinterpret_cast<uint32_t*>(base + r.codes);
+  v.sz = reinterpret_cast<uint32_t*>(base + r.sz);
+  v.A = reinterpret_cast<uint16_t*>(base + r.A);
+  v.Bf = reinterpret_cast<uint16_t*>(base + r.Bf);
+  v.sp_table = reinterpret_cast<uint2*>(base + r.table);
+  v.sp_pool = reinterpret_cast<uint32_t*>(base + r.pool);
+  v.n = n; v.n_cap = r.n_cap; v.rank = rank;
+  v.ng_cap = r.ng_cap; v.nblk_cap = r.nblk_cap; v.ntile_cap = r.ntile_cap;
+  v.pool_cap = r.pool_cap;
+  v.t0 = t0; v.g0 = g0;
+  return v;
+}
+
+// seg 0 = prefill, seg j >= 1 = chunk j-1
+void seg_views(const gear_cache* cache, const ArenaLayout& a, int seg, int n, int rank, SegView* k, SegView* v) {
+  char* base = static_cast<char*>(cache->arena);
+  const int g = cache->cfg.group;
+  if (seg == 0) {
+    *k = make_view(base + a.off_kp, a.kp, n, rank, 0, 0);
+    *v = make_view(base + a.off_vp, a.vp, n, rank, 0, 0);
+    return;
+  }
+  int t0 = cache->n_prefill, g0 = (cache->n_prefill + g - 1) / g;
+  for (int j = 0; j < seg - 1; ++j) {
+    t0 += cache->chunk_n[j];
+    g0 += (cache->chunk_n[j] + g - 1) / g;
+  }
+  char* cb = base + a.off_chunks + a.chunk_stride * (size_t)(seg - 1);
+  *k = make_view(cb, a.kc, n, rank, t0, g0);
+  *v = make_view(cb + a.kc.bytes, a.vc, n, rank, t0, g0);
+}
+
+int n_segments(const gear_cache* c) { return (c->n_prefill > 0 ? 1 : 0) + c->n_chunks; }
+int seg_n(const gear_cache* c, int seg) { return seg == 0 ? c->n_prefill : c->chunk_n[seg - 1]; }
+int seg_rank(const gear_cache* c, int seg) { return seg == 0 ? c->rank_prefill : c->chunk_rank[seg - 1]; }
+int total_groups(const gear_cache* c) {
+  const int g = c->cfg.group;
+  int ng = (c->n_prefill + g - 1) / g;
+  for (int j = 0; j < c->n_chunks; ++j) ng += (c->chunk_n[j] + g - 1) / g;
+  return ng;
+}
+
+int check_cache(const gear_cache* c) {
+  if (!c || !c->arena) return GEAR_EINVAL;
+  return check_config(&c->cfg);
+}
+
+#define GEAR_HIP(expr)                           \
+  do {                                           \
+    hipError_t e__ = (expr);                     \
+    if (e__ != hipSuccess) return GEAR_EHIP;     \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int gear_cache_bytes(const gear_config* cfg, size_t* arena_bytes, size_t* workspace_bytes) {
+  const int rc = check_config(cfg);
+  if (rc) return rc;
+  if (arena_bytes) *arena_bytes = arena_layout(*cfg).bytes;
+  if (workspace_bytes) *workspace_bytes = work_layout(*cfg).bytes;
+  return GEAR_OK;
+}
+
+int gear_cache_init(const gear_config* cfg, void* arena, size_t arena_bytes, gear_cache* cache) {
+  const int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!arena || !cache) return GEAR_EINVAL;
+  if (reinterpret_cast<uintptr_t>(arena) & (ALIGN - 1)) return GEAR_EALIGN;
+  if (arena_bytes < arena_layout(*cfg).bytes) return GEAR_ECAPACITY;
+  memset(cache, 0, sizeof(*cache));
+  cache->cfg = *cfg;
+  cache->arena = arena;
+  cache->arena_bytes = arena_bytes;
+  return GEAR_OK;
+}
+
+int gear_cache_reset(gear_cache* cache) {
+  const int rc = check_cache(cache);
+  if (rc) return rc;
+  cache->n_prefill = cache->rank_prefill = cache->n_chunks = cache->n_total = 0;
+  return GEAR_OK;
+}
+
+int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, int32_t rank, int32_t iters,
+                  const float* init_B, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_cache(cache);
+  if (rc) return rc;
+  const gear_config& c = cache->cfg;
+  if (!K || !V || !workspace) return GEAR_EINVAL;
+  if (n < 1 || rank < 0 || rank > c.rank_max || iters < 1 || iters > 64) return GEAR_EINVAL;
+  if (rank > 0 && !init_B) return GEAR_EINVAL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(workspace) || (init_B && !aligned16(init_B))) return GEAR_EALIGN;
+  const bool first = cache->n_prefill == 0;
+  if (first) {
+    if (n > c.n_prefill_max) return GEAR_ECAPACITY;
+  } else {
+    if (n > c.n_buf_cap) return GEAR_ECAPACITY;
+    if (cache->n_chunks >= c.n_chunks_max) return GEAR_ECAPACITY;
+  }
+  const WorkLayout w = work_layout(c);
+  if (workspace_bytes < w.bytes) return GEAR_ECAPACITY;
+
+  const ArenaLayout a = arena_layout(c);
+  const Dims dm = make_dims(c);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  const int seg = first ? 0 : cache->n_chunks + 1;
+  SegView ks, vs;
+  seg_views(cache, a, seg, n, rank, &ks, &vs);
+  const uint16_t* Kp = static_cast<const uint16_t*>(K);
+  const uint16_t* Vp = static_cast<const uint16_t*>(V);
+  Thresh* thrK = reinterpret_cast<Thresh*>(ws + w.thrK);
+  Thresh* thrV = reinterpret_cast<Thresh*>(ws + w.thrV);
+  uint32_t* pool_ctr = reinterpret_cast<uint32_t*>(ws + w.pool_ctr);
+
+  const int kv_k = outlier_count(n, c.outlier_ppm);
+  const int kv_v = outlier_count((long long)c.H_kv * D, c.outlier_ppm);
+  if (c.outlier_ppm > 0) {
+    GEAR_HIP(launch_fill_u32(pool_ctr, 0u, (size_t)c.B * c.H_kv, st));
+    GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, st));
+  }
+  GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, st));
+  GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, st));
+  if (rank > 0) {
+    float* Bcur = reinterpret_cast<float*>(ws + w.Bcur);
+    float* partial = reinterpret_cast<float*>(ws + w.partial);
+    float* Atmp = reinterpret_cast<float*>(ws + w.Atmp);
+    float* cmat = reinterpret_cast<float*>(ws + w.cmat);
+    const size_t half = (size_t)c.B * c.H_kv * D * rank;
+    GEAR_HIP(launch_power_iteration(true, Kp, ks, dm, n, iters, init_B, thrK, Bcur, partial, Atmp, cmat, st));
+    GEAR_HIP(launch_power_iteration(false, Vp, vs, dm, n, iters, init_B + half, thrV, Bcur, partial, Atmp, cmat, st));
+  }
+
+  if (first) {
+    cache->n_prefill = n;
+    cache->rank_prefill = rank;
+  } else {
+    cache->chunk_n[cache->n_chunks] = (uint8_t)n;
+    cache->chunk_rank[cache->n_chunks] = (uint8_t)rank;
+    cache->n_chunks += 1;
+  }
+  cache->n_total += n;
+  return GEAR_OK;
+}
+
+int gear_decompress(const gear_cache* cache, void* K_out, void* V_out, void* stream) {
+  const int rc = check_cache(cache);
+  if (rc) return rc;
+  if (!K_out && !V_out) return GEAR_EINVAL;
+  if ((K_out && !aligned16(K_out)) || (V_out && !aligned16(V_out))) return GEAR_EALIGN;
+  const ArenaLayout a = arena_layout(cache->cfg);
+  const Dims dm = make_dims(cache->cfg);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int seg = 0; seg <= cache->n_chunks; ++seg) {
+    if (seg == 0 && cache->n_prefill == 0) continue;
+    SegView ks, vs;
+    seg_views(cache, a, seg, seg_n(cache, seg), seg_rank(cache, seg), &ks, &vs);
+    GEAR_HIP(launch_decompress(dm, ks, vs, static_cast<uint16_t*>(K_out), static_cast<uint16_t*>(V_out),
+                               cache->n_total, st));
+  }
+  return GEAR_OK;
+}
+
+int gear_decode_attn(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf, int32_t n_buf,
+                     void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  const int rc = check_cache(cache);
+  if (rc) return rc;
+  const gear_config& c = cache->cfg;
+  if (!q || !out || !workspace) return GEAR_EINVAL;
+  if (n_buf < 0 || n_buf > c.n_buf_cap) return GEAR_EINVAL;
+  if (n_buf > 0 && (!K_buf || !V_buf)) return GEAR_EINVAL;
+  if (n_buf == 0 && cache->n_total == 0) return GEAR_EINVAL;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(workspace) || (K_buf && !aligned16(K_buf)) ||
+      (V_buf && !aligned16(V_buf)))
+    return GEAR_EALIGN;
+  const WorkLayout w = work_layout(c);
+  if (workspace_bytes < w.bytes) return GEAR_ECAPACITY;
+  const ArenaLayout a = arena_layout(c);
+  const Dims dm = make_dims(c);
+  SegView k0, v0;
+  seg_views(cache, a, 0, cache->n_prefill, cache->rank_prefill, &k0, &v0);
+  ChunkSet cs;
+  memset(&cs, 0, sizeof(cs));
+  {
+    // views of chunk 0 (token offsets are irrelevant for attention)
+    char* cb = static_cast<char*>(cache->arena) + a.off_chunks;
+    cs.k0 = make_view(cb, a.kc, 0, 0, 0, 0);
+    cs.v0 = make_view(cb + a.kc.bytes, a.vc, 0, 0, 0, 0);
+  }
+  cs.stride = a.chunk_stride;
+  cs.n_chunks = cache->n_chunks;
+  for (int j = 0; j < cache->n_chunks; ++j) {
+    cs.n[j] = cache->chunk_n[j];
+    cs.rank[j] = cache->chunk_rank[j];
+  }
+  float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dec);
+  GEAR_HIP(launch_decode(dm, k0, v0, cs, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(K_buf),
+                         static_cast<const uint16_t*>(V_buf), n_buf, c.n_buf_cap, static_cast<uint16_t*>(out),
+                         partial, static_cast<hipStream_t>(stream)));
+  return GEAR_OK;
+}
+
+int gear_export_codes(const gear_cache* cache, int which, void* codes_u8, void* scale_f16, void* zero_f16,
+                      void* stream) {
+  const int rc = check_cache(cache);
+  if (rc) return rc;
+  if ((which != 0 && which != 1) || !codes_u8 || !scale_f16 || !zero_f16) return GEAR_EINVAL;
+  const ArenaLayout a = arena_layout(cache->cfg);
+  const Dims dm = make_dims(cache->cfg);
+  const int ng_total = total_groups(cache);
+  for (int seg = 0; seg <= cache->n_chunks; ++seg) {
+    if (seg == 0 && cache->n_prefill == 0) continue;
+    SegView ks, vs;
+    seg_views(cache, a, seg, seg_n(cache, seg), seg_rank(cache, seg), &ks, &vs);
+    GEAR_HIP(launch_export_codes(dm, which == 0 ? ks : vs, which == 0, static_cast<uint8_t*>(codes_u8),
+                                 static_cast<uint16_t*>(scale_f16), static_cast<uint16_t*>(zero_f16),
+                                 cache->n_total, ng_total, static_cast<hipStream_t>(stream)));
+  }
+  return GEAR_OK;
+}
+
+int gear_export_sparse(const gear_cache* cache, int which, void* mask_u8, void* values_f16, void* stream) {
+  const int rc = check_cache(cache);
+  if (rc) return rc;
+  if ((which != 0 && which != 1) || !mask_u8 || !values_f16) return GEAR_EINVAL;
+  if (!aligned16(mask_u8) || !aligned16(values_f16)) return GEAR_EALIGN;
+  const ArenaLayout a = arena_layout(cache->cfg);
+  const Dims dm = make_dims(cache->cfg);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t entries = (size_t)cache->cfg.B * cache->cfg.H_kv * cache->n_total * D;
+  GEAR_HIP(launch_fill_u32(static_cast<uint32_t*>(mask_u8), 0u, entries / 4, st));
+  GEAR_HIP(launch_fill_u32(static_cast<uint32_t*>(values_f16), 0u, entries / 2, st));
+  for (int seg = 0; seg <= cache->n_chunks; ++seg) {
+    if (seg == 0 && cache->n_prefill == 0) continue;
+    SegView ks, vs;
+    seg_views(cache, a, seg, seg_n(cache, seg), seg_rank(cache, seg), &ks, &vs);
+    GEAR_HIP(launch_export_sparse(dm, which == 0 ? ks : vs, which == 0, static_cast<uint8_t*>(mask_u8),
+                                  static_cast<uint16_t*>(values_f16), cache->n_total, st));
+  }
+  return GEAR_OK;
+}
+
+int gear_export_lowrank(const gear_cache* cache, int which, int seg, void* A_f16, void* B_f16, void* stream) {
+  const int rc = check_cache(cache);
+  if (rc) return rc;
+  if ((which != 0 && which != 1) || !A_f16 || !B_f16) return GEAR_EINVAL;
+  if (seg < 0 || seg > cache->n_chunks || (seg == 0 && cache->n_prefill == 0)) return GEAR_EINVAL;
+  const ArenaLayout a = arena_layout(cache->cfg);
+  const Dims dm = make_dims(cache->cfg);
+  SegView ks, vs;
+  seg_views(cache, a, seg, seg_n(cache, seg), seg_rank(cache, seg), &ks, &vs);
+  GEAR_HIP(launch_export_lowrank(dm, which == 0 ? ks : vs, static_cast<uint16_t*>(A_f16),
+                                 static_cast<uint16_t*>(B_f16), static_cast<hipStream_t>(stream)));
+  return GEAR_OK;
+}
+
+const char* gear_strerror(int status) {
+  switch (status) {
+    case GEAR_OK: return "ok";
+    case GEAR_EINVAL: return "invalid or unsupported argument";
+    case GEAR_ECAPACITY: return "capacity exceeded (arena, workspace, segment or chunk count)";
+    case GEAR_EALIGN: return "pointer not sufficiently aligned";
+    case GEAR_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

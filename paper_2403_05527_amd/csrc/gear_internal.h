@@ -1,0 +1,173 @@
+// Internal definitions shared by the HIP translation units of libgear:
+// the private arena layout, kernel argument structs and small device helpers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <limits.h>
+
+#include "gear.h"
+
+namespace gear {
+
+constexpr int D = 128;      // head dimension
+constexpr int TILE = 64;    // tokens per sparse-list tile
+
+// ---------------------------------------------------------------------------
+// Filter_s thresholds of one vector (Eq. 4).  An entry with monotone key `k`
+// and in-vector index `i` is an outlier iff
+//   k > tau_top || (k == tau_top && i <= i_top) ||
+//   k < tau_bot || (k == tau_bot && l_bot < i && i <= i_bot).
+// ---------------------------------------------------------------------------
+struct Thresh {
+  uint32_t tau_top;
+  int32_t i_top;
+  uint32_t tau_bot;
+  int32_t i_bot;
+  int32_t l_bot;
+  int32_t pad[3];
+};
+
+// Geometry shared by all kernels of one cache.
+struct Dims {
+  int B, H, Hq;
+  int bits;   // b
+  int g;      // group size
+  int ppm;    // outlier ratio in parts per million
+  int wpr;    // 32-bit words per Key code row (128*b/32)
+  int tpw;    // tokens per Value code word (32/b)
+  float qmax; // 2^b - 1
+};
+
+// One tensor (K or V) of one stored segment.  Private physical layout:
+//  Keys   codes : [slab][n_cap][wpr] u32, token-major rows, channel c at bits
+//                 (c % (32/b))*b of word c*b/32.
+//  Values codes : [slab][nblk_cap][512] u32 in blocks of 4*tpw tokens; word
+//                 (kg*16 + c/8)*8 + c%8 of a block holds channel c for the tpw
+//                 tokens 4*tpw*blk + tpw*kg + i at bits i*b.
+//  sz           : (scale, zero) as two fp16 in one u32 (scale low half).
+//                 Keys [slab][ng_cap][128]; Values [slab][n_cap][128/g].
+//  A, Bf        : fp16 [slab][n_cap][rank], [slab][128][rank].
+//  sp_table     : [slab][ntile_cap] (offset, count) of the tile's outlier list.
+//  sp_pool      : u32 entries (low 16 bits: (t % 64)*128 + c, high 16: fp16
+//                 value).  Keys: one pool per slab, lists ordered (t, c);
+//                 Values: one pool per batch element, lists ordered (c, t).
+struct SegView {
+  uint32_t* codes;
+  uint32_t* sz;
+  uint16_t* A;
+  uint16_t* Bf;
+  uint2* sp_table;
+  uint32_t* sp_pool;
+  int n;         // tokens stored
+  int n_cap;     // token capacity of this region
+  int rank;
+  int ng_cap;    // Key groups capacity
+  int nblk_cap;  // Value code blocks capacity
+  int ntile_cap;
+  uint32_t pool_cap;  // entries per slab (Keys) / per batch element (Values)
+  int t0;        // first token of this segment in the whole cache
+  int g0;        // first Key group of this segment in the whole cache
+};
+
+// ---------------------------------------------------------------------------
+// fp16 helpers (bit patterns travel as integers)
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float h2f(uint32_t bits16) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+}
+__device__ __forceinline__ uint32_t f2h(float f) {  // round to nearest even
+  return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+// Monotone 16-bit key of an fp16 bit pattern; -0 and +0 share one key.
+__device__ __forceinline__ uint32_t key16(uint32_t h) {
+  h &= 0xFFFFu;
+  if (h == 0x8000u) h = 0u;
+  return (h & 0x8000u) ? (h ^ 0xFFFFu) : (h | 0x8000u);
+}
+__device__ __forceinline__ bool is_outlier(uint32_t key, int idx, const Thresh& th) {
+  return key > th.tau_top || (key == th.tau_top && idx <= th.i_top) || key < th.tau_bot ||
+         (key == th.tau_bot && idx > th.l_bot && idx <= th.i_bot);
+}
+__device__ __forceinline__ Thresh thresh_none() {
+  Thresh th;
+  th.tau_top = 0x10000u;
+  th.i_top = -1;
+  th.tau_bot = 0u;
+  th.i_bot = -1;
+  th.l_bot = -1;
+  th.pad[0] = th.pad[1] = th.pad[2] = 0;
+  return th;
+}
+
+// ---------------------------------------------------------------------------
+// Group quantizer (Eq. 2).  The integer code is decided in fp32 with this exact
+// operation sequence: delta32 = (mx - mn) / qmax; delta = fp16(delta32);
+// inv = 1 / delta; t = (y - mn) * inv; code = clamp(rint(t), 0, qmax).
+// ---------------------------------------------------------------------------
+struct GroupQ {
+  float mn;     // zero-point (an fp16 value)
+  float delta;  // fp16-rounded scale, as float
+  float inv;    // 1/delta, 0 when delta == 0
+};
+__device__ __forceinline__ GroupQ make_group(float mn, float mx, float qmax) {
+  GroupQ q;
+  q.mn = mn + 0.0f;  // -0 -> +0
+  mx = mx + 0.0f;
+  float d32 = __fdiv_rn(__fsub_rn(mx, q.mn), qmax);
+  q.delta = h2f(f2h(d32));
+  q.inv = q.delta > 0.0f ? __fdiv_rn(1.0f, q.delta) : 0.0f;
+  return q;
+}
+__device__ __forceinline__ GroupQ load_group(uint32_t sz_bits) {
+  GroupQ q;
+  q.delta = h2f(sz_bits & 0xFFFFu);
+  q.mn = h2f(sz_bits >> 16);
+  q.inv = q.delta > 0.0f ? __fdiv_rn(1.0f, q.delta) : 0.0f;
+  return q;
+}
+__device__ __forceinline__ uint32_t group_bits(const GroupQ& q) {
+  return f2h(q.delta) | (f2h(q.mn) << 16);
+}
+__device__ __forceinline__ uint32_t quant_code(float y, const GroupQ& q, float qmax) {
+  float t = __fmul_rn(__fsub_rn(y, q.mn), q.inv);
+  float c = fminf(fmaxf(rintf(t), 0.0f), qmax);
+  return (uint32_t)c;
+}
+
+// ---------------------------------------------------------------------------
+// wavefront (64 lanes) primitives
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// inclusive prefix sum over lanes
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    uint32_t t = __shfl_up(v, o, 64);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_incl_suffix(uint32_t v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    uint32_t t = __shfl_down(v, o, 64);
+    if (lane + o < 64) v += t;
+  }
+  return v;
+}
+
+}  // namespace gear

@@ -1,0 +1,45 @@
+// Host-side launch functions of the kernel translation units.
+#pragma once
+#include "gear_internal.h"
+
+namespace gear {
+
+// Chunk segments live in equally sized regions; view j = view 0 advanced by
+// j * stride bytes on every pointer.
+struct ChunkSet {
+  SegView k0, v0;       // views of chunk 0 (n / rank filled per chunk on the device)
+  uint64_t stride;      // bytes between consecutive chunk regions
+  int n_chunks;
+  uint8_t n[GEAR_MAX_CHUNKS];
+  uint8_t rank[GEAR_MAX_CHUNKS];
+};
+
+hipError_t launch_fill_u32(uint32_t* p, uint32_t v, size_t count, hipStream_t st);
+
+hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, Thresh* thrK,
+                           hipStream_t st);
+hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const Thresh* thrK,
+                          uint32_t* pool_ctr, hipStream_t st);
+hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
+                                 int k_bot, Thresh* thrV, hipStream_t st);
+
+int pi_padded_rank(int rank);
+hipError_t launch_power_iteration(bool is_k, const uint16_t* X, const SegView& sv, const Dims& dm, int n,
+                                  int iters, const float* init_B, const Thresh* thr, float* Bcur,
+                                  float* partial, float* Atmp, float* cmat, hipStream_t st);
+
+constexpr int DECODE_TS = 256;           // tokens per split block
+constexpr int DECODE_REC = 2 + D;        // floats per partial record: m, l, o[128]
+hipError_t launch_decode(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
+                         const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
+                         int n_buf_cap, uint16_t* out, float* partial, hipStream_t st);
+
+hipError_t launch_decompress(const Dims& dm, const SegView& ks, const SegView& vs, uint16_t* Kout,
+                             uint16_t* Vout, int n_total, hipStream_t st);
+hipError_t launch_export_codes(const Dims& dm, const SegView& sv, bool is_k, uint8_t* codes, uint16_t* scale,
+                               uint16_t* zero, int n_total, int ng_total, hipStream_t st);
+hipError_t launch_export_sparse(const Dims& dm, const SegView& sv, bool is_k, uint8_t* mask, uint16_t* vals,
+                                int n_total, hipStream_t st);
+hipError_t launch_export_lowrank(const Dims& dm, const SegView& sv, uint16_t* A, uint16_t* Bf, hipStream_t st);
+
+}  // namespace gear

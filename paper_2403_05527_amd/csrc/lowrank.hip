@@ -1,0 +1,340 @@
+// SVDSolver_r (Eq. 6, Algorithm 2): batched power iteration on the per-head
+// residual R = X - D - S, which is never stored: every sweep rebuilds it from X,
+// the Filter thresholds and the stored (scale, zero).
+//
+//   pi_update  : B <- start matrix or sum of the sweep partials; column scaling
+//                between rounds (the span, hence A B^T, is unchanged); QR of B
+//                before the last round; after the last round the r x r factor
+//                that orthonormalises A, and the final B = R^T orth(A).
+//   pi_sweep   : one pass over a slab: a_t = R_t B (per token), partial
+//                B' = sum_t R_t^T a_t, and in the last round a_t itself and the
+//                Gram matrix sum_t a_t a_t^T.
+//   pi_finish  : A = a C  (C = the r x r factor), rounded to fp16.
+#include "gear_internal.h"
+#include "gear_launch.h"
+
+namespace gear {
+
+constexpr int PT = 256;  // tokens per sweep block
+
+template <typename T>
+__device__ __forceinline__ T block128_sum(T v, T* red /* >= 2 */) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1];
+}
+
+// grid (B*H), block 128: thread c owns row c of the [128 x R] matrix.
+// src_init != nullptr : B <- init (fp32 [slab][128][rank], zero-padded to R)
+// else                : B <- sum over `npart` partials ([slab][npart][128*R + R*R])
+// do_orth : replace B by the Q factor of its QR (twice-applied modified
+//           Gram-Schmidt, fp64; dependent columns become 0)
+// final   : also sum the Gram partials, build C with orth(A) = A C, write
+//           B_out = B C as fp16 into the arena and C into cmat.
+template <int R>
+__global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict__ src_init, int rank,
+                                                        const float* __restrict__ partial, int npart,
+                                                        int do_orth, int final_round,
+                                                        float* __restrict__ Bcur, float* __restrict__ cmat,
+                                                        SegView sv) {
+  __shared__ double red[2];
+  __shared__ double G[R][R];
+  __shared__ double C[R][R];
+  const int slab = blockIdx.x, c = threadIdx.x;
+  double q[R];
+  if (src_init) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) q[r] = r < rank ? (double)src_init[((size_t)slab * D + c) * rank + r] : 0.0;
+  } else {
+#pragma unroll
+    for (int r = 0; r < R; ++r) q[r] = 0.0;
+    const float* p = partial + (size_t)slab * npart * (D * R + R * R);
+    for (int i = 0; i < npart; ++i) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) q[r] += (double)p[(size_t)i * (D * R + R * R) + c * R + r];
+    }
+  }
+
+  if (final_round) {
+    if (c < R * R) {
+      const float* p = partial + (size_t)slab * npart * (D * R + R * R) + D * R;
+      double s = 0.0;
+      for (int i = 0; i < npart; ++i) s += (double)p[(size_t)i * (D * R + R * R) + c];
+      G[c / R][c % R] = s;
+    }
+    __syncthreads();
+    if (c == 0) {
+      // Gram-Schmidt in coefficient space: column j of orth(A) is A * C[:, j].
+      bool valid[R];
+      for (int j = 0; j < R; ++j) {
+        double cj[R];
+        for (int i = 0; i < R; ++i) cj[i] = (i == j) ? 1.0 : 0.0;
+        const double before2 = G[j][j];
+        valid[j] = before2 > 0.0;
+        if (valid[j]) {
+          for (int pass = 0; pass < 2; ++pass)
+            for (int k = 0; k < j; ++k) {
+              if (!valid[k]) continue;
+              double dot = 0.0;  // q_k^T v = c_k^T G c_j
+              for (int a = 0; a < R; ++a)
+                for (int b = 0; b < R; ++b) dot += C[a][k] * G[a][b] * cj[b];
+              for (int a = 0; a < R; ++a) cj[a] -= dot * C[a][k];
+            }
+          double after2 = 0.0;
+          for (int a = 0; a < R; ++a)
+            for (int b = 0; b < R; ++b) after2 += cj[a] * G[a][b] * cj[b];
+          if (!(after2 > 1e-10 * before2)) valid[j] = false;
+          else {
+            const double inv = 1.0 / sqrt(after2);
+            for (int a = 0; a < R; ++a) cj[a] *= inv;
+          }
+        }
+        for (int a = 0; a < R; ++a) C[a][j] = valid[j] ? cj[a] : 0.0;
+      }
+    }
+    __syncthreads();
+    double o[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      double s = 0.0;
+#pragma unroll
+      for (int r = 0; r < R; ++r) s += q[r] * C[r][j];
+      o[j] = s;
+    }
+    for (int j = 0; j < rank; ++j) sv.Bf[((size_t)slab * D + c) * sv.rank + j] = (uint16_t)f2h((float)o[j]);
+    if (c < R * R) cmat[(size_t)slab * R * R + c] = (float)C[c / R][c % R];
+    return;
+  }
+
+  if (do_orth) {
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      const double before2 = block128_sum(q[j] * q[j], red);
+      if (before2 == 0.0) { q[j] = 0.0; continue; }
+      for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+          if (i < j) {
+            const double dot = block128_sum(q[i] * q[j], red);
+            q[j] -= dot * q[i];
+          }
+        }
+      }
+      const double after2 = block128_sum(q[j] * q[j], red);
+      if (!(sqrt(after2) > 1e-12 * sqrt(before2))) q[j] = 0.0;
+      else q[j] *= 1.0 / sqrt(after2);
+    }
+  } else {
+    // keep magnitudes in range between rounds
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      const double n2 = block128_sum(q[j] * q[j], red);
+      if (n2 > 0.0) q[j] *= 1.0 / sqrt(n2);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) Bcur[((size_t)slab * D + c) * R + r] = (float)q[r];
+}
+
+// grid (ceil(n/PT), B*H), block 256; thread (r0 = tid/16, oc = tid%16) owns
+// channels 8*oc..+7 of rows pt*PT + r0 + 16*k.
+template <bool IS_K, int R>
+__global__ __launch_bounds__(256) void pi_sweep_kernel(const uint16_t* __restrict__ X, SegView sv, Dims dm,
+                                                       int n, const Thresh* __restrict__ thr,
+                                                       const float* __restrict__ Bcur, int last,
+                                                       float* __restrict__ partial, int npart,
+                                                       float* __restrict__ Atmp) {
+  __shared__ float red[4][D * R];
+  __shared__ float redg[4][R * R];
+  const int slab = blockIdx.y, pt = blockIdx.x;
+  const int b = slab / dm.H, h = slab - b * dm.H;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r0 = tid >> 4, oc = tid & 15;
+  const uint16_t* Xs = X + (size_t)slab * n * D;
+  const int g = dm.g;
+
+  float bc[8][R];
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int r = 0; r < R; ++r) bc[e][r] = Bcur[((size_t)slab * D + oc * 8 + e) * R + r];
+
+  Thresh thk[8];
+  if (IS_K) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) thk[e] = dm.ppm > 0 ? thr[(size_t)slab * D + oc * 8 + e] : thresh_none();
+  }
+
+  float acc[8][R];
+  float gacc[R];
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[e][r] = 0.0f;
+#pragma unroll
+  for (int r = 0; r < R; ++r) gacc[r] = 0.0f;
+
+  GroupQ gq[8];
+  int cur_group = -1;
+  for (int k = 0; k < PT / 16; ++k) {
+    const int t = pt * PT + r0 + 16 * k;
+    if (pt * PT + 16 * k >= n) break;  // block-uniform
+    const bool tv = t < n;
+    uint4 xv = make_uint4(0, 0, 0, 0);
+    if (tv) xv = *reinterpret_cast<const uint4*>(Xs + (size_t)t * D + oc * 8);
+    const uint32_t w[4] = {xv.x, xv.y, xv.z, xv.w};
+    Thresh thv = thresh_none();
+    if (IS_K) {
+      const int grp = (pt * PT + 16 * k) / g;
+      if (grp != cur_group) {
+        cur_group = grp;
+        const uint4* p = reinterpret_cast<const uint4*>(sv.sz + ((size_t)slab * sv.ng_cap + grp) * D + oc * 8);
+        const uint4 s0 = p[0], s1 = p[1];
+        const uint32_t sb[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gq[e] = load_group(sb[e]);
+      }
+    } else {
+      if (tv) {
+        if (dm.ppm > 0) thv = thr[(size_t)b * n + t];
+        const GroupQ q = load_group(sv.sz[((size_t)slab * sv.n_cap + t) * (D / g) + (oc * 8) / g]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gq[e] = q;
+      }
+    }
+    float res[8];
+    float a[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) a[r] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t hb = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+      bool out;
+      if (IS_K) out = is_outlier(key16(hb), t, thk[e]);
+      else out = is_outlier(key16(hb), h * D + oc * 8 + e, thv);
+      const float y = out ? 0.0f : h2f(hb);
+      const float code = (float)quant_code(y, gq[e], dm.qmax);
+      res[e] = tv ? (y - (code * gq[e].delta + gq[e].mn)) : 0.0f;
+#pragma unroll
+      for (int r = 0; r < R; ++r) a[r] += res[e] * bc[e][r];
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      a[r] += __shfl_xor(a[r], 1, 64);
+      a[r] += __shfl_xor(a[r], 2, 64);
+      a[r] += __shfl_xor(a[r], 4, 64);
+      a[r] += __shfl_xor(a[r], 8, 64);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+      for (int r = 0; r < R; ++r) acc[e][r] += res[e] * a[r];
+    if (last) {
+      if (oc == 0 && tv) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) Atmp[((size_t)slab * n + t) * R + r] = a[r];
+      }
+      if (oc < R) {
+        float mine = 0.0f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) mine = (r == oc) ? a[r] : mine;
+#pragma unroll
+        for (int r = 0; r < R; ++r) gacc[r] += mine * a[r];
+      }
+    }
+  }
+
+  // reduce over the 16 row-threads that share a channel octet
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float v = acc[e][r];
+      v += __shfl_xor(v, 16, 64);
+      v += __shfl_xor(v, 32, 64);
+      acc[e][r] = v;
+    }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    float v = gacc[r];
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    gacc[r] = v;
+  }
+  if (lane < 16) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+      for (int r = 0; r < R; ++r) red[wave][(oc * 8 + e) * R + r] = acc[e][r];
+    if (oc < R) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) redg[wave][oc * R + r] = gacc[r];
+    }
+  }
+  __syncthreads();
+  float* out = partial + ((size_t)slab * npart + pt) * (D * R + R * R);
+  for (int i = tid; i < D * R; i += 256) out[i] = red[0][i] + red[1][i] + red[2][i] + red[3][i];
+  if (tid < R * R) out[D * R + tid] = last ? (redg[0][tid] + redg[1][tid] + redg[2][tid] + redg[3][tid]) : 0.0f;
+}
+
+// grid (ceil(n/256), B*H), block 256: one token per thread.
+template <int R>
+__global__ __launch_bounds__(256) void pi_finish_kernel(const float* __restrict__ Atmp,
+                                                        const float* __restrict__ cmat, SegView sv, int n) {
+  __shared__ float C[R * R];
+  const int slab = blockIdx.y;
+  if (threadIdx.x < R * R) C[threadIdx.x] = cmat[(size_t)slab * R * R + threadIdx.x];
+  __syncthreads();
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= n) return;
+  float a[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) a[r] = Atmp[((size_t)slab * n + t) * R + r];
+  for (int j = 0; j < sv.rank; ++j) {
+    float s = 0.0f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) s += a[r] * C[r * R + j];
+    sv.A[((size_t)slab * sv.n_cap + t) * sv.rank + j] = (uint16_t)f2h(s);
+  }
+}
+
+// ------------------------------------------------------------------ host side
+template <int R>
+static hipError_t run_pi(bool is_k, const uint16_t* X, const SegView& sv, const Dims& dm, int n, int iters,
+                         const float* init_B, const Thresh* thr, float* Bcur, float* partial, float* Atmp,
+                         float* cmat, hipStream_t st) {
+  const int slabs = dm.B * dm.H;
+  const int npart = (n + PT - 1) / PT;
+  hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, init_B, sv.rank, (const float*)nullptr,
+                     0, iters == 1 ? 1 : 0, 0, Bcur, cmat, sv);
+  for (int l = 0; l < iters; ++l) {
+    const int last = (l == iters - 1);
+    if (is_k)
+      hipLaunchKernelGGL((pi_sweep_kernel<true, R>), dim3(npart, slabs), dim3(256), 0, st, X, sv, dm, n, thr,
+                         (const float*)Bcur, last, partial, npart, Atmp);
+    else
+      hipLaunchKernelGGL((pi_sweep_kernel<false, R>), dim3(npart, slabs), dim3(256), 0, st, X, sv, dm, n, thr,
+                         (const float*)Bcur, last, partial, npart, Atmp);
+    hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, (const float*)nullptr, sv.rank,
+                       (const float*)partial, npart, (l == iters - 2) ? 1 : 0, last, Bcur, cmat, sv);
+  }
+  hipLaunchKernelGGL(pi_finish_kernel<R>, dim3((n + 255) / 256, slabs), dim3(256), 0, st, (const float*)Atmp,
+                     (const float*)cmat, sv, n);
+  return hipGetLastError();
+}
+
+int pi_padded_rank(int rank) { return rank <= 2 ? 2 : rank <= 4 ? 4 : 8; }
+
+hipError_t launch_power_iteration(bool is_k, const uint16_t* X, const SegView& sv, const Dims& dm, int n,
+                                  int iters, const float* init_B, const Thresh* thr, float* Bcur,
+                                  float* partial, float* Atmp, float* cmat, hipStream_t st) {
+  switch (pi_padded_rank(sv.rank)) {
+    case 2: return run_pi<2>(is_k, X, sv, dm, n, iters, init_B, thr, Bcur, partial, Atmp, cmat, st);
+    case 4: return run_pi<4>(is_k, X, sv, dm, n, iters, init_B, thr, Bcur, partial, Atmp, cmat, st);
+    default: return run_pi<8>(is_k, X, sv, dm, n, iters, init_B, thr, Bcur, partial, Atmp, cmat, st);
+  }
+}
+
+}  // namespace gear

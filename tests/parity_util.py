@@ -1,0 +1,95 @@
+"""Element-by-element comparison of the HIP path (through the C ABI binding)
+with the CPU oracle on the same seeded inputs.  Shared by the GPU tests and the
+smoke check."""
+import numpy as np
+import torch
+
+from oracle import gear_oracle as go
+from paper_2403_05527_amd import binding as gb
+
+REL_FROB_TOL = 1e-3      # reconstructed K/V vs the oracle's
+ATTN_ABS_TOL = 2e-3      # attention outputs, max-abs
+
+
+def np16(t):
+    return t.detach().cpu().numpy()
+
+
+def make_pair(B, H_kv, H_q, bits, group, ppm, n_buf_cap, n_prefill_max, n_chunks_max, rank_max, device="cuda:0"):
+    cfg = gb.make_config(B, H_kv, H_q, bits, group, ppm, n_buf_cap, n_prefill_max, n_chunks_max, rank_max)
+    gc = gb.GearCache(cfg, device)
+    oc = go.OracleCache(B, H_kv, H_q, 128, bits, group, ppm)
+    return gc, oc
+
+
+def compress_both(gc, oc, K, V, rank, iters, init_B):
+    """K, V, init_B: device tensors; the oracle gets host copies of the same bytes."""
+    gc.compress(K, V, rank, iters, init_B if rank > 0 else None)
+    oc.compress(np16(K), np16(V), rank, iters, np16(init_B) if rank > 0 else None)
+
+
+def compare_components(gc, oc):
+    """Bit-exact checks on codes, scale/zero, outlier support and values.
+    Returns a report dict; raises AssertionError on any mismatch that is not an
+    exact rounding tie."""
+    rep = {}
+    for which, (name, segs) in enumerate((("K", oc.K), ("V", oc.V))):
+        codes, scale, zero = [np16(x) for x in gc.export_codes(which)]
+        o_codes = np.concatenate([s.codes for s in segs], axis=2)
+        o_scale = np.concatenate([s.scale for s in segs], axis=2)
+        o_zero = np.concatenate([s.zero for s in segs], axis=2)
+        assert codes.shape == o_codes.shape and scale.shape == o_scale.shape
+        assert np.array_equal(scale.astype(np.float32), o_scale.astype(np.float32)), name + " scale"
+        assert np.array_equal(zero.astype(np.float32), o_zero.astype(np.float32)), name + " zero"
+        mism = int(np.count_nonzero(codes != o_codes))
+        ties = sum(s.ties for s in segs)
+        rep[name + "_code_mismatches"] = mism
+        rep[name + "_exact_ties"] = ties
+        if mism:
+            # allowed only as off-by-one at exact rounding ties
+            assert np.abs(codes.astype(np.int32) - o_codes.astype(np.int32)).max() <= 1, name + " codes"
+            assert mism <= ties, "%s codes: %d mismatches but only %d exact ties" % (name, mism, ties)
+        mask, vals = [np16(x) for x in gc.export_sparse(which)]
+        o_mask = np.concatenate([s.mask for s in segs], axis=2)
+        o_vals = np.concatenate([s.svals for s in segs], axis=2)
+        assert np.array_equal(mask.astype(bool), o_mask), name + " outlier support"
+        assert np.array_equal(vals.view(np.uint16)[o_mask], o_vals.view(np.uint16)[o_mask]), name + " outlier values"
+        assert not vals.view(np.uint16)[~o_mask].any(), name + " values off the support"
+        rep[name + "_nnz"] = int(o_mask.sum())
+    return rep
+
+
+def rel_frob(a, b):
+    a = a.astype(np.float64)
+    b = b.astype(np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def compare_decompress(gc, oc):
+    Kg, Vg = [np16(x) for x in gc.decompress()]
+    Ko, Vo = oc.decompress()
+    ek, ev = rel_frob(Kg, Ko), rel_frob(Vg, Vo)
+    assert ek <= REL_FROB_TOL, "K-hat rel. Frobenius %.3e" % ek
+    assert ev <= REL_FROB_TOL, "V-hat rel. Frobenius %.3e" % ev
+    return {"K_rel_frob": ek, "V_rel_frob": ev}
+
+
+def compare_lowrank_product(gc, oc, seg):
+    """Only the product A B^T is defined (the basis is not): compare that."""
+    out = {}
+    for which, (name, segs) in enumerate((("K", oc.K), ("V", oc.V))):
+        A, Bf = [np16(x).astype(np.float64) for x in gc.export_lowrank(which, seg)]
+        Lg = np.einsum("bhnr,bhdr->bhnd", A, Bf)
+        Lo = np.einsum("bhnr,bhdr->bhnd", segs[seg].A.astype(np.float64), segs[seg].Bf.astype(np.float64))
+        out[name + "_L_rel"] = float(np.linalg.norm(Lg - Lo) / max(np.linalg.norm(Lo), 1e-30))
+    return out
+
+
+def compare_attention(gc, oc, q, K_buf=None, V_buf=None, n_buf=0):
+    out_g = np16(gc.decode_attn(q, K_buf, V_buf, n_buf)).astype(np.float64)
+    out_o = oc.decode_attn(np16(q), None if K_buf is None else np16(K_buf),
+                           None if V_buf is None else np16(V_buf), n_buf).astype(np.float64)
+    err = float(np.abs(out_g - out_o).max())
+    assert np.isfinite(out_g).all()
+    assert err <= ATTN_ABS_TOL, "attention max-abs error %.3e" % err
+    return {"attn_max_abs": err}

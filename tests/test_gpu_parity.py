@@ -1,0 +1,157 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element, on seeded synthetic inputs.  Bars: codes / scale / zero / outlier
+support and values bit-exact (off-by-one codes only at counted exact rounding
+ties); reconstructed K/V within 1e-3 relative Frobenius of the oracle's;
+attention outputs within 2e-3 max-abs."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import gear_workloads as gw
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def small_workload(B, H_kv, H_q, n, bits, g, ppm, rank, seed, nu=4):
+    return gw.Workload("t", B=B, H_kv=H_kv, H_q=H_q, n=n, bits=bits, group=g, outlier_ppm=ppm, rank=rank,
+                       rank_chunk=2, n_b=20, steps=1, seed=seed, v_nu=nu)
+
+
+def run_case(w, n_chunks=1, chunk_n=20, n_buf=7, iters=3, check_attn=True):
+    say("case", w, "chunks", n_chunks, "chunk_n", chunk_n, "n_buf", n_buf)
+    gc, oc = pu.make_pair(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, max(w.n_b, chunk_n), w.n,
+                          max(n_chunks, 1), max(w.rank, w.rank_chunk))
+    K = gw.make_keys(w, w.n, 0, DEV)
+    V = gw.make_values(w, w.n, 0, DEV)
+    ib = gw.make_init_B(w, w.rank, 0, DEV)
+    pu.compress_both(gc, oc, K, V, w.rank, iters, ib)
+    rep = pu.compare_components(gc, oc)
+    rep.update(pu.compare_decompress(gc, oc))
+    if w.rank > 0:
+        rep.update(pu.compare_lowrank_product(gc, oc, 0))
+    for j in range(n_chunks):
+        Kc = gw.make_keys(w, chunk_n, 1 + j, DEV)
+        Vc = gw.make_values(w, chunk_n, 1 + j, DEV)
+        ibc = gw.make_init_B(w, w.rank_chunk, 1 + j, DEV)
+        pu.compress_both(gc, oc, Kc, Vc, w.rank_chunk, iters, ibc)
+    if n_chunks:
+        rep.update(pu.compare_components(gc, oc))
+        rep.update(pu.compare_decompress(gc, oc))
+    if check_attn:
+        q = gw.make_queries(w, 0, DEV)
+        cap = gc.cfg.n_buf_cap
+        Kb = gw.make_keys(w, cap, 50, DEV)
+        Vb = gw.make_values(w, cap, 50, DEV)
+        rep.update(pu.compare_attention(gc, oc, q, Kb, Vb, n_buf))
+        rep["attn_nobuf"] = pu.compare_attention(gc, oc, q)["attn_max_abs"]
+    say("  ->", rep)
+    return rep
+
+
+@pytest.mark.parametrize("bits,g", [(2, 64), (4, 64), (2, 128), (4, 128), (2, 32), (4, 32)])
+def test_small_ragged(bits, g):
+    w = small_workload(B=2, H_kv=4, H_q=8, n=200, bits=bits, g=g, ppm=20000, rank=4, seed=bits * 10 + g)
+    rep = run_case(w, n_chunks=2)
+    assert rep["K_nnz"] > 0 and rep["V_nnz"] > 0
+
+
+@pytest.mark.parametrize("ppm,rank", [(0, 0), (0, 4), (20000, 0), (10000, 8), (50000, 2), (20000, 3)])
+def test_modes(ppm, rank):
+    w = small_workload(B=1, H_kv=8, H_q=8, n=300, bits=2, g=64, ppm=ppm, rank=rank, seed=ppm + rank)
+    run_case(w, n_chunks=1)
+
+
+@pytest.mark.parametrize("n", [1, 7, 20, 63, 64, 65, 513])
+def test_token_counts(n):
+    w = small_workload(B=1, H_kv=4, H_q=4, n=n, bits=4, g=64, ppm=20000, rank=2, seed=n)
+    run_case(w, n_chunks=1, chunk_n=min(20, 13 + n % 5), n_buf=1)
+
+
+@pytest.mark.parametrize("H_kv,H_q", [(1, 1), (2, 16), (3, 6), (40, 40)])
+def test_head_counts(H_kv, H_q):
+    w = small_workload(B=1, H_kv=H_kv, H_q=H_q, n=96, bits=2, g=64, ppm=20000, rank=4, seed=H_kv, nu=3)
+    run_case(w, n_chunks=1)
+
+
+def test_heavy_ties_and_constant_vectors():
+    """Values on a coarse grid (many exact ties at the Filter threshold and at
+    quantizer rounding boundaries), one all-equal head, signed zeros."""
+    w = small_workload(B=1, H_kv=4, H_q=4, n=150, bits=2, g=64, ppm=40000, rank=2, seed=99)
+    say("case ties", w)
+    gc, oc = pu.make_pair(1, 4, 4, 2, 64, 40000, 20, 150, 1, 2)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    K = (torch.randint(-6, 7, (1, 4, 150, 128), generator=g).float() * 0.5)
+    V = (torch.randint(-3, 4, (1, 4, 150, 128), generator=g).float() * 0.25)
+    K[0, 1] = 1.5                                        # constant head
+    V[0, 2] = 0.0
+    V[0, 2, ::2] = -0.0                                  # signed zeros only
+    K = K.to(torch.float16).to(DEV)
+    V = V.to(torch.float16).to(DEV)
+    ib = gw.make_init_B(w, 2, 0, DEV)
+    pu.compress_both(gc, oc, K, V, 2, 3, ib)
+    rep = pu.compare_components(gc, oc)
+    rep.update(pu.compare_decompress(gc, oc))
+    q = gw.make_queries(w, 0, DEV)
+    rep.update(pu.compare_attention(gc, oc, q))
+    say("  ->", rep)
+
+
+def test_lossless_grid_reconstructs_input_bit_exact():
+    gc, oc = pu.make_pair(1, 2, 2, 2, 64, 0, 20, 128, 1, 4)
+    g = torch.Generator(device="cpu").manual_seed(6)
+    k = torch.randint(0, 4, (1, 2, 128, 128), generator=g)
+    k[:, :, 0::64, :] = 0
+    k[:, :, 1::64, :] = 3
+    K = (-1.0 + 0.5 * k.float()).to(torch.float16).to(DEV)
+    v = torch.randint(0, 4, (1, 2, 128, 128), generator=g)
+    v[..., 0::64] = 0
+    v[..., 1::64] = 3
+    V = (2.0 + 0.25 * v.float()).to(torch.float16).to(DEV)
+    w = small_workload(1, 2, 2, 128, 2, 64, 0, 4, 7)
+    ib = gw.make_init_B(w, 4, 0, DEV)
+    pu.compress_both(gc, oc, K, V, 4, 3, ib)
+    Kg, Vg = gc.decompress()
+    assert torch.equal(Kg, K) and torch.equal(Vg, V)
+
+
+def test_config0_full():
+    w = gw.CONFIGS[0]
+    rep = run_case(w, n_chunks=0, n_buf=0, check_attn=False)
+    gc, oc = pu.make_pair(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, w.n_b, w.n, 1, w.rank)
+    K = gw.make_keys(w, w.n, 0, DEV)
+    V = gw.make_values(w, w.n, 0, DEV)
+    ib = gw.make_init_B(w, w.rank, 0, DEV)
+    pu.compress_both(gc, oc, K, V, w.rank, w.iters, ib)
+    q = gw.make_queries(w, 0, DEV)
+    rep = pu.compare_attention(gc, oc, q)          # one decode query, empty buffer
+    say("  config0 attention ->", rep)
+    # exactly ceil(2% * N) outliers per vector
+    mask, _ = gc.export_sparse(0)
+    assert (mask.sum(dim=2) == 11).all()           # ceil(0.02*512) per Key channel
+    mask, _ = gc.export_sparse(1)
+    assert (mask.sum(dim=(1, 3)) == 82).all()      # ceil(0.02*4096) per Value token
+
+
+def test_repeatable_bitwise():
+    """No float atomics on the path: two runs give identical bytes."""
+    w = small_workload(B=1, H_kv=4, H_q=8, n=200, bits=2, g=64, ppm=20000, rank=4, seed=3)
+    outs = []
+    for _ in range(2):
+        gc, _ = pu.make_pair(1, 4, 8, 2, 64, 20000, 20, 200, 1, 4)
+        K = gw.make_keys(w, 200, 0, DEV)
+        V = gw.make_values(w, 200, 0, DEV)
+        gc.compress(K, V, 4, 3, gw.make_init_B(w, 4, 0, DEV))
+        Kh, Vh = gc.decompress()
+        o = gc.decode_attn(gw.make_queries(w, 0, DEV))
+        outs.append((Kh.clone(), Vh.clone(), o.clone()))
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)
