@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the GEAR hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic KV of the
+configured LLaMA-2-7B layer shape (BASELINE config 1 by default):
+  1. gear_compress of the n-token prefill (Filter, Quant, power iteration),
+  2. n_b decode iterations: the new token's k/v row is already in its buffer
+     slot (the push is the caller writing that row), then gear_decode_attn over
+     the compressed cache + the buffer rows so far,
+  3. gear_compress of the full buffer as a new chunk (rank r_g).
+Decode iterations run on a cache replica that was compressed in an earlier step
+and rotate over three replicas, so their reads come from HBM and not from the
+256 MB Infinity Cache.
+
+Prints ONE JSON line.  value = KV compress GB/s (fp16 K+V input bytes of the
+prefill / time of its gear_compress call); the decode-attention rate is given
+beside it.  Both carry their fraction of the 8 TB/s HBM roofline computed from
+ALGORITHMIC bytes (one read of the input plus the compressed output for
+compress; the compressed cache plus live buffer rows for decode).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def outlier_count(n_v, ppm):
+    return min(n_v, -((-ppm * n_v) // 1_000_000))
+
+
+def compressed_bytes(w, n, rank):
+    """Algorithmic bytes of one compressed segment of n tokens, K + V, whole batch."""
+    slabs = w.B * w.H_kv
+    d = w.d_h
+    codes = 2 * slabs * n * d * w.bits // 8
+    sz = slabs * (4 * (-(-n // w.group)) * d + 4 * n * d // w.group)
+    lowrank = 2 * slabs * (2 * n * rank + 2 * d * rank)
+    sparse = 4 * (slabs * d * outlier_count(n, w.outlier_ppm) + w.B * n * outlier_count(w.H_kv * d, w.outlier_ppm))
+    return codes + sz + lowrank + sparse
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=6)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=1, help="index into gear_workloads.CONFIGS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over batch with no "
+              "exchange; see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import gear_workloads as gw
+    from paper_2403_05527_amd import binding as gb
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    gb.load_library()
+    dev = "cuda:0"
+    w = gw.CONFIGS[args.config]
+    NREP = 3
+    max_chunks = min(128, args.steps + args.warmup + 1)
+    cfg = gb.make_config(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, w.n_b, w.n, max_chunks,
+                         max(w.rank, w.rank_chunk))
+    K = gw.make_keys(w, w.n, 0, dev)
+    V = gw.make_values(w, w.n, 0, dev)
+    ib = gw.make_init_B(w, w.rank, 0, dev)
+    ibc = gw.make_init_B(w, w.rank_chunk, 1, dev)
+    Kb = gw.make_keys(w, w.n_b, 1, dev)          # decode-time tokens, one buffer's worth
+    Vb = gw.make_values(w, w.n_b, 1, dev)
+    qs = [gw.make_queries(w, i, dev) for i in range(w.n_b)]
+    out = torch.empty_like(qs[0])
+    pre = gb.GearCache(cfg, dev)                 # target of the timed prefill compress
+    reps = [gb.GearCache(cfg, dev) for _ in range(NREP)]   # caches the decode iterations read
+    for r in reps:
+        r.compress(K, V, w.rank, w.iters, ib)
+    torch.cuda.synchronize()
+
+    in_bytes = 2 * K.numel() * 2
+    comp_bytes = compressed_bytes(w, w.n, w.rank)
+    chunk_bytes = compressed_bytes(w, w.n_b, w.rank_chunk)
+    row_bytes = 2 * w.B * w.H_kv * w.d_h * 2          # one k row + one v row per slab
+    qo_bytes = 2 * w.B * w.H_q * w.d_h * 2
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    t_comp, t_dec, t_chunk, dec_bytes = [], [], [], []
+
+    def step(i, record):
+        e0, e1 = ev(), ev()
+        pre.reset()
+        e0.record()
+        pre.compress(K, V, w.rank, w.iters, ib)
+        e1.record()
+        devs = []
+        for t in range(w.n_b):
+            d = reps[(i * w.n_b + t) % NREP]     # rotate: each read of a replica follows reads of the other two
+            a, b = ev(), ev()
+            a.record()
+            d.decode_attn(qs[t], Kb, Vb, t + 1, out)
+            b.record()
+            devs.append((a, b, d.cache.n_chunks, t + 1))
+        c0, c1 = ev(), ev()
+        d = reps[i % NREP]
+        c0.record()
+        if d.cache.n_chunks < max_chunks:
+            d.compress(Kb, Vb, w.rank_chunk, w.iters, ibc)
+        c1.record()
+        return (e0, e1, devs, c0, c1) if record else None
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    recs = []
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        recs.append(step(args.warmup + i, True))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for (e0, e1, devs, c0, c1) in recs:
+        t_comp.append(e0.elapsed_time(e1) * 1e-3)
+        t_chunk.append(c0.elapsed_time(c1) * 1e-3)
+        for (a, b, n_chunks, n_buf) in devs:
+            t_dec.append(a.elapsed_time(b) * 1e-3)
+            dec_bytes.append(comp_bytes + n_chunks * chunk_bytes + n_buf * row_bytes + qo_bytes)
+
+    mean = lambda x: sum(x) / len(x)
+    tc, td = mean(t_comp), mean(t_dec)
+    comp_gbps = in_bytes / tc / 1e9
+    comp_algo_gbps = (in_bytes + comp_bytes) / tc / 1e9
+    dec_algo_gbps = mean(dec_bytes) / td / 1e9
+    res = {
+        "metric": "KV compress GB/s + compressed-KV decode attn tokens/s; % of HBM roofline",
+        "value": round(comp_gbps, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H_kv": w.H_kv, "H_q": w.H_q, "d_h": w.d_h, "n": w.n,
+                   "bits": w.bits, "group": w.group, "outlier_ppm": w.outlier_ppm, "rank": w.rank,
+                   "rank_chunk": w.rank_chunk, "n_b": w.n_b, "iters": w.iters},
+        "compress_ms": round(tc * 1e3, 4),
+        "chunk_compress_ms": round(mean(t_chunk) * 1e3, 4),
+        "decode_attn_us": round(td * 1e6, 2),
+        "decode_attn_tokens_per_s": round(w.B / td, 1),
+        "roofline": {"bound": "hbm", "kernel": "gear_decode_attn (decode_split_kernel + combine)",
+                     "achieved": round(dec_algo_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(dec_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+        "roofline_compress": {"bound": "hbm", "kernel": "gear_compress (all kernels of the call)",
+                              "achieved": round(comp_algo_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                              "frac": round(comp_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, K, V, ib, qs[0])
+    print(json.dumps(res), flush=True)
+
+
+def cpu_baseline(w, K, V, ib, q):
+    """The oracle as it stands, timed on the host cores on ONE batch element
+    (all heads) of the same workload: one compress + two decode reads."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import gear_oracle as go
+    Kh = K[:1].cpu().numpy()
+    Vh = V[:1].cpu().numpy()
+    ibh = ib[:, :1].cpu().numpy()
+    qh = q[:1].cpu().numpy()
+    cores = len(os.sched_getaffinity(0))
+    with threadpool_limits(limits=1):
+        oc = go.OracleCache(1, w.H_kv, w.H_q, w.d_h, w.bits, w.group, w.outlier_ppm)
+        t0 = time.perf_counter()
+        oc.compress(Kh, Vh, w.rank, w.iters, ibh)
+        tc = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        for _ in range(2):
+            oc.decode_attn(qh)
+        td = (time.perf_counter() - t0) / 2
+    return {"value": round(2 * Kh.nbytes / tc / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "host_cores_available": cores,
+            "decode_attn_tokens_per_s": round(1.0 / td, 3),
+            "sample": "1 of %d batch elements (all %d heads, n=%d): one compress (%.1f s) + 2 decode reads "
+                      "(%.2f s each), numpy oracle pinned to 1 thread" % (w.B, w.H_kv, w.n, tc, td)}
+
+
+if __name__ == "__main__":
+    main()
