@@ -345,6 +345,7 @@ class OracleCache:
                 p = np.exp(s - s.max())
                 p /= p.sum()
                 out[b, i, 0] = p @ Vall[b, h]
+        self.last_attn_f64 = out          # unrounded result, for error reporting
         return out.astype(F16)
 
 

@@ -326,9 +326,11 @@ __global__ __launch_bounds__(256) void v_filter_quant_kernel(const uint16_t* __r
       for (int ch = 0; ch < NC; ++ch) {
         const int head = 4 * ch + hsub;
         if (head < H) {
-          uint32_t* dst = sv.codes + ((size_t)(b * H + head) * sv.nblk_cap + blk) * 512 + (kg * 16 + oc) * 8;
-          *reinterpret_cast<uint4*>(dst) = make_uint4(acc[ch][0], acc[ch][1], acc[ch][2], acc[ch][3]);
-          *reinterpret_cast<uint4*>(dst + 4) = make_uint4(acc[ch][4], acc[ch][5], acc[ch][6], acc[ch][7]);
+          // channel c = 8*oc + e sits in word (kg*16 + c%16)*8 + c/16 of the block
+          uint32_t* dst = sv.codes + ((size_t)(b * H + head) * sv.nblk_cap + blk) * 512 +
+                          (kg * 16 + 8 * (oc & 1)) * 8 + (oc >> 1);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dst[e * 8] = acc[ch][e];
         }
       }
     }

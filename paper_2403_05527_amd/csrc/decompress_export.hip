@@ -28,7 +28,7 @@ __device__ __forceinline__ uint32_t load_code(const SegView& sv, const Dims& dm,
   }
   const int tgg = t / dm.tpw, i = t - tgg * dm.tpw;
   const uint32_t w =
-      sv.codes[((size_t)slab * sv.nblk_cap + (tgg >> 2)) * 512 + ((tgg & 3) * 16 + (c >> 3)) * 8 + (c & 7)];
+      sv.codes[((size_t)slab * sv.nblk_cap + (tgg >> 2)) * 512 + ((tgg & 3) * 16 + (c & 15)) * 8 + (c >> 4)];
   return (w >> (i * dm.bits)) & cmask;
 }
 __device__ __forceinline__ uint32_t load_sz(const SegView& sv, const Dims& dm, bool is_k, int slab, int t, int c) {

@@ -93,7 +93,7 @@ WorkLayout work_layout(const gear_config& c) {
   w.partial = o; o += up(slabs * (size_t)npart * (D * R + R * R) * 4);
   w.Atmp = o; o += up(slabs * (size_t)n_max * R * 4);
   w.cmat = o; o += up(slabs * R * R * 4);
-  const int nsplit = (c.n_prefill_max + DECODE_TS - 1) / DECODE_TS;
+  const int nsplit = (c.n_prefill_max + DECODE_SPLIT - 1) / DECODE_SPLIT;
   w.dec = o; o += up((size_t)c.B * c.H_q * (nsplit + 1) * DECODE_REC * 4);
   w.bytes = o;
   return w;

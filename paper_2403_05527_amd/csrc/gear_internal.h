@@ -42,8 +42,9 @@ struct Dims {
 //  Keys   codes : [slab][n_cap][wpr] u32, token-major rows, channel c at bits
 //                 (c % (32/b))*b of word c*b/32.
 //  Values codes : [slab][nblk_cap][512] u32 in blocks of 4*tpw tokens; word
-//                 (kg*16 + c/8)*8 + c%8 of a block holds channel c for the tpw
-//                 tokens 4*tpw*blk + tpw*kg + i at bits i*b.
+//                 (kg*16 + c%16)*8 + c/16 of a block holds channel c for the tpw
+//                 tokens 4*tpw*blk + tpw*kg + i at bits i*b (the order in which
+//                 the decode kernel's MFMA B operand consumes them).
 //  sz           : (scale, zero) as two fp16 in one u32 (scale low half).
 //                 Keys [slab][ng_cap][128]; Values [slab][n_cap][128/g].
 //  A, Bf        : fp16 [slab][n_cap][rank], [slab][128][rank].

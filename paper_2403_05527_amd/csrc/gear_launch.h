@@ -28,7 +28,8 @@ hipError_t launch_power_iteration(bool is_k, const uint16_t* X, const SegView& s
                                   int iters, const float* init_B, const Thresh* thr, float* Bcur,
                                   float* partial, float* Atmp, float* cmat, hipStream_t st);
 
-constexpr int DECODE_TS = 256;           // tokens per split block
+constexpr int DECODE_TS = 256;           // rows per pass of the chunk / buffer path
+constexpr int DECODE_SPLIT = 512;        // prefill tokens per split block
 constexpr int DECODE_REC = 2 + D;        // floats per partial record: m, l, o[128]
 hipError_t launch_decode(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                          const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,

@@ -86,10 +86,17 @@ def compare_lowrank_product(gc, oc, seg):
 
 
 def compare_attention(gc, oc, q, K_buf=None, V_buf=None, n_buf=0):
+    """fp16 outputs within max-abs 2e-3 of the oracle's; where an output is so
+    large (|o| >= 4) that one fp16 unit in the last place exceeds 2e-3, one such
+    unit is allowed (both sides round the final result to fp16)."""
     out_g = np16(gc.decode_attn(q, K_buf, V_buf, n_buf)).astype(np.float64)
     out_o = oc.decode_attn(np16(q), None if K_buf is None else np16(K_buf),
                            None if V_buf is None else np16(V_buf), n_buf).astype(np.float64)
-    err = float(np.abs(out_g - out_o).max())
     assert np.isfinite(out_g).all()
-    assert err <= ATTN_ABS_TOL, "attention max-abs error %.3e" % err
-    return {"attn_max_abs": err}
+    diff = np.abs(out_g - out_o)
+    ulp = np.spacing(np.abs(out_o).astype(np.float16)).astype(np.float64)
+    tol = np.maximum(ATTN_ABS_TOL, ulp)
+    err = float(diff.max())
+    assert (diff <= tol).all(), "attention max-abs error %.3e (max |o| %.2f)" % (err, np.abs(out_o).max())
+    pre = float(np.abs(out_g - oc.last_attn_f64).max())      # against the unrounded oracle
+    return {"attn_max_abs": err, "attn_vs_f64": pre, "attn_max_out": float(np.abs(out_o).max())}
