@@ -343,7 +343,7 @@ __global__ __launch_bounds__(256) void v_filter_quant_kernel(const uint16_t* __r
       const int j0 = h * D + 2 * lane;
       const uint32_t c = __popc(colmask[2 * j0]) + __popc(colmask[2 * j0 + 1]) + __popc(colmask[2 * j0 + 2]) +
                          __popc(colmask[2 * j0 + 3]);
-      const uint32_t tot = wave_sum(c);
+      const uint32_t tot = wave_sum_shfl(c);
       if (lane == 0) head_cnt[h] = tot;
     }
     __syncthreads();

@@ -13,6 +13,11 @@
 // code * 2^(s-24); gfx950's MFMA honours fp16 denormals, and the 2^s is undone
 // in the other operand.  The zero-point, low-rank and sparse terms are added
 // outside the MFMA.
+//
+// The block is latency-bound unless every global load is in flight at once:
+// a prologue issues all loads (Key codes into registers; scale/zero, low-rank
+// factors and outlier lists into LDS), and the phases after it touch global
+// memory only for the Value codes, which are requested before the softmax.
 #pragma once
 #include "gear_internal.h"
 
@@ -21,22 +26,20 @@ namespace gear {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int MFMA_TS = 512;                 // tokens per block
+constexpr int MFMA_TS = 512;                 // tokens per block (128 per wave)
 constexpr float MFMA_OUT_SCALE = 1048576.f;  // 2^24 / 16: undoes the denormal and operand scaling
 
 __device__ __forceinline__ half8 as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
   return __builtin_bit_cast(half8, make_uint4(a, b, c, d));
 }
 
-// Pairs of one 32-bit code word, in operand order.  Pair v holds the codes at
-// index (v, v + P/… ) of the low and high 16-bit halves.
-//  2 bits: 16 codes, 8 pairs: pair v = codes (v, v+8), bit shift LG2[v]
-//  4 bits:  8 codes, 4 pairs: pair v = codes (v, v+4), bit shift LG4[v]
+// Pairs of one 32-bit code word, in operand order.
+//  2 bits: 16 codes, 8 pairs: pair v = codes (v, v+8), bit shift lg(v)
+//  4 bits:  8 codes, 4 pairs: pair v = codes (v, v+4), bit shift lg(v)
 template <int BITS>
 struct Codec;
 template <>
 struct Codec<2> {
-  static constexpr int PAIRS = 8;
   __device__ static __forceinline__ void unpack(uint32_t w, uint32_t* v) {
     v[0] = w & 0x00030003u;
     v[1] = w & 0x000C000Cu;
@@ -52,7 +55,6 @@ struct Codec<2> {
 };
 template <>
 struct Codec<4> {
-  static constexpr int PAIRS = 4;
   __device__ static __forceinline__ void unpack(uint32_t w, uint32_t* v) {
     v[0] = w & 0x000F000Fu;
     v[1] = w & 0x00F000F0u;
@@ -66,11 +68,11 @@ struct Codec<4> {
 // 2^(4 - lg) as a float (operand scale 16 / 2^lg)
 __device__ __forceinline__ float opscale(int lg) { return __uint_as_float((uint32_t)(127 + 4 - lg) << 23); }
 
-// Position of Key channel ch inside the B operand of lane group kg = ch/32:
-// returns the fp16 index (0..31) within the lane's 4 k-blocks x 8 slots and the
+// Position of Key channel ch (r = ch % 32 inside lane group ch / 32) in the B
+// operand: fp16 index (0..31) within the lane's 4 k-blocks x 8 slots, and the
 // bit shift of its pair.
 template <int BITS>
-__device__ __forceinline__ void key_slot(int r /* ch % 32 */, int& idx, int& lg) {
+__device__ __forceinline__ void key_slot(int r, int& idx, int& lg) {
   if (BITS == 2) {
     const int wi = r >> 4, i = r & 15, p = i >> 3, vv = i & 7;
     idx = (wi * 2 + (vv >> 2)) * 8 + (vv & 3) * 2 + p;
@@ -81,8 +83,8 @@ __device__ __forceinline__ void key_slot(int r /* ch % 32 */, int& idx, int& lg)
     lg = Codec<4>::lg(v);
   }
 }
-// Position of token t (inside a Value code block) in the A operand of lane
-// group kg: kg, fp16 index within the lane's slots, bit shift.
+// Position of token t of a Value code block in the A operand: lane group,
+// fp16 index within the lane's slots, bit shift.
 template <int BITS>
 __device__ __forceinline__ void val_slot(int t, int& kg, int& idx, int& lg) {
   if (BITS == 2) {  // 64-token block, 16 tokens per word, two MFMAs
@@ -98,33 +100,186 @@ __device__ __forceinline__ void val_slot(int t, int& kg, int& idx, int& lg) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// LDS layout of one MFMA block (byte offsets into dynamic shared memory)
+// ---------------------------------------------------------------------------
+struct MfmaLayout {
+  int q, sc, szk, szv, ak, av, bfk, bfv, spk, spv, osp, opnd, misc, total;
+  int spcap;       // staged outlier entries per tensor
+  int opnd_halfs;  // operand staging per wave
+};
 template <int GQ>
-struct MfmaSmem {
-  float q[GQ][D];
-  float sc[GQ][MFMA_TS];      // raw scores, then p
-  float o_fin[GQ][D];
-  float kbase[GQ][MFMA_TS / 32];
+struct MfmaMisc {
+  float kbase[GQ][16];
   float qB[GQ][8];
   float wv[GQ][8];
+  float wred[4][GQ][8];
   float pm[4][GQ][4];
   float red[GQ][4];
   float stat[GQ][2];
+  uint2 tabk[8], tabv[8];
+  uint32_t offk[9], offv[9];
 };
+__host__ __device__ inline int up16i(int x) { return (x + 15) & ~15; }
+template <int GQ>
+__host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int rv, int ppm) {
+  MfmaLayout L;
+  const int TB = bits == 2 ? 64 : 32, NG = D / g;
+  int o = 0;
+  L.q = o; o += GQ * D * 4;
+  L.sc = o; o += GQ * MFMA_TS * 4;
+  L.szk = o; o += (MFMA_TS / g) * D * 4;
+  L.szv = o; o += MFMA_TS * NG * 4;
+  L.ak = o; o += up16i(MFMA_TS * rk * 2);
+  L.av = o; o += up16i(MFMA_TS * rv * 2);
+  L.bfk = o; o += up16i(D * rk * 2);
+  L.bfv = o; o += up16i(D * rv * 2);
+  int cap = 0;
+  if (ppm > 0) {
+    const long long expect = ((long long)MFMA_TS * D * ppm + 999999) / 1000000;
+    cap = (int)((expect * 12 / 10 + 64 + 127) / 128 * 128);
+    if (cap > 2048) cap = 2048;
+  }
+  L.spcap = cap;
+  L.spk = o; o += cap * 4;
+  L.spv = o; o += cap * 4;
+  L.osp = o; o += 4 * GQ * D * 4;
+  int oh = 2 * GQ * D;
+  if (NG * 2 * GQ * TB > oh) oh = NG * 2 * GQ * TB;
+  L.opnd_halfs = oh;
+  L.opnd = o; o += 4 * oh * 2;
+  L.misc = o; o += up16i((int)sizeof(MfmaMisc<GQ>));
+  L.total = o;
+  return L;
+}
 
-// Key scores of the block's tokens into S.sc (raw: before the 1/sqrt(d) scale,
-// without low-rank and sparse terms but including the zero-point term).
-// opnd: this wave's operand staging area (>= 16*128 fp16).
+// Cooperative copy of `count` fp16 values global -> LDS (any alignment).
+__device__ __forceinline__ void stage_halfs(uint16_t* dst, const uint16_t* src, int count) {
+  const int tid = threadIdx.x;
+  if (((reinterpret_cast<uintptr_t>(src) & 7u) == 0) && (count & 3) == 0) {
+    for (int i = tid; i < count / 4; i += 256)
+      reinterpret_cast<uint2*>(dst)[i] = reinterpret_cast<const uint2*>(src)[i];
+  } else {
+    for (int i = tid; i < count; i += 256) dst[i] = src[i];
+  }
+}
+
+// One block of MFMA_TS prefill tokens [t_begin, t_end) of slab (b, h): writes the
+// partial softmax record (m, l, o[128]) of each of the GQ query heads.
 template <int BITS, int GQ>
-__device__ __forceinline__ void mfma_key_scores(MfmaSmem<GQ>& S, _Float16* opnd, const Dims& dm, const SegView& ks,
-                                                int slab, int t_begin, int t_end) {
+__device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& ks, const SegView& vs,
+                           const uint16_t* __restrict__ qg /* q of query head h*GQ of batch b */, int slab, int b,
+                           int t_begin, int t_end, float* __restrict__ rec_base, int rec_stride) {
+  constexpr int TB = (BITS == 2) ? 64 : 32;   // tokens per Value code block
+  constexpr int KW = (BITS == 2) ? 2 : 4;     // Key code words per lane per M-tile
+  constexpr int VBLK = 128 / TB;              // Value blocks per wave
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n16 = lane & 15, kg = lane >> 4;
-  const int g = dm.g;
-  const int ngroups = MFMA_TS / g;  // uniform over waves; groups past t_end are skipped
-  for (int gl = wave; gl < ngroups; gl += 4) {
-    const int tg0 = t_begin + gl * g;
-    const bool gvalid = tg0 < t_end;
-    // ---- operand w = q * scale (hi / lo parts), and the zero-point term
+  const int g = dm.g, NG = D / g;
+  const int rk = ks.rank, rv = vs.rank;
+  const int nr = t_end - t_begin;
+  const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk, rv, dm.ppm);
+  float* Sq = reinterpret_cast<float*>(smem + L.q);                 // [GQ][128]
+  float* Ssc = reinterpret_cast<float*>(smem + L.sc);               // [GQ][512]
+  uint32_t* Sszk = reinterpret_cast<uint32_t*>(smem + L.szk);       // [512/g][128]
+  uint32_t* Sszv = reinterpret_cast<uint32_t*>(smem + L.szv);       // [512][NG]
+  uint16_t* Sak = reinterpret_cast<uint16_t*>(smem + L.ak);         // [512][rk]
+  uint16_t* Sav = reinterpret_cast<uint16_t*>(smem + L.av);
+  uint16_t* Sbfk = reinterpret_cast<uint16_t*>(smem + L.bfk);       // [128][rk]
+  uint16_t* Sbfv = reinterpret_cast<uint16_t*>(smem + L.bfv);
+  uint32_t* Sspk = reinterpret_cast<uint32_t*>(smem + L.spk);       // staged lists, (row*128 + c) | val << 16
+  uint32_t* Sspv = reinterpret_cast<uint32_t*>(smem + L.spv);
+  float* Sosp = reinterpret_cast<float*>(smem + L.osp);             // [4 waves][GQ][128]
+  _Float16* opnd = reinterpret_cast<_Float16*>(smem + L.opnd) + (size_t)wave * L.opnd_halfs;
+  MfmaMisc<GQ>& M = *reinterpret_cast<MfmaMisc<GQ>*>(smem + L.misc);
+  const float scale = 0.08838834764831845f;  // 1/sqrt(128)
+  const int tile0 = t_begin / TILE, ntiles = (nr + TILE - 1) / TILE;
+  const int tw0 = t_begin + 128 * wave;       // first token owned by this wave
+
+  // =================== prologue: every load in flight ===================
+  if (dm.ppm > 0 && tid < 16) {
+    const int i = tid & 7;
+    uint2 e = make_uint2(0, 0);
+    if (i < ntiles)
+      e = (tid < 8) ? ks.sp_table[(size_t)slab * ks.ntile_cap + tile0 + i]
+                    : vs.sp_table[(size_t)slab * vs.ntile_cap + tile0 + i];
+    if (tid < 8) M.tabk[i] = e; else M.tabv[i] = e;
+  }
+  // Key codes of this wave's 8 M-tiles into registers
+  uint32_t kw[8][KW];
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) {
+    const int t = tw0 + 16 * mt + n16;
+#pragma unroll
+    for (int j = 0; j < KW; ++j) kw[mt][j] = 0u;
+    if (t < t_end) {
+      const uint32_t* p = ks.codes + ((size_t)slab * ks.n_cap + t) * (4 * BITS) + KW * kg;
+      if (BITS == 2) {
+        const uint2 w = *reinterpret_cast<const uint2*>(p);
+        kw[mt][0] = w.x; kw[mt][1] = w.y;
+      } else {
+        const uint4 w = *reinterpret_cast<const uint4*>(p);
+        kw[mt][0] = w.x; kw[mt][1] = w.y; kw[mt][2] = w.z; kw[mt][3] = w.w;
+      }
+    }
+  }
+  for (int i = tid; i < GQ * D; i += 256) Sq[i] = h2f(qg[i]);
+  {
+    const int ngl = (nr + g - 1) / g;
+    const uint32_t* src = ks.sz + ((size_t)slab * ks.ng_cap + t_begin / g) * D;
+    for (int i = tid; i < ngl * D; i += 256) Sszk[i] = src[i];
+    const uint32_t* srcv = vs.sz + ((size_t)slab * vs.n_cap + t_begin) * NG;
+    for (int i = tid; i < nr * NG; i += 256) Sszv[i] = srcv[i];
+  }
+  if (rk > 0) {
+    stage_halfs(Sak, ks.A + ((size_t)slab * ks.n_cap + t_begin) * rk, nr * rk);
+    stage_halfs(Sbfk, ks.Bf + (size_t)slab * D * rk, D * rk);
+  }
+  if (rv > 0) {
+    stage_halfs(Sav, vs.A + ((size_t)slab * vs.n_cap + t_begin) * rv, nr * rv);
+    stage_halfs(Sbfv, vs.Bf + (size_t)slab * D * rv, D * rv);
+  }
+  for (int i = tid; i < 4 * GQ * D; i += 256) Sosp[i] = 0.0f;
+  __syncthreads();
+
+  // outlier lists: prefix offsets of the tiles' lists inside the staging area
+  bool sp_fits = true;
+  if (dm.ppm > 0) {
+    if (tid < 2) {
+      uint32_t run = 0;
+      uint32_t* off = tid == 0 ? M.offk : M.offv;
+      const uint2* tab = tid == 0 ? M.tabk : M.tabv;
+      for (int i = 0; i < 8; ++i) { off[i] = run; run += tab[i].y; }
+      off[8] = run;
+    }
+    __syncthreads();
+    sp_fits = M.offk[8] <= (uint32_t)L.spcap && M.offv[8] <= (uint32_t)L.spcap;
+  }
+
+  // q^T B_K (down-projection of the low-rank Key term)
+  if (tid < GQ * 8) {
+    const int hq = tid >> 3, r = tid & 7;
+    float s = 0.0f;
+    if (r < rk)
+      for (int c = 0; c < D; ++c) s += Sq[hq * D + c] * h2f(Sbfk[c * rk + r]);
+    M.qB[hq][r] = s;
+  }
+
+  // =================== Key scores on the matrix cores ===================
+  // wave owns tokens tw0 .. tw0+127: 128/g groups of g/16 M-tiles
+  int kslot[2];     // operand position of channels lane and lane + 64 (same for every group)
+  float kscale[2];
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) {
+    const int ch = lane + 64 * rep;
+    int idx, lg;
+    key_slot<BITS>(ch & 31, idx, lg);
+    kslot[rep] = (ch >> 5) * 32 + idx;
+    kscale[rep] = opscale(lg);
+  }
+  for (int gw = 0; gw < 128 / g; ++gw) {
+    const int gl = (128 * wave) / g + gw;           // group index inside the block
+    const bool gvalid = t_begin + gl * g < t_end;   // wave-uniform
     if (gvalid) {
       float base[GQ];
 #pragma unroll
@@ -132,15 +287,13 @@ __device__ __forceinline__ void mfma_key_scores(MfmaSmem<GQ>& S, _Float16* opnd,
 #pragma unroll
       for (int rep = 0; rep < 2; ++rep) {
         const int ch = lane + 64 * rep;
-        const uint32_t sb = ks.sz[((size_t)slab * ks.ng_cap + tg0 / g) * D + ch];
+        const uint32_t sb = Sszk[gl * D + ch];
         const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
-        int idx, lg;
-        key_slot<BITS>(ch & 31, idx, lg);
-        const float os = opscale(lg);
-        _Float16* dst = opnd + (ch >> 5) * 32 + idx;
+        const float os = kscale[rep];
+        _Float16* dst = opnd + kslot[rep];
 #pragma unroll
         for (int hq = 0; hq < GQ; ++hq) {
-          const float qv = S.q[hq][ch];
+          const float qv = Sq[hq * D + ch];
           const float w = qv * delta * os;
           const _Float16 hi = (_Float16)w;
           const _Float16 lo = (_Float16)(w - (float)hi);
@@ -151,11 +304,11 @@ __device__ __forceinline__ void mfma_key_scores(MfmaSmem<GQ>& S, _Float16* opnd,
       }
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
-        const float b = wave_sum(base[hq]);
-        if (lane == 0) S.kbase[hq][gl] = b;
+        const float bsum = wave_sum(base[hq]);
+        if (lane == 0) M.kbase[hq][gl] = bsum;
       }
     }
-    __syncthreads();
+    wave_lds_sync();  // staging area is private to the wave
     if (gvalid) {
       half8 bop[4];
 #pragma unroll
@@ -164,142 +317,393 @@ __device__ __forceinline__ void mfma_key_scores(MfmaSmem<GQ>& S, _Float16* opnd,
         if (n16 < 2 * GQ) raw = *reinterpret_cast<const uint4*>(opnd + n16 * D + kg * 32 + jb * 8);
         bop[jb] = __builtin_bit_cast(half8, raw);
       }
-      for (int mt = 0; mt < g / 16; ++mt) {
-        const int t = tg0 + 16 * mt + n16;
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        if (BITS == 2) {
-          uint2 w = make_uint2(0, 0);
-          if (t < t_end) w = *reinterpret_cast<const uint2*>(ks.codes + ((size_t)slab * ks.n_cap + t) * 8 + 2 * kg);
-          uint32_t v[8];
-          Codec<2>::unpack(w.x, v);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[0], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[1], acc, 0, 0, 0);
-          Codec<2>::unpack(w.y, v);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[2], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[3], acc, 0, 0, 0);
-        } else {
-          uint4 w = make_uint4(0, 0, 0, 0);
-          if (t < t_end) w = *reinterpret_cast<const uint4*>(ks.codes + ((size_t)slab * ks.n_cap + t) * 16 + 4 * kg);
-          const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+      const int hq = n16 >> 1;
+      const float kb = (hq < GQ) ? M.kbase[hq][gl] : 0.0f;
 #pragma unroll
-          for (int jb = 0; jb < 4; ++jb) {
-            uint32_t v[4];
-            Codec<4>::unpack(ww[jb], v);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[jb], acc, 0, 0, 0);
+      for (int mt = 0; mt < 8; ++mt) {
+        if (mt / (g / 16) == gw) {
+          floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+          if (BITS == 2) {
+            uint32_t v[8];
+            Codec<2>::unpack(kw[mt][0], v);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[0], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[1], acc, 0, 0, 0);
+            Codec<2>::unpack(kw[mt][1], v);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[2], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[3], acc, 0, 0, 0);
+          } else {
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+              uint32_t v[4];
+              Codec<4>::unpack(kw[mt][jb % KW], v);
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[jb], acc, 0, 0, 0);
+            }
+          }
+          // D[token 4*kg + i][col n16]: add the hi and lo columns, keep the even ones
+          float4 s4;
+          s4.x = acc[0] + dpp_f<DPP_XOR1>(acc[0]);
+          s4.y = acc[1] + dpp_f<DPP_XOR1>(acc[1]);
+          s4.z = acc[2] + dpp_f<DPP_XOR1>(acc[2]);
+          s4.w = acc[3] + dpp_f<DPP_XOR1>(acc[3]);
+          if ((n16 & 1) == 0 && hq < GQ) {
+            s4.x = s4.x * MFMA_OUT_SCALE + kb;
+            s4.y = s4.y * MFMA_OUT_SCALE + kb;
+            s4.z = s4.z * MFMA_OUT_SCALE + kb;
+            s4.w = s4.w * MFMA_OUT_SCALE + kb;
+            *reinterpret_cast<float4*>(&Ssc[hq * MFMA_TS + 128 * wave + 16 * mt + 4 * kg]) = s4;
           }
         }
-        // D[token 4*kg + i][col n16]: add the hi and lo columns, keep the even ones
-        const int hq = n16 >> 1;
-        float4 s4;
-        s4.x = acc[0] + __shfl_xor(acc[0], 1, 64);
-        s4.y = acc[1] + __shfl_xor(acc[1], 1, 64);
-        s4.z = acc[2] + __shfl_xor(acc[2], 1, 64);
-        s4.w = acc[3] + __shfl_xor(acc[3], 1, 64);
-        if ((n16 & 1) == 0 && hq < GQ) {
-          const float kb = S.kbase[hq][gl];
-          s4.x = s4.x * MFMA_OUT_SCALE + kb;
-          s4.y = s4.y * MFMA_OUT_SCALE + kb;
-          s4.z = s4.z * MFMA_OUT_SCALE + kb;
-          s4.w = s4.w * MFMA_OUT_SCALE + kb;
-          *reinterpret_cast<float4*>(&S.sc[hq][gl * g + 16 * mt + 4 * kg]) = s4;
+      }
+    }
+    wave_lds_sync();  // staging area is private to the wave
+  }
+  __syncthreads();  // scores of all four waves are in LDS
+
+  // request this wave's Value codes now; they are consumed after the softmax
+  uint32_t vw[VBLK][8];
+#pragma unroll
+  for (int bl = 0; bl < VBLK; ++bl) {
+    const int tb0 = tw0 + bl * TB;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) vw[bl][j] = 0u;
+    if (tb0 < t_end) {
+      const uint32_t* cw = vs.codes + ((size_t)slab * vs.nblk_cap + tb0 / TB) * 512 + (kg * 16 + n16) * 8;
+      const uint4 c0 = *reinterpret_cast<const uint4*>(cw);
+      const uint4 c1 = *reinterpret_cast<const uint4*>(cw + 4);
+      vw[bl][0] = c0.x; vw[bl][1] = c0.y; vw[bl][2] = c0.z; vw[bl][3] = c0.w;
+      vw[bl][4] = c1.x; vw[bl][5] = c1.y; vw[bl][6] = c1.z; vw[bl][7] = c1.w;
+    }
+  }
+
+  // request the outlier lists (rows rebased to the block: (row*128 + c) | value << 16)
+  constexpr int SPR = 8;  // staged entries per thread and tensor (2048 / 256)
+  uint32_t spk_r[SPR], spv_r[SPR];
+  if (dm.ppm > 0 && sp_fits) {
+    const uint32_t* poolk = ks.sp_pool + (size_t)slab * ks.pool_cap;
+    const uint32_t* poolv = vs.sp_pool + (size_t)b * vs.pool_cap;
+#pragma unroll
+    for (int r = 0; r < SPR; ++r) {
+      const uint32_t e = tid + 256 * r;
+      spk_r[r] = 0u; spv_r[r] = 0u;
+      if (e < M.offk[8]) {
+        int ti = 0;
+#pragma unroll
+        for (int i = 1; i < 8; ++i) ti += (e >= M.offk[i]) ? 1 : 0;
+        const uint32_t en = poolk[M.tabk[ti].x + (e - M.offk[ti])];
+        spk_r[r] = ((en & 0xFFFFu) + (uint32_t)ti * (TILE * D)) | (en & 0xFFFF0000u);
+      }
+      if (e < M.offv[8]) {
+        int ti = 0;
+#pragma unroll
+        for (int i = 1; i < 8; ++i) ti += (e >= M.offv[i]) ? 1 : 0;
+        const uint32_t en = poolv[M.tabv[ti].x + (e - M.offv[ti])];
+        spv_r[r] = ((en & 0xFFFFu) + (uint32_t)ti * (TILE * D)) | (en & 0xFFFF0000u);
+      }
+    }
+  }
+  // low-rank Key term, tokens tid and tid + 256
+  if (rk > 0) {
+    for (int tl = tid; tl < nr; tl += 256) {
+      float a[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) a[r] = r < rk ? h2f(Sak[tl * rk + r]) : 0.0f;
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) {
+        float s = Ssc[hq * MFMA_TS + tl];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) s += M.qB[hq][r] * a[r];
+        Ssc[hq * MFMA_TS + tl] = s;
+      }
+    }
+  }
+  // staged outlier lists land in LDS
+  if (dm.ppm > 0 && sp_fits) {
+#pragma unroll
+    for (int r = 0; r < SPR; ++r) {
+      const uint32_t e = tid + 256 * r;
+      if (e < M.offk[8]) Sspk[e] = spk_r[r];
+      if (e < M.offv[8]) Sspv[e] = spv_r[r];
+    }
+  }
+  __syncthreads();
+
+  // sparse Key term.  Staged list is ordered (row, c): the first entry of a row sums the row's run.
+  if (dm.ppm > 0) {
+    if (sp_fits) {
+      const uint32_t cnt = M.offk[8];
+      for (uint32_t e = tid; e < cnt; e += 256) {
+        const uint32_t me = Sspk[e];
+        const uint32_t row = (me & 0xFFFFu) >> 7;
+        if (e > 0 && ((Sspk[e - 1] & 0xFFFFu) >> 7) == row) continue;
+        float a2[GQ];
+#pragma unroll
+        for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
+        for (uint32_t f = e; f < cnt; ++f) {
+          const uint32_t en = Sspk[f];
+          if (((en & 0xFFFFu) >> 7) != row) break;
+          const float v = h2f(en >> 16);
+          const int c = en & 127u;
+#pragma unroll
+          for (int hq = 0; hq < GQ; ++hq) a2[hq] += Sq[hq * D + c] * v;
+        }
+#pragma unroll
+        for (int hq = 0; hq < GQ; ++hq) Ssc[hq * MFMA_TS + row] += a2[hq];
+      }
+    } else {  // lists larger than the staging area: read them from global memory
+      for (int ti = 0; ti < ntiles; ++ti) {
+        const uint2 oc = M.tabk[ti];
+        const uint32_t* lst = ks.sp_pool + (size_t)slab * ks.pool_cap + oc.x;
+        for (uint32_t e = tid; e < oc.y; e += 256) {
+          const uint32_t me = lst[e];
+          const uint32_t tl = (me & 0xFFFFu) >> 7;
+          if (e > 0 && ((lst[e - 1] & 0xFFFFu) >> 7) == tl) continue;
+          float a2[GQ];
+#pragma unroll
+          for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
+          for (uint32_t f = e; f < oc.y; ++f) {
+            const uint32_t en = lst[f];
+            if (((en & 0xFFFFu) >> 7) != tl) break;
+            const float v = h2f(en >> 16);
+            const int c = en & 127u;
+#pragma unroll
+            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Sq[hq * D + c] * v;
+          }
+#pragma unroll
+          for (int hq = 0; hq < GQ; ++hq) Ssc[hq * MFMA_TS + ti * TILE + tl] += a2[hq];
         }
       }
     }
     __syncthreads();
   }
-}
 
-// Value side: o[hq][c] (quantized backbone incl. zero-point) of the block's
-// tokens from p in S.sc.  Results: acc_out[j][i] per lane (column n16 of
-// N-tile j, rows 4*kg + i), and S.pm[wave][hq][G] = sum_t p_t * zero_V[t][G].
-// opnd: this wave's staging area (>= NG*16*TB fp16).
-template <int BITS, int GQ>
-__device__ __forceinline__ void mfma_value_accum(MfmaSmem<GQ>& S, _Float16* opnd, const Dims& dm, const SegView& vs,
-                                                 int slab, int t_begin, int t_end, floatx4 (&acc)[8]) {
-  constexpr int TB = (BITS == 2) ? 64 : 32;  // tokens per code block
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int n16 = lane & 15, kg = lane >> 4;
-  const int g = dm.g, NG = D / g;
-  float pmr[GQ][4];
+  // =================== block-local softmax ===================
+  {
+    float s0[GQ], s1[GQ];
 #pragma unroll
-  for (int hq = 0; hq < GQ; ++hq)
+    for (int hq = 0; hq < GQ; ++hq) {
+      s0[hq] = tid < nr ? Ssc[hq * MFMA_TS + tid] * scale : -INFINITY;
+      s1[hq] = tid + 256 < nr ? Ssc[hq * MFMA_TS + tid + 256] * scale : -INFINITY;
+      const float mx = wave_max(fmaxf(s0[hq], s1[hq]));
+      if (lane == 0) M.red[hq][wave] = mx;
+    }
+    __syncthreads();
+    if (tid < GQ) M.stat[tid][0] = fmaxf(fmaxf(M.red[tid][0], M.red[tid][1]), fmaxf(M.red[tid][2], M.red[tid][3]));
+    __syncthreads();
 #pragma unroll
-    for (int G = 0; G < 4; ++G) pmr[hq][G] = 0.0f;
+    for (int hq = 0; hq < GQ; ++hq) {
+      const float m = M.stat[hq][0];
+      const float p0 = tid < nr ? __expf(s0[hq] - m) : 0.0f;
+      const float p1 = tid + 256 < nr ? __expf(s1[hq] - m) : 0.0f;
+      Ssc[hq * MFMA_TS + tid] = p0;         // rows >= nr hold p = 0
+      Ssc[hq * MFMA_TS + tid + 256] = p1;
+      const float sum = wave_sum(p0 + p1);
+      if (lane == 0) M.red[hq][wave] = sum;
+    }
+    __syncthreads();
+    if (tid < GQ) M.stat[tid][1] = M.red[tid][0] + M.red[tid][1] + M.red[tid][2] + M.red[tid][3];
+  }
+
+  // =================== Value side on the matrix cores ===================
+  floatx4 acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-  for (int bl = wave; bl < MFMA_TS / TB; bl += 4) {
-    const int tb0 = t_begin + bl * TB;
-    const bool bvalid = tb0 < t_end;
+  // operand prep: lane handles rows (lane >> lgNG) + k * (64 >> lgNG) of a code block for its own
+  // channel group Gl; positions and scales are the same for every block
+  const int lgNG = (NG == 1) ? 0 : (NG == 2) ? 1 : 2;
+  const int Gl = lane & (NG - 1);
+  const int tstep = 64 >> lgNG;
+  int vslot[4], vrow[4];
+  float vscale[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int tl = (lane >> lgNG) + k * tstep;
+    int skg, idx, lg;
+    val_slot<BITS>(tl & (TB - 1), skg, idx, lg);
+    vrow[k] = tl < TB ? tl : -1;
+    vslot[k] = Gl * 2 * GQ * TB + skg * (TB / 4) + idx;
+    vscale[k] = opscale(lg);
+  }
+  float pmr[GQ];
+#pragma unroll
+  for (int hq = 0; hq < GQ; ++hq) pmr[hq] = 0.0f;
+#pragma unroll
+  for (int bl = 0; bl < VBLK; ++bl) {
+    const int tl0 = 128 * wave + bl * TB;          // block-local first row of this code block
+    const bool bvalid = tl0 < nr;                  // wave-uniform
     if (bvalid) {
-      // ---- operand P = p * scale_V (hi / lo), and the zero-point sums
-      for (int pi = lane; pi < TB * NG; pi += 64) {
-        const int tl = pi / NG, G = pi - tl * NG;
-        const int tok = tb0 + tl;
-        const bool tv = tok < t_end;
-        const uint32_t sb = tv ? vs.sz[((size_t)slab * vs.n_cap + tok) * NG + G] : 0u;
-        const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
-        int skg, idx, lg;
-        val_slot<BITS>(tl, skg, idx, lg);
-        const float os = opscale(lg);
-        _Float16* dst = opnd + (size_t)G * 16 * TB + skg * (TB / 4) + idx;
 #pragma unroll
-        for (int hq = 0; hq < GQ; ++hq) {
-          const float pv = tv ? S.sc[hq][tok - t_begin] : 0.0f;
-          const float w = pv * delta * os;
-          const _Float16 hi = (_Float16)w;
-          const _Float16 lo = (_Float16)(w - (float)hi);
-          dst[(2 * hq) * TB] = hi;
-          dst[(2 * hq + 1) * TB] = lo;
+      for (int k = 0; k < 4; ++k) {
+        if (vrow[k] >= 0) {
+          const int row = tl0 + vrow[k];
+          const uint32_t sb = row < nr ? Sszv[row * NG + Gl] : 0u;
+          const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
+          const float ds = delta * vscale[k];
+          _Float16* dst = opnd + vslot[k];
 #pragma unroll
-          for (int GG = 0; GG < 4; ++GG)
-            if (GG == G) pmr[hq][GG] += pv * mn;
+          for (int hq = 0; hq < GQ; ++hq) {
+            const float pv = Ssc[hq * MFMA_TS + row];
+            const float w = pv * ds;
+            const _Float16 hi = (_Float16)w;
+            const _Float16 lo = (_Float16)(w - (float)hi);
+            dst[(2 * hq) * TB] = hi;
+            dst[(2 * hq + 1) * TB] = lo;
+            pmr[hq] += pv * mn;
+          }
         }
       }
     }
-    __syncthreads();
+    wave_lds_sync();  // staging area is private to the wave
     if (bvalid) {
-      const uint32_t* cw = vs.codes + ((size_t)slab * vs.nblk_cap + tb0 / TB) * 512 + (kg * 16 + n16) * 8;
-      const uint4 c0 = *reinterpret_cast<const uint4*>(cw);
-      const uint4 c1 = *reinterpret_cast<const uint4*>(cw + 4);
-      const uint32_t words[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
       const int tiles_per_G = g / 16;
       for (int G = 0; G < NG; ++G) {
-        const _Float16* src = opnd + (size_t)(G * 16 + n16) * TB + kg * (TB / 4);
-        half8 pa0, pa1;
+        half8 pa0 = __builtin_bit_cast(half8, make_uint4(0, 0, 0, 0)), pa1 = pa0;
         if (n16 < 2 * GQ) {
+          const _Float16* src = opnd + (size_t)(G * 2 * GQ + n16) * TB + kg * (TB / 4);
           pa0 = __builtin_bit_cast(half8, *reinterpret_cast<const uint4*>(src));
           if (BITS == 2) pa1 = __builtin_bit_cast(half8, *reinterpret_cast<const uint4*>(src + 8));
-        } else {
-          pa0 = __builtin_bit_cast(half8, make_uint4(0, 0, 0, 0));
-          pa1 = pa0;
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           if (j / tiles_per_G == G) {
             if (BITS == 2) {
               uint32_t v[8];
-              Codec<2>::unpack(words[j], v);
+              Codec<2>::unpack(vw[bl][j], v);
               acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa0, as_half8(v[0], v[1], v[2], v[3]), acc[j], 0, 0, 0);
               acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa1, as_half8(v[4], v[5], v[6], v[7]), acc[j], 0, 0, 0);
             } else {
               uint32_t v[4];
-              Codec<4>::unpack(words[j], v);
+              Codec<4>::unpack(vw[bl][j], v);
               acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa0, as_half8(v[0], v[1], v[2], v[3]), acc[j], 0, 0, 0);
             }
           }
         }
       }
     }
-    __syncthreads();
+    wave_lds_sync();  // staging area is private to the wave
   }
 #pragma unroll
   for (int hq = 0; hq < GQ; ++hq)
 #pragma unroll
     for (int G = 0; G < 4; ++G) {
-      const float s = wave_sum(pmr[hq][G]);
-      if (lane == 0) S.pm[wave][hq][G] = s;
+      if (G < NG) {  // wave-uniform
+        const float s = wave_sum(Gl == G ? pmr[hq] : 0.0f);
+        if (lane == 0) M.pm[wave][hq][G] = s;
+      } else if (lane == 0) {
+        M.pm[wave][hq][G] = 0.0f;
+      }
     }
+  // D[col 4*kg + i][channel 16 j + n16] -> this wave's accumulator plane
+  {
+    float* mine = Sosp + (size_t)wave * GQ * D;
+    const int hq0 = 2 * kg, hq1 = 2 * kg + 1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (hq0 < GQ) mine[hq0 * D + 16 * j + n16] = (acc[j][0] + acc[j][1]) * MFMA_OUT_SCALE;
+      if (hq1 < GQ) mine[hq1 * D + 16 * j + n16] = (acc[j][2] + acc[j][3]) * MFMA_OUT_SCALE;
+    }
+  }
+
+  // p^T A_V (down-projection of the low-rank Value term)
+  if (rv > 0) {
+    float part[GQ][8];
+#pragma unroll
+    for (int hq = 0; hq < GQ; ++hq)
+#pragma unroll
+      for (int r = 0; r < 8; ++r) part[hq][r] = 0.0f;
+    for (int tl = tid; tl < nr; tl += 256) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        if (r < rv) {
+          const float a = h2f(Sav[tl * rv + r]);
+#pragma unroll
+          for (int hq = 0; hq < GQ; ++hq) part[hq][r] += Ssc[hq * MFMA_TS + tl] * a;
+        }
+      }
+    }
+#pragma unroll
+    for (int hq = 0; hq < GQ; ++hq)
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        if (r < rv) {
+          const float s = wave_sum(part[hq][r]);
+          if (lane == 0) M.wred[wave][hq][r] = s;
+        }
+      }
+  }
+  __syncthreads();
+  if (tid < GQ * 8) {
+    const int hq = tid >> 3, r = tid & 7;
+    M.wv[hq][r] = r < rv ? (M.wred[0][hq][r] + M.wred[1][hq][r] + M.wred[2][hq][r] + M.wred[3][hq][r]) : 0.0f;
+  }
+
+  // sparse Value term.  Each tile's list is ordered (c, row): the first entry of a channel
+  // sums the channel's run.  Wave w takes tiles w, w+4 one after the other and
+  // adds into its own accumulator plane, so no two lanes ever update one address
+  // at the same time and the summation order is fixed.
+  if (dm.ppm > 0) {
+    float* mine = Sosp + (size_t)wave * GQ * D;
+    for (int ti = wave; ti < ntiles; ti += 4) {
+      if (sp_fits) {
+        const uint32_t e0 = M.offv[ti], e1 = M.offv[ti + 1];
+        for (uint32_t e = e0 + lane; e < e1; e += 64) {
+          const uint32_t me = Sspv[e];
+          const uint32_t ch = me & 127u;
+          if (e > e0 && (Sspv[e - 1] & 127u) == ch) continue;
+          float a2[GQ];
+#pragma unroll
+          for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
+          for (uint32_t f = e; f < e1; ++f) {
+            const uint32_t en = Sspv[f];
+            if ((en & 127u) != ch) break;
+            const float v = h2f(en >> 16);
+            const int row = (en & 0xFFFFu) >> 7;
+#pragma unroll
+            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * MFMA_TS + row] * v;
+          }
+#pragma unroll
+          for (int hq = 0; hq < GQ; ++hq) mine[hq * D + ch] += a2[hq];
+        }
+      } else {
+        const uint2 oc = M.tabv[ti];
+        const uint32_t* lst = vs.sp_pool + (size_t)b * vs.pool_cap + oc.x;
+        for (uint32_t e = lane; e < oc.y; e += 64) {
+          const uint32_t me = lst[e];
+          const uint32_t ch = me & 127u;
+          if (e > 0 && (lst[e - 1] & 127u) == ch) continue;
+          float a2[GQ];
+#pragma unroll
+          for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
+          for (uint32_t f = e; f < oc.y; ++f) {
+            const uint32_t en = lst[f];
+            if ((en & 127u) != ch) break;
+            const float v = h2f(en >> 16);
+            const int row = ti * TILE + (int)((en & 0xFFFFu) >> 7);
+#pragma unroll
+            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * MFMA_TS + row] * v;
+          }
+#pragma unroll
+          for (int hq = 0; hq < GQ; ++hq) mine[hq * D + ch] += a2[hq];
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+  __syncthreads();
+
+  // =================== combine the four waves, write the record ===================
+  for (int i = tid; i < GQ * D; i += 256) {
+    const int hq = i / D, c = i % D, G = c / g;
+    float o = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) o += Sosp[((size_t)w * GQ + hq) * D + c] + M.pm[w][hq][G];
+    for (int r = 0; r < rv; ++r) o += M.wv[hq][r] * h2f(Sbfv[c * rv + r]);
+    float* rec = rec_base + (size_t)hq * rec_stride;
+    rec[2 + c] = o;
+    if (c == 0) {
+      rec[0] = M.stat[hq][0];
+      rec[1] = M.stat[hq][1];
+    }
+  }
 }
 
 }  // namespace gear

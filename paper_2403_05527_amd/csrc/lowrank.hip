@@ -19,7 +19,7 @@ constexpr int PT = 256;  // tokens per sweep block
 
 template <typename T>
 __device__ __forceinline__ T block128_sum(T v, T* red /* >= 2 */) {
-  v = wave_sum(v);
+  v = wave_sum_shfl(v);
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
