@@ -251,15 +251,17 @@ class Segment:
 
 
 def compress_tensor(X16: np.ndarray, kind: str, bits: int, g: int, outlier_ppm: int,
-                    rank: int, iters: int, init_B: Optional[np.ndarray]) -> Segment:
+                    rank: int, iters: int, init_B: Optional[np.ndarray],
+                    mask: Optional[np.ndarray] = None) -> Segment:
     """Algorithm 1, prefill-phase body for one tensor X in {K, V} (the decoding
     phase runs the same body on the buffered tokens):
       S = Filter_s(X); D-hat = Quant_b(X - S); R = X - D-hat - S;
       L_h = SVDSolver_r(R_h) for every head (and batch element)."""
     assert X16.dtype == F16
     B, H, n, d = X16.shape
-    mask = (filter_keys if kind == "K" else filter_values)(X16, outlier_ppm) if outlier_ppm > 0 \
-        else np.zeros(X16.shape, bool)
+    if mask is None:       # a caller that holds only some heads passes the support it computed on all
+        mask = (filter_keys if kind == "K" else filter_values)(X16, outlier_ppm) if outlier_ppm > 0 \
+            else np.zeros(X16.shape, bool)
     svals = np.where(mask, X16, F16(0))
     Y16 = np.where(mask, F16(0), X16)                       # X - S, exact
     if kind == "K":
@@ -304,12 +306,14 @@ class OracleCache:
     def n_total(self):
         return sum(s.n for s in self.K)
 
-    def compress(self, K16, V16, rank, iters, init_B):
-        """Append one segment.  init_B: fp32 [2,B,H,d,rank] (index 0 = K, 1 = V)."""
+    def compress(self, K16, V16, rank, iters, init_B, v_mask=None):
+        """Append one segment.  init_B: fp32 [2,B,H,d,rank] (index 0 = K, 1 = V).
+        v_mask: optional precomputed support of S for V (used when this cache holds
+        a subset of the heads: Filter ranks a Value token across all heads)."""
         iK = init_B[0] if rank > 0 else None
         iV = init_B[1] if rank > 0 else None
         self.K.append(compress_tensor(K16, "K", self.bits, self.group, self.outlier_ppm, rank, iters, iK))
-        self.V.append(compress_tensor(V16, "V", self.bits, self.group, self.outlier_ppm, rank, iters, iV))
+        self.V.append(compress_tensor(V16, "V", self.bits, self.group, self.outlier_ppm, rank, iters, iV, v_mask))
 
     def reconstruct(self):
         """(K-hat, V-hat) fp64 [B,H,n_total,d]."""
