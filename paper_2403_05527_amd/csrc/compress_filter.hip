@@ -85,7 +85,8 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
 template <int WT>
 __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict__ K, SegView sv, Dims dm,
                                                       int n, const Thresh* __restrict__ thrK,
-                                                      uint32_t* __restrict__ pool_ctr) {
+                                                      uint32_t* __restrict__ pool_ctr,
+                                                      uint16_t* __restrict__ Rout, uint8_t* __restrict__ Rlo) {
   constexpr int NK = WT / 16;
   __shared__ float red_mn[4][D];
   __shared__ float red_mx[4][D];
@@ -171,13 +172,22 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
     if (t < n) {
       const int gi = tl / g;
       uint32_t w = 0;
+      uint32_t rh[8], rl[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         GroupQ q;
         q.mn = gq_mn[gi][oc * 8 + e];
         q.inv = gq_inv[gi][oc * 8 + e];
         q.delta = 0.0f;
-        w |= quant_code(y[k][e], q, dm.qmax) << (e * dm.bits);
+        const uint32_t code = quant_code_resid(y[k][e], q, dm.qmax, rh[e], rl[e]);   // residual R = u * delta
+        w |= code << (e * dm.bits);
+      }
+      if (Rout) {
+        *reinterpret_cast<uint4*>(Rout + ((size_t)slab * n + t) * D + oc * 8) =
+            make_uint4(rh[0] | (rh[1] << 16), rh[2] | (rh[3] << 16), rh[4] | (rh[5] << 16), rh[6] | (rh[7] << 16));
+        *reinterpret_cast<uint2*>(Rlo + ((size_t)slab * n + t) * D + oc * 8) =
+            make_uint2(rl[0] | (rl[1] << 8) | (rl[2] << 16) | (rl[3] << 24),
+                       rl[4] | (rl[5] << 8) | (rl[6] << 16) | (rl[7] << 24));
       }
       if (dm.bits == 4) {
         crow[(size_t)t * dm.wpr + oc] = w;
@@ -240,7 +250,8 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
 template <int NC>
 __global__ __launch_bounds__(256) void v_filter_quant_kernel(const uint16_t* __restrict__ V, SegView sv,
                                                              Dims dm, int n, int k_top, int k_bot,
-                                                             Thresh* __restrict__ thrV) {
+                                                             Thresh* __restrict__ thrV,
+                                                             uint16_t* __restrict__ Rout, uint8_t* __restrict__ Rlo) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   uint32_t* smem = reinterpret_cast<uint32_t*>(smem_raw);
   const int H = dm.H, N = H * D;
@@ -311,8 +322,19 @@ __global__ __launch_bounds__(256) void v_filter_quant_kernel(const uint16_t* __r
                 const int G = (oc * 8) / g;
                 sv.sz[((size_t)(b * H + head) * sv.n_cap + t) * (D / g) + G] = group_bits(q);
               }
+              uint32_t rh[8], rl[8];
 #pragma unroll
-              for (int e = 0; e < 8; ++e) acc[ch][e] |= quant_code(yv[e], q, dm.qmax) << (bits * ti);
+              for (int e = 0; e < 8; ++e) {
+                const uint32_t code = quant_code_resid(yv[e], q, dm.qmax, rh[e], rl[e]);   // residual R = u * delta
+                acc[ch][e] |= code << (bits * ti);
+              }
+              if (Rout) {
+                const size_t ro = ((size_t)(b * H + head) * n + t) * D + oc * 8;
+                *reinterpret_cast<uint4*>(Rout + ro) = make_uint4(
+                    rh[0] | (rh[1] << 16), rh[2] | (rh[3] << 16), rh[4] | (rh[5] << 16), rh[6] | (rh[7] << 16));
+                *reinterpret_cast<uint2*>(Rlo + ro) = make_uint2(rl[0] | (rl[1] << 8) | (rl[2] << 16) | (rl[3] << 24),
+                                                                 rl[4] | (rl[5] << 8) | (rl[6] << 16) | (rl[7] << 24));
+              }
             }
           }
         }
@@ -408,37 +430,37 @@ hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, 
 }
 
 hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const Thresh* thrK,
-                          uint32_t* pool_ctr, hipStream_t st) {
+                          uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
   if (dm.g == 128) {
     dim3 grid((n + 127) / 128, dm.B * dm.H);
-    hipLaunchKernelGGL(k_quant_kernel<128>, grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr);
+    hipLaunchKernelGGL(k_quant_kernel<128>, grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
   } else {
     dim3 grid((n + 63) / 64, dm.B * dm.H);
-    hipLaunchKernelGGL(k_quant_kernel<64>, grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr);
+    hipLaunchKernelGGL(k_quant_kernel<64>, grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
   }
   return hipGetLastError();
 }
 
 template <int NC>
 static hipError_t launch_v_nc(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                              int k_bot, Thresh* thrV, hipStream_t st) {
+                              int k_bot, Thresh* thrV, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
   const size_t lds = (2048 + 2 * (size_t)dm.H * D + dm.H + 1) * sizeof(uint32_t);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v_filter_quant_kernel<NC>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   dim3 grid((n + TILE - 1) / TILE, dm.B);
-  hipLaunchKernelGGL(v_filter_quant_kernel<NC>, grid, dim3(256), lds, st, V, sv, dm, n, k_top, k_bot, thrV);
+  hipLaunchKernelGGL(v_filter_quant_kernel<NC>, grid, dim3(256), lds, st, V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo);
   return hipGetLastError();
 }
 
 hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                                 int k_bot, Thresh* thrV, hipStream_t st) {
+                                 int k_bot, Thresh* thrV, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
   const int nc = (dm.H + 3) / 4;
-  if (nc <= 2) return launch_v_nc<2>(V, sv, dm, n, k_top, k_bot, thrV, st);
-  if (nc <= 4) return launch_v_nc<4>(V, sv, dm, n, k_top, k_bot, thrV, st);
-  if (nc <= 8) return launch_v_nc<8>(V, sv, dm, n, k_top, k_bot, thrV, st);
-  if (nc <= 10) return launch_v_nc<10>(V, sv, dm, n, k_top, k_bot, thrV, st);
-  return launch_v_nc<16>(V, sv, dm, n, k_top, k_bot, thrV, st);
+  if (nc <= 2) return launch_v_nc<2>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
+  if (nc <= 4) return launch_v_nc<4>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
+  if (nc <= 8) return launch_v_nc<8>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
+  if (nc <= 10) return launch_v_nc<10>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
+  return launch_v_nc<16>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
 }
 
 }  // namespace gear

@@ -76,7 +76,7 @@ ArenaLayout arena_layout(const gear_config& c) {
 }
 
 struct WorkLayout {
-  size_t thrK, thrV, pool_ctr, Bcur, partial, Atmp, cmat, dec, bytes;
+  size_t thrK, thrV, pool_ctr, Bcur, partial, Atmp, cmat, dec, resid, resid_lo, bytes;
 };
 
 WorkLayout work_layout(const gear_config& c) {
@@ -95,6 +95,8 @@ WorkLayout work_layout(const gear_config& c) {
   w.cmat = o; o += up(slabs * R * R * 4);
   const int nsplit = (c.n_prefill_max + DECODE_SPLIT - 1) / DECODE_SPLIT;
   w.dec = o; o += up((size_t)c.B * c.H_q * (nsplit + 1) * DECODE_REC * 4);
+  w.resid = o; o += up(c.rank_max > 0 ? slabs * (size_t)n_max * D * 2 : 0);
+  w.resid_lo = o; o += up(c.rank_max > 0 ? slabs * (size_t)n_max * D : 0);
   w.bytes = o;
   return w;
 }
@@ -255,17 +257,20 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
     GEAR_HIP(launch_fill_u32(pool_ctr, 0u, (size_t)c.B * c.H_kv, st));
     GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, st));
   }
-  GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, st));
-  GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, st));
-  if (rank > 0) {
-    float* Bcur = reinterpret_cast<float*>(ws + w.Bcur);
-    float* partial = reinterpret_cast<float*>(ws + w.partial);
-    float* Atmp = reinterpret_cast<float*>(ws + w.Atmp);
-    float* cmat = reinterpret_cast<float*>(ws + w.cmat);
-    const size_t half = (size_t)c.B * c.H_kv * D * rank;
-    GEAR_HIP(launch_power_iteration(true, Kp, ks, dm, n, iters, init_B, thrK, Bcur, partial, Atmp, cmat, st));
-    GEAR_HIP(launch_power_iteration(false, Vp, vs, dm, n, iters, init_B + half, thrV, Bcur, partial, Atmp, cmat, st));
-  }
+  // Keys: quantize (leaving the residual in the workspace), then their power iteration;
+  // Values reuse the same residual buffer afterwards.
+  uint16_t* resid = rank > 0 ? reinterpret_cast<uint16_t*>(ws + w.resid) : nullptr;
+  uint8_t* resid_lo = rank > 0 ? reinterpret_cast<uint8_t*>(ws + w.resid_lo) : nullptr;
+  float* Bcur = reinterpret_cast<float*>(ws + w.Bcur);
+  float* partial = reinterpret_cast<float*>(ws + w.partial);
+  float* Atmp = reinterpret_cast<float*>(ws + w.Atmp);
+  float* cmat = reinterpret_cast<float*>(ws + w.cmat);
+  const size_t half = (size_t)c.B * c.H_kv * D * rank;
+  GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, resid, resid_lo, st));
+  if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, resid_lo, ks, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st));
+  GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, resid, resid_lo, st));
+  if (rank > 0)
+    GEAR_HIP(launch_power_iteration(false, resid, resid_lo, vs, dm, n, iters, init_B + half, Bcur, partial, Atmp, cmat, st));
 
   if (first) {
     cache->n_prefill = n;

@@ -134,6 +134,23 @@ __device__ __forceinline__ uint32_t quant_code(float y, const GroupQ& q, float q
   float c = fminf(fmaxf(rintf(t), 0.0f), qmax);
   return (uint32_t)c;
 }
+// Code plus the rounding remainder u = t - code (|u| <= 0.5 up to the fp16
+// rounding of the scale), as a 24-bit fixed-point number u * 2^23 (fp32's own
+// precision for |u| >= 0.5) split into a high 16-bit and a low 8-bit part.  The
+// quantization residual is R = y - (code*delta + zero) = u * delta.
+constexpr float RESID_FIX = 8388608.0f;  // 2^23
+__device__ __forceinline__ uint32_t quant_code_resid(float y, const GroupQ& q, float qmax, uint32_t& hi16,
+                                                     uint32_t& lo8) {
+  float t = __fmul_rn(__fsub_rn(y, q.mn), q.inv);
+  float c = fminf(fmaxf(rintf(t), 0.0f), qmax);
+  const int f = (int)rintf((t - c) * RESID_FIX);
+  hi16 = (uint32_t)(f >> 8) & 0xFFFFu;
+  lo8 = (uint32_t)f & 0xFFu;
+  return (uint32_t)c;
+}
+__device__ __forceinline__ float resid_to_float(uint32_t hi16, uint32_t lo8) {  // u, not yet times delta
+  return (float)((int)(short)(hi16 & 0xFFFFu) * 256 + (int)(lo8 & 0xFFu)) * (1.0f / RESID_FIX);
+}
 
 // ---------------------------------------------------------------------------
 // wavefront (64 lanes) primitives

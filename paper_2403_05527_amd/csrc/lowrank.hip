@@ -1,12 +1,14 @@
 // SVDSolver_r (Eq. 6, Algorithm 2): batched power iteration on the per-head
-// residual R = X - D - S, which is never stored: every sweep rebuilds it from X,
-// the Filter thresholds and the stored (scale, zero).
+// residual R = X - D - S, which the quantization kernels leave in a workspace
+// buffer as the rounding remainder u = R / scale in 24-bit fixed point (|u| <= 1/2,
+// i.e. fp32's own precision in 3 bytes per entry; a 16-bit copy flips too many
+// fp16 roundings of the stored factors against a double-precision computation).
 //
 //   pi_update  : B <- start matrix or sum of the sweep partials; column scaling
 //                between rounds (the span, hence A B^T, is unchanged); QR of B
 //                before the last round; after the last round the r x r factor
 //                that orthonormalises A, and the final B = R^T orth(A).
-//   pi_sweep   : one pass over a slab: a_t = R_t B (per token), partial
+//   pi_sweep   : one pass over a slab's residual: a_t = R_t B (per token), partial
 //                B' = sum_t R_t^T a_t, and in the last round a_t itself and the
 //                Gram matrix sum_t a_t a_t^T.
 //   pi_finish  : A = a C  (C = the r x r factor), rounded to fp16.
@@ -139,33 +141,27 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
 }
 
 // grid (ceil(n/PT), B*H), block 256; thread (r0 = tid/16, oc = tid%16) owns
-// channels 8*oc..+7 of rows pt*PT + r0 + 16*k.
+// channels 8*oc..+7 of rows pt*PT + r0 + 16*k of the stored residual
+// (u = R / scale as 16-bit fixed point; the scale is applied per group here).
 template <bool IS_K, int R>
-__global__ __launch_bounds__(256) void pi_sweep_kernel(const uint16_t* __restrict__ X, SegView sv, Dims dm,
-                                                       int n, const Thresh* __restrict__ thr,
+__global__ __launch_bounds__(256) void pi_sweep_kernel(const uint16_t* __restrict__ Rres,
+                                                       const uint8_t* __restrict__ Rlo, SegView sv, int g, int n,
                                                        const float* __restrict__ Bcur, int last,
                                                        float* __restrict__ partial, int npart,
                                                        float* __restrict__ Atmp) {
   __shared__ float red[4][D * R];
   __shared__ float redg[4][R * R];
   const int slab = blockIdx.y, pt = blockIdx.x;
-  const int b = slab / dm.H, h = slab - b * dm.H;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r0 = tid >> 4, oc = tid & 15;
-  const uint16_t* Xs = X + (size_t)slab * n * D;
-  const int g = dm.g;
+  const uint16_t* Xs = Rres + (size_t)slab * n * D;
+  const uint8_t* Xl = Rlo + (size_t)slab * n * D;
 
   float bc[8][R];
 #pragma unroll
   for (int e = 0; e < 8; ++e)
 #pragma unroll
     for (int r = 0; r < R; ++r) bc[e][r] = Bcur[((size_t)slab * D + oc * 8 + e) * R + r];
-
-  Thresh thk[8];
-  if (IS_K) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) thk[e] = dm.ppm > 0 ? thr[(size_t)slab * D + oc * 8 + e] : thresh_none();
-  }
 
   float acc[8][R];
   float gacc[R];
@@ -176,72 +172,66 @@ __global__ __launch_bounds__(256) void pi_sweep_kernel(const uint16_t* __restric
 #pragma unroll
   for (int r = 0; r < R; ++r) gacc[r] = 0.0f;
 
-  GroupQ gq[8];
-  int cur_group = -1;
-  for (int k = 0; k < PT / 16; ++k) {
-    const int t = pt * PT + r0 + 16 * k;
-    if (pt * PT + 16 * k >= n) break;  // block-uniform
-    const bool tv = t < n;
-    uint4 xv = make_uint4(0, 0, 0, 0);
-    if (tv) xv = *reinterpret_cast<const uint4*>(Xs + (size_t)t * D + oc * 8);
-    const uint32_t w[4] = {xv.x, xv.y, xv.z, xv.w};
-    Thresh thv = thresh_none();
-    if (IS_K) {
-      const int grp = (pt * PT + 16 * k) / g;
-      if (grp != cur_group) {
-        cur_group = grp;
-        const uint4* p = reinterpret_cast<const uint4*>(sv.sz + ((size_t)slab * sv.ng_cap + grp) * D + oc * 8);
-        const uint4 s0 = p[0], s1 = p[1];
-        const uint32_t sb[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+  constexpr int UN = 4;  // rows in flight per thread
+  for (int k0 = 0; k0 < PT / 16; k0 += UN) {
+    if (pt * PT + 16 * k0 >= n) break;  // block-uniform
+    uint4 xv[UN];
+    uint2 xl[UN];
+    float dl[UN][IS_K ? 8 : 1];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) gq[e] = load_group(sb[e]);
-      }
-    } else {
-      if (tv) {
-        if (dm.ppm > 0) thv = thr[(size_t)b * n + t];
-        const GroupQ q = load_group(sv.sz[((size_t)slab * sv.n_cap + t) * (D / g) + (oc * 8) / g]);
+    for (int u = 0; u < UN; ++u) {
+      const int t = pt * PT + r0 + 16 * (k0 + u);
+      xv[u] = make_uint4(0, 0, 0, 0);
+      xl[u] = make_uint2(0, 0);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) gq[e] = q;
+      for (int e = 0; e < (IS_K ? 8 : 1); ++e) dl[u][e] = 0.0f;
+      if (t < n) {
+        xv[u] = *reinterpret_cast<const uint4*>(Xs + (size_t)t * D + oc * 8);
+        xl[u] = *reinterpret_cast<const uint2*>(Xl + (size_t)t * D + oc * 8);
+        if (IS_K) {  // scale of (group of t, my 8 channels)
+          const uint4* p = reinterpret_cast<const uint4*>(sv.sz + ((size_t)slab * sv.ng_cap + t / g) * D + oc * 8);
+          const uint4 s0 = p[0], s1 = p[1];
+          const uint32_t sb[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+#pragma unroll
+          for (int e = 0; e < (IS_K ? 8 : 1); ++e) dl[u][e] = h2f(sb[e] & 0xFFFFu);
+        } else {     // scale of (token t, the channel group of my 8 channels)
+          dl[u][0] = h2f(sv.sz[((size_t)slab * sv.n_cap + t) * (D / g) + (oc * 8) / g] & 0xFFFFu);
+        }
       }
     }
-    float res[8];
-    float a[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) a[r] = 0.0f;
+    for (int u = 0; u < UN; ++u) {
+      const int t = pt * PT + r0 + 16 * (k0 + u);
+      const uint32_t w[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+      const uint32_t wl[2] = {xl[u].x, xl[u].y};
+      float res[8];
+      float a[R];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint32_t hb = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-      bool out;
-      if (IS_K) out = is_outlier(key16(hb), t, thk[e]);
-      else out = is_outlier(key16(hb), h * D + oc * 8 + e, thv);
-      const float y = out ? 0.0f : h2f(hb);
-      const float code = (float)quant_code(y, gq[e], dm.qmax);
-      res[e] = tv ? (y - (code * gq[e].delta + gq[e].mn)) : 0.0f;
+      for (int r = 0; r < R; ++r) a[r] = 0.0f;
 #pragma unroll
-      for (int r = 0; r < R; ++r) a[r] += res[e] * bc[e][r];
-    }
+      for (int e = 0; e < 8; ++e) {
+        res[e] = resid_to_float(w[e >> 1] >> ((e & 1) * 16), wl[e >> 2] >> ((e & 3) * 8)) * dl[u][IS_K ? e : 0];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      a[r] += __shfl_xor(a[r], 1, 64);
-      a[r] += __shfl_xor(a[r], 2, 64);
-      a[r] += __shfl_xor(a[r], 4, 64);
-      a[r] += __shfl_xor(a[r], 8, 64);
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-#pragma unroll
-      for (int r = 0; r < R; ++r) acc[e][r] += res[e] * a[r];
-    if (last) {
-      if (oc == 0 && tv) {
-#pragma unroll
-        for (int r = 0; r < R; ++r) Atmp[((size_t)slab * n + t) * R + r] = a[r];
+        for (int r = 0; r < R; ++r) a[r] += res[e] * bc[e][r];
       }
-      if (oc < R) {
-        float mine = 0.0f;
 #pragma unroll
-        for (int r = 0; r < R; ++r) mine = (r == oc) ? a[r] : mine;
+      for (int r = 0; r < R; ++r) a[r] = row16_sum(a[r]);   // the 16 lanes of a row hold one token
 #pragma unroll
-        for (int r = 0; r < R; ++r) gacc[r] += mine * a[r];
+      for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[e][r] += res[e] * a[r];
+      if (last) {
+        if (oc == 0 && t < n) {
+#pragma unroll
+          for (int r = 0; r < R; ++r) Atmp[((size_t)slab * n + t) * R + r] = a[r];
+        }
+        if (oc < R) {
+          float mine = 0.0f;
+#pragma unroll
+          for (int r = 0; r < R; ++r) mine = (r == oc) ? a[r] : mine;
+#pragma unroll
+          for (int r = 0; r < R; ++r) gacc[r] += mine * a[r];
+        }
       }
     }
   }
@@ -302,9 +292,9 @@ __global__ __launch_bounds__(256) void pi_finish_kernel(const float* __restrict_
 
 // ------------------------------------------------------------------ host side
 template <int R>
-static hipError_t run_pi(bool is_k, const uint16_t* X, const SegView& sv, const Dims& dm, int n, int iters,
-                         const float* init_B, const Thresh* thr, float* Bcur, float* partial, float* Atmp,
-                         float* cmat, hipStream_t st) {
+static hipError_t run_pi(bool is_k, const uint16_t* Rres, const uint8_t* Rlo, const SegView& sv, const Dims& dm, int n, int iters,
+                         const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat,
+                         hipStream_t st) {
   const int slabs = dm.B * dm.H;
   const int npart = (n + PT - 1) / PT;
   hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, init_B, sv.rank, (const float*)nullptr,
@@ -312,10 +302,10 @@ static hipError_t run_pi(bool is_k, const uint16_t* X, const SegView& sv, const 
   for (int l = 0; l < iters; ++l) {
     const int last = (l == iters - 1);
     if (is_k)
-      hipLaunchKernelGGL((pi_sweep_kernel<true, R>), dim3(npart, slabs), dim3(256), 0, st, X, sv, dm, n, thr,
+      hipLaunchKernelGGL((pi_sweep_kernel<true, R>), dim3(npart, slabs), dim3(256), 0, st, Rres, Rlo, sv, dm.g, n,
                          (const float*)Bcur, last, partial, npart, Atmp);
     else
-      hipLaunchKernelGGL((pi_sweep_kernel<false, R>), dim3(npart, slabs), dim3(256), 0, st, X, sv, dm, n, thr,
+      hipLaunchKernelGGL((pi_sweep_kernel<false, R>), dim3(npart, slabs), dim3(256), 0, st, Rres, Rlo, sv, dm.g, n,
                          (const float*)Bcur, last, partial, npart, Atmp);
     hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, (const float*)nullptr, sv.rank,
                        (const float*)partial, npart, (l == iters - 2) ? 1 : 0, last, Bcur, cmat, sv);
@@ -327,13 +317,13 @@ static hipError_t run_pi(bool is_k, const uint16_t* X, const SegView& sv, const 
 
 int pi_padded_rank(int rank) { return rank <= 2 ? 2 : rank <= 4 ? 4 : 8; }
 
-hipError_t launch_power_iteration(bool is_k, const uint16_t* X, const SegView& sv, const Dims& dm, int n,
-                                  int iters, const float* init_B, const Thresh* thr, float* Bcur,
-                                  float* partial, float* Atmp, float* cmat, hipStream_t st) {
+hipError_t launch_power_iteration(bool is_k, const uint16_t* Rres, const uint8_t* Rlo, const SegView& sv, const Dims& dm, int n, int iters,
+                                  const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat,
+                                  hipStream_t st) {
   switch (pi_padded_rank(sv.rank)) {
-    case 2: return run_pi<2>(is_k, X, sv, dm, n, iters, init_B, thr, Bcur, partial, Atmp, cmat, st);
-    case 4: return run_pi<4>(is_k, X, sv, dm, n, iters, init_B, thr, Bcur, partial, Atmp, cmat, st);
-    default: return run_pi<8>(is_k, X, sv, dm, n, iters, init_B, thr, Bcur, partial, Atmp, cmat, st);
+    case 2: return run_pi<2>(is_k, Rres, Rlo, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
+    case 4: return run_pi<4>(is_k, Rres, Rlo, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
+    default: return run_pi<8>(is_k, Rres, Rlo, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
   }
 }
 

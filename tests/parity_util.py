@@ -94,7 +94,7 @@ def compare_attention(gc, oc, q, K_buf=None, V_buf=None, n_buf=0):
                            None if V_buf is None else np16(V_buf), n_buf).astype(np.float64)
     assert np.isfinite(out_g).all()
     diff = np.abs(out_g - out_o)
-    ulp = np.spacing(np.abs(out_o).astype(np.float16)).astype(np.float64)
+    ulp = np.spacing(np.maximum(np.abs(out_o), np.abs(out_g)).astype(np.float16)).astype(np.float64)
     tol = np.maximum(ATTN_ABS_TOL, ulp)
     err = float(diff.max())
     assert (diff <= tol).all(), "attention max-abs error %.3e (max |o| %.2f)" % (err, np.abs(out_o).max())

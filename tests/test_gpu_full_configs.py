@@ -99,7 +99,8 @@ def run_full(w, b_sel, heads, n_buf):
                            np.ascontiguousarray(host(Kb[b_sel:b_sel + 1])[:, heads]),
                            np.ascontiguousarray(host(Vb[b_sel:b_sel + 1])[:, heads]), n_buf).astype(np.float64)
     diff = np.abs(out_g - out_o)
-    tol = np.maximum(pu.ATTN_ABS_TOL, np.spacing(np.abs(out_o).astype(np.float16)).astype(np.float64))
+    tol = np.maximum(pu.ATTN_ABS_TOL,
+                     np.spacing(np.maximum(np.abs(out_o), np.abs(out_g)).astype(np.float16)).astype(np.float64))
     rep["attn_max_abs"] = float(diff.max())
     assert np.isfinite(out_g).all() and (diff <= tol).all(), rep
     say("  ->", rep)
