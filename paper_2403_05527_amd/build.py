@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libgear.so")
 
-SOURCES = ["gear_api.hip", "compress_filter.hip", "lowrank.hip", "decode.hip", "decompress_export.hip"]
+SOURCES = ["gear_api.hip", "compress_filter.hip", "compress_values.hip", "lowrank.hip", "decode.hip", "decompress_export.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -1,8 +1,7 @@
-// Filter_s (Eq. 4) + Quant_b(X - S) (Eq. 2 / Eq. 5) kernels of gear_compress:
+// Filter_s (Eq. 4) + Quant_b(X - S) (Eq. 2 / Eq. 5) kernels of gear_compress, Key side:
 //   k_select_kernel       thresholds of every Key channel vector (over tokens)
-//   k_quant_kernel        Key codes, (scale, zero), ordered outlier lists
-//   v_filter_quant_kernel Value thresholds (per token over all heads), codes in
-//                         the token-blocked layout, (scale, zero), outlier lists
+//   k_quant_kernel        Key codes, (scale, zero), ordered outlier lists, residual
+// (the Value side is in compress_values.hip)
 #include "gear_internal.h"
 #include "gear_select.h"
 #include "gear_launch.h"
@@ -10,7 +9,7 @@
 namespace gear {
 
 // ------------------------------------------------------------------ sources
-struct LdsSource {  // one vector stored contiguously in LDS as fp16 bit patterns
+struct LdsSource {  // one vector stored contiguously in LDS as 16-bit keys
   static constexpr int kMaxChunks = 0;
   const uint16_t* base;
   int n_pad;  // multiple of 8
@@ -59,7 +58,7 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
     } else {
       v[0] = *p;
     }
-    for (int e = 0; e < VW; ++e) tile[(size_t)(u * VW + e) * n_pad + row] = v[e];
+    for (int e = 0; e < VW; ++e) tile[(size_t)(u * VW + e) * n_pad + row] = (uint16_t)key16(v[e]);   // keys, not values
   }
   // zero the padding so stray lanes read defined data
   for (int idx = tid; idx < CB * (n_pad - n); idx += 256) {
@@ -242,173 +241,6 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
   }
 }
 
-// ------------------------------------------------------------------ V filter + quant
-// grid (ceil(n/64), B); block 256 (4 waves).  A wave owns one token group of
-// tpw tokens at a time, for all heads: lane l, chunk ch  <->  head 4*ch + l/16,
-// channels 8*(l%16)..+7, i.e. in-vector index ch*512 + l*8 + e.
-// LDS: 4*512 u32 histograms | colmask [H*128][2] u32 | head_cnt [H+1] u32.
-template <int NC>
-__global__ __launch_bounds__(256) void v_filter_quant_kernel(const uint16_t* __restrict__ V, SegView sv,
-                                                             Dims dm, int n, int k_top, int k_bot,
-                                                             Thresh* __restrict__ thrV,
-                                                             uint16_t* __restrict__ Rout, uint8_t* __restrict__ Rlo) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint32_t* smem = reinterpret_cast<uint32_t*>(smem_raw);
-  const int H = dm.H, N = H * D;
-  uint32_t* hist = smem;
-  uint32_t* colmask = smem + 2048;
-  uint32_t* head_cnt = colmask + 2 * N;
-
-  const int b = blockIdx.y, tile = blockIdx.x;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int hsub = lane >> 4, oc = lane & 15;
-  const int g = dm.g, bits = dm.bits, tpw = dm.tpw;
-  const int lanes_per_group = g >> 3;  // 4, 8 or 16
-  const int ngroups_tile = TILE / tpw;
-
-  for (int i = tid; i < 2 * N; i += 256) colmask[i] = 0u;
-  __syncthreads();
-
-  for (int tg = wave; tg < ngroups_tile; tg += 4) {
-    uint32_t acc[NC][8];
-#pragma unroll
-    for (int ch = 0; ch < NC; ++ch)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[ch][e] = 0u;
-
-    for (int ti = 0; ti < tpw; ++ti) {
-      const int tl = tg * tpw + ti;
-      const int t = tile * TILE + tl;
-      const bool tvalid = t < n;
-      uint4 x[NC];
-#pragma unroll
-      for (int ch = 0; ch < NC; ++ch) {
-        const int head = 4 * ch + hsub;
-        x[ch] = make_uint4(0, 0, 0, 0);
-        if (tvalid && head < H)
-          x[ch] = *reinterpret_cast<const uint4*>(V + (((size_t)(b * H + head) * n + t) * D + oc * 8));
-      }
-      Thresh th = thresh_none();
-      if (dm.ppm > 0) {
-        RegSource<NC> src{x};
-        th = wave_select(src, N, k_top, k_bot, hist + wave * 512, tvalid);
-        if (tvalid && lane == 0) thrV[(size_t)b * n + t] = th;
-      }
-      if (tvalid) {
-#pragma unroll
-        for (int ch = 0; ch < NC; ++ch) {
-          const int head = 4 * ch + hsub;
-          if (4 * ch < H) {  // wave-uniform; lanes of heads >= H compute on zeros and store nothing
-            const uint32_t w[4] = {x[ch].x, x[ch].y, x[ch].z, x[ch].w};
-            float yv[8];
-            float lmn = INFINITY, lmx = -INFINITY;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              const uint32_t hb = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-              const int j = ch * 512 + lane * 8 + e;
-              const bool out = head < H && is_outlier(key16(hb), j, th);
-              if (out) atomicOr(&colmask[2 * j + (tl >> 5)], 1u << (tl & 31));
-              yv[e] = out ? 0.0f : h2f(hb);
-              lmn = fminf(lmn, yv[e]);
-              lmx = fmaxf(lmx, yv[e]);
-            }
-            for (int o = 1; o < lanes_per_group; o <<= 1) {
-              lmn = fminf(lmn, __shfl_xor(lmn, o, 64));
-              lmx = fmaxf(lmx, __shfl_xor(lmx, o, 64));
-            }
-            const GroupQ q = make_group(lmn, lmx, dm.qmax);
-            if (head < H) {
-              if ((oc & (lanes_per_group - 1)) == 0) {
-                const int G = (oc * 8) / g;
-                sv.sz[((size_t)(b * H + head) * sv.n_cap + t) * (D / g) + G] = group_bits(q);
-              }
-              uint32_t rh[8], rl[8];
-#pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                const uint32_t code = quant_code_resid(yv[e], q, dm.qmax, rh[e], rl[e]);   // residual R = u * delta
-                acc[ch][e] |= code << (bits * ti);
-              }
-              if (Rout) {
-                const size_t ro = ((size_t)(b * H + head) * n + t) * D + oc * 8;
-                *reinterpret_cast<uint4*>(Rout + ro) = make_uint4(
-                    rh[0] | (rh[1] << 16), rh[2] | (rh[3] << 16), rh[4] | (rh[5] << 16), rh[6] | (rh[7] << 16));
-                *reinterpret_cast<uint2*>(Rlo + ro) = make_uint2(rl[0] | (rl[1] << 8) | (rl[2] << 16) | (rl[3] << 24),
-                                                                 rl[4] | (rl[5] << 8) | (rl[6] << 16) | (rl[7] << 24));
-              }
-            }
-          }
-        }
-      }
-    }
-    // store this token group's code words (zero bits for tokens beyond n)
-    const int tgg = tile * ngroups_tile + tg;
-    if (tgg * tpw < n) {
-      const int blk = tgg >> 2, kg = tgg & 3;
-#pragma unroll
-      for (int ch = 0; ch < NC; ++ch) {
-        const int head = 4 * ch + hsub;
-        if (head < H) {
-          // channel c = 8*oc + e sits in word (kg*16 + c%16)*8 + c/16 of the block
-          uint32_t* dst = sv.codes + ((size_t)(b * H + head) * sv.nblk_cap + blk) * 512 +
-                          (kg * 16 + 8 * (oc & 1)) * 8 + (oc >> 1);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) dst[e * 8] = acc[ch][e];
-        }
-      }
-    }
-  }
-  __syncthreads();
-
-  // outlier lists per (head, tile), ordered (c, t); lane owns columns 2l, 2l+1
-  if (dm.ppm > 0) {
-    for (int h = wave; h < H; h += 4) {
-      const int j0 = h * D + 2 * lane;
-      const uint32_t c = __popc(colmask[2 * j0]) + __popc(colmask[2 * j0 + 1]) + __popc(colmask[2 * j0 + 2]) +
-                         __popc(colmask[2 * j0 + 3]);
-      const uint32_t tot = wave_sum_shfl(c);
-      if (lane == 0) head_cnt[h] = tot;
-    }
-    __syncthreads();
-    if (tid == 0) {
-      uint32_t run = 0;
-      for (int h = 0; h < H; ++h) {
-        const uint32_t c = head_cnt[h];
-        head_cnt[h] = run;
-        run += c;
-      }
-      head_cnt[H] = run;
-    }
-    __syncthreads();
-    const uint32_t region = (uint32_t)tile * TILE * (uint32_t)(k_top + k_bot);
-    uint32_t* pool = sv.sp_pool + (size_t)b * sv.pool_cap;
-    for (int h = wave; h < H; h += 4) {
-      const int j0 = h * D + 2 * lane;
-      uint32_t m[4] = {colmask[2 * j0], colmask[2 * j0 + 1], colmask[2 * j0 + 2], colmask[2 * j0 + 3]};
-      const uint32_t c = __popc(m[0]) + __popc(m[1]) + __popc(m[2]) + __popc(m[3]);
-      const uint32_t inc = wave_incl_scan(c);
-      uint32_t off = region + head_cnt[h] + inc - c;
-      const uint16_t* Xh = V + (size_t)(b * H + h) * n * D;
-      for (int cc = 0; cc < 2; ++cc) {
-        const int ch = 2 * lane + cc;
-        for (int half = 0; half < 2; ++half) {
-          uint32_t mm = m[2 * cc + half];
-          while (mm) {
-            const int bit = __ffs((int)mm) - 1;
-            mm &= mm - 1;
-            const int tl = half * 32 + bit;
-            const uint32_t hb = Xh[(size_t)(tile * TILE + tl) * D + ch];
-            if (off < sv.pool_cap) pool[off] = (uint32_t)(tl * D + ch) | (hb << 16);
-            ++off;
-          }
-        }
-      }
-      if (lane == 0)
-        sv.sp_table[(size_t)(b * H + h) * sv.ntile_cap + tile] =
-            make_uint2(region + head_cnt[h], head_cnt[h + 1] - head_cnt[h]);
-    }
-  }
-}
-
 // ------------------------------------------------------------------ launchers
 static int k_select_cb(int n_pad) {
   int cb = 128;
@@ -439,28 +271,6 @@ hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, 
     hipLaunchKernelGGL(k_quant_kernel<64>, grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
   }
   return hipGetLastError();
-}
-
-template <int NC>
-static hipError_t launch_v_nc(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                              int k_bot, Thresh* thrV, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
-  const size_t lds = (2048 + 2 * (size_t)dm.H * D + dm.H + 1) * sizeof(uint32_t);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v_filter_quant_kernel<NC>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
-  dim3 grid((n + TILE - 1) / TILE, dm.B);
-  hipLaunchKernelGGL(v_filter_quant_kernel<NC>, grid, dim3(256), lds, st, V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo);
-  return hipGetLastError();
-}
-
-hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                                 int k_bot, Thresh* thrV, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
-  const int nc = (dm.H + 3) / 4;
-  if (nc <= 2) return launch_v_nc<2>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
-  if (nc <= 4) return launch_v_nc<4>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
-  if (nc <= 8) return launch_v_nc<8>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
-  if (nc <= 10) return launch_v_nc<10>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
-  return launch_v_nc<16>(V, sv, dm, n, k_top, k_bot, thrV, Rout, Rlo, st);
 }
 
 }  // namespace gear

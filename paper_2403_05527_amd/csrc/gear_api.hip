@@ -88,7 +88,7 @@ WorkLayout work_layout(const gear_config& c) {
   size_t o = 0;
   w.thrK = o; o += up(slabs * D * sizeof(Thresh));
   w.thrV = o; o += up((size_t)c.B * n_max * sizeof(Thresh));
-  w.pool_ctr = o; o += up(slabs * 4);
+  w.pool_ctr = o; o += up((slabs + (size_t)c.B) * 4);   // Key counters per slab, then Value counters per batch
   w.Bcur = o; o += up(slabs * D * R * 4);
   w.partial = o; o += up(slabs * (size_t)npart * (D * R + R * R) * 4);
   w.Atmp = o; o += up(slabs * (size_t)n_max * R * 4);
@@ -254,7 +254,7 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   const int kv_k = outlier_count(n, c.outlier_ppm);
   const int kv_v = outlier_count((long long)c.H_kv * D, c.outlier_ppm);
   if (c.outlier_ppm > 0) {
-    GEAR_HIP(launch_fill_u32(pool_ctr, 0u, (size_t)c.B * c.H_kv, st));
+    GEAR_HIP(launch_fill_u32(pool_ctr, 0u, (size_t)c.B * c.H_kv + c.B, st));
     GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, st));
   }
   // Keys: quantize (leaving the residual in the workspace), then their power iteration;
@@ -268,7 +268,7 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   const size_t half = (size_t)c.B * c.H_kv * D * rank;
   GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, resid, resid_lo, st));
   if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, resid_lo, ks, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st));
-  GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, resid, resid_lo, st));
+  GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, pool_ctr + (size_t)c.B * c.H_kv, resid, resid_lo, st));
   if (rank > 0)
     GEAR_HIP(launch_power_iteration(false, resid, resid_lo, vs, dm, n, iters, init_B + half, Bcur, partial, Atmp, cmat, st));
 

@@ -82,8 +82,15 @@ __device__ __forceinline__ uint32_t f2h(float f) {  // round to nearest even
 // Monotone 16-bit key of an fp16 bit pattern; -0 and +0 share one key.
 __device__ __forceinline__ uint32_t key16(uint32_t h) {
   h &= 0xFFFFu;
-  if (h == 0x8000u) h = 0u;
-  return (h & 0x8000u) ? (h ^ 0xFFFFu) : (h | 0x8000u);
+  return (h & 0x8000u) ? ((0u - h) & 0xFFFFu) : (h | 0x8000u);
+}
+// The same key for two fp16 values packed in one 32-bit word (negative: two's
+// complement of the pattern, which also maps -0 onto +0's key; positive: + 0x8000).
+__device__ __forceinline__ uint32_t key16x2(uint32_t h2) {
+  const uint32_t lo = h2 & 0xFFFFu, hi = h2 >> 16;
+  const uint32_t klo = (lo & 0x8000u) ? ((0u - lo) & 0xFFFFu) : (lo | 0x8000u);
+  const uint32_t khi = (hi & 0x8000u) ? ((0u - hi) & 0xFFFFu) : (hi | 0x8000u);
+  return klo | (khi << 16);
 }
 __device__ __forceinline__ bool is_outlier(uint32_t key, int idx, const Thresh& th) {
   return key > th.tau_top || (key == th.tau_top && idx <= th.i_top) || key < th.tau_bot ||

@@ -23,7 +23,8 @@ hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, 
 hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const Thresh* thrK,
                           uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st);
 hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                                 int k_bot, Thresh* thrV, uint16_t* Rout, uint8_t* Rlo, hipStream_t st);
+                                 int k_bot, Thresh* thrV, uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo,
+                                 hipStream_t st);
 
 int pi_padded_rank(int rank);
 hipError_t launch_power_iteration(bool is_k, const uint16_t* Rres, const uint8_t* Rlo, const SegView& sv, const Dims& dm, int n, int iters,

@@ -11,7 +11,8 @@
 namespace gear {
 
 // Entry layout a source presents: chunk ch, lane l, slot e  <->  index
-// ch*512 + l*8 + e.  src(ch) returns the lane's 8 fp16 bit patterns.
+// ch*512 + l*8 + e.  src(ch) returns the lane's 8 entries as 16-bit monotone
+// KEYS (key16 of the fp16 bit patterns), two per 32-bit word.
 //   Src::kMaxChunks > 0 : the vector lives in registers; loops are unrolled.
 //   Src::kMaxChunks == 0: runtime loop (vector in LDS).
 template <class Src, class F>
@@ -104,7 +105,7 @@ __device__ __forceinline__ int find_kth_equal(const Src& src, int N, int nch, ui
     uint32_t c = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      if (base + e < N && key16(slot16(v, e)) == tau) ++c;
+      if (base + e < N && slot16(v, e) == tau) ++c;
     const uint32_t inc = wave_incl_scan(c);
     const uint32_t total = __shfl(inc, 63, 64);
     if (base_cnt + total >= m) {
@@ -115,7 +116,7 @@ __device__ __forceinline__ int find_kth_equal(const Src& src, int N, int nch, ui
         uint32_t r = exc;
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (base + e < N && key16(slot16(v, e)) == tau) {
+          if (base + e < N && slot16(v, e) == tau) {
             ++r;
             if (r == m) idx = base + e;
           }
@@ -147,7 +148,7 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
     const int base = ch * 512 + lane * 8;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      if (base + e < N) atomicAdd(&hist[key16(slot16(v, e)) >> 8], 1u);
+      if (base + e < N) atomicAdd(&hist[slot16(v, e) >> 8], 1u);
   });
   __syncthreads();
   int bin_t = -1, bin_b = -1;
@@ -172,7 +173,7 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (base + e < N) {
-        const uint32_t k = key16(slot16(v, e));
+        const uint32_t k = slot16(v, e);
         if ((int)(k >> 8) == bin_t) atomicAdd(&hist[k & 255u], 1u);
         if ((int)(k >> 8) == bin_b) atomicAdd(&hist[256 + (k & 255u)], 1u);
       }
