@@ -31,7 +31,7 @@ struct RegSource {  // the vector lives in the wave's registers
 __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restrict__ K, int n, int n_pad,
                                                        int CB, int k_top, int k_bot,
                                                        Thresh* __restrict__ thrK) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
+  GEAR_DYN_LDS(smem_raw);
   uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem_raw);
   uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + 4 * 512 * sizeof(uint32_t));
   const int slab = blockIdx.y, cb = blockIdx.x;
@@ -102,10 +102,15 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
   const int g = dm.g;
   const int ngw = WT / g;  // groups per block (1 or 2)
 
-  // thresholds of my 8 channels
+  // thresholds of my 8 channels (staged through LDS: one coalesced read per block)
+  __shared__ Thresh thr_s[D];
+  if (dm.ppm > 0) {
+    if (tid < D) thr_s[tid] = thrK[(size_t)slab * D + tid];
+    __syncthreads();
+  }
   Thresh th[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) th[e] = dm.ppm > 0 ? thrK[(size_t)slab * D + oc * 8 + e] : thresh_none();
+  for (int e = 0; e < 8; ++e) th[e] = dm.ppm > 0 ? thr_s[oc * 8 + e] : thresh_none();
 
   float y[NK][8];
   uint32_t raw[NK][4];

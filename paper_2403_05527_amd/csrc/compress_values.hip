@@ -139,7 +139,9 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
       const int kg = rem >> 7, n16 = (rem >> 3) & 15, j = rem & 7;
       const int c = 16 * j + n16;
       const int row0 = blk * TB + kg * tpw;
-      if (t0 + row0 < n) {
+      // every word of a block that holds at least one token is written (rows past n carry code 0),
+      // so a reader of the block never sees stale memory
+      if (t0 + blk * TB < n) {
         uint32_t word = 0;
         for (int i = 0; i < tpw; ++i) word |= (uint32_t)stage[(row0 + i) * PITCH + c] << (i * bits);
         sv.codes[((size_t)slab * sv.nblk_cap + (size_t)tile * nblk + blk) * 512 + rem] = word;

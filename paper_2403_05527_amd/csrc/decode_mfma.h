@@ -14,10 +14,13 @@
 // in the other operand.  The zero-point, low-rank and sparse terms are added
 // outside the MFMA.
 //
-// The block is latency-bound unless every global load is in flight at once:
-// a prologue issues all loads (Key codes into registers; scale/zero, low-rank
-// factors and outlier lists into LDS), and the phases after it touch global
-// memory only for the Value codes, which are requested before the softmax.
+// A block is four independent wavefronts: each owns 128 of the block's tokens
+// end to end (scores, its own softmax maximum and sum, Value accumulation,
+// low-rank and sparse terms) and the four (m, l, o) states are merged once at
+// the end, so no wave ever waits at a barrier in the middle of its work.  Each
+// wave issues every global load it needs up front (Key codes into registers;
+// scale/zero, low-rank rows and its tiles' outlier lists into its own LDS
+// region); only the Value codes are requested later, before the softmax.
 #pragma once
 #include "gear_internal.h"
 
@@ -103,22 +106,19 @@ __device__ __forceinline__ void val_slot(int t, int& kg, int& idx, int& lg) {
 // ---------------------------------------------------------------------------
 // LDS layout of one MFMA block (byte offsets into dynamic shared memory)
 // ---------------------------------------------------------------------------
+constexpr int WTOK = 128;  // tokens per wave
 struct MfmaLayout {
-  int q, sc, szk, szv, ak, av, bfk, bfv, spk, spv, osp, opnd, misc, total;
-  int spcap;       // staged outlier entries per tensor
-  int opnd_halfs;  // operand staging per wave
+  int q, bfk, bfv, misc;                       // shared by the four waves
+  int wave0, wave_stride;                      // per-wave region
+  int sc, szk, szv, ak, av, spk, spv, osp, opnd;  // offsets inside a wave region
+  int total;
+  int spcap;       // staged outlier entries per wave and tensor
 };
 template <int GQ>
 struct MfmaMisc {
-  float kbase[GQ][16];
-  float qB[GQ][8];
-  float wv[GQ][8];
-  float wred[4][GQ][8];
-  float pm[4][GQ][4];
-  float red[GQ][4];
-  float stat[GQ][2];
-  uint2 tabk[8], tabv[8];
-  uint32_t offk[9], offv[9];
+  float wstat[4][GQ][2];   // per wave: m, l
+  float wv[4][GQ][8];      // per wave: p^T A_V
+  float pm[4][GQ][4];      // per wave: sum_t p_t * zero_V[t][G]
 };
 __host__ __device__ inline int up16i(int x) { return (x + 15) & ~15; }
 template <int GQ>
@@ -127,33 +127,35 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int r
   const int TB = bits == 2 ? 64 : 32, NG = D / g;
   int o = 0;
   L.q = o; o += GQ * D * 4;
-  L.sc = o; o += GQ * MFMA_TS * 4;
-  L.szk = o; o += (MFMA_TS / g) * D * 4;
-  L.szv = o; o += MFMA_TS * NG * 4;
-  L.ak = o; o += up16i(MFMA_TS * rk * 2);
-  L.av = o; o += up16i(MFMA_TS * rv * 2);
   L.bfk = o; o += up16i(D * rk * 2);
   L.bfv = o; o += up16i(D * rv * 2);
+  L.misc = o; o += up16i((int)sizeof(MfmaMisc<GQ>));
+  L.wave0 = o;
+  int w = 0;
+  L.sc = w; w += GQ * WTOK * 4;
+  L.szk = w; w += (WTOK / g) * D * 4;
+  L.szv = w; w += WTOK * NG * 4;
+  L.ak = w; w += up16i(WTOK * rk * 2);
+  L.av = w; w += up16i(WTOK * rv * 2);
   int cap = 0;
   if (ppm > 0) {
-    const long long expect = ((long long)MFMA_TS * D * ppm + 999999) / 1000000;
-    cap = (int)((expect * 12 / 10 + 64 + 127) / 128 * 128);
-    if (cap > 2048) cap = 2048;
+    const long long expect = ((long long)WTOK * D * ppm + 999999) / 1000000;
+    cap = (int)((expect * 12 / 10 + 32 + 31) / 32 * 32);
+    if (cap > 1024) cap = 1024;
   }
   L.spcap = cap;
-  L.spk = o; o += cap * 4;
-  L.spv = o; o += cap * 4;
-  L.osp = o; o += 4 * GQ * D * 4;
+  L.spk = w; w += cap * 4;
+  L.spv = w; w += cap * 4;
+  L.osp = w; w += GQ * D * 4;
   int oh = 2 * GQ * D;
   if (NG * 2 * GQ * TB > oh) oh = NG * 2 * GQ * TB;
-  L.opnd_halfs = oh;
-  L.opnd = o; o += 4 * oh * 2;
-  L.misc = o; o += up16i((int)sizeof(MfmaMisc<GQ>));
-  L.total = o;
+  L.opnd = w; w += oh * 2;
+  L.wave_stride = up16i(w);
+  L.total = L.wave0 + 4 * L.wave_stride;
   return L;
 }
 
-// Cooperative copy of `count` fp16 values global -> LDS (any alignment).
+// Cooperative copy of `count` fp16 values global -> LDS by the block (any alignment).
 __device__ __forceinline__ void stage_halfs(uint16_t* dst, const uint16_t* src, int count) {
   const int tid = threadIdx.x;
   if (((reinterpret_cast<uintptr_t>(src) & 7u) == 0) && (count & 3) == 0) {
@@ -161,6 +163,16 @@ __device__ __forceinline__ void stage_halfs(uint16_t* dst, const uint16_t* src, 
       reinterpret_cast<uint2*>(dst)[i] = reinterpret_cast<const uint2*>(src)[i];
   } else {
     for (int i = tid; i < count; i += 256) dst[i] = src[i];
+  }
+}
+// Copy of `count` fp16 values global -> LDS by one wave (any alignment).
+__device__ __forceinline__ void wave_stage_halfs(uint16_t* dst, const uint16_t* src, int count) {
+  const int lane = lane_id();
+  if (((reinterpret_cast<uintptr_t>(src) & 7u) == 0) && (count & 3) == 0) {
+    for (int i = lane; i < count / 4; i += 64)
+      reinterpret_cast<uint2*>(dst)[i] = reinterpret_cast<const uint2*>(src)[i];
+  } else {
+    for (int i = lane; i < count; i += 64) dst[i] = src[i];
   }
 }
 
@@ -172,38 +184,40 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
                            int t_begin, int t_end, float* __restrict__ rec_base, int rec_stride) {
   constexpr int TB = (BITS == 2) ? 64 : 32;   // tokens per Value code block
   constexpr int KW = (BITS == 2) ? 2 : 4;     // Key code words per lane per M-tile
-  constexpr int VBLK = 128 / TB;              // Value blocks per wave
+  constexpr int VBLK = WTOK / TB;             // Value blocks per wave
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n16 = lane & 15, kg = lane >> 4;
   const int g = dm.g, NG = D / g;
   const int rk = ks.rank, rv = vs.rank;
-  const int nr = t_end - t_begin;
   const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk, rv, dm.ppm);
   float* Sq = reinterpret_cast<float*>(smem + L.q);                 // [GQ][128]
-  float* Ssc = reinterpret_cast<float*>(smem + L.sc);               // [GQ][512]
-  uint32_t* Sszk = reinterpret_cast<uint32_t*>(smem + L.szk);       // [512/g][128]
-  uint32_t* Sszv = reinterpret_cast<uint32_t*>(smem + L.szv);       // [512][NG]
-  uint16_t* Sak = reinterpret_cast<uint16_t*>(smem + L.ak);         // [512][rk]
-  uint16_t* Sav = reinterpret_cast<uint16_t*>(smem + L.av);
   uint16_t* Sbfk = reinterpret_cast<uint16_t*>(smem + L.bfk);       // [128][rk]
   uint16_t* Sbfv = reinterpret_cast<uint16_t*>(smem + L.bfv);
-  uint32_t* Sspk = reinterpret_cast<uint32_t*>(smem + L.spk);       // staged lists, (row*128 + c) | val << 16
-  uint32_t* Sspv = reinterpret_cast<uint32_t*>(smem + L.spv);
-  float* Sosp = reinterpret_cast<float*>(smem + L.osp);             // [4 waves][GQ][128]
-  _Float16* opnd = reinterpret_cast<_Float16*>(smem + L.opnd) + (size_t)wave * L.opnd_halfs;
   MfmaMisc<GQ>& M = *reinterpret_cast<MfmaMisc<GQ>*>(smem + L.misc);
+  unsigned char* wbase = smem + L.wave0 + (size_t)wave * L.wave_stride;
+  float* Ssc = reinterpret_cast<float*>(wbase + L.sc);              // [GQ][128] raw scores, then p
+  uint32_t* Sszk = reinterpret_cast<uint32_t*>(wbase + L.szk);      // [128/g][128]
+  uint32_t* Sszv = reinterpret_cast<uint32_t*>(wbase + L.szv);      // [128][NG]
+  uint16_t* Sak = reinterpret_cast<uint16_t*>(wbase + L.ak);        // [128][rk]
+  uint16_t* Sav = reinterpret_cast<uint16_t*>(wbase + L.av);
+  uint32_t* Sspk = reinterpret_cast<uint32_t*>(wbase + L.spk);      // (row*128 + c) | val << 16, row in the wave
+  uint32_t* Sspv = reinterpret_cast<uint32_t*>(wbase + L.spv);
+  float* Sosp = reinterpret_cast<float*>(wbase + L.osp);            // [GQ][128] this wave's output plane
+  _Float16* opnd = reinterpret_cast<_Float16*>(wbase + L.opnd);
   const float scale = 0.08838834764831845f;  // 1/sqrt(128)
-  const int tile0 = t_begin / TILE, ntiles = (nr + TILE - 1) / TILE;
-  const int tw0 = t_begin + 128 * wave;       // first token owned by this wave
+  const int tw0 = t_begin + WTOK * wave;      // first token owned by this wave
+  int nw = t_end - tw0;                       // tokens this wave owns (may be <= 0)
+  nw = nw < 0 ? 0 : (nw > WTOK ? WTOK : nw);
 
   // =================== prologue: every load in flight ===================
-  if (dm.ppm > 0 && tid < 16) {
-    const int i = tid & 7;
-    uint2 e = make_uint2(0, 0);
-    if (i < ntiles)
-      e = (tid < 8) ? ks.sp_table[(size_t)slab * ks.ntile_cap + tile0 + i]
-                    : vs.sp_table[(size_t)slab * vs.ntile_cap + tile0 + i];
-    if (tid < 8) M.tabk[i] = e; else M.tabv[i] = e;
+  // the (offset, count) entries of this wave's two tiles of each tensor
+  uint2 tab = make_uint2(0, 0);
+  if (dm.ppm > 0 && lane < 4) {
+    const int ti = lane & 1;
+    if (ti * TILE < nw) {
+      const int tile = tw0 / TILE + ti;
+      tab = (lane < 2) ? ks.sp_table[(size_t)slab * ks.ntile_cap + tile] : vs.sp_table[(size_t)slab * vs.ntile_cap + tile];
+    }
   }
   // Key codes of this wave's 8 M-tiles into registers
   uint32_t kw[8][KW];
@@ -223,50 +237,58 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       }
     }
   }
+  // shared: q and the B factors
   for (int i = tid; i < GQ * D; i += 256) Sq[i] = h2f(qg[i]);
+  if (rk > 0) stage_halfs(Sbfk, ks.Bf + (size_t)slab * D * rk, D * rk);
+  if (rv > 0) stage_halfs(Sbfv, vs.Bf + (size_t)slab * D * rv, D * rv);
+  // per wave: (scale, zero) of its groups / tokens, its rows of A
+  if (nw > 0) {
+    const int ngl = (nw + g - 1) / g;
+    const uint32_t* src = ks.sz + ((size_t)slab * ks.ng_cap + tw0 / g) * D;
+    for (int i = lane; i < ngl * D; i += 64) Sszk[i] = src[i];
+    const uint32_t* srcv = vs.sz + ((size_t)slab * vs.n_cap + tw0) * NG;
+    for (int i = lane; i < nw * NG; i += 64) Sszv[i] = srcv[i];
+    if (rk > 0) wave_stage_halfs(Sak, ks.A + ((size_t)slab * ks.n_cap + tw0) * rk, nw * rk);
+    if (rv > 0) wave_stage_halfs(Sav, vs.A + ((size_t)slab * vs.n_cap + tw0) * rv, nw * rv);
+  }
+  // outlier lists of the wave's tiles: K tiles then V tiles, rows rebased to the wave
+  // a table entry is trusted only as far as its pool reaches
   {
-    const int ngl = (nr + g - 1) / g;
-    const uint32_t* src = ks.sz + ((size_t)slab * ks.ng_cap + t_begin / g) * D;
-    for (int i = tid; i < ngl * D; i += 256) Sszk[i] = src[i];
-    const uint32_t* srcv = vs.sz + ((size_t)slab * vs.n_cap + t_begin) * NG;
-    for (int i = tid; i < nr * NG; i += 256) Sszv[i] = srcv[i];
+    const uint32_t cap = (lane < 2) ? ks.pool_cap : vs.pool_cap;
+    if (tab.x > cap) tab.x = cap;
+    if (tab.y > cap - tab.x) tab.y = cap - tab.x;
   }
-  if (rk > 0) {
-    stage_halfs(Sak, ks.A + ((size_t)slab * ks.n_cap + t_begin) * rk, nr * rk);
-    stage_halfs(Sbfk, ks.Bf + (size_t)slab * D * rk, D * rk);
-  }
-  if (rv > 0) {
-    stage_halfs(Sav, vs.A + ((size_t)slab * vs.n_cap + t_begin) * rv, nr * rv);
-    stage_halfs(Sbfv, vs.Bf + (size_t)slab * D * rv, D * rv);
-  }
-  for (int i = tid; i < 4 * GQ * D; i += 256) Sosp[i] = 0.0f;
-  __syncthreads();
-
-  // outlier lists: prefix offsets of the tiles' lists inside the staging area
-  bool sp_fits = true;
-  if (dm.ppm > 0) {
-    if (tid < 2) {
-      uint32_t run = 0;
-      uint32_t* off = tid == 0 ? M.offk : M.offv;
-      const uint2* tab = tid == 0 ? M.tabk : M.tabv;
-      for (int i = 0; i < 8; ++i) { off[i] = run; run += tab[i].y; }
-      off[8] = run;
+  const uint32_t ck0 = __shfl(tab.y, 0, 64), ck1 = __shfl(tab.y, 1, 64);
+  const uint32_t cv0 = __shfl(tab.y, 2, 64), cv1 = __shfl(tab.y, 3, 64);
+  const uint32_t ok0 = __shfl(tab.x, 0, 64), ok1 = __shfl(tab.x, 1, 64);
+  const uint32_t ov0 = __shfl(tab.x, 2, 64), ov1 = __shfl(tab.x, 3, 64);
+  const bool sp_fits = (ck0 + ck1 <= (uint32_t)L.spcap) && (cv0 + cv1 <= (uint32_t)L.spcap);  // wave-uniform
+  const uint32_t* poolk = ks.sp_pool + (size_t)slab * ks.pool_cap;
+  const uint32_t* poolv = vs.sp_pool + (size_t)b * vs.pool_cap;
+  if (dm.ppm > 0 && sp_fits) {
+    for (uint32_t e = lane; e < ck0 + ck1; e += 64) {
+      const bool second = e >= ck0;
+      const uint32_t en = second ? poolk[ok1 + (e - ck0)] : poolk[ok0 + e];
+      Sspk[e] = ((en & 0xFFFFu) + (second ? TILE * D : 0)) | (en & 0xFFFF0000u);
     }
-    __syncthreads();
-    sp_fits = M.offk[8] <= (uint32_t)L.spcap && M.offv[8] <= (uint32_t)L.spcap;
+    for (uint32_t e = lane; e < cv0 + cv1; e += 64) {
+      const bool second = e >= cv0;
+      const uint32_t en = second ? poolv[ov1 + (e - cv0)] : poolv[ov0 + e];
+      Sspv[e] = ((en & 0xFFFFu) + (second ? TILE * D : 0)) | (en & 0xFFFF0000u);
+    }
   }
+  for (int i = lane; i < GQ * D; i += 64) Sosp[i] = 0.0f;
+  __syncthreads();   // q and the B factors are visible to all waves; from here on waves run independently
 
-  // q^T B_K (down-projection of the low-rank Key term)
-  if (tid < GQ * 8) {
-    const int hq = tid >> 3, r = tid & 7;
-    float s = 0.0f;
+  // q^T B_K (down-projection of the low-rank Key term): lane (hq, r) -> registers of every lane via shuffles
+  float qB_l = 0.0f;
+  if (rk > 0 && lane < GQ * 8) {
+    const int hq = lane >> 3, r = lane & 7;
     if (r < rk)
-      for (int c = 0; c < D; ++c) s += Sq[hq * D + c] * h2f(Sbfk[c * rk + r]);
-    M.qB[hq][r] = s;
+      for (int c = 0; c < D; ++c) qB_l += Sq[hq * D + c] * h2f(Sbfk[c * rk + r]);
   }
 
   // =================== Key scores on the matrix cores ===================
-  // wave owns tokens tw0 .. tw0+127: 128/g groups of g/16 M-tiles
   int kslot[2];     // operand position of channels lane and lane + 64 (same for every group)
   float kscale[2];
 #pragma unroll
@@ -277,161 +299,106 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     kslot[rep] = (ch >> 5) * 32 + idx;
     kscale[rep] = opscale(lg);
   }
-  for (int gw = 0; gw < 128 / g; ++gw) {
-    const int gl = (128 * wave) / g + gw;           // group index inside the block
-    const bool gvalid = t_begin + gl * g < t_end;   // wave-uniform
-    if (gvalid) {
-      float base[GQ];
+  for (int gw = 0; gw < WTOK / g; ++gw) {
+    if (gw * g >= nw) break;                        // wave-uniform
+    float kb[GQ];
 #pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) base[hq] = 0.0f;
+    for (int hq = 0; hq < GQ; ++hq) kb[hq] = 0.0f;
 #pragma unroll
-      for (int rep = 0; rep < 2; ++rep) {
-        const int ch = lane + 64 * rep;
-        const uint32_t sb = Sszk[gl * D + ch];
-        const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
-        const float os = kscale[rep];
-        _Float16* dst = opnd + kslot[rep];
-#pragma unroll
-        for (int hq = 0; hq < GQ; ++hq) {
-          const float qv = Sq[hq * D + ch];
-          const float w = qv * delta * os;
-          const _Float16 hi = (_Float16)w;
-          const _Float16 lo = (_Float16)(w - (float)hi);
-          dst[(2 * hq) * D] = hi;
-          dst[(2 * hq + 1) * D] = lo;
-          base[hq] += qv * mn;
-        }
-      }
+    for (int rep = 0; rep < 2; ++rep) {
+      const int ch = lane + 64 * rep;
+      const uint32_t sb = Sszk[gw * D + ch];
+      const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
+      const float os = kscale[rep];
+      _Float16* dst = opnd + kslot[rep];
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
-        const float bsum = wave_sum(base[hq]);
-        if (lane == 0) M.kbase[hq][gl] = bsum;
+        const float qv = Sq[hq * D + ch];
+        const float w = qv * delta * os;
+        const _Float16 hi = (_Float16)w;
+        const _Float16 lo = (_Float16)(w - (float)hi);
+        dst[(2 * hq) * D] = hi;
+        dst[(2 * hq + 1) * D] = lo;
+        kb[hq] += qv * mn;
       }
     }
-    wave_lds_sync();  // staging area is private to the wave
-    if (gvalid) {
-      half8 bop[4];
 #pragma unroll
-      for (int jb = 0; jb < 4; ++jb) {
-        uint4 raw = make_uint4(0, 0, 0, 0);
-        if (n16 < 2 * GQ) raw = *reinterpret_cast<const uint4*>(opnd + n16 * D + kg * 32 + jb * 8);
-        bop[jb] = __builtin_bit_cast(half8, raw);
-      }
-      const int hq = n16 >> 1;
-      const float kb = (hq < GQ) ? M.kbase[hq][gl] : 0.0f;
+    for (int hq = 0; hq < GQ; ++hq) kb[hq] = wave_sum(kb[hq]);   // zero-point term q . zero_K of the group
+    wave_lds_sync();
+    half8 bop[4];
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) {
-        if (mt / (g / 16) == gw) {
-          floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-          if (BITS == 2) {
-            uint32_t v[8];
-            Codec<2>::unpack(kw[mt][0], v);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[0], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[1], acc, 0, 0, 0);
-            Codec<2>::unpack(kw[mt][1], v);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[2], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[3], acc, 0, 0, 0);
-          } else {
+    for (int jb = 0; jb < 4; ++jb) {
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (n16 < 2 * GQ) raw = *reinterpret_cast<const uint4*>(opnd + n16 * D + kg * 32 + jb * 8);
+      bop[jb] = __builtin_bit_cast(half8, raw);
+    }
+    const int hq_l = n16 >> 1;
+    float kbl = 0.0f;
 #pragma unroll
-            for (int jb = 0; jb < 4; ++jb) {
-              uint32_t v[4];
-              Codec<4>::unpack(kw[mt][jb % KW], v);
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[jb], acc, 0, 0, 0);
-            }
-          }
-          // D[token 4*kg + i][col n16]: add the hi and lo columns, keep the even ones
-          float4 s4;
-          s4.x = acc[0] + dpp_f<DPP_XOR1>(acc[0]);
-          s4.y = acc[1] + dpp_f<DPP_XOR1>(acc[1]);
-          s4.z = acc[2] + dpp_f<DPP_XOR1>(acc[2]);
-          s4.w = acc[3] + dpp_f<DPP_XOR1>(acc[3]);
-          if ((n16 & 1) == 0 && hq < GQ) {
-            s4.x = s4.x * MFMA_OUT_SCALE + kb;
-            s4.y = s4.y * MFMA_OUT_SCALE + kb;
-            s4.z = s4.z * MFMA_OUT_SCALE + kb;
-            s4.w = s4.w * MFMA_OUT_SCALE + kb;
-            *reinterpret_cast<float4*>(&Ssc[hq * MFMA_TS + 128 * wave + 16 * mt + 4 * kg]) = s4;
+    for (int hq = 0; hq < GQ; ++hq) kbl = (hq == hq_l) ? kb[hq] : kbl;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) {
+      if (mt / (g / 16) == gw) {
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (BITS == 2) {
+          uint32_t v[8];
+          Codec<2>::unpack(kw[mt][0], v);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[0], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[1], acc, 0, 0, 0);
+          Codec<2>::unpack(kw[mt][1], v);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[2], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[3], acc, 0, 0, 0);
+        } else {
+#pragma unroll
+          for (int jb = 0; jb < 4; ++jb) {
+            uint32_t v[4];
+            Codec<4>::unpack(kw[mt][jb % KW], v);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[jb], acc, 0, 0, 0);
           }
         }
+        // D[token 4*kg + i][col n16]: add the hi and lo columns, keep the even ones
+        float4 s4;
+        s4.x = acc[0] + dpp_f<DPP_XOR1>(acc[0]);
+        s4.y = acc[1] + dpp_f<DPP_XOR1>(acc[1]);
+        s4.z = acc[2] + dpp_f<DPP_XOR1>(acc[2]);
+        s4.w = acc[3] + dpp_f<DPP_XOR1>(acc[3]);
+        if ((n16 & 1) == 0 && hq_l < GQ) {
+          s4.x = s4.x * MFMA_OUT_SCALE + kbl;
+          s4.y = s4.y * MFMA_OUT_SCALE + kbl;
+          s4.z = s4.z * MFMA_OUT_SCALE + kbl;
+          s4.w = s4.w * MFMA_OUT_SCALE + kbl;
+          *reinterpret_cast<float4*>(&Ssc[hq_l * WTOK + 16 * mt + 4 * kg]) = s4;
+        }
       }
+      __builtin_amdgcn_sched_barrier(0);   // keep one tile's unpacked codes live at a time
     }
-    wave_lds_sync();  // staging area is private to the wave
-  }
-  __syncthreads();  // scores of all four waves are in LDS
-
-  // request this wave's Value codes now; they are consumed after the softmax
-  uint32_t vw[VBLK][8];
-#pragma unroll
-  for (int bl = 0; bl < VBLK; ++bl) {
-    const int tb0 = tw0 + bl * TB;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) vw[bl][j] = 0u;
-    if (tb0 < t_end) {
-      const uint32_t* cw = vs.codes + ((size_t)slab * vs.nblk_cap + tb0 / TB) * 512 + (kg * 16 + n16) * 8;
-      const uint4 c0 = *reinterpret_cast<const uint4*>(cw);
-      const uint4 c1 = *reinterpret_cast<const uint4*>(cw + 4);
-      vw[bl][0] = c0.x; vw[bl][1] = c0.y; vw[bl][2] = c0.z; vw[bl][3] = c0.w;
-      vw[bl][4] = c1.x; vw[bl][5] = c1.y; vw[bl][6] = c1.z; vw[bl][7] = c1.w;
-    }
+    wave_lds_sync();
   }
 
-  // request the outlier lists (rows rebased to the block: (row*128 + c) | value << 16)
-  constexpr int SPR = 8;  // staged entries per thread and tensor (2048 / 256)
-  uint32_t spk_r[SPR], spv_r[SPR];
-  if (dm.ppm > 0 && sp_fits) {
-    const uint32_t* poolk = ks.sp_pool + (size_t)slab * ks.pool_cap;
-    const uint32_t* poolv = vs.sp_pool + (size_t)b * vs.pool_cap;
-#pragma unroll
-    for (int r = 0; r < SPR; ++r) {
-      const uint32_t e = tid + 256 * r;
-      spk_r[r] = 0u; spv_r[r] = 0u;
-      if (e < M.offk[8]) {
-        int ti = 0;
-#pragma unroll
-        for (int i = 1; i < 8; ++i) ti += (e >= M.offk[i]) ? 1 : 0;
-        const uint32_t en = poolk[M.tabk[ti].x + (e - M.offk[ti])];
-        spk_r[r] = ((en & 0xFFFFu) + (uint32_t)ti * (TILE * D)) | (en & 0xFFFF0000u);
-      }
-      if (e < M.offv[8]) {
-        int ti = 0;
-#pragma unroll
-        for (int i = 1; i < 8; ++i) ti += (e >= M.offv[i]) ? 1 : 0;
-        const uint32_t en = poolv[M.tabv[ti].x + (e - M.offv[ti])];
-        spv_r[r] = ((en & 0xFFFFu) + (uint32_t)ti * (TILE * D)) | (en & 0xFFFF0000u);
-      }
-    }
-  }
-  // low-rank Key term, tokens tid and tid + 256
+  // low-rank Key term: lane handles rows lane and lane + 64
   if (rk > 0) {
-    for (int tl = tid; tl < nr; tl += 256) {
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+      const int row = lane + 64 * rep;
       float a[8];
 #pragma unroll
-      for (int r = 0; r < 8; ++r) a[r] = r < rk ? h2f(Sak[tl * rk + r]) : 0.0f;
+      for (int r = 0; r < 8; ++r) a[r] = (r < rk && row < nw) ? h2f(Sak[row * rk + r]) : 0.0f;
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
-        float s = Ssc[hq * MFMA_TS + tl];
+        float s = Ssc[hq * WTOK + row];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) s += M.qB[hq][r] * a[r];
-        Ssc[hq * MFMA_TS + tl] = s;
+        for (int r = 0; r < 8; ++r) s += __shfl(qB_l, hq * 8 + r, 64) * a[r];
+        Ssc[hq * WTOK + row] = s;
       }
     }
+    wave_lds_sync();
   }
-  // staged outlier lists land in LDS
-  if (dm.ppm > 0 && sp_fits) {
-#pragma unroll
-    for (int r = 0; r < SPR; ++r) {
-      const uint32_t e = tid + 256 * r;
-      if (e < M.offk[8]) Sspk[e] = spk_r[r];
-      if (e < M.offv[8]) Sspv[e] = spv_r[r];
-    }
-  }
-  __syncthreads();
 
   // sparse Key term.  Staged list is ordered (row, c): the first entry of a row sums the row's run.
   if (dm.ppm > 0) {
     if (sp_fits) {
-      const uint32_t cnt = M.offk[8];
-      for (uint32_t e = tid; e < cnt; e += 256) {
+      const uint32_t cnt = ck0 + ck1;
+      for (uint32_t e = lane; e < cnt; e += 64) {
         const uint32_t me = Sspk[e];
         const uint32_t row = (me & 0xFFFFu) >> 7;
         if (e > 0 && ((Sspk[e - 1] & 0xFFFFu) >> 7) == row) continue;
@@ -447,20 +414,20 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           for (int hq = 0; hq < GQ; ++hq) a2[hq] += Sq[hq * D + c] * v;
         }
 #pragma unroll
-        for (int hq = 0; hq < GQ; ++hq) Ssc[hq * MFMA_TS + row] += a2[hq];
+        for (int hq = 0; hq < GQ; ++hq) Ssc[hq * WTOK + row] += a2[hq];
       }
     } else {  // lists larger than the staging area: read them from global memory
-      for (int ti = 0; ti < ntiles; ++ti) {
-        const uint2 oc = M.tabk[ti];
-        const uint32_t* lst = ks.sp_pool + (size_t)slab * ks.pool_cap + oc.x;
-        for (uint32_t e = tid; e < oc.y; e += 256) {
+      for (int ti = 0; ti < 2; ++ti) {
+        const uint32_t off = ti ? ok1 : ok0, cnt = ti ? ck1 : ck0;
+        const uint32_t* lst = poolk + off;
+        for (uint32_t e = lane; e < cnt; e += 64) {
           const uint32_t me = lst[e];
           const uint32_t tl = (me & 0xFFFFu) >> 7;
           if (e > 0 && ((lst[e - 1] & 0xFFFFu) >> 7) == tl) continue;
           float a2[GQ];
 #pragma unroll
           for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
-          for (uint32_t f = e; f < oc.y; ++f) {
+          for (uint32_t f = e; f < cnt; ++f) {
             const uint32_t en = lst[f];
             if (((en & 0xFFFFu) >> 7) != tl) break;
             const float v = h2f(en >> 16);
@@ -469,38 +436,47 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
             for (int hq = 0; hq < GQ; ++hq) a2[hq] += Sq[hq * D + c] * v;
           }
 #pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) Ssc[hq * MFMA_TS + ti * TILE + tl] += a2[hq];
+          for (int hq = 0; hq < GQ; ++hq) Ssc[hq * WTOK + ti * TILE + tl] += a2[hq];
         }
       }
     }
-    __syncthreads();
+    wave_lds_sync();
   }
 
-  // =================== block-local softmax ===================
+  // request this wave's Value codes; they arrive while the softmax runs
+  uint32_t vw[VBLK][8];
+#pragma unroll
+  for (int bl = 0; bl < VBLK; ++bl) {
+    const int tb0 = tw0 + bl * TB;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) vw[bl][j] = 0u;
+    if (tb0 < t_end) {
+      const uint32_t* cw = vs.codes + ((size_t)slab * vs.nblk_cap + tb0 / TB) * 512 + (kg * 16 + n16) * 8;
+      const uint4 c0 = *reinterpret_cast<const uint4*>(cw);
+      const uint4 c1 = *reinterpret_cast<const uint4*>(cw + 4);
+      vw[bl][0] = c0.x; vw[bl][1] = c0.y; vw[bl][2] = c0.z; vw[bl][3] = c0.w;
+      vw[bl][4] = c1.x; vw[bl][5] = c1.y; vw[bl][6] = c1.z; vw[bl][7] = c1.w;
+    }
+  }
+
+  // =================== this wave's softmax state ===================
   {
-    float s0[GQ], s1[GQ];
 #pragma unroll
     for (int hq = 0; hq < GQ; ++hq) {
-      s0[hq] = tid < nr ? Ssc[hq * MFMA_TS + tid] * scale : -INFINITY;
-      s1[hq] = tid + 256 < nr ? Ssc[hq * MFMA_TS + tid + 256] * scale : -INFINITY;
-      const float mx = wave_max(fmaxf(s0[hq], s1[hq]));
-      if (lane == 0) M.red[hq][wave] = mx;
+      const float s0 = lane < nw ? Ssc[hq * WTOK + lane] * scale : -INFINITY;
+      const float s1 = lane + 64 < nw ? Ssc[hq * WTOK + lane + 64] * scale : -INFINITY;
+      const float m = wave_max(fmaxf(s0, s1));
+      const float p0 = lane < nw ? __expf(s0 - m) : 0.0f;
+      const float p1 = lane + 64 < nw ? __expf(s1 - m) : 0.0f;
+      Ssc[hq * WTOK + lane] = p0;          // rows >= nw hold p = 0
+      Ssc[hq * WTOK + lane + 64] = p1;
+      const float l = wave_sum(p0 + p1);
+      if (lane == 0) {
+        M.wstat[wave][hq][0] = m;          // -inf when the wave owns no token
+        M.wstat[wave][hq][1] = l;
+      }
     }
-    __syncthreads();
-    if (tid < GQ) M.stat[tid][0] = fmaxf(fmaxf(M.red[tid][0], M.red[tid][1]), fmaxf(M.red[tid][2], M.red[tid][3]));
-    __syncthreads();
-#pragma unroll
-    for (int hq = 0; hq < GQ; ++hq) {
-      const float m = M.stat[hq][0];
-      const float p0 = tid < nr ? __expf(s0[hq] - m) : 0.0f;
-      const float p1 = tid + 256 < nr ? __expf(s1[hq] - m) : 0.0f;
-      Ssc[hq * MFMA_TS + tid] = p0;         // rows >= nr hold p = 0
-      Ssc[hq * MFMA_TS + tid + 256] = p1;
-      const float sum = wave_sum(p0 + p1);
-      if (lane == 0) M.red[hq][wave] = sum;
-    }
-    __syncthreads();
-    if (tid < GQ) M.stat[tid][1] = M.red[tid][0] + M.red[tid][1] + M.red[tid][2] + M.red[tid][3];
+    wave_lds_sync();
   }
 
   // =================== Value side on the matrix cores ===================
@@ -528,20 +504,19 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   for (int hq = 0; hq < GQ; ++hq) pmr[hq] = 0.0f;
 #pragma unroll
   for (int bl = 0; bl < VBLK; ++bl) {
-    const int tl0 = 128 * wave + bl * TB;          // block-local first row of this code block
-    const bool bvalid = tl0 < nr;                  // wave-uniform
-    if (bvalid) {
+    const int tl0 = bl * TB;                       // first row (inside the wave) of this code block
+    if (tl0 < nw) {                                // wave-uniform
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         if (vrow[k] >= 0) {
           const int row = tl0 + vrow[k];
-          const uint32_t sb = row < nr ? Sszv[row * NG + Gl] : 0u;
+          const uint32_t sb = row < nw ? Sszv[row * NG + Gl] : 0u;
           const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
           const float ds = delta * vscale[k];
           _Float16* dst = opnd + vslot[k];
 #pragma unroll
           for (int hq = 0; hq < GQ; ++hq) {
-            const float pv = Ssc[hq * MFMA_TS + row];
+            const float pv = Ssc[hq * WTOK + row];
             const float w = pv * ds;
             const _Float16 hi = (_Float16)w;
             const _Float16 lo = (_Float16)(w - (float)hi);
@@ -551,9 +526,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           }
         }
       }
-    }
-    wave_lds_sync();  // staging area is private to the wave
-    if (bvalid) {
+      wave_lds_sync();
       const int tiles_per_G = g / 16;
       for (int G = 0; G < NG; ++G) {
         half8 pa0 = __builtin_bit_cast(half8, make_uint4(0, 0, 0, 0)), pa1 = pa0;
@@ -576,47 +549,48 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
               acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa0, as_half8(v[0], v[1], v[2], v[3]), acc[j], 0, 0, 0);
             }
           }
+          __builtin_amdgcn_sched_barrier(0);   // keep one tile's unpacked codes live at a time
         }
       }
+      wave_lds_sync();
     }
-    wave_lds_sync();  // staging area is private to the wave
   }
 #pragma unroll
   for (int hq = 0; hq < GQ; ++hq)
 #pragma unroll
     for (int G = 0; G < 4; ++G) {
-      if (G < NG) {  // wave-uniform
-        const float s = wave_sum(Gl == G ? pmr[hq] : 0.0f);
-        if (lane == 0) M.pm[wave][hq][G] = s;
-      } else if (lane == 0) {
-        M.pm[wave][hq][G] = 0.0f;
-      }
+      float s = 0.0f;
+      if (G < NG) s = wave_sum(Gl == G ? pmr[hq] : 0.0f);   // wave-uniform branch
+      if (lane == 0) M.pm[wave][hq][G] = s;
     }
-  // D[col 4*kg + i][channel 16 j + n16] -> this wave's accumulator plane
+  // D[col 4*kg + i][channel 16 j + n16] -> this wave's output plane
   {
-    float* mine = Sosp + (size_t)wave * GQ * D;
     const int hq0 = 2 * kg, hq1 = 2 * kg + 1;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      if (hq0 < GQ) mine[hq0 * D + 16 * j + n16] = (acc[j][0] + acc[j][1]) * MFMA_OUT_SCALE;
-      if (hq1 < GQ) mine[hq1 * D + 16 * j + n16] = (acc[j][2] + acc[j][3]) * MFMA_OUT_SCALE;
+      if (hq0 < GQ) Sosp[hq0 * D + 16 * j + n16] = (acc[j][0] + acc[j][1]) * MFMA_OUT_SCALE;
+      if (hq1 < GQ) Sosp[hq1 * D + 16 * j + n16] = (acc[j][2] + acc[j][3]) * MFMA_OUT_SCALE;
     }
   }
 
-  // p^T A_V (down-projection of the low-rank Value term)
+  // p^T A_V (down-projection of the low-rank Value term) over the wave's rows
   if (rv > 0) {
     float part[GQ][8];
 #pragma unroll
     for (int hq = 0; hq < GQ; ++hq)
 #pragma unroll
       for (int r = 0; r < 8; ++r) part[hq][r] = 0.0f;
-    for (int tl = tid; tl < nr; tl += 256) {
 #pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        if (r < rv) {
-          const float a = h2f(Sav[tl * rv + r]);
+    for (int rep = 0; rep < 2; ++rep) {
+      const int row = lane + 64 * rep;
+      if (row < nw) {
 #pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) part[hq][r] += Ssc[hq * MFMA_TS + tl] * a;
+        for (int r = 0; r < 8; ++r) {
+          if (r < rv) {
+            const float a = h2f(Sav[row * rv + r]);
+#pragma unroll
+            for (int hq = 0; hq < GQ; ++hq) part[hq][r] += Ssc[hq * WTOK + row] * a;
+          }
         }
       }
     }
@@ -624,27 +598,23 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     for (int hq = 0; hq < GQ; ++hq)
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
-        if (r < rv) {
-          const float s = wave_sum(part[hq][r]);
-          if (lane == 0) M.wred[wave][hq][r] = s;
-        }
+        float s = 0.0f;
+        if (r < rv) s = wave_sum(part[hq][r]);
+        if (lane == 0) M.wv[wave][hq][r] = s;
       }
+  } else if (lane < GQ * 8) {
+    M.wv[wave][lane >> 3][lane & 7] = 0.0f;
   }
-  __syncthreads();
-  if (tid < GQ * 8) {
-    const int hq = tid >> 3, r = tid & 7;
-    M.wv[hq][r] = r < rv ? (M.wred[0][hq][r] + M.wred[1][hq][r] + M.wred[2][hq][r] + M.wred[3][hq][r]) : 0.0f;
-  }
+  wave_lds_sync();
 
   // sparse Value term.  Each tile's list is ordered (c, row): the first entry of a channel
-  // sums the channel's run.  Wave w takes tiles w, w+4 one after the other and
-  // adds into its own accumulator plane, so no two lanes ever update one address
-  // at the same time and the summation order is fixed.
+  // sums the channel's run; the wave walks its two tiles one after the other, so
+  // no two lanes ever update one address at the same time and the summation
+  // order is fixed.
   if (dm.ppm > 0) {
-    float* mine = Sosp + (size_t)wave * GQ * D;
-    for (int ti = wave; ti < ntiles; ti += 4) {
+    for (int ti = 0; ti < 2; ++ti) {
       if (sp_fits) {
-        const uint32_t e0 = M.offv[ti], e1 = M.offv[ti + 1];
+        const uint32_t e0 = ti ? cv0 : 0u, e1 = ti ? cv0 + cv1 : cv0;
         for (uint32_t e = e0 + lane; e < e1; e += 64) {
           const uint32_t me = Sspv[e];
           const uint32_t ch = me & 127u;
@@ -658,50 +628,61 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
             const float v = h2f(en >> 16);
             const int row = (en & 0xFFFFu) >> 7;
 #pragma unroll
-            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * MFMA_TS + row] * v;
+            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * WTOK + row] * v;
           }
 #pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) mine[hq * D + ch] += a2[hq];
+          for (int hq = 0; hq < GQ; ++hq) Sosp[hq * D + ch] += a2[hq];
         }
       } else {
-        const uint2 oc = M.tabv[ti];
-        const uint32_t* lst = vs.sp_pool + (size_t)b * vs.pool_cap + oc.x;
-        for (uint32_t e = lane; e < oc.y; e += 64) {
+        const uint32_t off = ti ? ov1 : ov0, cnt = ti ? cv1 : cv0;
+        const uint32_t* lst = poolv + off;
+        for (uint32_t e = lane; e < cnt; e += 64) {
           const uint32_t me = lst[e];
           const uint32_t ch = me & 127u;
           if (e > 0 && (lst[e - 1] & 127u) == ch) continue;
           float a2[GQ];
 #pragma unroll
           for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
-          for (uint32_t f = e; f < oc.y; ++f) {
+          for (uint32_t f = e; f < cnt; ++f) {
             const uint32_t en = lst[f];
             if ((en & 127u) != ch) break;
             const float v = h2f(en >> 16);
             const int row = ti * TILE + (int)((en & 0xFFFFu) >> 7);
 #pragma unroll
-            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * MFMA_TS + row] * v;
+            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * WTOK + row] * v;
           }
 #pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) mine[hq * D + ch] += a2[hq];
+          for (int hq = 0; hq < GQ; ++hq) Sosp[hq * D + ch] += a2[hq];
         }
       }
-      __builtin_amdgcn_wave_barrier();
+      wave_lds_sync();
     }
   }
   __syncthreads();
 
-  // =================== combine the four waves, write the record ===================
+  // =================== merge the four waves' states, write the record ===================
   for (int i = tid; i < GQ * D; i += 256) {
     const int hq = i / D, c = i % D, G = c / g;
-    float o = 0.0f;
+    float Mx = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) o += Sosp[((size_t)w * GQ + hq) * D + c] + M.pm[w][hq][G];
-    for (int r = 0; r < rv; ++r) o += M.wv[hq][r] * h2f(Sbfv[c * rv + r]);
+    for (int w = 0; w < 4; ++w) Mx = fmaxf(Mx, M.wstat[w][hq][0]);
+    float o = 0.0f, l = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = M.wstat[w][hq][0];
+      if (mw == -INFINITY) continue;
+      const float f = __expf(mw - Mx);
+      const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
+      float ow = plane[hq * D + c] + M.pm[w][hq][G];
+      for (int r = 0; r < rv; ++r) ow += M.wv[w][hq][r] * h2f(Sbfv[c * rv + r]);
+      o += f * ow;
+      l += f * M.wstat[w][hq][1];
+    }
     float* rec = rec_base + (size_t)hq * rec_stride;
     rec[2 + c] = o;
     if (c == 0) {
-      rec[0] = M.stat[hq][0];
-      rec[1] = M.stat[hq][1];
+      rec[0] = Mx;
+      rec[1] = l;
     }
   }
 }

@@ -139,6 +139,8 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
         if (tile * TILE < n_j) {
           const SegView v = chunk_view(which ? cs.v0 : cs.k0, cs.stride, j, n_j, cs.rank[j]);
           e = v.sp_table[(size_t)slab * v.ntile_cap + tile];
+          if (e.x > v.pool_cap) e.x = v.pool_cap;   // a table entry is trusted only as far as its pool reaches
+          if (e.y > v.pool_cap - e.x) e.y = v.pool_cap - e.x;
         }
         if (which) S.tabv[jc][tile] = e; else S.tabk[jc][tile] = e;
       }

@@ -7,6 +7,12 @@
 
 #include "gear.h"
 
+// Declares the kernel's dynamically sized LDS array (a build that runs the
+// kernels elsewhere than on the GPU may predefine this).
+#ifndef GEAR_DYN_LDS
+#define GEAR_DYN_LDS(name) extern __shared__ __align__(16) unsigned char name[]
+#endif
+
 namespace gear {
 
 constexpr int D = 128;      // head dimension
