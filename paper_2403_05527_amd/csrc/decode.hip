@@ -21,7 +21,7 @@ static_assert(MFMA_TS == DECODE_SPLIT, "split size is part of the workspace layo
 
 // grid (nsplit + 1, B*H_kv), block 256.
 template <int BITS, int GQ>
-__global__ __launch_bounds__(256, 2) void decode_split_kernel(Dims dm, SegView k0, SegView v0, ChunkSet cs,
+__global__ __launch_bounds__(256, 4) void decode_split_kernel(Dims dm, SegView k0, SegView v0, ChunkSet cs,
                                                               const uint16_t* __restrict__ q,
                                                               const uint16_t* __restrict__ Kbuf,
                                                               const uint16_t* __restrict__ Vbuf, int n_buf,

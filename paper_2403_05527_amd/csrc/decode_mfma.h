@@ -32,6 +32,14 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int MFMA_TS = 512;                 // tokens per block (128 per wave)
 constexpr float MFMA_OUT_SCALE = 1048576.f;  // 2^24 / 16: undoes the denormal and operand scaling
 
+// Returns w through an empty volatile asm: the unpacking that follows stays where it is
+// written (inside the group loop, next to its MFMA) instead of being hoisted out of the
+// loop for all tiles at once, which would hold every tile's unpacked codes in registers.
+__device__ __forceinline__ uint32_t pin_here(uint32_t w) {
+  GEAR_PIN_VGPR(w);
+  return w;
+}
+
 __device__ __forceinline__ half8 as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
   return __builtin_bit_cast(half8, make_uint4(a, b, c, d));
 }
@@ -342,17 +350,17 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
         if (BITS == 2) {
           uint32_t v[8];
-          Codec<2>::unpack(kw[mt][0], v);
+          Codec<2>::unpack(pin_here(kw[mt][0]), v);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[0], acc, 0, 0, 0);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[1], acc, 0, 0, 0);
-          Codec<2>::unpack(kw[mt][1], v);
+          Codec<2>::unpack(pin_here(kw[mt][1]), v);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[2], acc, 0, 0, 0);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[3], acc, 0, 0, 0);
         } else {
 #pragma unroll
           for (int jb = 0; jb < 4; ++jb) {
             uint32_t v[4];
-            Codec<4>::unpack(kw[mt][jb % KW], v);
+            Codec<4>::unpack(pin_here(kw[mt][jb % KW]), v);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[jb], acc, 0, 0, 0);
           }
         }
@@ -370,7 +378,6 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           *reinterpret_cast<float4*>(&Ssc[hq_l * WTOK + 16 * mt + 4 * kg]) = s4;
         }
       }
-      __builtin_amdgcn_sched_barrier(0);   // keep one tile's unpacked codes live at a time
     }
     wave_lds_sync();
   }
@@ -540,17 +547,16 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           if (j / tiles_per_G == G) {
             if (BITS == 2) {
               uint32_t v[8];
-              Codec<2>::unpack(vw[bl][j], v);
+              Codec<2>::unpack(pin_here(vw[bl][j]), v);
               acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa0, as_half8(v[0], v[1], v[2], v[3]), acc[j], 0, 0, 0);
               acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa1, as_half8(v[4], v[5], v[6], v[7]), acc[j], 0, 0, 0);
             } else {
               uint32_t v[4];
-              Codec<4>::unpack(vw[bl][j], v);
+              Codec<4>::unpack(pin_here(vw[bl][j]), v);
               acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa0, as_half8(v[0], v[1], v[2], v[3]), acc[j], 0, 0, 0);
             }
           }
-          __builtin_amdgcn_sched_barrier(0);   // keep one tile's unpacked codes live at a time
-        }
+            }
       }
       wave_lds_sync();
     }

@@ -13,6 +13,12 @@
 #define GEAR_DYN_LDS(name) extern __shared__ __align__(16) unsigned char name[]
 #endif
 
+// An empty volatile asm that takes and returns a value in a vector register: the
+// compiler can neither hoist nor sink what depends on it.
+#ifndef GEAR_PIN_VGPR
+#define GEAR_PIN_VGPR(x) asm volatile("" : "+v"(x))
+#endif
+
 namespace gear {
 
 constexpr int D = 128;      // head dimension
