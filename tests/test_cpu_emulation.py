@@ -1,0 +1,92 @@
+"""The library's kernels and launchers, compiled as plain C++ against the CPU stand-in
+for the HIP device environment in tests/simt/ and run under the address sanitizer:
+one small end-to-end case (prefill compress, one chunk, decode attention over cache +
+buffer, decompress) through the C ABI, compared with the oracle.  This checks the host
+logic (grids, LDS sizes, arena and workspace layout) and that no kernel reads or
+writes outside its buffers or its LDS; it does not replace the GPU parity tests (the
+emulation knows nothing of the real compiler's code or the hardware's timing)."""
+import os
+import shutil
+import subprocess
+
+import numpy as np
+import pytest
+
+import gear_workloads as gw
+from oracle import gear_oracle as go
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SIMT = os.path.join(ROOT, "tests", "simt")
+CSRC = os.path.join(ROOT, "paper_2403_05527_amd", "csrc")
+SOURCES = ["gear_api", "compress_filter", "compress_values", "lowrank", "decode", "decompress_export"]
+
+
+def find_clang():
+    for c in ("/opt/rocm/llvm/bin/clang++", shutil.which("clang++")):
+        if c and os.path.exists(c):
+            return c
+    return None
+
+
+@pytest.fixture(scope="module")
+def emulator(tmp_path_factory):
+    cxx = find_clang()
+    if cxx is None:
+        pytest.skip("no clang++ to build the CPU emulation")
+    out = tmp_path_factory.mktemp("simt")
+    flags = ["-std=c++17", "-O1", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-pthread",
+             "-I", SIMT, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    procs = []
+    objs = []
+    for s in SOURCES:
+        o = str(out / (s + ".o"))
+        objs.append(o)
+        procs.append(subprocess.Popen([cxx, "-x", "c++", "-c", os.path.join(CSRC, s + ".hip"), "-o", o] + flags,
+                                      stderr=subprocess.PIPE, text=True))
+    for s in ("simt_rt", "run_pipeline"):
+        o = str(out / (s + ".o"))
+        objs.append(o)
+        procs.append(subprocess.Popen([cxx, "-c", os.path.join(SIMT, s + ".cpp"), "-o", o] + flags,
+                                      stderr=subprocess.PIPE, text=True))
+    for p in procs:
+        err = p.communicate()[1]
+        assert p.returncode == 0, err[-3000:]
+    exe = str(out / "run_pipeline")
+    r = subprocess.run([cxx] + objs + ["-o", exe] + flags, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    return exe
+
+
+def test_pipeline_under_address_sanitizer(emulator, tmp_path):
+    B, H, Hq, n, bits, g, ppm, rank, n_buf = 1, 2, 4, 150, 2, 64, 20000, 4, 5
+    w = gw.Workload("emu", B=B, H_kv=H, H_q=Hq, n=n, bits=bits, group=g, outlier_ppm=ppm, rank=rank,
+                    rank_chunk=2, n_b=20, steps=1, seed=5)
+    d = str(tmp_path)
+    a = lambda t: t.numpy()
+    oc = go.OracleCache(B, H, Hq, 128, bits, g, ppm)
+    K, V, ib = a(gw.make_keys(w, n, 0)), a(gw.make_values(w, n, 0)), a(gw.make_init_B(w, rank, 0))
+    for name, x in (("K", K), ("V", V), ("ib", ib)):
+        x.tofile(os.path.join(d, name + ".bin"))
+    oc.compress(K, V, rank, 3, ib)
+    Kc, Vc, ibc = a(gw.make_keys(w, 20, 1)), a(gw.make_values(w, 20, 1)), a(gw.make_init_B(w, 2, 1))
+    for name, x in (("Kc0", Kc), ("Vc0", Vc), ("ibc0", ibc)):
+        x.tofile(os.path.join(d, name + ".bin"))
+    oc.compress(Kc, Vc, 2, 3, ibc)
+    q, Kb, Vb = a(gw.make_queries(w, 0)), a(gw.make_keys(w, 20, 50)), a(gw.make_values(w, 20, 50))
+    for name, x in (("q", q), ("Kb", Kb), ("Vb", Vb)):
+        x.tofile(os.path.join(d, name + ".bin"))
+    with open(os.path.join(d, "meta.txt"), "w") as f:
+        f.write(" ".join(str(x) for x in [B, H, Hq, bits, g, ppm, n, rank, 1, 20, 2, n_buf, 20, 3]) + "\n")
+    r = subprocess.run([emulator, d], capture_output=True, text=True, timeout=900,
+                       env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0"))
+    assert r.returncode == 0, r.stderr[-4000:]
+    assert "AddressSanitizer" not in r.stderr
+    out = np.fromfile(os.path.join(d, "out.bin"), np.float16).reshape(B, Hq, 1, 128).astype(np.float64)
+    ref = oc.decode_attn(q, Kb, Vb, n_buf).astype(np.float64)
+    tol = np.maximum(2e-3, np.spacing(np.maximum(np.abs(ref), np.abs(out)).astype(np.float16)).astype(np.float64))
+    assert (np.abs(out - ref) <= tol).all(), float(np.abs(out - ref).max())
+    Ko, Vo = oc.decompress()
+    Kg = np.fromfile(os.path.join(d, "Khat.bin"), np.float16).reshape(Ko.shape).astype(np.float64)
+    Vg = np.fromfile(os.path.join(d, "Vhat.bin"), np.float16).reshape(Vo.shape).astype(np.float64)
+    for got, want in ((Kg, Ko.astype(np.float64)), (Vg, Vo.astype(np.float64))):
+        assert np.linalg.norm(got - want) <= 1e-3 * np.linalg.norm(want)
