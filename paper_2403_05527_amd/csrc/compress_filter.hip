@@ -27,38 +27,75 @@ struct RegSource {  // the vector lives in the wave's registers
 };
 
 // ------------------------------------------------------------------ K select
-// grid (128/CB, B*H); block 256.  LDS: [CB][n_pad] fp16 + 4*512 u32.
+// 1-D grid of (128/CB) * B*H blocks of 256 threads; LDS: [CB][n_pad] keys + 4*512 u32.
+// Consecutive block ids go round-robin to the chip's 8 XCDs (each with its own L2), so
+// the id is decoded with the column block fastest INSIDE one XCD: the 128/CB blocks
+// that share the 128-byte lines of one slab then meet in one L2 instead of eight.
 __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restrict__ K, int n, int n_pad,
-                                                       int CB, int k_top, int k_bot,
+                                                       int CB, int nslab, int k_top, int k_bot,
                                                        Thresh* __restrict__ thrK) {
   GEAR_DYN_LDS(smem_raw);
   uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem_raw);
   uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + 4 * 512 * sizeof(uint32_t));
-  const int slab = blockIdx.y, cb = blockIdx.x;
+  const int ncb = D / CB;
+  int slab, cb;
+  if ((nslab & 7) == 0) {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    cb = j % ncb;
+    slab = (j / ncb) * 8 + xcd;
+  } else {
+    cb = blockIdx.x % ncb;
+    slab = blockIdx.x / ncb;
+  }
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const uint16_t* X = K + (size_t)slab * n * D + cb * CB;
 
-  // transpose-load the [n x CB] column block so every vector is contiguous
+  // transpose-load the [n x CB] column block so every vector is contiguous; a
+  // thread has UNR row segments in flight at a time
   const int VW = CB < 8 ? CB : 8;
   const int U = CB / VW;
-  for (int idx = tid; idx < n * U; idx += 256) {
-    const int row = idx / U, u = idx - row * U;
-    const uint16_t* p = X + (size_t)row * D + u * VW;
-    uint16_t v[8];
-    if (VW == 8) {
-      const uint4 q = *reinterpret_cast<const uint4*>(p);
-      v[0] = q.x & 0xFFFF; v[1] = q.x >> 16; v[2] = q.y & 0xFFFF; v[3] = q.y >> 16;
-      v[4] = q.z & 0xFFFF; v[5] = q.z >> 16; v[6] = q.w & 0xFFFF; v[7] = q.w >> 16;
-    } else if (VW == 4) {
-      const uint2 q = *reinterpret_cast<const uint2*>(p);
-      v[0] = q.x & 0xFFFF; v[1] = q.x >> 16; v[2] = q.y & 0xFFFF; v[3] = q.y >> 16;
-    } else if (VW == 2) {
-      const uint32_t q = *reinterpret_cast<const uint32_t*>(p);
-      v[0] = q & 0xFFFF; v[1] = q >> 16;
-    } else {
-      v[0] = *p;
+  if (VW == 8) {
+    constexpr int UNR = 8;
+    const int total = n * U;
+    for (int base = 0; base < total; base += 256 * UNR) {
+      uint4 q[UNR];
+#pragma unroll
+      for (int k = 0; k < UNR; ++k) {
+        const int idx = base + k * 256 + tid;
+        q[k] = make_uint4(0, 0, 0, 0);
+        if (idx < total) {
+          const int row = idx / U, u = idx - row * U;
+          q[k] = *reinterpret_cast<const uint4*>(X + (size_t)row * D + u * 8);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < UNR; ++k) {
+        const int idx = base + k * 256 + tid;
+        if (idx < total) {
+          const int row = idx / U, u = idx - row * U;
+          const uint32_t w[4] = {key16x2(q[k].x), key16x2(q[k].y), key16x2(q[k].z), key16x2(q[k].w)};
+          uint16_t* dst = tile + (size_t)(u * 8) * n_pad + row;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dst[(size_t)e * n_pad] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));   // keys, not values
+        }
+      }
     }
-    for (int e = 0; e < VW; ++e) tile[(size_t)(u * VW + e) * n_pad + row] = (uint16_t)key16(v[e]);   // keys, not values
+  } else {
+    for (int idx = tid; idx < n * U; idx += 256) {
+      const int row = idx / U, u = idx - row * U;
+      const uint16_t* p = X + (size_t)row * D + u * VW;
+      uint16_t v[4];
+      if (VW == 4) {
+        const uint2 q = *reinterpret_cast<const uint2*>(p);
+        v[0] = q.x & 0xFFFF; v[1] = q.x >> 16; v[2] = q.y & 0xFFFF; v[3] = q.y >> 16;
+      } else if (VW == 2) {
+        const uint32_t q = *reinterpret_cast<const uint32_t*>(p);
+        v[0] = q & 0xFFFF; v[1] = q >> 16;
+      } else {
+        v[0] = *p;
+      }
+      for (int e = 0; e < VW; ++e) tile[(size_t)(u * VW + e) * n_pad + row] = (uint16_t)key16(v[e]);   // keys, not values
+    }
   }
   // zero the padding so stray lanes read defined data
   for (int idx = tid; idx < CB * (n_pad - n); idx += 256) {
@@ -103,14 +140,12 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
   const int ngw = WT / g;  // groups per block (1 or 2)
 
   // thresholds of my 8 channels (staged through LDS: one coalesced read per block)
-  __shared__ Thresh thr_s[D];
-  if (dm.ppm > 0) {
-    if (tid < D) thr_s[tid] = thrK[(size_t)slab * D + tid];
-    __syncthreads();
-  }
-  Thresh th[8];
+  __shared__ ThreshPair thr_s[D];
+  if (tid < D) thr_s[tid] = pack_thresh(dm.ppm > 0 ? thrK[(size_t)slab * D + tid] : thresh_none());
+  __syncthreads();
+  ThreshPair th[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) th[e] = dm.ppm > 0 ? thr_s[oc * 8 + e] : thresh_none();
+  for (int e = 0; e < 8; ++e) th[e] = thr_s[oc * 8 + e];
 
   float y[NK][8];
   uint32_t raw[NK][4];
@@ -125,7 +160,7 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-      const bool out = (t < n) && is_outlier(key16(hb), t, th[e]);
+      const bool out = (t < n) && is_outlier(key16(hb), (uint32_t)t, th[e]);
       if (out) flags[k] |= 1u << e;
       y[k][e] = out ? 0.0f : h2f(hb);
     }
@@ -261,8 +296,8 @@ hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, 
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  dim3 grid(D / cb, dm.B * dm.H);
-  hipLaunchKernelGGL(k_select_kernel, grid, dim3(256), lds, st, K, n, n_pad, cb, k_top, k_bot, thrK);
+  dim3 grid((D / cb) * dm.B * dm.H);
+  hipLaunchKernelGGL(k_select_kernel, grid, dim3(256), lds, st, K, n, n_pad, cb, dm.B * dm.H, k_top, k_bot, thrK);
   return hipGetLastError();
 }
 

@@ -76,11 +76,12 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
     const int tl = r0 + 16 * k, t = t0 + tl;
     const bool tv = t < n;
     uint4 xv = make_uint4(0, 0, 0, 0);
-    Thresh th = thresh_none();
+    Thresh thf = thresh_none();
     if (tv) {
       xv = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
-      if (dm.ppm > 0) th = thrV[(size_t)b * n + t];
+      if (dm.ppm > 0) thf = thrV[(size_t)b * n + t];
     }
+    const ThreshPair th = pack_thresh(thf);
     const uint32_t w[4] = {xv.x, xv.y, xv.z, xv.w};
     float y[8];
     float lmn = INFINITY, lmx = -INFINITY;
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
     for (int e = 0; e < 8; ++e) {
       const uint32_t hb = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
       const int c = oc * 8 + e;
-      const bool out = tv && is_outlier(key16(hb), h * D + c, th);
+      const bool out = tv && is_outlier(key16(hb), (uint32_t)(h * D + c), th);
       if (out) atomicOr(&colmask[c][tl >> 5], 1u << (tl & 31));
       y[e] = out ? 0.0f : h2f(hb);
       lmn = fminf(lmn, y[e]);

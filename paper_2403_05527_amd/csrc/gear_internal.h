@@ -104,9 +104,30 @@ __device__ __forceinline__ uint32_t key16x2(uint32_t h2) {
   const uint32_t khi = (hi & 0x8000u) ? ((0u - hi) & 0xFFFFu) : (hi | 0x8000u);
   return klo | (khi << 16);
 }
-__device__ __forceinline__ bool is_outlier(uint32_t key, int idx, const Thresh& th) {
-  return key > th.tau_top || (key == th.tau_top && idx <= th.i_top) || key < th.tau_bot ||
-         (key == th.tau_bot && idx > th.l_bot && idx <= th.i_bot);
+// The predicate of Thresh as two 32-bit compares.  With cT = key << 16 | (0xFFFF - idx)
+// (larger key first, then smaller index) and cB = key << 16 | idx, an entry is an
+// outlier iff cT >= top || cB < bot.  The l_bot bound needs no term of its own: it
+// is set only where top and bottom share one threshold value, and there the entries
+// it excludes (idx <= l_bot = i_top) are top outliers anyway.  Needs idx <= 0xFFFF
+// and finite inputs (keys <= 0xFC00), which the entry points guarantee.
+struct ThreshPair {
+  uint32_t top, bot;
+};
+__device__ __forceinline__ ThreshPair pack_thresh(const Thresh& th) {
+  ThreshPair p;
+  if (th.tau_top > 0xFFFFu) {
+    p.top = 0xFFFFFFFFu;                                   // no top outliers
+  } else {
+    const uint32_t lo = th.i_top < 0 ? 0x10000u : (th.i_top > 0xFFFF ? 0u : 0xFFFFu - (uint32_t)th.i_top);
+    p.top = (th.tau_top << 16) + lo;
+  }
+  const uint32_t lob = th.i_bot < 0 ? 0u : (th.i_bot >= 0xFFFF ? 0x10000u : (uint32_t)th.i_bot + 1u);
+  p.bot = (th.tau_bot << 16) + lob;
+  return p;
+}
+__device__ __forceinline__ bool is_outlier(uint32_t key, uint32_t idx, const ThreshPair& p) {
+  const uint32_t k = key << 16;
+  return (k | (0xFFFFu - idx)) >= p.top || (k | idx) < p.bot;
 }
 __device__ __forceinline__ Thresh thresh_none() {
   Thresh th;
