@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
     const int c = idx / (n_pad - n), r = idx - c * (n_pad - n);
     tile[(size_t)c * n_pad + n + r] = 0;
   }
-  __syncthreads();
+  block_lds_sync();
 
   const int iters = (CB + 3) >> 2;
   for (int it = 0; it < iters; ++it) {
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
   // thresholds of my 8 channels (staged through LDS: one coalesced read per block)
   __shared__ ThreshPair thr_s[D];
   if (tid < D) thr_s[tid] = pack_thresh(dm.ppm > 0 ? thrK[(size_t)slab * D + tid] : thresh_none());
-  __syncthreads();
+  block_lds_sync();
   ThreshPair th[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) th[e] = thr_s[oc * 8 + e];
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
 #pragma unroll
       for (int e = 0; e < 8; ++e) { red_mn[wave][oc * 8 + e] = lmn[e]; red_mx[wave][oc * 8 + e] = lmx[e]; }
     }
-    __syncthreads();
+    block_lds_sync();
     if (tid < D && t0 + gi * g < n) {
       const float mn = fminf(fminf(red_mn[0][tid], red_mn[1][tid]), fminf(red_mn[2][tid], red_mn[3][tid]));
       const float mx = fmaxf(fmaxf(red_mx[0][tid], red_mx[1][tid]), fmaxf(red_mx[2][tid], red_mx[3][tid]));
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
       const int grp = (t0 + gi * g) / g;
       sv.sz[((size_t)slab * sv.ng_cap + grp) * D + tid] = group_bits(q);
     }
-    __syncthreads();
+    block_lds_sync();
   }
 
   // codes, packed token-major
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
       inc[k] = wave_incl_scan(cnt[k]);
       if (lane == 63) band_cnt[k][wave] = inc[k];
     }
-    __syncthreads();
+    block_lds_sync();
     if (tid < WT / TILE) {
       uint32_t tot = 0;
       for (int k = tid * 4; k < tid * 4 + 4; ++k)
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
       }
       tile_off[tid] = off;
     }
-    __syncthreads();
+    block_lds_sync();
     uint32_t* pool = sv.sp_pool + (size_t)slab * sv.pool_cap;
 #pragma unroll
     for (int k = 0; k < NK; ++k) {

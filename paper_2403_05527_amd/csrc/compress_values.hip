@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
   const uint16_t* X = V + (size_t)slab * n * D;
 
   if (tid < D) { colmask[tid][0] = 0u; colmask[tid][1] = 0u; }
-  __syncthreads();
+  block_lds_sync();
 
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
       }
     }
   }
-  __syncthreads();
+  block_lds_sync();
 
   // code words in operand order: block of 4*tpw tokens, word (kg*16 + c%16)*8 + c/16 holds
   // channel c for tokens tpw*kg + i at bits i*b
@@ -162,14 +162,14 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
       inc = wave_incl_scan(cnt);
       if (lane == 63) wtot[wave] = inc;
     }
-    __syncthreads();
+    block_lds_sync();
     if (tid == 0) {
       const uint32_t tot = wtot[0] + wtot[1];
       const uint32_t off = atomicAdd(&pool_ctr[b], tot);
       sv.sp_table[(size_t)slab * sv.ntile_cap + tile] = make_uint2(off, tot);
       list_off = off;
     }
-    __syncthreads();
+    block_lds_sync();
     if (tid < D) {
       uint32_t off = list_off + (wave == 1 ? wtot[0] : 0u) + inc - cnt;
       uint32_t* pool = sv.sp_pool + (size_t)b * sv.pool_cap;

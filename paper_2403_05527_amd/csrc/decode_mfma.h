@@ -118,9 +118,8 @@ constexpr int WTOK = 128;  // tokens per wave
 struct MfmaLayout {
   int q, bfk, bfv, misc;                       // shared by the four waves
   int wave0, wave_stride;                      // per-wave region
-  int sc, szk, szv, ak, av, spk, spv, osp, opnd;  // offsets inside a wave region
+  int sc, szk, szv, ak, av, osp, opnd, qb;  // offsets inside a wave region
   int total;
-  int spcap;       // staged outlier entries per wave and tensor
 };
 template <int GQ>
 struct MfmaMisc {
@@ -145,19 +144,11 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int r
   L.szv = w; w += WTOK * NG * 4;
   L.ak = w; w += up16i(WTOK * rk * 2);
   L.av = w; w += up16i(WTOK * rv * 2);
-  int cap = 0;
-  if (ppm > 0) {
-    const long long expect = ((long long)WTOK * D * ppm + 999999) / 1000000;
-    cap = (int)((expect * 12 / 10 + 32 + 31) / 32 * 32);
-    if (cap > 1024) cap = 1024;
-  }
-  L.spcap = cap;
-  L.spk = w; w += cap * 4;
-  L.spv = w; w += cap * 4;
   L.osp = w; w += GQ * D * 4;
   int oh = 2 * GQ * D;
   if (NG * 2 * GQ * TB > oh) oh = NG * 2 * GQ * TB;
   L.opnd = w; w += oh * 2;
+  L.qb = w; w += GQ * 8 * 4;
   L.wave_stride = up16i(w);
   L.total = L.wave0 + 4 * L.wave_stride;
   return L;
@@ -208,10 +199,9 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   uint32_t* Sszv = reinterpret_cast<uint32_t*>(wbase + L.szv);      // [128][NG]
   uint16_t* Sak = reinterpret_cast<uint16_t*>(wbase + L.ak);        // [128][rk]
   uint16_t* Sav = reinterpret_cast<uint16_t*>(wbase + L.av);
-  uint32_t* Sspk = reinterpret_cast<uint32_t*>(wbase + L.spk);      // (row*128 + c) | val << 16, row in the wave
-  uint32_t* Sspv = reinterpret_cast<uint32_t*>(wbase + L.spv);
   float* Sosp = reinterpret_cast<float*>(wbase + L.osp);            // [GQ][128] this wave's output plane
   _Float16* opnd = reinterpret_cast<_Float16*>(wbase + L.opnd);
+  float* SqB = reinterpret_cast<float*>(wbase + L.qb);              // [GQ][8] q^T B_K
   const float scale = 0.08838834764831845f;  // 1/sqrt(128)
   const int tw0 = t_begin + WTOK * wave;      // first token owned by this wave
   int nw = t_end - tw0;                       // tokens this wave owns (may be <= 0)
@@ -270,30 +260,47 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const uint32_t cv0 = __shfl(tab.y, 2, 64), cv1 = __shfl(tab.y, 3, 64);
   const uint32_t ok0 = __shfl(tab.x, 0, 64), ok1 = __shfl(tab.x, 1, 64);
   const uint32_t ov0 = __shfl(tab.x, 2, 64), ov1 = __shfl(tab.x, 3, 64);
-  const bool sp_fits = (ck0 + ck1 <= (uint32_t)L.spcap) && (cv0 + cv1 <= (uint32_t)L.spcap);  // wave-uniform
   const uint32_t* poolk = ks.sp_pool + (size_t)slab * ks.pool_cap;
   const uint32_t* poolv = vs.sp_pool + (size_t)b * vs.pool_cap;
-  if (dm.ppm > 0 && sp_fits) {
-    for (uint32_t e = lane; e < ck0 + ck1; e += 64) {
+  // the first SPR * 64 entries of each list travel in registers: entry lane + 64 i,
+  // as (row in the wave) * 128 + c | value << 16; 0 (adds +0 to row 0) where there is none
+  constexpr int SPR = 6;
+  uint32_t spk_r[SPR], spv_r[SPR];
+#pragma unroll
+  for (int i = 0; i < SPR; ++i) {
+    const uint32_t e = lane + 64 * i;
+    spk_r[i] = 0u;
+    spv_r[i] = 0u;
+    if (e < ck0 + ck1) {
       const bool second = e >= ck0;
       const uint32_t en = second ? poolk[ok1 + (e - ck0)] : poolk[ok0 + e];
-      Sspk[e] = ((en & 0xFFFFu) + (second ? TILE * D : 0)) | (en & 0xFFFF0000u);
+      spk_r[i] = en + (second ? TILE * D : 0);
     }
-    for (uint32_t e = lane; e < cv0 + cv1; e += 64) {
+    if (e < cv0 + cv1) {
       const bool second = e >= cv0;
       const uint32_t en = second ? poolv[ov1 + (e - cv0)] : poolv[ov0 + e];
-      Sspv[e] = ((en & 0xFFFFu) + (second ? TILE * D : 0)) | (en & 0xFFFF0000u);
+      spv_r[i] = en + (second ? TILE * D : 0);
     }
   }
   for (int i = lane; i < GQ * D; i += 64) Sosp[i] = 0.0f;
-  __syncthreads();   // q and the B factors are visible to all waves; from here on waves run independently
+  block_lds_sync();   // q and the B factors are visible to all waves; from here on waves run independently
 
-  // q^T B_K (down-projection of the low-rank Key term): lane (hq, r) -> registers of every lane via shuffles
-  float qB_l = 0.0f;
-  if (rk > 0 && lane < GQ * 8) {
-    const int hq = lane >> 3, r = lane & 7;
+  // q^T B_K (down-projection of the low-rank Key term).  The GQ * rkp outputs (rkp = rank
+  // rounded up to a power of two) are spread over the 64 lanes, P lanes per output, each
+  // summing 128 / P channels; a butterfly over the P lanes finishes the sums.
+  if (rk > 0) {
+    const int rkp = rk <= 1 ? 1 : rk <= 2 ? 2 : rk <= 4 ? 4 : 8;
+    for (int i = lane; i < GQ * 8; i += 64) SqB[i] = 0.0f;   // slots r >= rk stay 0
+    wave_lds_sync();
+    const int P = 64 / (GQ * rkp);
+    const int outi = lane / P, part = lane - outi * P;
+    const int hq = outi / rkp, r = outi - hq * rkp;
+    float s = 0.0f;
     if (r < rk)
-      for (int c = 0; c < D; ++c) qB_l += Sq[hq * D + c] * h2f(Sbfk[c * rk + r]);
+      for (int c = part; c < D; c += P) s += Sq[hq * D + c] * h2f(Sbfk[c * rk + r]);
+    for (int o = 1; o < P; o <<= 1) s += __shfl_xor(s, o, 64);
+    if (part == 0) SqB[hq * 8 + r] = s;
+    wave_lds_sync();
   }
 
   // =================== Key scores on the matrix cores ===================
@@ -384,7 +391,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
 
   // low-rank Key term: lane handles rows lane and lane + 64
   if (rk > 0) {
-#pragma unroll
+#pragma unroll 1
     for (int rep = 0; rep < 2; ++rep) {
       const int row = lane + 64 * rep;
       float a[8];
@@ -392,60 +399,34 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       for (int r = 0; r < 8; ++r) a[r] = (r < rk && row < nw) ? h2f(Sak[row * rk + r]) : 0.0f;
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
+        const float4 b0 = *reinterpret_cast<const float4*>(&SqB[hq * 8]);       // entries r >= rk are unused (a = 0)
+        const float4 b1 = *reinterpret_cast<const float4*>(&SqB[hq * 8 + 4]);
         float s = Ssc[hq * WTOK + row];
-#pragma unroll
-        for (int r = 0; r < 8; ++r) s += __shfl(qB_l, hq * 8 + r, 64) * a[r];
+        s += b0.x * a[0] + b0.y * a[1] + b0.z * a[2] + b0.w * a[3];
+        if (rk > 4) s += b1.x * a[4] + b1.y * a[5] + b1.z * a[6] + b1.w * a[7];
         Ssc[hq * WTOK + row] = s;
       }
     }
     wave_lds_sync();
   }
 
-  // sparse Key term.  Staged list is ordered (row, c): the first entry of a row sums the row's run.
+  // sparse Key term: every entry adds q[c] * value to its row's score.  LDS float
+  // adds from one wave are applied in program order (and in a fixed lane order inside
+  // one instruction), so the result does not vary from run to run.
   if (dm.ppm > 0) {
-    if (sp_fits) {
-      const uint32_t cnt = ck0 + ck1;
-      for (uint32_t e = lane; e < cnt; e += 64) {
-        const uint32_t me = Sspk[e];
-        const uint32_t row = (me & 0xFFFFu) >> 7;
-        if (e > 0 && ((Sspk[e - 1] & 0xFFFFu) >> 7) == row) continue;
-        float a2[GQ];
+    auto add_k = [&](uint32_t en) {
+      const int row = (en & 0xFFFFu) >> 7, c = en & 127u;
+      const float v = h2f(en >> 16);
 #pragma unroll
-        for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
-        for (uint32_t f = e; f < cnt; ++f) {
-          const uint32_t en = Sspk[f];
-          if (((en & 0xFFFFu) >> 7) != row) break;
-          const float v = h2f(en >> 16);
-          const int c = en & 127u;
+      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Ssc[hq * WTOK + row], Sq[hq * D + c] * v);
+    };
 #pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) a2[hq] += Sq[hq * D + c] * v;
-        }
-#pragma unroll
-        for (int hq = 0; hq < GQ; ++hq) Ssc[hq * WTOK + row] += a2[hq];
-      }
-    } else {  // lists larger than the staging area: read them from global memory
-      for (int ti = 0; ti < 2; ++ti) {
-        const uint32_t off = ti ? ok1 : ok0, cnt = ti ? ck1 : ck0;
-        const uint32_t* lst = poolk + off;
-        for (uint32_t e = lane; e < cnt; e += 64) {
-          const uint32_t me = lst[e];
-          const uint32_t tl = (me & 0xFFFFu) >> 7;
-          if (e > 0 && ((lst[e - 1] & 0xFFFFu) >> 7) == tl) continue;
-          float a2[GQ];
-#pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
-          for (uint32_t f = e; f < cnt; ++f) {
-            const uint32_t en = lst[f];
-            if (((en & 0xFFFFu) >> 7) != tl) break;
-            const float v = h2f(en >> 16);
-            const int c = en & 127u;
-#pragma unroll
-            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Sq[hq * D + c] * v;
-          }
-#pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) Ssc[hq * WTOK + ti * TILE + tl] += a2[hq];
-        }
-      }
+    for (int i = 0; i < SPR; ++i)
+      if ((uint32_t)(lane + 64 * i) < ck0 + ck1) add_k(spk_r[i]);
+    for (uint32_t e = SPR * 64 + lane; e < ck0 + ck1; e += 64) {   // longer lists: the rest from global memory
+      const bool second = e >= ck0;
+      const uint32_t en = second ? poolk[ok1 + (e - ck0)] : poolk[ok0 + e];
+      add_k(en + (second ? TILE * D : 0));
     }
     wave_lds_sync();
   }
@@ -613,58 +594,25 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   }
   wave_lds_sync();
 
-  // sparse Value term.  Each tile's list is ordered (c, row): the first entry of a channel
-  // sums the channel's run; the wave walks its two tiles one after the other, so
-  // no two lanes ever update one address at the same time and the summation
-  // order is fixed.
+  // sparse Value term: every entry adds p[row] * value to its channel of this wave's plane
   if (dm.ppm > 0) {
-    for (int ti = 0; ti < 2; ++ti) {
-      if (sp_fits) {
-        const uint32_t e0 = ti ? cv0 : 0u, e1 = ti ? cv0 + cv1 : cv0;
-        for (uint32_t e = e0 + lane; e < e1; e += 64) {
-          const uint32_t me = Sspv[e];
-          const uint32_t ch = me & 127u;
-          if (e > e0 && (Sspv[e - 1] & 127u) == ch) continue;
-          float a2[GQ];
+    auto add_v = [&](uint32_t en) {
+      const int row = (en & 0xFFFFu) >> 7, c = en & 127u;
+      const float v = h2f(en >> 16);
 #pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
-          for (uint32_t f = e; f < e1; ++f) {
-            const uint32_t en = Sspv[f];
-            if ((en & 127u) != ch) break;
-            const float v = h2f(en >> 16);
-            const int row = (en & 0xFFFFu) >> 7;
+      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Sosp[hq * D + c], Ssc[hq * WTOK + row] * v);
+    };
 #pragma unroll
-            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * WTOK + row] * v;
-          }
-#pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) Sosp[hq * D + ch] += a2[hq];
-        }
-      } else {
-        const uint32_t off = ti ? ov1 : ov0, cnt = ti ? cv1 : cv0;
-        const uint32_t* lst = poolv + off;
-        for (uint32_t e = lane; e < cnt; e += 64) {
-          const uint32_t me = lst[e];
-          const uint32_t ch = me & 127u;
-          if (e > 0 && (lst[e - 1] & 127u) == ch) continue;
-          float a2[GQ];
-#pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
-          for (uint32_t f = e; f < cnt; ++f) {
-            const uint32_t en = lst[f];
-            if ((en & 127u) != ch) break;
-            const float v = h2f(en >> 16);
-            const int row = ti * TILE + (int)((en & 0xFFFFu) >> 7);
-#pragma unroll
-            for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * WTOK + row] * v;
-          }
-#pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) Sosp[hq * D + ch] += a2[hq];
-        }
-      }
-      wave_lds_sync();
+    for (int i = 0; i < SPR; ++i)
+      if ((uint32_t)(lane + 64 * i) < cv0 + cv1) add_v(spv_r[i]);
+    for (uint32_t e = SPR * 64 + lane; e < cv0 + cv1; e += 64) {
+      const bool second = e >= cv0;
+      const uint32_t en = second ? poolv[ov1 + (e - cv0)] : poolv[ov0 + e];
+      add_v(en + (second ? TILE * D : 0));
     }
+    wave_lds_sync();
   }
-  __syncthreads();
+  block_lds_sync();
 
   // =================== merge the four waves' states, write the record ===================
   for (int i = tid; i < GQ * D; i += 256) {

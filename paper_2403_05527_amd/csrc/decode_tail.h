@@ -60,7 +60,7 @@ __device__ __forceinline__ void tail_softmax_merge(TailSmem<GQ>& S, int n_rows) 
     const float mx = wave_max(s[hq]);
     if (lane == 0) S.red[hq][wave] = mx;
   }
-  __syncthreads();
+  block_lds_sync();
   if (tid < GQ) {
     const float m_loc = fmaxf(fmaxf(S.red[tid][0], S.red[tid][1]), fmaxf(S.red[tid][2], S.red[tid][3]));
     const float m_old = S.m_run[tid];
@@ -68,7 +68,7 @@ __device__ __forceinline__ void tail_softmax_merge(TailSmem<GQ>& S, int n_rows) 
     S.bc[tid][0] = m_new;
     S.bc[tid][1] = (m_old == -INFINITY) ? 0.0f : __expf(m_old - m_new);
   }
-  __syncthreads();
+  block_lds_sync();
 #pragma unroll
   for (int hq = 0; hq < GQ; ++hq) {
     const float p = tid < n_rows ? __expf(s[hq] - S.bc[hq][0]) : 0.0f;
@@ -77,12 +77,12 @@ __device__ __forceinline__ void tail_softmax_merge(TailSmem<GQ>& S, int n_rows) 
     if (lane == 0) S.red[hq][wave] = sum;
   }
   for (int i = tid; i < GQ * D; i += 256) S.o_run[i / D][i % D] *= S.bc[i / D][1];
-  __syncthreads();
+  block_lds_sync();
   if (tid < GQ) {
     S.l_run[tid] = S.l_run[tid] * S.bc[tid][1] + (S.red[tid][0] + S.red[tid][1] + S.red[tid][2] + S.red[tid][3]);
     S.m_run[tid] = S.bc[tid][0];
   }
-  __syncthreads();
+  block_lds_sync();
 }
 
 template <int GQ>
@@ -104,7 +104,7 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
   int j_next = 0, buf_done = 0;
   // block-uniform loop; every pass consumes at least one chunk or one buffer row
   for (int pass = 0; pass < 2 * GEAR_MAX_CHUNKS && (j_next < cs.n_chunks || buf_done < n_buf); ++pass) {
-    __syncthreads();
+    block_lds_sync();
     // ---- plan the pass (every thread computes the same plan)
     int npc = 0, nrows = 0;
     while (j_next + npc < cs.n_chunks && npc < TAIL_CHUNKS && nrows + cs.n[j_next + npc] <= TAIL_ROWS) {
@@ -124,7 +124,7 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
       S.row0[npc] = run;
     }
     for (int i = tid; i < 4 * GQ * D; i += 256) (&S.osp[0][0][0])[i] = 0.0f;
-    __syncthreads();
+    block_lds_sync();
     // ---- row map, per-chunk tables, q^T B_K, Value (scale, zero) of every row
     for (int jc = tid; jc < npc; jc += 256) {
       const int n_j = cs.n[jbase + jc], r0 = S.row0[jc];
@@ -155,7 +155,7 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
       }
       S.qB[jc][hq][r] = s;
     }
-    __syncthreads();
+    block_lds_sync();
     if (tid < nrows) {
       const int jc = S.row_chunk[tid], t = S.row_tok[tid], j = jbase + jc;
       const SegView vv = chunk_view(cs.v0, cs.stride, j, cs.n[j], cs.rank[j]);
@@ -210,7 +210,7 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) S.sc[hq][tid] = s[hq];
     }
-    __syncthreads();
+    block_lds_sync();
     // ---- sparse Key term: wave w takes chunks w, w+4, ...; lists ordered (t, c)
     if (dm.ppm > 0) {
       for (int jc = wave; jc < npc; jc += 4) {
@@ -240,7 +240,7 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
           }
         }
       }
-      __syncthreads();
+      block_lds_sync();
     }
 
     tail_softmax_merge<GQ>(S, ntot);
@@ -318,7 +318,7 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
         }
       }
     }
-    __syncthreads();
+    block_lds_sync();
     for (int i = tid; i < GQ * D; i += 256) {
       const int hq = i / D, c = i % D;
       float o = S.o_half[0][hq][c] + S.o_half[1][hq][c];
@@ -336,7 +336,7 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
     j_next += npc;
     buf_done += nbuf_rows;
   }
-  __syncthreads();
+  block_lds_sync();
   for (int i = tid; i < GQ * D; i += 256) {
     const int hq = i / D, c = i % D;
     float* rec = rec_base + (size_t)hq * rec_stride;

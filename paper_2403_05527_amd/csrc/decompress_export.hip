@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void decompress_kernel(Dims dm, SegView sv, in
     const int c = i >> 3, r = i & 7;
     Bs[c][r] = r < sv.rank ? h2f(sv.Bf[((size_t)slab * D + c) * sv.rank + r]) : 0.0f;
   }
-  __syncthreads();
+  block_lds_sync();
   if (dm.ppm > 0) {
     const uint2 oc = sv.sp_table[(size_t)slab * sv.ntile_cap + tile];
     const uint32_t* lst = sv.sp_pool + (size_t)(is_k ? slab : b) * sv.pool_cap + oc.x;
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void decompress_kernel(Dims dm, SegView sv, in
       sp[(en & 0xFFFFu) >> 7][en & 127u] = h2f(en >> 16);
     }
   }
-  __syncthreads();
+  block_lds_sync();
   for (int i = tid; i < TILE * D; i += 256) {
     const int tl = i / D, c = i % D, t = tile * TILE + tl;
     if (t >= sv.n) break;

@@ -19,6 +19,20 @@
 #define GEAR_PIN_VGPR(x) asm volatile("" : "+v"(x))
 #endif
 
+// Block barrier that orders LDS traffic only.  __syncthreads() also drains every
+// outstanding global load and store of the wave (loads and stores share one
+// counter on this chip), which would serialise prefetched loads with the barrier;
+// none of the kernels exchanges data between threads of a block through global
+// memory, so LDS ordering is all they need.
+#ifndef GEAR_LDS_BARRIER
+#define GEAR_LDS_BARRIER()                                              \
+  do {                                                                  \
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");     \
+    __builtin_amdgcn_s_barrier();                                       \
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");     \
+  } while (0)
+#endif
+
 namespace gear {
 
 constexpr int D = 128;      // head dimension
@@ -191,6 +205,8 @@ __device__ __forceinline__ uint32_t quant_code_resid(float y, const GroupQ& q, f
 __device__ __forceinline__ float resid_to_float(uint32_t hi16, uint32_t lo8) {  // u, not yet times delta
   return (float)((int)(short)(hi16 & 0xFFFFu) * 256 + (int)(lo8 & 0xFFu)) * (1.0f / RESID_FIX);
 }
+
+__device__ __forceinline__ void block_lds_sync() { GEAR_LDS_BARRIER(); }
 
 // ---------------------------------------------------------------------------
 // wavefront (64 lanes) primitives

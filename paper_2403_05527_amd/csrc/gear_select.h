@@ -143,14 +143,14 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
 
   // ---- level 1: histogram of the high key byte
   for (int i = lane; i < 512; i += 64) hist[i] = 0u;
-  __syncthreads();
+  block_lds_sync();
   for_each_chunk(src, nch, [&](int ch, const uint4& v) {
     const int base = ch * 512 + lane * 8;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (base + e < N) atomicAdd(&hist[slot16(v, e) >> 8], 1u);
   });
-  __syncthreads();
+  block_lds_sync();
   int bin_t = -1, bin_b = -1;
   uint32_t need_t = 0, need_b = 0;
   if (active && k_top > 0) {
@@ -163,11 +163,11 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
     scan_from_bottom(hist, (uint32_t)k_bot, bin_b, below);
     need_b = (uint32_t)k_bot - below;
   }
-  __syncthreads();
+  block_lds_sync();
 
   // ---- level 2: histograms of the low key byte inside the two boundary bins
   for (int i = lane; i < 512; i += 64) hist[i] = 0u;
-  __syncthreads();
+  block_lds_sync();
   for_each_chunk(src, nch, [&](int ch, const uint4& v) {
     const int base = ch * 512 + lane * 8;
 #pragma unroll
@@ -178,7 +178,7 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
         if ((int)(k >> 8) == bin_b) atomicAdd(&hist[256 + (k & 255u)], 1u);
       }
   });
-  __syncthreads();
+  block_lds_sync();
   uint32_t need_eq_t = 0, cnt_eq_t = 0, need_eq_b = 0, cnt_eq_b = 0;
   if (active && k_top > 0) {
     int lo;
@@ -196,7 +196,7 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
     need_eq_b = need_b - below;
     cnt_eq_b = hist[256 + lo];
   }
-  __syncthreads();
+  block_lds_sync();
 
   // ---- ties: among entries equal to the threshold the lowest indices win;
   // when top and bottom share one threshold value the bottom set continues

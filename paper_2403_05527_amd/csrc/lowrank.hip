@@ -22,9 +22,9 @@ constexpr int PT = 256;  // tokens per sweep block
 template <typename T>
 __device__ __forceinline__ T block128_sum(T v, T* red /* >= 2 */) {
   v = wave_sum_shfl(v);
-  __syncthreads();
+  block_lds_sync();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
+  block_lds_sync();
   return red[0] + red[1];
 }
 
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
       for (int i = 0; i < npart; ++i) s += (double)p[(size_t)i * (D * R + R * R) + c];
       G[c / R][c % R] = s;
     }
-    __syncthreads();
+    block_lds_sync();
     if (c == 0) {
       // Gram-Schmidt in coefficient space: column j of orth(A) is A * C[:, j].
       bool valid[R];
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
         for (int a = 0; a < R; ++a) C[a][j] = valid[j] ? cj[a] : 0.0;
       }
     }
-    __syncthreads();
+    block_lds_sync();
     double o[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void pi_sweep_kernel(const uint16_t* __restric
       for (int r = 0; r < R; ++r) redg[wave][oc * R + r] = gacc[r];
     }
   }
-  __syncthreads();
+  block_lds_sync();
   float* out = partial + ((size_t)slab * npart + pt) * (D * R + R * R);
   for (int i = tid; i < D * R; i += 256) out[i] = red[0][i] + red[1][i] + red[2][i] + red[3][i];
   if (tid < R * R) out[D * R + tid] = last ? (redg[0][tid] + redg[1][tid] + redg[2][tid] + redg[3][tid]) : 0.0f;
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) void pi_finish_kernel(const float* __restrict_
   __shared__ float C[R * R];
   const int slab = blockIdx.y;
   if (threadIdx.x < R * R) C[threadIdx.x] = cmat[(size_t)slab * R * R + threadIdx.x];
-  __syncthreads();
+  block_lds_sync();
   const int t = blockIdx.x * 256 + threadIdx.x;
   if (t >= n) return;
   float a[R];

@@ -42,6 +42,7 @@ inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess
 inline const char* hipGetErrorString(hipError_t) { return "emulated"; }
 #define GEAR_DYN_LDS(name) unsigned char* name = simt::dyn_lds
 #define GEAR_PIN_VGPR(x) asm volatile("" : "+r"(x))
+#define GEAR_LDS_BARRIER() pthread_barrier_wait(&simt::block_bar)
 extern thread_local dim3 threadIdx;
 extern thread_local dim3 blockIdx;
 extern dim3 blockDim, gridDim;
@@ -149,6 +150,17 @@ inline int __ffs(int x) { return __builtin_ffs(x); }
 inline int __ffsll(long long x) { return __builtin_ffsll(x); }
 inline int __clzll(long long x) { return x ? __builtin_clzll((unsigned long long)x) : 64; }
 inline uint32_t atomicAdd(uint32_t* p, uint32_t v) { return __atomic_fetch_add(p, v, __ATOMIC_RELAXED); }
+inline float atomicAdd(float* p, float v) {
+  uint32_t* u = reinterpret_cast<uint32_t*>(p);
+  uint32_t old = __atomic_load_n(u, __ATOMIC_RELAXED), nw;
+  float f;
+  do {
+    memcpy(&f, &old, 4);
+    const float g = f + v;
+    memcpy(&nw, &g, 4);
+  } while (!__atomic_compare_exchange_n(u, &old, nw, false, __ATOMIC_RELAXED, __ATOMIC_RELAXED));
+  return f;
+}
 inline uint32_t atomicOr(uint32_t* p, uint32_t v) { return __atomic_fetch_or(p, v, __ATOMIC_RELAXED); }
 
 #define hipLaunchKernelGGL(kernel, grid, block, lds, st, ...) simt::launch((grid), (block), (lds), [&] { kernel(__VA_ARGS__); })
