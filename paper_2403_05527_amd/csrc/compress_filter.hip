@@ -236,12 +236,38 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
     }
   }
 
-  // outlier lists, one per 64-token tile, ordered (t, c)
+  // Outliers of a token row: the first ELL_K in channel order take the row's fixed
+  // slots, the rest go to the tile's overflow list, ordered (t, c).  The 16 lanes
+  // that own a row are 16 consecutive lanes.
   if (dm.ppm > 0) {
-    uint32_t cnt[NK], inc[NK];
+    uint32_t cnt[NK], inc[NK], pre[NK];   // overflow entries of this lane, their scan over the wave; outliers of the row before this lane
 #pragma unroll
     for (int k = 0; k < NK; ++k) {
-      cnt[k] = __popc(flags[k]);
+      const int t = t0 + r0 + 16 * k;
+      const uint32_t c_all = __popc(flags[k]);
+      uint32_t rinc = c_all;              // inclusive scan over the row's 16 lanes
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) {
+        const uint32_t up = __shfl_up(rinc, o, 16);
+        if (oc >= o) rinc += up;
+      }
+      pre[k] = rinc - c_all;
+      const uint32_t row_total = __shfl(rinc, 15, 16);
+      const uint32_t in_slots = pre[k] >= ELL_K ? 0u : (pre[k] + c_all > ELL_K ? ELL_K - pre[k] : c_all);
+      cnt[k] = c_all - in_slots;
+      if (t < n) {
+        uint32_t* slots = sv.ell + ((size_t)slab * sv.n_cap + t) * ELL_K;
+        uint32_t s_i = pre[k];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if ((flags[k] & (1u << e)) && s_i < ELL_K) {
+            const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+            slots[s_i] = (uint32_t)(oc * 8 + e) | ELL_VALID | (hb << 16);
+            ++s_i;
+          }
+        }
+        if (oc < ELL_K && (uint32_t)oc >= row_total) slots[oc] = 0u;   // empty slots
+      }
       inc[k] = wave_incl_scan(cnt[k]);
       if (lane == 63) band_cnt[k][wave] = inc[k];
     }
@@ -269,12 +295,16 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
         for (int w = 0; w < 4; ++w) off += band_cnt[kk][w];
       for (int w = 0; w < wave; ++w) off += band_cnt[k][w];
       off += inc[k] - cnt[k];
+      uint32_t s_i = pre[k];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         if (flags[k] & (1u << e)) {
-          const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-          if (off < sv.pool_cap) pool[off] = (uint32_t)((tl & 63) * D + oc * 8 + e) | (hb << 16);
-          ++off;
+          if (s_i >= ELL_K) {
+            const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+            if (off < sv.pool_cap) pool[off] = (uint32_t)((tl & 63) * D + oc * 8 + e) | (hb << 16);
+            ++off;
+          }
+          ++s_i;
         }
       }
     }

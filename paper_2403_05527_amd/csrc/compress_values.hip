@@ -150,13 +150,16 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
     }
   }
 
-  // outlier list of this (head, tile), ordered (c, t): thread c owns column c
+  // Outliers of this (head, tile): thread c owns channel c.  The first ELL_V of a
+  // channel in token order take the channel's fixed slots, the rest go to the tile's
+  // overflow list, ordered (c, t).
   if (dm.ppm > 0) {
     uint32_t m0 = 0, m1 = 0, cnt = 0, inc = 0;
     if (tid < D) {
       m0 = colmask[tid][0];
       m1 = colmask[tid][1];
-      cnt = __popc(m0) + __popc(m1);
+      const uint32_t c_all = __popc(m0) + __popc(m1);
+      cnt = c_all > ELL_V ? c_all - ELL_V : 0u;
     }
     if (wave < 2) {
       inc = wave_incl_scan(cnt);
@@ -173,6 +176,8 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
     if (tid < D) {
       uint32_t off = list_off + (wave == 1 ? wtot[0] : 0u) + inc - cnt;
       uint32_t* pool = sv.sp_pool + (size_t)b * sv.pool_cap;
+      uint32_t* slots = sv.ell + (((size_t)slab * sv.ntile_cap + tile) * D + tid) * ELL_V;
+      uint32_t s_i = 0;
       for (int half = 0; half < 2; ++half) {
         uint32_t mm = half ? m1 : m0;
         while (mm) {
@@ -180,10 +185,16 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
           mm &= mm - 1;
           const int tl = half * 32 + bit;
           const uint32_t hb = X[(size_t)(t0 + tl) * D + tid];
-          if (off < sv.pool_cap) pool[off] = (uint32_t)(tl * D + tid) | (hb << 16);
-          ++off;
+          if (s_i < ELL_V) {
+            slots[s_i] = (uint32_t)tl | ELL_VALID | (hb << 16);
+          } else {
+            if (off < sv.pool_cap) pool[off] = (uint32_t)(tl * D + tid) | (hb << 16);
+            ++off;
+          }
+          ++s_i;
         }
       }
+      for (; s_i < ELL_V; ++s_i) slots[s_i] = 0u;   // empty slots
     }
   }
 }

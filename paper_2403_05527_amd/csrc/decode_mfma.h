@@ -262,9 +262,26 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const uint32_t ov0 = __shfl(tab.x, 2, 64), ov1 = __shfl(tab.x, 3, 64);
   const uint32_t* poolk = ks.sp_pool + (size_t)slab * ks.pool_cap;
   const uint32_t* poolv = vs.sp_pool + (size_t)b * vs.pool_cap;
-  // the first SPR * 64 entries of each list travel in registers: entry lane + 64 i,
-  // as (row in the wave) * 128 + c | value << 16; 0 (adds +0 to row 0) where there is none
-  constexpr int SPR = 6;
+  // fixed outlier slots: Keys of rows lane and lane + 64, Values of channels lane and
+  // lane + 64 in the wave's two tiles (an empty slot is 0: index 0, value +0)
+  uint4 ellk[2];
+  uint2 ellv[2][2];
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) {
+    ellk[rep] = make_uint4(0, 0, 0, 0);
+    if (dm.ppm > 0 && lane + 64 * rep < nw)
+      ellk[rep] = *reinterpret_cast<const uint4*>(ks.ell + ((size_t)slab * ks.n_cap + tw0 + lane + 64 * rep) * ELL_K);
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti) {
+      ellv[ti][rep] = make_uint2(0, 0);
+      if (dm.ppm > 0 && ti * TILE < nw)
+        ellv[ti][rep] = *reinterpret_cast<const uint2*>(
+            vs.ell + (((size_t)slab * vs.ntile_cap + tw0 / TILE + ti) * D + lane + 64 * rep) * ELL_V);
+    }
+  }
+  // overflow lists: the first SPR * 64 entries travel in registers, entry lane + 64 i,
+  // as (row in the wave) * 128 + c | value << 16
+  constexpr int SPR = 1;
   uint32_t spk_r[SPR], spv_r[SPR];
 #pragma unroll
   for (int i = 0; i < SPR; ++i) {
@@ -410,10 +427,29 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     wave_lds_sync();
   }
 
-  // sparse Key term: every entry adds q[c] * value to its row's score.  LDS float
-  // adds from one wave are applied in program order (and in a fixed lane order inside
-  // one instruction), so the result does not vary from run to run.
+  // sparse Key term.  Fixed slots: the lane owns the row, plain adds.  Overflow
+  // entries (rows with more outliers than slots): LDS float adds; those of one wave
+  // are applied in program order and in a fixed lane order inside one instruction,
+  // so the result does not vary from run to run.
   if (dm.ppm > 0) {
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+      const int row = lane + 64 * rep;
+      const uint32_t es[4] = {ellk[rep].x, ellk[rep].y, ellk[rep].z, ellk[rep].w};
+      float a2[GQ];
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < ELL_K; ++i) {
+        const float v = h2f(es[i] >> 16);
+        const int c = es[i] & 127u;
+#pragma unroll
+        for (int hq = 0; hq < GQ; ++hq) a2[hq] += Sq[hq * D + c] * v;
+      }
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) Ssc[hq * WTOK + row] += a2[hq];
+    }
+    wave_lds_sync();
     auto add_k = [&](uint32_t en) {
       const int row = (en & 0xFFFFu) >> 7, c = en & 127u;
       const float v = h2f(en >> 16);
@@ -594,8 +630,29 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   }
   wave_lds_sync();
 
-  // sparse Value term: every entry adds p[row] * value to its channel of this wave's plane
+  // sparse Value term into this wave's plane.  Fixed slots: the lane owns the channel.
   if (dm.ppm > 0) {
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+      const int c = lane + 64 * rep;
+      float a2[GQ];
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) {
+        const uint32_t es[2] = {ellv[ti][rep].x, ellv[ti][rep].y};
+#pragma unroll
+        for (int i = 0; i < ELL_V; ++i) {
+          const float v = h2f(es[i] >> 16);
+          const int row = ti * TILE + (int)(es[i] & 63u);
+#pragma unroll
+          for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * WTOK + row] * v;
+        }
+      }
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) Sosp[hq * D + c] += a2[hq];
+    }
+    wave_lds_sync();
     auto add_v = [&](uint32_t en) {
       const int row = (en & 0xFFFFu) >> 7, c = en & 127u;
       const float v = h2f(en >> 16);

@@ -40,6 +40,7 @@ __device__ __forceinline__ SegView chunk_view(const SegView& base, uint64_t stri
   v.sz = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(base.sz) + off);
   v.A = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(base.A) + off);
   v.Bf = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(base.Bf) + off);
+  v.ell = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(base.ell) + off);
   v.sp_table = reinterpret_cast<uint2*>(reinterpret_cast<char*>(base.sp_table) + off);
   v.sp_pool = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(base.sp_pool) + off);
   v.n = n;
@@ -194,6 +195,17 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
 #pragma unroll
           for (int hq = 0; hq < GQ; ++hq) s[hq] += S.qB[jc][hq][r] * a;
         }
+        if (dm.ppm > 0) {  // the row's fixed outlier slots (an empty slot is channel 0 with value +0)
+          const uint4 e4 = *reinterpret_cast<const uint4*>(kv.ell + ((size_t)slab * kv.n_cap + t) * ELL_K);
+          const uint32_t es[4] = {e4.x, e4.y, e4.z, e4.w};
+#pragma unroll
+          for (int i = 0; i < ELL_K; ++i) {
+            const float v = h2f(es[i] >> 16);
+            const int c = es[i] & 127u;
+#pragma unroll
+            for (int hq = 0; hq < GQ; ++hq) s[hq] += S.q[hq][c] * v;
+          }
+        }
       } else {
         const uint4* row = reinterpret_cast<const uint4*>(Kb + (size_t)t * D);
         for (int i = 0; i < D / 8; ++i) {
@@ -254,6 +266,19 @@ __device__ void tail_block(TailSmem<GQ>& S, const Dims& dm, const ChunkSet& cs, 
       for (int jc = half; jc < npc; jc += 2) {
         const int j = jbase + jc, n_j = cs.n[j], r0 = S.row0[jc];
         const SegView vv = chunk_view(cs.v0, cs.stride, j, n_j, cs.rank[j]);
+        if (dm.ppm > 0) {  // the channel's fixed outlier slots of every tile (empty: row 0, value +0)
+          for (int tile = 0; tile * TILE < n_j; ++tile) {
+            const uint2 ev = *reinterpret_cast<const uint2*>(vv.ell + (((size_t)slab * vv.ntile_cap + tile) * D + c) * ELL_V);
+            const uint32_t es[2] = {ev.x, ev.y};
+#pragma unroll
+            for (int i = 0; i < ELL_V; ++i) {
+              const float v = h2f(es[i] >> 16);
+              const int row = r0 + tile * TILE + (int)(es[i] & 63u);
+#pragma unroll
+              for (int hq = 0; hq < GQ; ++hq) o[hq] += S.sc[hq][row] * v;
+            }
+          }
+        }
         const int ntg = (n_j + tpw - 1) / tpw;
         for (int tg = 0; tg < ntg; ++tg) {
           const uint32_t w =

@@ -36,6 +36,26 @@ __device__ __forceinline__ uint32_t load_sz(const SegView& sv, const Dims& dm, b
   return sv.sz[((size_t)slab * sv.n_cap + t) * (D / dm.g) + c / dm.g];
 }
 
+// Calls f(row in the tile, channel, fp16 bits) for every filled fixed slot of one
+// 64-token tile; the slots are spread over the 256 threads of the block.
+template <class F>
+__device__ __forceinline__ void for_each_ell(const SegView& sv, int is_k, int slab, int tile, int tid, F&& f) {
+  if (is_k) {
+    for (int i = tid; i < TILE * ELL_K; i += 256) {
+      const int tl = i / ELL_K, t = tile * TILE + tl;
+      if (t >= sv.n) continue;
+      const uint32_t en = sv.ell[((size_t)slab * sv.n_cap + t) * ELL_K + (i % ELL_K)];
+      if (en & ELL_VALID) f(tl, (int)(en & 127u), en >> 16);
+    }
+  } else {
+    for (int i = tid; i < D * ELL_V; i += 256) {
+      const int c = i / ELL_V;
+      const uint32_t en = sv.ell[(((size_t)slab * sv.ntile_cap + tile) * D + c) * ELL_V + (i % ELL_V)];
+      if ((en & ELL_VALID) && tile * TILE + (int)(en & 63u) < sv.n) f((int)(en & 63u), c, en >> 16);
+    }
+  }
+}
+
 // grid (ceil(n/64), B*H), block 256.
 __global__ __launch_bounds__(256) void decompress_kernel(Dims dm, SegView sv, int is_k, uint16_t* __restrict__ out,
                                                          int n_total) {
@@ -57,6 +77,7 @@ __global__ __launch_bounds__(256) void decompress_kernel(Dims dm, SegView sv, in
       const uint32_t en = lst[e];
       sp[(en & 0xFFFFu) >> 7][en & 127u] = h2f(en >> 16);
     }
+    for_each_ell(sv, is_k, slab, tile, tid, [&](int tl, int c, uint32_t hb) { sp[tl][c] = h2f(hb); });
   }
   block_lds_sync();
   for (int i = tid; i < TILE * D; i += 256) {
@@ -111,6 +132,11 @@ __global__ __launch_bounds__(256) void export_sparse_kernel(Dims dm, SegView sv,
       vals[o] = (uint16_t)(en >> 16);
     }
   }
+  for_each_ell(sv, is_k, slab, tile, tid, [&](int tl, int c, uint32_t hb) {
+    const size_t o = ((size_t)slab * n_total + sv.t0 + tile * TILE + tl) * D + c;
+    mask[o] = 1;
+    vals[o] = (uint16_t)hb;
+  });
 }
 
 __global__ void export_lowrank_kernel(SegView sv, uint16_t* __restrict__ A, uint16_t* __restrict__ Bf, int slabs) {

@@ -20,7 +20,7 @@ inline int outlier_count(long long n_v, long long ppm) {  // ceil(ppm * n_v / 1e
 }
 
 struct Region {  // byte offsets of one tensor's arrays inside a segment region
-  size_t codes, sz, A, Bf, table, pool, bytes;
+  size_t codes, sz, A, Bf, ell, table, pool, bytes;
   int n_cap, ng_cap, nblk_cap, ntile_cap;
   uint32_t pool_cap;
 };
@@ -42,6 +42,8 @@ Region region_layout(const gear_config& c, bool is_k, int n_cap) {
   o += up(slabs * (size_t)n_cap * (c.rank_max > 0 ? c.rank_max : 1) * 2);
   r.Bf = o;
   o += up(slabs * (size_t)D * (c.rank_max > 0 ? c.rank_max : 1) * 2);
+  r.ell = o;
+  o += up(is_k ? slabs * (size_t)n_cap * ELL_K * 4 : slabs * (size_t)r.ntile_cap * D * ELL_V * 4);
   r.table = o;
   o += up(slabs * (size_t)r.ntile_cap * 8);
   r.pool = o;
@@ -138,6 +140,7 @@ SegView make_view(char* base, const Region& r, int n, int rank, int t0, int g0) 
   v.sz = reinterpret_cast<uint32_t*>(base + r.sz);
   v.A = reinterpret_cast<uint16_t*>(base + r.A);
   v.Bf = reinterpret_cast<uint16_t*>(base + r.Bf);
+  v.ell = reinterpret_cast<uint32_t*>(base + r.ell);
   v.sp_table = reinterpret_cast<uint2*>(base + r.table);
   v.sp_pool = reinterpret_cast<uint32_t*>(base + r.pool);
   v.n = n; v.n_cap = r.n_cap; v.rank = rank;

@@ -37,6 +37,9 @@ namespace gear {
 
 constexpr int D = 128;      // head dimension
 constexpr int TILE = 64;    // tokens per sparse-list tile
+constexpr int ELL_K = 4;    // fixed outlier slots per Key token row
+constexpr int ELL_V = 2;    // fixed outlier slots per Value channel and tile
+constexpr uint32_t ELL_VALID = 0x8000u;
 
 // ---------------------------------------------------------------------------
 // Filter_s thresholds of one vector (Eq. 4).  An entry with monotone key `k`
@@ -74,7 +77,16 @@ struct Dims {
 //  sz           : (scale, zero) as two fp16 in one u32 (scale low half).
 //                 Keys [slab][ng_cap][128]; Values [slab][n_cap][128/g].
 //  A, Bf        : fp16 [slab][n_cap][rank], [slab][128][rank].
-//  sp_table     : [slab][ntile_cap] (offset, count) of the tile's outlier list.
+//  ell          : the sparse matrix S (Filter_s, Eq. 4), fixed-slot part.  Keys:
+//                 [slab][n_cap][4] u32, the first 4 outliers of a token row in
+//                 channel order, slot = c | 0x8000 | fp16 value << 16.  Values:
+//                 [slab][ntile_cap][128][2] u32, the first 2 outliers of one
+//                 channel inside a 64-token tile in token order, slot =
+//                 (t % 64) | 0x8000 | value << 16.  An empty slot is 0.  A reader
+//                 that owns the row (Keys) / the channel (Values) sums its slots
+//                 without any exchange with other lanes.
+//  sp_table     : [slab][ntile_cap] (offset, count) of the tile's overflow list:
+//                 the outliers that found no slot.
 //  sp_pool      : u32 entries (low 16 bits: (t % 64)*128 + c, high 16: fp16
 //                 value).  Keys: one pool per slab, lists ordered (t, c);
 //                 Values: one pool per batch element, lists ordered (c, t).
@@ -83,6 +95,7 @@ struct SegView {
   uint32_t* sz;
   uint16_t* A;
   uint16_t* Bf;
+  uint32_t* ell;
   uint2* sp_table;
   uint32_t* sp_pool;
   int n;         // tokens stored

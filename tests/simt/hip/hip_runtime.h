@@ -133,10 +133,20 @@ inline void launch(dim3 grid, dim3 block, size_t lds, F&& body) {
 #define __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, x, y, z) \
   __builtin_bit_cast(gear::floatx4, simt::mfma(__builtin_bit_cast(simt::h8, (a)), __builtin_bit_cast(simt::h8, (b)), __builtin_bit_cast(simt::f4, (c))))
 #define __syncthreads() pthread_barrier_wait(&simt::block_bar)
-template <typename T> inline T __shfl(T v, int src, int w = 64) { return simt::shfl(v, src); }
-template <typename T> inline T __shfl_xor(T v, int m, int w = 64) { return simt::shfl(v, simt::lane() ^ m); }
-template <typename T> inline T __shfl_up(T v, int o, int w = 64) { return simt::shfl(v, simt::lane() - o < 0 ? simt::lane() : simt::lane() - o); }
-template <typename T> inline T __shfl_down(T v, int o, int w = 64) { return simt::shfl(v, simt::lane() + o > 63 ? simt::lane() : simt::lane() + o); }
+// shuffles inside segments of w lanes (w a power of two), as HIP defines them
+template <typename T> inline T __shfl(T v, int src, int w = 64) { return simt::shfl(v, (simt::lane() & ~(w - 1)) + (src & (w - 1))); }
+template <typename T> inline T __shfl_xor(T v, int m, int w = 64) {
+  const int l = simt::lane(), t = l ^ m;
+  return simt::shfl(v, (t & ~(w - 1)) == (l & ~(w - 1)) ? t : l);
+}
+template <typename T> inline T __shfl_up(T v, int o, int w = 64) {
+  const int l = simt::lane();
+  return simt::shfl(v, (l & (w - 1)) >= o ? l - o : l);
+}
+template <typename T> inline T __shfl_down(T v, int o, int w = 64) {
+  const int l = simt::lane();
+  return simt::shfl(v, (l & (w - 1)) + o < w ? l + o : l);
+}
 inline unsigned long long __ballot(bool p) { return simt::ballot(p); }
 inline float __expf(float x) { return expf(x); }
 inline float __int_as_float(int i) { float f; memcpy(&f, &i, 4); return f; }
