@@ -154,27 +154,6 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int r
   return L;
 }
 
-// Cooperative copy of `count` fp16 values global -> LDS by the block (any alignment).
-__device__ __forceinline__ void stage_halfs(uint16_t* dst, const uint16_t* src, int count) {
-  const int tid = threadIdx.x;
-  if (((reinterpret_cast<uintptr_t>(src) & 7u) == 0) && (count & 3) == 0) {
-    for (int i = tid; i < count / 4; i += 256)
-      reinterpret_cast<uint2*>(dst)[i] = reinterpret_cast<const uint2*>(src)[i];
-  } else {
-    for (int i = tid; i < count; i += 256) dst[i] = src[i];
-  }
-}
-// Copy of `count` fp16 values global -> LDS by one wave (any alignment).
-__device__ __forceinline__ void wave_stage_halfs(uint16_t* dst, const uint16_t* src, int count) {
-  const int lane = lane_id();
-  if (((reinterpret_cast<uintptr_t>(src) & 7u) == 0) && (count & 3) == 0) {
-    for (int i = lane; i < count / 4; i += 64)
-      reinterpret_cast<uint2*>(dst)[i] = reinterpret_cast<const uint2*>(src)[i];
-  } else {
-    for (int i = lane; i < count; i += 64) dst[i] = src[i];
-  }
-}
-
 // One block of MFMA_TS prefill tokens [t_begin, t_end) of slab (b, h): writes the
 // partial softmax record (m, l, o[128]) of each of the GQ query heads.
 template <int BITS, int GQ>
@@ -235,20 +214,32 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       }
     }
   }
-  // shared: q and the B factors
-  for (int i = tid; i < GQ * D; i += 256) Sq[i] = h2f(qg[i]);
-  if (rk > 0) stage_halfs(Sbfk, ks.Bf + (size_t)slab * D * rk, D * rk);
-  if (rv > 0) stage_halfs(Sbfv, vs.Bf + (size_t)slab * D * rv, D * rv);
-  // per wave: (scale, zero) of its groups / tokens, its rows of A
-  if (nw > 0) {
-    const int ngl = (nw + g - 1) / g;
-    const uint32_t* src = ks.sz + ((size_t)slab * ks.ng_cap + tw0 / g) * D;
-    for (int i = lane; i < ngl * D; i += 64) Sszk[i] = src[i];
-    const uint32_t* srcv = vs.sz + ((size_t)slab * vs.n_cap + tw0) * NG;
-    for (int i = lane; i < nw * NG; i += 64) Sszv[i] = srcv[i];
-    if (rk > 0) wave_stage_halfs(Sak, ks.A + ((size_t)slab * ks.n_cap + tw0) * rk, nw * rk);
-    if (rv > 0) wave_stage_halfs(Sav, vs.A + ((size_t)slab * vs.n_cap + tw0) * rv, nw * rv);
+  // shared q and B factors, this wave's (scale, zero) and rows of A: first every load
+  // into registers (16 bytes per lane and request), LDS writes afterwards, so that all
+  // of them are in flight together.  The arena keeps these arrays 16-byte aligned per
+  // slab and padded, so whole 16-byte pieces may be read past the wave's last row.
+  uint32_t qreg[2], bkreg[2], bvreg[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int i = tid + 256 * k;
+    qreg[k] = 0u; bkreg[k] = 0u; bvreg[k] = 0u;
+    if (i < GQ * D / 2) qreg[k] = reinterpret_cast<const uint32_t*>(qg)[i];
+    if (i < D * rk / 2) bkreg[k] = reinterpret_cast<const uint32_t*>(ks.Bf + (size_t)slab * D * rk)[i];
+    if (i < D * rv / 2) bvreg[k] = reinterpret_cast<const uint32_t*>(vs.Bf + (size_t)slab * D * rv)[i];
   }
+  const int ngl = (nw + g - 1) / g;
+  const int n4_szk = ngl * (D / 4), n4_szv = (nw * NG + 3) >> 2, n4_ak = (nw * rk + 7) >> 3, n4_av = (nw * rv + 7) >> 3;
+  const uint4* g_szk = reinterpret_cast<const uint4*>(ks.sz + ((size_t)slab * ks.ng_cap + tw0 / g) * D);
+  const uint4* g_szv = reinterpret_cast<const uint4*>(vs.sz + ((size_t)slab * vs.n_cap + tw0) * NG);
+  const uint4* g_ak = reinterpret_cast<const uint4*>(ks.A + ((size_t)slab * ks.n_cap + tw0) * rk);
+  const uint4* g_av = reinterpret_cast<const uint4*>(vs.A + ((size_t)slab * vs.n_cap + tw0) * rv);
+  // (written as conditional loads: a "cond ? *p : zero" is compiled into a load through
+  // a selected address, with the zero parked in scratch memory)
+  uint4 r_szk = make_uint4(0, 0, 0, 0), r_szv = r_szk, r_ak = r_szk, r_av = r_szk;
+  if (lane < n4_szk) r_szk = g_szk[lane];   // pieces 64.. (g = 32, rank 8) follow after the first
+  if (lane < n4_szv) r_szv = g_szv[lane];
+  if (lane < n4_ak) r_ak = g_ak[lane];
+  if (lane < n4_av) r_av = g_av[lane];
   // outlier lists of the wave's tiles: K tiles then V tiles, rows rebased to the wave
   // a table entry is trusted only as far as its pool reaches
   {
@@ -262,23 +253,6 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const uint32_t ov0 = __shfl(tab.x, 2, 64), ov1 = __shfl(tab.x, 3, 64);
   const uint32_t* poolk = ks.sp_pool + (size_t)slab * ks.pool_cap;
   const uint32_t* poolv = vs.sp_pool + (size_t)b * vs.pool_cap;
-  // fixed outlier slots: Keys of rows lane and lane + 64, Values of channels lane and
-  // lane + 64 in the wave's two tiles (an empty slot is 0: index 0, value +0)
-  uint4 ellk[2];
-  uint2 ellv[2][2];
-#pragma unroll
-  for (int rep = 0; rep < 2; ++rep) {
-    ellk[rep] = make_uint4(0, 0, 0, 0);
-    if (dm.ppm > 0 && lane + 64 * rep < nw)
-      ellk[rep] = *reinterpret_cast<const uint4*>(ks.ell + ((size_t)slab * ks.n_cap + tw0 + lane + 64 * rep) * ELL_K);
-#pragma unroll
-    for (int ti = 0; ti < 2; ++ti) {
-      ellv[ti][rep] = make_uint2(0, 0);
-      if (dm.ppm > 0 && ti * TILE < nw)
-        ellv[ti][rep] = *reinterpret_cast<const uint2*>(
-            vs.ell + (((size_t)slab * vs.ntile_cap + tw0 / TILE + ti) * D + lane + 64 * rep) * ELL_V);
-    }
-  }
   // overflow lists: the first SPR * 64 entries travel in registers, entry lane + 64 i,
   // as (row in the wave) * 128 + c | value << 16
   constexpr int SPR = 1;
@@ -299,8 +273,40 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       spv_r[i] = en + (second ? TILE * D : 0);
     }
   }
+  // everything is requested; now the LDS writes
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int i = tid + 256 * k;
+    if (i < GQ * D / 2) {
+      Sq[2 * i] = h2f(qreg[k] & 0xFFFFu);
+      Sq[2 * i + 1] = h2f(qreg[k] >> 16);
+    }
+    if (i < D * rk / 2) reinterpret_cast<uint32_t*>(Sbfk)[i] = bkreg[k];
+    if (i < D * rv / 2) reinterpret_cast<uint32_t*>(Sbfv)[i] = bvreg[k];
+  }
+  if (lane < n4_szk) reinterpret_cast<uint4*>(Sszk)[lane] = r_szk;
+  if (lane < n4_szv) reinterpret_cast<uint4*>(Sszv)[lane] = r_szv;
+  if (lane < n4_ak) reinterpret_cast<uint4*>(Sak)[lane] = r_ak;
+  if (lane < n4_av) reinterpret_cast<uint4*>(Sav)[lane] = r_av;
+  if (n4_szk > 64 || n4_szv > 64 || n4_ak > 64 || n4_av > 64) {   // wave-uniform: second pieces
+    const int j = lane + 64;
+    if (j < n4_szk) reinterpret_cast<uint4*>(Sszk)[j] = g_szk[j];
+    if (j < n4_szv) reinterpret_cast<uint4*>(Sszv)[j] = g_szv[j];
+    if (j < n4_ak) reinterpret_cast<uint4*>(Sak)[j] = g_ak[j];
+    if (j < n4_av) reinterpret_cast<uint4*>(Sav)[j] = g_av[j];
+  }
   for (int i = lane; i < GQ * D; i += 64) Sosp[i] = 0.0f;
   block_lds_sync();   // q and the B factors are visible to all waves; from here on waves run independently
+
+  // fixed outlier slots of the Key rows lane and lane + 64 (an empty slot is 0: channel 0,
+  // value +0); they arrive while the Key scores are computed
+  uint4 ellk[2];
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) {
+    ellk[rep] = make_uint4(0, 0, 0, 0);
+    if (dm.ppm > 0 && lane + 64 * rep < nw)
+      ellk[rep] = *reinterpret_cast<const uint4*>(ks.ell + ((size_t)slab * ks.n_cap + tw0 + lane + 64 * rep) * ELL_K);
+  }
 
   // q^T B_K (down-projection of the low-rank Key term).  The GQ * rkp outputs (rkp = rank
   // rounded up to a power of two) are spread over the 64 lanes, P lanes per output, each
@@ -467,6 +473,17 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     wave_lds_sync();
   }
 
+  // fixed outlier slots of the Value channels lane and lane + 64 in the wave's two tiles
+  uint2 ellv[2][2];
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep)
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti) {
+      ellv[ti][rep] = make_uint2(0, 0);
+      if (dm.ppm > 0 && ti * TILE < nw)
+        ellv[ti][rep] = *reinterpret_cast<const uint2*>(
+            vs.ell + (((size_t)slab * vs.ntile_cap + tw0 / TILE + ti) * D + lane + 64 * rep) * ELL_V);
+    }
   // request this wave's Value codes; they arrive while the softmax runs
   uint32_t vw[VBLK][8];
 #pragma unroll

@@ -29,6 +29,7 @@ Region region_layout(const gear_config& c, bool is_k, int n_cap) {
   Region r;
   const size_t slabs = (size_t)c.B * c.H_kv;
   const int wpr = D * c.bits / 32, tpw = 32 / c.bits;
+  n_cap = (n_cap + 7) & ~7;   // row strides of A, scale/zero and slots stay 16-byte aligned per slab
   r.n_cap = n_cap;
   r.ng_cap = (n_cap + c.group - 1) / c.group;
   r.nblk_cap = (n_cap + 4 * tpw - 1) / (4 * tpw);
@@ -37,9 +38,9 @@ Region region_layout(const gear_config& c, bool is_k, int n_cap) {
   r.codes = o;
   o += up(is_k ? slabs * n_cap * wpr * 4 : slabs * (size_t)r.nblk_cap * 2048);
   r.sz = o;
-  o += up(is_k ? slabs * (size_t)r.ng_cap * D * 4 : slabs * (size_t)n_cap * (D / c.group) * 4);
+  o += up((is_k ? slabs * (size_t)r.ng_cap * D * 4 : slabs * (size_t)n_cap * (D / c.group) * 4) + 16);   // readers fetch whole 16-byte pieces
   r.A = o;
-  o += up(slabs * (size_t)n_cap * (c.rank_max > 0 ? c.rank_max : 1) * 2);
+  o += up(slabs * (size_t)n_cap * (c.rank_max > 0 ? c.rank_max : 1) * 2 + 16);
   r.Bf = o;
   o += up(slabs * (size_t)D * (c.rank_max > 0 ? c.rank_max : 1) * 2);
   r.ell = o;
