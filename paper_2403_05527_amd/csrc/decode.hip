@@ -19,28 +19,50 @@ namespace gear {
 
 static_assert(MFMA_TS == DECODE_SPLIT, "split size is part of the workspace layout");
 
-// grid (nsplit + 1, B*H_kv), block 256.
+// grid (nsplit + ncb + 1, B*H_kv), block 256.  Blocks [0, nsplit): 512 prefill tokens each;
+// blocks [nsplit, nsplit + ncb): four pieces of appended chunks each (one piece = up to 128
+// rows of one chunk, pp pieces per chunk), through the same code as the prefill; the
+// last block: the fp16 streaming-buffer rows.
 template <int BITS, int GQ>
 __global__ __launch_bounds__(256, 4) void decode_split_kernel(Dims dm, SegView k0, SegView v0, ChunkSet cs,
                                                               const uint16_t* __restrict__ q,
                                                               const uint16_t* __restrict__ Kbuf,
                                                               const uint16_t* __restrict__ Vbuf, int n_buf,
-                                                              int n_buf_cap, float* __restrict__ partial) {
+                                                              int n_buf_cap, int nsplit, int pp, int rank_cap,
+                                                              float* __restrict__ partial) {
   GEAR_DYN_LDS(smem_raw);
   const int slab = blockIdx.y, split = blockIdx.x;
-  const int nsplit = (int)gridDim.x - 1;
+  const int nrec = (int)gridDim.x;
   const int b = slab / dm.H, h = slab - b * dm.H;
-  float* rec_base = partial + (((size_t)b * dm.Hq + h * GQ) * (nsplit + 1) + split) * DECODE_REC;
-  const int rec_stride = (nsplit + 1) * DECODE_REC;
+  float* rec_base = partial + (((size_t)b * dm.Hq + h * GQ) * nrec + split) * DECODE_REC;
+  const int rec_stride = nrec * DECODE_REC;
   const uint16_t* qg = q + ((size_t)b * dm.Hq + h * GQ) * D;
-  if (split == nsplit) {
-    tail_block<GQ>(*reinterpret_cast<TailSmem<GQ>*>(smem_raw), dm, cs, qg, Kbuf + (size_t)slab * n_buf_cap * D,
-                   Vbuf + (size_t)slab * n_buf_cap * D, n_buf, slab, b, rec_base, rec_stride);
+  const int wave = GEAR_WAVE_UNIFORM((int)(threadIdx.x >> 6));
+  if (split == nrec - 1) {
+    buffer_block<GQ>(*reinterpret_cast<TailSmem<GQ>*>(smem_raw), qg, Kbuf + (size_t)slab * n_buf_cap * D,
+                     Vbuf + (size_t)slab * n_buf_cap * D, n_buf, rec_base, rec_stride);
     return;
   }
-  const int t_begin = split * MFMA_TS;
-  const int t_end = min(k0.n, t_begin + MFMA_TS);
-  mfma_block<BITS, GQ>(smem_raw, dm, k0, v0, qg, slab, b, t_begin, t_end, rec_base, rec_stride);
+  // one call site: the prefill segment for every wave, or one chunk piece per wave
+  // (piece i = 4 * (split - nsplit) + wave covers rows [128 * (i % pp), ...) of chunk i / pp)
+  SegView kw_ = k0, vw_ = v0;
+  int tw0 = split * MFMA_TS + WTOK * wave, nw = k0.n - tw0, rkc = k0.rank, rvc = v0.rank;
+  if (split >= nsplit) {
+    const int item = 4 * (split - nsplit) + wave;
+    const int j = item / pp, part = item - j * pp;
+    int n_j = 0, r_j = 0;
+    if (j < cs.n_chunks) {
+      n_j = cs.n[j];
+      r_j = cs.rank[j];
+    }
+    kw_ = chunk_view(cs.k0, cs.stride, j < cs.n_chunks ? j : 0, n_j, r_j);
+    vw_ = chunk_view(cs.v0, cs.stride, j < cs.n_chunks ? j : 0, n_j, r_j);
+    tw0 = WTOK * part;
+    nw = n_j - tw0;
+    rkc = rank_cap;
+    rvc = rank_cap;
+  }
+  mfma_block<BITS, GQ>(smem_raw, dm, kw_, vw_, qg, slab, b, tw0, nw, rkc, rvc, rec_base, rec_stride);
 }
 
 // grid (B*H_q), block 128.
@@ -64,9 +86,13 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
 template <int BITS, int GQ>
 static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                                   const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
-                                  int n_buf_cap, uint16_t* out, float* partial, hipStream_t st) {
+                                  int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st) {
   const int nsplit = (k0.n + MFMA_TS - 1) / MFMA_TS;
-  size_t lds = (size_t)mfma_layout<GQ>(BITS, dm.g, k0.rank, v0.rank, dm.ppm).total;
+  const int pp = n_buf_cap > WTOK ? 2 : 1;            // pieces per chunk
+  const int ncb = (cs.n_chunks * pp + 3) / 4;
+  const int rcap = k0.rank > rank_cap ? k0.rank : rank_cap;
+  const int rcap_v = v0.rank > rank_cap ? v0.rank : rank_cap;
+  size_t lds = (size_t)mfma_layout<GQ>(BITS, dm.g, ncb ? rcap : k0.rank, ncb ? rcap_v : v0.rank, dm.ppm).total;
   if (lds < sizeof(TailSmem<GQ>)) lds = sizeof(TailSmem<GQ>);
   static size_t lds_allowed = 0;  // raised once per process and kernel instance
   if (lds > lds_allowed) {
@@ -75,32 +101,32 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
     if (e != hipSuccess) return e;
     lds_allowed = lds;
   }
-  dim3 grid(nsplit + 1, dm.B * dm.H);
+  dim3 grid(nsplit + ncb + 1, dm.B * dm.H);
   hipLaunchKernelGGL((decode_split_kernel<BITS, GQ>), grid, dim3(256), lds, st, dm, k0, v0, cs, q, Kbuf, Vbuf,
-                     n_buf, n_buf_cap, partial);
+                     n_buf, n_buf_cap, nsplit, pp, ncb ? rcap : 0, partial);
   hipLaunchKernelGGL(decode_combine_kernel, dim3(dm.B * dm.Hq), dim3(128), 0, st, (const float*)partial,
-                     nsplit + 1, out);
+                     nsplit + ncb + 1, out);
   return hipGetLastError();
 }
 
 template <int BITS>
 static hipError_t launch_decode_b(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                                   const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
-                                  int n_buf_cap, uint16_t* out, float* partial, hipStream_t st) {
+                                  int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st) {
   switch (dm.Hq / dm.H) {
-    case 1: return launch_decode_t<BITS, 1>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, out, partial, st);
-    case 2: return launch_decode_t<BITS, 2>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, out, partial, st);
-    case 4: return launch_decode_t<BITS, 4>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, out, partial, st);
-    case 8: return launch_decode_t<BITS, 8>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, out, partial, st);
+    case 1: return launch_decode_t<BITS, 1>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
+    case 2: return launch_decode_t<BITS, 2>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
+    case 4: return launch_decode_t<BITS, 4>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
+    case 8: return launch_decode_t<BITS, 8>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
     default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_decode(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                          const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
-                         int n_buf_cap, uint16_t* out, float* partial, hipStream_t st) {
-  if (dm.bits == 2) return launch_decode_b<2>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, out, partial, st);
-  return launch_decode_b<4>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, out, partial, st);
+                         int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st) {
+  if (dm.bits == 2) return launch_decode_b<2>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
+  return launch_decode_b<4>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
 }
 
 }  // namespace gear

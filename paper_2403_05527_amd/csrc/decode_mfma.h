@@ -116,9 +116,9 @@ __device__ __forceinline__ void val_slot(int t, int& kg, int& idx, int& lg) {
 // ---------------------------------------------------------------------------
 constexpr int WTOK = 128;  // tokens per wave
 struct MfmaLayout {
-  int q, bfk, bfv, misc;                       // shared by the four waves
+  int q, misc;                                 // shared by the four waves
   int wave0, wave_stride;                      // per-wave region
-  int sc, szk, szv, ak, av, osp, opnd, qb;  // offsets inside a wave region
+  int sc, szk, szv, ak, av, bfk, bfv, osp, opnd, qb;  // offsets inside a wave region
   int total;
 };
 template <int GQ>
@@ -126,6 +126,7 @@ struct MfmaMisc {
   float wstat[4][GQ][2];   // per wave: m, l
   float wv[4][GQ][8];      // per wave: p^T A_V
   float pm[4][GQ][4];      // per wave: sum_t p_t * zero_V[t][G]
+  int rv[4];               // per wave: rank of its Value factors
 };
 __host__ __device__ inline int up16i(int x) { return (x + 15) & ~15; }
 template <int GQ>
@@ -134,8 +135,6 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int r
   const int TB = bits == 2 ? 64 : 32, NG = D / g;
   int o = 0;
   L.q = o; o += GQ * D * 4;
-  L.bfk = o; o += up16i(D * rk * 2);
-  L.bfv = o; o += up16i(D * rv * 2);
   L.misc = o; o += up16i((int)sizeof(MfmaMisc<GQ>));
   L.wave0 = o;
   int w = 0;
@@ -144,6 +143,8 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int r
   L.szv = w; w += WTOK * NG * 4;
   L.ak = w; w += up16i(WTOK * rk * 2);
   L.av = w; w += up16i(WTOK * rv * 2);
+  L.bfk = w; w += up16i(D * rk * 2);
+  L.bfv = w; w += up16i(D * rv * 2);
   L.osp = w; w += GQ * D * 4;
   int oh = 2 * GQ * D;
   if (NG * 2 * GQ * TB > oh) oh = NG * 2 * GQ * TB;
@@ -154,23 +155,24 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int r
   return L;
 }
 
-// One block of MFMA_TS prefill tokens [t_begin, t_end) of slab (b, h): writes the
-// partial softmax record (m, l, o[128]) of each of the GQ query heads.
+// One block: each of the four waves takes up to 128 consecutive token rows [tw0, tw0 + nw)
+// of the stored segment it is given (ks, vs may differ from wave to wave: the prefill
+// segment for every wave, or one appended chunk per wave), all of slab (b, h).  Writes
+// the block's merged partial softmax record (m, l, o[128]) of each of the GQ query
+// heads.  rk_cap / rv_cap size the LDS layout (>= every wave's ranks).
 template <int BITS, int GQ>
 __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& ks, const SegView& vs,
                            const uint16_t* __restrict__ qg /* q of query head h*GQ of batch b */, int slab, int b,
-                           int t_begin, int t_end, float* __restrict__ rec_base, int rec_stride) {
+                           int tw0, int nw, int rk_cap, int rv_cap, float* __restrict__ rec_base, int rec_stride) {
   constexpr int TB = (BITS == 2) ? 64 : 32;   // tokens per Value code block
   constexpr int KW = (BITS == 2) ? 2 : 4;     // Key code words per lane per M-tile
   constexpr int VBLK = WTOK / TB;             // Value blocks per wave
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = GEAR_WAVE_UNIFORM(tid >> 6), lane = tid & 63;
   const int n16 = lane & 15, kg = lane >> 4;
   const int g = dm.g, NG = D / g;
   const int rk = ks.rank, rv = vs.rank;
-  const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk, rv, dm.ppm);
+  const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk_cap, rv_cap, dm.ppm);
   float* Sq = reinterpret_cast<float*>(smem + L.q);                 // [GQ][128]
-  uint16_t* Sbfk = reinterpret_cast<uint16_t*>(smem + L.bfk);       // [128][rk]
-  uint16_t* Sbfv = reinterpret_cast<uint16_t*>(smem + L.bfv);
   MfmaMisc<GQ>& M = *reinterpret_cast<MfmaMisc<GQ>*>(smem + L.misc);
   unsigned char* wbase = smem + L.wave0 + (size_t)wave * L.wave_stride;
   float* Ssc = reinterpret_cast<float*>(wbase + L.sc);              // [GQ][128] raw scores, then p
@@ -178,13 +180,14 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   uint32_t* Sszv = reinterpret_cast<uint32_t*>(wbase + L.szv);      // [128][NG]
   uint16_t* Sak = reinterpret_cast<uint16_t*>(wbase + L.ak);        // [128][rk]
   uint16_t* Sav = reinterpret_cast<uint16_t*>(wbase + L.av);
+  uint16_t* Sbfk = reinterpret_cast<uint16_t*>(wbase + L.bfk);      // [128][rk]
+  uint16_t* Sbfv = reinterpret_cast<uint16_t*>(wbase + L.bfv);
   float* Sosp = reinterpret_cast<float*>(wbase + L.osp);            // [GQ][128] this wave's output plane
   _Float16* opnd = reinterpret_cast<_Float16*>(wbase + L.opnd);
   float* SqB = reinterpret_cast<float*>(wbase + L.qb);              // [GQ][8] q^T B_K
   const float scale = 0.08838834764831845f;  // 1/sqrt(128)
-  const int tw0 = t_begin + WTOK * wave;      // first token owned by this wave
-  int nw = t_end - tw0;                       // tokens this wave owns (may be <= 0)
-  nw = nw < 0 ? 0 : (nw > WTOK ? WTOK : nw);
+  nw = GEAR_WAVE_UNIFORM(nw < 0 ? 0 : (nw > WTOK ? WTOK : nw));   // rows this wave owns (may be 0)
+  tw0 = GEAR_WAVE_UNIFORM(tw0);
 
   // =================== prologue: every load in flight ===================
   // the (offset, count) entries of this wave's two tiles of each tensor
@@ -203,7 +206,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     const int t = tw0 + 16 * mt + n16;
 #pragma unroll
     for (int j = 0; j < KW; ++j) kw[mt][j] = 0u;
-    if (t < t_end) {
+    if (16 * mt + n16 < nw) {
       const uint32_t* p = ks.codes + ((size_t)slab * ks.n_cap + t) * (4 * BITS) + KW * kg;
       if (BITS == 2) {
         const uint2 w = *reinterpret_cast<const uint2*>(p);
@@ -218,28 +221,31 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   // into registers (16 bytes per lane and request), LDS writes afterwards, so that all
   // of them are in flight together.  The arena keeps these arrays 16-byte aligned per
   // slab and padded, so whole 16-byte pieces may be read past the wave's last row.
-  uint32_t qreg[2], bkreg[2], bvreg[2];
+  uint32_t qreg[2];
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
     const int i = tid + 256 * k;
-    qreg[k] = 0u; bkreg[k] = 0u; bvreg[k] = 0u;
+    qreg[k] = 0u;
     if (i < GQ * D / 2) qreg[k] = reinterpret_cast<const uint32_t*>(qg)[i];
-    if (i < D * rk / 2) bkreg[k] = reinterpret_cast<const uint32_t*>(ks.Bf + (size_t)slab * D * rk)[i];
-    if (i < D * rv / 2) bvreg[k] = reinterpret_cast<const uint32_t*>(vs.Bf + (size_t)slab * D * rv)[i];
   }
   const int ngl = (nw + g - 1) / g;
   const int n4_szk = ngl * (D / 4), n4_szv = (nw * NG + 3) >> 2, n4_ak = (nw * rk + 7) >> 3, n4_av = (nw * rv + 7) >> 3;
+  const int n4_bk = nw > 0 ? 16 * rk : 0, n4_bv = nw > 0 ? 16 * rv : 0;   // 128 * rank fp16
   const uint4* g_szk = reinterpret_cast<const uint4*>(ks.sz + ((size_t)slab * ks.ng_cap + tw0 / g) * D);
   const uint4* g_szv = reinterpret_cast<const uint4*>(vs.sz + ((size_t)slab * vs.n_cap + tw0) * NG);
   const uint4* g_ak = reinterpret_cast<const uint4*>(ks.A + ((size_t)slab * ks.n_cap + tw0) * rk);
   const uint4* g_av = reinterpret_cast<const uint4*>(vs.A + ((size_t)slab * vs.n_cap + tw0) * rv);
+  const uint4* g_bk = reinterpret_cast<const uint4*>(ks.Bf + (size_t)slab * D * rk);
+  const uint4* g_bv = reinterpret_cast<const uint4*>(vs.Bf + (size_t)slab * D * rv);
   // (written as conditional loads: a "cond ? *p : zero" is compiled into a load through
   // a selected address, with the zero parked in scratch memory)
-  uint4 r_szk = make_uint4(0, 0, 0, 0), r_szv = r_szk, r_ak = r_szk, r_av = r_szk;
+  uint4 r_szk = make_uint4(0, 0, 0, 0), r_szv = r_szk, r_ak = r_szk, r_av = r_szk, r_bk = r_szk, r_bv = r_szk;
   if (lane < n4_szk) r_szk = g_szk[lane];   // pieces 64.. (g = 32, rank 8) follow after the first
   if (lane < n4_szv) r_szv = g_szv[lane];
   if (lane < n4_ak) r_ak = g_ak[lane];
   if (lane < n4_av) r_av = g_av[lane];
+  if (lane < n4_bk) r_bk = g_bk[lane];
+  if (lane < n4_bv) r_bv = g_bv[lane];
   // outlier lists of the wave's tiles: K tiles then V tiles, rows rebased to the wave
   // a table entry is trusted only as far as its pool reaches
   {
@@ -281,19 +287,21 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       Sq[2 * i] = h2f(qreg[k] & 0xFFFFu);
       Sq[2 * i + 1] = h2f(qreg[k] >> 16);
     }
-    if (i < D * rk / 2) reinterpret_cast<uint32_t*>(Sbfk)[i] = bkreg[k];
-    if (i < D * rv / 2) reinterpret_cast<uint32_t*>(Sbfv)[i] = bvreg[k];
   }
   if (lane < n4_szk) reinterpret_cast<uint4*>(Sszk)[lane] = r_szk;
   if (lane < n4_szv) reinterpret_cast<uint4*>(Sszv)[lane] = r_szv;
   if (lane < n4_ak) reinterpret_cast<uint4*>(Sak)[lane] = r_ak;
   if (lane < n4_av) reinterpret_cast<uint4*>(Sav)[lane] = r_av;
-  if (n4_szk > 64 || n4_szv > 64 || n4_ak > 64 || n4_av > 64) {   // wave-uniform: second pieces
+  if (lane < n4_bk) reinterpret_cast<uint4*>(Sbfk)[lane] = r_bk;
+  if (lane < n4_bv) reinterpret_cast<uint4*>(Sbfv)[lane] = r_bv;
+  if (n4_szk > 64 || n4_szv > 64 || n4_ak > 64 || n4_av > 64 || n4_bk > 64 || n4_bv > 64) {   // wave-uniform: second pieces
     const int j = lane + 64;
     if (j < n4_szk) reinterpret_cast<uint4*>(Sszk)[j] = g_szk[j];
     if (j < n4_szv) reinterpret_cast<uint4*>(Sszv)[j] = g_szv[j];
     if (j < n4_ak) reinterpret_cast<uint4*>(Sak)[j] = g_ak[j];
     if (j < n4_av) reinterpret_cast<uint4*>(Sav)[j] = g_av[j];
+    if (j < n4_bk) reinterpret_cast<uint4*>(Sbfk)[j] = g_bk[j];
+    if (j < n4_bv) reinterpret_cast<uint4*>(Sbfv)[j] = g_bv[j];
   }
   for (int i = lane; i < GQ * D; i += 64) Sosp[i] = 0.0f;
   block_lds_sync();   // q and the B factors are visible to all waves; from here on waves run independently
@@ -491,7 +499,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     const int tb0 = tw0 + bl * TB;
 #pragma unroll
     for (int j = 0; j < 8; ++j) vw[bl][j] = 0u;
-    if (tb0 < t_end) {
+    if (bl * TB < nw) {
       const uint32_t* cw = vs.codes + ((size_t)slab * vs.nblk_cap + tb0 / TB) * 512 + (kg * 16 + n16) * 8;
       const uint4 c0 = *reinterpret_cast<const uint4*>(cw);
       const uint4 c1 = *reinterpret_cast<const uint4*>(cw + 4);
@@ -513,6 +521,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       Ssc[hq * WTOK + lane + 64] = p1;
       const float l = wave_sum(p0 + p1);
       if (lane == 0) {
+        M.rv[wave] = rv;
         M.wstat[wave][hq][0] = m;          // -inf when the wave owns no token
         M.wstat[wave][hq][1] = l;
       }
@@ -702,7 +711,9 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       const float f = __expf(mw - Mx);
       const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
       float ow = plane[hq * D + c] + M.pm[w][hq][G];
-      for (int r = 0; r < rv; ++r) ow += M.wv[w][hq][r] * h2f(Sbfv[c * rv + r]);
+      const uint16_t* bfw = reinterpret_cast<const uint16_t*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.bfv);
+      const int rvw = M.rv[w];
+      for (int r = 0; r < rvw; ++r) ow += M.wv[w][hq][r] * h2f(bfw[c * rvw + r]);
       o += f * ow;
       l += f * M.wstat[w][hq][1];
     }

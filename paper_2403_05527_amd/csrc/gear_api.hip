@@ -96,8 +96,11 @@ WorkLayout work_layout(const gear_config& c) {
   w.partial = o; o += up(slabs * (size_t)npart * (D * R + R * R) * 4);
   w.Atmp = o; o += up(slabs * (size_t)n_max * R * 4);
   w.cmat = o; o += up(slabs * R * R * 4);
+  // decode records: one per 512 prefill tokens, one per four chunk pieces (a chunk is one
+  // piece of up to 128 rows, two when n_buf_cap > 128), one for the buffer
   const int nsplit = (c.n_prefill_max + DECODE_SPLIT - 1) / DECODE_SPLIT;
-  w.dec = o; o += up((size_t)c.B * c.H_q * (nsplit + 1) * DECODE_REC * 4);
+  const int ncb = (c.n_chunks_max * (c.n_buf_cap > 128 ? 2 : 1) + 3) / 4;
+  w.dec = o; o += up((size_t)c.B * c.H_q * (nsplit + ncb + 1) * DECODE_REC * 4);
   w.resid = o; o += up(c.rank_max > 0 ? slabs * (size_t)n_max * D * 2 : 0);
   w.resid_lo = o; o += up(c.rank_max > 0 ? slabs * (size_t)n_max * D : 0);
   w.bytes = o;
@@ -340,7 +343,7 @@ int gear_decode_attn(const gear_cache* cache, const void* q, const void* K_buf, 
   }
   float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dec);
   GEAR_HIP(launch_decode(dm, k0, v0, cs, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(K_buf),
-                         static_cast<const uint16_t*>(V_buf), n_buf, c.n_buf_cap, static_cast<uint16_t*>(out),
+                         static_cast<const uint16_t*>(V_buf), n_buf, c.n_buf_cap, c.rank_max, static_cast<uint16_t*>(out),
                          partial, static_cast<hipStream_t>(stream)));
   return GEAR_OK;
 }

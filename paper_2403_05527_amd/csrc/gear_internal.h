@@ -13,6 +13,12 @@
 #define GEAR_DYN_LDS(name) extern __shared__ __align__(16) unsigned char name[]
 #endif
 
+// Tells the compiler that an integer is the same in every lane of the wave (it is
+// then kept in a scalar register and branches on it are scalar branches).
+#ifndef GEAR_WAVE_UNIFORM
+#define GEAR_WAVE_UNIFORM(x) __builtin_amdgcn_readfirstlane(x)
+#endif
+
 // An empty volatile asm that takes and returns a value in a vector register: the
 // compiler can neither hoist nor sink what depends on it.
 #ifndef GEAR_PIN_VGPR

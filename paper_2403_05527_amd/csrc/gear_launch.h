@@ -36,7 +36,7 @@ constexpr int DECODE_SPLIT = 512;        // prefill tokens per split block
 constexpr int DECODE_REC = 2 + D;        // floats per partial record: m, l, o[128]
 hipError_t launch_decode(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                          const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
-                         int n_buf_cap, uint16_t* out, float* partial, hipStream_t st);
+                         int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st);
 
 hipError_t launch_decompress(const Dims& dm, const SegView& ks, const SegView& vs, uint16_t* Kout,
                              uint16_t* Vout, int n_total, hipStream_t st);

@@ -43,6 +43,7 @@ inline const char* hipGetErrorString(hipError_t) { return "emulated"; }
 #define GEAR_DYN_LDS(name) unsigned char* name = simt::dyn_lds
 #define GEAR_PIN_VGPR(x) asm volatile("" : "+r"(x))
 #define GEAR_LDS_BARRIER() pthread_barrier_wait(&simt::block_bar)
+#define GEAR_WAVE_UNIFORM(x) (x)
 extern thread_local dim3 threadIdx;
 extern thread_local dim3 blockIdx;
 extern dim3 blockDim, gridDim;
