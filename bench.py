@@ -8,9 +8,10 @@ configured LLaMA-2-7B layer shape (BASELINE config 1 by default):
      slot (the push is the caller writing that row), then gear_decode_attn over
      the compressed cache + the buffer rows so far,
   3. gear_compress of the full buffer as a new chunk (rank r_g).
-Decode iterations run on a cache replica that was compressed in an earlier step
-and rotate over three replicas, so their reads come from HBM and not from the
-256 MB Infinity Cache.
+Decode iterations read cache replicas that hold the prefill segment plus
+--chunks appended chunks (default: half of the flushes of the config's decode
+run, i.e. the cache as it is in the middle of that run) and rotate over three
+replicas, so their reads come from HBM and not from the 256 MB Infinity Cache.
 
 Prints ONE JSON line.  value = KV compress GB/s (fp16 K+V input bytes of the
 prefill / time of its gear_compress call); the decode-attention rate is given
@@ -51,6 +52,7 @@ def main():
     ap.add_argument("--steps", type=int, default=6)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=1, help="index into gear_workloads.CONFIGS")
+    ap.add_argument("--chunks", type=int, default=-1, help="appended chunks in the caches the decode steps read")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -69,7 +71,8 @@ def main():
     dev = "cuda:0"
     w = gw.CONFIGS[args.config]
     NREP = 3
-    max_chunks = min(128, args.steps + args.warmup + 1)
+    pre_chunks = args.chunks if args.chunks >= 0 else (w.steps // w.n_b) // 2
+    max_chunks = max(pre_chunks, 1)
     cfg = gb.make_config(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, w.n_b, w.n, max_chunks,
                          max(w.rank, w.rank_chunk))
     K = gw.make_keys(w, w.n, 0, dev)
@@ -84,6 +87,8 @@ def main():
     reps = [gb.GearCache(cfg, dev) for _ in range(NREP)]   # caches the decode iterations read
     for r in reps:
         r.compress(K, V, w.rank, w.iters, ib)
+        for _ in range(pre_chunks):
+            r.compress(Kb, Vb, w.rank_chunk, w.iters, ibc)
     torch.cuda.synchronize()
 
     in_bytes = 2 * K.numel() * 2
@@ -110,10 +115,8 @@ def main():
             b.record()
             devs.append((a, b, d.cache.n_chunks, t + 1))
         c0, c1 = ev(), ev()
-        d = reps[i % NREP]
         c0.record()
-        if d.cache.n_chunks < max_chunks:
-            d.compress(Kb, Vb, w.rank_chunk, w.iters, ibc)
+        pre.compress(Kb, Vb, w.rank_chunk, w.iters, ibc)     # the flush: the buffer becomes a chunk of the fresh cache
         c1.record()
         return (e0, e1, devs, c0, c1) if record else None
 
@@ -153,7 +156,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H_kv": w.H_kv, "H_q": w.H_q, "d_h": w.d_h, "n": w.n,
                    "bits": w.bits, "group": w.group, "outlier_ppm": w.outlier_ppm, "rank": w.rank,
-                   "rank_chunk": w.rank_chunk, "n_b": w.n_b, "iters": w.iters},
+                   "rank_chunk": w.rank_chunk, "n_b": w.n_b, "iters": w.iters,
+                   "chunks_in_decoded_cache": pre_chunks},
         "compress_ms": round(tc * 1e3, 4),
         "chunk_compress_ms": round(mean(t_chunk) * 1e3, 4),
         "decode_attn_us": round(td * 1e6, 2),
