@@ -140,23 +140,28 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
   const int ngw = WT / g;  // groups per block (1 or 2)
 
   // thresholds of my 8 channels (staged through LDS: one coalesced read per block)
+  float y[NK][8];
+  uint32_t raw[NK][4];
+  uint32_t flags[NK];
+  // every row of the tile is requested before the first one is used
+#pragma unroll
+  for (int k = 0; k < NK; ++k) {
+    const int t = t0 + r0 + 16 * k;
+    uint4 q = make_uint4(0, 0, 0, 0);
+    if (t < n) q = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
+    raw[k][0] = q.x; raw[k][1] = q.y; raw[k][2] = q.z; raw[k][3] = q.w;
+  }
+  // thresholds of my 8 channels (staged through LDS: one coalesced read per block)
   __shared__ ThreshPair thr_s[D];
   if (tid < D) thr_s[tid] = pack_thresh(dm.ppm > 0 ? thrK[(size_t)slab * D + tid] : thresh_none());
   block_lds_sync();
   ThreshPair th[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) th[e] = thr_s[oc * 8 + e];
-
-  float y[NK][8];
-  uint32_t raw[NK][4];
-  uint32_t flags[NK];
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
     const int t = t0 + r0 + 16 * k;
     flags[k] = 0;
-    uint4 q = make_uint4(0, 0, 0, 0);
-    if (t < n) q = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
-    raw[k][0] = q.x; raw[k][1] = q.y; raw[k][2] = q.z; raw[k][3] = q.w;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;

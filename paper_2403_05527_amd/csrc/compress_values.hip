@@ -71,17 +71,25 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
   if (tid < D) { colmask[tid][0] = 0u; colmask[tid][1] = 0u; }
   block_lds_sync();
 
+  // every row of the tile and its thresholds are requested before the first one is used
+  uint4 xrow[4];
+  Thresh trow[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int t = t0 + r0 + 16 * k;
+    xrow[k] = make_uint4(0, 0, 0, 0);
+    trow[k] = thresh_none();
+    if (t < n) {
+      xrow[k] = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
+      if (dm.ppm > 0) trow[k] = thrV[(size_t)b * n + t];
+    }
+  }
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     const int tl = r0 + 16 * k, t = t0 + tl;
     const bool tv = t < n;
-    uint4 xv = make_uint4(0, 0, 0, 0);
-    Thresh thf = thresh_none();
-    if (tv) {
-      xv = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
-      if (dm.ppm > 0) thf = thrV[(size_t)b * n + t];
-    }
-    const ThreshPair th = pack_thresh(thf);
+    const uint4 xv = xrow[k];
+    const ThreshPair th = pack_thresh(trow[k]);
     const uint32_t w[4] = {xv.x, xv.y, xv.z, xv.w};
     float y[8];
     float lmn = INFINITY, lmx = -INFINITY;

@@ -177,28 +177,49 @@ __global__ __launch_bounds__(256) void pi_sweep_kernel(const uint16_t* __restric
     if (pt * PT + 16 * k0 >= n) break;  // block-uniform
     uint4 xv[UN];
     uint2 xl[UN];
-    float dl[UN][IS_K ? 8 : 1];
+    // Keys: the UN = 4 bands of 16 rows in flight lie in one group (g >= 64) or two (g = 32),
+    // so at most two sets of per-channel scales are needed
+    const int ush = g >= 64 ? 2 : 1;                 // band u uses scale set u >> ush
+    uint4 sk0[IS_K ? 2 : 1], sk1[IS_K ? 2 : 1];     // raw (scale, zero) words, Keys
+    uint32_t svw[UN];                               // raw (scale, zero) word, Values
+    // every load of the UN rows is issued before the first result is touched
+    if (IS_K) {
+#pragma unroll
+      for (int gs = 0; gs < 2; ++gs) {
+        const int t = pt * PT + 16 * (k0 + (gs << ush));       // first row of the set's first band
+        sk0[gs] = make_uint4(0, 0, 0, 0);
+        sk1[gs] = make_uint4(0, 0, 0, 0);
+        if ((gs << ush) < UN && t < n) {
+          const uint4* p = reinterpret_cast<const uint4*>(sv.sz + ((size_t)slab * sv.ng_cap + t / g) * D + oc * 8);
+          sk0[gs] = p[0];
+          sk1[gs] = p[1];
+        }
+      }
+    }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const int t = pt * PT + r0 + 16 * (k0 + u);
       xv[u] = make_uint4(0, 0, 0, 0);
       xl[u] = make_uint2(0, 0);
-#pragma unroll
-      for (int e = 0; e < (IS_K ? 8 : 1); ++e) dl[u][e] = 0.0f;
+      svw[u] = 0u;
       if (t < n) {
         xv[u] = *reinterpret_cast<const uint4*>(Xs + (size_t)t * D + oc * 8);
         xl[u] = *reinterpret_cast<const uint2*>(Xl + (size_t)t * D + oc * 8);
-        if (IS_K) {  // scale of (group of t, my 8 channels)
-          const uint4* p = reinterpret_cast<const uint4*>(sv.sz + ((size_t)slab * sv.ng_cap + t / g) * D + oc * 8);
-          const uint4 s0 = p[0], s1 = p[1];
-          const uint32_t sb[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-#pragma unroll
-          for (int e = 0; e < (IS_K ? 8 : 1); ++e) dl[u][e] = h2f(sb[e] & 0xFFFFu);
-        } else {     // scale of (token t, the channel group of my 8 channels)
-          dl[u][0] = h2f(sv.sz[((size_t)slab * sv.n_cap + t) * (D / g) + (oc * 8) / g] & 0xFFFFu);
-        }
+        if (!IS_K)   // scale of (token t, the channel group of my 8 channels)
+          svw[u] = sv.sz[((size_t)slab * sv.n_cap + t) * (D / g) + (oc * 8) / g];
       }
     }
+    float dlk[IS_K ? 2 : 1][IS_K ? 8 : 1], dlv[UN];
+    if (IS_K) {
+#pragma unroll
+      for (int gs = 0; gs < 2; ++gs) {
+        const uint32_t sb[8] = {sk0[gs].x, sk0[gs].y, sk0[gs].z, sk0[gs].w, sk1[gs].x, sk1[gs].y, sk1[gs].z, sk1[gs].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dlk[gs][IS_K ? e : 0] = h2f(sb[e] & 0xFFFFu);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) dlv[u] = h2f(svw[u] & 0xFFFFu);
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const int t = pt * PT + r0 + 16 * (k0 + u);
@@ -210,7 +231,8 @@ __global__ __launch_bounds__(256) void pi_sweep_kernel(const uint16_t* __restric
       for (int r = 0; r < R; ++r) a[r] = 0.0f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        res[e] = resid_to_float(w[e >> 1] >> ((e & 1) * 16), wl[e >> 2] >> ((e & 3) * 8)) * dl[u][IS_K ? e : 0];
+        res[e] = resid_to_float(w[e >> 1] >> ((e & 1) * 16), wl[e >> 2] >> ((e & 3) * 8)) *
+                 (IS_K ? dlk[IS_K ? ((u >> ush) & 1) : 0][IS_K ? e : 0] : dlv[u]);
 #pragma unroll
         for (int r = 0; r < R; ++r) a[r] += res[e] * bc[e][r];
       }
