@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void v_select_kernel(const uint16_t* __restric
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int hsub = lane >> 4, oc = lane & 15;
   const int N = H * D;
-  for (int i = 0; i < VSEL_TOKENS / 4; ++i) {  // same trip count in every wave (block barriers inside)
+  for (int i = 0; i < VSEL_TOKENS / 4; ++i) {
     const int t = blockIdx.x * VSEL_TOKENS + i * 4 + wave;
     const bool tvalid = t < n;
     uint4 x[NC];

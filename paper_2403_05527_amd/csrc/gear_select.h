@@ -131,9 +131,9 @@ __device__ __forceinline__ int find_kth_equal(const Src& src, int N, int nch, ui
   return found;
 }
 
-// All waves of the block must call this the same number of times (it contains
-// block barriers); a wave with nothing to do passes active = false.
-// hist: 512 u32 of LDS private to the calling wave.
+// A wave with nothing to do passes active = false.  hist: 512 u32 of LDS private to
+// the calling wave; only wave-level synchronisation is used, so the waves of a block
+// run their selections independently of each other.
 template <class Src>
 __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, int k_bot,
                                               uint32_t* hist, bool active) {
@@ -143,14 +143,14 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
 
   // ---- level 1: histogram of the high key byte
   for (int i = lane; i < 512; i += 64) hist[i] = 0u;
-  block_lds_sync();
+  wave_lds_sync();
   for_each_chunk(src, nch, [&](int ch, const uint4& v) {
     const int base = ch * 512 + lane * 8;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (base + e < N) atomicAdd(&hist[slot16(v, e) >> 8], 1u);
   });
-  block_lds_sync();
+  wave_lds_sync();
   int bin_t = -1, bin_b = -1;
   uint32_t need_t = 0, need_b = 0;
   if (active && k_top > 0) {
@@ -163,11 +163,11 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
     scan_from_bottom(hist, (uint32_t)k_bot, bin_b, below);
     need_b = (uint32_t)k_bot - below;
   }
-  block_lds_sync();
+  wave_lds_sync();
 
   // ---- level 2: histograms of the low key byte inside the two boundary bins
   for (int i = lane; i < 512; i += 64) hist[i] = 0u;
-  block_lds_sync();
+  wave_lds_sync();
   for_each_chunk(src, nch, [&](int ch, const uint4& v) {
     const int base = ch * 512 + lane * 8;
 #pragma unroll
@@ -178,7 +178,7 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
         if ((int)(k >> 8) == bin_b) atomicAdd(&hist[256 + (k & 255u)], 1u);
       }
   });
-  block_lds_sync();
+  wave_lds_sync();
   uint32_t need_eq_t = 0, cnt_eq_t = 0, need_eq_b = 0, cnt_eq_b = 0;
   if (active && k_top > 0) {
     int lo;
@@ -196,7 +196,7 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
     need_eq_b = need_b - below;
     cnt_eq_b = hist[256 + lo];
   }
-  block_lds_sync();
+  wave_lds_sync();
 
   // ---- ties: among entries equal to the threshold the lowest indices win;
   // when top and bottom share one threshold value the bottom set continues
