@@ -27,7 +27,7 @@ struct RegSource {  // the vector lives in the wave's registers
 };
 
 // ------------------------------------------------------------------ K select
-// 1-D grid of (128/CB) * B*H blocks of 256 threads; LDS: [CB][n_pad] keys + 4*512 u32.
+// 1-D grid of (128/CB) * B*H blocks of 64 * min(CB, 4) threads; LDS: 512 u32 per wave + [CB][n_pad] keys.
 // Consecutive block ids go round-robin to the chip's 8 XCDs (each with its own L2), so
 // the id is decoded with the column block fastest INSIDE one XCD: the 128/CB blocks
 // that share the 128-byte lines of one slab then meet in one L2 instead of eight.
@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
                                                        Thresh* __restrict__ thrK) {
   GEAR_DYN_LDS(smem_raw);
   uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem_raw);
-  uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + 4 * 512 * sizeof(uint32_t));
+  uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + (blockDim.x >> 6) * 512 * sizeof(uint32_t));
   const int ncb = D / CB;
   int slab, cb;
   if ((nslab & 7) == 0) {
@@ -48,65 +48,61 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
     slab = blockIdx.x / ncb;
   }
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int NT = blockDim.x, NW = NT >> 6;   // 64 threads per vector in flight
   const uint16_t* X = K + (size_t)slab * n * D + cb * CB;
 
   // transpose-load the [n x CB] column block so every vector is contiguous; a
   // thread has UNR row segments in flight at a time
-  const int VW = CB < 8 ? CB : 8;
+  const int VW = CB < 8 ? CB : 8;   // fp16 values per row segment
   const int U = CB / VW;
-  if (VW == 8) {
+  {
     constexpr int UNR = 8;
     const int total = n * U;
-    for (int base = 0; base < total; base += 256 * UNR) {
+    for (int base = 0; base < total; base += NT * UNR) {
       uint4 q[UNR];
 #pragma unroll
       for (int k = 0; k < UNR; ++k) {
-        const int idx = base + k * 256 + tid;
+        const int idx = base + k * NT + tid;
         q[k] = make_uint4(0, 0, 0, 0);
         if (idx < total) {
           const int row = idx / U, u = idx - row * U;
-          q[k] = *reinterpret_cast<const uint4*>(X + (size_t)row * D + u * 8);
+          const uint16_t* p = X + (size_t)row * D + u * VW;
+          if (VW == 8) {
+            q[k] = *reinterpret_cast<const uint4*>(p);
+          } else if (VW == 4) {
+            const uint2 t2 = *reinterpret_cast<const uint2*>(p);
+            q[k].x = t2.x; q[k].y = t2.y;
+          } else if (VW == 2) {
+            q[k].x = *reinterpret_cast<const uint32_t*>(p);
+          } else {
+            q[k].x = *p;
+          }
         }
       }
 #pragma unroll
       for (int k = 0; k < UNR; ++k) {
-        const int idx = base + k * 256 + tid;
+        const int idx = base + k * NT + tid;
         if (idx < total) {
           const int row = idx / U, u = idx - row * U;
           const uint32_t w[4] = {key16x2(q[k].x), key16x2(q[k].y), key16x2(q[k].z), key16x2(q[k].w)};
-          uint16_t* dst = tile + (size_t)(u * 8) * n_pad + row;
+          uint16_t* dst = tile + (size_t)(u * VW) * n_pad + row;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) dst[(size_t)e * n_pad] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));   // keys, not values
+          for (int e = 0; e < 8; ++e)
+            if (e < VW) dst[(size_t)e * n_pad] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));   // keys, not values
         }
       }
     }
-  } else {
-    for (int idx = tid; idx < n * U; idx += 256) {
-      const int row = idx / U, u = idx - row * U;
-      const uint16_t* p = X + (size_t)row * D + u * VW;
-      uint16_t v[4];
-      if (VW == 4) {
-        const uint2 q = *reinterpret_cast<const uint2*>(p);
-        v[0] = q.x & 0xFFFF; v[1] = q.x >> 16; v[2] = q.y & 0xFFFF; v[3] = q.y >> 16;
-      } else if (VW == 2) {
-        const uint32_t q = *reinterpret_cast<const uint32_t*>(p);
-        v[0] = q & 0xFFFF; v[1] = q >> 16;
-      } else {
-        v[0] = *p;
-      }
-      for (int e = 0; e < VW; ++e) tile[(size_t)(u * VW + e) * n_pad + row] = (uint16_t)key16(v[e]);   // keys, not values
-    }
   }
   // zero the padding so stray lanes read defined data
-  for (int idx = tid; idx < CB * (n_pad - n); idx += 256) {
+  for (int idx = tid; idx < CB * (n_pad - n); idx += NT) {
     const int c = idx / (n_pad - n), r = idx - c * (n_pad - n);
     tile[(size_t)c * n_pad + n + r] = 0;
   }
   block_lds_sync();
 
-  const int iters = (CB + 3) >> 2;
+  const int iters = (CB + NW - 1) / NW;
   for (int it = 0; it < iters; ++it) {
-    const int v = it * 4 + wave;
+    const int v = it * NW + wave;
     const bool active = v < CB;
     LdsSource src{tile + (size_t)(active ? v : 0) * n_pad, n_pad};
     const Thresh th = wave_select(src, n, k_top, k_bot, hist_all + wave * 512, active);
@@ -317,9 +313,10 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
 }
 
 // ------------------------------------------------------------------ launchers
+constexpr size_t KSEL_TILE_BYTES = 32768;   // LDS tile of one block: 4 blocks per CU; smaller tiles mean 4-byte row pieces, measured slower
 static int k_select_cb(int n_pad) {
   int cb = 128;
-  while (cb > 1 && (size_t)cb * n_pad * 2 > 65536) cb >>= 1;
+  while (cb > 1 && (size_t)cb * n_pad * 2 > KSEL_TILE_BYTES) cb >>= 1;
   return cb;
 }
 
@@ -327,12 +324,13 @@ hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, 
                            hipStream_t st) {
   const int n_pad = (n + 7) & ~7;
   const int cb = k_select_cb(n_pad);
-  const size_t lds = 4 * 512 * sizeof(uint32_t) + (size_t)cb * n_pad * 2;
+  const int nw = cb < 4 ? cb : 4;   // waves per block: one vector each per round
+  const size_t lds = (size_t)nw * 512 * sizeof(uint32_t) + (size_t)cb * n_pad * 2;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   dim3 grid((D / cb) * dm.B * dm.H);
-  hipLaunchKernelGGL(k_select_kernel, grid, dim3(256), lds, st, K, n, n_pad, cb, dm.B * dm.H, k_top, k_bot, thrK);
+  hipLaunchKernelGGL(k_select_kernel, grid, dim3(64 * nw), lds, st, K, n, n_pad, cb, dm.B * dm.H, k_top, k_bot, thrK);
   return hipGetLastError();
 }
 
