@@ -111,11 +111,17 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
 }
 
 // ------------------------------------------------------------------ K quant
+// Entry e of a row piece after the Filter: X - S, i.e. 0 where the entry is an outlier
+// (re-derived from the raw words where needed instead of being kept in registers).
+__device__ __forceinline__ float yval(const uint32_t* raw4, uint32_t flags, int e) {
+  const uint32_t hb = (raw4[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+  return (flags & (1u << e)) ? 0.0f : h2f(hb);
+}
 // grid (ceil(n/WT), B*H); block 256; WT = max(64, g) tokens per block.
 // thread (r0 = tid/16, oc = tid%16) owns channels 8*oc..8*oc+7 of rows
 // t0 + r0 + 16*k.
 template <int WT>
-__global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict__ K, SegView sv, Dims dm,
+__global__ __launch_bounds__(256, (WT == 64 ? 3 : 2)) void k_quant_kernel(const uint16_t* __restrict__ K, SegView sv, Dims dm,
                                                       int n, const Thresh* __restrict__ thrK,
                                                       uint32_t* __restrict__ pool_ctr,
                                                       uint16_t* __restrict__ Rout, uint8_t* __restrict__ Rlo) {
@@ -136,7 +142,6 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
   const int ngw = WT / g;  // groups per block (1 or 2)
 
   // thresholds of my 8 channels (staged through LDS: one coalesced read per block)
-  float y[NK][8];
   uint32_t raw[NK][4];
   uint32_t flags[NK];
   // every row of the tile is requested before the first one is used
@@ -151,9 +156,6 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
   __shared__ ThreshPair thr_s[D];
   if (tid < D) thr_s[tid] = pack_thresh(dm.ppm > 0 ? thrK[(size_t)slab * D + tid] : thresh_none());
   block_lds_sync();
-  ThreshPair th[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) th[e] = thr_s[oc * 8 + e];
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
     const int t = t0 + r0 + 16 * k;
@@ -161,9 +163,8 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-      const bool out = (t < n) && is_outlier(key16(hb), (uint32_t)t, th[e]);
+      const bool out = (t < n) && is_outlier(key16(hb), (uint32_t)t, thr_s[oc * 8 + e]);   // read per use: saves 16 registers
       if (out) flags[k] |= 1u << e;
-      y[k][e] = out ? 0.0f : h2f(hb);
     }
   }
 
@@ -177,7 +178,11 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
       const int tl = r0 + 16 * k;
       if (tl / g == gi && t0 + tl < n) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { lmn[e] = fminf(lmn[e], y[k][e]); lmx[e] = fmaxf(lmx[e], y[k][e]); }
+        for (int e = 0; e < 8; ++e) {
+          const float yv = yval(raw[k], flags[k], e);
+          lmn[e] = fminf(lmn[e], yv);
+          lmx[e] = fmaxf(lmx[e], yv);
+        }
       }
     }
 #pragma unroll
@@ -219,7 +224,7 @@ __global__ __launch_bounds__(256) void k_quant_kernel(const uint16_t* __restrict
         q.mn = gq_mn[gi][oc * 8 + e];
         q.inv = gq_inv[gi][oc * 8 + e];
         q.delta = 0.0f;
-        const uint32_t code = quant_code_resid(y[k][e], q, dm.qmax, rh[e], rl[e]);   // residual R = u * delta
+        const uint32_t code = quant_code_resid(yval(raw[k], flags[k], e), q, dm.qmax, rh[e], rl[e]);   // residual R = u * delta
         w |= code << (e * dm.bits);
       }
       if (Rout) {

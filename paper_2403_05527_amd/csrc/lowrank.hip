@@ -144,7 +144,7 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
 // channels 8*oc..+7 of rows pt*PT + r0 + 16*k of the stored residual
 // (u = R / scale as 16-bit fixed point; the scale is applied per group here).
 template <bool IS_K, int R>
-__global__ __launch_bounds__(256) void pi_sweep_kernel(const uint16_t* __restrict__ Rres,
+__global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_kernel(const uint16_t* __restrict__ Rres,
                                                        const uint8_t* __restrict__ Rlo, SegView sv, int g, int n,
                                                        const float* __restrict__ Bcur, int last,
                                                        float* __restrict__ partial, int npart,
