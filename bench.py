@@ -54,6 +54,10 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into gear_workloads.CONFIGS")
     ap.add_argument("--chunks", type=int, default=-1, help="appended chunks in the caches the decode steps read")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run three plain streaming kernels over 1 GiB (each reads 1 GiB "
+                         "and writes 1 GiB: out = in + 1 on bytes): the reference the rocprofv3 FETCH_SIZE / "
+                         "WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over batch with no "
@@ -136,6 +140,14 @@ def main():
             t_dec.append(a.elapsed_time(b) * 1e-3)
             dec_bytes.append(comp_bytes + n_chunks * chunk_bytes + n_buf * row_bytes + qo_bytes)
 
+    # HBM bytes per decode launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a streaming kernel of
+    # known size); measured offline for the default workload only, see the file for the commands
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", "decode_split_c1_hbm_traffic.txt")
+    if args.config == 1 and args.chunks < 0 and os.path.exists(tf):
+        for line in open(tf):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
     mean = lambda x: sum(x) / len(x)
     tc, td = mean(t_comp), mean(t_dec)
     comp_gbps = in_bytes / tc / 1e9
@@ -164,11 +176,19 @@ def main():
         "decode_attn_tokens_per_s": round(w.B / td, 1),
         "roofline": {"bound": "hbm", "kernel": "gear_decode_attn (decode_split_kernel + combine)",
                      "achieved": round(dec_algo_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(dec_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+                     "frac": round(dec_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
+                     "algorithmic_bytes_per_launch": int(mean(dec_bytes))},
         "roofline_compress": {"bound": "hbm", "kernel": "gear_compress (all kernels of the call)",
                               "achieved": round(comp_algo_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": round(comp_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
     }
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, K, V, ib, qs[0])
     print(json.dumps(res), flush=True)
