@@ -65,20 +65,39 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(Dims dm, SegView k
   mfma_block<BITS, GQ>(smem_raw, dm, kw_, vw_, qg, slab, b, tw0, nw, rkc, rvc, rec_base, rec_stride);
 }
 
-// grid (B*H_q), block 128.
+// grid (B*H_q), block 128: thread c merges channel c of the row's nrec records.  Lane s of
+// every wave fetches (m, l) of record s, so the weights of up to 64 records come from one
+// round of loads and the weighted sum over the records has no dependent loads in it.
 __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __restrict__ partial, int nrec,
                                                              uint16_t* __restrict__ out) {
-  const int row = blockIdx.x, c = threadIdx.x;
+  const int row = blockIdx.x, c = threadIdx.x, lane = threadIdx.x & 63;
   const float* rec = partial + (size_t)row * nrec * DECODE_REC;
-  float M = -INFINITY;
-  for (int s = 0; s < nrec; ++s) M = fmaxf(M, rec[(size_t)s * DECODE_REC]);
-  float L = 0.0f, o = 0.0f;
-  for (int s = 0; s < nrec; ++s) {
-    const float m = rec[(size_t)s * DECODE_REC];
-    if (m == -INFINITY) continue;
-    const float f = __expf(m - M);
-    L += rec[(size_t)s * DECODE_REC + 1] * f;
-    o += rec[(size_t)s * DECODE_REC + 2 + c] * f;
+  float M = -INFINITY, L = 0.0f, o = 0.0f;
+  for (int s0 = 0; s0 < nrec; s0 += 64) {
+    const int cnt = nrec - s0 < 64 ? nrec - s0 : 64;
+    float m = -INFINITY, l = 0.0f;
+    if (lane < cnt) {
+      m = rec[(size_t)(s0 + lane) * DECODE_REC];
+      l = rec[(size_t)(s0 + lane) * DECODE_REC + 1];
+    }
+    float Mn = m;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) Mn = fmaxf(Mn, __shfl_xor(Mn, d, 64));
+    Mn = fmaxf(Mn, M);
+    if (Mn == -INFINITY) continue;                      // nothing but empty records so far
+    const float f = (m == -INFINITY) ? 0.0f : __expf(m - Mn);
+    const float keep = (M == -INFINITY) ? 0.0f : __expf(M - Mn);
+    L = L * keep + wave_sum_shfl(l * f);
+    o *= keep;
+    M = Mn;
+    constexpr int UN = 8;
+    for (int j0 = 0; j0 < cnt; j0 += UN) {
+      float v[UN];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) v[u] = (j0 + u < cnt) ? rec[(size_t)(s0 + j0 + u) * DECODE_REC + 2 + c] : 0.0f;
+#pragma unroll
+      for (int u = 0; u < UN; ++u) o += v[u] * __shfl(f, (j0 + u) & 63, 64);
+    }
   }
   out[(size_t)row * D + c] = (uint16_t)f2h(o / L);
 }
