@@ -111,25 +111,34 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
 }
 
 // ------------------------------------------------------------------ K quant
-// Entry e of a row piece after the Filter: X - S, i.e. 0 where the entry is an outlier
-// (re-derived from the raw words where needed instead of being kept in registers).
-__device__ __forceinline__ float yval(const uint32_t* raw4, uint32_t flags, int e) {
-  const uint32_t hb = (raw4[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-  return (flags & (1u << e)) ? 0.0f : h2f(hb);
-}
-// grid (ceil(n/WT), B*H); block 256; WT = max(64, g) tokens per block.
+// grid (ceil(n/WT), B*H); block 256; WT = max(64, G) tokens per block (G = group size).
 // thread (r0 = tid/16, oc = tid%16) owns channels 8*oc..8*oc+7 of rows
-// t0 + r0 + 16*k.
-template <int WT>
-__global__ __launch_bounds__(256, (WT == 64 ? 3 : 2)) void k_quant_kernel(const uint16_t* __restrict__ K, SegView sv, Dims dm,
+// t0 + r0 + 16*k.  The kernel is bound by instruction issue, so the arithmetic is kept
+// to what Eq. 2 / Eq. 4 need:
+//  * the Filter works on the 16-bit keys, two per word; its result is a mask word
+//    (0xFFFF over an outlier's half), which zeroes the entry for min/max and for the
+//    quantizer with one bit-select per two entries;
+//  * group min / max are taken on the keys (two per instruction) and turned back into
+//    fp16 once per (group, channel);
+//  * the code goes into its word by a multiply-add (code * 2^(b*e) is exact in fp32),
+//    the rounding remainder is read off the mantissa of (t - code) * 2^23 + 1.5 * 2^23,
+//    whose low 24 bits are 2^22 + the fixed-point remainder;
+//  * outlier entries are visited by a loop over the set bits, not over all entries.
+template <int G, int BITS>
+__global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const uint16_t* __restrict__ K, SegView sv, Dims dm,
                                                       int n, const Thresh* __restrict__ thrK,
                                                       uint32_t* __restrict__ pool_ctr,
                                                       uint16_t* __restrict__ Rout, uint8_t* __restrict__ Rlo) {
-  constexpr int NK = WT / 16;
-  __shared__ float red_mn[4][D];
-  __shared__ float red_mx[4][D];
-  __shared__ float gq_mn[2][D];
-  __shared__ float gq_inv[2][D];
+  constexpr int WT = G < 64 ? 64 : G;
+  constexpr int NK = WT / 16;        // row pieces per thread
+  constexpr int NGW = WT / G;        // groups per block (1 or 2)
+  constexpr int KPG = NK / NGW;      // row pieces per group
+  constexpr float QMAX = (float)((1 << BITS) - 1);
+  __shared__ uint32_t red_mn[NGW][4][16][4];   // [group][wave][octet]: 8 keys, two per word
+  __shared__ uint32_t red_mx[NGW][4][16][4];
+  __shared__ __attribute__((aligned(16))) float gq_mn[NGW][D];
+  __shared__ __attribute__((aligned(16))) float gq_inv[NGW][D];
+  __shared__ ThreshPair thr_s[D];
   __shared__ uint32_t band_cnt[NK][4];
   __shared__ uint32_t tile_off[2];
 
@@ -138,13 +147,9 @@ __global__ __launch_bounds__(256, (WT == 64 ? 3 : 2)) void k_quant_kernel(const 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r0 = tid >> 4, oc = tid & 15;
   const uint16_t* X = K + (size_t)slab * n * D;
-  const int g = dm.g;
-  const int ngw = WT / g;  // groups per block (1 or 2)
 
-  // thresholds of my 8 channels (staged through LDS: one coalesced read per block)
-  uint32_t raw[NK][4];
-  uint32_t flags[NK];
   // every row of the tile is requested before the first one is used
+  uint32_t raw[NK][4];
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
     const int t = t0 + r0 + 16 * k;
@@ -152,92 +157,126 @@ __global__ __launch_bounds__(256, (WT == 64 ? 3 : 2)) void k_quant_kernel(const 
     if (t < n) q = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
     raw[k][0] = q.x; raw[k][1] = q.y; raw[k][2] = q.z; raw[k][3] = q.w;
   }
-  // thresholds of my 8 channels (staged through LDS: one coalesced read per block)
-  __shared__ ThreshPair thr_s[D];
+  // thresholds of the 128 channels, staged through LDS: one coalesced read per block
   if (tid < D) thr_s[tid] = pack_thresh(dm.ppm > 0 ? thrK[(size_t)slab * D + tid] : thresh_none());
   block_lds_sync();
-#pragma unroll
-  for (int k = 0; k < NK; ++k) {
-    const int t = t0 + r0 + 16 * k;
-    flags[k] = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-      const bool out = (t < n) && is_outlier(key16(hb), (uint32_t)t, thr_s[oc * 8 + e]);   // read per use: saves 16 registers
-      if (out) flags[k] |= 1u << e;
-    }
-  }
 
-  // group min / max per channel
-  for (int gi = 0; gi < ngw; ++gi) {
-    float lmn[8], lmx[8];
+  // Filter + group min / max on the keys
+  uint32_t msk[NK][4];
+  uint32_t mn2[NGW][4], mx2[NGW][4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { lmn[e] = INFINITY; lmx[e] = -INFINITY; }
+  for (int gi = 0; gi < NGW; ++gi)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) { mn2[gi][w] = 0xFFFFFFFFu; mx2[gi][w] = 0u; }
+  {
+    uint32_t top[8], bot[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { top[e] = thr_s[oc * 8 + e].top; bot[e] = thr_s[oc * 8 + e].bot; }
 #pragma unroll
     for (int k = 0; k < NK; ++k) {
-      const int tl = r0 + 16 * k;
-      if (tl / g == gi && t0 + tl < n) {
+      const int t = t0 + r0 + 16 * k;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float yv = yval(raw[k], flags[k], e);
-          lmn[e] = fminf(lmn[e], yv);
-          lmx[e] = fmaxf(lmx[e], yv);
+      for (int w = 0; w < 4; ++w) msk[k][w] = 0u;
+      if (t < n) {   // the 16 lanes of a row decide alike
+        const uint32_t cT = 0xFFFFu - (uint32_t)t, cB = (uint32_t)t;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint32_t kw = key16x2(raw[k][w]);
+          const uint32_t klo = kw << 16, khi = kw & 0xFFFF0000u;
+          const bool olo = (klo | cT) >= top[2 * w] || (klo | cB) < bot[2 * w];
+          const bool ohi = (khi | cT) >= top[2 * w + 1] || (khi | cB) < bot[2 * w + 1];
+          const uint32_t m = (olo ? 0xFFFFu : 0u) | (ohi ? 0xFFFF0000u : 0u);
+          msk[k][w] = m;
+          const uint32_t yk = (kw & ~m) | (0x80008000u & m);   // an outlier counts as 0 (Eq. 4: X - S)
+          mn2[k / KPG][w] = pk_min_u16(mn2[k / KPG][w], yk);
+          mx2[k / KPG][w] = pk_max_u16(mx2[k / KPG][w], yk);
         }
       }
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      lmn[e] = fminf(lmn[e], __shfl_xor(lmn[e], 16, 64));
-      lmn[e] = fminf(lmn[e], __shfl_xor(lmn[e], 32, 64));
-      lmx[e] = fmaxf(lmx[e], __shfl_xor(lmx[e], 16, 64));
-      lmx[e] = fmaxf(lmx[e], __shfl_xor(lmx[e], 32, 64));
-    }
-    if (lane < 16) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { red_mn[wave][oc * 8 + e] = lmn[e]; red_mx[wave][oc * 8 + e] = lmx[e]; }
-    }
-    block_lds_sync();
-    if (tid < D && t0 + gi * g < n) {
-      const float mn = fminf(fminf(red_mn[0][tid], red_mn[1][tid]), fminf(red_mn[2][tid], red_mn[3][tid]));
-      const float mx = fmaxf(fmaxf(red_mx[0][tid], red_mx[1][tid]), fmaxf(red_mx[2][tid], red_mx[3][tid]));
-      const GroupQ q = make_group(mn, mx, dm.qmax);
-      gq_mn[gi][tid] = q.mn;
-      gq_inv[gi][tid] = q.inv;
-      const int grp = (t0 + gi * g) / g;
-      sv.sz[((size_t)slab * sv.ng_cap + grp) * D + tid] = group_bits(q);
-    }
-    block_lds_sync();
   }
+  // the four row-threads of a wave that share a channel octet, then the four waves
+#pragma unroll
+  for (int gi = 0; gi < NGW; ++gi)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      mn2[gi][w] = pk_min_u16(mn2[gi][w], __shfl_xor(mn2[gi][w], 16, 64));
+      mn2[gi][w] = pk_min_u16(mn2[gi][w], __shfl_xor(mn2[gi][w], 32, 64));
+      mx2[gi][w] = pk_max_u16(mx2[gi][w], __shfl_xor(mx2[gi][w], 16, 64));
+      mx2[gi][w] = pk_max_u16(mx2[gi][w], __shfl_xor(mx2[gi][w], 32, 64));
+    }
+  if (lane < 16) {
+#pragma unroll
+    for (int gi = 0; gi < NGW; ++gi)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) { red_mn[gi][wave][oc][w] = mn2[gi][w]; red_mx[gi][wave][oc][w] = mx2[gi][w]; }
+  }
+  block_lds_sync();
+  if (tid < D) {
+    const int o = tid >> 3, w = (tid & 7) >> 1, sh = (tid & 1) * 16;
+#pragma unroll
+    for (int gi = 0; gi < NGW; ++gi) {
+      if (t0 + gi * G < n) {
+        uint32_t kmn = 0xFFFFu, kmx = 0u;
+#pragma unroll
+        for (int wv = 0; wv < 4; ++wv) {
+          const uint32_t a = (red_mn[gi][wv][o][w] >> sh) & 0xFFFFu, b = (red_mx[gi][wv][o][w] >> sh) & 0xFFFFu;
+          kmn = a < kmn ? a : kmn;
+          kmx = b > kmx ? b : kmx;
+        }
+        const GroupQ q = make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), QMAX);
+        gq_mn[gi][tid] = q.mn;
+        gq_inv[gi][tid] = q.inv;
+        sv.sz[((size_t)slab * sv.ng_cap + (t0 + gi * G) / G) * D + tid] = group_bits(q);
+      }
+    }
+  }
+  block_lds_sync();
 
-  // codes, packed token-major
+  // codes (packed token-major) and the residual
   uint32_t* crow = sv.codes + (size_t)slab * sv.n_cap * dm.wpr;
 #pragma unroll
-  for (int k = 0; k < NK; ++k) {
-    const int tl = r0 + 16 * k, t = t0 + tl;
-    if (t < n) {
-      const int gi = tl / g;
-      uint32_t w = 0;
-      uint32_t rh[8], rl[8];
+  for (int gi = 0; gi < NGW; ++gi) {
+    float gmn[8], ginv[8];
+    {
+      const float4 a0 = *reinterpret_cast<const float4*>(&gq_mn[gi][oc * 8]);
+      const float4 a1 = *reinterpret_cast<const float4*>(&gq_mn[gi][oc * 8 + 4]);
+      const float4 b0 = *reinterpret_cast<const float4*>(&gq_inv[gi][oc * 8]);
+      const float4 b1 = *reinterpret_cast<const float4*>(&gq_inv[gi][oc * 8 + 4]);
+      gmn[0] = a0.x; gmn[1] = a0.y; gmn[2] = a0.z; gmn[3] = a0.w; gmn[4] = a1.x; gmn[5] = a1.y; gmn[6] = a1.z; gmn[7] = a1.w;
+      ginv[0] = b0.x; ginv[1] = b0.y; ginv[2] = b0.z; ginv[3] = b0.w; ginv[4] = b1.x; ginv[5] = b1.y; ginv[6] = b1.z; ginv[7] = b1.w;
+    }
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        GroupQ q;
-        q.mn = gq_mn[gi][oc * 8 + e];
-        q.inv = gq_inv[gi][oc * 8 + e];
-        q.delta = 0.0f;
-        const uint32_t code = quant_code_resid(yval(raw[k], flags[k], e), q, dm.qmax, rh[e], rl[e]);   // residual R = u * delta
-        w |= code << (e * dm.bits);
-      }
-      if (Rout) {
-        *reinterpret_cast<uint4*>(Rout + ((size_t)slab * n + t) * D + oc * 8) =
-            make_uint4(rh[0] | (rh[1] << 16), rh[2] | (rh[3] << 16), rh[4] | (rh[5] << 16), rh[6] | (rh[7] << 16));
-        *reinterpret_cast<uint2*>(Rlo + ((size_t)slab * n + t) * D + oc * 8) =
-            make_uint2(rl[0] | (rl[1] << 8) | (rl[2] << 16) | (rl[3] << 24),
-                       rl[4] | (rl[5] << 8) | (rl[6] << 16) | (rl[7] << 24));
-      }
-      if (dm.bits == 4) {
-        crow[(size_t)t * dm.wpr + oc] = w;
-      } else {  // 2 bits: 16 bits per thread
-        reinterpret_cast<uint16_t*>(crow + (size_t)t * dm.wpr)[oc] = (uint16_t)w;
+    for (int kk = 0; kk < KPG; ++kk) {
+      const int k = gi * KPG + kk;
+      const int t = t0 + r0 + 16 * k;
+      if (t < n) {
+        uint32_t fb[8];          // bits of (t - code) * 2^23 + 1.5 * 2^23
+        float cw0 = 0.0f, cw1 = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t x = raw[k][e >> 1] & ~msk[k][e >> 1];
+          const float y = h2f((e & 1) ? (x >> 16) : (x & 0xFFFFu));
+          const float tq = __fmul_rn(__fsub_rn(y, gmn[e]), ginv[e]);
+          const float c = clamp_f32(rintf(tq), 0.0f, QMAX);
+          fb[e] = __float_as_uint(__builtin_fmaf(tq - c, RESID_FIX, RESID_MAGIC));
+          if (BITS == 2) {
+            cw0 = __builtin_fmaf(c, (float)(1u << (2 * e)), cw0);
+          } else {
+            if (e < 4) cw0 = __builtin_fmaf(c, (float)(1u << (4 * e)), cw0);
+            else cw1 = __builtin_fmaf(c, (float)(1u << (4 * (e - 4))), cw1);
+          }
+        }
+        if (Rout) {
+          *reinterpret_cast<uint4*>(Rout + ((size_t)slab * n + t) * D + oc * 8) =
+              make_uint4(resid_hi2(fb[0], fb[1]), resid_hi2(fb[2], fb[3]), resid_hi2(fb[4], fb[5]), resid_hi2(fb[6], fb[7]));
+          *reinterpret_cast<uint2*>(Rlo + ((size_t)slab * n + t) * D + oc * 8) =
+              make_uint2(resid_lo4(fb[0], fb[1], fb[2], fb[3]), resid_lo4(fb[4], fb[5], fb[6], fb[7]));
+        }
+        if (BITS == 4) {
+          crow[(size_t)t * dm.wpr + oc] = (uint32_t)cw0 | ((uint32_t)cw1 << 16);
+        } else {  // 2 bits: 16 bits per thread
+          reinterpret_cast<uint16_t*>(crow + (size_t)t * dm.wpr)[oc] = (uint16_t)(uint32_t)cw0;
+        }
       }
     }
   }
@@ -246,11 +285,19 @@ __global__ __launch_bounds__(256, (WT == 64 ? 3 : 2)) void k_quant_kernel(const 
   // slots, the rest go to the tile's overflow list, ordered (t, c).  The 16 lanes
   // that own a row are 16 consecutive lanes.
   if (dm.ppm > 0) {
-    uint32_t cnt[NK], inc[NK], pre[NK];   // overflow entries of this lane, their scan over the wave; outliers of the row before this lane
+    uint32_t fl8[NK];                      // bit e: entry e of the row piece is an outlier
+    uint32_t cnt[NK], inc[NK], pre[NK];    // overflow entries of this lane, their scan over the wave; outliers of the row before this lane
 #pragma unroll
     for (int k = 0; k < NK; ++k) {
       const int t = t0 + r0 + 16 * k;
-      const uint32_t c_all = __popc(flags[k]);
+      uint32_t f = 0;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t x = msk[k][w] & 0x00010001u;
+        f |= ((x | (x >> 15)) & 3u) << (2 * w);
+      }
+      fl8[k] = f;
+      const uint32_t c_all = __popc(f);
       uint32_t rinc = c_all;              // inclusive scan over the row's 16 lanes
 #pragma unroll
       for (int o = 1; o < 16; o <<= 1) {
@@ -263,14 +310,12 @@ __global__ __launch_bounds__(256, (WT == 64 ? 3 : 2)) void k_quant_kernel(const 
       cnt[k] = c_all - in_slots;
       if (t < n) {
         uint32_t* slots = sv.ell + ((size_t)slab * sv.n_cap + t) * ELL_K;
-        uint32_t s_i = pre[k];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          if ((flags[k] & (1u << e)) && s_i < ELL_K) {
-            const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-            slots[s_i] = (uint32_t)(oc * 8 + e) | ELL_VALID | (hb << 16);
-            ++s_i;
-          }
+        uint32_t s_i = pre[k], ff = f;
+        while (ff != 0u && s_i < ELL_K) {
+          const int e = __ffs((int)ff) - 1;
+          ff &= ff - 1u;
+          slots[s_i] = (uint32_t)(oc * 8 + e) | ELL_VALID | (half_of(raw[k][0], raw[k][1], raw[k][2], raw[k][3], e) << 16);
+          ++s_i;
         }
         if (oc < ELL_K && (uint32_t)oc >= row_total) slots[oc] = 0u;   // empty slots
       }
@@ -294,6 +339,7 @@ __global__ __launch_bounds__(256, (WT == 64 ? 3 : 2)) void k_quant_kernel(const 
     uint32_t* pool = sv.sp_pool + (size_t)slab * sv.pool_cap;
 #pragma unroll
     for (int k = 0; k < NK; ++k) {
+      if (cnt[k] == 0u) continue;          // rows with more than ELL_K outliers are the exception
       const int tl = r0 + 16 * k;
       const int ti = k / 4;  // tile inside the block
       uint32_t off = tile_off[ti];
@@ -301,17 +347,15 @@ __global__ __launch_bounds__(256, (WT == 64 ? 3 : 2)) void k_quant_kernel(const 
         for (int w = 0; w < 4; ++w) off += band_cnt[kk][w];
       for (int w = 0; w < wave; ++w) off += band_cnt[k][w];
       off += inc[k] - cnt[k];
-      uint32_t s_i = pre[k];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if (flags[k] & (1u << e)) {
-          if (s_i >= ELL_K) {
-            const uint32_t hb = (raw[k][e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-            if (off < sv.pool_cap) pool[off] = (uint32_t)((tl & 63) * D + oc * 8 + e) | (hb << 16);
-            ++off;
-          }
-          ++s_i;
+      uint32_t s_i = pre[k], ff = fl8[k];
+      while (ff != 0u) {
+        const int e = __ffs((int)ff) - 1;
+        ff &= ff - 1u;
+        if (s_i >= ELL_K) {
+          if (off < sv.pool_cap) pool[off] = (uint32_t)((tl & 63) * D + oc * 8 + e) | (half_of(raw[k][0], raw[k][1], raw[k][2], raw[k][3], e) << 16);
+          ++off;
         }
+        ++s_i;
       }
     }
   }
@@ -339,15 +383,22 @@ hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, 
   return hipGetLastError();
 }
 
+template <int G>
+static void launch_k_quant_g(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const Thresh* thrK,
+                             uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
+  constexpr int WT = G < 64 ? 64 : G;
+  dim3 grid((n + WT - 1) / WT, dm.B * dm.H);
+  if (dm.bits == 2)
+    hipLaunchKernelGGL((k_quant_kernel<G, 2>), grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
+  else
+    hipLaunchKernelGGL((k_quant_kernel<G, 4>), grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
+}
+
 hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const Thresh* thrK,
                           uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
-  if (dm.g == 128) {
-    dim3 grid((n + 127) / 128, dm.B * dm.H);
-    hipLaunchKernelGGL(k_quant_kernel<128>, grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
-  } else {
-    dim3 grid((n + 63) / 64, dm.B * dm.H);
-    hipLaunchKernelGGL(k_quant_kernel<64>, grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
-  }
+  if (dm.g == 128) launch_k_quant_g<128>(K, sv, dm, n, thrK, pool_ctr, Rout, Rlo, st);
+  else if (dm.g == 64) launch_k_quant_g<64>(K, sv, dm, n, thrK, pool_ctr, Rout, Rlo, st);
+  else launch_k_quant_g<32>(K, sv, dm, n, thrK, pool_ctr, Rout, Rlo, st);
   return hipGetLastError();
 }
 

@@ -39,6 +39,16 @@
   } while (0)
 #endif
 
+// v_perm_b32: byte i of the result is byte sel.byte[i] of the 8 bytes {hi, lo}
+// (0..3 = bytes of lo, 4..7 = bytes of hi, 0x0c = zero).
+#ifndef GEAR_BYTE_PERM
+#define GEAR_BYTE_PERM(hi, lo, sel) __builtin_amdgcn_perm((hi), (lo), (sel))
+#endif
+// v_med3_f32: the median of three = x clamped to [lo, hi]
+#ifndef GEAR_FMED3
+#define GEAR_FMED3(x, lo, hi) __builtin_amdgcn_fmed3f((x), (lo), (hi))
+#endif
+
 namespace gear {
 
 constexpr int D = 128;      // head dimension
@@ -132,10 +142,34 @@ __device__ __forceinline__ uint32_t key16(uint32_t h) {
 // The same key for two fp16 values packed in one 32-bit word (negative: two's
 // complement of the pattern, which also maps -0 onto +0's key; positive: + 0x8000).
 __device__ __forceinline__ uint32_t key16x2(uint32_t h2) {
-  const uint32_t lo = h2 & 0xFFFFu, hi = h2 >> 16;
-  const uint32_t klo = (lo & 0x8000u) ? ((0u - lo) & 0xFFFFu) : (lo | 0x8000u);
-  const uint32_t khi = (hi & 0x8000u) ? ((0u - hi) & 0xFFFFu) : (hi | 0x8000u);
-  return klo | (khi << 16);
+  typedef short i16x2_t __attribute__((ext_vector_type(2)));
+  typedef unsigned short k16x2_t __attribute__((ext_vector_type(2)));
+  const uint32_t s = __builtin_bit_cast(uint32_t, __builtin_bit_cast(i16x2_t, h2) >> 15);   // 0xFFFF over a negative half
+  const uint32_t x = h2 ^ (s | 0x80008000u);                                                // negative: ~h, positive: h + 0x8000
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(k16x2_t, x) - __builtin_bit_cast(k16x2_t, s));   // negative: ~h + 1
+}
+// fp16 bit pattern of a key (the key of +-0 gives +0)
+__device__ __forceinline__ uint32_t unkey16(uint32_t k) {
+  return (k & 0x8000u) ? (k & 0x7FFFu) : ((0u - k) & 0xFFFFu);
+}
+// two unsigned 16-bit lanes per 32-bit word
+typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, a), __builtin_bit_cast(u16x2_t, b)));
+}
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, a), __builtin_bit_cast(u16x2_t, b)));
+}
+__device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {   // wraps in each lane
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, a) - __builtin_bit_cast(u16x2_t, b));
+}
+// fp16 entry e (0..7) of a row piece of four words
+// (the words are passed by value: selecting between elements of an array in place is
+// compiled into an indexed load, which moves the array to scratch memory)
+__device__ __forceinline__ uint32_t half_of(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, int e) {
+  const uint32_t w01 = (e & 2) ? w1 : w0, w23 = (e & 2) ? w3 : w2;
+  const uint32_t w = (e & 4) ? w23 : w01;
+  return (w >> ((e & 1) * 16)) & 0xFFFFu;
 }
 // The predicate of Thresh as two 32-bit compares.  With cT = key << 16 | (0xFFFF - idx)
 // (larger key first, then smaller index) and cB = key << 16 | idx, an entry is an
@@ -221,6 +255,18 @@ __device__ __forceinline__ uint32_t quant_code_resid(float y, const GroupQ& q, f
   lo8 = (uint32_t)f & 0xFFu;
   return (uint32_t)c;
 }
+// The same remainder read off a float's mantissa: the bits of (t - code) * 2^23 + 1.5 * 2^23
+// are 0x4B400000 + f for the fixed-point remainder f = rint((t - code) * 2^23), |f| <= 2^22
+// (round to nearest even either way).  resid_hi2: bits 8..23 of f for two entries in one
+// word; resid_lo4: bits 0..7 of f for four entries.
+constexpr float RESID_MAGIC = 12582912.0f;   // 1.5 * 2^23
+__device__ __forceinline__ uint32_t resid_hi2(uint32_t b0, uint32_t b1) {
+  return pk_sub_u16(GEAR_BYTE_PERM(b1, b0, 0x06050201u), 0x40004000u);
+}
+__device__ __forceinline__ uint32_t resid_lo4(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3) {
+  return GEAR_BYTE_PERM(GEAR_BYTE_PERM(b3, b2, 0x0c0c0400u), GEAR_BYTE_PERM(b1, b0, 0x0c0c0400u), 0x05040100u);
+}
+__device__ __forceinline__ float clamp_f32(float x, float lo, float hi) { return GEAR_FMED3(x, lo, hi); }
 __device__ __forceinline__ float resid_to_float(uint32_t hi16, uint32_t lo8) {  // u, not yet times delta
   return (float)((int)(short)(hi16 & 0xFFFFu) * 256 + (int)(lo8 & 0xFFu)) * (1.0f / RESID_FIX);
 }

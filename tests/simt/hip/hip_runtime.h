@@ -44,6 +44,18 @@ inline const char* hipGetErrorString(hipError_t) { return "emulated"; }
 #define GEAR_PIN_VGPR(x) asm volatile("" : "+r"(x))
 #define GEAR_LDS_BARRIER() pthread_barrier_wait(&simt::block_bar)
 #define GEAR_WAVE_UNIFORM(x) (x)
+#define GEAR_BYTE_PERM(hi, lo, sel) simt_byte_perm((hi), (lo), (sel))
+#define GEAR_FMED3(x, lo, hi) fminf(fmaxf((x), (lo)), (hi))
+static inline uint32_t simt_byte_perm(uint32_t hi, uint32_t lo, uint32_t sel) {
+  const uint64_t src = ((uint64_t)hi << 32) | lo;
+  uint32_t r = 0;
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t s = (sel >> (8 * i)) & 0xFFu;
+    const uint32_t b = s < 8 ? (uint32_t)((src >> (8 * s)) & 0xFFu) : 0u;   // 0x0c: zero
+    r |= b << (8 * i);
+  }
+  return r;
+}
 extern thread_local dim3 threadIdx;
 extern thread_local dim3 blockIdx;
 extern dim3 blockDim, gridDim;
@@ -153,6 +165,7 @@ inline float __expf(float x) { return expf(x); }
 inline float __int_as_float(int i) { float f; memcpy(&f, &i, 4); return f; }
 inline int __float_as_int(float f) { int i; memcpy(&i, &f, 4); return i; }
 inline float __uint_as_float(uint32_t i) { float f; memcpy(&f, &i, 4); return f; }
+inline uint32_t __float_as_uint(float f) { uint32_t i; memcpy(&i, &f, 4); return i; }
 inline float __fdiv_rn(float a, float b) { return a / b; }
 inline float __fsub_rn(float a, float b) { return a - b; }
 inline float __fmul_rn(float a, float b) { return a * b; }
