@@ -33,7 +33,7 @@ struct RegSource {  // the vector lives in the wave's registers
 // that share the 128-byte lines of one slab then meet in one L2 instead of eight.
 __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restrict__ K, int n, int n_pad,
                                                        int CB, int nslab, int k_top, int k_bot,
-                                                       Thresh* __restrict__ thrK) {
+                                                       ThreshPair* __restrict__ thrK) {
   GEAR_DYN_LDS(smem_raw);
   uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem_raw);
   uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + (blockDim.x >> 6) * 512 * sizeof(uint32_t));
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
     const bool active = v < CB;
     LdsSource src{tile + (size_t)(active ? v : 0) * n_pad, n_pad};
     const Thresh th = wave_select(src, n, k_top, k_bot, hist_all + wave * 512, active);
-    if (active && lane == 0) thrK[(size_t)slab * D + cb * CB + v] = th;
+    if (active && lane == 0) thrK[(size_t)slab * D + cb * CB + v] = pack_thresh(th);
   }
 }
 
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
 //  * outlier entries are visited by a loop over the set bits, not over all entries.
 template <int G, int BITS>
 __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const uint16_t* __restrict__ K, SegView sv, Dims dm,
-                                                      int n, const Thresh* __restrict__ thrK,
+                                                      int n, const ThreshPair* __restrict__ thrK,
                                                       uint32_t* __restrict__ pool_ctr,
                                                       uint16_t* __restrict__ Rout, uint8_t* __restrict__ Rlo) {
   constexpr int WT = G < 64 ? 64 : G;
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
     raw[k][0] = q.x; raw[k][1] = q.y; raw[k][2] = q.z; raw[k][3] = q.w;
   }
   // thresholds of the 128 channels, staged through LDS: one coalesced read per block
-  if (tid < D) thr_s[tid] = pack_thresh(dm.ppm > 0 ? thrK[(size_t)slab * D + tid] : thresh_none());
+  if (tid < D) thr_s[tid] = dm.ppm > 0 ? thrK[(size_t)slab * D + tid] : pack_thresh(thresh_none());
   block_lds_sync();
 
   // Filter + group min / max on the keys
@@ -369,7 +369,7 @@ static int k_select_cb(int n_pad) {
   return cb;
 }
 
-hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, Thresh* thrK,
+hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
                            hipStream_t st) {
   const int n_pad = (n + 7) & ~7;
   const int cb = k_select_cb(n_pad);
@@ -384,7 +384,7 @@ hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, 
 }
 
 template <int G>
-static void launch_k_quant_g(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const Thresh* thrK,
+static void launch_k_quant_g(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const ThreshPair* thrK,
                              uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
   constexpr int WT = G < 64 ? 64 : G;
   dim3 grid((n + WT - 1) / WT, dm.B * dm.H);
@@ -394,7 +394,7 @@ static void launch_k_quant_g(const uint16_t* K, const SegView& sv, const Dims& d
     hipLaunchKernelGGL((k_quant_kernel<G, 4>), grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
 }
 
-hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const Thresh* thrK,
+hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const ThreshPair* thrK,
                           uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
   if (dm.g == 128) launch_k_quant_g<128>(K, sv, dm, n, thrK, pool_ctr, Rout, Rlo, st);
   else if (dm.g == 64) launch_k_quant_g<64>(K, sv, dm, n, thrK, pool_ctr, Rout, Rlo, st);

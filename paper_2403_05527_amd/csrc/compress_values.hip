@@ -25,7 +25,7 @@ constexpr int VSEL_TOKENS = 16;  // tokens per block (4 per wave)
 // channels 8*(l%16)..+7, i.e. in-vector index ch*512 + l*8 + e.
 template <int NC>
 __global__ __launch_bounds__(256) void v_select_kernel(const uint16_t* __restrict__ V, int H, int n, int k_top,
-                                                       int k_bot, Thresh* __restrict__ thrV) {
+                                                       int k_bot, ThreshPair* __restrict__ thrV) {
   __shared__ uint32_t hist[4 * 512];
   const int b = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -46,18 +46,24 @@ __global__ __launch_bounds__(256) void v_select_kernel(const uint16_t* __restric
     }
     RegSource<NC> src{x};
     const Thresh th = wave_select(src, N, k_top, k_bot, hist + wave * 512, tvalid);
-    if (tvalid && lane == 0) thrV[(size_t)b * n + t] = th;
+    if (tvalid && lane == 0) thrV[(size_t)b * n + t] = pack_thresh(th);
   }
 }
 
 // grid (ceil(n/64), B*H); block 256; thread (r0 = tid/16, oc = tid%16) owns
-// channels 8*oc..+7 of rows t0 + r0 + 16*k, k = 0..3.
+// channels 8*oc..+7 of rows t0 + r0 + 16*k, k = 0..3.  Same arithmetic as the Key
+// kernel: Filter and min/max on packed 16-bit keys with a mask word per two entries,
+// code bytes and the rounding remainder read off float mantissas.
+template <int BITS>
 __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict__ V, SegView sv, Dims dm, int n,
-                                                      const Thresh* __restrict__ thrV, uint32_t* __restrict__ pool_ctr,
+                                                      const ThreshPair* __restrict__ thrV, uint32_t* __restrict__ pool_ctr,
                                                       uint16_t* __restrict__ Rout, uint8_t* __restrict__ Rlo) {
   constexpr int PITCH = 136;  // bytes per staged code row (multiple of 8)
+  constexpr float QMAX = (float)((1 << BITS) - 1);
+  constexpr int bits = BITS, tpw = 32 / BITS;
   __shared__ __align__(16) uint8_t stage[TILE * PITCH];
   __shared__ uint32_t colmask[D][2];
+  __shared__ uint16_t oval[D][TILE + 2];   // fp16 values of the tile's outliers (only their cells are written)
   __shared__ uint32_t wtot[2];
   __shared__ uint32_t list_off;
   const int slab = blockIdx.y, tile = blockIdx.x;
@@ -65,7 +71,7 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
   const int t0 = tile * TILE;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r0 = tid >> 4, oc = tid & 15;
-  const int g = dm.g, bits = dm.bits, tpw = dm.tpw;
+  const int g = dm.g, lg = 31 - __clz(g);   // g is a power of two
   const uint16_t* X = V + (size_t)slab * n * D;
 
   if (tid < D) { colmask[tid][0] = 0u; colmask[tid][1] = 0u; }
@@ -73,66 +79,94 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
 
   // every row of the tile and its thresholds are requested before the first one is used
   uint4 xrow[4];
-  Thresh trow[4];
+  ThreshPair trow[4];
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     const int t = t0 + r0 + 16 * k;
     xrow[k] = make_uint4(0, 0, 0, 0);
-    trow[k] = thresh_none();
+    trow[k] = pack_thresh(thresh_none());   // rows past the end have no outliers
     if (t < n) {
       xrow[k] = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
       if (dm.ppm > 0) trow[k] = thrV[(size_t)b * n + t];
     }
   }
+  // in-vector index of entry e: h*128 + 8*oc + e; the low three bits are e
+  const uint32_t cB0 = (uint32_t)(h * D + oc * 8), cT0 = (0xFFFFu - cB0) & ~7u;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     const int tl = r0 + 16 * k, t = t0 + tl;
     const bool tv = t < n;
-    const uint4 xv = xrow[k];
-    const ThreshPair th = pack_thresh(trow[k]);
-    const uint32_t w[4] = {xv.x, xv.y, xv.z, xv.w};
-    float y[8];
-    float lmn = INFINITY, lmx = -INFINITY;
+    const uint32_t raw[4] = {xrow[k].x, xrow[k].y, xrow[k].z, xrow[k].w};
+    const uint32_t top = trow[k].top, bot = trow[k].bot;
+    uint32_t msk[4];
+    uint32_t mn2 = 0xFFFFFFFFu, mx2 = 0u;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint32_t hb = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-      const int c = oc * 8 + e;
-      const bool out = tv && is_outlier(key16(hb), (uint32_t)(h * D + c), th);
-      if (out) atomicOr(&colmask[c][tl >> 5], 1u << (tl & 31));
-      y[e] = out ? 0.0f : h2f(hb);
-      lmn = fminf(lmn, y[e]);
-      lmx = fmaxf(lmx, y[e]);
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t kw = key16x2(raw[w]);
+      const uint32_t klo = kw << 16, khi = kw & 0xFFFF0000u;
+      const bool olo = (klo | cT0 | (uint32_t)(7 - 2 * w)) >= top || (klo | cB0 | (uint32_t)(2 * w)) < bot;
+      const bool ohi = (khi | cT0 | (uint32_t)(6 - 2 * w)) >= top || (khi | cB0 | (uint32_t)(2 * w + 1)) < bot;
+      const uint32_t m = (olo ? 0xFFFFu : 0u) | (ohi ? 0xFFFF0000u : 0u);
+      msk[w] = m;
+      const uint32_t yk = (kw & ~m) | (0x80008000u & m);   // an outlier counts as 0 (Eq. 4: X - S)
+      mn2 = pk_min_u16(mn2, yk);
+      mx2 = pk_max_u16(mx2, yk);
+    }
+    // column bitmask of the tile's outliers (few entries: visited by set bit)
+    {
+      uint32_t f = 0;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t x = msk[w] & 0x00010001u;
+        f |= ((x | (x >> 15)) & 3u) << (2 * w);
+      }
+      while (f != 0u) {
+        const int e = __ffs((int)f) - 1;
+        f &= f - 1u;
+        atomicOr(&colmask[oc * 8 + e][tl >> 5], 1u << (tl & 31));
+        oval[oc * 8 + e][tl] = (uint16_t)half_of(raw[0], raw[1], raw[2], raw[3], e);
+      }
     }
     // group = g consecutive channels of the row = g/8 neighbouring lanes
-    lmn = fminf(lmn, dpp_f<DPP_XOR1>(lmn));
-    lmx = fmaxf(lmx, dpp_f<DPP_XOR1>(lmx));
-    lmn = fminf(lmn, dpp_f<DPP_XOR2>(lmn));
-    lmx = fmaxf(lmx, dpp_f<DPP_XOR2>(lmx));
+    // (reduced as integer keys: the lane exchange folds into the min / max instruction)
+    uint32_t kmn = mn2 & 0xFFFFu, kmx = mx2 & 0xFFFFu;
+    kmn = min(kmn, mn2 >> 16);
+    kmx = max(kmx, mx2 >> 16);
+    kmn = min(kmn, dpp_u<DPP_XOR1>(kmn));
+    kmx = max(kmx, dpp_u<DPP_XOR1>(kmx));
+    kmn = min(kmn, dpp_u<DPP_XOR2>(kmn));
+    kmx = max(kmx, dpp_u<DPP_XOR2>(kmx));
     if (g >= 64) {
-      lmn = fminf(lmn, dpp_f<DPP_HALF_MIRROR>(lmn));
-      lmx = fmaxf(lmx, dpp_f<DPP_HALF_MIRROR>(lmx));
+      kmn = min(kmn, dpp_u<DPP_HALF_MIRROR>(kmn));
+      kmx = max(kmx, dpp_u<DPP_HALF_MIRROR>(kmx));
     }
     if (g >= 128) {
-      lmn = fminf(lmn, dpp_f<DPP_MIRROR>(lmn));
-      lmx = fmaxf(lmx, dpp_f<DPP_MIRROR>(lmx));
+      kmn = min(kmn, dpp_u<DPP_MIRROR>(kmn));
+      kmx = max(kmx, dpp_u<DPP_MIRROR>(kmx));
     }
-    const GroupQ q = make_group(lmn, lmx, dm.qmax);
-    uint32_t cb[2] = {0u, 0u};   // 8 code bytes
-    uint32_t rh[8], rl[8];
+    const float lmn = h2f(unkey16(kmn)), lmx = h2f(unkey16(kmx));
+    const GroupQ q = make_group(lmn, lmx, QMAX);
+    uint32_t fb[8], fc[8];   // bits of (t - code) * 2^23 + 1.5 * 2^23 and of code + 2^23
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const uint32_t code = quant_code_resid(y[e], q, dm.qmax, rh[e], rl[e]);
-      cb[e >> 2] |= (tv ? code : 0u) << ((e & 3) * 8);
+      const uint32_t x = raw[e >> 1] & ~msk[e >> 1];
+      const float y = h2f((e & 1) ? (x >> 16) : (x & 0xFFFFu));
+      const float tq = __fmul_rn(__fsub_rn(y, q.mn), q.inv);
+      const float c = clamp_f32(rintf(tq), 0.0f, QMAX);
+      fb[e] = __float_as_uint(__builtin_fmaf(tq - c, RESID_FIX, RESID_MAGIC));
+      fc[e] = __float_as_uint(c + 8388608.0f);   // low byte of the mantissa = the code
     }
-    *reinterpret_cast<uint2*>(&stage[tl * PITCH + oc * 8]) = make_uint2(cb[0], cb[1]);
+    // 8 code bytes (0 for a row past the end)
+    const uint32_t cb0 = tv ? resid_lo4(fc[0], fc[1], fc[2], fc[3]) : 0u;
+    const uint32_t cb1 = tv ? resid_lo4(fc[4], fc[5], fc[6], fc[7]) : 0u;
+    *reinterpret_cast<uint2*>(&stage[tl * PITCH + oc * 8]) = make_uint2(cb0, cb1);
     if (tv) {
-      if ((oc & ((g >> 3) - 1)) == 0) sv.sz[((size_t)slab * sv.n_cap + t) * (D / g) + (oc * 8) / g] = group_bits(q);
+      if ((oc & ((g >> 3) - 1)) == 0) sv.sz[((size_t)slab * sv.n_cap + t) * (D >> lg) + ((oc * 8) >> lg)] = group_bits(q);
       if (Rout) {
         const size_t ro = ((size_t)slab * n + t) * D + oc * 8;
         *reinterpret_cast<uint4*>(Rout + ro) =
-            make_uint4(rh[0] | (rh[1] << 16), rh[2] | (rh[3] << 16), rh[4] | (rh[5] << 16), rh[6] | (rh[7] << 16));
-        *reinterpret_cast<uint2*>(Rlo + ro) = make_uint2(rl[0] | (rl[1] << 8) | (rl[2] << 16) | (rl[3] << 24),
-                                                         rl[4] | (rl[5] << 8) | (rl[6] << 16) | (rl[7] << 24));
+            make_uint4(resid_hi2(fb[0], fb[1]), resid_hi2(fb[2], fb[3]), resid_hi2(fb[4], fb[5]), resid_hi2(fb[6], fb[7]));
+        *reinterpret_cast<uint2*>(Rlo + ro) = make_uint2(resid_lo4(fb[0], fb[1], fb[2], fb[3]), resid_lo4(fb[4], fb[5], fb[6], fb[7]));
       }
     }
   }
@@ -176,7 +210,9 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
     block_lds_sync();
     if (tid == 0) {
       const uint32_t tot = wtot[0] + wtot[1];
-      const uint32_t off = atomicAdd(&pool_ctr[b], tot);
+      // a list that fits takes the tile's reserved region; a longer one is allocated behind the regions
+      const uint32_t off = tot <= VPOOL_FIXED ? (uint32_t)(h * sv.ntile_cap + tile) * VPOOL_FIXED
+                                              : (uint32_t)(dm.H * sv.ntile_cap) * VPOOL_FIXED + atomicAdd(&pool_ctr[b], tot);
       sv.sp_table[(size_t)slab * sv.ntile_cap + tile] = make_uint2(off, tot);
       list_off = off;
     }
@@ -184,7 +220,9 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
     if (tid < D) {
       uint32_t off = list_off + (wave == 1 ? wtot[0] : 0u) + inc - cnt;
       uint32_t* pool = sv.sp_pool + (size_t)b * sv.pool_cap;
-      uint32_t* slots = sv.ell + (((size_t)slab * sv.ntile_cap + tile) * D + tid) * ELL_V;
+      uint32_t slot[ELL_V];
+#pragma unroll
+      for (int i = 0; i < ELL_V; ++i) slot[i] = 0u;   // empty slots
       uint32_t s_i = 0;
       for (int half = 0; half < 2; ++half) {
         uint32_t mm = half ? m1 : m0;
@@ -192,9 +230,11 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
           const int bit = __ffs((int)mm) - 1;
           mm &= mm - 1;
           const int tl = half * 32 + bit;
-          const uint32_t hb = X[(size_t)(t0 + tl) * D + tid];
+          const uint32_t hb = oval[tid][tl];
           if (s_i < ELL_V) {
-            slots[s_i] = (uint32_t)tl | ELL_VALID | (hb << 16);
+#pragma unroll
+            for (int i = 0; i < ELL_V; ++i)
+              if (s_i == (uint32_t)i) slot[i] = (uint32_t)tl | ELL_VALID | (hb << 16);
           } else {
             if (off < sv.pool_cap) pool[off] = (uint32_t)(tl * D + tid) | (hb << 16);
             ++off;
@@ -202,14 +242,15 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
           ++s_i;
         }
       }
-      for (; s_i < ELL_V; ++s_i) slots[s_i] = 0u;   // empty slots
+      static_assert(ELL_V == 2, "the channel's slots are stored as one 8-byte word");
+      *reinterpret_cast<uint2*>(sv.ell + (((size_t)slab * sv.ntile_cap + tile) * D + tid) * ELL_V) = make_uint2(slot[0], slot[1]);
     }
   }
 }
 
 // ------------------------------------------------------------------ launchers
 template <int NC>
-static hipError_t launch_vsel(const uint16_t* V, const Dims& dm, int n, int k_top, int k_bot, Thresh* thrV,
+static hipError_t launch_vsel(const uint16_t* V, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrV,
                               hipStream_t st) {
   dim3 grid((n + VSEL_TOKENS - 1) / VSEL_TOKENS, dm.B);
   hipLaunchKernelGGL(v_select_kernel<NC>, grid, dim3(256), 0, st, V, dm.H, n, k_top, k_bot, thrV);
@@ -217,7 +258,7 @@ static hipError_t launch_vsel(const uint16_t* V, const Dims& dm, int n, int k_to
 }
 
 hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                                 int k_bot, Thresh* thrV, uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo,
+                                 int k_bot, ThreshPair* thrV, uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo,
                                  hipStream_t st) {
   if (dm.ppm > 0) {
     const int nc = (dm.H + 3) / 4;
@@ -230,7 +271,10 @@ hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dim
     if (e != hipSuccess) return e;
   }
   dim3 grid((n + TILE - 1) / TILE, dm.B * dm.H);
-  hipLaunchKernelGGL(v_quant_kernel, grid, dim3(256), 0, st, V, sv, dm, n, (const Thresh*)thrV, pool_ctr, Rout, Rlo);
+  if (dm.bits == 2)
+    hipLaunchKernelGGL(v_quant_kernel<2>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, pool_ctr, Rout, Rlo);
+  else
+    hipLaunchKernelGGL(v_quant_kernel<4>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, pool_ctr, Rout, Rlo);
   return hipGetLastError();
 }
 

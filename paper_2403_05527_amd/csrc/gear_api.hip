@@ -52,7 +52,8 @@ Region region_layout(const gear_config& c, bool is_k, int n_cap) {
     r.pool_cap = (uint32_t)D * outlier_count(n_cap, c.outlier_ppm);
     o += up(slabs * (size_t)r.pool_cap * 4);
   } else {
-    r.pool_cap = (uint32_t)n_cap * outlier_count((long long)c.H_kv * D, c.outlier_ppm);
+    r.pool_cap = (uint32_t)c.H_kv * r.ntile_cap * VPOOL_FIXED +   // reserved regions, then the worst case
+                 (uint32_t)n_cap * outlier_count((long long)c.H_kv * D, c.outlier_ppm);
     o += up((size_t)c.B * r.pool_cap * 4);
   }
   r.bytes = o;
@@ -89,8 +90,8 @@ WorkLayout work_layout(const gear_config& c) {
   const int npart = (n_max + 255) / 256;
   const int R = 8;
   size_t o = 0;
-  w.thrK = o; o += up(slabs * D * sizeof(Thresh));
-  w.thrV = o; o += up((size_t)c.B * n_max * sizeof(Thresh));
+  w.thrK = o; o += up(slabs * D * sizeof(ThreshPair));
+  w.thrV = o; o += up((size_t)c.B * n_max * sizeof(ThreshPair));
   w.pool_ctr = o; o += up((slabs + (size_t)c.B) * 4);   // Key counters per slab, then Value counters per batch
   w.Bcur = o; o += up(slabs * D * R * 4);
   w.partial = o; o += up(slabs * (size_t)npart * (D * R + R * R) * 4);
@@ -254,8 +255,8 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   seg_views(cache, a, seg, n, rank, &ks, &vs);
   const uint16_t* Kp = static_cast<const uint16_t*>(K);
   const uint16_t* Vp = static_cast<const uint16_t*>(V);
-  Thresh* thrK = reinterpret_cast<Thresh*>(ws + w.thrK);
-  Thresh* thrV = reinterpret_cast<Thresh*>(ws + w.thrV);
+  ThreshPair* thrK = reinterpret_cast<ThreshPair*>(ws + w.thrK);
+  ThreshPair* thrV = reinterpret_cast<ThreshPair*>(ws + w.thrV);
   uint32_t* pool_ctr = reinterpret_cast<uint32_t*>(ws + w.pool_ctr);
 
   const int kv_k = outlier_count(n, c.outlier_ppm);

@@ -53,6 +53,7 @@ namespace gear {
 
 constexpr int D = 128;      // head dimension
 constexpr int TILE = 64;    // tokens per sparse-list tile
+constexpr int VPOOL_FIXED = 48;   // entries of the reserved list region of one Value (head, tile)
 constexpr int ELL_K = 4;    // fixed outlier slots per Key token row
 constexpr int ELL_V = 2;    // fixed outlier slots per Value channel and tile
 constexpr uint32_t ELL_VALID = 0x8000u;
@@ -105,7 +106,13 @@ struct Dims {
 //                 the outliers that found no slot.
 //  sp_pool      : u32 entries (low 16 bits: (t % 64)*128 + c, high 16: fp16
 //                 value).  Keys: one pool per slab, lists ordered (t, c);
-//                 Values: one pool per batch element, lists ordered (c, t).
+//                 Values: one pool per batch element, lists ordered (c, t).  A Value
+//                 pool starts with one reserved region of VPOOL_FIXED entries per
+//                 (head, tile), at (head * ntile_cap + tile) * VPOOL_FIXED: a list that
+//                 fits lies there and needs no allocation; longer lists are
+//                 allocated behind the reserved regions from a counter per batch
+//                 element (every tile of 32 heads bumping one counter costs more
+//                 than the rest of the kernel's list handling).
 struct SegView {
   uint32_t* codes;
   uint32_t* sz;
@@ -282,6 +289,10 @@ __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 constexpr int DPP_XOR1 = 0xB1;         // quad_perm [1,0,3,2]
 constexpr int DPP_XOR2 = 0x4E;         // quad_perm [2,3,0,1]

@@ -16,14 +16,14 @@ struct ChunkSet {
 
 hipError_t launch_fill_u32(uint32_t* p, uint32_t v, size_t count, hipStream_t st);
 
-hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, Thresh* thrK,
+hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
                            hipStream_t st);
 // Rout / Rlo (nullable): [slab][n][128] high 16 and low 8 bits of the residual R = X - S - D in
 // units of its group's scale, 24-bit fixed point (2^-23)
-hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const Thresh* thrK,
+hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const ThreshPair* thrK,
                           uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st);
 hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                                 int k_bot, Thresh* thrV, uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo,
+                                 int k_bot, ThreshPair* thrV, uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo,
                                  hipStream_t st);
 
 int pi_padded_rank(int rank);

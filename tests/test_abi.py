@@ -55,13 +55,14 @@ def test_arena_accounting_matches_algorithmic_bytes(lib):
     """Arena size = the algorithmic compressed size (codes + scale/zero + factors +
     4-byte sparse entries, the lists sized for the worst case) + the fixed outlier
     slots (4 per Key token row, 2 per Value channel and 64-token tile, 4 bytes
-    each) + small tables and alignment."""
+    each) + the reserved list regions of the Value tiles (48 entries each) + small
+    tables and alignment."""
     c = gb.make_config(16, 32, 32, 2, 64, 20000, 20, 4096, 0, 4)
     a, _ = gb.gear_cache_bytes(c)
     slabs, n = 16 * 32, 4096
     algo = 2 * slabs * (n * 128 * 2 // 8 + 4 * (n // 64) * 128 + 2 * n * 4 + 2 * 128 * 4) \
         + 4 * (slabs * 128 * 82 + 16 * n * 82)
-    slots = slabs * (n * 4 * 4 + (n // 64) * 128 * 2 * 4)
+    slots = slabs * (n * 4 * 4 + (n // 64) * 128 * 2 * 4 + (n // 64) * 48 * 4)
     assert algo + slots <= a <= (algo + slots) * 1.03
 
 
