@@ -27,7 +27,7 @@ struct RegSource {  // the vector lives in the wave's registers
 };
 
 // ------------------------------------------------------------------ K select
-// 1-D grid of (128/CB) * B*H blocks of 64 * min(CB, 4) threads; LDS: 512 u32 per wave + [CB][n_pad] keys.
+// 1-D grid of (128/CB) * B*H blocks of 64 * min(CB, 4) threads; LDS: SELECT_LDS_WORDS u32 per wave + [CB][n_pad] keys.
 // Consecutive block ids go round-robin to the chip's 8 XCDs (each with its own L2), so
 // the id is decoded with the column block fastest INSIDE one XCD: the 128/CB blocks
 // that share the 128-byte lines of one slab then meet in one L2 instead of eight.
@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
                                                        ThreshPair* __restrict__ thrK) {
   GEAR_DYN_LDS(smem_raw);
   uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem_raw);
-  uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + (blockDim.x >> 6) * 512 * sizeof(uint32_t));
+  uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + (blockDim.x >> 6) * SELECT_LDS_WORDS * sizeof(uint32_t));
   const int ncb = D / CB;
   int slab, cb;
   if ((nslab & 7) == 0) {
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
     const int v = it * NW + wave;
     const bool active = v < CB;
     LdsSource src{tile + (size_t)(active ? v : 0) * n_pad, n_pad};
-    const Thresh th = wave_select(src, n, k_top, k_bot, hist_all + wave * 512, active);
+    const Thresh th = wave_select(src, n, k_top, k_bot, hist_all + wave * SELECT_LDS_WORDS, active);
     if (active && lane == 0) thrK[(size_t)slab * D + cb * CB + v] = pack_thresh(th);
   }
 }
@@ -374,7 +374,7 @@ hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, 
   const int n_pad = (n + 7) & ~7;
   const int cb = k_select_cb(n_pad);
   const int nw = cb < 4 ? cb : 4;   // waves per block: one vector each per round
-  const size_t lds = (size_t)nw * 512 * sizeof(uint32_t) + (size_t)cb * n_pad * 2;
+  const size_t lds = (size_t)nw * SELECT_LDS_WORDS * sizeof(uint32_t) + (size_t)cb * n_pad * 2;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;

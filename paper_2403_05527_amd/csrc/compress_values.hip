@@ -26,7 +26,7 @@ constexpr int VSEL_TOKENS = 16;  // tokens per block (4 per wave)
 template <int NC>
 __global__ __launch_bounds__(256) void v_select_kernel(const uint16_t* __restrict__ V, int H, int n, int k_top,
                                                        int k_bot, ThreshPair* __restrict__ thrV) {
-  __shared__ uint32_t hist[4 * 512];
+  __shared__ uint32_t hist[4 * SELECT_LDS_WORDS];
   const int b = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int hsub = lane >> 4, oc = lane & 15;
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void v_select_kernel(const uint16_t* __restric
       }
     }
     RegSource<NC> src{x};
-    const Thresh th = wave_select(src, N, k_top, k_bot, hist + wave * 512, tvalid);
+    const Thresh th = wave_select(src, N, k_top, k_bot, hist + wave * SELECT_LDS_WORDS, tvalid);
     if (tvalid && lane == 0) thrV[(size_t)b * n + t] = pack_thresh(th);
   }
 }

@@ -131,7 +131,71 @@ __device__ __forceinline__ int find_kth_equal(const Src& src, int N, int nch, ui
   return found;
 }
 
-// A wave with nothing to do passes active = false.  hist: 512 u32 of LDS private to
+// The same for both thresholds at once when few entries equal them (the usual case):
+// every entry equal to tau_a / tau_b puts its index on a list in LDS (lists[0..63],
+// lists[64..127], counters at lists[128], lists[129]); the m-th smallest index of a list
+// of at most 64 is then found by ranking.  m_a / m_b = 0: that side is not wanted.
+template <class Src>
+__device__ __forceinline__ void find_kth_equal_pair(const Src& src, int N, int nch, uint32_t tau_a, uint32_t m_a,
+                                                    uint32_t tau_b, uint32_t m_b, uint32_t* lists, int& idx_a,
+                                                    int& idx_b) {
+  const int lane = lane_id();
+  if (lane < 2) lists[128 + lane] = 0u;
+  wave_lds_sync();
+  const uint32_t ta2 = tau_a | (tau_a << 16), tb2 = tau_b | (tau_b << 16);
+  for_each_chunk(src, nch, [&](int ch, const uint4& v) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // a word with a half equal to tau has a zero half after the xor
+      const uint32_t za = w[j] ^ ta2, zb = w[j] ^ tb2;
+      const uint32_t hit = (m_a ? ((za - 0x00010001u) & ~za & 0x80008000u) : 0u) |
+                           (m_b ? ((zb - 0x00010001u) & ~zb & 0x80008000u) : 0u);
+      if (hit) {   // rare
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int idx = ch * 512 + lane * 8 + 2 * j + h;
+          const uint32_t k = (w[j] >> (16 * h)) & 0xFFFFu;
+          if (idx < N) {
+            if (m_a && k == tau_a) {
+              const uint32_t pos = atomicAdd(&lists[128], 1u);
+              if (pos < 64u) lists[pos] = (uint32_t)idx;
+            }
+            if (m_b && k == tau_b) {
+              const uint32_t pos = atomicAdd(&lists[129], 1u);
+              if (pos < 64u) lists[64 + pos] = (uint32_t)idx;
+            }
+          }
+        }
+      }
+    }
+  });
+  wave_lds_sync();
+  const uint32_t ca = lists[128] < 64u ? lists[128] : 64u, cb = lists[129] < 64u ? lists[129] : 64u;
+  const uint32_t mine_a = lane < (int)ca ? lists[lane] : 0xFFFFFFFFu;
+  const uint32_t mine_b = lane < (int)cb ? lists[64 + lane] : 0xFFFFFFFFu;
+  uint32_t rank_a = 0, rank_b = 0;
+  const uint32_t cmax = ca > cb ? ca : cb;
+  for (uint32_t j = 0; j < cmax; ++j) {   // wave-uniform trip count
+    rank_a += (uint32_t)__shfl(mine_a, (int)j, 64) < mine_a ? 1u : 0u;
+    rank_b += (uint32_t)__shfl(mine_b, (int)j, 64) < mine_b ? 1u : 0u;
+  }
+  idx_a = INT_MAX;
+  idx_b = INT_MAX;
+  if (m_a) {
+    const unsigned long long bm = __ballot(lane < (int)ca && rank_a + 1u == m_a);
+    if (bm) idx_a = (int)__shfl(mine_a, (int)__ffsll((long long)bm) - 1, 64);
+  }
+  if (m_b) {
+    const unsigned long long bm = __ballot(lane < (int)cb && rank_b + 1u == m_b);
+    if (bm) idx_b = (int)__shfl(mine_b, (int)__ffsll((long long)bm) - 1, 64);
+  }
+  wave_lds_sync();
+}
+
+constexpr int SELECT_LDS_WORDS = 512;   // LDS words wave_select needs per wave
+
+// A wave with nothing to do passes active = false.  hist: SELECT_LDS_WORDS u32 of LDS private to
 // the calling wave; only wave-level synchronisation is used, so the waves of a block
 // run their selections independently of each other.
 template <class Src>
@@ -166,19 +230,25 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
   wave_lds_sync();
 
   // ---- level 2: histograms of the low key byte inside the two boundary bins
+  // one add per entry and no branch: entries of neither bin (and the padding past N)
+  // add 0
   for (int i = lane; i < 512; i += 64) hist[i] = 0u;
   wave_lds_sync();
   for_each_chunk(src, nch, [&](int ch, const uint4& v) {
     const int base = ch * 512 + lane * 8;
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (base + e < N) {
-        const uint32_t k = slot16(v, e);
-        if ((int)(k >> 8) == bin_t) atomicAdd(&hist[k & 255u], 1u);
-        if ((int)(k >> 8) == bin_b) atomicAdd(&hist[256 + (k & 255u)], 1u);
-      }
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t k = slot16(v, e);
+      const int hi = (base + e < N) ? (int)(k >> 8) : -2;
+      const bool in_t = hi == bin_t, in_b = hi == bin_b;
+      atomicAdd(&hist[(in_t ? 0u : 256u) + (k & 255u)], (in_t || in_b) ? 1u : 0u);
+    }
   });
   wave_lds_sync();
+  if (bin_t == bin_b && bin_t >= 0) {   // one bin holds both thresholds: its entries count for both
+    for (int i = lane; i < 256; i += 64) hist[256 + i] = hist[i];
+    wave_lds_sync();
+  }
   uint32_t need_eq_t = 0, cnt_eq_t = 0, need_eq_b = 0, cnt_eq_b = 0;
   if (active && k_top > 0) {
     int lo;
@@ -201,7 +271,20 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
   // ---- ties: among entries equal to the threshold the lowest indices win;
   // when top and bottom share one threshold value the bottom set continues
   // where the top set stopped.
-  if (active && k_top > 0) {
+  const bool want_t = active && k_top > 0 && need_eq_t != cnt_eq_t;
+  const bool want_b = active && k_bot > 0 && need_eq_b != cnt_eq_b;
+  const bool shared = active && k_top > 0 && k_bot > 0 && th.tau_top == th.tau_bot;
+  if (!shared && cnt_eq_t <= 64u && cnt_eq_b <= 64u) {
+    if (want_t || want_b) {   // wave-uniform
+      int it, ib;
+      find_kth_equal_pair(src, N, nch, th.tau_top, want_t ? need_eq_t : 0u, th.tau_bot, want_b ? need_eq_b : 0u, hist,
+                          it, ib);
+      if (want_t) th.i_top = it;
+      if (want_b) th.i_bot = ib;
+    }
+    if (active && k_top > 0 && !want_t) th.i_top = INT_MAX;
+    if (active && k_bot > 0 && !want_b) th.i_bot = INT_MAX;
+  } else if (active && k_top > 0) {
     if (k_bot > 0 && th.tau_top == th.tau_bot) {
       th.i_top = find_kth_equal(src, N, nch, th.tau_top, need_eq_t);
       th.l_bot = th.i_top;

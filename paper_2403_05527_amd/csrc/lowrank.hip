@@ -156,6 +156,7 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
   const int r0 = tid >> 4, oc = tid & 15;
   const uint16_t* Xs = Rres + (size_t)slab * n * D;
   const uint8_t* Xl = Rlo + (size_t)slab * n * D;
+  const int lg = 31 - __clz(g);   // g is a power of two
 
   float bc[8][R];
 #pragma unroll
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
         sk0[gs] = make_uint4(0, 0, 0, 0);
         sk1[gs] = make_uint4(0, 0, 0, 0);
         if ((gs << ush) < UN && t < n) {
-          const uint4* p = reinterpret_cast<const uint4*>(sv.sz + ((size_t)slab * sv.ng_cap + t / g) * D + oc * 8);
+          const uint4* p = reinterpret_cast<const uint4*>(sv.sz + ((size_t)slab * sv.ng_cap + (t >> lg)) * D + oc * 8);
           sk0[gs] = p[0];
           sk1[gs] = p[1];
         }
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
         xv[u] = *reinterpret_cast<const uint4*>(Xs + (size_t)t * D + oc * 8);
         xl[u] = *reinterpret_cast<const uint2*>(Xl + (size_t)t * D + oc * 8);
         if (!IS_K)   // scale of (token t, the channel group of my 8 channels)
-          svw[u] = sv.sz[((size_t)slab * sv.n_cap + t) * (D / g) + (oc * 8) / g];
+          svw[u] = sv.sz[((size_t)slab * sv.n_cap + t) * (D >> lg) + ((oc * 8) >> lg)];
       }
     }
     float dlk[IS_K ? 2 : 1][IS_K ? 8 : 1], dlv[UN];
