@@ -155,6 +155,18 @@ __device__ __forceinline__ uint32_t key16x2(uint32_t h2) {
   const uint32_t x = h2 ^ (s | 0x80008000u);                                                // negative: ~h, positive: h + 0x8000
   return __builtin_bit_cast(uint32_t, __builtin_bit_cast(k16x2_t, x) - __builtin_bit_cast(k16x2_t, s));   // negative: ~h + 1
 }
+// Loads of data that is read once per kernel and is larger than the caches
+// (non-temporal: the lines are not kept).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 load_stream8(const void* p) {
+  const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+  return make_uint2(v.x, v.y);
+}
 // fp16 bit pattern of a key (the key of +-0 gives +0)
 __device__ __forceinline__ uint32_t unkey16(uint32_t k) {
   return (k & 0x8000u) ? (k & 0x7FFFu) : ((0u - k) & 0xFFFFu);
@@ -274,6 +286,12 @@ __device__ __forceinline__ uint32_t resid_lo4(uint32_t b0, uint32_t b1, uint32_t
   return GEAR_BYTE_PERM(GEAR_BYTE_PERM(b3, b2, 0x0c0c0400u), GEAR_BYTE_PERM(b1, b0, 0x0c0c0400u), 0x05040100u);
 }
 __device__ __forceinline__ float clamp_f32(float x, float lo, float hi) { return GEAR_FMED3(x, lo, hi); }
+// Entry e (0..3) of a word of four low bytes and of the word of two high halves that holds
+// it (e & 1): the remainder times 2^31, exactly (one byte permute and one conversion).
+__device__ __forceinline__ float resid_x2p31(uint32_t hi2, uint32_t lo4, int e) {   // e: a constant after unrolling
+  const uint32_t sel = 0x0cu | ((uint32_t)(e & 3) << 8) | ((4u + 2u * (e & 1)) << 16) | ((5u + 2u * (e & 1)) << 24);
+  return (float)(int)GEAR_BYTE_PERM(hi2, lo4, sel);
+}
 __device__ __forceinline__ float resid_to_float(uint32_t hi16, uint32_t lo8) {  // u, not yet times delta
   return (float)((int)(short)(hi16 & 0xFFFFu) * 256 + (int)(lo8 & 0xFFu)) * (1.0f / RESID_FIX);
 }

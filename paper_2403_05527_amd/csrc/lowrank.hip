@@ -18,6 +18,7 @@
 namespace gear {
 
 constexpr int PT = 256;  // tokens per sweep block
+constexpr float RESID_UNIT = 1.0f / 2147483648.0f;   // 2^-31: the stored remainder is read as an integer times 2^8
 
 template <typename T>
 __device__ __forceinline__ T block128_sum(T v, T* red /* >= 2 */) {
@@ -143,10 +144,12 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
 // grid (ceil(n/PT), B*H), block 256; thread (r0 = tid/16, oc = tid%16) owns
 // channels 8*oc..+7 of rows pt*PT + r0 + 16*k of the stored residual
 // (u = R / scale as 16-bit fixed point; the scale is applied per group here).
-template <bool IS_K, int R>
+// LAST: the final round, which also leaves a_t and the Gram matrix (its extra state costs
+// one resident block per CU, so the rounds before it are compiled without).
+template <bool IS_K, int R, bool LAST>
 __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_kernel(const uint16_t* __restrict__ Rres,
                                                        const uint8_t* __restrict__ Rlo, SegView sv, int g, int n,
-                                                       const float* __restrict__ Bcur, int last,
+                                                       const float* __restrict__ Bcur,
                                                        float* __restrict__ partial, int npart,
                                                        float* __restrict__ Atmp) {
   __shared__ float red[4][D * R];
@@ -204,8 +207,8 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
       xl[u] = make_uint2(0, 0);
       svw[u] = 0u;
       if (t < n) {
-        xv[u] = *reinterpret_cast<const uint4*>(Xs + (size_t)t * D + oc * 8);
-        xl[u] = *reinterpret_cast<const uint2*>(Xl + (size_t)t * D + oc * 8);
+        xv[u] = load_stream16(Xs + (size_t)t * D + oc * 8);
+        xl[u] = load_stream8(Xl + (size_t)t * D + oc * 8);
         if (!IS_K)   // scale of (token t, the channel group of my 8 channels)
           svw[u] = sv.sz[((size_t)slab * sv.n_cap + t) * (D >> lg) + ((oc * 8) >> lg)];
       }
@@ -216,24 +219,24 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
       for (int gs = 0; gs < 2; ++gs) {
         const uint32_t sb[8] = {sk0[gs].x, sk0[gs].y, sk0[gs].z, sk0[gs].w, sk1[gs].x, sk1[gs].y, sk1[gs].z, sk1[gs].w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dlk[gs][IS_K ? e : 0] = h2f(sb[e] & 0xFFFFu);
+        for (int e = 0; e < 8; ++e) dlk[gs][IS_K ? e : 0] = h2f(sb[e] & 0xFFFFu) * RESID_UNIT;
       }
     }
 #pragma unroll
-    for (int u = 0; u < UN; ++u) dlv[u] = h2f(svw[u] & 0xFFFFu);
+    for (int u = 0; u < UN; ++u) dlv[u] = h2f(svw[u] & 0xFFFFu) * RESID_UNIT;
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const int t = pt * PT + r0 + 16 * (k0 + u);
       const uint32_t w[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
       const uint32_t wl[2] = {xl[u].x, xl[u].y};
+      // the remainder times 2^31 (exact), times the scale with the 2^-31 folded in
       float res[8];
       float a[R];
 #pragma unroll
       for (int r = 0; r < R; ++r) a[r] = 0.0f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        res[e] = resid_to_float(w[e >> 1] >> ((e & 1) * 16), wl[e >> 2] >> ((e & 3) * 8)) *
-                 (IS_K ? dlk[IS_K ? ((u >> ush) & 1) : 0][IS_K ? e : 0] : dlv[u]);
+        res[e] = resid_x2p31(w[e >> 1], wl[e >> 2], e) * (IS_K ? dlk[IS_K ? ((u >> ush) & 1) : 0][IS_K ? e : 0] : dlv[u]);
 #pragma unroll
         for (int r = 0; r < R; ++r) a[r] += res[e] * bc[e][r];
       }
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
       for (int e = 0; e < 8; ++e)
 #pragma unroll
         for (int r = 0; r < R; ++r) acc[e][r] += res[e] * a[r];
-      if (last) {
+      if (LAST) {
         if (oc == 0 && t < n) {
 #pragma unroll
           for (int r = 0; r < R; ++r) Atmp[((size_t)slab * n + t) * R + r] = a[r];
@@ -289,7 +292,7 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
   block_lds_sync();
   float* out = partial + ((size_t)slab * npart + pt) * (D * R + R * R);
   for (int i = tid; i < D * R; i += 256) out[i] = red[0][i] + red[1][i] + red[2][i] + red[3][i];
-  if (tid < R * R) out[D * R + tid] = last ? (redg[0][tid] + redg[1][tid] + redg[2][tid] + redg[3][tid]) : 0.0f;
+  if (tid < R * R) out[D * R + tid] = LAST ? (redg[0][tid] + redg[1][tid] + redg[2][tid] + redg[3][tid]) : 0.0f;
 }
 
 // grid (ceil(n/256), B*H), block 256: one token per thread.
@@ -324,12 +327,15 @@ static hipError_t run_pi(bool is_k, const uint16_t* Rres, const uint8_t* Rlo, co
                      0, iters == 1 ? 1 : 0, 0, Bcur, cmat, sv);
   for (int l = 0; l < iters; ++l) {
     const int last = (l == iters - 1);
-    if (is_k)
-      hipLaunchKernelGGL((pi_sweep_kernel<true, R>), dim3(npart, slabs), dim3(256), 0, st, Rres, Rlo, sv, dm.g, n,
-                         (const float*)Bcur, last, partial, npart, Atmp);
+    const dim3 grid(npart, slabs);
+    if (is_k && last)
+      hipLaunchKernelGGL((pi_sweep_kernel<true, R, true>), grid, dim3(256), 0, st, Rres, Rlo, sv, dm.g, n, (const float*)Bcur, partial, npart, Atmp);
+    else if (is_k)
+      hipLaunchKernelGGL((pi_sweep_kernel<true, R, false>), grid, dim3(256), 0, st, Rres, Rlo, sv, dm.g, n, (const float*)Bcur, partial, npart, Atmp);
+    else if (last)
+      hipLaunchKernelGGL((pi_sweep_kernel<false, R, true>), grid, dim3(256), 0, st, Rres, Rlo, sv, dm.g, n, (const float*)Bcur, partial, npart, Atmp);
     else
-      hipLaunchKernelGGL((pi_sweep_kernel<false, R>), dim3(npart, slabs), dim3(256), 0, st, Rres, Rlo, sv, dm.g, n,
-                         (const float*)Bcur, last, partial, npart, Atmp);
+      hipLaunchKernelGGL((pi_sweep_kernel<false, R, false>), grid, dim3(256), 0, st, Rres, Rlo, sv, dm.g, n, (const float*)Bcur, partial, npart, Atmp);
     hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, (const float*)nullptr, sv.rank,
                        (const float*)partial, npart, (l == iters - 2) ? 1 : 0, last, Bcur, cmat, sv);
   }
