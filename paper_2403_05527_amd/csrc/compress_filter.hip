@@ -267,10 +267,10 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
           }
         }
         if (Rout) {
-          *reinterpret_cast<uint4*>(Rout + ((size_t)slab * n + t) * D + oc * 8) =
-              make_uint4(resid_hi2(fb[0], fb[1]), resid_hi2(fb[2], fb[3]), resid_hi2(fb[4], fb[5]), resid_hi2(fb[6], fb[7]));
-          *reinterpret_cast<uint2*>(Rlo + ((size_t)slab * n + t) * D + oc * 8) =
-              make_uint2(resid_lo4(fb[0], fb[1], fb[2], fb[3]), resid_lo4(fb[4], fb[5], fb[6], fb[7]));
+          store_stream16(Rout + ((size_t)slab * n + t) * D + oc * 8,
+                         make_uint4(resid_hi2(fb[0], fb[1]), resid_hi2(fb[2], fb[3]), resid_hi2(fb[4], fb[5]), resid_hi2(fb[6], fb[7])));
+          store_stream8(Rlo + ((size_t)slab * n + t) * D + oc * 8,
+                        make_uint2(resid_lo4(fb[0], fb[1], fb[2], fb[3]), resid_lo4(fb[4], fb[5], fb[6], fb[7])));
         }
         if (BITS == 4) {
           crow[(size_t)t * dm.wpr + oc] = (uint32_t)cw0 | ((uint32_t)cw1 << 16);

@@ -164,9 +164,8 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
       if ((oc & ((g >> 3) - 1)) == 0) sv.sz[((size_t)slab * sv.n_cap + t) * (D >> lg) + ((oc * 8) >> lg)] = group_bits(q);
       if (Rout) {
         const size_t ro = ((size_t)slab * n + t) * D + oc * 8;
-        *reinterpret_cast<uint4*>(Rout + ro) =
-            make_uint4(resid_hi2(fb[0], fb[1]), resid_hi2(fb[2], fb[3]), resid_hi2(fb[4], fb[5]), resid_hi2(fb[6], fb[7]));
-        *reinterpret_cast<uint2*>(Rlo + ro) = make_uint2(resid_lo4(fb[0], fb[1], fb[2], fb[3]), resid_lo4(fb[4], fb[5], fb[6], fb[7]));
+        store_stream16(Rout + ro, make_uint4(resid_hi2(fb[0], fb[1]), resid_hi2(fb[2], fb[3]), resid_hi2(fb[4], fb[5]), resid_hi2(fb[6], fb[7])));
+        store_stream8(Rlo + ro, make_uint2(resid_lo4(fb[0], fb[1], fb[2], fb[3]), resid_lo4(fb[4], fb[5], fb[6], fb[7])));
       }
     }
   }

@@ -155,8 +155,8 @@ __device__ __forceinline__ uint32_t key16x2(uint32_t h2) {
   const uint32_t x = h2 ^ (s | 0x80008000u);                                                // negative: ~h, positive: h + 0x8000
   return __builtin_bit_cast(uint32_t, __builtin_bit_cast(k16x2_t, x) - __builtin_bit_cast(k16x2_t, s));   // negative: ~h + 1
 }
-// Loads of data that is read once per kernel and is larger than the caches
-// (non-temporal: the lines are not kept).
+// Loads and stores of data that is touched once per kernel and is larger than the
+// caches (non-temporal: the lines are not kept).
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint4 load_stream16(const void* p) {
@@ -166,6 +166,14 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
 __device__ __forceinline__ uint2 load_stream8(const void* p) {
   const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
   return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ void store_stream16(void* p, uint4 v) {
+  u32x4_t x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<u32x4_t*>(p));
+}
+__device__ __forceinline__ void store_stream8(void* p, uint2 v) {
+  u32x2_t x = {v.x, v.y};
+  __builtin_nontemporal_store(x, reinterpret_cast<u32x2_t*>(p));
 }
 // fp16 bit pattern of a key (the key of +-0 gives +0)
 __device__ __forceinline__ uint32_t unkey16(uint32_t k) {
