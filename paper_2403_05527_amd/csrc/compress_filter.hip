@@ -31,13 +31,16 @@ struct RegSource {  // the vector lives in the wave's registers
 // Consecutive block ids go round-robin to the chip's 8 XCDs (each with its own L2), so
 // the id is decoded with the column block fastest INSIDE one XCD: the 128/CB blocks
 // that share the 128-byte lines of one slab then meet in one L2 instead of eight.
+// CB (channels per block, a power of two) is a template parameter: the row pieces of the
+// transposing load are then indexed with shifts and loaded with one fixed instruction.
+template <int CB>
 __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restrict__ K, int n, int n_pad,
-                                                       int CB, int nslab, int k_top, int k_bot,
+                                                       int nslab, int k_top, int k_bot,
                                                        ThreshPair* __restrict__ thrK) {
   GEAR_DYN_LDS(smem_raw);
   uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem_raw);
   uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + (blockDim.x >> 6) * SELECT_LDS_WORDS * sizeof(uint32_t));
-  const int ncb = D / CB;
+  constexpr int ncb = D / CB;
   int slab, cb;
   if ((nslab & 7) == 0) {
     const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
@@ -53,8 +56,8 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
 
   // transpose-load the [n x CB] column block so every vector is contiguous; a
   // thread has UNR row segments in flight at a time
-  const int VW = CB < 8 ? CB : 8;   // fp16 values per row segment
-  const int U = CB / VW;
+  constexpr int VW = CB < 8 ? CB : 8;   // fp16 values per row segment
+  constexpr int U = CB / VW;
   {
     constexpr int UNR = 8;
     const int total = n * U;
@@ -369,18 +372,32 @@ static int k_select_cb(int n_pad) {
   return cb;
 }
 
+template <int CB>
+static hipError_t launch_k_select_cb(const uint16_t* K, const Dims& dm, int n, int n_pad, int k_top, int k_bot,
+                                     ThreshPair* thrK, hipStream_t st) {
+  constexpr int nw = CB < 4 ? CB : 4;   // waves per block: one vector each per round
+  const size_t lds = (size_t)nw * SELECT_LDS_WORDS * sizeof(uint32_t) + (size_t)CB * n_pad * 2;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel<CB>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  dim3 grid((D / CB) * dm.B * dm.H);
+  hipLaunchKernelGGL(k_select_kernel<CB>, grid, dim3(64 * nw), lds, st, K, n, n_pad, dm.B * dm.H, k_top, k_bot, thrK);
+  return hipGetLastError();
+}
+
 hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
                            hipStream_t st) {
   const int n_pad = (n + 7) & ~7;
-  const int cb = k_select_cb(n_pad);
-  const int nw = cb < 4 ? cb : 4;   // waves per block: one vector each per round
-  const size_t lds = (size_t)nw * SELECT_LDS_WORDS * sizeof(uint32_t) + (size_t)cb * n_pad * 2;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
-  dim3 grid((D / cb) * dm.B * dm.H);
-  hipLaunchKernelGGL(k_select_kernel, grid, dim3(64 * nw), lds, st, K, n, n_pad, cb, dm.B * dm.H, k_top, k_bot, thrK);
-  return hipGetLastError();
+  switch (k_select_cb(n_pad)) {
+    case 128: return launch_k_select_cb<128>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
+    case 64: return launch_k_select_cb<64>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
+    case 32: return launch_k_select_cb<32>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
+    case 16: return launch_k_select_cb<16>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
+    case 8: return launch_k_select_cb<8>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
+    case 4: return launch_k_select_cb<4>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
+    case 2: return launch_k_select_cb<2>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
+    default: return launch_k_select_cb<1>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
+  }
 }
 
 template <int G>
