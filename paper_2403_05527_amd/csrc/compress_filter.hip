@@ -54,52 +54,52 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
   const int NT = blockDim.x, NW = NT >> 6;   // 64 threads per vector in flight
   const uint16_t* X = K + (size_t)slab * n * D + cb * CB;
 
-  // transpose-load the [n x CB] column block so every vector is contiguous; a
-  // thread has UNR row segments in flight at a time
+  // transpose-load the [n x CB] column block so every vector is contiguous: a thread takes
+  // one row segment (VW channels) of 8 consecutive rows, all 8 loads in flight, turns the
+  // values into keys, transposes the 8 x VW block in registers (one byte permute per
+  // output word) and stores 8 tokens of a channel with one 16-byte LDS write.  Rows past
+  // n get key 0, so stray lanes of the selection read defined data.
   constexpr int VW = CB < 8 ? CB : 8;   // fp16 values per row segment
-  constexpr int U = CB / VW;
+  constexpr int U = CB / VW;            // row segments per row (a power of two)
+  constexpr int NWD = VW >= 2 ? VW / 2 : 1;
   {
-    constexpr int UNR = 8;
-    const int total = n * U;
-    for (int base = 0; base < total; base += NT * UNR) {
-      uint4 q[UNR];
+    const int ngrp = (n_pad >> 3) * U;
+    for (int gidx = tid; gidx < ngrp; gidx += NT) {
+      const int rg = gidx / U, u = gidx - rg * U;
+      const int row0 = rg * 8;
+      uint32_t w[8][NWD];
 #pragma unroll
-      for (int k = 0; k < UNR; ++k) {
-        const int idx = base + k * NT + tid;
-        q[k] = make_uint4(0, 0, 0, 0);
-        if (idx < total) {
-          const int row = idx / U, u = idx - row * U;
-          const uint16_t* p = X + (size_t)row * D + u * VW;
+      for (int k = 0; k < 8; ++k) {
+#pragma unroll
+        for (int j = 0; j < NWD; ++j) w[k][j] = 0u;
+        if (row0 + k < n) {
+          const uint16_t* p = X + (size_t)(row0 + k) * D + u * VW;
           if (VW == 8) {
-            q[k] = *reinterpret_cast<const uint4*>(p);
+            const uint4 t4 = *reinterpret_cast<const uint4*>(p);
+            w[k][0] = t4.x; w[k][NWD > 1 ? 1 : 0] = t4.y; w[k][NWD > 2 ? 2 : 0] = t4.z; w[k][NWD > 3 ? 3 : 0] = t4.w;
           } else if (VW == 4) {
             const uint2 t2 = *reinterpret_cast<const uint2*>(p);
-            q[k].x = t2.x; q[k].y = t2.y;
+            w[k][0] = t2.x; w[k][NWD > 1 ? 1 : 0] = t2.y;
           } else if (VW == 2) {
-            q[k].x = *reinterpret_cast<const uint32_t*>(p);
+            w[k][0] = *reinterpret_cast<const uint32_t*>(p);
           } else {
-            q[k].x = *p;
+            w[k][0] = *p;
           }
         }
       }
 #pragma unroll
-      for (int k = 0; k < UNR; ++k) {
-        const int idx = base + k * NT + tid;
-        if (idx < total) {
-          const int row = idx / U, u = idx - row * U;
-          const uint32_t w[4] = {key16x2(q[k].x), key16x2(q[k].y), key16x2(q[k].z), key16x2(q[k].w)};
-          uint16_t* dst = tile + (size_t)(u * VW) * n_pad + row;
+      for (int k = 0; k < 8; ++k)
 #pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (e < VW) dst[(size_t)e * n_pad] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));   // keys, not values
-        }
+        for (int j = 0; j < NWD; ++j) w[k][j] = (row0 + k < n) ? key16x2(w[k][j]) : 0u;
+#pragma unroll
+      for (int c = 0; c < VW; ++c) {
+        const int j = c >> 1;
+        const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;   // the high / the low halves of two words
+        const uint4 o = make_uint4(GEAR_BYTE_PERM(w[1][j], w[0][j], sel), GEAR_BYTE_PERM(w[3][j], w[2][j], sel),
+                                   GEAR_BYTE_PERM(w[5][j], w[4][j], sel), GEAR_BYTE_PERM(w[7][j], w[6][j], sel));
+        *reinterpret_cast<uint4*>(tile + (size_t)(u * VW + c) * n_pad + row0) = o;
       }
     }
-  }
-  // zero the padding so stray lanes read defined data
-  for (int idx = tid; idx < CB * (n_pad - n); idx += NT) {
-    const int c = idx / (n_pad - n), r = idx - c * (n_pad - n);
-    tile[(size_t)c * n_pad + n + r] = 0;
   }
   block_lds_sync();
 
