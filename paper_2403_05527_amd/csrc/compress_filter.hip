@@ -108,7 +108,8 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
     const int v = it * NW + wave;
     const bool active = v < CB;
     LdsSource src{tile + (size_t)(active ? v : 0) * n_pad, n_pad};
-    const Thresh th = wave_select(src, n, k_top, k_bot, hist_all + wave * SELECT_LDS_WORDS, active);
+    const Thresh th = n <= 64 ? wave_select_small(src.base, n, k_top, k_bot, active)
+                              : wave_select(src, n, k_top, k_bot, hist_all + wave * SELECT_LDS_WORDS, active);
     if (active && lane == 0) thrK[(size_t)slab * D + cb * CB + v] = pack_thresh(th);
   }
 }
@@ -366,9 +367,12 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
 
 // ------------------------------------------------------------------ launchers
 constexpr size_t KSEL_TILE_BYTES = 32768;   // LDS tile of one block: 4 blocks per CU; smaller tiles mean 4-byte row pieces, measured slower
-static int k_select_cb(int n_pad) {
+static int k_select_cb(int n_pad, int slabs) {
   int cb = 128;
   while (cb > 1 && (size_t)cb * n_pad * 2 > KSEL_TILE_BYTES) cb >>= 1;
+  // short segments (a flushed buffer): more, smaller blocks, so that the vectors are selected
+  // side by side instead of 32 after another in each wave
+  while (cb > 4 && (128 / cb) * slabs < 4096) cb >>= 1;
   return cb;
 }
 
@@ -388,7 +392,7 @@ static hipError_t launch_k_select_cb(const uint16_t* K, const Dims& dm, int n, i
 hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
                            hipStream_t st) {
   const int n_pad = (n + 7) & ~7;
-  switch (k_select_cb(n_pad)) {
+  switch (k_select_cb(n_pad, dm.B * dm.H)) {
     case 128: return launch_k_select_cb<128>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
     case 64: return launch_k_select_cb<64>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
     case 32: return launch_k_select_cb<32>(K, dm, n, n_pad, k_top, k_bot, thrK, st);

@@ -19,20 +19,19 @@ struct RegSource {  // the vector lives in the wave's registers
   __device__ __forceinline__ uint4 operator()(int ch) const { return x[ch]; }
 };
 
-constexpr int VSEL_TOKENS = 16;  // tokens per block (4 per wave)
-
-// grid (ceil(n/16), B); block 256.  lane l, chunk ch  <->  head 4*ch + l/16,
-// channels 8*(l%16)..+7, i.e. in-vector index ch*512 + l*8 + e.
+// grid (ceil(n / (4 * tpw)), B); block 256: tpw tokens per wave, one after another.
+// lane l, chunk ch  <->  head 4*ch + l/16, channels 8*(l%16)..+7, i.e. in-vector index
+// ch*512 + l*8 + e.
 template <int NC>
-__global__ __launch_bounds__(256) void v_select_kernel(const uint16_t* __restrict__ V, int H, int n, int k_top,
+__global__ __launch_bounds__(256) void v_select_kernel(const uint16_t* __restrict__ V, int H, int n, int tpw, int k_top,
                                                        int k_bot, ThreshPair* __restrict__ thrV) {
   __shared__ uint32_t hist[4 * SELECT_LDS_WORDS];
   const int b = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int hsub = lane >> 4, oc = lane & 15;
   const int N = H * D;
-  for (int i = 0; i < VSEL_TOKENS / 4; ++i) {
-    const int t = blockIdx.x * VSEL_TOKENS + i * 4 + wave;
+  for (int i = 0; i < tpw; ++i) {
+    const int t = (blockIdx.x * tpw + i) * 4 + wave;
     const bool tvalid = t < n;
     uint4 x[NC];
 #pragma unroll
@@ -251,8 +250,10 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
 template <int NC>
 static hipError_t launch_vsel(const uint16_t* V, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrV,
                               hipStream_t st) {
-  dim3 grid((n + VSEL_TOKENS - 1) / VSEL_TOKENS, dm.B);
-  hipLaunchKernelGGL(v_select_kernel<NC>, grid, dim3(256), 0, st, V, dm.H, n, k_top, k_bot, thrV);
+  // four tokens per wave, or one when the call has few tokens (a flushed buffer)
+  const int tpw = (long long)n * dm.B >= 16384 ? 4 : 1;
+  dim3 grid((n + 4 * tpw - 1) / (4 * tpw), dm.B);
+  hipLaunchKernelGGL(v_select_kernel<NC>, grid, dim3(256), 0, st, V, dm.H, n, tpw, k_top, k_bot, thrV);
   return hipGetLastError();
 }
 

@@ -193,6 +193,42 @@ __device__ __forceinline__ void find_kth_equal_pair(const Src& src, int N, int n
   wave_lds_sync();
 }
 
+// A vector of at most 64 entries (a flushed buffer's Key channel): lane i takes entry i and
+// finds its rank among the others by comparing with every lane in turn; no LDS, no passes.
+// keys: the vector as 16-bit keys, contiguous.
+__device__ __forceinline__ Thresh wave_select_small(const uint16_t* keys, int N, int k_top, int k_bot, bool active) {
+  const int lane = lane_id();
+  Thresh th = thresh_none();
+  if (!active) return th;                      // wave-uniform
+  const bool valid = lane < N;
+  const uint32_t key = valid ? (uint32_t)keys[lane] : 0u;
+  const uint32_t cT = valid ? ((key << 16) | (0xFFFFu - (uint32_t)lane)) : 0u;   // valid composites are > 0
+  uint32_t rank_t = 0;
+  for (int j = 0; j < N; ++j) rank_t += (uint32_t)__builtin_amdgcn_readlane((int)cT, j) > cT ? 1u : 0u;
+  const bool in_top = valid && rank_t < (uint32_t)k_top;
+  if (k_top > 0) {
+    const unsigned long long bm = __ballot(valid && rank_t == (uint32_t)k_top - 1u);
+    if (bm) {
+      const int L = (int)__ffsll((long long)bm) - 1;
+      th.tau_top = (uint32_t)__builtin_amdgcn_readlane((int)key, L);
+      th.i_top = L;
+    }
+  }
+  if (k_bot > 0) {
+    const uint32_t cB = (valid && !in_top) ? ((key << 16) | (uint32_t)lane) : 0xFFFFFFFFu;
+    uint32_t rank_b = 0;
+    for (int j = 0; j < N; ++j) rank_b += (uint32_t)__builtin_amdgcn_readlane((int)cB, j) < cB ? 1u : 0u;
+    const unsigned long long bm = __ballot(valid && !in_top && rank_b == (uint32_t)k_bot - 1u);
+    if (bm) {
+      const int L = (int)__ffsll((long long)bm) - 1;
+      th.tau_bot = (uint32_t)__builtin_amdgcn_readlane((int)key, L);
+      th.i_bot = L;
+      th.l_bot = (k_top > 0 && th.tau_bot == th.tau_top) ? th.i_top : -1;
+    }
+  }
+  return th;
+}
+
 constexpr int SELECT_LDS_WORDS = 512;   // LDS words wave_select needs per wave
 
 // A wave with nothing to do passes active = false.  hist: SELECT_LDS_WORDS u32 of LDS private to
@@ -241,7 +277,8 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
       const uint32_t k = slot16(v, e);
       const int hi = (base + e < N) ? (int)(k >> 8) : -2;
       const bool in_t = hi == bin_t, in_b = hi == bin_b;
-      atomicAdd(&hist[(in_t ? 0u : 256u) + (k & 255u)], (in_t || in_b) ? 1u : 0u);
+      const uint32_t lo = hi >= 0 ? (k & 255u) : (uint32_t)lane;   // padding: one address per lane, not one for all
+      atomicAdd(&hist[(in_t ? 0u : 256u) + lo], (in_t || in_b) ? 1u : 0u);
     }
   });
   wave_lds_sync();
