@@ -82,15 +82,17 @@ def test_head_counts(H_kv, H_q):
     run_case(w, n_chunks=1)
 
 
-def test_heavy_ties_and_constant_vectors():
+@pytest.mark.parametrize("n", [150, 48, 64])
+def test_heavy_ties_and_constant_vectors(n):
     """Values on a coarse grid (many exact ties at the Filter threshold and at
-    quantizer rounding boundaries), one all-equal head, signed zeros."""
-    w = small_workload(B=1, H_kv=4, H_q=4, n=150, bits=2, g=64, ppm=40000, rank=2, seed=99)
+    quantizer rounding boundaries), one all-equal head, signed zeros.  n <= 64 takes
+    the rank-based selection of short Key vectors, n = 150 the radix selection."""
+    w = small_workload(B=1, H_kv=4, H_q=4, n=n, bits=2, g=64, ppm=40000, rank=2, seed=99)
     say("case ties", w)
-    gc, oc = pu.make_pair(1, 4, 4, 2, 64, 40000, 20, 150, 1, 2)
+    gc, oc = pu.make_pair(1, 4, 4, 2, 64, 40000, 20, n, 1, 2)
     g = torch.Generator(device="cpu").manual_seed(5)
-    K = (torch.randint(-6, 7, (1, 4, 150, 128), generator=g).float() * 0.5)
-    V = (torch.randint(-3, 4, (1, 4, 150, 128), generator=g).float() * 0.25)
+    K = (torch.randint(-6, 7, (1, 4, n, 128), generator=g).float() * 0.5)
+    V = (torch.randint(-3, 4, (1, 4, n, 128), generator=g).float() * 0.25)
     K[0, 1] = 1.5                                        # constant head
     V[0, 2] = 0.0
     V[0, 2, ::2] = -0.0                                  # signed zeros only
