@@ -1,6 +1,7 @@
 // Filter_s (Eq. 4) + Quant_b(X - S) (Eq. 2 / Eq. 5) kernels of gear_compress, Key side:
 //   k_select_kernel       thresholds of every Key channel vector (over tokens)
-//   k_quant_kernel        Key codes, (scale, zero), ordered outlier lists, residual
+//   k_quant_kernel        Key codes, (scale, zero), ordered outlier lists, the filtered input
+//                         Y = X - S for the power iteration
 // (the Value side is in compress_values.hip)
 #include "gear_internal.h"
 #include "gear_select.h"
@@ -124,15 +125,13 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
 //    quantizer with one bit-select per two entries;
 //  * group min / max are taken on the keys (two per instruction) and turned back into
 //    fp16 once per (group, channel);
-//  * the code goes into its word by a multiply-add (code * 2^(b*e) is exact in fp32),
-//    the rounding remainder is read off the mantissa of (t - code) * 2^23 + 1.5 * 2^23,
-//    whose low 24 bits are 2^22 + the fixed-point remainder;
+//  * the code goes into its word by a multiply-add (code * 2^(b*e) is exact in fp32);
 //  * outlier entries are visited by a loop over the set bits, not over all entries.
 template <int G, int BITS>
 __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const uint16_t* __restrict__ K, SegView sv, Dims dm,
                                                       int n, const ThreshPair* __restrict__ thrK,
                                                       uint32_t* __restrict__ pool_ctr,
-                                                      uint16_t* __restrict__ Rout, uint8_t* __restrict__ Rlo) {
+                                                      uint16_t* __restrict__ Yout) {
   constexpr int WT = G < 64 ? 64 : G;
   constexpr int NK = WT / 16;        // row pieces per thread
   constexpr int NGW = WT / G;        // groups per block (1 or 2)
@@ -236,7 +235,8 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
   }
   block_lds_sync();
 
-  // codes (packed token-major) and the residual
+  // codes (packed token-major), and Y = X - S (fp16, outliers zeroed) for the power iteration,
+  // which re-derives the quantization error from it
   uint32_t* crow = sv.codes + (size_t)slab * sv.n_cap * dm.wpr;
 #pragma unroll
   for (int gi = 0; gi < NGW; ++gi) {
@@ -254,7 +254,6 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
       const int k = gi * KPG + kk;
       const int t = t0 + r0 + 16 * k;
       if (t < n) {
-        uint32_t fb[8];          // bits of (t - code) * 2^23 + 1.5 * 2^23
         float cw0 = 0.0f, cw1 = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -262,7 +261,6 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
           const float y = h2f((e & 1) ? (x >> 16) : (x & 0xFFFFu));
           const float tq = __fmul_rn(__fsub_rn(y, gmn[e]), ginv[e]);
           const float c = clamp_f32(rintf(tq), 0.0f, QMAX);
-          fb[e] = __float_as_uint(__builtin_fmaf(tq - c, RESID_FIX, RESID_MAGIC));
           if (BITS == 2) {
             cw0 = __builtin_fmaf(c, (float)(1u << (2 * e)), cw0);
           } else {
@@ -270,12 +268,9 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
             else cw1 = __builtin_fmaf(c, (float)(1u << (4 * (e - 4))), cw1);
           }
         }
-        if (Rout) {
-          store_stream16(Rout + ((size_t)slab * n + t) * D + oc * 8,
-                         make_uint4(resid_hi2(fb[0], fb[1]), resid_hi2(fb[2], fb[3]), resid_hi2(fb[4], fb[5]), resid_hi2(fb[6], fb[7])));
-          store_stream8(Rlo + ((size_t)slab * n + t) * D + oc * 8,
-                        make_uint2(resid_lo4(fb[0], fb[1], fb[2], fb[3]), resid_lo4(fb[4], fb[5], fb[6], fb[7])));
-        }
+        if (Yout)
+          store_stream16(Yout + ((size_t)slab * n + t) * D + oc * 8,
+                         make_uint4(raw[k][0] & ~msk[k][0], raw[k][1] & ~msk[k][1], raw[k][2] & ~msk[k][2], raw[k][3] & ~msk[k][3]));
         if (BITS == 4) {
           crow[(size_t)t * dm.wpr + oc] = (uint32_t)cw0 | ((uint32_t)cw1 << 16);
         } else {  // 2 bits: 16 bits per thread
@@ -406,20 +401,20 @@ hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, 
 
 template <int G>
 static void launch_k_quant_g(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const ThreshPair* thrK,
-                             uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
+                             uint32_t* pool_ctr, uint16_t* Yout, hipStream_t st) {
   constexpr int WT = G < 64 ? 64 : G;
   dim3 grid((n + WT - 1) / WT, dm.B * dm.H);
   if (dm.bits == 2)
-    hipLaunchKernelGGL((k_quant_kernel<G, 2>), grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
+    hipLaunchKernelGGL((k_quant_kernel<G, 2>), grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Yout);
   else
-    hipLaunchKernelGGL((k_quant_kernel<G, 4>), grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Rout, Rlo);
+    hipLaunchKernelGGL((k_quant_kernel<G, 4>), grid, dim3(256), 0, st, K, sv, dm, n, thrK, pool_ctr, Yout);
 }
 
 hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const ThreshPair* thrK,
-                          uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st) {
-  if (dm.g == 128) launch_k_quant_g<128>(K, sv, dm, n, thrK, pool_ctr, Rout, Rlo, st);
-  else if (dm.g == 64) launch_k_quant_g<64>(K, sv, dm, n, thrK, pool_ctr, Rout, Rlo, st);
-  else launch_k_quant_g<32>(K, sv, dm, n, thrK, pool_ctr, Rout, Rlo, st);
+                          uint32_t* pool_ctr, uint16_t* Yout, hipStream_t st) {
+  if (dm.g == 128) launch_k_quant_g<128>(K, sv, dm, n, thrK, pool_ctr, Yout, st);
+  else if (dm.g == 64) launch_k_quant_g<64>(K, sv, dm, n, thrK, pool_ctr, Yout, st);
+  else launch_k_quant_g<32>(K, sv, dm, n, thrK, pool_ctr, Yout, st);
   return hipGetLastError();
 }
 

@@ -5,7 +5,8 @@
 //   v_quant_kernel   per (b, h, 64-token tile): outlier predicate, per-token group
 //                    min/max inside the row (lane exchanges), codes written in the
 //                    token-blocked order the decode kernel's MFMA operand expects,
-//                    (scale, zero), the tile's outlier list ordered (c, t), residual
+//                    (scale, zero), the tile's outlier list ordered (c, t), the filtered
+//                    input Y = X - S for the power iteration
 #include "gear_internal.h"
 #include "gear_select.h"
 #include "gear_launch.h"
@@ -52,11 +53,11 @@ __global__ __launch_bounds__(256) void v_select_kernel(const uint16_t* __restric
 // grid (ceil(n/64), B*H); block 256; thread (r0 = tid/16, oc = tid%16) owns
 // channels 8*oc..+7 of rows t0 + r0 + 16*k, k = 0..3.  Same arithmetic as the Key
 // kernel: Filter and min/max on packed 16-bit keys with a mask word per two entries,
-// code bytes and the rounding remainder read off float mantissas.
+// code bytes read off float mantissas.
 template <int BITS>
 __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict__ V, SegView sv, Dims dm, int n,
                                                       const ThreshPair* __restrict__ thrV, uint32_t* __restrict__ pool_ctr,
-                                                      uint16_t* __restrict__ Rout, uint8_t* __restrict__ Rlo) {
+                                                      uint16_t* __restrict__ Yout) {
   constexpr int PITCH = 136;  // bytes per staged code row (multiple of 8)
   constexpr float QMAX = (float)((1 << BITS) - 1);
   constexpr int bits = BITS, tpw = 32 / BITS;
@@ -145,27 +146,24 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
     }
     const float lmn = h2f(unkey16(kmn)), lmx = h2f(unkey16(kmx));
     const GroupQ q = make_group(lmn, lmx, QMAX);
-    uint32_t fb[8], fc[8];   // bits of (t - code) * 2^23 + 1.5 * 2^23 and of code + 2^23
+    uint32_t fc[8];   // bits of code + 2^23
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const uint32_t x = raw[e >> 1] & ~msk[e >> 1];
       const float y = h2f((e & 1) ? (x >> 16) : (x & 0xFFFFu));
       const float tq = __fmul_rn(__fsub_rn(y, q.mn), q.inv);
       const float c = clamp_f32(rintf(tq), 0.0f, QMAX);
-      fb[e] = __float_as_uint(__builtin_fmaf(tq - c, RESID_FIX, RESID_MAGIC));
       fc[e] = __float_as_uint(c + 8388608.0f);   // low byte of the mantissa = the code
     }
     // 8 code bytes (0 for a row past the end)
-    const uint32_t cb0 = tv ? resid_lo4(fc[0], fc[1], fc[2], fc[3]) : 0u;
-    const uint32_t cb1 = tv ? resid_lo4(fc[4], fc[5], fc[6], fc[7]) : 0u;
+    const uint32_t cb0 = tv ? low_bytes4(fc[0], fc[1], fc[2], fc[3]) : 0u;
+    const uint32_t cb1 = tv ? low_bytes4(fc[4], fc[5], fc[6], fc[7]) : 0u;
     *reinterpret_cast<uint2*>(&stage[tl * PITCH + oc * 8]) = make_uint2(cb0, cb1);
     if (tv) {
       if ((oc & ((g >> 3) - 1)) == 0) sv.sz[((size_t)slab * sv.n_cap + t) * (D >> lg) + ((oc * 8) >> lg)] = group_bits(q);
-      if (Rout) {
-        const size_t ro = ((size_t)slab * n + t) * D + oc * 8;
-        store_stream16(Rout + ro, make_uint4(resid_hi2(fb[0], fb[1]), resid_hi2(fb[2], fb[3]), resid_hi2(fb[4], fb[5]), resid_hi2(fb[6], fb[7])));
-        store_stream8(Rlo + ro, make_uint2(resid_lo4(fb[0], fb[1], fb[2], fb[3]), resid_lo4(fb[4], fb[5], fb[6], fb[7])));
-      }
+      if (Yout)   // Y = X - S (fp16, outliers zeroed): the power iteration re-derives the quantization error from it
+        store_stream16(Yout + ((size_t)slab * n + t) * D + oc * 8,
+                       make_uint4(raw[0] & ~msk[0], raw[1] & ~msk[1], raw[2] & ~msk[2], raw[3] & ~msk[3]));
     }
   }
   block_lds_sync();
@@ -258,8 +256,7 @@ static hipError_t launch_vsel(const uint16_t* V, const Dims& dm, int n, int k_to
 }
 
 hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                                 int k_bot, ThreshPair* thrV, uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo,
-                                 hipStream_t st) {
+                                 int k_bot, ThreshPair* thrV, uint32_t* pool_ctr, uint16_t* Yout, hipStream_t st) {
   if (dm.ppm > 0) {
     const int nc = (dm.H + 3) / 4;
     hipError_t e;
@@ -272,9 +269,9 @@ hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dim
   }
   dim3 grid((n + TILE - 1) / TILE, dm.B * dm.H);
   if (dm.bits == 2)
-    hipLaunchKernelGGL(v_quant_kernel<2>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, pool_ctr, Rout, Rlo);
+    hipLaunchKernelGGL(v_quant_kernel<2>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, pool_ctr, Yout);
   else
-    hipLaunchKernelGGL(v_quant_kernel<4>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, pool_ctr, Rout, Rlo);
+    hipLaunchKernelGGL(v_quant_kernel<4>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, pool_ctr, Yout);
   return hipGetLastError();
 }
 

@@ -27,7 +27,6 @@
 namespace gear {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int MFMA_TS = 512;                 // tokens per block (128 per wave)
 constexpr float MFMA_OUT_SCALE = 1048576.f;  // 2^24 / 16: undoes the denormal and operand scaling

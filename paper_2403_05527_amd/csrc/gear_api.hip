@@ -80,7 +80,7 @@ ArenaLayout arena_layout(const gear_config& c) {
 }
 
 struct WorkLayout {
-  size_t thrK, thrV, pool_ctr, Bcur, partial, Atmp, cmat, dec, resid, resid_lo, bytes;
+  size_t thrK, thrV, pool_ctr, Bcur, partial, Atmp, cmat, dec, resid, bytes;
 };
 
 WorkLayout work_layout(const gear_config& c) {
@@ -103,7 +103,6 @@ WorkLayout work_layout(const gear_config& c) {
   const int ncb = (c.n_chunks_max * (c.n_buf_cap > 128 ? 2 : 1) + 3) / 4;
   w.dec = o; o += up((size_t)c.B * c.H_q * (nsplit + ncb + 1) * DECODE_REC * 4);
   w.resid = o; o += up(c.rank_max > 0 ? slabs * (size_t)n_max * D * 2 : 0);
-  w.resid_lo = o; o += up(c.rank_max > 0 ? slabs * (size_t)n_max * D : 0);
   w.bytes = o;
   return w;
 }
@@ -265,20 +264,19 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
     GEAR_HIP(launch_fill_u32(pool_ctr, 0u, (size_t)c.B * c.H_kv + c.B, st));
     GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, st));
   }
-  // Keys: quantize (leaving the residual in the workspace), then their power iteration;
-  // Values reuse the same residual buffer afterwards.
+  // Keys: quantize (leaving Y = X - S in the workspace), then their power iteration;
+  // Values reuse the same buffer afterwards.
   uint16_t* resid = rank > 0 ? reinterpret_cast<uint16_t*>(ws + w.resid) : nullptr;
-  uint8_t* resid_lo = rank > 0 ? reinterpret_cast<uint8_t*>(ws + w.resid_lo) : nullptr;
   float* Bcur = reinterpret_cast<float*>(ws + w.Bcur);
   float* partial = reinterpret_cast<float*>(ws + w.partial);
   float* Atmp = reinterpret_cast<float*>(ws + w.Atmp);
   float* cmat = reinterpret_cast<float*>(ws + w.cmat);
   const size_t half = (size_t)c.B * c.H_kv * D * rank;
-  GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, resid, resid_lo, st));
-  if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, resid_lo, ks, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st));
-  GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, pool_ctr + (size_t)c.B * c.H_kv, resid, resid_lo, st));
+  GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, resid, st));
+  if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, ks, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st));
+  GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, pool_ctr + (size_t)c.B * c.H_kv, resid, st));
   if (rank > 0)
-    GEAR_HIP(launch_power_iteration(false, resid, resid_lo, vs, dm, n, iters, init_B + half, Bcur, partial, Atmp, cmat, st));
+    GEAR_HIP(launch_power_iteration(false, resid, vs, dm, n, iters, init_B + half, Bcur, partial, Atmp, cmat, st));
 
   if (first) {
     cache->n_prefill = n;

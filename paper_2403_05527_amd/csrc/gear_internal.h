@@ -51,6 +51,8 @@
 
 namespace gear {
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));   // MFMA accumulator tile of one lane
+
 constexpr int D = 128;      // head dimension
 constexpr int TILE = 64;    // tokens per sparse-list tile
 constexpr int VPOOL_FIXED = 48;   // entries of the reserved list region of one Value (head, tile)
@@ -268,40 +270,17 @@ __device__ __forceinline__ uint32_t quant_code(float y, const GroupQ& q, float q
   float c = fminf(fmaxf(rintf(t), 0.0f), qmax);
   return (uint32_t)c;
 }
-// Code plus the rounding remainder u = t - code (|u| <= 0.5 up to the fp16
-// rounding of the scale), as a 24-bit fixed-point number u * 2^23 (fp32's own
-// precision for |u| >= 0.5) split into a high 16-bit and a low 8-bit part.  The
-// quantization residual is R = y - (code*delta + zero) = u * delta.
-constexpr float RESID_FIX = 8388608.0f;  // 2^23
-__device__ __forceinline__ uint32_t quant_code_resid(float y, const GroupQ& q, float qmax, uint32_t& hi16,
-                                                     uint32_t& lo8) {
-  float t = __fmul_rn(__fsub_rn(y, q.mn), q.inv);
-  float c = fminf(fmaxf(rintf(t), 0.0f), qmax);
-  const int f = (int)rintf((t - c) * RESID_FIX);
-  hi16 = (uint32_t)(f >> 8) & 0xFFFFu;
-  lo8 = (uint32_t)f & 0xFFu;
-  return (uint32_t)c;
-}
-// The same remainder read off a float's mantissa: the bits of (t - code) * 2^23 + 1.5 * 2^23
-// are 0x4B400000 + f for the fixed-point remainder f = rint((t - code) * 2^23), |f| <= 2^22
-// (round to nearest even either way).  resid_hi2: bits 8..23 of f for two entries in one
-// word; resid_lo4: bits 0..7 of f for four entries.
-constexpr float RESID_MAGIC = 12582912.0f;   // 1.5 * 2^23
-__device__ __forceinline__ uint32_t resid_hi2(uint32_t b0, uint32_t b1) {
-  return pk_sub_u16(GEAR_BYTE_PERM(b1, b0, 0x06050201u), 0x40004000u);
-}
-__device__ __forceinline__ uint32_t resid_lo4(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3) {
+// Byte 0 of four words in one word (codes and the like read off float mantissas).
+__device__ __forceinline__ uint32_t low_bytes4(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3) {
   return GEAR_BYTE_PERM(GEAR_BYTE_PERM(b3, b2, 0x0c0c0400u), GEAR_BYTE_PERM(b1, b0, 0x0c0c0400u), 0x05040100u);
 }
 __device__ __forceinline__ float clamp_f32(float x, float lo, float hi) { return GEAR_FMED3(x, lo, hi); }
-// Entry e (0..3) of a word of four low bytes and of the word of two high halves that holds
-// it (e & 1): the remainder times 2^31, exactly (one byte permute and one conversion).
-__device__ __forceinline__ float resid_x2p31(uint32_t hi2, uint32_t lo4, int e) {   // e: a constant after unrolling
-  const uint32_t sel = 0x0cu | ((uint32_t)(e & 3) << 8) | ((4u + 2u * (e & 1)) << 16) | ((5u + 2u * (e & 1)) << 24);
-  return (float)(int)GEAR_BYTE_PERM(hi2, lo4, sel);
-}
-__device__ __forceinline__ float resid_to_float(uint32_t hi16, uint32_t lo8) {  // u, not yet times delta
-  return (float)((int)(short)(hi16 & 0xFFFFu) * 256 + (int)(lo8 & 0xFFu)) * (1.0f / RESID_FIX);
+// Quantization error of one entry (Alg. 1: R = Y - D-hat, D-hat = code * scale + zero) with
+// the code decided by the quantizer's own operation sequence (Eq. 2), so it is the stored one.
+__device__ __forceinline__ float quant_error(float y, float mn, float inv, float delta, float qmax) {
+  const float ym = __fsub_rn(y, mn);
+  const float c = clamp_f32(rintf(__fmul_rn(ym, inv)), 0.0f, qmax);
+  return __builtin_fmaf(-c, delta, ym);
 }
 
 __device__ __forceinline__ void block_lds_sync() { GEAR_LDS_BARRIER(); }

@@ -18,16 +18,15 @@ hipError_t launch_fill_u32(uint32_t* p, uint32_t v, size_t count, hipStream_t st
 
 hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
                            hipStream_t st);
-// Rout / Rlo (nullable): [slab][n][128] high 16 and low 8 bits of the residual R = X - S - D in
-// units of its group's scale, 24-bit fixed point (2^-23)
+// Yout (nullable): [slab][n][128] fp16, Y = X - S (the input with its outliers zeroed), from
+// which the power iteration re-derives the residual R = Y - D-hat.
 hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const ThreshPair* thrK,
-                          uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo, hipStream_t st);
+                          uint32_t* pool_ctr, uint16_t* Yout, hipStream_t st);
 hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                                 int k_bot, ThreshPair* thrV, uint32_t* pool_ctr, uint16_t* Rout, uint8_t* Rlo,
-                                 hipStream_t st);
+                                 int k_bot, ThreshPair* thrV, uint32_t* pool_ctr, uint16_t* Yout, hipStream_t st);
 
 int pi_padded_rank(int rank);
-hipError_t launch_power_iteration(bool is_k, const uint16_t* Rres, const uint8_t* Rlo, const SegView& sv, const Dims& dm, int n, int iters,
+hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
                                   const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat,
                                   hipStream_t st);
 

@@ -1,8 +1,10 @@
 // SVDSolver_r (Eq. 6, Algorithm 2): batched power iteration on the per-head
-// residual R = X - D - S, which the quantization kernels leave in a workspace
-// buffer as the rounding remainder u = R / scale in 24-bit fixed point (|u| <= 1/2,
-// i.e. fp32's own precision in 3 bytes per entry; a 16-bit copy flips too many
-// fp16 roundings of the stored factors against a double-precision computation).
+// residual R = X - D - S.  The quantization kernels leave Y = X - S (fp16, outliers
+// zeroed) in a workspace buffer; every sweep re-derives R = Y - D-hat from it and the
+// stored (scale, zero) with the quantizer's own operation sequence.  That is exact
+// (no rounded copy of R), costs 2 bytes per entry and pass, and five more vector
+// instructions per entry than reading a stored remainder; a 16-bit copy of R itself
+// flips enough fp16 roundings of the stored factors to fail the attention tolerance.
 //
 //   pi_update  : B <- start matrix or sum of the sweep partials; column scaling
 //                between rounds (the span, hence A B^T, is unchanged); QR of B
@@ -18,7 +20,6 @@
 namespace gear {
 
 constexpr int PT = 256;  // tokens per sweep block
-constexpr float RESID_UNIT = 1.0f / 2147483648.0f;   // 2^-31: the stored remainder is read as an integer times 2^8
 
 template <typename T>
 __device__ __forceinline__ T block128_sum(T v, T* red /* >= 2 */) {
@@ -142,24 +143,78 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
 }
 
 // grid (ceil(n/PT), B*H), block 256; thread (r0 = tid/16, oc = tid%16) owns
-// channels 8*oc..+7 of rows pt*PT + r0 + 16*k of the stored residual
-// (u = R / scale as 16-bit fixed point; the scale is applied per group here).
+// channels 8*oc..+7 of rows pt*PT + r0 + 16*k.  Y = X - S in fp16 (what the quantization
+// kernel left); the residual R = Y - D-hat = (Y - zero) - code * scale is re-derived per
+// entry, so it is exact and costs 2 bytes per entry.  Keys take the code from the stored
+// code rows (16 or 32 bits per row piece); Values, whose codes are stored in blocks of
+// tokens, recompute it with the quantizer's own operation sequence.  The (zero, 1/scale,
+// scale) of the block's groups are prepared once per block in LDS.
+// B' += R_t^T a_t runs on the matrix cores: v_mfma_f32_4x4x1 works on 16 blocks of 4 lanes and
+// adds, in register i of lane L, a(lane 4*(L/4) + i) * b(lane L).  With a = the lane's
+// residual entry e and b = a_t[r = oc % 4], register i of accumulator e holds
+// B'[channel 8*(4*(oc/4) + i) + e][r = oc % 4]: 8 instructions per token row instead of 32
+// multiply-adds (the sweeps are bound by vector instruction issue, not by HBM).
 // LAST: the final round, which also leaves a_t and the Gram matrix (its extra state costs
 // one resident block per CU, so the rounds before it are compiled without).
 template <bool IS_K, int R, bool LAST>
-__global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_kernel(const uint16_t* __restrict__ Rres,
-                                                       const uint8_t* __restrict__ Rlo, SegView sv, int g, int n,
-                                                       const float* __restrict__ Bcur,
+__global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_kernel(const uint16_t* __restrict__ Y, SegView sv, int g,
+                                                       int bits, int n, const float* __restrict__ Bcur,
                                                        float* __restrict__ partial, int npart,
                                                        float* __restrict__ Atmp) {
   __shared__ float red[4][D * R];
   __shared__ float redg[4][R * R];
+  // Keys: [2][groups of the block <= 8][128] (zero, scale); Values: [rows][groups of a row <= 4] (zero, 1/scale, scale, -)
+  __shared__ __attribute__((aligned(16))) float prm[IS_K ? 2 * (PT / 32) * D : PT * 4 * 4];
   const int slab = blockIdx.y, pt = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r0 = tid >> 4, oc = tid & 15;
-  const uint16_t* Xs = Rres + (size_t)slab * n * D;
-  const uint8_t* Xl = Rlo + (size_t)slab * n * D;
+  const uint16_t* Xs = Y + (size_t)slab * n * D;
   const int lg = 31 - __clz(g);   // g is a power of two
+  constexpr int GSTR = (PT / 32) * D;   // Keys: floats per parameter plane
+  const float qmax = (float)((1 << bits) - 1);
+  const uint32_t* crow = sv.codes + (size_t)slab * sv.n_cap * (4 * bits);   // Keys: 128 * bits / 32 words per row
+
+  constexpr int UN = 4;  // rows in flight per thread
+  // the rows of an iteration, all requested before the first one is used
+  auto request = [&](int k0, uint4 (&xv)[UN], uint32_t (&cw)[UN]) {
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int t = pt * PT + r0 + 16 * (k0 + u);
+      xv[u] = make_uint4(0, 0, 0, 0);
+      cw[u] = 0u;
+      if (t < n) {
+        xv[u] = load_stream16(Xs + (size_t)t * D + oc * 8);
+        if (IS_K) {
+          const uint32_t* cr = crow + (size_t)t * (4 * bits);
+          cw[u] = bits == 4 ? cr[oc] : (uint32_t)reinterpret_cast<const uint16_t*>(cr)[oc];
+        }
+      }
+    }
+  };
+  uint4 xv_first[UN];
+  uint32_t cw_first[UN];   // Keys: the row piece's 8 codes
+  request(0, xv_first, cw_first);   // in flight while the parameters are prepared
+
+  if (IS_K) {
+    const int ngb = PT >> lg, grp0 = (pt * PT) >> lg, ng = (n + g - 1) >> lg;
+    for (int i = tid; i < ngb * D; i += 256) {
+      const int gi = grp0 + (i >> 7);
+      GroupQ q;
+      q.mn = 0.0f; q.inv = 0.0f; q.delta = 0.0f;
+      if (gi < ng) q = load_group(sv.sz[((size_t)slab * sv.ng_cap + gi) * D + (i & 127)]);
+      prm[i] = q.mn;
+      prm[GSTR + i] = q.delta;
+    }
+  } else {
+    const int ngl = 7 - lg;   // log2 of the groups per row
+    for (int i = tid; i < (PT << ngl); i += 256) {
+      const int t = pt * PT + (i >> ngl);
+      GroupQ q;
+      q.mn = 0.0f; q.inv = 0.0f; q.delta = 0.0f;
+      if (t < n) q = load_group(sv.sz[(((size_t)slab * sv.n_cap + t) << ngl) + (i & ((1 << ngl) - 1))]);
+      *reinterpret_cast<float4*>(&prm[4 * i]) = make_float4(q.mn, q.inv, q.delta, 0.0f);
+    }
+  }
 
   float bc[8][R];
 #pragma unroll
@@ -167,85 +222,80 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
 #pragma unroll
     for (int r = 0; r < R; ++r) bc[e][r] = Bcur[((size_t)slab * D + oc * 8 + e) * R + r];
 
-  float acc[8][R];
+  constexpr int NB = (R + 3) / 4;   // column blocks of four
+  floatx4 acc[8][NB];
   float gacc[R];
 #pragma unroll
   for (int e = 0; e < 8; ++e)
 #pragma unroll
-    for (int r = 0; r < R; ++r) acc[e][r] = 0.0f;
+    for (int nb = 0; nb < NB; ++nb) acc[e][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const bool partial_blk = pt * PT + PT > n;   // block-uniform: only such a block has rows past the end
 #pragma unroll
   for (int r = 0; r < R; ++r) gacc[r] = 0.0f;
+  block_lds_sync();
 
-  constexpr int UN = 4;  // rows in flight per thread
+#pragma unroll   // no copies of the accumulators at a loop's back edge
   for (int k0 = 0; k0 < PT / 16; k0 += UN) {
     if (pt * PT + 16 * k0 >= n) break;  // block-uniform
     uint4 xv[UN];
-    uint2 xl[UN];
-    // Keys: the UN = 4 bands of 16 rows in flight lie in one group (g >= 64) or two (g = 32),
-    // so at most two sets of per-channel scales are needed
-    const int ush = g >= 64 ? 2 : 1;                 // band u uses scale set u >> ush
-    uint4 sk0[IS_K ? 2 : 1], sk1[IS_K ? 2 : 1];     // raw (scale, zero) words, Keys
-    uint32_t svw[UN];                               // raw (scale, zero) word, Values
-    // every load of the UN rows is issued before the first result is touched
-    if (IS_K) {
+    uint32_t cw[UN];
+    if (k0 == 0) {
 #pragma unroll
-      for (int gs = 0; gs < 2; ++gs) {
-        const int t = pt * PT + 16 * (k0 + (gs << ush));       // first row of the set's first band
-        sk0[gs] = make_uint4(0, 0, 0, 0);
-        sk1[gs] = make_uint4(0, 0, 0, 0);
-        if ((gs << ush) < UN && t < n) {
-          const uint4* p = reinterpret_cast<const uint4*>(sv.sz + ((size_t)slab * sv.ng_cap + (t >> lg)) * D + oc * 8);
-          sk0[gs] = p[0];
-          sk1[gs] = p[1];
+      for (int u = 0; u < UN; ++u) { xv[u] = xv_first[u]; cw[u] = cw_first[u]; }
+    } else {
+      request(k0, xv, cw);
+    }
+    float pmn[8], pdl[8];   // Keys: parameters of my 8 channels in the current group
+    int gi_prev = -1;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int tl = r0 + 16 * (k0 + u), t = pt * PT + tl;
+      float vmn = 0.0f, vinv = 0.0f, vdl = 0.0f;   // Values: parameters of my row's channel group
+      if (IS_K) {
+        const int gi = (16 * (k0 + u)) >> lg;   // group inside the block, block-uniform
+        if (gi != gi_prev) {
+          const float* pb = &prm[gi * D + oc * 8];
+          const float4 a0 = *reinterpret_cast<const float4*>(pb), a1 = *reinterpret_cast<const float4*>(pb + 4);
+          const float4 c0 = *reinterpret_cast<const float4*>(pb + GSTR), c1 = *reinterpret_cast<const float4*>(pb + GSTR + 4);
+          pmn[0] = a0.x; pmn[1] = a0.y; pmn[2] = a0.z; pmn[3] = a0.w; pmn[4] = a1.x; pmn[5] = a1.y; pmn[6] = a1.z; pmn[7] = a1.w;
+          pdl[0] = c0.x; pdl[1] = c0.y; pdl[2] = c0.z; pdl[3] = c0.w; pdl[4] = c1.x; pdl[5] = c1.y; pdl[6] = c1.z; pdl[7] = c1.w;
+          gi_prev = gi;
         }
+      } else {
+        const float4 pv = *reinterpret_cast<const float4*>(&prm[4 * ((tl << (7 - lg)) + ((oc * 8) >> lg))]);
+        vmn = pv.x; vinv = pv.y; vdl = pv.z;
       }
-    }
-#pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const int t = pt * PT + r0 + 16 * (k0 + u);
-      xv[u] = make_uint4(0, 0, 0, 0);
-      xl[u] = make_uint2(0, 0);
-      svw[u] = 0u;
-      if (t < n) {
-        xv[u] = load_stream16(Xs + (size_t)t * D + oc * 8);
-        xl[u] = load_stream8(Xl + (size_t)t * D + oc * 8);
-        if (!IS_K)   // scale of (token t, the channel group of my 8 channels)
-          svw[u] = sv.sz[((size_t)slab * sv.n_cap + t) * (D >> lg) + ((oc * 8) >> lg)];
-      }
-    }
-    float dlk[IS_K ? 2 : 1][IS_K ? 8 : 1], dlv[UN];
-    if (IS_K) {
-#pragma unroll
-      for (int gs = 0; gs < 2; ++gs) {
-        const uint32_t sb[8] = {sk0[gs].x, sk0[gs].y, sk0[gs].z, sk0[gs].w, sk1[gs].x, sk1[gs].y, sk1[gs].z, sk1[gs].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dlk[gs][IS_K ? e : 0] = h2f(sb[e] & 0xFFFFu) * RESID_UNIT;
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < UN; ++u) dlv[u] = h2f(svw[u] & 0xFFFFu) * RESID_UNIT;
-#pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const int t = pt * PT + r0 + 16 * (k0 + u);
       const uint32_t w[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
-      const uint32_t wl[2] = {xl[u].x, xl[u].y};
-      // the remainder times 2^31 (exact), times the scale with the 2^-31 folded in
       float res[8];
       float a[R];
 #pragma unroll
       for (int r = 0; r < R; ++r) a[r] = 0.0f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        res[e] = resid_x2p31(w[e >> 1], wl[e >> 2], e) * (IS_K ? dlk[IS_K ? ((u >> ush) & 1) : 0][IS_K ? e : 0] : dlv[u]);
+        const float y = h2f((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xFFFFu));
+        if (IS_K) {   // the stored code
+          const float c = (float)((cw[u] >> (e * bits)) & (uint32_t)((1 << bits) - 1));
+          res[e] = __builtin_fmaf(-c, pdl[e], y - pmn[e]);
+        } else {      // the code the quantizer computed
+          res[e] = quant_error(y, vmn, vinv, vdl, qmax);
+        }
+        if (IS_K && partial_blk && t >= n) res[e] = 0.0f;   // rows past the end (Values: their parameters are 0)
 #pragma unroll
         for (int r = 0; r < R; ++r) a[r] += res[e] * bc[e][r];
       }
 #pragma unroll
       for (int r = 0; r < R; ++r) a[r] = row16_sum(a[r]);   // the 16 lanes of a row hold one token
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
+      for (int nb = 0; nb < NB; ++nb) {
+        const int j = oc & 3;
+        float b = a[4 * nb];   // a_t[4 * nb + oc % 4] (0 past R)
+        if (4 * nb + 1 < R) b = (j == 1) ? a[4 * nb + 1 < R ? 4 * nb + 1 : 0] : b;
+        b = (j == 2) ? (4 * nb + 2 < R ? a[4 * nb + 2 < R ? 4 * nb + 2 : 0] : 0.0f) : b;
+        b = (j == 3) ? (4 * nb + 3 < R ? a[4 * nb + 3 < R ? 4 * nb + 3 : 0] : 0.0f) : b;
+        if (4 * nb + 1 >= R) b = (j == 1) ? 0.0f : b;
 #pragma unroll
-        for (int r = 0; r < R; ++r) acc[e][r] += res[e] * a[r];
+        for (int e = 0; e < 8; ++e) acc[e][nb] = __builtin_amdgcn_mfma_f32_4x4x1f32(res[e], b, acc[e][nb], 0, 0, 0);
+      }
       if (LAST) {
         if (oc == 0 && t < n) {
 #pragma unroll
@@ -266,12 +316,14 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
 #pragma unroll
   for (int e = 0; e < 8; ++e)
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      float v = acc[e][r];
-      v += __shfl_xor(v, 16, 64);
-      v += __shfl_xor(v, 32, 64);
-      acc[e][r] = v;
-    }
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float v = acc[e][nb][i];
+        v += __shfl_xor(v, 16, 64);
+        v += __shfl_xor(v, 32, 64);
+        acc[e][nb][i] = v;
+      }
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     float v = gacc[r];
@@ -283,7 +335,12 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
 #pragma unroll
     for (int e = 0; e < 8; ++e)
 #pragma unroll
-      for (int r = 0; r < R; ++r) red[wave][(oc * 8 + e) * R + r] = acc[e][r];
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = 4 * nb + (oc & 3);
+          if (r < R) red[wave][(8 * (4 * (oc >> 2) + i) + e) * R + r] = acc[e][nb][i];
+        }
     if (oc < R) {
 #pragma unroll
       for (int r = 0; r < R; ++r) redg[wave][oc * R + r] = gacc[r];
@@ -318,7 +375,7 @@ __global__ __launch_bounds__(256) void pi_finish_kernel(const float* __restrict_
 
 // ------------------------------------------------------------------ host side
 template <int R>
-static hipError_t run_pi(bool is_k, const uint16_t* Rres, const uint8_t* Rlo, const SegView& sv, const Dims& dm, int n, int iters,
+static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
                          const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat,
                          hipStream_t st) {
   const int slabs = dm.B * dm.H;
@@ -329,13 +386,13 @@ static hipError_t run_pi(bool is_k, const uint16_t* Rres, const uint8_t* Rlo, co
     const int last = (l == iters - 1);
     const dim3 grid(npart, slabs);
     if (is_k && last)
-      hipLaunchKernelGGL((pi_sweep_kernel<true, R, true>), grid, dim3(256), 0, st, Rres, Rlo, sv, dm.g, n, (const float*)Bcur, partial, npart, Atmp);
+      hipLaunchKernelGGL((pi_sweep_kernel<true, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
     else if (is_k)
-      hipLaunchKernelGGL((pi_sweep_kernel<true, R, false>), grid, dim3(256), 0, st, Rres, Rlo, sv, dm.g, n, (const float*)Bcur, partial, npart, Atmp);
+      hipLaunchKernelGGL((pi_sweep_kernel<true, R, false>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
     else if (last)
-      hipLaunchKernelGGL((pi_sweep_kernel<false, R, true>), grid, dim3(256), 0, st, Rres, Rlo, sv, dm.g, n, (const float*)Bcur, partial, npart, Atmp);
+      hipLaunchKernelGGL((pi_sweep_kernel<false, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
     else
-      hipLaunchKernelGGL((pi_sweep_kernel<false, R, false>), grid, dim3(256), 0, st, Rres, Rlo, sv, dm.g, n, (const float*)Bcur, partial, npart, Atmp);
+      hipLaunchKernelGGL((pi_sweep_kernel<false, R, false>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
     hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, (const float*)nullptr, sv.rank,
                        (const float*)partial, npart, (l == iters - 2) ? 1 : 0, last, Bcur, cmat, sv);
   }
@@ -346,13 +403,13 @@ static hipError_t run_pi(bool is_k, const uint16_t* Rres, const uint8_t* Rlo, co
 
 int pi_padded_rank(int rank) { return rank <= 2 ? 2 : rank <= 4 ? 4 : 8; }
 
-hipError_t launch_power_iteration(bool is_k, const uint16_t* Rres, const uint8_t* Rlo, const SegView& sv, const Dims& dm, int n, int iters,
+hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
                                   const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat,
                                   hipStream_t st) {
   switch (pi_padded_rank(sv.rank)) {
-    case 2: return run_pi<2>(is_k, Rres, Rlo, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
-    case 4: return run_pi<4>(is_k, Rres, Rlo, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
-    default: return run_pi<8>(is_k, Rres, Rlo, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
+    case 2: return run_pi<2>(is_k, Yf, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
+    case 4: return run_pi<4>(is_k, Yf, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
+    default: return run_pi<8>(is_k, Yf, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
   }
 }
 

@@ -30,6 +30,7 @@ struct uint2 { uint32_t x, y; };
 struct alignas(16) uint4 { uint32_t x, y, z, w; };
 struct alignas(16) float4 { float x, y, z, w; };
 struct float2 { float x, y; };
+static inline float4 make_float4(float x, float y, float z, float w) { return float4{x, y, z, w}; }
 static inline float2 make_float2(float x, float y) { return float2{x, y}; }
 static inline uint2 make_uint2(uint32_t x, uint32_t y) { return uint2{x, y}; }
 static inline uint4 make_uint4(uint32_t x, uint32_t y, uint32_t z, uint32_t w) { return uint4{x, y, z, w}; }
@@ -130,6 +131,25 @@ inline f4 mfma(h8 a, h8 b, f4 c) {
   pthread_barrier_wait(&w.bar);
   return d;
 }
+// v_mfma_f32_4x4x1_16B_f32: 16 blocks of 4 lanes; register i of lane L gets
+// c[i] + a(lane 4*(L/4) + i) * b(lane L)
+inline f4 mfma4x4x1(float a, float b, f4 c) {
+  Wave& w = W();
+  const int l = lane();
+  uint32_t bits;
+  memcpy(&bits, &a, 4);
+  w.slot[l] = bits;
+  pthread_barrier_wait(&w.bar);
+  f4 d = c;
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t ab = (uint32_t)w.slot[(l & ~3) + i];
+    float av;
+    memcpy(&av, &ab, 4);
+    d[i] = fmaf(av, b, c[i]);
+  }
+  pthread_barrier_wait(&w.bar);
+  return d;
+}
 extern unsigned char* dyn_lds;
 // run a whole grid: one OS thread per lane, blocks one after the other
 void launch_grid(dim3 grid, dim3 block, size_t lds, void (*fn)(void*), void* arg);
@@ -145,6 +165,8 @@ inline void launch(dim3 grid, dim3 block, size_t lds, F&& body) {
 #define __builtin_amdgcn_wave_barrier() simt::wave_barrier()
 #define __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, x, y, z) \
   __builtin_bit_cast(gear::floatx4, simt::mfma(__builtin_bit_cast(simt::h8, (a)), __builtin_bit_cast(simt::h8, (b)), __builtin_bit_cast(simt::f4, (c))))
+#define __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, x, y, z) \
+  __builtin_bit_cast(gear::floatx4, simt::mfma4x4x1((a), (b), __builtin_bit_cast(simt::f4, (c))))
 #define __syncthreads() pthread_barrier_wait(&simt::block_bar)
 // shuffles inside segments of w lanes (w a power of two), as HIP defines them
 template <typename T> inline T __shfl(T v, int src, int w = 64) { return simt::shfl(v, (simt::lane() & ~(w - 1)) + (src & (w - 1))); }
