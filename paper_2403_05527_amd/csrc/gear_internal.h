@@ -160,22 +160,13 @@ __device__ __forceinline__ uint32_t key16x2(uint32_t h2) {
 // Loads and stores of data that is touched once per kernel and is larger than the
 // caches (non-temporal: the lines are not kept).
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint4 load_stream16(const void* p) {
   const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
-__device__ __forceinline__ uint2 load_stream8(const void* p) {
-  const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
-  return make_uint2(v.x, v.y);
-}
 __device__ __forceinline__ void store_stream16(void* p, uint4 v) {
   u32x4_t x = {v.x, v.y, v.z, v.w};
   __builtin_nontemporal_store(x, reinterpret_cast<u32x4_t*>(p));
-}
-__device__ __forceinline__ void store_stream8(void* p, uint2 v) {
-  u32x2_t x = {v.x, v.y};
-  __builtin_nontemporal_store(x, reinterpret_cast<u32x2_t*>(p));
 }
 // fp16 bit pattern of a key (the key of +-0 gives +0)
 __device__ __forceinline__ uint32_t unkey16(uint32_t k) {
@@ -188,9 +179,6 @@ __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
 }
 __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, a), __builtin_bit_cast(u16x2_t, b)));
-}
-__device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {   // wraps in each lane
-  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, a) - __builtin_bit_cast(u16x2_t, b));
 }
 // fp16 entry e (0..7) of a row piece of four words
 // (the words are passed by value: selecting between elements of an array in place is
@@ -220,10 +208,6 @@ __device__ __forceinline__ ThreshPair pack_thresh(const Thresh& th) {
   const uint32_t lob = th.i_bot < 0 ? 0u : (th.i_bot >= 0xFFFF ? 0x10000u : (uint32_t)th.i_bot + 1u);
   p.bot = (th.tau_bot << 16) + lob;
   return p;
-}
-__device__ __forceinline__ bool is_outlier(uint32_t key, uint32_t idx, const ThreshPair& p) {
-  const uint32_t k = key << 16;
-  return (k | (0xFFFFu - idx)) >= p.top || (k | idx) < p.bot;
 }
 __device__ __forceinline__ Thresh thresh_none() {
   Thresh th;
@@ -264,11 +248,6 @@ __device__ __forceinline__ GroupQ load_group(uint32_t sz_bits) {
 }
 __device__ __forceinline__ uint32_t group_bits(const GroupQ& q) {
   return f2h(q.delta) | (f2h(q.mn) << 16);
-}
-__device__ __forceinline__ uint32_t quant_code(float y, const GroupQ& q, float qmax) {
-  float t = __fmul_rn(__fsub_rn(y, q.mn), q.inv);
-  float c = fminf(fmaxf(rintf(t), 0.0f), qmax);
-  return (uint32_t)c;
 }
 // Byte 0 of four words in one word (codes and the like read off float mantissas).
 __device__ __forceinline__ uint32_t low_bytes4(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3) {
@@ -317,13 +296,6 @@ __device__ __forceinline__ float row16_max(float v) {
   v = fmaxf(v, dpp_f<DPP_XOR2>(v));
   v = fmaxf(v, dpp_f<DPP_HALF_MIRROR>(v));
   v = fmaxf(v, dpp_f<DPP_MIRROR>(v));
-  return v;
-}
-__device__ __forceinline__ float row16_min(float v) {
-  v = fminf(v, dpp_f<DPP_XOR1>(v));
-  v = fminf(v, dpp_f<DPP_XOR2>(v));
-  v = fminf(v, dpp_f<DPP_HALF_MIRROR>(v));
-  v = fminf(v, dpp_f<DPP_MIRROR>(v));
   return v;
 }
 __device__ __forceinline__ float lane_bcast(float v, int lane) {
