@@ -21,13 +21,16 @@ namespace gear {
 
 constexpr int PT = 256;  // tokens per sweep block
 
+// Sum over the block (128 or 256 threads; the same value in every thread).
 template <typename T>
-__device__ __forceinline__ T block128_sum(T v, T* red /* >= 2 */) {
+__device__ __forceinline__ T block_sum(T v, T* red /* 4 */) {
   v = wave_sum_shfl(v);
   block_lds_sync();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   block_lds_sync();
-  return red[0] + red[1];
+  T s = red[0] + red[1];
+  if (blockDim.x > 128) s += red[2] + red[3];
+  return s;
 }
 
 // grid (B*H), block 128: thread c owns row c of the [128 x R] matrix.
@@ -38,26 +41,37 @@ __device__ __forceinline__ T block128_sum(T v, T* red /* >= 2 */) {
 // final   : also sum the Gram partials, build C with orth(A) = A C, write
 //           B_out = B C as fp16 into the arena and C into cmat.
 template <int R>
-__global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict__ src_init, int rank,
-                                                        const float* __restrict__ partial, int npart,
-                                                        int do_orth, int final_round,
-                                                        float* __restrict__ Bcur, float* __restrict__ cmat,
-                                                        SegView sv) {
-  __shared__ double red[2];
-  __shared__ double G[R][R];
-  __shared__ double C[R][R];
-  const int slab = blockIdx.x, c = threadIdx.x;
+struct UpdateSmem {
+  double red[4];
+  double G[R][R];
+  double C[R][R];
+  double cj[R];   // work vector of the one thread that orthonormalises in coefficient space
+};
+// The body runs in a block of 128 threads (its own kernel) or of 256 (the one-block power
+// iteration of short segments, where threads 128.. only take part in the barriers).
+template <int R>
+__device__ __forceinline__ void pi_update_body(UpdateSmem<R>& sm, int slab, const float* __restrict__ src_init, int rank,
+                                               const float* __restrict__ partial, int npart, int do_orth,
+                                               int final_round, float* __restrict__ Bcur, float* __restrict__ cmat,
+                                               const SegView& sv) {
+  double (&G)[R][R] = sm.G;
+  double (&C)[R][R] = sm.C;
+  double* red = sm.red;
+  const int c = threadIdx.x;
+  const bool act = c < D;
   double q[R];
-  if (src_init) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) q[r] = r < rank ? (double)src_init[((size_t)slab * D + c) * rank + r] : 0.0;
-  } else {
+  for (int r = 0; r < R; ++r) q[r] = 0.0;
+  if (act) {
+    if (src_init) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) q[r] = 0.0;
-    const float* p = partial + (size_t)slab * npart * (D * R + R * R);
-    for (int i = 0; i < npart; ++i) {
+      for (int r = 0; r < R; ++r) q[r] = r < rank ? (double)src_init[((size_t)slab * D + c) * rank + r] : 0.0;
+    } else {
+      const float* p = partial + (size_t)slab * npart * (D * R + R * R);
+      for (int i = 0; i < npart; ++i) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) q[r] += (double)p[(size_t)i * (D * R + R * R) + c * R + r];
+        for (int r = 0; r < R; ++r) q[r] += (double)p[(size_t)i * (D * R + R * R) + c * R + r];
+      }
     }
   }
 
@@ -71,16 +85,16 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
     block_lds_sync();
     if (c == 0) {
       // Gram-Schmidt in coefficient space: column j of orth(A) is A * C[:, j].
-      bool valid[R];
+      uint32_t valid = 0;   // bit j: column j is kept
+      double* cj = sm.cj;
       for (int j = 0; j < R; ++j) {
-        double cj[R];
         for (int i = 0; i < R; ++i) cj[i] = (i == j) ? 1.0 : 0.0;
         const double before2 = G[j][j];
-        valid[j] = before2 > 0.0;
-        if (valid[j]) {
+        bool ok = before2 > 0.0;
+        if (ok) {
           for (int pass = 0; pass < 2; ++pass)
             for (int k = 0; k < j; ++k) {
-              if (!valid[k]) continue;
+              if (!((valid >> k) & 1u)) continue;
               double dot = 0.0;  // q_k^T v = c_k^T G c_j
               for (int a = 0; a < R; ++a)
                 for (int b = 0; b < R; ++b) dot += C[a][k] * G[a][b] * cj[b];
@@ -89,13 +103,14 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
           double after2 = 0.0;
           for (int a = 0; a < R; ++a)
             for (int b = 0; b < R; ++b) after2 += cj[a] * G[a][b] * cj[b];
-          if (!(after2 > 1e-10 * before2)) valid[j] = false;
+          if (!(after2 > 1e-10 * before2)) ok = false;
           else {
             const double inv = 1.0 / sqrt(after2);
             for (int a = 0; a < R; ++a) cj[a] *= inv;
           }
         }
-        for (int a = 0; a < R; ++a) C[a][j] = valid[j] ? cj[a] : 0.0;
+        if (ok) valid |= 1u << j;
+        for (int a = 0; a < R; ++a) C[a][j] = ok ? cj[a] : 0.0;
       }
     }
     block_lds_sync();
@@ -107,7 +122,8 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
       for (int r = 0; r < R; ++r) s += q[r] * C[r][j];
       o[j] = s;
     }
-    for (int j = 0; j < rank; ++j) sv.Bf[((size_t)slab * D + c) * sv.rank + j] = (uint16_t)f2h((float)o[j]);
+    if (act)
+      for (int j = 0; j < rank; ++j) sv.Bf[((size_t)slab * D + c) * sv.rank + j] = (uint16_t)f2h((float)o[j]);
     if (c < R * R) cmat[(size_t)slab * R * R + c] = (float)C[c / R][c % R];
     return;
   }
@@ -115,18 +131,18 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
   if (do_orth) {
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-      const double before2 = block128_sum(q[j] * q[j], red);
+      const double before2 = block_sum(q[j] * q[j], red);
       if (before2 == 0.0) { q[j] = 0.0; continue; }
       for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
         for (int i = 0; i < R; ++i) {
           if (i < j) {
-            const double dot = block128_sum(q[i] * q[j], red);
+            const double dot = block_sum(q[i] * q[j], red);
             q[j] -= dot * q[i];
           }
         }
       }
-      const double after2 = block128_sum(q[j] * q[j], red);
+      const double after2 = block_sum(q[j] * q[j], red);
       if (!(sqrt(after2) > 1e-12 * sqrt(before2))) q[j] = 0.0;
       else q[j] *= 1.0 / sqrt(after2);
     }
@@ -134,12 +150,24 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
     // keep magnitudes in range between rounds
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-      const double n2 = block128_sum(q[j] * q[j], red);
+      const double n2 = block_sum(q[j] * q[j], red);
       if (n2 > 0.0) q[j] *= 1.0 / sqrt(n2);
     }
   }
+  if (act) {
 #pragma unroll
-  for (int r = 0; r < R; ++r) Bcur[((size_t)slab * D + c) * R + r] = (float)q[r];
+    for (int r = 0; r < R; ++r) Bcur[((size_t)slab * D + c) * R + r] = (float)q[r];
+  }
+}
+
+template <int R>
+__global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict__ src_init, int rank,
+                                                        const float* __restrict__ partial, int npart,
+                                                        int do_orth, int final_round,
+                                                        float* __restrict__ Bcur, float* __restrict__ cmat,
+                                                        SegView sv) {
+  __shared__ UpdateSmem<R> sm;
+  pi_update_body<R>(sm, blockIdx.x, src_init, rank, partial, npart, do_orth, final_round, Bcur, cmat, sv);
 }
 
 // grid (ceil(n/PT), B*H), block 256; thread (r0 = tid/16, oc = tid%16) owns
@@ -156,23 +184,30 @@ __global__ __launch_bounds__(128) void pi_update_kernel(const float* __restrict_
 // multiply-adds (the sweeps are bound by vector instruction issue, not by HBM).
 // LAST: the final round, which also leaves a_t and the Gram matrix (its extra state costs
 // one resident block per CU, so the rounds before it are compiled without).
-template <bool IS_K, int R, bool LAST>
-__global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_kernel(const uint16_t* __restrict__ Y, SegView sv, int g,
-                                                       int bits, int n, const float* __restrict__ Bcur,
-                                                       float* __restrict__ partial, int npart,
-                                                       float* __restrict__ Atmp) {
-  __shared__ float red[4][D * R];
-  __shared__ float redg[4][R * R];
+template <bool IS_K, int R>
+struct SweepSmem {
+  float red[4][D * R];
+  float redg[4][R * R];
   // Keys: [2][groups of the block <= 8][128] (zero, scale); Values: [rows][groups of a row <= 4] (zero, 1/scale, scale, -)
-  __shared__ __attribute__((aligned(16))) float prm[IS_K ? 2 * (PT / 32) * D : PT * 4 * 4];
-  const int slab = blockIdx.y, pt = blockIdx.x;
+  __attribute__((aligned(16))) float prm[IS_K ? 2 * (PT / 32) * D : PT * 4 * 4];
+};
+// One block's share of a sweep: rows [pt * PT, pt * PT + PT) of slab `slab`, 256 threads.
+template <bool IS_K, int R, bool LAST>
+__device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, int pt, const uint16_t* __restrict__ Y,
+                                              const uint32_t* __restrict__ sv_sz, const uint32_t* __restrict__ sv_codes,
+                                              int sv_n_cap, int sv_ng_cap, int g, int bits, int n,
+                                              const float* __restrict__ Bcur, float* __restrict__ partial, int npart,
+                                              float* __restrict__ Atmp) {
+  float (&red)[4][D * R] = sm.red;
+  float (&redg)[4][R * R] = sm.redg;
+  float* prm = sm.prm;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r0 = tid >> 4, oc = tid & 15;
   const uint16_t* Xs = Y + (size_t)slab * n * D;
   const int lg = 31 - __clz(g);   // g is a power of two
   constexpr int GSTR = (PT / 32) * D;   // Keys: floats per parameter plane
   const float qmax = (float)((1 << bits) - 1);
-  const uint32_t* crow = sv.codes + (size_t)slab * sv.n_cap * (4 * bits);   // Keys: 128 * bits / 32 words per row
+  const uint32_t* crow = sv_codes + (size_t)slab * sv_n_cap * (4 * bits);   // Keys: 128 * bits / 32 words per row
 
   constexpr int UN = 4;  // rows in flight per thread
   // the rows of an iteration, all requested before the first one is used
@@ -201,7 +236,7 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
       const int gi = grp0 + (i >> 7);
       GroupQ q;
       q.mn = 0.0f; q.inv = 0.0f; q.delta = 0.0f;
-      if (gi < ng) q = load_group(sv.sz[((size_t)slab * sv.ng_cap + gi) * D + (i & 127)]);
+      if (gi < ng) q = load_group(sv_sz[((size_t)slab * sv_ng_cap + gi) * D + (i & 127)]);
       prm[i] = q.mn;
       prm[GSTR + i] = q.delta;
     }
@@ -211,7 +246,7 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
       const int t = pt * PT + (i >> ngl);
       GroupQ q;
       q.mn = 0.0f; q.inv = 0.0f; q.delta = 0.0f;
-      if (t < n) q = load_group(sv.sz[(((size_t)slab * sv.n_cap + t) << ngl) + (i & ((1 << ngl) - 1))]);
+      if (t < n) q = load_group(sv_sz[(((size_t)slab * sv_n_cap + t) << ngl) + (i & ((1 << ngl) - 1))]);
       *reinterpret_cast<float4*>(&prm[4 * i]) = make_float4(q.mn, q.inv, q.delta, 0.0f);
     }
   }
@@ -352,15 +387,24 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
   if (tid < R * R) out[D * R + tid] = LAST ? (redg[0][tid] + redg[1][tid] + redg[2][tid] + redg[3][tid]) : 0.0f;
 }
 
-// grid (ceil(n/256), B*H), block 256: one token per thread.
+template <bool IS_K, int R, bool LAST>
+__global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_kernel(const uint16_t* __restrict__ Y, SegView sv, int g,
+                                                       int bits, int n, const float* __restrict__ Bcur,
+                                                       float* __restrict__ partial, int npart,
+                                                       float* __restrict__ Atmp) {
+  __shared__ SweepSmem<IS_K, R> sm;
+  pi_sweep_body<IS_K, R, LAST>(sm, blockIdx.y, blockIdx.x, Y, sv.sz, sv.codes, sv.n_cap, sv.ng_cap, g, bits, n, Bcur, partial,
+                               npart, Atmp);
+}
+
+// A = a C for tokens [256 * pt, 256 * pt + 256) of one slab, one token per thread.  Cs: LDS, R * R floats.
 template <int R>
-__global__ __launch_bounds__(256) void pi_finish_kernel(const float* __restrict__ Atmp,
-                                                        const float* __restrict__ cmat, SegView sv, int n) {
-  __shared__ float C[R * R];
-  const int slab = blockIdx.y;
+__device__ __forceinline__ void pi_finish_body(float* Cs, int slab, int pt, const float* __restrict__ Atmp,
+                                               const float* __restrict__ cmat, const SegView& sv, int n) {
+  float* C = Cs;
   if (threadIdx.x < R * R) C[threadIdx.x] = cmat[(size_t)slab * R * R + threadIdx.x];
   block_lds_sync();
-  const int t = blockIdx.x * 256 + threadIdx.x;
+  const int t = pt * 256 + threadIdx.x;
   if (t >= n) return;
   float a[R];
 #pragma unroll
@@ -373,6 +417,50 @@ __global__ __launch_bounds__(256) void pi_finish_kernel(const float* __restrict_
   }
 }
 
+// grid (ceil(n/256), B*H), block 256.
+template <int R>
+__global__ __launch_bounds__(256) void pi_finish_kernel(const float* __restrict__ Atmp,
+                                                        const float* __restrict__ cmat, SegView sv, int n) {
+  __shared__ float C[R * R];
+  pi_finish_body<R>(C, blockIdx.y, blockIdx.x, Atmp, cmat, sv, n);
+}
+
+// The whole power iteration of a short segment (n <= PT: a flushed buffer) in one block per
+// slab: the same steps as the separate kernels, in the same order and on the same workspace
+// arrays, with block barriers where the kernel boundaries were (a slab's steps only depend
+// on that slab).  Saves 7 launches of a few microseconds each per tensor.
+// grid (B*H), block 256.
+template <bool IS_K, int R>
+__global__ __launch_bounds__(256, 1) void pi_small_kernel(const uint16_t* __restrict__ Y, SegView sv, int g, int bits,
+                                                          int n, int iters, const float* __restrict__ init_B,
+                                                          float* __restrict__ Bcur, float* __restrict__ partial,
+                                                          float* __restrict__ Atmp, float* __restrict__ cmat) {
+  __shared__ UpdateSmem<R> um;
+  __shared__ SweepSmem<IS_K, R> ss;
+  __shared__ float Cs[R * R];
+  const int slab = blockIdx.x;
+  pi_update_body<R>(um, slab, init_B, sv.rank, nullptr, 0, iters == 1 ? 1 : 0, 0, Bcur, cmat, sv);
+  __syncthreads();   // also orders the block's global writes before its reads
+#pragma unroll 1
+  for (int l = 0; l < iters; ++l) {
+    const int last = (l == iters - 1);
+    // the rounds read the same Y, codes and scales: an offset the compiler cannot see through
+    // keeps it from hoisting those loads out of the loop (and holding them in registers)
+    int off = 0;
+    GEAR_PIN_VGPR(off);
+    if (last)
+      pi_sweep_body<IS_K, R, true>(ss, slab, 0, Y + off, sv.sz + off, sv.codes + off, sv.n_cap, sv.ng_cap, g, bits, n, Bcur,
+                                   partial, 1, Atmp);
+    else
+      pi_sweep_body<IS_K, R, false>(ss, slab, 0, Y + off, sv.sz + off, sv.codes + off, sv.n_cap, sv.ng_cap, g, bits, n, Bcur,
+                                    partial, 1, Atmp);
+    __syncthreads();
+    pi_update_body<R>(um, slab, nullptr, sv.rank, partial, 1, (l == iters - 2) ? 1 : 0, last, Bcur, cmat, sv);
+    __syncthreads();
+  }
+  pi_finish_body<R>(Cs, slab, 0, Atmp, cmat, sv, n);
+}
+
 // ------------------------------------------------------------------ host side
 template <int R>
 static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
@@ -380,6 +468,13 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
                          hipStream_t st) {
   const int slabs = dm.B * dm.H;
   const int npart = (n + PT - 1) / PT;
+  if (npart == 1) {   // a short segment: everything in one block per slab
+    if (is_k)
+      hipLaunchKernelGGL((pi_small_kernel<true, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, iters, init_B, Bcur, partial, Atmp, cmat);
+    else
+      hipLaunchKernelGGL((pi_small_kernel<false, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, iters, init_B, Bcur, partial, Atmp, cmat);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, init_B, sv.rank, (const float*)nullptr,
                      0, iters == 1 ? 1 : 0, 0, Bcur, cmat, sv);
   for (int l = 0; l < iters; ++l) {
