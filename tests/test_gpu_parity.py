@@ -64,6 +64,21 @@ def test_small_ragged(bits, g):
     assert rep["K_nnz"] > 0 and rep["V_nnz"] > 0
 
 
+@pytest.mark.parametrize("iters", [1, 2, 4])
+def test_iteration_counts(iters):
+    """L = 1 (the only round is also the last), 2 and 4 rounds of Algorithm 2, on a prefill that
+    takes the kernel-per-step path (n > 256) and chunks that take the one-block path."""
+    w = small_workload(B=1, H_kv=4, H_q=4, n=300, bits=2, g=64, ppm=20000, rank=4, seed=40 + iters)
+    run_case(w, n_chunks=2, iters=iters)
+
+
+def test_value_lists_in_reserved_and_allocated_regions():
+    """s = 2.5 %: the overflow lists of the Value tiles are about as long as their reserved
+    regions (48 entries), so some lie there and some are allocated behind them."""
+    w = small_workload(B=2, H_kv=8, H_q=8, n=320, bits=2, g=64, ppm=25000, rank=2, seed=77)
+    run_case(w, n_chunks=1)
+
+
 @pytest.mark.parametrize("ppm,rank", [(0, 0), (0, 4), (20000, 0), (10000, 8), (50000, 2), (20000, 3)])
 def test_modes(ppm, rank):
     w = small_workload(B=1, H_kv=8, H_q=8, n=300, bits=2, g=64, ppm=ppm, rank=rank, seed=ppm + rank)
