@@ -318,7 +318,8 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
         }
         if (oc < ELL_K && (uint32_t)oc >= row_total) slots[oc] = 0u;   // empty slots
       }
-      inc[k] = wave_incl_scan(cnt[k]);
+      // rows with more than ELL_K outliers are the exception: most waves have nothing to scan
+      inc[k] = __ballot(cnt[k] != 0u) != 0ull ? wave_incl_scan(cnt[k]) : 0u;
       if (lane == 63) band_cnt[k][wave] = inc[k];
     }
     block_lds_sync();
