@@ -1,10 +1,11 @@
 // SVDSolver_r (Eq. 6, Algorithm 2): batched power iteration on the per-head
 // residual R = X - D - S.  The quantization kernels leave Y = X - S (fp16, outliers
-// zeroed) in a workspace buffer; every sweep re-derives R = Y - D-hat from it and the
-// stored (scale, zero) with the quantizer's own operation sequence.  That is exact
-// (no rounded copy of R), costs 2 bytes per entry and pass, and five more vector
-// instructions per entry than reading a stored remainder; a 16-bit copy of R itself
-// flips enough fp16 roundings of the stored factors to fail the attention tolerance.
+// zeroed) in a workspace buffer; every sweep re-derives R = (Y - zero) - code * scale from it
+// (Keys: with the stored codes; Values: with the code recomputed by the quantizer's own
+// operation sequence).  That is exact (no rounded copy of R) and costs 2 bytes per entry and
+// pass, for three more vector instructions per entry than reading a stored remainder; a
+// 16-bit copy of R itself flips enough fp16 roundings of the stored factors to fail the
+// attention tolerance.
 //
 //   pi_update  : B <- start matrix or sum of the sweep partials; column scaling
 //                between rounds (the span, hence A B^T, is unchanged); QR of B
@@ -14,6 +15,7 @@
 //                B' = sum_t R_t^T a_t, and in the last round a_t itself and the
 //                Gram matrix sum_t a_t a_t^T.
 //   pi_finish  : A = a C  (C = the r x r factor), rounded to fp16.
+//   pi_small   : all of the above for a segment of at most 256 tokens, in one block per slab.
 #include "gear_internal.h"
 #include "gear_launch.h"
 
