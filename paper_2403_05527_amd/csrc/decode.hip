@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(Dims dm, SegView k
   int tw0 = split * MFMA_TS + WTOK * wave, nw = k0.n - tw0, rkc = k0.rank, rvc = v0.rank;
   if (split >= nsplit) {
     const int item = 4 * (split - nsplit) + wave;
-    const int j = item / pp, part = item - j * pp;
+    const int j = pp == 2 ? item >> 1 : item, part = item - j * pp;   // pp is 1 or 2
     int n_j = 0, r_j = 0;
     if (j < cs.n_chunks) {
       n_j = cs.n[j];

@@ -131,14 +131,14 @@ __host__ __device__ inline int up16i(int x) { return (x + 15) & ~15; }
 template <int GQ>
 __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int rv, int ppm) {
   MfmaLayout L;
-  const int TB = bits == 2 ? 64 : 32, NG = D / g;
+  const int TB = bits == 2 ? 64 : 32, lg = g >= 128 ? 7 : g >= 64 ? 6 : 5, NG = D >> lg;   // g is 32, 64 or 128
   int o = 0;
   L.q = o; o += GQ * D * 4;
   L.misc = o; o += up16i((int)sizeof(MfmaMisc<GQ>));
   L.wave0 = o;
   int w = 0;
   L.sc = w; w += GQ * WTOK * 4;
-  L.szk = w; w += (WTOK / g) * D * 4;
+  L.szk = w; w += (WTOK >> lg) * D * 4;
   L.szv = w; w += WTOK * NG * 4;
   L.ak = w; w += up16i(WTOK * rk * 2);
   L.av = w; w += up16i(WTOK * rv * 2);
@@ -168,7 +168,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   constexpr int VBLK = WTOK / TB;             // Value blocks per wave
   const int tid = threadIdx.x, wave = GEAR_WAVE_UNIFORM(tid >> 6), lane = tid & 63;
   const int n16 = lane & 15, kg = lane >> 4;
-  const int g = dm.g, NG = D / g;
+  const int g = dm.g, lg = g >= 128 ? 7 : g >= 64 ? 6 : 5, NG = D >> lg;   // group indices are shifts: g is 32, 64 or 128
   const int rk = ks.rank, rv = vs.rank;
   const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk_cap, rv_cap, dm.ppm);
   float* Sq = reinterpret_cast<float*>(smem + L.q);                 // [GQ][128]
@@ -227,10 +227,10 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     qreg[k] = 0u;
     if (i < GQ * D / 2) qreg[k] = reinterpret_cast<const uint32_t*>(qg)[i];
   }
-  const int ngl = (nw + g - 1) / g;
+  const int ngl = (nw + g - 1) >> lg;
   const int n4_szk = ngl * (D / 4), n4_szv = (nw * NG + 3) >> 2, n4_ak = (nw * rk + 7) >> 3, n4_av = (nw * rv + 7) >> 3;
   const int n4_bk = nw > 0 ? 16 * rk : 0, n4_bv = nw > 0 ? 16 * rv : 0;   // 128 * rank fp16
-  const uint4* g_szk = reinterpret_cast<const uint4*>(ks.sz + ((size_t)slab * ks.ng_cap + tw0 / g) * D);
+  const uint4* g_szk = reinterpret_cast<const uint4*>(ks.sz + ((size_t)slab * ks.ng_cap + (tw0 >> lg)) * D);
   const uint4* g_szv = reinterpret_cast<const uint4*>(vs.sz + ((size_t)slab * vs.n_cap + tw0) * NG);
   const uint4* g_ak = reinterpret_cast<const uint4*>(ks.A + ((size_t)slab * ks.n_cap + tw0) * rk);
   const uint4* g_av = reinterpret_cast<const uint4*>(vs.A + ((size_t)slab * vs.n_cap + tw0) * rv);
@@ -319,12 +319,13 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   // rounded up to a power of two) are spread over the 64 lanes, P lanes per output, each
   // summing 128 / P channels; a butterfly over the P lanes finishes the sums.
   if (rk > 0) {
-    const int rkp = rk <= 1 ? 1 : rk <= 2 ? 2 : rk <= 4 ? 4 : 8;
+    const int lrk = rk <= 1 ? 0 : rk <= 2 ? 1 : rk <= 4 ? 2 : 3, rkp = 1 << lrk;
+    constexpr int LGQ = GQ == 1 ? 0 : GQ == 2 ? 1 : GQ == 4 ? 2 : 3;
     for (int i = lane; i < GQ * 8; i += 64) SqB[i] = 0.0f;   // slots r >= rk stay 0
     wave_lds_sync();
-    const int P = 64 / (GQ * rkp);
-    const int outi = lane / P, part = lane - outi * P;
-    const int hq = outi / rkp, r = outi - hq * rkp;
+    const int lP = 6 - LGQ - lrk, P = 1 << lP;   // 64 / (GQ * rkp)
+    const int outi = lane >> lP, part = lane & (P - 1);
+    const int hq = outi >> lrk, r = outi & (rkp - 1);
     float s = 0.0f;
     if (r < rk)
       for (int c = part; c < D; c += P) s += Sq[hq * D + c] * h2f(Sbfk[c * rk + r]);
@@ -344,7 +345,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     kslot[rep] = (ch >> 5) * 32 + idx;
     kscale[rep] = opscale(lg);
   }
-  for (int gw = 0; gw < WTOK / g; ++gw) {
+  for (int gw = 0; gw < (WTOK >> lg); ++gw) {
     if (gw * g >= nw) break;                        // wave-uniform
     float kb[GQ];
 #pragma unroll
@@ -698,7 +699,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
 
   // =================== merge the four waves' states, write the record ===================
   for (int i = tid; i < GQ * D; i += 256) {
-    const int hq = i / D, c = i % D, G = c / g;
+    const int hq = i / D, c = i % D, G = c >> lg;
     float Mx = -INFINITY;
 #pragma unroll
     for (int w = 0; w < 4; ++w) Mx = fmaxf(Mx, M.wstat[w][hq][0]);
