@@ -384,7 +384,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     for (int hq = 0; hq < GQ; ++hq) kbl = (hq == hq_l) ? kb[hq] : kbl;
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
-      if (mt / (g / 16) == gw) {
+      if ((mt >> (lg - 4)) == gw) {   // tile mt (16 tokens) lies in group gw
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
         if (BITS == 2) {
           uint32_t v[8];
@@ -577,7 +577,6 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
         }
       }
       wave_lds_sync();
-      const int tiles_per_G = g / 16;
       for (int G = 0; G < NG; ++G) {
         half8 pa0 = __builtin_bit_cast(half8, make_uint4(0, 0, 0, 0)), pa1 = pa0;
         if (n16 < 2 * GQ) {
@@ -587,7 +586,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          if (j / tiles_per_G == G) {
+          if ((j >> (lg - 4)) == G) {   // channel tile j (16 channels) lies in group G
             if (BITS == 2) {
               uint32_t v[8];
               Codec<2>::unpack(pin_here(vw[bl][j]), v);
