@@ -23,7 +23,7 @@ static_assert(MFMA_TS == DECODE_SPLIT, "split size is part of the workspace layo
 // blocks [nsplit, nsplit + ncb): four pieces of appended chunks each (one piece = up to 128
 // rows of one chunk, pp pieces per chunk), through the same code as the prefill; the
 // last block: the fp16 streaming-buffer rows.
-template <int BITS, int GQ>
+template <int BITS, int GQ, int LG>
 __global__ __launch_bounds__(256, 4) void decode_split_kernel(Dims dm, SegView k0, SegView v0, ChunkSet cs,
                                                               const uint16_t* __restrict__ q,
                                                               const uint16_t* __restrict__ Kbuf,
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(Dims dm, SegView k
     rkc = rank_cap;
     rvc = rank_cap;
   }
-  mfma_block<BITS, GQ>(smem_raw, dm, kw_, vw_, qg, slab, b, tw0, nw, rkc, rvc, rec_base, rec_stride);
+  mfma_block<BITS, GQ, LG>(smem_raw, dm, kw_, vw_, qg, slab, b, tw0, nw, rkc, rvc, rec_base, rec_stride);
 }
 
 // grid (B*H_q), block 128: thread c merges channel c of the row's nrec records.  Lane s of
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
   out[(size_t)row * D + c] = (uint16_t)f2h(o / L);
 }
 
-template <int BITS, int GQ>
+template <int BITS, int GQ, int LG>
 static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                                   const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
                                   int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st) {
@@ -115,13 +115,13 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
   if (lds < sizeof(TailSmem<GQ>)) lds = sizeof(TailSmem<GQ>);
   static size_t lds_allowed = 0;  // raised once per process and kernel instance
   if (lds > lds_allowed) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_split_kernel<BITS, GQ>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_split_kernel<BITS, GQ, LG>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     lds_allowed = lds;
   }
   dim3 grid(nsplit + ncb + 1, dm.B * dm.H);
-  hipLaunchKernelGGL((decode_split_kernel<BITS, GQ>), grid, dim3(256), lds, st, dm, k0, v0, cs, q, Kbuf, Vbuf,
+  hipLaunchKernelGGL((decode_split_kernel<BITS, GQ, LG>), grid, dim3(256), lds, st, dm, k0, v0, cs, q, Kbuf, Vbuf,
                      n_buf, n_buf_cap, nsplit, pp, ncb ? rcap : 0, partial);
   hipLaunchKernelGGL(decode_combine_kernel, dim3(dm.B * dm.Hq), dim3(128), 0, st, (const float*)partial,
                      nsplit + ncb + 1, out);
@@ -132,13 +132,19 @@ template <int BITS>
 static hipError_t launch_decode_b(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                                   const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
                                   int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st) {
+#define GEAR_DECODE_CASE(GQV)                                                                                          \
+  case GQV:                                                                                                            \
+    if (dm.g == 32) return launch_decode_t<BITS, GQV, 5>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st); \
+    if (dm.g == 64) return launch_decode_t<BITS, GQV, 6>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st); \
+    return launch_decode_t<BITS, GQV, 7>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
   switch (dm.Hq / dm.H) {
-    case 1: return launch_decode_t<BITS, 1>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
-    case 2: return launch_decode_t<BITS, 2>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
-    case 4: return launch_decode_t<BITS, 4>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
-    case 8: return launch_decode_t<BITS, 8>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
+    GEAR_DECODE_CASE(1)
+    GEAR_DECODE_CASE(2)
+    GEAR_DECODE_CASE(4)
+    GEAR_DECODE_CASE(8)
     default: return hipErrorInvalidValue;
   }
+#undef GEAR_DECODE_CASE
 }
 
 hipError_t launch_decode(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,

@@ -159,7 +159,7 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int r
 // segment for every wave, or one appended chunk per wave), all of slab (b, h).  Writes
 // the block's merged partial softmax record (m, l, o[128]) of each of the GQ query
 // heads.  rk_cap / rv_cap size the LDS layout (>= every wave's ranks).
-template <int BITS, int GQ>
+template <int BITS, int GQ, int LG>
 __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& ks, const SegView& vs,
                            const uint16_t* __restrict__ qg /* q of query head h*GQ of batch b */, int slab, int b,
                            int tw0, int nw, int rk_cap, int rv_cap, float* __restrict__ rec_base, int rec_stride) {
@@ -168,7 +168,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   constexpr int VBLK = WTOK / TB;             // Value blocks per wave
   const int tid = threadIdx.x, wave = GEAR_WAVE_UNIFORM(tid >> 6), lane = tid & 63;
   const int n16 = lane & 15, kg = lane >> 4;
-  const int g = dm.g, lg = g >= 128 ? 7 : g >= 64 ? 6 : 5, NG = D >> lg;   // group indices are shifts: g is 32, 64 or 128
+  constexpr int g = 1 << LG, lg = LG, NG = D >> LG;   // the group size (32, 64 or 128) is a template parameter: group loops unroll
   const int rk = ks.rank, rv = vs.rank;
   const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk_cap, rv_cap, dm.ppm);
   float* Sq = reinterpret_cast<float*>(smem + L.q);                 // [GQ][128]
