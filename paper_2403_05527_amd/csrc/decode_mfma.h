@@ -78,6 +78,49 @@ struct Codec<4> {
 // 2^(4 - lg) as a float (operand scale 16 / 2^lg)
 __device__ __forceinline__ float opscale(int lg) { return __uint_as_float((uint32_t)(127 + 4 - lg) << 23); }
 
+// R consecutive fp16 (R = 2, 4 or 8; p aligned to 2 R bytes) as floats: one LDS read.
+template <int R>
+__device__ __forceinline__ void lds_row_f16(const uint16_t* p, float* a) {
+  static_assert(R == 2 || R == 4 || R == 8, "one 4-, 8- or 16-byte read");
+  uint32_t w[R / 2];
+  if constexpr (R == 2) {
+    w[0] = *reinterpret_cast<const uint32_t*>(p);
+  } else if constexpr (R == 4) {
+    const uint2 v = *reinterpret_cast<const uint2*>(p);
+    w[0] = v.x; w[1] = v.y;
+  } else {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+  }
+#pragma unroll
+  for (int i = 0; i < R / 2; ++i) {
+    a[2 * i] = h2f(w[i] & 0xFFFFu);
+    a[2 * i + 1] = h2f(w[i] >> 16);
+  }
+}
+
+// Sums of several per-lane values over a row of 16 lanes in one go: the first exchanges
+// halve the number of values a lane carries instead of summing each value separately.
+// Lane l returns the row's sum of v[l & 3] (sum4) or v[l & 1] (sum2).
+constexpr int DPP_ROR4 = 0x124, DPP_ROR8 = 0x128;   // rotate by 4 / 8 lanes inside a row of 16
+__device__ __forceinline__ float row16_sum4(float v0, float v1, float v2, float v3, int lane) {
+  const bool b0 = (lane & 1) != 0, b1 = (lane & 2) != 0;
+  const float t0 = (b0 ? v1 : v0) + dpp_f<DPP_XOR1>(b0 ? v0 : v1);
+  const float t1 = (b0 ? v3 : v2) + dpp_f<DPP_XOR1>(b0 ? v2 : v3);
+  float u = (b1 ? t1 : t0) + dpp_f<DPP_XOR2>(b1 ? t0 : t1);
+  u += dpp_f<DPP_ROR4>(u);
+  u += dpp_f<DPP_ROR8>(u);
+  return u;
+}
+__device__ __forceinline__ float row16_sum2(float v0, float v1, int lane) {
+  const bool b0 = (lane & 1) != 0;
+  float u = (b0 ? v1 : v0) + dpp_f<DPP_XOR1>(b0 ? v0 : v1);
+  u += dpp_f<DPP_XOR2>(u);
+  u += dpp_f<DPP_ROR4>(u);
+  u += dpp_f<DPP_ROR8>(u);
+  return u;
+}
+
 // Position of Key channel ch (r = ch % 32 inside lane group ch / 32) in the B
 // operand: fp16 index (0..31) within the lane's 4 k-blocks x 8 slots, and the
 // bit shift of its pair.
@@ -152,6 +195,64 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int r
   L.wave_stride = up16i(w);
   L.total = L.wave0 + 4 * L.wave_stride;
   return L;
+}
+
+// Low-rank Key term of the rows lane and lane + 64 for a rank that is one LDS read per row:
+// score[row] += A_K[row] . (q^T B_K).
+template <int GQ, int R>
+__device__ __forceinline__ void lowrank_key_rows(const uint16_t* Sak, const float* SqB, float* Ssc, int lane, int nw) {
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) {
+    const int row = lane + 64 * rep;
+    if (row < nw) {
+      float a[R];
+      lds_row_f16<R>(Sak + row * R, a);
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) {
+        float s = Ssc[hq * WTOK + row];
+#pragma unroll
+        for (int r = 0; r < R; ++r) s += SqB[hq * 8 + r] * a[r];
+        Ssc[hq * WTOK + row] = s;
+      }
+    }
+  }
+}
+// p^T A_V over the wave's rows for such a rank, added into wv[hq * 8 + r] (zero on entry).
+template <int GQ, int R>
+__device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const float* Ssc, float* wv, int lane, int nw) {
+  float part[GQ][R];
+#pragma unroll
+  for (int hq = 0; hq < GQ; ++hq)
+#pragma unroll
+    for (int r = 0; r < R; ++r) part[hq][r] = 0.0f;
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) {
+    const int row = lane + 64 * rep;
+    if (row < nw) {
+      float a[R];
+      lds_row_f16<R>(Sav + row * R, a);
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) {
+        const float p = Ssc[hq * WTOK + row];
+#pragma unroll
+        for (int r = 0; r < R; ++r) part[hq][r] += p * a[r];
+      }
+    }
+  }
+  // the four rows of 16 lanes add their sums into LDS (fixed lane order inside the one instruction)
+#pragma unroll
+  for (int hq = 0; hq < GQ; ++hq) {
+    if constexpr (R == 2) {
+      const float u = row16_sum2(part[hq][0], part[hq][1], lane);
+      if ((lane & 15) < 2) atomicAdd(&wv[hq * 8 + (lane & 1)], u);
+    } else {
+#pragma unroll
+      for (int r0 = 0; r0 < R; r0 += 4) {
+        const float u = row16_sum4(part[hq][r0], part[hq][r0 + 1], part[hq][r0 + 2], part[hq][r0 + 3], lane);
+        if ((lane & 15) < 4) atomicAdd(&wv[hq * 8 + r0 + (lane & 3)], u);
+      }
+    }
+  }
 }
 
 // One block: each of the four waves takes up to 128 consecutive token rows [tw0, tw0 + nw)
@@ -303,6 +404,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     if (j < n4_bv) reinterpret_cast<uint4*>(Sbfv)[j] = g_bv[j];
   }
   for (int i = lane; i < GQ * D; i += 64) Sosp[i] = 0.0f;
+  if (lane < GQ * 8) (&M.wv[wave][0][0])[lane] = 0.0f;
   block_lds_sync();   // q and the B factors are visible to all waves; from here on waves run independently
 
   // fixed outlier slots of the Key rows lane and lane + 64 (an empty slot is 0: channel 0,
@@ -421,7 +523,16 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   }
 
   // low-rank Key term: lane handles rows lane and lane + 64
-  if (rk > 0) {
+  if (rk == 4) {
+    lowrank_key_rows<GQ, 4>(Sak, SqB, Ssc, lane, nw);
+    wave_lds_sync();
+  } else if (rk == 2) {
+    lowrank_key_rows<GQ, 2>(Sak, SqB, Ssc, lane, nw);
+    wave_lds_sync();
+  } else if (rk == 8) {
+    lowrank_key_rows<GQ, 8>(Sak, SqB, Ssc, lane, nw);
+    wave_lds_sync();
+  } else if (rk > 0) {
 #pragma unroll 1
     for (int rep = 0; rep < 2; ++rep) {
       const int row = lane + 64 * rep;
@@ -621,8 +732,15 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     }
   }
 
-  // p^T A_V (down-projection of the low-rank Value term) over the wave's rows
-  if (rv > 0) {
+  // p^T A_V (down-projection of the low-rank Value term) over the wave's rows; wv starts at 0
+  float* wv = &M.wv[wave][0][0];
+  if (rv == 4) {
+    lowrank_value_down<GQ, 4>(Sav, Ssc, wv, lane, nw);
+  } else if (rv == 2) {
+    lowrank_value_down<GQ, 2>(Sav, Ssc, wv, lane, nw);
+  } else if (rv == 8) {
+    lowrank_value_down<GQ, 8>(Sav, Ssc, wv, lane, nw);
+  } else if (rv > 0) {
     float part[GQ][8];
 #pragma unroll
     for (int hq = 0; hq < GQ; ++hq)
@@ -646,12 +764,11 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     for (int hq = 0; hq < GQ; ++hq)
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
-        float s = 0.0f;
-        if (r < rv) s = wave_sum(part[hq][r]);
-        if (lane == 0) M.wv[wave][hq][r] = s;
+        if (r < rv) {
+          const float s = wave_sum(part[hq][r]);
+          if (lane == 0) wv[hq * 8 + r] = s;
+        }
       }
-  } else if (lane < GQ * 8) {
-    M.wv[wave][lane >> 3][lane & 7] = 0.0f;
   }
   wave_lds_sync();
 
@@ -711,8 +828,25 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
       float ow = plane[hq * D + c] + M.pm[w][hq][G];
       const uint16_t* bfw = reinterpret_cast<const uint16_t*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.bfv);
-      const int rvw = M.rv[w];
-      for (int r = 0; r < rvw; ++r) ow += M.wv[w][hq][r] * h2f(bfw[c * rvw + r]);
+      const int rvw = GEAR_WAVE_UNIFORM(M.rv[w]);
+      const float* wvw = &M.wv[w][hq][0];
+      if (rvw == 4) {
+        float bb[4];
+        lds_row_f16<4>(bfw + c * 4, bb);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ow += wvw[r] * bb[r];
+      } else if (rvw == 2) {
+        float bb[2];
+        lds_row_f16<2>(bfw + c * 2, bb);
+        ow += wvw[0] * bb[0] + wvw[1] * bb[1];
+      } else if (rvw == 8) {
+        float bb[8];
+        lds_row_f16<8>(bfw + c * 8, bb);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) ow += wvw[r] * bb[r];
+      } else {
+        for (int r = 0; r < rvw; ++r) ow += wvw[r] * h2f(bfw[c * rvw + r]);
+      }
       o += f * ow;
       l += f * M.wstat[w][hq][1];
     }

@@ -88,6 +88,7 @@ inline int dpp_src(int l, int ctrl) {
   }
   if (ctrl == 0x140) return row + (15 - i);            // row_mirror
   if (ctrl == 0x141) return (l & ~7) + (7 - (l & 7));  // row_half_mirror
+  if (ctrl > 0x120 && ctrl <= 0x12F) return row + ((i - (ctrl & 15)) & 15);  // row_ror:n
   fprintf(stderr, "dpp ctrl %x not modelled\n", ctrl);
   abort();
 }
