@@ -24,7 +24,7 @@ static_assert(MFMA_TS == DECODE_SPLIT, "split size is part of the workspace layo
 // rows of one chunk, pp pieces per chunk), through the same code as the prefill; the
 // last block: the fp16 streaming-buffer rows.
 template <int BITS, int GQ, int LG>
-__global__ __launch_bounds__(256, 4) void decode_split_kernel(Dims dm, SegView k0, SegView v0, ChunkSet cs,
+__global__ __launch_bounds__(256, ((BITS == 2 && GQ <= 2) ? 5 : 4)) void decode_split_kernel(Dims dm, SegView k0, SegView v0, ChunkSet cs,
                                                               const uint16_t* __restrict__ q,
                                                               const uint16_t* __restrict__ Kbuf,
                                                               const uint16_t* __restrict__ Vbuf, int n_buf,
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(Dims dm, SegView k
   // one call site: the prefill segment for every wave, or one chunk piece per wave
   // (piece i = 4 * (split - nsplit) + wave covers rows [128 * (i % pp), ...) of chunk i / pp)
   SegView kw_ = k0, vw_ = v0;
-  int tw0 = split * MFMA_TS + WTOK * wave, nw = k0.n - tw0, rkc = k0.rank, rvc = v0.rank;
+  int tw0 = split * MFMA_TS + WTOK * wave, nw = k0.n - tw0;
   if (split >= nsplit) {
     const int item = 4 * (split - nsplit) + wave;
     const int j = pp == 2 ? item >> 1 : item, part = item - j * pp;   // pp is 1 or 2
@@ -59,10 +59,9 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(Dims dm, SegView k
     vw_ = chunk_view(cs.v0, cs.stride, j < cs.n_chunks ? j : 0, n_j, r_j);
     tw0 = WTOK * part;
     nw = n_j - tw0;
-    rkc = rank_cap;
-    rvc = rank_cap;
   }
-  mfma_block<BITS, GQ, LG>(smem_raw, dm, kw_, vw_, qg, slab, b, tw0, nw, rkc, rvc, rec_base, rec_stride);
+  mfma_block<BITS, GQ, LG>(smem_raw, dm, kw_, vw_, qg, slab, b, tw0, nw, k0.rank, v0.rank, rank_cap, split < nsplit,
+                           rec_base, rec_stride);
 }
 
 // grid (B*H_q), block 128: thread c merges channel c of the row's nrec records.  Lane s of
@@ -109,9 +108,10 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
   const int nsplit = (k0.n + MFMA_TS - 1) / MFMA_TS;
   const int pp = n_buf_cap > WTOK ? 2 : 1;            // pieces per chunk
   const int ncb = (cs.n_chunks * pp + 3) / 4;
-  const int rcap = k0.rank > rank_cap ? k0.rank : rank_cap;
-  const int rcap_v = v0.rank > rank_cap ? v0.rank : rank_cap;
-  size_t lds = (size_t)mfma_layout<GQ>(BITS, dm.g, ncb ? rcap : k0.rank, ncb ? rcap_v : v0.rank, dm.ppm).total;
+  int rc = 0;                                         // largest rank of an appended chunk
+  for (int j = 0; j < cs.n_chunks; ++j) rc = cs.rank[j] > rc ? cs.rank[j] : rc;
+  if (rc > rank_cap) return hipErrorInvalidValue;     // the cache never stores more than its configured rank
+  size_t lds = (size_t)mfma_layout<GQ>(BITS, dm.g, k0.rank, v0.rank, rc, dm.ppm).total;
   if (lds < sizeof(TailSmem<GQ>)) lds = sizeof(TailSmem<GQ>);
   static size_t lds_allowed = 0;  // raised once per process and kernel instance
   if (lds > lds_allowed) {
@@ -122,7 +122,7 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
   }
   dim3 grid(nsplit + ncb + 1, dm.B * dm.H);
   hipLaunchKernelGGL((decode_split_kernel<BITS, GQ, LG>), grid, dim3(256), lds, st, dm, k0, v0, cs, q, Kbuf, Vbuf,
-                     n_buf, n_buf_cap, nsplit, pp, ncb ? rcap : 0, partial);
+                     n_buf, n_buf_cap, nsplit, pp, rc, partial);
   hipLaunchKernelGGL(decode_combine_kernel, dim3(dm.B * dm.Hq), dim3(128), 0, st, (const float*)partial,
                      nsplit + ncb + 1, out);
   return hipGetLastError();

@@ -1,8 +1,8 @@
 // MFMA formulation of the compressed-cache attention read for one block of
 // MFMA_TS prefill tokens (v_mfma_f32_16x16x32_f16, fp32 accumulate).
 //
-// Key side    D[token][col]   = sum_c  code[token][c] * w[c][col]
-//             w[c][col] = q[hq][c] * scale_K[group][c]       (hi and lo fp16 parts)
+// Key side    D[col][token]   = sum_c  w[col][c] * code[token][c]
+//             w[col][c] = q[hq][c] * scale_K[group][c]       (hi and lo fp16 parts)
 // Value side  D[col][channel] = sum_t  P[col][t] * code[t][channel]
 //             P[col][t] = p[hq][t] * scale_V[t][G]           (hi and lo fp16 parts)
 // col = 2*hq + part: the query heads of one KV head (GQA) and the two fp16
@@ -159,8 +159,9 @@ __device__ __forceinline__ void val_slot(int t, int& kg, int& idx, int& lg) {
 constexpr int WTOK = 128;  // tokens per wave
 struct MfmaLayout {
   int q, misc;                                 // shared by the four waves
+  int bf, bf_v0, bf_cw, bf_vc;                 // B factors: one (K, V) pair for the block, or one per wave (chunks)
   int wave0, wave_stride;                      // per-wave region
-  int sc, szk, szv, ak, av, bfk, bfv, osp, opnd, qb;  // offsets inside a wave region
+  int sc, szk, szv, ak, av, osp, opnd, qb;     // offsets inside a wave region
   int total;
 };
 template <int GQ>
@@ -171,13 +172,25 @@ struct MfmaMisc {
   int rv[4];               // per wave: rank of its Value factors
 };
 __host__ __device__ inline int up16i(int x) { return (x + 15) & ~15; }
+// rk0, rv0: ranks of the prefill segment; rc: largest rank of an appended chunk (0: no chunk
+// blocks in the launch).  The four waves of a prefill block read one copy of B_K and B_V at
+// bf and bf + bf_v0; wave w of a chunk block keeps its chunk's pair at bf + w * bf_cw (+ bf_vc).
 template <int GQ>
-__host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int rv, int ppm) {
+__host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk0, int rv0, int rc, int ppm) {
   MfmaLayout L;
   const int TB = bits == 2 ? 64 : 32, lg = g >= 128 ? 7 : g >= 64 ? 6 : 5, NG = D >> lg;   // g is 32, 64 or 128
+  const int rk = rk0 > rc ? rk0 : rc, rv = rv0 > rc ? rv0 : rc;
   int o = 0;
   L.q = o; o += GQ * D * 4;
   L.misc = o; o += up16i((int)sizeof(MfmaMisc<GQ>));
+  L.bf = o;
+  L.bf_v0 = up16i(D * rk0 * 2);
+  L.bf_vc = up16i(D * rc * 2);
+  L.bf_cw = 2 * L.bf_vc;
+  {
+    const int shared = L.bf_v0 + up16i(D * rv0 * 2), per_wave = 4 * L.bf_cw;
+    o += shared > per_wave ? shared : per_wave;
+  }
   L.wave0 = o;
   int w = 0;
   L.sc = w; w += GQ * WTOK * 4;
@@ -185,8 +198,6 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk, int r
   L.szv = w; w += WTOK * NG * 4;
   L.ak = w; w += up16i(WTOK * rk * 2);
   L.av = w; w += up16i(WTOK * rv * 2);
-  L.bfk = w; w += up16i(D * rk * 2);
-  L.bfv = w; w += up16i(D * rv * 2);
   L.osp = w; w += GQ * D * 4;
   int oh = 2 * GQ * D;
   if (NG * 2 * GQ * TB > oh) oh = NG * 2 * GQ * TB;
@@ -259,11 +270,13 @@ __device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const fl
 // of the stored segment it is given (ks, vs may differ from wave to wave: the prefill
 // segment for every wave, or one appended chunk per wave), all of slab (b, h).  Writes
 // the block's merged partial softmax record (m, l, o[128]) of each of the GQ query
-// heads.  rk_cap / rv_cap size the LDS layout (>= every wave's ranks).
+// heads.  rk0 / rv0 / rc size the LDS layout (see mfma_layout); shared_b: the four waves
+// read the same segment (a prefill block), so its B factors are staged once.
 template <int BITS, int GQ, int LG>
 __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& ks, const SegView& vs,
                            const uint16_t* __restrict__ qg /* q of query head h*GQ of batch b */, int slab, int b,
-                           int tw0, int nw, int rk_cap, int rv_cap, float* __restrict__ rec_base, int rec_stride) {
+                           int tw0, int nw, int rk0, int rv0, int rc, bool shared_b, float* __restrict__ rec_base,
+                           int rec_stride) {
   constexpr int TB = (BITS == 2) ? 64 : 32;   // tokens per Value code block
   constexpr int KW = (BITS == 2) ? 2 : 4;     // Key code words per lane per M-tile
   constexpr int VBLK = WTOK / TB;             // Value blocks per wave
@@ -271,7 +284,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const int n16 = lane & 15, kg = lane >> 4;
   constexpr int g = 1 << LG, lg = LG, NG = D >> LG;   // the group size (32, 64 or 128) is a template parameter: group loops unroll
   const int rk = ks.rank, rv = vs.rank;
-  const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk_cap, rv_cap, dm.ppm);
+  const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk0, rv0, rc, dm.ppm);
   float* Sq = reinterpret_cast<float*>(smem + L.q);                 // [GQ][128]
   MfmaMisc<GQ>& M = *reinterpret_cast<MfmaMisc<GQ>*>(smem + L.misc);
   unsigned char* wbase = smem + L.wave0 + (size_t)wave * L.wave_stride;
@@ -280,8 +293,8 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   uint32_t* Sszv = reinterpret_cast<uint32_t*>(wbase + L.szv);      // [128][NG]
   uint16_t* Sak = reinterpret_cast<uint16_t*>(wbase + L.ak);        // [128][rk]
   uint16_t* Sav = reinterpret_cast<uint16_t*>(wbase + L.av);
-  uint16_t* Sbfk = reinterpret_cast<uint16_t*>(wbase + L.bfk);      // [128][rk]
-  uint16_t* Sbfv = reinterpret_cast<uint16_t*>(wbase + L.bfv);
+  uint16_t* Sbfk = reinterpret_cast<uint16_t*>(smem + L.bf + (shared_b ? 0 : wave * L.bf_cw));   // [128][rk]
+  uint16_t* Sbfv = reinterpret_cast<uint16_t*>(smem + L.bf + (shared_b ? L.bf_v0 : wave * L.bf_cw + L.bf_vc));
   float* Sosp = reinterpret_cast<float*>(wbase + L.osp);            // [GQ][128] this wave's output plane
   _Float16* opnd = reinterpret_cast<_Float16*>(wbase + L.opnd);
   float* SqB = reinterpret_cast<float*>(wbase + L.qb);              // [GQ][8] q^T B_K
@@ -330,7 +343,8 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   }
   const int ngl = (nw + g - 1) >> lg;
   const int n4_szk = ngl * (D / 4), n4_szv = (nw * NG + 3) >> 2, n4_ak = (nw * rk + 7) >> 3, n4_av = (nw * rv + 7) >> 3;
-  const int n4_bk = nw > 0 ? 16 * rk : 0, n4_bv = nw > 0 ? 16 * rv : 0;   // 128 * rank fp16
+  const bool stage_b = shared_b ? wave == 0 : nw > 0;   // a prefill block's first wave always owns rows
+  const int n4_bk = stage_b ? 16 * rk : 0, n4_bv = stage_b ? 16 * rv : 0;   // 128 * rank fp16
   const uint4* g_szk = reinterpret_cast<const uint4*>(ks.sz + ((size_t)slab * ks.ng_cap + (tw0 >> lg)) * D);
   const uint4* g_szv = reinterpret_cast<const uint4*>(vs.sz + ((size_t)slab * vs.n_cap + tw0) * NG);
   const uint4* g_ak = reinterpret_cast<const uint4*>(ks.A + ((size_t)slab * ks.n_cap + tw0) * rk);
@@ -405,6 +419,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   }
   for (int i = lane; i < GQ * D; i += 64) Sosp[i] = 0.0f;
   if (lane < GQ * 8) (&M.wv[wave][0][0])[lane] = 0.0f;
+  if (lane < GQ * 4) (&M.pm[wave][0][0])[lane] = 0.0f;
   block_lds_sync();   // q and the B factors are visible to all waves; from here on waves run independently
 
   // fixed outlier slots of the Key rows lane and lane + 64 (an empty slot is 0: channel 0,
@@ -480,10 +495,14 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       if (n16 < 2 * GQ) raw = *reinterpret_cast<const uint4*>(opnd + n16 * D + kg * 32 + jb * 8);
       bop[jb] = __builtin_bit_cast(half8, raw);
     }
-    const int hq_l = n16 >> 1;
-    float kbl = 0.0f;
+    // lane group kg receives columns 4 kg .. 4 kg + 3: both parts of query heads 2 kg and 2 kg + 1
+    const int hq0 = 2 * kg, hq1 = 2 * kg + 1;
+    float kb0 = 0.0f, kb1 = 0.0f;
 #pragma unroll
-    for (int hq = 0; hq < GQ; ++hq) kbl = (hq == hq_l) ? kb[hq] : kbl;
+    for (int hq = 0; hq < GQ; ++hq) {
+      kb0 = (hq == hq0) ? kb[hq] : kb0;
+      kb1 = (hq == hq1) ? kb[hq] : kb1;
+    }
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
       if ((mt >> (lg - 4)) == gw) {   // tile mt (16 tokens) lies in group gw
@@ -491,32 +510,22 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
         if (BITS == 2) {
           uint32_t v[8];
           Codec<2>::unpack(pin_here(kw[mt][0]), v);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[0], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[1], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(bop[0], as_half8(v[0], v[1], v[2], v[3]), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(bop[1], as_half8(v[4], v[5], v[6], v[7]), acc, 0, 0, 0);
           Codec<2>::unpack(pin_here(kw[mt][1]), v);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[2], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[4], v[5], v[6], v[7]), bop[3], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(bop[2], as_half8(v[0], v[1], v[2], v[3]), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(bop[3], as_half8(v[4], v[5], v[6], v[7]), acc, 0, 0, 0);
         } else {
 #pragma unroll
           for (int jb = 0; jb < 4; ++jb) {
             uint32_t v[4];
             Codec<4>::unpack(pin_here(kw[mt][jb % KW]), v);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(v[0], v[1], v[2], v[3]), bop[jb], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(bop[jb], as_half8(v[0], v[1], v[2], v[3]), acc, 0, 0, 0);
           }
         }
-        // D[token 4*kg + i][col n16]: add the hi and lo columns, keep the even ones
-        float4 s4;
-        s4.x = acc[0] + dpp_f<DPP_XOR1>(acc[0]);
-        s4.y = acc[1] + dpp_f<DPP_XOR1>(acc[1]);
-        s4.z = acc[2] + dpp_f<DPP_XOR1>(acc[2]);
-        s4.w = acc[3] + dpp_f<DPP_XOR1>(acc[3]);
-        if ((n16 & 1) == 0 && hq_l < GQ) {
-          s4.x = s4.x * MFMA_OUT_SCALE + kbl;
-          s4.y = s4.y * MFMA_OUT_SCALE + kbl;
-          s4.z = s4.z * MFMA_OUT_SCALE + kbl;
-          s4.w = s4.w * MFMA_OUT_SCALE + kbl;
-          *reinterpret_cast<float4*>(&Ssc[hq_l * WTOK + 16 * mt + 4 * kg]) = s4;
-        }
+        // D[col 4*kg + i][token n16]: the hi and lo columns of a query head sit in one lane
+        if (hq0 < GQ) Ssc[hq0 * WTOK + 16 * mt + n16] = (acc[0] + acc[1]) * MFMA_OUT_SCALE + kb0;
+        if (hq1 < GQ) Ssc[hq1 * WTOK + 16 * mt + n16] = (acc[2] + acc[3]) * MFMA_OUT_SCALE + kb1;
       }
     }
     wave_lds_sync();
@@ -714,14 +723,17 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       wave_lds_sync();
     }
   }
+  // sum_t p_t zero_V[t][G]: lanes with equal lane % NG hold group G's terms; the four rows
+  // of 16 lanes add their sums into pm (zero on entry; groups G >= NG stay 0)
 #pragma unroll
-  for (int hq = 0; hq < GQ; ++hq)
-#pragma unroll
-    for (int G = 0; G < 4; ++G) {
-      float s = 0.0f;
-      if (G < NG) s = wave_sum(Gl == G ? pmr[hq] : 0.0f);   // wave-uniform branch
-      if (lane == 0) M.pm[wave][hq][G] = s;
-    }
+  for (int hq = 0; hq < GQ; ++hq) {
+    float u = pmr[hq];
+    if (NG == 1) u += dpp_f<DPP_XOR1>(u);
+    if (NG <= 2) u += dpp_f<DPP_XOR2>(u);
+    u += dpp_f<DPP_ROR4>(u);
+    u += dpp_f<DPP_ROR8>(u);
+    if ((lane & 15) < NG) atomicAdd(&M.pm[wave][hq][lane & 15], u);
+  }
   // D[col 4*kg + i][channel 16 j + n16] -> this wave's output plane
   {
     const int hq0 = 2 * kg, hq1 = 2 * kg + 1;
@@ -827,7 +839,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       const float f = __expf(mw - Mx);
       const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
       float ow = plane[hq * D + c] + M.pm[w][hq][G];
-      const uint16_t* bfw = reinterpret_cast<const uint16_t*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.bfv);
+      const uint16_t* bfw = reinterpret_cast<const uint16_t*>(smem + L.bf + (shared_b ? L.bf_v0 : w * L.bf_cw + L.bf_vc));
       const int rvw = GEAR_WAVE_UNIFORM(M.rv[w]);
       const float* wvw = &M.wv[w][hq][0];
       if (rvw == 4) {
