@@ -312,20 +312,19 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       tab = (lane < 2) ? ks.sp_table[(size_t)slab * ks.ntile_cap + tile] : vs.sp_table[(size_t)slab * vs.ntile_cap + tile];
     }
   }
-  // Key codes of this wave's 8 M-tiles into registers
+  // Key codes of this wave's 8 M-tiles into registers (rows past the wave's last read as 0)
   uint32_t kw[8][KW];
+  {
+    constexpr int ROWB = 16 * BITS;   // bytes of one token's codes
+    const GEAR_BUF_T kbuf = GEAR_BUF_MAKE(ks.codes + ((size_t)slab * ks.n_cap + tw0) * (4 * BITS), nw * ROWB);
+    const uint32_t koff = n16 * ROWB + kg * (KW * 4);
 #pragma unroll
-  for (int mt = 0; mt < 8; ++mt) {
-    const int t = tw0 + 16 * mt + n16;
-#pragma unroll
-    for (int j = 0; j < KW; ++j) kw[mt][j] = 0u;
-    if (16 * mt + n16 < nw) {
-      const uint32_t* p = ks.codes + ((size_t)slab * ks.n_cap + t) * (4 * BITS) + KW * kg;
-      if (BITS == 2) {
-        const uint2 w = *reinterpret_cast<const uint2*>(p);
+    for (int mt = 0; mt < 8; ++mt) {
+      if constexpr (BITS == 2) {
+        const uint2 w = GEAR_BUF_LOAD8(kbuf, koff + mt * 16 * ROWB);
         kw[mt][0] = w.x; kw[mt][1] = w.y;
       } else {
-        const uint4 w = *reinterpret_cast<const uint4*>(p);
+        const uint4 w = GEAR_BUF_LOAD16(kbuf, koff + mt * 16 * ROWB);
         kw[mt][0] = w.x; kw[mt][1] = w.y; kw[mt][2] = w.z; kw[mt][3] = w.w;
       }
     }
@@ -351,15 +350,13 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const uint4* g_av = reinterpret_cast<const uint4*>(vs.A + ((size_t)slab * vs.n_cap + tw0) * rv);
   const uint4* g_bk = reinterpret_cast<const uint4*>(ks.Bf + (size_t)slab * D * rk);
   const uint4* g_bv = reinterpret_cast<const uint4*>(vs.Bf + (size_t)slab * D * rv);
-  // (written as conditional loads: a "cond ? *p : zero" is compiled into a load through
-  // a selected address, with the zero parked in scratch memory)
-  uint4 r_szk = make_uint4(0, 0, 0, 0), r_szv = r_szk, r_ak = r_szk, r_av = r_szk, r_bk = r_szk, r_bv = r_szk;
-  if (lane < n4_szk) r_szk = g_szk[lane];   // pieces 64.. (g = 32, rank 8) follow after the first
-  if (lane < n4_szv) r_szv = g_szv[lane];
-  if (lane < n4_ak) r_ak = g_ak[lane];
-  if (lane < n4_av) r_av = g_av[lane];
-  if (lane < n4_bk) r_bk = g_bk[lane];
-  if (lane < n4_bv) r_bv = g_bv[lane];
+  // piece lane of each array; pieces 64.. (g = 32, rank 8) follow after the first
+  const uint4 r_szk = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_szk, n4_szk * 16), lane * 16);
+  const uint4 r_szv = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_szv, n4_szv * 16), lane * 16);
+  const uint4 r_ak = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_ak, n4_ak * 16), lane * 16);
+  const uint4 r_av = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_av, n4_av * 16), lane * 16);
+  const uint4 r_bk = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_bk, n4_bk * 16), lane * 16);
+  const uint4 r_bv = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_bv, n4_bv * 16), lane * 16);
   // outlier lists of the wave's tiles: K tiles then V tiles, rows rebased to the wave
   // a table entry is trusted only as far as its pool reaches
   {
@@ -425,11 +422,11 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   // fixed outlier slots of the Key rows lane and lane + 64 (an empty slot is 0: channel 0,
   // value +0); they arrive while the Key scores are computed
   uint4 ellk[2];
+  {
+    static_assert(ELL_K == 4, "one 16-byte read per row");
+    const GEAR_BUF_T ebuf = GEAR_BUF_MAKE(ks.ell + ((size_t)slab * ks.n_cap + tw0) * ELL_K, dm.ppm > 0 ? nw * 16 : 0);
 #pragma unroll
-  for (int rep = 0; rep < 2; ++rep) {
-    ellk[rep] = make_uint4(0, 0, 0, 0);
-    if (dm.ppm > 0 && lane + 64 * rep < nw)
-      ellk[rep] = *reinterpret_cast<const uint4*>(ks.ell + ((size_t)slab * ks.n_cap + tw0 + lane + 64 * rep) * ELL_K);
+    for (int rep = 0; rep < 2; ++rep) ellk[rep] = GEAR_BUF_LOAD16(ebuf, (lane + 64 * rep) * 16);
   }
 
   // q^T B_K (down-projection of the low-rank Key term).  The GQ * rkp outputs (rkp = rank

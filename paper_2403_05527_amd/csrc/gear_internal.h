@@ -49,6 +49,16 @@
 #define GEAR_FMED3(x, lo, hi) __builtin_amdgcn_fmed3f((x), (lo), (hi))
 #endif
 
+// Raw buffer views: a load whose bytes do not all lie below the view's size returns 0,
+// so a ragged tail needs neither a per-lane test nor a 64-bit address per lane.
+#ifndef GEAR_BUF_T
+#define GEAR_BUF_T __amdgpu_buffer_rsrc_t
+#define GEAR_BUF_MAKE(p, bytes) \
+  __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(static_cast<const void*>(p)), 0, (int)(bytes), 0x00020000)
+#define GEAR_BUF_LOAD8(b, off) __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64((b), (int)(off), 0, 0))
+#define GEAR_BUF_LOAD16(b, off) __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128((b), (int)(off), 0, 0))
+#endif
+
 namespace gear {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));   // MFMA accumulator tile of one lane

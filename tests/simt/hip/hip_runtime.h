@@ -34,6 +34,8 @@ static inline float4 make_float4(float x, float y, float z, float w) { return fl
 static inline float2 make_float2(float x, float y) { return float2{x, y}; }
 static inline uint2 make_uint2(uint32_t x, uint32_t y) { return uint2{x, y}; }
 static inline uint4 make_uint4(uint32_t x, uint32_t y, uint32_t z, uint32_t w) { return uint4{x, y, z, w}; }
+struct simt_buf;
+template <typename T> static inline T simt_buf_load(const simt_buf& b, uint32_t off);
 typedef int hipError_t;
 typedef void* hipStream_t;
 enum { hipSuccess = 0, hipErrorInvalidValue = 1 };
@@ -47,6 +49,18 @@ inline const char* hipGetErrorString(hipError_t) { return "emulated"; }
 #define GEAR_WAVE_UNIFORM(x) (x)
 #define GEAR_BYTE_PERM(hi, lo, sel) simt_byte_perm((hi), (lo), (sel))
 #define GEAR_FMED3(x, lo, hi) fminf(fmaxf((x), (lo)), (hi))
+struct simt_buf { const unsigned char* p; uint32_t n; };
+#define GEAR_BUF_T simt_buf
+#define GEAR_BUF_MAKE(p, bytes) simt_buf{reinterpret_cast<const unsigned char*>(p), (uint32_t)(bytes)}
+#define GEAR_BUF_LOAD8(b, off) simt_buf_load<uint2>((b), (uint32_t)(off))
+#define GEAR_BUF_LOAD16(b, off) simt_buf_load<uint4>((b), (uint32_t)(off))
+// a load that does not lie wholly inside the view returns 0
+template <typename T> static inline T simt_buf_load(const simt_buf& b, uint32_t off) {
+  T r;
+  memset(&r, 0, sizeof(T));
+  if ((uint64_t)off + sizeof(T) <= b.n) memcpy(&r, b.p + off, sizeof(T));
+  return r;
+}
 static inline uint32_t simt_byte_perm(uint32_t hi, uint32_t lo, uint32_t sel) {
   const uint64_t src = ((uint64_t)hi << 32) | lo;
   uint32_t r = 0;
