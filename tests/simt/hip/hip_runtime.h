@@ -198,6 +198,7 @@ template <typename T> inline T __shfl_down(T v, int o, int w = 64) {
   return simt::shfl(v, (l & (w - 1)) + o < w ? l + o : l);
 }
 inline unsigned long long __ballot(bool p) { return simt::ballot(p); }
+inline int __popcll(unsigned long long x) { return __builtin_popcountll(x); }
 inline float __expf(float x) { return expf(x); }
 inline float __int_as_float(int i) { float f; memcpy(&f, &i, 4); return f; }
 inline int __float_as_int(float f) { int i; memcpy(&i, &f, 4); return i; }
