@@ -85,6 +85,17 @@ def test_modes(ppm, rank):
     run_case(w, n_chunks=1)
 
 
+@pytest.mark.parametrize("rank,rank_chunk", [(2, 4), (0, 2), (8, 1), (4, 3)])
+def test_chunk_rank_differs_from_prefill_rank(rank, rank_chunk):
+    # the decode kernel keeps one copy of the prefill's B factors per block and one per wave for
+    # the chunks: both orders of the two ranks, a prefill without factors, and a rank without a
+    # vector-read path (3) next to one with it
+    import dataclasses
+    w = dataclasses.replace(small_workload(B=1, H_kv=4, H_q=8, n=530, bits=2, g=64, ppm=20000, rank=rank,
+                                           seed=17 + rank), rank_chunk=rank_chunk)
+    run_case(w, n_chunks=5)
+
+
 @pytest.mark.parametrize("n", [1, 7, 20, 63, 64, 65, 513])
 def test_token_counts(n):
     w = small_workload(B=1, H_kv=4, H_q=4, n=n, bits=4, g=64, ppm=20000, rank=2, seed=n)
