@@ -55,9 +55,9 @@ def main():
     ap.add_argument("--chunks", type=int, default=-1, help="appended chunks in the caches the decode steps read")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="after the timed region, run three plain streaming kernels over 1 GiB (each reads 1 GiB "
-                         "and writes 1 GiB: out = in + 1 on bytes): the reference the rocprofv3 FETCH_SIZE / "
-                         "WRITE_SIZE readings are scaled by")
+                    help="kept for the profiling commands: the plain streaming kernel over 1 GiB (reads 1 GiB and "
+                         "writes 1 GiB: out = in + 1 on bytes) that the rocprofv3 FETCH_SIZE / WRITE_SIZE readings "
+                         "are scaled by now runs after every timed region")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over batch with no "
@@ -174,6 +174,8 @@ def main():
         "chunk_compress_ms": round(mean(t_chunk) * 1e3, 4),
         "decode_attn_us": round(td * 1e6, 2),
         "decode_attn_tokens_per_s": round(w.B / td, 1),
+        # the streaming loop: n_b decode steps and the flush of the full buffer into a chunk
+        "decode_loop_tokens_per_s": round(w.B * w.n_b / (w.n_b * td + mean(t_chunk)), 1),
         "roofline": {"bound": "hbm", "kernel": "gear_decode_attn (decode_split_kernel + combine)",
                      "achieved": round(dec_algo_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(dec_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
@@ -183,12 +185,20 @@ def main():
                               "achieved": round(comp_algo_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": round(comp_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
     }
-    if args.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.add(src, 1, out=dst)
-        torch.cuda.synchronize()
+    # a plain streaming kernel on the same box (out = in + 1 over 1 GiB of bytes: 1 GiB read + 1 GiB written),
+    # the practical ceiling next to the nominal peak; --calibrate-copy also uses it to scale the profiler's counters
+    src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 1, out=dst)
+    s0, s1 = ev(), ev()
+    s0.record()
+    for _ in range(5):
+        torch.add(src, 1, out=dst)
+    s1.record()
+    torch.cuda.synchronize()
+    res["roofline"]["measured_stream_gbps"] = round(5 * 2 * (1 << 30) / (s0.elapsed_time(s1) * 1e-3) / 1e9, 1)
+    del src, dst
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, K, V, ib, qs[0])
     print(json.dumps(res), flush=True)
