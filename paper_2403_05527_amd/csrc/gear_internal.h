@@ -308,6 +308,28 @@ __device__ __forceinline__ float row16_max(float v) {
   v = fmaxf(v, dpp_f<DPP_MIRROR>(v));
   return v;
 }
+// Sums of several per-lane values over a row of 16 lanes in one go: the first exchanges
+// halve the number of values a lane carries instead of summing each value separately.
+// Lane l returns the row's sum of v[l & 3] (sum4) or v[l & 1] (sum2).
+constexpr int DPP_ROR4 = 0x124, DPP_ROR8 = 0x128;   // rotate by 4 / 8 lanes inside a row of 16
+__device__ __forceinline__ float row16_sum4(float v0, float v1, float v2, float v3, int lane) {
+  const bool b0 = (lane & 1) != 0, b1 = (lane & 2) != 0;
+  const float t0 = (b0 ? v1 : v0) + dpp_f<DPP_XOR1>(b0 ? v0 : v1);
+  const float t1 = (b0 ? v3 : v2) + dpp_f<DPP_XOR1>(b0 ? v2 : v3);
+  float u = (b1 ? t1 : t0) + dpp_f<DPP_XOR2>(b1 ? t0 : t1);
+  u += dpp_f<DPP_ROR4>(u);
+  u += dpp_f<DPP_ROR8>(u);
+  return u;
+}
+__device__ __forceinline__ float row16_sum2(float v0, float v1, int lane) {
+  const bool b0 = (lane & 1) != 0;
+  float u = (b0 ? v1 : v0) + dpp_f<DPP_XOR1>(b0 ? v0 : v1);
+  u += dpp_f<DPP_XOR2>(u);
+  u += dpp_f<DPP_ROR4>(u);
+  u += dpp_f<DPP_ROR8>(u);
+  return u;
+}
+
 __device__ __forceinline__ float lane_bcast(float v, int lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }

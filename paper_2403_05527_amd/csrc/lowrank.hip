@@ -320,30 +320,34 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
 #pragma unroll
         for (int r = 0; r < R; ++r) a[r] += res[e] * bc[e][r];
       }
+      // the 16 lanes of a row hold one token: row sums of a[], delivered where the product
+      // B' += R^T a wants them, a_t[4 * nb + oc % 4] in lane oc (0 past R)
+      float bsel[NB];
+      if constexpr (R == 2) {
+        const float u = row16_sum2(a[0], a[1], lane);
+        bsel[0] = (oc & 2) ? 0.0f : u;
+      } else {
 #pragma unroll
-      for (int r = 0; r < R; ++r) a[r] = row16_sum(a[r]);   // the 16 lanes of a row hold one token
+        for (int nb = 0; nb < NB; ++nb) bsel[nb] = row16_sum4(a[4 * nb], a[4 * nb + 1], a[4 * nb + 2], a[4 * nb + 3], lane);
+      }
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        const int j = oc & 3;
-        float b = a[4 * nb];   // a_t[4 * nb + oc % 4] (0 past R)
-        if (4 * nb + 1 < R) b = (j == 1) ? a[4 * nb + 1 < R ? 4 * nb + 1 : 0] : b;
-        b = (j == 2) ? (4 * nb + 2 < R ? a[4 * nb + 2 < R ? 4 * nb + 2 : 0] : 0.0f) : b;
-        b = (j == 3) ? (4 * nb + 3 < R ? a[4 * nb + 3 < R ? 4 * nb + 3 : 0] : 0.0f) : b;
-        if (4 * nb + 1 >= R) b = (j == 1) ? 0.0f : b;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e][nb] = __builtin_amdgcn_mfma_f32_4x4x1f32(res[e], b, acc[e][nb], 0, 0, 0);
+        for (int e = 0; e < 8; ++e) acc[e][nb] = __builtin_amdgcn_mfma_f32_4x4x1f32(res[e], bsel[nb], acc[e][nb], 0, 0, 0);
       }
       if (LAST) {
-        if (oc == 0 && t < n) {
+        // lane oc < R holds a_t[oc]
+        const float mine = (NB > 1 && oc >= 4) ? bsel[NB - 1] : bsel[0];
+        if (oc < R && t < n) Atmp[((size_t)slab * n + t) * R + oc] = mine;
+        float ar[R];   // the whole a_t in every lane, from the four lanes of the quad
 #pragma unroll
-          for (int r = 0; r < R; ++r) Atmp[((size_t)slab * n + t) * R + r] = a[r];
+        for (int r = 0; r < R; ++r) {
+          const float src = bsel[r >> 2];
+          ar[r] = (r & 3) == 0 ? dpp_f<0x00>(src) : (r & 3) == 1 ? dpp_f<0x55>(src) : (r & 3) == 2 ? dpp_f<0xAA>(src) : dpp_f<0xFF>(src);
         }
         if (oc < R) {
-          float mine = 0.0f;
 #pragma unroll
-          for (int r = 0; r < R; ++r) mine = (r == oc) ? a[r] : mine;
-#pragma unroll
-          for (int r = 0; r < R; ++r) gacc[r] += mine * a[r];
+          for (int r = 0; r < R; ++r) gacc[r] += mine * ar[r];
         }
       }
     }
