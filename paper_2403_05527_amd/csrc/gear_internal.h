@@ -57,6 +57,10 @@
   __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(static_cast<const void*>(p)), 0, (int)(bytes), 0x00020000)
 #define GEAR_BUF_LOAD8(b, off) __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64((b), (int)(off), 0, 0))
 #define GEAR_BUF_LOAD16(b, off) __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128((b), (int)(off), 0, 0))
+// the same with the non-temporal hint (data that is read once)
+#define GEAR_BUF_LOAD16_NT(b, off) __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128((b), (int)(off), 0, 2))
+#define GEAR_BUF_LOAD4(b, off) ((uint32_t)__builtin_amdgcn_raw_buffer_load_b32((b), (int)(off), 0, 0))
+#define GEAR_BUF_LOAD2(b, off) ((uint32_t)__builtin_amdgcn_raw_buffer_load_b16((b), (int)(off), 0, 0))
 #endif
 
 namespace gear {

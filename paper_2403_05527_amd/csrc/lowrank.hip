@@ -213,18 +213,19 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
 
   constexpr int UN = 4;  // rows in flight per thread
   // the rows of an iteration, all requested before the first one is used
+  // (buffer views of the slab's rows: a row past the end reads as 0)
+  const GEAR_BUF_T xbuf = GEAR_BUF_MAKE(Xs, n * (D * 2));
+  const GEAR_BUF_T cbuf = GEAR_BUF_MAKE(crow, IS_K ? n * (16 * bits) : 0);
+  const int xoff0 = (pt * PT + r0) * (D * 2) + oc * 16;
+  const int coff0 = (pt * PT + r0) * (16 * bits) + oc * (bits == 4 ? 4 : 2);
   auto request = [&](int k0, uint4 (&xv)[UN], uint32_t (&cw)[UN]) {
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      const int t = pt * PT + r0 + 16 * (k0 + u);
-      xv[u] = make_uint4(0, 0, 0, 0);
+      xv[u] = GEAR_BUF_LOAD16_NT(xbuf, xoff0 + 16 * (k0 + u) * (D * 2));
       cw[u] = 0u;
-      if (t < n) {
-        xv[u] = load_stream16(Xs + (size_t)t * D + oc * 8);
-        if (IS_K) {
-          const uint32_t* cr = crow + (size_t)t * (4 * bits);
-          cw[u] = bits == 4 ? cr[oc] : (uint32_t)reinterpret_cast<const uint16_t*>(cr)[oc];
-        }
+      if (IS_K) {
+        const int co = coff0 + 16 * (k0 + u) * (16 * bits);
+        cw[u] = bits == 4 ? GEAR_BUF_LOAD4(cbuf, co) : GEAR_BUF_LOAD2(cbuf, co);
       }
     }
   };
@@ -316,7 +317,6 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
         } else {      // the code the quantizer computed
           res[e] = quant_error(y, vmn, vinv, vdl, qmax);
         }
-        if (IS_K && partial_blk && t >= n) res[e] = 0.0f;   // rows past the end (Values: their parameters are 0)
 #pragma unroll
         for (int r = 0; r < R; ++r) a[r] += res[e] * bc[e][r];
       }
@@ -329,6 +329,12 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
       } else {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) bsel[nb] = row16_sum4(a[4 * nb], a[4 * nb + 1], a[4 * nb + 2], a[4 * nb + 3], lane);
+      }
+      // Keys: a row past the end has res = -zero-point, not 0; its a_t is dropped instead
+      // (Values: the parameters of such rows are 0, so res is)
+      if (IS_K && partial_blk && t >= n) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) bsel[nb] = 0.0f;
       }
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {

@@ -54,6 +54,9 @@ struct simt_buf { const unsigned char* p; uint32_t n; };
 #define GEAR_BUF_MAKE(p, bytes) simt_buf{reinterpret_cast<const unsigned char*>(p), (uint32_t)(bytes)}
 #define GEAR_BUF_LOAD8(b, off) simt_buf_load<uint2>((b), (uint32_t)(off))
 #define GEAR_BUF_LOAD16(b, off) simt_buf_load<uint4>((b), (uint32_t)(off))
+#define GEAR_BUF_LOAD16_NT(b, off) simt_buf_load<uint4>((b), (uint32_t)(off))
+#define GEAR_BUF_LOAD4(b, off) simt_buf_load<uint32_t>((b), (uint32_t)(off))
+#define GEAR_BUF_LOAD2(b, off) ((uint32_t)simt_buf_load<uint16_t>((b), (uint32_t)(off)))
 // a load that does not lie wholly inside the view returns 0
 template <typename T> static inline T simt_buf_load(const simt_buf& b, uint32_t off) {
   T r;
