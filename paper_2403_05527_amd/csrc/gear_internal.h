@@ -44,6 +44,10 @@
 #ifndef GEAR_BYTE_PERM
 #define GEAR_BYTE_PERM(hi, lo, sel) __builtin_amdgcn_perm((hi), (lo), (sel))
 #endif
+// v_bfe_u32: `width` bits of x from bit `off`
+#ifndef GEAR_UBFE
+#define GEAR_UBFE(x, off, width) __builtin_amdgcn_ubfe((x), (off), (width))
+#endif
 // v_med3_f32: the median of three = x clamped to [lo, hi]
 #ifndef GEAR_FMED3
 #define GEAR_FMED3(x, lo, hi) __builtin_amdgcn_fmed3f((x), (lo), (hi))

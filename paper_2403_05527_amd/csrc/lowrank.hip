@@ -304,6 +304,11 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
         vmn = pv.x; vinv = pv.y; vdl = pv.z;
       }
       const uint32_t w[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+      float cf[8];   // Keys: the stored codes of my 8 channels as floats (one bit-field extract each)
+      if (IS_K) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) cf[e] = (float)GEAR_UBFE(cw[u], e * bits, bits);
+      }
       float res[8];
       float a[R];
 #pragma unroll
@@ -312,8 +317,7 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
       for (int e = 0; e < 8; ++e) {
         const float y = h2f((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xFFFFu));
         if (IS_K) {   // the stored code
-          const float c = (float)((cw[u] >> (e * bits)) & (uint32_t)((1 << bits) - 1));
-          res[e] = __builtin_fmaf(-c, pdl[e], y - pmn[e]);
+          res[e] = __builtin_fmaf(-cf[e], pdl[e], y - pmn[e]);
         } else {      // the code the quantizer computed
           res[e] = quant_error(y, vmn, vinv, vdl, qmax);
         }

@@ -49,6 +49,7 @@ inline const char* hipGetErrorString(hipError_t) { return "emulated"; }
 #define GEAR_WAVE_UNIFORM(x) (x)
 #define GEAR_BYTE_PERM(hi, lo, sel) simt_byte_perm((hi), (lo), (sel))
 #define GEAR_FMED3(x, lo, hi) fminf(fmaxf((x), (lo)), (hi))
+#define GEAR_UBFE(x, off, width) (((uint32_t)(x) >> (off)) & ((1u << (width)) - 1u))
 struct simt_buf { const unsigned char* p; uint32_t n; };
 #define GEAR_BUF_T simt_buf
 #define GEAR_BUF_MAKE(p, bytes) simt_buf{reinterpret_cast<const unsigned char*>(p), (uint32_t)(bytes)}
