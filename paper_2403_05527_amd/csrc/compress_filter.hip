@@ -65,33 +65,34 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
   constexpr int NWD = VW >= 2 ? VW / 2 : 1;
   {
     const int ngrp = (n_pad >> 3) * U;
-    for (int gidx = tid; gidx < ngrp; gidx += NT) {
+    // a view of the column block that ends with its last row: rows past n read as 0 (the
+    // selection never looks at them, they only have to be defined)
+    const GEAR_BUF_T xb = GEAR_BUF_MAKE(X, n > 0 ? (n - 1) * (D * 2) + CB * 2 : 0);
+    auto load_unit = [&](int gidx, uint32_t (&w)[8][NWD]) {
       const int rg = gidx / U, u = gidx - rg * U;
-      const int row0 = rg * 8;
-      uint32_t w[8][NWD];
+      const int off = rg * 8 * (D * 2) + u * (VW * 2);
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-#pragma unroll
-        for (int j = 0; j < NWD; ++j) w[k][j] = 0u;
-        if (row0 + k < n) {
-          const uint16_t* p = X + (size_t)(row0 + k) * D + u * VW;
-          if (VW == 8) {
-            const uint4 t4 = *reinterpret_cast<const uint4*>(p);
-            w[k][0] = t4.x; w[k][NWD > 1 ? 1 : 0] = t4.y; w[k][NWD > 2 ? 2 : 0] = t4.z; w[k][NWD > 3 ? 3 : 0] = t4.w;
-          } else if (VW == 4) {
-            const uint2 t2 = *reinterpret_cast<const uint2*>(p);
-            w[k][0] = t2.x; w[k][NWD > 1 ? 1 : 0] = t2.y;
-          } else if (VW == 2) {
-            w[k][0] = *reinterpret_cast<const uint32_t*>(p);
-          } else {
-            w[k][0] = *p;
-          }
+        if constexpr (VW == 8) {
+          const uint4 t4 = GEAR_BUF_LOAD16(xb, off + k * (D * 2));
+          w[k][0] = t4.x; w[k][1] = t4.y; w[k][2] = t4.z; w[k][3] = t4.w;
+        } else if constexpr (VW == 4) {
+          const uint2 t2 = GEAR_BUF_LOAD8(xb, off + k * (D * 2));
+          w[k][0] = t2.x; w[k][1] = t2.y;
+        } else if constexpr (VW == 2) {
+          w[k][0] = GEAR_BUF_LOAD4(xb, off + k * (D * 2));
+        } else {
+          w[k][0] = GEAR_BUF_LOAD2(xb, off + k * (D * 2));
         }
       }
+    };
+    auto store_unit = [&](int gidx, uint32_t (&w)[8][NWD]) {
+      const int rg = gidx / U, u = gidx - rg * U;
+      const int row0 = rg * 8;
 #pragma unroll
       for (int k = 0; k < 8; ++k)
 #pragma unroll
-        for (int j = 0; j < NWD; ++j) w[k][j] = (row0 + k < n) ? key16x2(w[k][j]) : 0u;
+        for (int j = 0; j < NWD; ++j) w[k][j] = key16x2(w[k][j]);
 #pragma unroll
       for (int c = 0; c < VW; ++c) {
         const int j = c >> 1;
@@ -100,6 +101,15 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
                                    GEAR_BYTE_PERM(w[5][j], w[4][j], sel), GEAR_BYTE_PERM(w[7][j], w[6][j], sel));
         *reinterpret_cast<uint4*>(tile + (size_t)(u * VW + c) * n_pad + row0) = o;
       }
+    };
+    // two units per round, the loads of both in flight together
+    for (int gidx = tid; gidx < ngrp; gidx += 2 * NT) {
+      uint32_t wa[8][NWD], wb[8][NWD];
+      const bool second = gidx + NT < ngrp;
+      load_unit(gidx, wa);
+      if (second) load_unit(gidx + NT, wb);
+      store_unit(gidx, wa);
+      if (second) store_unit(gidx + NT, wb);
     }
   }
   block_lds_sync();
