@@ -34,15 +34,15 @@ __global__ __launch_bounds__(256, (NC <= 10 ? 4 : 2)) void v_select_kernel(const
   for (int i = 0; i < tpw; ++i) {
     const int t = (blockIdx.x * tpw + i) * 4 + wave;
     const bool tvalid = t < n;
+    // (a view of the batch element's H * n rows: heads past H read as 0; entries past N are
+    // never looked at by the selection, they only have to be defined)
+    const GEAR_BUF_T vb = GEAR_BUF_MAKE(V + (size_t)b * H * n * D, tvalid ? (uint32_t)H * n * (D * 2) : 0u);
+    const uint32_t off0 = ((uint32_t)hsub * n + t) * (D * 2) + oc * 16;
     uint4 x[NC];
 #pragma unroll
     for (int ch = 0; ch < NC; ++ch) {
-      const int head = 4 * ch + hsub;
-      x[ch] = make_uint4(0, 0, 0, 0);
-      if (tvalid && head < H) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(V + (((size_t)(b * H + head) * n + t) * D + oc * 8));
-        x[ch] = make_uint4(key16x2(raw.x), key16x2(raw.y), key16x2(raw.z), key16x2(raw.w));
-      }
+      const uint4 raw = GEAR_BUF_LOAD16(vb, off0 + (uint32_t)ch * 4u * n * (D * 2));
+      x[ch] = make_uint4(key16x2(raw.x), key16x2(raw.y), key16x2(raw.z), key16x2(raw.w));
     }
     RegSource<NC> src{x};
     const Thresh th = wave_select(src, N, k_top, k_bot, hist + wave * SELECT_LDS_WORDS, tvalid);
