@@ -162,12 +162,13 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
   const uint16_t* X = K + (size_t)slab * n * D;
 
   // every row of the tile is requested before the first one is used
+  const GEAR_BUF_T xb = GEAR_BUF_MAKE(X, (uint32_t)n * (D * 2));
+  const GEAR_BUF_T yb = GEAR_BUF_MAKE(Yout ? Yout + (size_t)slab * n * D : nullptr, Yout ? (uint32_t)n * (D * 2) : 0u);
   uint32_t raw[NK][4];
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
     const int t = t0 + r0 + 16 * k;
-    uint4 q = make_uint4(0, 0, 0, 0);
-    if (t < n) q = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
+    const uint4 q = GEAR_BUF_LOAD16(xb, (uint32_t)t * (D * 2) + oc * 16);   // rows past the end read as 0
     raw[k][0] = q.x; raw[k][1] = q.y; raw[k][2] = q.z; raw[k][3] = q.w;
   }
   // thresholds of the 128 channels, staged through LDS: one coalesced read per block
@@ -278,9 +279,9 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
             else cw1 = __builtin_fmaf(c, (float)(1u << (4 * (e - 4))), cw1);
           }
         }
-        if (Yout)
-          store_stream16(Yout + ((size_t)slab * n + t) * D + oc * 8,
-                         make_uint4(raw[k][0] & ~msk[k][0], raw[k][1] & ~msk[k][1], raw[k][2] & ~msk[k][2], raw[k][3] & ~msk[k][3]));
+        // (an empty view when the caller wants no Y)
+        GEAR_BUF_STORE16_NT(yb, (uint32_t)t * (D * 2) + oc * 16,
+                            make_uint4(raw[k][0] & ~msk[k][0], raw[k][1] & ~msk[k][1], raw[k][2] & ~msk[k][2], raw[k][3] & ~msk[k][3]));
         if (BITS == 4) {
           crow[(size_t)t * dm.wpr + oc] = (uint32_t)cw0 | ((uint32_t)cw1 << 16);
         } else {  // 2 bits: 16 bits per thread

@@ -78,17 +78,16 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
   block_lds_sync();
 
   // every row of the tile and its thresholds are requested before the first one is used
+  const GEAR_BUF_T xb = GEAR_BUF_MAKE(X, (uint32_t)n * (D * 2));
+  const GEAR_BUF_T yb = GEAR_BUF_MAKE(Yout ? Yout + (size_t)slab * n * D : nullptr, Yout ? (uint32_t)n * (D * 2) : 0u);
   uint4 xrow[4];
   ThreshPair trow[4];
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     const int t = t0 + r0 + 16 * k;
-    xrow[k] = make_uint4(0, 0, 0, 0);
-    trow[k] = pack_thresh(thresh_none());   // rows past the end have no outliers
-    if (t < n) {
-      xrow[k] = *reinterpret_cast<const uint4*>(X + (size_t)t * D + oc * 8);
-      if (dm.ppm > 0) trow[k] = thrV[(size_t)b * n + t];
-    }
+    xrow[k] = GEAR_BUF_LOAD16(xb, (uint32_t)t * (D * 2) + oc * 16);   // rows past the end read as 0
+    trow[k] = pack_thresh(thresh_none());                             // and have no outliers
+    if (t < n && dm.ppm > 0) trow[k] = thrV[(size_t)b * n + t];
   }
   // in-vector index of entry e: h*128 + 8*oc + e; the low three bits are e
   const uint32_t cB0 = (uint32_t)(h * D + oc * 8), cT0 = (0xFFFFu - cB0) & ~7u;
@@ -161,10 +160,11 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
     *reinterpret_cast<uint2*>(&stage[tl * PITCH + oc * 8]) = make_uint2(cb0, cb1);
     if (tv) {
       if ((oc & ((g >> 3) - 1)) == 0) sv.sz[((size_t)slab * sv.n_cap + t) * (D >> lg) + ((oc * 8) >> lg)] = group_bits(q);
-      if (Yout)   // Y = X - S (fp16, outliers zeroed): the power iteration re-derives the quantization error from it
-        store_stream16(Yout + ((size_t)slab * n + t) * D + oc * 8,
-                       make_uint4(raw[0] & ~msk[0], raw[1] & ~msk[1], raw[2] & ~msk[2], raw[3] & ~msk[3]));
     }
+    // Y = X - S (fp16, outliers zeroed): the power iteration re-derives the quantization error from it
+    // (an empty view when the caller wants no Y; rows past the end fall outside the view)
+    GEAR_BUF_STORE16_NT(yb, (uint32_t)t * (D * 2) + oc * 16,
+                        make_uint4(raw[0] & ~msk[0], raw[1] & ~msk[1], raw[2] & ~msk[2], raw[3] & ~msk[3]));
   }
   block_lds_sync();
 

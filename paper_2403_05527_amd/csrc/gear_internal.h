@@ -65,6 +65,9 @@
 #define GEAR_BUF_LOAD16_NT(b, off) __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128((b), (int)(off), 0, 2))
 #define GEAR_BUF_LOAD4(b, off) ((uint32_t)__builtin_amdgcn_raw_buffer_load_b32((b), (int)(off), 0, 0))
 #define GEAR_BUF_LOAD2(b, off) ((uint32_t)__builtin_amdgcn_raw_buffer_load_b16((b), (int)(off), 0, 0))
+// a store that does not lie wholly inside the view is dropped; non-temporal (data written once, read by a later kernel)
+#define GEAR_BUF_STORE16_NT(b, off, v) \
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(gear::u32x4_t, (v)), (b), (int)(off), 0, 2)
 #endif
 
 namespace gear {

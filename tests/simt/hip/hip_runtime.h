@@ -58,6 +58,11 @@ struct simt_buf { const unsigned char* p; uint32_t n; };
 #define GEAR_BUF_LOAD16_NT(b, off) simt_buf_load<uint4>((b), (uint32_t)(off))
 #define GEAR_BUF_LOAD4(b, off) simt_buf_load<uint32_t>((b), (uint32_t)(off))
 #define GEAR_BUF_LOAD2(b, off) ((uint32_t)simt_buf_load<uint16_t>((b), (uint32_t)(off)))
+#define GEAR_BUF_STORE16_NT(b, off, v) simt_buf_store((b), (uint32_t)(off), (v))
+// a store that does not lie wholly inside the view is dropped
+template <typename T> static inline void simt_buf_store(const simt_buf& b, uint32_t off, const T& v) {
+  if ((uint64_t)off + sizeof(T) <= b.n) memcpy(const_cast<unsigned char*>(b.p) + off, &v, sizeof(T));
+}
 // a load that does not lie wholly inside the view returns 0
 template <typename T> static inline T simt_buf_load(const simt_buf& b, uint32_t off) {
   T r;
