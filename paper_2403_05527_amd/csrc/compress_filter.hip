@@ -248,7 +248,7 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
 
   // codes (packed token-major), and Y = X - S (fp16, outliers zeroed) for the power iteration,
   // which re-derives the quantization error from it
-  uint32_t* crow = sv.codes + (size_t)slab * sv.n_cap * dm.wpr;
+  const GEAR_BUF_T cbuf = GEAR_BUF_MAKE(sv.codes + (size_t)slab * sv.n_cap * dm.wpr, (uint32_t)n * (dm.wpr * 4));
 #pragma unroll
   for (int gi = 0; gi < NGW; ++gi) {
     float gmn[8], ginv[8];
@@ -283,9 +283,9 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
         GEAR_BUF_STORE16_NT(yb, (uint32_t)t * (D * 2) + oc * 16,
                             make_uint4(raw[k][0] & ~msk[k][0], raw[k][1] & ~msk[k][1], raw[k][2] & ~msk[k][2], raw[k][3] & ~msk[k][3]));
         if (BITS == 4) {
-          crow[(size_t)t * dm.wpr + oc] = (uint32_t)cw0 | ((uint32_t)cw1 << 16);
+          GEAR_BUF_STORE4(cbuf, (uint32_t)t * (dm.wpr * 4) + oc * 4, (uint32_t)cw0 | ((uint32_t)cw1 << 16));
         } else {  // 2 bits: 16 bits per thread
-          reinterpret_cast<uint16_t*>(crow + (size_t)t * dm.wpr)[oc] = (uint16_t)(uint32_t)cw0;
+          GEAR_BUF_STORE2(cbuf, (uint32_t)t * (dm.wpr * 4) + oc * 2, (uint32_t)cw0);
         }
       }
     }

@@ -68,6 +68,8 @@
 // a store that does not lie wholly inside the view is dropped; non-temporal (data written once, read by a later kernel)
 #define GEAR_BUF_STORE16_NT(b, off, v) \
   __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(gear::u32x4_t, (v)), (b), (int)(off), 0, 2)
+#define GEAR_BUF_STORE4(b, off, v) __builtin_amdgcn_raw_buffer_store_b32((uint32_t)(v), (b), (int)(off), 0, 0)
+#define GEAR_BUF_STORE2(b, off, v) __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(v), (b), (int)(off), 0, 0)
 #endif
 
 namespace gear {

@@ -59,6 +59,8 @@ struct simt_buf { const unsigned char* p; uint32_t n; };
 #define GEAR_BUF_LOAD4(b, off) simt_buf_load<uint32_t>((b), (uint32_t)(off))
 #define GEAR_BUF_LOAD2(b, off) ((uint32_t)simt_buf_load<uint16_t>((b), (uint32_t)(off)))
 #define GEAR_BUF_STORE16_NT(b, off, v) simt_buf_store((b), (uint32_t)(off), (v))
+#define GEAR_BUF_STORE4(b, off, v) simt_buf_store<uint32_t>((b), (uint32_t)(off), (uint32_t)(v))
+#define GEAR_BUF_STORE2(b, off, v) simt_buf_store<uint16_t>((b), (uint32_t)(off), (uint16_t)(v))
 // a store that does not lie wholly inside the view is dropped
 template <typename T> static inline void simt_buf_store(const simt_buf& b, uint32_t off, const T& v) {
   if ((uint64_t)off + sizeof(T) <= b.n) memcpy(const_cast<unsigned char*>(b.p) + off, &v, sizeof(T));
