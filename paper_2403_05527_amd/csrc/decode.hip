@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256, ((BITS == 2 && GQ <= 2) ? 5 : 4)) void decode_
                                                               const uint16_t* __restrict__ Kbuf,
                                                               const uint16_t* __restrict__ Vbuf, int n_buf,
                                                               int n_buf_cap, int nsplit, int pp, int rank_cap,
-                                                              float* __restrict__ partial) {
+                                                              int odd_rank, float* __restrict__ partial) {
   GEAR_DYN_LDS(smem_raw);
   const int slab = blockIdx.y, split = blockIdx.x;
   const int nrec = (int)gridDim.x;
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256, ((BITS == 2 && GQ <= 2) ? 5 : 4)) void decode_
     tw0 = WTOK * part;
     nw = n_j - tw0;
   }
-  mfma_block<BITS, GQ, LG>(smem_raw, dm, kw_, vw_, qg, slab, b, tw0, nw, k0.rank, v0.rank, rank_cap, split < nsplit,
+  mfma_block<BITS, GQ, LG>(smem_raw, dm, kw_, vw_, qg, slab, b, tw0, nw, k0.rank, v0.rank, rank_cap, odd_rank != 0, split < nsplit,
                            rec_base, rec_stride);
 }
 
@@ -111,7 +111,11 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
   int rc = 0;                                         // largest rank of an appended chunk
   for (int j = 0; j < cs.n_chunks; ++j) rc = cs.rank[j] > rc ? cs.rank[j] : rc;
   if (rc > rank_cap) return hipErrorInvalidValue;     // the cache never stores more than its configured rank
-  size_t lds = (size_t)mfma_layout<GQ>(BITS, dm.g, k0.rank, v0.rank, rc, dm.ppm).total;
+  // a rank whose rows are not one 4-, 8- or 16-byte read anywhere in the launch
+  auto one_read = [](int r) { return r == 0 || r == 2 || r == 4 || r == 8; };
+  bool odd_rank = !one_read(k0.rank) || !one_read(v0.rank);
+  for (int j = 0; j < cs.n_chunks; ++j) odd_rank = odd_rank || !one_read(cs.rank[j]);
+  size_t lds = (size_t)mfma_layout<GQ>(BITS, dm.g, k0.rank, v0.rank, rc, dm.ppm, odd_rank).total;
   if (lds < sizeof(TailSmem<GQ>)) lds = sizeof(TailSmem<GQ>);
   static size_t lds_allowed = 0;  // raised once per process and kernel instance
   if (lds > lds_allowed) {
@@ -122,7 +126,7 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
   }
   dim3 grid(nsplit + ncb + 1, dm.B * dm.H);
   hipLaunchKernelGGL((decode_split_kernel<BITS, GQ, LG>), grid, dim3(256), lds, st, dm, k0, v0, cs, q, Kbuf, Vbuf,
-                     n_buf, n_buf_cap, nsplit, pp, rc, partial);
+                     n_buf, n_buf_cap, nsplit, pp, rc, odd_rank ? 1 : 0, partial);
   hipLaunchKernelGGL(decode_combine_kernel, dim3(dm.B * dm.Hq), dim3(128), 0, st, (const float*)partial,
                      nsplit + ncb + 1, out);
   return hipGetLastError();

@@ -153,8 +153,14 @@ __host__ __device__ inline int up16i(int x) { return (x + 15) & ~15; }
 // rk0, rv0: ranks of the prefill segment; rc: largest rank of an appended chunk (0: no chunk
 // blocks in the launch).  The four waves of a prefill block read one copy of B_K and B_V at
 // bf and bf + bf_v0; wave w of a chunk block keeps its chunk's pair at bf + w * bf_cw (+ bf_vc).
+// lds_rows: the rows of A_K / A_V are staged in LDS.  With four or more query heads per KV head
+// the LDS of a block decides how many blocks a CU holds, and the rows then stay in registers
+// instead (each lane reads the rows it uses) unless a rank in the launch has no one-read row
+// (ranks other than 0, 2, 4, 8).
 template <int GQ>
-__host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk0, int rv0, int rc, int ppm) {
+__host__ __device__ inline bool mfma_rows_in_lds(bool odd_rank) { return GQ < 4 || odd_rank; }
+template <int GQ>
+__host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk0, int rv0, int rc, int ppm, bool odd_rank) {
   MfmaLayout L;
   const int TB = bits == 2 ? 64 : 32, lg = g >= 128 ? 7 : g >= 64 ? 6 : 5, NG = D >> lg;   // g is 32, 64 or 128
   const int rk = rk0 > rc ? rk0 : rc, rv = rv0 > rc ? rv0 : rc;
@@ -174,8 +180,8 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk0, int 
   L.sc = w; w += GQ * WTOK * 4;
   L.szk = w; w += (WTOK >> lg) * D * 4;
   L.szv = w; w += WTOK * NG * 4;
-  L.ak = w; w += up16i(WTOK * rk * 2);
-  L.av = w; w += up16i(WTOK * rv * 2);
+  L.ak = w; w += mfma_rows_in_lds<GQ>(odd_rank) ? up16i(WTOK * rk * 2) : 0;
+  L.av = w; w += mfma_rows_in_lds<GQ>(odd_rank) ? up16i(WTOK * rv * 2) : 0;
   L.osp = w; w += GQ * D * 4;
   int oh = 2 * GQ * D;
   if (NG * 2 * GQ * TB > oh) oh = NG * 2 * GQ * TB;
@@ -188,14 +194,26 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk0, int 
 
 // Low-rank Key term of the rows lane and lane + 64 for a rank that is one LDS read per row:
 // score[row] += A_K[row] . (q^T B_K).
-template <int GQ, int R>
-__device__ __forceinline__ void lowrank_key_rows(const uint16_t* Sak, const float* SqB, float* Ssc, int lane, int nw) {
+// (REGS: the two rows as loaded by the lane itself; otherwise they are read from LDS)
+template <int R>
+__device__ __forceinline__ void reg_row_f16(const uint4& v, float* a) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < R / 2; ++i) {
+    a[2 * i] = h2f(w[i] & 0xFFFFu);
+    a[2 * i + 1] = h2f(w[i] >> 16);
+  }
+}
+template <int GQ, int R, bool REGS>
+__device__ __forceinline__ void lowrank_key_rows(const uint16_t* Sak, const uint4 (&regs)[2], const float* SqB, float* Ssc,
+                                                 int lane, int nw) {
 #pragma unroll
   for (int rep = 0; rep < 2; ++rep) {
     const int row = lane + 64 * rep;
     if (row < nw) {
       float a[R];
-      lds_row_f16<R>(Sak + row * R, a);
+      if constexpr (REGS) reg_row_f16<R>(regs[rep], a);
+      else lds_row_f16<R>(Sak + row * R, a);
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
         float s = Ssc[hq * WTOK + row];
@@ -207,8 +225,9 @@ __device__ __forceinline__ void lowrank_key_rows(const uint16_t* Sak, const floa
   }
 }
 // p^T A_V over the wave's rows for such a rank, added into wv[hq * 8 + r] (zero on entry).
-template <int GQ, int R>
-__device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const float* Ssc, float* wv, int lane, int nw) {
+template <int GQ, int R, bool REGS>
+__device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const uint4 (&regs)[2], const float* Ssc, float* wv,
+                                                   int lane, int nw) {
   float part[GQ][R];
 #pragma unroll
   for (int hq = 0; hq < GQ; ++hq)
@@ -219,7 +238,8 @@ __device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const fl
     const int row = lane + 64 * rep;
     if (row < nw) {
       float a[R];
-      lds_row_f16<R>(Sav + row * R, a);
+      if constexpr (REGS) reg_row_f16<R>(regs[rep], a);
+      else lds_row_f16<R>(Sav + row * R, a);
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
         const float p = Ssc[hq * WTOK + row];
@@ -244,6 +264,20 @@ __device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const fl
   }
 }
 
+// Row `row` of a rank-rk factor (rk = 2, 4 or 8; 2 rk bytes) from a view of the wave's rows; 0 past the view.
+__device__ __forceinline__ uint4 load_factor_row(GEAR_BUF_T view, int row, int rk) {
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (rk == 8) {
+    v = GEAR_BUF_LOAD16(view, row * 16);
+  } else if (rk == 4) {
+    const uint2 t = GEAR_BUF_LOAD8(view, row * 8);
+    v.x = t.x; v.y = t.y;
+  } else if (rk == 2) {
+    v.x = GEAR_BUF_LOAD4(view, row * 4);
+  }
+  return v;
+}
+
 // One block: each of the four waves takes up to 128 consecutive token rows [tw0, tw0 + nw)
 // of the stored segment it is given (ks, vs may differ from wave to wave: the prefill
 // segment for every wave, or one appended chunk per wave), all of slab (b, h).  Writes
@@ -253,8 +287,8 @@ __device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const fl
 template <int BITS, int GQ, int LG>
 __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& ks, const SegView& vs,
                            const uint16_t* __restrict__ qg /* q of query head h*GQ of batch b */, int slab, int b,
-                           int tw0, int nw, int rk0, int rv0, int rc, bool shared_b, float* __restrict__ rec_base,
-                           int rec_stride) {
+                           int tw0, int nw, int rk0, int rv0, int rc, bool odd_rank, bool shared_b,
+                           float* __restrict__ rec_base, int rec_stride) {
   constexpr int TB = (BITS == 2) ? 64 : 32;   // tokens per Value code block
   constexpr int KW = (BITS == 2) ? 2 : 4;     // Key code words per lane per M-tile
   constexpr int VBLK = WTOK / TB;             // Value blocks per wave
@@ -262,7 +296,8 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const int n16 = lane & 15, kg = lane >> 4;
   constexpr int g = 1 << LG, lg = LG, NG = D >> LG;   // the group size (32, 64 or 128) is a template parameter: group loops unroll
   const int rk = ks.rank, rv = vs.rank;
-  const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk0, rv0, rc, dm.ppm);
+  const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk0, rv0, rc, dm.ppm, odd_rank);
+  const bool rows_lds = mfma_rows_in_lds<GQ>(odd_rank);   // compile-time true for fewer than four query heads
   float* Sq = reinterpret_cast<float*>(smem + L.q);                 // [GQ][128]
   MfmaMisc<GQ>& M = *reinterpret_cast<MfmaMisc<GQ>*>(smem + L.misc);
   unsigned char* wbase = smem + L.wave0 + (size_t)wave * L.wave_stride;
@@ -319,7 +354,8 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     if (i < GQ * D / 2) qreg[k] = reinterpret_cast<const uint32_t*>(qg)[i];
   }
   const int ngl = (nw + g - 1) >> lg;
-  const int n4_szk = ngl * (D / 4), n4_szv = (nw * NG + 3) >> 2, n4_ak = (nw * rk + 7) >> 3, n4_av = (nw * rv + 7) >> 3;
+  const int n4_szk = ngl * (D / 4), n4_szv = (nw * NG + 3) >> 2, n4_ak = rows_lds ? (nw * rk + 7) >> 3 : 0,
+            n4_av = rows_lds ? (nw * rv + 7) >> 3 : 0;
   const bool stage_b = shared_b ? wave == 0 : nw > 0;   // a prefill block's first wave always owns rows
   const int n4_bk = stage_b ? 16 * rk : 0, n4_bv = stage_b ? 16 * rv : 0;   // 128 * rank fp16
   const uint4* g_szk = reinterpret_cast<const uint4*>(ks.sz + ((size_t)slab * ks.ng_cap + (tw0 >> lg)) * D);
@@ -335,6 +371,12 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const uint4 r_av = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_av, n4_av * 16), lane * 16);
   const uint4 r_bk = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_bk, n4_bk * 16), lane * 16);
   const uint4 r_bv = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_bv, n4_bv * 16), lane * 16);
+  uint4 akr[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};   // rows lane, lane + 64 of A_K when they are not staged
+  if (!rows_lds) {
+    const GEAR_BUF_T av = GEAR_BUF_MAKE(g_ak, nw * rk * 2);
+    akr[0] = load_factor_row(av, lane, rk);
+    akr[1] = load_factor_row(av, lane + 64, rk);
+  }
   // outlier lists of the wave's tiles: K tiles then V tiles, rows rebased to the wave
   // a table entry is trusted only as far as its pool reaches
   {
@@ -508,13 +550,16 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
 
   // low-rank Key term: lane handles rows lane and lane + 64
   if (rk == 4) {
-    lowrank_key_rows<GQ, 4>(Sak, SqB, Ssc, lane, nw);
+    if (rows_lds) lowrank_key_rows<GQ, 4, false>(Sak, akr, SqB, Ssc, lane, nw);
+    else lowrank_key_rows<GQ, 4, true>(Sak, akr, SqB, Ssc, lane, nw);
     wave_lds_sync();
   } else if (rk == 2) {
-    lowrank_key_rows<GQ, 2>(Sak, SqB, Ssc, lane, nw);
+    if (rows_lds) lowrank_key_rows<GQ, 2, false>(Sak, akr, SqB, Ssc, lane, nw);
+    else lowrank_key_rows<GQ, 2, true>(Sak, akr, SqB, Ssc, lane, nw);
     wave_lds_sync();
   } else if (rk == 8) {
-    lowrank_key_rows<GQ, 8>(Sak, SqB, Ssc, lane, nw);
+    if (rows_lds) lowrank_key_rows<GQ, 8, false>(Sak, akr, SqB, Ssc, lane, nw);
+    else lowrank_key_rows<GQ, 8, true>(Sak, akr, SqB, Ssc, lane, nw);
     wave_lds_sync();
   } else if (rk > 0) {
 #pragma unroll 1
@@ -587,6 +632,12 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
         ellv[ti][rep] = *reinterpret_cast<const uint2*>(
             vs.ell + (((size_t)slab * vs.ntile_cap + tw0 / TILE + ti) * D + lane + 64 * rep) * ELL_V);
     }
+  uint4 avr[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};   // rows lane, lane + 64 of A_V when they are not staged
+  if (!rows_lds) {
+    const GEAR_BUF_T av = GEAR_BUF_MAKE(g_av, nw * rv * 2);
+    avr[0] = load_factor_row(av, lane, rv);
+    avr[1] = load_factor_row(av, lane + 64, rv);
+  }
   // request this wave's Value codes; they arrive while the softmax runs
   uint32_t vw[VBLK][8];
 #pragma unroll
@@ -722,11 +773,14 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   // p^T A_V (down-projection of the low-rank Value term) over the wave's rows; wv starts at 0
   float* wv = &M.wv[wave][0][0];
   if (rv == 4) {
-    lowrank_value_down<GQ, 4>(Sav, Ssc, wv, lane, nw);
+    if (rows_lds) lowrank_value_down<GQ, 4, false>(Sav, avr, Ssc, wv, lane, nw);
+    else lowrank_value_down<GQ, 4, true>(Sav, avr, Ssc, wv, lane, nw);
   } else if (rv == 2) {
-    lowrank_value_down<GQ, 2>(Sav, Ssc, wv, lane, nw);
+    if (rows_lds) lowrank_value_down<GQ, 2, false>(Sav, avr, Ssc, wv, lane, nw);
+    else lowrank_value_down<GQ, 2, true>(Sav, avr, Ssc, wv, lane, nw);
   } else if (rv == 8) {
-    lowrank_value_down<GQ, 8>(Sav, Ssc, wv, lane, nw);
+    if (rows_lds) lowrank_value_down<GQ, 8, false>(Sav, avr, Ssc, wv, lane, nw);
+    else lowrank_value_down<GQ, 8, true>(Sav, avr, Ssc, wv, lane, nw);
   } else if (rv > 0) {
     float part[GQ][8];
 #pragma unroll
