@@ -96,6 +96,16 @@ def test_chunk_rank_differs_from_prefill_rank(rank, rank_chunk):
     run_case(w, n_chunks=5)
 
 
+@pytest.mark.parametrize("H_kv,H_q,rank,rank_chunk", [(2, 8, 3, 2), (2, 8, 4, 2), (1, 8, 8, 4), (2, 8, 2, 5)])
+def test_grouped_queries_with_and_without_one_read_ranks(H_kv, H_q, rank, rank_chunk):
+    # four or more query heads per KV head: the decode kernel keeps the low-rank rows in registers
+    # when every rank of the launch is 0, 2, 4 or 8 and stages them in LDS otherwise
+    import dataclasses
+    w = dataclasses.replace(small_workload(B=1, H_kv=H_kv, H_q=H_q, n=300, bits=2, g=64, ppm=20000, rank=rank,
+                                           seed=31 + rank), rank_chunk=rank_chunk)
+    run_case(w, n_chunks=3)
+
+
 @pytest.mark.parametrize("n", [1, 7, 20, 63, 64, 65, 513])
 def test_token_counts(n):
     w = small_workload(B=1, H_kv=4, H_q=4, n=n, bits=4, g=64, ppm=20000, rank=2, seed=n)
