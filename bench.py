@@ -60,8 +60,8 @@ def main():
                          "are scaled by now runs after every timed region")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards over batch with no "
-              "exchange; see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path would shard over the batch with no "
+              "exchange between GPUs); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
