@@ -37,8 +37,12 @@ struct RegSource {  // the vector lives in the wave's registers
 template <int CB>
 __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restrict__ K, int n, int n_pad,
                                                        int nslab, int k_top, int k_bot,
-                                                       ThreshPair* __restrict__ thrK) {
+                                                       ThreshPair* __restrict__ thrK, uint32_t* __restrict__ zero,
+                                                       int zero_count) {
   GEAR_DYN_LDS(smem_raw);
+  // the first kernel of a compress call also clears the call's list counters (the kernels that
+  // count run after this one on the stream)
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < zero_count; i += gridDim.x * blockDim.x) zero[i] = 0u;
   uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem_raw);
   uint16_t* tile = reinterpret_cast<uint16_t*>(smem_raw + (blockDim.x >> 6) * SELECT_LDS_WORDS * sizeof(uint32_t));
   constexpr int ncb = D / CB;
@@ -385,29 +389,30 @@ static int k_select_cb(int n_pad, int slabs) {
 
 template <int CB>
 static hipError_t launch_k_select_cb(const uint16_t* K, const Dims& dm, int n, int n_pad, int k_top, int k_bot,
-                                     ThreshPair* thrK, hipStream_t st) {
+                                     ThreshPair* thrK, uint32_t* zero, int zero_count, hipStream_t st) {
   constexpr int nw = CB < 4 ? CB : 4;   // waves per block: one vector each per round
   const size_t lds = (size_t)nw * SELECT_LDS_WORDS * sizeof(uint32_t) + (size_t)CB * n_pad * 2;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel<CB>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   dim3 grid((D / CB) * dm.B * dm.H);
-  hipLaunchKernelGGL(k_select_kernel<CB>, grid, dim3(64 * nw), lds, st, K, n, n_pad, dm.B * dm.H, k_top, k_bot, thrK);
+  hipLaunchKernelGGL(k_select_kernel<CB>, grid, dim3(64 * nw), lds, st, K, n, n_pad, dm.B * dm.H, k_top, k_bot, thrK, zero,
+                     zero_count);
   return hipGetLastError();
 }
 
 hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
-                           hipStream_t st) {
+                           uint32_t* zero, int zero_count, hipStream_t st) {
   const int n_pad = (n + 7) & ~7;
   switch (k_select_cb(n_pad, dm.B * dm.H)) {
-    case 128: return launch_k_select_cb<128>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
-    case 64: return launch_k_select_cb<64>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
-    case 32: return launch_k_select_cb<32>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
-    case 16: return launch_k_select_cb<16>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
-    case 8: return launch_k_select_cb<8>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
-    case 4: return launch_k_select_cb<4>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
-    case 2: return launch_k_select_cb<2>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
-    default: return launch_k_select_cb<1>(K, dm, n, n_pad, k_top, k_bot, thrK, st);
+    case 128: return launch_k_select_cb<128>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
+    case 64: return launch_k_select_cb<64>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
+    case 32: return launch_k_select_cb<32>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
+    case 16: return launch_k_select_cb<16>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
+    case 8: return launch_k_select_cb<8>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
+    case 4: return launch_k_select_cb<4>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
+    case 2: return launch_k_select_cb<2>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
+    default: return launch_k_select_cb<1>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
   }
 }
 

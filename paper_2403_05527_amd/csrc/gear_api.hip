@@ -261,8 +261,7 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   const int kv_k = outlier_count(n, c.outlier_ppm);
   const int kv_v = outlier_count((long long)c.H_kv * D, c.outlier_ppm);
   if (c.outlier_ppm > 0) {
-    GEAR_HIP(launch_fill_u32(pool_ctr, 0u, (size_t)c.B * c.H_kv + c.B, st));
-    GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, st));
+    GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, pool_ctr, c.B * c.H_kv + c.B, st));
   }
   // Keys: quantize (leaving Y = X - S in the workspace), then their power iteration;
   // Values reuse the same buffer afterwards.
