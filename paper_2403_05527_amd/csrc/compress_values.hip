@@ -24,7 +24,7 @@ struct RegSource {  // the vector lives in the wave's registers
 // lane l, chunk ch  <->  head 4*ch + l/16, channels 8*(l%16)..+7, i.e. in-vector index
 // ch*512 + l*8 + e.
 template <int NC>
-__global__ __launch_bounds__(256, (NC <= 10 ? 4 : 2)) void v_select_kernel(const uint16_t* __restrict__ V, int H, int n, int tpw, int k_top,
+__global__ __launch_bounds__(256, (NC <= 8 ? 5 : NC <= 10 ? 4 : 2)) void v_select_kernel(const uint16_t* __restrict__ V, int H, int n, int tpw, int k_top,
                                                        int k_bot, ThreshPair* __restrict__ thrV) {
   __shared__ uint32_t hist[4 * SELECT_LDS_WORDS];
   const int b = blockIdx.y;
