@@ -39,6 +39,8 @@ typedef enum gear_status {
 } gear_status;
 
 #define GEAR_MAX_CHUNKS 256
+/* Size of the library's built-in scratch array (gear_decode_attn_static). */
+#define GEAR_STATIC_SCRATCH_BYTES (32u << 20)
 
 /* Hyper-parameters of Algorithm 1 of the paper plus the capacities of one
  * layer's cache. */
@@ -123,6 +125,25 @@ int gear_decompress(const gear_cache* cache, void* K_out, void* V_out, void* str
 int gear_decode_attn(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf,
                      int32_t n_buf, void* out, void* workspace, size_t workspace_bytes,
                      void* stream);
+
+/*
+ * gear_decode_attn for callers that cannot allocate device memory or bring a
+ * workspace along: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same computation, same kernels and same results as
+ * gear_decode_attn; the partial softmax records of the split blocks go to a
+ * fixed array of GEAR_STATIC_SCRATCH_BYTES (32 MiB) that is part of the library
+ * and that every GPU the library runs on holds until the process ends.  The call
+ * allocates and frees nothing.
+ *  - The records take B * H_q * (ceil(n_prefill / 512) + ceil(pieces / 4) + 1) * 520
+ *    bytes (pieces = n_chunks, or 2 * n_chunks when n_buf_cap > 128); a cache
+ *    that needs more than the array returns GEAR_ECAPACITY and launches nothing.
+ *  - All calls on one GPU share that GPU's array: two calls that may overlap on
+ *    one GPU (different streams, different threads) race and must be ordered
+ *    by the caller.  Nothing has to be cleared between calls: every record a
+ *    call reads it has written itself.
+ */
+int gear_decode_attn_static(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf,
+                            int32_t n_buf, void* out, void* stream);
 
 /*
  * Canonical views of the stored components (the physical arena layout is

@@ -10,11 +10,12 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libgear.so")
 
 GEAR_MAX_CHUNKS = 256
+GEAR_STATIC_SCRATCH_BYTES = 32 << 20
 GEAR_OK, GEAR_EINVAL, GEAR_ECAPACITY, GEAR_EALIGN, GEAR_EHIP = 0, -1, -2, -3, -4
 
 EXPORTED = [
     "gear_cache_bytes", "gear_cache_init", "gear_cache_reset", "gear_compress", "gear_decompress",
-    "gear_decode_attn", "gear_export_codes", "gear_export_sparse", "gear_export_lowrank", "gear_strerror",
+    "gear_decode_attn", "gear_decode_attn_static", "gear_export_codes", "gear_export_sparse", "gear_export_lowrank", "gear_strerror",
 ]
 
 
@@ -63,6 +64,7 @@ def load_library():
     lib.gear_compress.argtypes = [cachep, vp, vp, i32, i32, i32, vp, vp, sz, vp]
     lib.gear_decompress.argtypes = [cachep, vp, vp, vp]
     lib.gear_decode_attn.argtypes = [cachep, vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.gear_decode_attn_static.argtypes = [cachep, vp, vp, vp, i32, vp, vp]
     lib.gear_export_codes.argtypes = [cachep, ctypes.c_int, vp, vp, vp, vp]
     lib.gear_export_sparse.argtypes = [cachep, ctypes.c_int, vp, vp, vp]
     lib.gear_export_lowrank.argtypes = [cachep, ctypes.c_int, ctypes.c_int, vp, vp, vp]
@@ -132,6 +134,11 @@ def gear_decode_attn(cache, q, K_buf, V_buf, n_buf, out, workspace):
     _check(load_library().gear_decode_attn(ctypes.byref(cache), _ptr(q), _ptr(K_buf), _ptr(V_buf), n_buf, _ptr(out),
                                            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
            "gear_decode_attn")
+
+
+def gear_decode_attn_static(cache, q, K_buf, V_buf, n_buf, out):
+    _check(load_library().gear_decode_attn_static(ctypes.byref(cache), _ptr(q), _ptr(K_buf), _ptr(V_buf), n_buf,
+                                                  _ptr(out), _stream()), "gear_decode_attn_static")
 
 
 def gear_export_codes(cache, which, codes, scale, zero):

@@ -1,6 +1,7 @@
 // C ABI of libgear: argument validation, arena / workspace layout and the launch
 // sequences of the entry points declared in gear.h.
 #include <string.h>
+#include <mutex>
 
 #include "gear_internal.h"
 #include "gear_launch.h"
@@ -194,6 +195,82 @@ int check_cache(const gear_cache* c) {
     if (e__ != hipSuccess) return GEAR_EHIP;     \
   } while (0)
 
+
+// ---------------------------------------------------------------------------
+// Scratch memory of gear_decode_attn_static: a fixed array in device memory that
+// every GPU holds from the moment the library is loaded until the process ends.
+// In host code the array's name is only a handle; the address the kernels get is
+// looked up once per device with hipGetSymbolAddress and kept.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[GEAR_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[MAX_DEVICES];   // per device: address of that device's copy of `scratch`, nullptr until looked up
+
+// Address of the current device's scratch array (looked up on the first call on that device).
+int current_device_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return GEAR_EHIP;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GEAR_EHIP;
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  return GEAR_OK;
+}
+
+// Common body of the two decode entry points.  `partial` holds the split records
+// (at least decode_record_bytes(cache) bytes).
+size_t decode_record_bytes(const gear_cache* cache) {
+  const gear_config& c = cache->cfg;
+  const int nsplit = (cache->n_prefill + DECODE_SPLIT - 1) / DECODE_SPLIT;
+  const int ncb = (cache->n_chunks * (c.n_buf_cap > 128 ? 2 : 1) + 3) / 4;
+  return (size_t)c.B * c.H_q * (nsplit + ncb + 1) * DECODE_REC * 4;
+}
+
+int decode_checked(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf, int32_t n_buf,
+                   void* out, float* partial, void* stream) {
+  const gear_config& c = cache->cfg;
+  const ArenaLayout a = arena_layout(c);
+  const Dims dm = make_dims(c);
+  SegView k0, v0;
+  seg_views(cache, a, 0, cache->n_prefill, cache->rank_prefill, &k0, &v0);
+  ChunkSet cs;
+  memset(&cs, 0, sizeof(cs));
+  {
+    // views of chunk 0 (token offsets are irrelevant for attention)
+    char* cb = static_cast<char*>(cache->arena) + a.off_chunks;
+    cs.k0 = make_view(cb, a.kc, 0, 0, 0, 0);
+    cs.v0 = make_view(cb + a.kc.bytes, a.vc, 0, 0, 0, 0);
+  }
+  cs.stride = a.chunk_stride;
+  cs.n_chunks = cache->n_chunks;
+  for (int j = 0; j < cache->n_chunks; ++j) {
+    cs.n[j] = cache->chunk_n[j];
+    cs.rank[j] = cache->chunk_rank[j];
+  }
+  GEAR_HIP(launch_decode(dm, k0, v0, cs, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(K_buf),
+                         static_cast<const uint16_t*>(V_buf), n_buf, c.n_buf_cap, c.rank_max, static_cast<uint16_t*>(out),
+                         partial, static_cast<hipStream_t>(stream)));
+  return GEAR_OK;
+}
+
+int check_decode_args(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf, int32_t n_buf,
+                      const void* out) {
+  const int rc = check_cache(cache);
+  if (rc) return rc;
+  const gear_config& c = cache->cfg;
+  if (!q || !out) return GEAR_EINVAL;
+  if (n_buf < 0 || n_buf > c.n_buf_cap) return GEAR_EINVAL;
+  if (n_buf > 0 && (!K_buf || !V_buf)) return GEAR_EINVAL;
+  if (n_buf == 0 && cache->n_total == 0) return GEAR_EINVAL;
+  if (!aligned16(q) || !aligned16(out) || (K_buf && !aligned16(K_buf)) || (V_buf && !aligned16(V_buf))) return GEAR_EALIGN;
+  return GEAR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -309,41 +386,25 @@ int gear_decompress(const gear_cache* cache, void* K_out, void* V_out, void* str
 
 int gear_decode_attn(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf, int32_t n_buf,
                      void* out, void* workspace, size_t workspace_bytes, void* stream) {
-  const int rc = check_cache(cache);
+  const int rc = check_decode_args(cache, q, K_buf, V_buf, n_buf, out);
   if (rc) return rc;
-  const gear_config& c = cache->cfg;
-  if (!q || !out || !workspace) return GEAR_EINVAL;
-  if (n_buf < 0 || n_buf > c.n_buf_cap) return GEAR_EINVAL;
-  if (n_buf > 0 && (!K_buf || !V_buf)) return GEAR_EINVAL;
-  if (n_buf == 0 && cache->n_total == 0) return GEAR_EINVAL;
-  if (!aligned16(q) || !aligned16(out) || !aligned16(workspace) || (K_buf && !aligned16(K_buf)) ||
-      (V_buf && !aligned16(V_buf)))
-    return GEAR_EALIGN;
-  const WorkLayout w = work_layout(c);
+  if (!workspace) return GEAR_EINVAL;
+  if (!aligned16(workspace)) return GEAR_EALIGN;
+  const WorkLayout w = work_layout(cache->cfg);
   if (workspace_bytes < w.bytes) return GEAR_ECAPACITY;
-  const ArenaLayout a = arena_layout(c);
-  const Dims dm = make_dims(c);
-  SegView k0, v0;
-  seg_views(cache, a, 0, cache->n_prefill, cache->rank_prefill, &k0, &v0);
-  ChunkSet cs;
-  memset(&cs, 0, sizeof(cs));
-  {
-    // views of chunk 0 (token offsets are irrelevant for attention)
-    char* cb = static_cast<char*>(cache->arena) + a.off_chunks;
-    cs.k0 = make_view(cb, a.kc, 0, 0, 0, 0);
-    cs.v0 = make_view(cb + a.kc.bytes, a.vc, 0, 0, 0, 0);
-  }
-  cs.stride = a.chunk_stride;
-  cs.n_chunks = cache->n_chunks;
-  for (int j = 0; j < cache->n_chunks; ++j) {
-    cs.n[j] = cache->chunk_n[j];
-    cs.rank[j] = cache->chunk_rank[j];
-  }
-  float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dec);
-  GEAR_HIP(launch_decode(dm, k0, v0, cs, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(K_buf),
-                         static_cast<const uint16_t*>(V_buf), n_buf, c.n_buf_cap, c.rank_max, static_cast<uint16_t*>(out),
-                         partial, static_cast<hipStream_t>(stream)));
-  return GEAR_OK;
+  return decode_checked(cache, q, K_buf, V_buf, n_buf, out,
+                        reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dec), stream);
+}
+
+int gear_decode_attn_static(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf,
+                            int32_t n_buf, void* out, void* stream) {
+  const int rc = check_decode_args(cache, q, K_buf, V_buf, n_buf, out);
+  if (rc) return rc;
+  if (decode_record_bytes(cache) > (size_t)GEAR_STATIC_SCRATCH_BYTES) return GEAR_ECAPACITY;
+  void* sp = nullptr;
+  const int rs = current_device_scratch(&sp);
+  if (rs) return rs;
+  return decode_checked(cache, q, K_buf, V_buf, n_buf, out, static_cast<float*>(sp), stream);
 }
 
 int gear_export_codes(const gear_cache* cache, int which, void* codes_u8, void* scale_f16, void* zero_f16,

@@ -43,6 +43,9 @@ enum { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
 inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
 inline const char* hipGetErrorString(hipError_t) { return "emulated"; }
+inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
+#define HIP_SYMBOL(x) x
+inline hipError_t hipGetSymbolAddress(void** p, const void* sym) { *p = const_cast<void*>(sym); return hipSuccess; }
 #define GEAR_DYN_LDS(name) unsigned char* name = simt::dyn_lds
 #define GEAR_PIN_VGPR(x) asm volatile("" : "+r"(x))
 #define GEAR_LDS_BARRIER() pthread_barrier_wait(&simt::block_bar)
