@@ -81,7 +81,8 @@ ArenaLayout arena_layout(const gear_config& c) {
 }
 
 struct WorkLayout {
-  size_t thrK, thrV, pool_ctr, Bcur, partial, Atmp, cmat, dec, resid, bytes;
+  size_t thrK, thrV, pool_ctr, Bcur, partial, Atmp, cmat, dec, gram, resid, bytes;
+  int gram_strips;
 };
 
 WorkLayout work_layout(const gear_config& c) {
@@ -103,6 +104,8 @@ WorkLayout work_layout(const gear_config& c) {
   const int nsplit = (c.n_prefill_max + DECODE_SPLIT - 1) / DECODE_SPLIT;
   const int ncb = (c.n_chunks_max * (c.n_buf_cap > 128 ? 2 : 1) + 3) / 4;
   w.dec = o; o += up((size_t)c.B * c.H_q * (nsplit + ncb + 1) * DECODE_REC * 4);
+  w.gram_strips = c.rank_max > 0 && n_max > 256 ? pi_gram_strips_max(n_max, (int)slabs) : 0;
+  w.gram = o; o += up(slabs * (size_t)w.gram_strips * 36 * 256 * 4);
   w.resid = o; o += up(c.rank_max > 0 ? slabs * (size_t)n_max * D * 2 : 0);
   w.bytes = o;
   return w;
@@ -347,12 +350,13 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   float* partial = reinterpret_cast<float*>(ws + w.partial);
   float* Atmp = reinterpret_cast<float*>(ws + w.Atmp);
   float* cmat = reinterpret_cast<float*>(ws + w.cmat);
+  float* gram = reinterpret_cast<float*>(ws + w.gram);
   const size_t half = (size_t)c.B * c.H_kv * D * rank;
   GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, resid, st));
-  if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, ks, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st));
+  if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, ks, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
   GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, pool_ctr + (size_t)c.B * c.H_kv, resid, st));
   if (rank > 0)
-    GEAR_HIP(launch_power_iteration(false, resid, vs, dm, n, iters, init_B + half, Bcur, partial, Atmp, cmat, st));
+    GEAR_HIP(launch_power_iteration(false, resid, vs, dm, n, iters, init_B + half, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
 
   if (first) {
     cache->n_prefill = n;

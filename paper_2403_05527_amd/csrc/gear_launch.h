@@ -27,9 +27,12 @@ hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dim
                                  int k_bot, ThreshPair* thrV, uint32_t* pool_ctr, uint16_t* Yout, hipStream_t st);
 
 int pi_padded_rank(int rank);
+// gram: [slab][strip][36 * 256] floats, the partial Gram matrices of the residual (segments of more than 256 tokens
+// with iters > 1); gram_strips_cap: strips per slab it has room for (pi_gram_strips_max of the largest segment)
+int pi_gram_strips_max(int n_max, int slabs);
 hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
                                   const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat,
-                                  hipStream_t st);
+                                  float* gram, int gram_strips_cap, hipStream_t st);
 
 constexpr int DECODE_TS = 256;           // rows per pass of the chunk / buffer path
 constexpr int DECODE_SPLIT = 512;        // prefill tokens per split block

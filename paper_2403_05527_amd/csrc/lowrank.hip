@@ -7,6 +7,12 @@
 // 16-bit copy of R itself flips enough fp16 roundings of the stored factors to fail the
 // attention tolerance.
 //
+//   pi_gram    : G = R^T R (128 x 128 per slab) in one pass over the residual, on the
+//                matrix cores.  Every round of Algorithm 2 before the last maps
+//                B -> R^T (R B) = G B, so those rounds need no pass over R of their
+//                own: they become 128 x 128 x r products on G.
+//   pi_solve   : B <- G^(L-1) B0 (columns rescaled between the products: the span,
+//                hence A B^T, is unchanged), then the QR of B that opens the last round.
 //   pi_update  : B <- start matrix or sum of the sweep partials; column scaling
 //                between rounds (the span, hence A B^T, is unchanged); QR of B
 //                before the last round; after the last round the r x r factor
@@ -477,11 +483,385 @@ __global__ __launch_bounds__(256, 1) void pi_small_kernel(const uint16_t* __rest
   pi_finish_body<R>(Cs, slab, 0, Atmp, cmat, sv, n);
 }
 
+// ------------------------------------------------------------------ Gram matrix of the residual
+// Rounds 1 .. L-1 of Algorithm 2 compute A = R B, B = R^T A without any orthonormalisation in
+// between, i.e. B <- (R^T R) B.  G = R^T R is formed once, in one pass over the slab, as a dense
+// contraction over the tokens on v_mfma_f32_16x16x32_f16; the rounds themselves then cost
+// 128 x 128 x r multiply-adds per slab (pi_solve_kernel).  A residual entry enters the
+// contraction as two fp16 numbers, its leading part and what that leaves (22 bits together), and
+// a product as three MFMA terms; accumulation is fp32.  (The leading parts alone are not enough:
+// without orthonormalisation between the rounds the weaker directions of G^(L-1) B0 are small
+// differences of large numbers, and a relative error of 2^-11 in G is amplified by the square
+// of the ratio of its leading eigenvalues.)  G only chooses the subspace that the last round
+// projects on: that round (pi_sweep_kernel<.., LAST>) still reads the residual itself, so
+// A = orth(R B) and B = R^T A are computed from R.
+//
+// grid (ceil(n / strip), B*H), block 256.  A block walks its strip of tokens in steps of 128;
+// thread (r0 = tid/16, oc = tid%16) takes channels 8*oc..+7 of rows base + r0 + 16*k, k = 0..7.
+// The 16 lanes that share r0 hold the same 8 tokens: as an MFMA operand, register j of
+// "channel e" holds rows (2j, 2j+1) of channel 8*oc + e, so operand e is the 16 channels
+// {8*oc + e} x 32 tokens of the wave and acc(e, e') += op_e^T op_e' is one 16 x 16 tile of G:
+// lane l, register i <-> G[8*(4*(l/16)+i) + e][8*(l%16) + e'].  Only the 36 tiles e <= e' are
+// computed (G is symmetric).  The four waves' tiles are summed through LDS and written as one
+// partial per strip: [slab][strip][36][4][64] floats.
+constexpr int GRAM_TILES = 36;
+constexpr int GRAM_FLOATS = GRAM_TILES * 256;
+
+typedef _Float16 gram_h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 gram_h8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ uint32_t pack_h2(float a, float b) {   // two roundings to nearest even, one instruction
+  gram_h2 h = {(_Float16)a, (_Float16)b};
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+// The loads of one step of the Gram pass (128 tokens, 8 rows per thread), requested together.
+template <bool IS_K, int NGS>
+struct GramLoads {
+  uint4 xv[8];
+  uint32_t cw[8];      // Keys: the row piece's 8 codes
+  uint32_t pv[8];      // Values: (scale, zero) of my row's channel group
+  uint4 pz[NGS][2];    // Keys: (scale, zero) of my 8 channels in the step's groups
+};
+
+template <bool IS_K, int LG>   // LG: log2 of the Key group size (Values take the group size at run time)
+__global__ __launch_bounds__(256, 2) void pi_gram_kernel(const uint16_t* __restrict__ Y, SegView sv, int g, int bits, int n,
+                                                         int strip, float* __restrict__ gram_partial) {
+  __shared__ float red[GRAM_FLOATS];
+  const int slab = blockIdx.y, sidx = blockIdx.x, nstrips = gridDim.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r0 = tid >> 4, oc = tid & 15;
+  const int t_begin = sidx * strip;
+  const int t_end = t_begin + strip < n ? t_begin + strip : n;
+  const float qmax = (float)((1 << bits) - 1);
+  const int lgv = 31 - __clz(g), ngl = 7 - lgv;   // Values: log2 of the group size / of the groups per row
+  const GEAR_BUF_T xbuf = GEAR_BUF_MAKE(Y + (size_t)slab * n * D, n * (D * 2));
+  const GEAR_BUF_T cbuf = GEAR_BUF_MAKE(sv.codes + (size_t)slab * sv.n_cap * (4 * bits), IS_K ? n * (16 * bits) : 0);
+  // (scale, zero) words: Keys [group][128] of this slab, Values [row][groups of a row]
+  const GEAR_BUF_T pbuf = IS_K ? GEAR_BUF_MAKE(sv.sz + (size_t)slab * sv.ng_cap * D, ((n + g - 1) >> LG) * (D * 4))
+                               : GEAR_BUF_MAKE(sv.sz + (((size_t)slab * sv.n_cap) << ngl), (n << ngl) * 4);
+  constexpr int GT = 128;                          // tokens per step (32 per wave)
+  constexpr int NGS = IS_K ? (GT >> LG) : 1;       // Key groups per step
+  typedef GramLoads<IS_K, NGS> Loads;
+
+  floatx4 acc[GRAM_TILES];
+#pragma unroll
+  for (int i = 0; i < GRAM_TILES; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll 1
+  for (int base = t_begin; base < t_end; base += GT) {
+    // every load of the step is requested before the first one is used
+    Loads L;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int t = base + r0 + 16 * k;
+      L.xv[k] = GEAR_BUF_LOAD16_NT(xbuf, t * (D * 2) + oc * 16);   // rows past the end read as 0
+      L.cw[k] = 0u;
+      L.pv[k] = 0u;
+      if (IS_K) {
+        const int co = t * (16 * bits) + oc * (bits == 4 ? 4 : 2);
+        L.cw[k] = bits == 4 ? GEAR_BUF_LOAD4(cbuf, co) : GEAR_BUF_LOAD2(cbuf, co);
+      } else {
+        L.pv[k] = GEAR_BUF_LOAD4(pbuf, ((t << ngl) + ((oc * 8) >> lgv)) * 4);
+      }
+    }
+    if (IS_K) {
+#pragma unroll
+      for (int j = 0; j < NGS; ++j) {
+        const int off = (((base >> LG) + j) * D + oc * 8) * 4;
+        L.pz[j][0] = GEAR_BUF_LOAD16(pbuf, off);
+        L.pz[j][1] = GEAR_BUF_LOAD16(pbuf, off + 16);
+      }
+    }
+    // residuals of the step as fp16 operands: leading part, and what it leaves (22 bits together)
+    const bool ragged = base + GT > n;   // block-uniform: only such a step has rows past the end
+    uint32_t oph[8][4], opl[8][4];
+    float pmn[8], pdl[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { pmn[e] = 0.0f; pdl[e] = 0.0f; }
+    float ra[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const uint32_t w[4] = {L.xv[k].x, L.xv[k].y, L.xv[k].z, L.xv[k].w};
+      float res[8];
+      if (IS_K) {
+        if ((16 * k) % (1 << LG) == 0) {   // first rows of a group: its parameters
+          const int j = (16 * k) >> LG;
+          const uint32_t z[8] = {L.pz[j][0].x, L.pz[j][0].y, L.pz[j][0].z, L.pz[j][0].w,
+                                 L.pz[j][1].x, L.pz[j][1].y, L.pz[j][1].z, L.pz[j][1].w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { pdl[e] = h2f(z[e] & 0xFFFFu); pmn[e] = h2f(z[e] >> 16); }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float y = h2f((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xFFFFu));
+          res[e] = __builtin_fmaf(-(float)GEAR_UBFE(L.cw[k], e * bits, bits), pdl[e], y - pmn[e]);
+        }
+      } else {
+        const GroupQ q = load_group(L.pv[k]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float y = h2f((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xFFFFu));
+          res[e] = quant_error(y, q.mn, q.inv, q.delta, qmax);
+        }
+      }
+      // Keys: a row past the end has res = -zero-point, not 0 (Values: the parameters of such rows are 0)
+      if (IS_K && ragged && base + r0 + 16 * k >= n) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) res[e] = 0.0f;
+      }
+      if ((k & 1) == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ra[e] = res[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t hi = pack_h2(ra[e], res[e]);
+          oph[e][k >> 1] = hi;
+          opl[e][k >> 1] = pack_h2(ra[e] - h2f(hi & 0xFFFFu), res[e] - h2f(hi >> 16));
+        }
+      }
+    }
+    // the 36 tiles: r r' = hi hi' + hi lo' + lo hi' (the lo lo' term is below fp32 resolution)
+    int ti = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const gram_h8 ah = __builtin_bit_cast(gram_h8, make_uint4(oph[e][0], oph[e][1], oph[e][2], oph[e][3]));
+      const gram_h8 al = __builtin_bit_cast(gram_h8, make_uint4(opl[e][0], opl[e][1], opl[e][2], opl[e][3]));
+#pragma unroll
+      for (int f = e; f < 8; ++f) {
+        const gram_h8 bh = __builtin_bit_cast(gram_h8, make_uint4(oph[f][0], oph[f][1], oph[f][2], oph[f][3]));
+        const gram_h8 bl = __builtin_bit_cast(gram_h8, make_uint4(opl[f][0], opl[f][1], opl[f][2], opl[f][3]));
+        acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh, acc[ti], 0, 0, 0);
+        acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bl, acc[ti], 0, 0, 0);
+        acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, bh, acc[ti], 0, 0, 0);
+        ++ti;
+      }
+    }
+  }
+
+  // the four waves' tiles, added in wave order (a fixed order: results do not vary from run to run);
+  // a few tiles at a time, so that the LDS reads in flight stay few
+  float* out = gram_partial + ((size_t)slab * nstrips + sidx) * GRAM_FLOATS;
+  if (wave == 0) {
+#pragma unroll
+    for (int ti = 0; ti < GRAM_TILES; ++ti)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) red[ti * 256 + i * 64 + lane] = acc[ti][i];
+  }
+  block_lds_sync();
+#pragma unroll 1
+  for (int w = 1; w < 3; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int ti = 0; ti < GRAM_TILES; ++ti) {
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = red[ti * 256 + i * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[ti * 256 + i * 64 + lane] = v[i] + acc[ti][i];
+        GEAR_PIN_VGPR(v[0]);   // keeps the tiles' reads from being hoisted above each other's writes en bloc
+      }
+    }
+    block_lds_sync();
+  }
+  if (wave == 3) {
+#pragma unroll
+    for (int ti = 0; ti < GRAM_TILES; ++ti) {
+      float v[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = red[ti * 256 + i * 64 + lane];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) out[ti * 256 + i * 64 + lane] = v[i] + acc[ti][i];
+      GEAR_PIN_VGPR(v[0]);
+    }
+  }
+}
+
+// B <- G^rounds B0, then the Q factor of its QR (the orthonormalisation of B that opens the last
+// round of Algorithm 2).  grid (B*H), block 128: thread c owns row c of B.  Dynamic LDS: G as
+// [128][129] floats, B as [128][R] doubles.
+constexpr int GP = D + 1;
+template <int R>
+struct SolveSmem {
+  float G[D * GP];
+  double Bs[D][R];
+  double part[D][R];   // the upper half block's share of a product
+  double red[4 * (R + 1)];
+};
+// Sum of a double over the 64 lanes, in every lane: lane exchanges inside rows of 16 (one
+// data-parallel-primitive move per 32-bit half), then the four row sums through scalar reads.
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) {
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = dpp_u<CTRL>((uint32_t)b), hi = dpp_u<CTRL>((uint32_t)(b >> 32));
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ double lane_bcast_d(double v, int lane) {
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), lane);
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ double wave_sum_d(double v) {
+  v += dpp_d<DPP_XOR1>(v);
+  v += dpp_d<DPP_XOR2>(v);
+  v += dpp_d<DPP_HALF_MIRROR>(v);
+  v += dpp_d<DPP_MIRROR>(v);
+  return (lane_bcast_d(v, 0) + lane_bcast_d(v, 16)) + (lane_bcast_d(v, 32) + lane_bcast_d(v, 48));
+}
+// Sums of N per-thread values over the block (256 threads), all in every thread: one pair of
+// barriers for the N sums together.
+template <int N>
+__device__ __forceinline__ void block_sum_vec(double (&v)[N], double* red /* 4 * N */) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = wave_sum_d(v[i]);
+  block_lds_sync();
+  if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) red[(threadIdx.x >> 6) * N + i] = v[i];
+  }
+  block_lds_sync();
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = (red[i] + red[N + i]) + (red[2 * N + i] + red[3 * N + i]);
+}
+// 1 / sqrt(x) for x > 0 in double: the single-precision estimate, refined by two Newton steps
+// (no double-precision square root or division, which are long instruction sequences)
+__device__ __forceinline__ double rsqrt_d(double x) {
+  // scaled into single-precision range by an even power of two taken from the exponent
+  const int ex = (int)((__builtin_bit_cast(uint64_t, x) >> 52) & 0x7FF) - 1023;
+  const int h = ex >> 1;                                   // x = m * 4^h, m in [1, 4)
+  const double m = __builtin_bit_cast(double, __builtin_bit_cast(uint64_t, x) - ((uint64_t)(2 * h) << 52));
+  double y = (double)__builtin_amdgcn_rsqf((float)m);
+  y = y * (1.5 - 0.5 * m * y * y);
+  y = y * (1.5 - 0.5 * m * y * y);
+  return __builtin_bit_cast(double, __builtin_bit_cast(uint64_t, y) - ((uint64_t)h << 52));   // y * 2^-h
+}
+// grid (B*H), block 256: thread (half = tid / 128, c = tid % 128).  Row c of B belongs to thread
+// (0, c); the upper half of the block helps with the loads of G and with half of every product.
+template <int R>
+__global__ __launch_bounds__(256) void pi_solve_kernel(const float* __restrict__ init, int rank,
+                                                       const float* __restrict__ gram_partial, int nstrips, int rounds,
+                                                       float* __restrict__ Bcur) {
+  GEAR_DYN_LDS(smem_raw);
+  SolveSmem<R>& sm = *reinterpret_cast<SolveSmem<R>*>(smem_raw);
+  const int slab = blockIdx.x, c = threadIdx.x & (D - 1), half = threadIdx.x >> 7;
+  const bool owner = half == 0;
+  if (rounds > 0) {
+    // G = sum of the strips' partial tiles (fixed order): element tid + 256 j is register j % 4... of tile j
+    const float* gp = gram_partial + (size_t)slab * nstrips * GRAM_FLOATS + threadIdx.x;
+    float s[GRAM_TILES];
+#pragma unroll
+    for (int j = 0; j < GRAM_TILES; ++j) s[j] = 0.0f;
+    for (int st = 0; st < nstrips; ++st) {
+      float t[GRAM_TILES];   // a loop of their own for the loads: added into the sums directly, each would be waited for in turn
+#pragma unroll
+      for (int j = 0; j < GRAM_TILES; ++j) t[j] = __builtin_nontemporal_load(gp + (size_t)st * GRAM_FLOATS + 256 * j);
+#pragma unroll
+      for (int j = 0; j < GRAM_TILES; ++j) s[j] += t[j];
+    }
+    // element tid of tile (e, f): register i = tid / 64 of lane l = tid % 64, i.e. G[8*(4*(l/16)+i) + e][8*(l%16) + f]
+    const int i = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int row0 = 8 * (4 * (l >> 4) + i), col0 = 8 * (l & 15);
+    int j = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+      for (int f = e; f < 8; ++f) {
+        sm.G[(row0 + e) * GP + col0 + f] = s[j];
+        if (e != f) sm.G[(col0 + f) * GP + row0 + e] = s[j];   // a diagonal tile holds both (row, col) and (col, row) itself
+        ++j;
+      }
+  }
+  double q[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) q[r] = (owner && r < rank) ? (double)init[((size_t)slab * D + c) * rank + r] : 0.0;
+  for (int l = 0; l < rounds; ++l) {
+    block_lds_sync();
+    if (owner) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) sm.Bs[c][r] = q[r];
+    }
+    block_lds_sync();
+    double qn[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) qn[r] = 0.0;
+#pragma unroll 8
+    for (int k = 64 * half; k < 64 * half + 64; ++k) {
+      const double gk = (double)sm.G[k * GP + c];   // G is symmetric: column c read as row-major neighbours
+#pragma unroll
+      for (int r = 0; r < R; ++r) qn[r] += gk * sm.Bs[k][r];
+    }
+    if (!owner) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) sm.part[c][r] = qn[r];
+    }
+    block_lds_sync();
+    // keep magnitudes in range between rounds
+    double n2[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      qn[r] = owner ? qn[r] + sm.part[c][r] : 0.0;
+      n2[r] = qn[r] * qn[r];
+    }
+    block_sum_vec<R>(n2, sm.red);
+#pragma unroll
+    for (int r = 0; r < R; ++r) q[r] = n2[r] > 0.0 ? qn[r] * rsqrt_d(n2[r]) : 0.0;
+  }
+  // QR of B by Gram-Schmidt applied twice (the projections of a pass are taken together: one
+  // block reduction per pass); dependent columns become 0.  (The upper half block holds zeros.)
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    double d[R + 1];
+#pragma unroll
+    for (int i = 0; i < R; ++i) d[i] = i < j ? q[i] * q[j] : 0.0;
+    d[R] = q[j] * q[j];
+    block_sum_vec<R + 1>(d, sm.red);
+    const double before2 = d[R];
+    if (before2 == 0.0) { q[j] = 0.0; continue; }   // block-uniform
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+      if (i < j) q[j] -= d[i] * q[i];
+#pragma unroll
+    for (int i = 0; i < R; ++i) d[i] = i < j ? q[i] * q[j] : 0.0;
+    d[R] = 0.0;
+    block_sum_vec<R + 1>(d, sm.red);
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+      if (i < j) q[j] -= d[i] * q[i];
+    double a2[1] = {q[j] * q[j]};
+    block_sum_vec<1>(a2, sm.red);
+    if (!(a2[0] > 1e-24 * before2)) q[j] = 0.0;   // norm after <= 1e-12 * norm before
+    else q[j] *= rsqrt_d(a2[0]);
+  }
+  if (owner) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) Bcur[((size_t)slab * D + c) * R + r] = (float)q[r];
+  }
+}
+
 // ------------------------------------------------------------------ host side
+int pi_gram_strip(int n, int slabs) {
+  for (int strip = 2048; strip > 512; strip >>= 1)
+    if ((long long)slabs * ((n + strip - 1) / strip) >= 1024) return strip;
+  return 512;
+}
+int pi_gram_strips_max(int n_max, int slabs) {
+  const int m = (1024 + slabs - 1) / slabs;   // strips per slab that fill the chip
+  const int coarse = (n_max + 2047) / 2048, fine = (n_max + 511) / 512;
+  const int want = 2 * m > coarse ? 2 * m : coarse;
+  return want < fine ? want : fine;
+}
+
+template <bool IS_K, int LG>
+static void launch_gram(const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int strip, int nstrips, float* gram,
+                        hipStream_t st) {
+  hipLaunchKernelGGL((pi_gram_kernel<IS_K, LG>), dim3(nstrips, dm.B * dm.H), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, strip, gram);
+}
+
 template <int R>
 static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
-                         const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat,
-                         hipStream_t st) {
+                         const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat, float* gram,
+                         int gram_strips_cap, hipStream_t st) {
   const int slabs = dm.B * dm.H;
   const int npart = (n + PT - 1) / PT;
   if (npart == 1) {   // a short segment: everything in one block per slab
@@ -491,21 +871,37 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
       hipLaunchKernelGGL((pi_small_kernel<false, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, iters, init_B, Bcur, partial, Atmp, cmat);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, init_B, sv.rank, (const float*)nullptr,
-                     0, iters == 1 ? 1 : 0, 0, Bcur, cmat, sv);
-  for (int l = 0; l < iters; ++l) {
-    const int last = (l == iters - 1);
+  // rounds 1 .. L-1: B <- (R^T R)^(L-1) B0 from one pass that forms the Gram matrix; then QR(B)
+  int nstrips = 0;
+  if (iters > 1) {
+    const int strip = pi_gram_strip(n, slabs);
+    nstrips = (n + strip - 1) / strip;
+    if (nstrips > gram_strips_cap) return hipErrorInvalidValue;
+    if (!is_k) launch_gram<false, 0>(Yf, sv, dm, n, strip, nstrips, gram, st);
+    else if (dm.g == 32) launch_gram<true, 5>(Yf, sv, dm, n, strip, nstrips, gram, st);
+    else if (dm.g == 64) launch_gram<true, 6>(Yf, sv, dm, n, strip, nstrips, gram, st);
+    else launch_gram<true, 7>(Yf, sv, dm, n, strip, nstrips, gram, st);
+  }
+  {
+    static bool lds_raised = false;   // per kernel instance (R)
+    if (!lds_raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pi_solve_kernel<R>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SolveSmem<R>));
+      if (e != hipSuccess) return e;
+      lds_raised = true;
+    }
+  }
+  hipLaunchKernelGGL(pi_solve_kernel<R>, dim3(slabs), dim3(256), sizeof(SolveSmem<R>), st, init_B, sv.rank, (const float*)gram,
+                     nstrips, iters - 1, Bcur);
+  // the last round: A = R B, orth(A) through its r x r Gram matrix, B = R^T A
+  {
     const dim3 grid(npart, slabs);
-    if (is_k && last)
+    if (is_k)
       hipLaunchKernelGGL((pi_sweep_kernel<true, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
-    else if (is_k)
-      hipLaunchKernelGGL((pi_sweep_kernel<true, R, false>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
-    else if (last)
-      hipLaunchKernelGGL((pi_sweep_kernel<false, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
     else
-      hipLaunchKernelGGL((pi_sweep_kernel<false, R, false>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
+      hipLaunchKernelGGL((pi_sweep_kernel<false, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
     hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, (const float*)nullptr, sv.rank,
-                       (const float*)partial, npart, (l == iters - 2) ? 1 : 0, last, Bcur, cmat, sv);
+                       (const float*)partial, npart, 0, 1, Bcur, cmat, sv);
   }
   hipLaunchKernelGGL(pi_finish_kernel<R>, dim3((n + 255) / 256, slabs), dim3(256), 0, st, (const float*)Atmp,
                      (const float*)cmat, sv, n);
@@ -516,11 +912,11 @@ int pi_padded_rank(int rank) { return rank <= 2 ? 2 : rank <= 4 ? 4 : 8; }
 
 hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
                                   const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat,
-                                  hipStream_t st) {
+                                  float* gram, int gram_strips_cap, hipStream_t st) {
   switch (pi_padded_rank(sv.rank)) {
-    case 2: return run_pi<2>(is_k, Yf, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
-    case 4: return run_pi<4>(is_k, Yf, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
-    default: return run_pi<8>(is_k, Yf, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, st);
+    case 2: return run_pi<2>(is_k, Yf, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, gram, gram_strips_cap, st);
+    case 4: return run_pi<4>(is_k, Yf, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, gram, gram_strips_cap, st);
+    default: return run_pi<8>(is_k, Yf, sv, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, gram, gram_strips_cap, st);
   }
 }
 

@@ -59,7 +59,7 @@ def emulator(tmp_path_factory):
 
 
 def test_pipeline_under_address_sanitizer(emulator, tmp_path):
-    B, H, Hq, n, bits, g, ppm, rank, n_buf = 1, 8, 16, 150, 2, 64, 20000, 4, 5
+    B, H, Hq, n, bits, g, ppm, rank, n_buf = 1, 4, 8, 290, 2, 64, 20000, 4, 5
     w = gw.Workload("emu", B=B, H_kv=H, H_q=Hq, n=n, bits=bits, group=g, outlier_ppm=ppm, rank=rank,
                     rank_chunk=2, n_b=20, steps=1, seed=5)
     d = str(tmp_path)
