@@ -124,3 +124,21 @@ def make_init_B(w: Workload, rank: int, stream: int, device="cpu", B: Optional[i
     k = torch.randint(0, 1 << 24, (2, B, w.H_kv, w.d_h, max(rank, 1)), generator=g, dtype=torch.int64)
     b0 = (k.to(torch.float64) / float(1 << 23) - 1.0).to(torch.float32)
     return b0[..., :rank].contiguous().to(device)
+
+
+def make_init_B_hashed(seed: int, B: int, H_kv: int, rank: int, device="cpu", d_h: int = D_HEAD) -> torch.Tensor:
+    """The start array the library draws itself when it is given a seed instead of an array
+    (include/gear.h, gear_compress): fp32 [2, B, H_kv, d_h, rank], entry i (row-major) =
+    ((z >> 40) - 2^23) / 2^23, z = mix(seed + (i + 1) * 0x9E3779B97F4A7C15) with the SplitMix64
+    finalizer.  Integers only, so this mirror gives the same floats bit for bit; handing it to the
+    oracle (and to the library as an explicit array) is how the seeded path is checked."""
+    import numpy as np
+    n = 2 * B * H_kv * d_h * max(rank, 1)
+    with np.errstate(over="ignore"):
+        z = np.uint64(seed) + np.uint64(0x9E3779B97F4A7C15) * (np.arange(n, dtype=np.uint64) + np.uint64(1))
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        z = z ^ (z >> np.uint64(31))
+    k = (z >> np.uint64(40)).astype(np.int64) - (1 << 23)
+    b0 = (k.astype(np.float64) / float(1 << 23)).astype(np.float32).reshape(2, B, H_kv, d_h, max(rank, 1))
+    return torch.from_numpy(b0[..., :rank].copy()).to(device)

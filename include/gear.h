@@ -98,14 +98,19 @@ int gear_cache_reset(gear_cache* cache);
  * K, V      : device fp16 [B, H_kv, n, d_h].
  * n         : first call: 1..n_prefill_max; later calls: 1..n_buf_cap.
  * rank      : 0..rank_max (0 = no low-rank term); iters >= 1.
- * init_B    : device fp32 [2 (K,V), B, H_kv, d_h, rank]; required when rank > 0
- *             (the random start of Algorithm 2 is an input so that runs are
- *             reproducible).
+ * init_B    : device fp32 [2 (K,V), B, H_kv, d_h, rank], the start matrices B0 of
+ *             Algorithm 2 (its random initialisation, taken as an input so that runs are
+ *             reproducible), or NULL: the library then draws the same array on the
+ *             device from `seed`: entry i (row-major) is ((z >> 40) - 2^23) / 2^23 with
+ *             z = mix(seed + (i + 1) * 0x9E3779B97F4A7C15), mix(z): z ^= z >> 30,
+ *             z *= 0xBF58476D1CE4E5B9, z ^= z >> 27, z *= 0x94D049BB133111EB,
+ *             z ^= z >> 31 (64-bit arithmetic): uniform on a 24-bit grid in [-1, 1).
+ * seed      : used only when init_B is NULL and rank > 0.
  * workspace : device, >= workspace_bytes of gear_cache_bytes.
  */
 int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, int32_t rank,
-                  int32_t iters, const float* init_B, void* workspace, size_t workspace_bytes,
-                  void* stream);
+                  int32_t iters, const float* init_B, uint64_t seed, void* workspace,
+                  size_t workspace_bytes, void* stream);
 
 /* X-hat = D + A B^T + S for every stored token (Algorithm 1, "replace X with
  * D + L + S"), rounded to fp16.  K_out, V_out: device fp16
@@ -163,6 +168,24 @@ int gear_export_sparse(const gear_cache* cache, int which, void* mask_u8, void* 
                        void* stream);
 int gear_export_lowrank(const gear_cache* cache, int which, int seg, void* A_f16, void* B_f16,
                         void* stream);
+
+/*
+ * The sparse matrix S of Filter_s (Eq. 4) in the coordinate form the paper's Sec. 3.1
+ * describes (index vectors plus one value vector), over all stored segments:
+ *  nnz           : host, out.  Fixed by Eq. 4: every Key channel of a segment of n tokens
+ *                  holds ceil(s n) entries, every Value token ceil(s H_kv d_h); the call
+ *                  computes it on the host, so a first call with lin_index_i64 ==
+ *                  value_f16 == NULL (nothing launched) tells the caller what to allocate.
+ *  lin_index_i64 : device int64 [nnz], the linear index ((b * H_kv + h) * n_total + t) * d_h + c
+ *                  of every entry, ascending (the two index vectors of the coordinate
+ *                  form are index / d_h and index % d_h).
+ *  value_f16     : device fp16 [nnz], the entries (bit copies of the input) in the same order.
+ *  workspace     : device scratch, >= 4 * B * H_kv * n_total + 4 * ceil(B * H_kv * n_total / 1024)
+ *                  + 512 bytes (the workspace of gear_cache_bytes is large enough whenever
+ *                  n_total <= 8 * n_prefill_max); GEAR_ECAPACITY otherwise.
+ */
+int gear_export_sparse_coo(const gear_cache* cache, int which, int64_t* nnz, void* lin_index_i64,
+                           void* value_f16, void* workspace, size_t workspace_bytes, void* stream);
 
 const char* gear_strerror(int status);
 

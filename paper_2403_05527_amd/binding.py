@@ -15,7 +15,7 @@ GEAR_OK, GEAR_EINVAL, GEAR_ECAPACITY, GEAR_EALIGN, GEAR_EHIP = 0, -1, -2, -3, -4
 
 EXPORTED = [
     "gear_cache_bytes", "gear_cache_init", "gear_cache_reset", "gear_compress", "gear_decompress",
-    "gear_decode_attn", "gear_decode_attn_static", "gear_export_codes", "gear_export_sparse", "gear_export_lowrank", "gear_strerror",
+    "gear_decode_attn", "gear_decode_attn_static", "gear_export_codes", "gear_export_sparse", "gear_export_sparse_coo", "gear_export_lowrank", "gear_strerror",
 ]
 
 
@@ -61,12 +61,13 @@ def load_library():
     lib.gear_cache_bytes.argtypes = [cfgp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.gear_cache_init.argtypes = [cfgp, vp, sz, cachep]
     lib.gear_cache_reset.argtypes = [cachep]
-    lib.gear_compress.argtypes = [cachep, vp, vp, i32, i32, i32, vp, vp, sz, vp]
+    lib.gear_compress.argtypes = [cachep, vp, vp, i32, i32, i32, vp, ctypes.c_uint64, vp, sz, vp]
     lib.gear_decompress.argtypes = [cachep, vp, vp, vp]
     lib.gear_decode_attn.argtypes = [cachep, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.gear_decode_attn_static.argtypes = [cachep, vp, vp, vp, i32, vp, vp]
     lib.gear_export_codes.argtypes = [cachep, ctypes.c_int, vp, vp, vp, vp]
     lib.gear_export_sparse.argtypes = [cachep, ctypes.c_int, vp, vp, vp]
+    lib.gear_export_sparse_coo.argtypes = [cachep, ctypes.c_int, ctypes.POINTER(ctypes.c_int64), vp, vp, vp, sz, vp]
     lib.gear_export_lowrank.argtypes = [cachep, ctypes.c_int, ctypes.c_int, vp, vp, vp]
     lib.gear_strerror.argtypes = [ctypes.c_int]
     lib.gear_strerror.restype = ctypes.c_char_p
@@ -118,10 +119,10 @@ def gear_cache_reset(cache):
     _check(load_library().gear_cache_reset(ctypes.byref(cache)), "gear_cache_reset")
 
 
-def gear_compress(cache, K, V, rank, iters, init_B, workspace):
+def gear_compress(cache, K, V, rank, iters, init_B, workspace, seed=0):
     n = K.shape[2]
     _check(load_library().gear_compress(ctypes.byref(cache), _ptr(K), _ptr(V), n, rank, iters, _ptr(init_B),
-                                        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+                                        ctypes.c_uint64(seed), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
            "gear_compress")
 
 
@@ -149,6 +150,15 @@ def gear_export_codes(cache, which, codes, scale, zero):
 def gear_export_sparse(cache, which, mask, values):
     _check(load_library().gear_export_sparse(ctypes.byref(cache), which, _ptr(mask), _ptr(values), _stream()),
            "gear_export_sparse")
+
+
+def gear_export_sparse_coo(cache, which, lin_index, values, workspace):
+    """Returns nnz; with lin_index = values = None only the count is computed (nothing is launched)."""
+    nnz = ctypes.c_int64(0)
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().gear_export_sparse_coo(ctypes.byref(cache), which, ctypes.byref(nnz), _ptr(lin_index),
+                                                 _ptr(values), _ptr(workspace), wb, _stream()), "gear_export_sparse_coo")
+    return nnz.value
 
 
 def gear_export_lowrank(cache, which, seg, A, Bf):
@@ -183,8 +193,8 @@ class GearCache:
     def reset(self):
         gear_cache_reset(self.cache)
 
-    def compress(self, K, V, rank, iters=3, init_B=None):
-        gear_compress(self.cache, K, V, rank, iters, init_B, self.workspace)
+    def compress(self, K, V, rank, iters=3, init_B=None, seed=0):
+        gear_compress(self.cache, K, V, rank, iters, init_B, self.workspace, seed)
 
     def decompress(self):
         c = self.cfg
@@ -219,6 +229,13 @@ class GearCache:
         vals = torch.empty(shape, dtype=torch.float16, device=self.device)
         gear_export_sparse(self.cache, which, mask, vals)
         return mask, vals
+
+    def export_sparse_coo(self, which):
+        nnz = gear_export_sparse_coo(self.cache, which, None, None, None)
+        lin = torch.empty(max(nnz, 1), dtype=torch.int64, device=self.device)
+        vals = torch.empty(max(nnz, 1), dtype=torch.float16, device=self.device)
+        gear_export_sparse_coo(self.cache, which, lin, vals, self.workspace)
+        return lin[:nnz], vals[:nnz]
 
     def export_lowrank(self, which, seg):
         c = self.cfg

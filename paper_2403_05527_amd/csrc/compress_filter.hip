@@ -269,6 +269,7 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
       const int k = gi * KPG + kk;
       const int t = t0 + r0 + 16 * k;
       if (t < n) {
+#pragma clang fp contract(off)
         float cw0 = 0.0f, cw1 = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {

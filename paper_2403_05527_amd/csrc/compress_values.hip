@@ -148,6 +148,7 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
     uint32_t fc[8];   // bits of code + 2^23
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
+#pragma clang fp contract(off)
       const uint32_t x = raw[e >> 1] & ~msk[e >> 1];
       const float y = h2f((e & 1) ? (x >> 16) : (x & 0xFFFFu));
       const float tq = __fmul_rn(__fsub_rn(y, q.mn), q.inv);

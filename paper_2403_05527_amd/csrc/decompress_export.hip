@@ -139,6 +139,107 @@ __global__ __launch_bounds__(256) void export_sparse_kernel(Dims dm, SegView sv,
   });
 }
 
+// ---- COO view of S: (linear index into [B, H, n_total, 128], fp16 value), sorted by index ----
+// Pass 1 (count = 1) leaves the number of outliers of every token row in rowcnt[slab * n_total + t];
+// after the prefix sums, pass 2 (count = 0) writes each row's entries in channel order from rowcnt[row]
+// (then the row's first position).  grid (ceil(n/64), B*H), block 256: the tile's part of S is
+// rebuilt in LDS as a bit per entry plus its value.
+__global__ __launch_bounds__(256) void coo_tile_kernel(Dims dm, SegView sv, int is_k, int count, uint32_t* __restrict__ rowcnt,
+                                                       long long* __restrict__ lin, uint16_t* __restrict__ vals, int n_total) {
+  __shared__ uint32_t bits[TILE][4];
+  __shared__ uint16_t val[TILE][D];
+  const int slab = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+  const int b = slab / dm.H;
+  if (tid < TILE * 4) (&bits[0][0])[tid] = 0u;
+  block_lds_sync();
+  auto put = [&](int tl, int c, uint32_t hb) {
+    atomicOr(&bits[tl][c >> 5], 1u << (c & 31));
+    val[tl][c] = (uint16_t)hb;
+  };
+  if (dm.ppm > 0) {
+    const uint2 oc = sv.sp_table[(size_t)slab * sv.ntile_cap + tile];
+    const uint32_t* lst = sv.sp_pool + (size_t)(is_k ? slab : b) * sv.pool_cap + oc.x;
+    for (uint32_t e = tid; e < oc.y; e += 256) {
+      const uint32_t en = lst[e];
+      const int tl = (int)((en & 0xFFFFu) >> 7);
+      if (tile * TILE + tl < sv.n) put(tl, (int)(en & 127u), en >> 16);
+    }
+    for_each_ell(sv, is_k, slab, tile, tid, put);
+  }
+  block_lds_sync();
+  if (tid < TILE && tile * TILE + tid < sv.n) {
+    const size_t row = (size_t)slab * n_total + sv.t0 + tile * TILE + tid;
+    if (count) {
+      rowcnt[row] = __popc(bits[tid][0]) + __popc(bits[tid][1]) + __popc(bits[tid][2]) + __popc(bits[tid][3]);
+    } else {
+      size_t o = rowcnt[row];
+      for (int w = 0; w < 4; ++w) {
+        uint32_t m = bits[tid][w];
+        while (m) {
+          const int c = 32 * w + __ffs((int)m) - 1;
+          m &= m - 1u;
+          lin[o] = (long long)(row * D + c);
+          vals[o] = val[tid][c];
+          ++o;
+        }
+      }
+    }
+  }
+}
+
+// Exclusive prefix sums of v[0 .. count) in place, in three launches: sums of chunks of 1024,
+// their prefix sums (one block), then each chunk's own scan.
+__global__ __launch_bounds__(256) void scan_chunk_sums_kernel(const uint32_t* __restrict__ v, size_t count, uint32_t* __restrict__ sums) {
+  __shared__ uint32_t red[4];
+  const size_t base = (size_t)blockIdx.x * 1024;
+  uint32_t s = 0;
+  for (int i = threadIdx.x; i < 1024; i += 256)
+    if (base + i < count) s += v[base + i];
+  s = wave_sum_shfl(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  block_lds_sync();
+  if (threadIdx.x == 0) sums[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+__global__ __launch_bounds__(256) void scan_sums_kernel(uint32_t* __restrict__ sums, int nchunks) {   // one block
+  __shared__ uint32_t wtot[4];
+  __shared__ uint32_t carry_s;
+  if (threadIdx.x == 0) carry_s = 0u;
+  block_lds_sync();
+  for (int i0 = 0; i0 < nchunks; i0 += 256) {
+    const int i = i0 + threadIdx.x;
+    const uint32_t x = i < nchunks ? sums[i] : 0u;
+    const uint32_t inc = wave_incl_scan(x);
+    if ((threadIdx.x & 63) == 63) wtot[threadIdx.x >> 6] = inc;
+    block_lds_sync();
+    uint32_t off = carry_s;
+    for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) off += wtot[w];
+    if (i < nchunks) sums[i] = off + inc - x;
+    block_lds_sync();
+    if (threadIdx.x == 255) carry_s = off + inc;
+    block_lds_sync();
+  }
+}
+__global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ v, size_t count, const uint32_t* __restrict__ sums) {
+  __shared__ uint32_t wtot[4];
+  const size_t base = (size_t)blockIdx.x * 1024 + (size_t)threadIdx.x * 4;
+  uint32_t x[4], t = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[i] = base + i < count ? v[base + i] : 0u;
+    t += x[i];
+  }
+  const uint32_t inc = wave_incl_scan(t);
+  if ((threadIdx.x & 63) == 63) wtot[threadIdx.x >> 6] = inc;
+  block_lds_sync();
+  uint32_t off = sums[blockIdx.x] + inc - t;
+  for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) off += wtot[w];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (base + i < count) v[base + i] = off;
+    off += x[i];
+  }
+}
+
 __global__ void export_lowrank_kernel(SegView sv, uint16_t* __restrict__ A, uint16_t* __restrict__ Bf, int slabs) {
   const size_t na = (size_t)slabs * sv.n * sv.rank, nb = (size_t)slabs * D * sv.rank;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < na + nb; i += (size_t)gridDim.x * blockDim.x) {
@@ -173,6 +274,22 @@ hipError_t launch_export_sparse(const Dims& dm, const SegView& sv, bool is_k, ui
   if (dm.ppm == 0) return hipSuccess;
   dim3 grid((sv.n + TILE - 1) / TILE, dm.B * dm.H);
   hipLaunchKernelGGL(export_sparse_kernel, grid, dim3(256), 0, st, dm, sv, is_k ? 1 : 0, mask, vals, n_total);
+  return hipGetLastError();
+}
+
+hipError_t launch_coo_tiles(const Dims& dm, const SegView& sv, bool is_k, bool count, uint32_t* rowcnt, long long* lin,
+                            uint16_t* vals, int n_total, hipStream_t st) {
+  dim3 grid((sv.n + TILE - 1) / TILE, dm.B * dm.H);
+  hipLaunchKernelGGL(coo_tile_kernel, grid, dim3(256), 0, st, dm, sv, is_k ? 1 : 0, count ? 1 : 0, rowcnt, lin, vals, n_total);
+  return hipGetLastError();
+}
+
+hipError_t launch_exclusive_scan(uint32_t* v, size_t count, uint32_t* sums, hipStream_t st) {
+  const int nchunks = (int)((count + 1023) / 1024);
+  if (nchunks == 0) return hipSuccess;
+  hipLaunchKernelGGL(scan_chunk_sums_kernel, dim3(nchunks), dim3(256), 0, st, (const uint32_t*)v, count, sums);
+  hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, st, sums, nchunks);
+  hipLaunchKernelGGL(scan_apply_kernel, dim3(nchunks), dim3(256), 0, st, v, count, (const uint32_t*)sums);
   return hipGetLastError();
 }
 

@@ -307,13 +307,12 @@ int gear_cache_reset(gear_cache* cache) {
 }
 
 int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, int32_t rank, int32_t iters,
-                  const float* init_B, void* workspace, size_t workspace_bytes, void* stream) {
+                  const float* init_B, uint64_t seed, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_cache(cache);
   if (rc) return rc;
   const gear_config& c = cache->cfg;
   if (!K || !V || !workspace) return GEAR_EINVAL;
   if (n < 1 || rank < 0 || rank > c.rank_max || iters < 1 || iters > 64) return GEAR_EINVAL;
-  if (rank > 0 && !init_B) return GEAR_EINVAL;
   if (!aligned16(K) || !aligned16(V) || !aligned16(workspace) || (init_B && !aligned16(init_B))) return GEAR_EALIGN;
   const bool first = cache->n_prefill == 0;
   if (first) {
@@ -351,12 +350,11 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   float* Atmp = reinterpret_cast<float*>(ws + w.Atmp);
   float* cmat = reinterpret_cast<float*>(ws + w.cmat);
   float* gram = reinterpret_cast<float*>(ws + w.gram);
-  const size_t half = (size_t)c.B * c.H_kv * D * rank;
   GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, resid, st));
-  if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, ks, dm, n, iters, init_B, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
+  if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, ks, dm, n, iters, init_B, seed, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
   GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, pool_ctr + (size_t)c.B * c.H_kv, resid, st));
   if (rank > 0)
-    GEAR_HIP(launch_power_iteration(false, resid, vs, dm, n, iters, init_B + half, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
+    GEAR_HIP(launch_power_iteration(false, resid, vs, dm, n, iters, init_B, seed, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
 
   if (first) {
     cache->n_prefill = n;
@@ -447,6 +445,47 @@ int gear_export_sparse(const gear_cache* cache, int which, void* mask_u8, void* 
     seg_views(cache, a, seg, seg_n(cache, seg), seg_rank(cache, seg), &ks, &vs);
     GEAR_HIP(launch_export_sparse(dm, which == 0 ? ks : vs, which == 0, static_cast<uint8_t*>(mask_u8),
                                   static_cast<uint16_t*>(values_f16), cache->n_total, st));
+  }
+  return GEAR_OK;
+}
+
+int gear_export_sparse_coo(const gear_cache* cache, int which, int64_t* nnz, void* lin_index_i64, void* value_f16,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  const int rc = check_cache(cache);
+  if (rc) return rc;
+  if ((which != 0 && which != 1) || !nnz) return GEAR_EINVAL;
+  const gear_config& c = cache->cfg;
+  // the counts are fixed by Filter_s: per Key channel of a segment, per Value token
+  long long total = 0;
+  for (int seg = 0; seg <= cache->n_chunks; ++seg) {
+    if (seg == 0 && cache->n_prefill == 0) continue;
+    const long long n = seg_n(cache, seg);
+    total += which == 0 ? (long long)c.B * c.H_kv * D * outlier_count(n, c.outlier_ppm)
+                        : (long long)c.B * n * outlier_count((long long)c.H_kv * D, c.outlier_ppm);
+  }
+  *nnz = total;
+  if (!lin_index_i64 && !value_f16) return GEAR_OK;   // size query
+  if (!lin_index_i64 || !value_f16 || !workspace) return GEAR_EINVAL;
+  if (!aligned16(lin_index_i64) || !aligned16(value_f16) || !aligned16(workspace)) return GEAR_EALIGN;
+  if (total == 0) return GEAR_OK;
+  if (total >= (1ll << 32)) return GEAR_ECAPACITY;
+  const size_t rows = (size_t)c.B * c.H_kv * cache->n_total;
+  const size_t need = up(rows * 4) + up(((rows + 1023) / 1024) * 4);
+  if (workspace_bytes < need) return GEAR_ECAPACITY;
+  uint32_t* rowcnt = static_cast<uint32_t*>(workspace);
+  uint32_t* sums = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + up(rows * 4));
+  const ArenaLayout a = arena_layout(c);
+  const Dims dm = make_dims(c);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int seg = 0; seg <= cache->n_chunks; ++seg) {
+      if (seg == 0 && cache->n_prefill == 0) continue;
+      SegView ks, vs;
+      seg_views(cache, a, seg, seg_n(cache, seg), seg_rank(cache, seg), &ks, &vs);
+      GEAR_HIP(launch_coo_tiles(dm, which == 0 ? ks : vs, which == 0, pass == 0, rowcnt, static_cast<long long*>(lin_index_i64),
+                                static_cast<uint16_t*>(value_f16), cache->n_total, st));
+    }
+    if (pass == 0) GEAR_HIP(launch_exclusive_scan(rowcnt, rows, sums, st));
   }
   return GEAR_OK;
 }

@@ -253,7 +253,10 @@ struct GroupQ {
   float delta;  // fp16-rounded scale, as float
   float inv;    // 1/delta, 0 when delta == 0
 };
+// (The decision sequence is kept free of fused multiply-adds whatever the compiler's default is:
+// contraction is switched off inside these functions and around the quantizer loops of the kernels.)
 __device__ __forceinline__ GroupQ make_group(float mn, float mx, float qmax) {
+#pragma clang fp contract(off)
   GroupQ q;
   q.mn = mn + 0.0f;  // -0 -> +0
   mx = mx + 0.0f;
@@ -280,9 +283,32 @@ __device__ __forceinline__ float clamp_f32(float x, float lo, float hi) { return
 // Quantization error of one entry (Alg. 1: R = Y - D-hat, D-hat = code * scale + zero) with
 // the code decided by the quantizer's own operation sequence (Eq. 2), so it is the stored one.
 __device__ __forceinline__ float quant_error(float y, float mn, float inv, float delta, float qmax) {
+#pragma clang fp contract(off)
   const float ym = __fsub_rn(y, mn);
   const float c = clamp_f32(rintf(__fmul_rn(ym, inv)), 0.0f, qmax);
   return __builtin_fmaf(-c, delta, ym);
+}
+
+// Start matrix B0 of Algorithm 2 (its "random_initialize"), as the caller's array or drawn here.
+// Entry i of the [2 (K, V), B, H, 128, rank] array is u(seed, i) = ((z >> 40) - 2^23) / 2^23 with
+// z = the 64-bit mix below of seed + (i + 1) * 0x9E3779B97F4A7C15 (the SplitMix64 step): integers
+// only, uniform on a 24-bit grid in [-1, 1), so any implementation of the same formula gives the
+// same floats.
+struct StartB {
+  const float* init;   // device fp32 [slabs of this tensor][128][rank], or nullptr: draw
+  uint64_t seed;
+  uint64_t base;       // index of this tensor's first entry in the whole array
+};
+__host__ __device__ inline float start_entry(uint64_t seed, uint64_t i) {
+  uint64_t z = seed + 0x9E3779B97F4A7C15ull * (i + 1ull);
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  return (float)((int)(z >> 40) - (1 << 23)) * (1.0f / 8388608.0f);
+}
+__device__ __forceinline__ float start_b(const StartB& sb, int slab, int c, int rank, int r) {
+  const uint64_t i = ((uint64_t)slab * D + c) * rank + r;
+  return sb.init ? sb.init[i] : start_entry(sb.seed, sb.base + i);
 }
 
 __device__ __forceinline__ void block_lds_sync() { GEAR_LDS_BARRIER(); }

@@ -30,8 +30,10 @@ int pi_padded_rank(int rank);
 // gram: [slab][strip][36 * 256] floats, the partial Gram matrices of the residual (segments of more than 256 tokens
 // with iters > 1); gram_strips_cap: strips per slab it has room for (pi_gram_strips_max of the largest segment)
 int pi_gram_strips_max(int n_max, int slabs);
+// init_B: the whole start array [2 (K, V), B, H, 128, rank] (the launcher takes this tensor's half), or
+// nullptr: the same array is drawn from `seed` (start_entry in gear_internal.h)
 hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
-                                  const float* init_B, float* Bcur, float* partial, float* Atmp, float* cmat,
+                                  const float* init_B, uint64_t seed, float* Bcur, float* partial, float* Atmp, float* cmat,
                                   float* gram, int gram_strips_cap, hipStream_t st);
 
 constexpr int DECODE_TS = 256;           // rows per pass of the chunk / buffer path
@@ -47,6 +49,12 @@ hipError_t launch_export_codes(const Dims& dm, const SegView& sv, bool is_k, uin
                                uint16_t* zero, int n_total, int ng_total, hipStream_t st);
 hipError_t launch_export_sparse(const Dims& dm, const SegView& sv, bool is_k, uint8_t* mask, uint16_t* vals,
                                 int n_total, hipStream_t st);
+// COO view of S: count = true writes every token row's outlier count to rowcnt[slab * n_total + t]; count = false
+// writes the rows' entries from the positions rowcnt then holds (launch_exclusive_scan in between; sums: scratch of
+// ceil(count / 1024) words)
+hipError_t launch_coo_tiles(const Dims& dm, const SegView& sv, bool is_k, bool count, uint32_t* rowcnt, long long* lin,
+                            uint16_t* vals, int n_total, hipStream_t st);
+hipError_t launch_exclusive_scan(uint32_t* v, size_t count, uint32_t* sums, hipStream_t st);
 hipError_t launch_export_lowrank(const Dims& dm, const SegView& sv, uint16_t* A, uint16_t* Bf, hipStream_t st);
 
 }  // namespace gear

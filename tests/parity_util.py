@@ -56,6 +56,11 @@ def compare_components(gc, oc):
         assert np.array_equal(vals.view(np.uint16)[o_mask], o_vals.view(np.uint16)[o_mask]), name + " outlier values"
         assert not vals.view(np.uint16)[~o_mask].any(), name + " values off the support"
         rep[name + "_nnz"] = int(o_mask.sum())
+        # the same matrix in coordinate form: ascending linear indices and the values in that order
+        lin, cv = [np16(x) for x in gc.export_sparse_coo(which)]
+        want = np.flatnonzero(o_mask)
+        assert lin.shape == want.shape and np.array_equal(lin, want), name + " COO indices"
+        assert np.array_equal(cv.view(np.uint16), o_vals.view(np.uint16).reshape(-1)[want]), name + " COO values"
     return rep
 
 
@@ -74,14 +79,21 @@ def compare_decompress(gc, oc):
     return {"K_rel_frob": ek, "V_rel_frob": ev}
 
 
+LOWRANK_REL_TOL = 5e-4   # A B^T of the stored fp16 factors vs the oracle's, relative Frobenius, per tensor
+
+
 def compare_lowrank_product(gc, oc, seg):
-    """Only the product A B^T is defined (the basis is not): compare that."""
+    """Only the product A B^T is defined (the basis is not): compare that, per tensor, in
+    relative Frobenius norm over the whole batch; a zero oracle product must be matched by zero."""
     out = {}
     for which, (name, segs) in enumerate((("K", oc.K), ("V", oc.V))):
         A, Bf = [np16(x).astype(np.float64) for x in gc.export_lowrank(which, seg)]
         Lg = np.einsum("bhnr,bhdr->bhnd", A, Bf)
         Lo = np.einsum("bhnr,bhdr->bhnd", segs[seg].A.astype(np.float64), segs[seg].Bf.astype(np.float64))
-        out[name + "_L_rel"] = float(np.linalg.norm(Lg - Lo) / max(np.linalg.norm(Lo), 1e-30))
+        no = np.linalg.norm(Lo)
+        rel = float(np.linalg.norm(Lg - Lo) / no) if no > 0 else float(np.linalg.norm(Lg))
+        assert rel <= LOWRANK_REL_TOL, "%s low-rank product: relative error %.3e" % (name, rel)
+        out[name + "_L_rel"] = rel
     return out
 
 

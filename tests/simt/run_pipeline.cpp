@@ -39,11 +39,11 @@ int main(int argc, char** argv) {
   CK(gear_cache_init(&cfg, arena, ab, &cache));
   void *K = rd(dir, "K", -1), *V = rd(dir, "V", -1), *ib = rd(dir, "ib", -1);
   fprintf(stderr, "compress prefill n=%d\n", n);
-  CK(gear_compress(&cache, K, V, n, rank, iters, rank ? (const float*)ib : nullptr, work, wb, nullptr));
+  CK(gear_compress(&cache, K, V, n, rank, iters, rank ? (const float*)ib : nullptr, 0, work, wb, nullptr));
   for (int j = 0; j < nchunks; ++j) {
     void *Kc = rd(dir, "Kc", j), *Vc = rd(dir, "Vc", j), *ibc = rd(dir, "ibc", j);
     fprintf(stderr, "compress chunk %d n=%d\n", j, chunk_n);
-    CK(gear_compress(&cache, Kc, Vc, chunk_n, rank_chunk, iters, (const float*)ibc, work, wb, nullptr));
+    CK(gear_compress(&cache, Kc, Vc, chunk_n, rank_chunk, iters, (const float*)ibc, 0, work, wb, nullptr));
   }
   void *q = rd(dir, "q", -1), *Kb = rd(dir, "Kb", -1), *Vb = rd(dir, "Vb", -1);
   const size_t ob = (size_t)B * Hq * 128 * 2;
@@ -56,6 +56,16 @@ int main(int argc, char** argv) {
   fprintf(stderr, "decompress n_total=%zu\n", ntot);
   CK(gear_decompress(&cache, Kh, Vh, nullptr));
   wr(dir, "Khat", Kh, hb); wr(dir, "Vhat", Vh, hb);
+  // canonical code / scale / zero views, for the bit-exact comparison with the oracle
+  const int ng_tot = (n + g - 1) / g + nchunks * ((chunk_n + g - 1) / g);
+  for (int which = 0; which < 2; ++which) {
+    const size_t cb = (size_t)B * H * ntot * 128, sb = which == 0 ? (size_t)B * H * ng_tot * 128 * 2 : (size_t)B * H * ntot * (128 / g) * 2;
+    void *codes = aligned_alloc(256, (cb + 255) / 256 * 256), *sc = aligned_alloc(256, (sb + 255) / 256 * 256), *ze = aligned_alloc(256, (sb + 255) / 256 * 256);
+    CK(gear_export_codes(&cache, which, codes, sc, ze, nullptr));
+    wr(dir, which ? "Vcodes" : "Kcodes", codes, cb);
+    wr(dir, which ? "Vscale" : "Kscale", sc, sb);
+    wr(dir, which ? "Vzero" : "Kzero", ze, sb);
+  }
   fprintf(stderr, "done\n");
   return 0;
 }

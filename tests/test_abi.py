@@ -78,14 +78,13 @@ def test_init_and_call_validation_on_host(lib):
     assert cache.n_total == 0 and cache.n_chunks == 0
     st = None
     # compress: bad n / rank / iters / pointers / capacity -- all rejected before any launch
-    assert lib.gear_compress(ctypes.byref(cache), None, fake, 8, 0, 3, None, fake, w, st) == gb.GEAR_EINVAL
-    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 0, 0, 3, None, fake, w, st) == gb.GEAR_EINVAL
-    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 8, 5, 3, fake, fake, w, st) == gb.GEAR_EINVAL
-    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 8, 2, 3, None, fake, w, st) == gb.GEAR_EINVAL
-    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 8, 0, 0, None, fake, w, st) == gb.GEAR_EINVAL
-    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 513, 0, 3, None, fake, w, st) == gb.GEAR_ECAPACITY
-    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 8, 0, 3, None, fake, w - 1, st) == gb.GEAR_ECAPACITY
-    assert lib.gear_compress(ctypes.byref(cache), ctypes.c_void_p(0x10000002), fake, 8, 0, 3, None, fake, w, st) \
+    assert lib.gear_compress(ctypes.byref(cache), None, fake, 8, 0, 3, None, 0, fake, w, st) == gb.GEAR_EINVAL
+    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 0, 0, 3, None, 0, fake, w, st) == gb.GEAR_EINVAL
+    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 8, 5, 3, fake, 0, fake, w, st) == gb.GEAR_EINVAL
+    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 8, 0, 0, None, 0, fake, w, st) == gb.GEAR_EINVAL
+    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 513, 0, 3, None, 0, fake, w, st) == gb.GEAR_ECAPACITY
+    assert lib.gear_compress(ctypes.byref(cache), fake, fake, 8, 0, 3, None, 0, fake, w - 1, st) == gb.GEAR_ECAPACITY
+    assert lib.gear_compress(ctypes.byref(cache), ctypes.c_void_p(0x10000002), fake, 8, 0, 3, None, 0, fake, w, st) \
         == gb.GEAR_EALIGN
     assert cache.n_total == 0                     # failed calls leave the descriptor untouched
     # decode on an empty cache with an empty buffer is an error; so is n_buf beyond capacity
@@ -94,4 +93,9 @@ def test_init_and_call_validation_on_host(lib):
     assert lib.gear_decode_attn(ctypes.byref(cache), fake, None, fake, 3, fake, fake, w, st) == gb.GEAR_EINVAL
     assert lib.gear_export_lowrank(ctypes.byref(cache), 0, 0, fake, fake, st) == gb.GEAR_EINVAL
     assert lib.gear_export_codes(ctypes.byref(cache), 2, fake, fake, fake, st) == gb.GEAR_EINVAL
+    nnz = ctypes.c_int64(-1)
+    assert lib.gear_export_sparse_coo(ctypes.byref(cache), 0, None, None, None, None, 0, st) == gb.GEAR_EINVAL
+    assert lib.gear_export_sparse_coo(ctypes.byref(cache), 0, ctypes.byref(nnz), None, None, None, 0, st) == gb.GEAR_OK
+    assert nnz.value == 0                         # an empty cache has no outliers
+    assert lib.gear_export_sparse_coo(ctypes.byref(cache), 0, ctypes.byref(nnz), fake, None, fake, w, st) == gb.GEAR_EINVAL
     assert gb.strerror(gb.GEAR_ECAPACITY).startswith("capacity")

@@ -35,7 +35,9 @@ def emulator(tmp_path_factory):
     if cxx is None:
         pytest.skip("no clang++ to build the CPU emulation")
     out = tmp_path_factory.mktemp("simt")
-    flags = ["-std=c++17", "-O1", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-pthread",
+    # -ffp-contract=fast: the host compiler may fuse every multiply-add it finds, except where the sources
+    # switch contraction off (the quantizer's decision sequence), which the bit-exact code comparison checks
+    flags = ["-std=c++17", "-O1", "-g", "-ffp-contract=fast", "-fsanitize=address", "-fno-omit-frame-pointer", "-pthread",
              "-I", SIMT, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     procs = []
     objs = []
@@ -90,3 +92,14 @@ def test_pipeline_under_address_sanitizer(emulator, tmp_path):
     Vg = np.fromfile(os.path.join(d, "Vhat.bin"), np.float16).reshape(Vo.shape).astype(np.float64)
     for got, want in ((Kg, Ko.astype(np.float64)), (Vg, Vo.astype(np.float64))):
         assert np.linalg.norm(got - want) <= 1e-3 * np.linalg.norm(want)
+    # codes, scales and zero-points bit for bit, although this build lets the compiler contract
+    for name, segs in (("K", oc.K), ("V", oc.V)):
+        o_codes = np.concatenate([s.codes for s in segs], axis=2)
+        o_scale = np.concatenate([s.scale for s in segs], axis=2)
+        o_zero = np.concatenate([s.zero for s in segs], axis=2)
+        codes = np.fromfile(os.path.join(d, name + "codes.bin"), np.uint8).reshape(o_codes.shape)
+        scale = np.fromfile(os.path.join(d, name + "scale.bin"), np.float16).reshape(o_scale.shape)
+        zero = np.fromfile(os.path.join(d, name + "zero.bin"), np.float16).reshape(o_zero.shape)
+        assert np.array_equal(scale.view(np.uint16), o_scale.view(np.uint16)), name
+        assert np.array_equal(zero.astype(np.float32), o_zero.astype(np.float32)), name
+        assert np.array_equal(codes, o_codes), name

@@ -37,7 +37,7 @@ def run_case(w, n_chunks=1, chunk_n=20, n_buf=7, iters=3, check_attn=True):
     rep = pu.compare_components(gc, oc)
     rep.update(pu.compare_decompress(gc, oc))
     if w.rank > 0:
-        rep.update(pu.compare_lowrank_product(gc, oc, 0))
+        rep.update(pu.compare_lowrank_product(gc, oc, 0))        # asserts the bound on A B^T
     for j in range(n_chunks):
         Kc = gw.make_keys(w, chunk_n, 1 + j, DEV)
         Vc = gw.make_values(w, chunk_n, 1 + j, DEV)
@@ -193,3 +193,73 @@ def test_repeatable_bitwise():
         outs.append((Kh.clone(), Vh.clone(), o.clone()))
     for a, b in zip(outs[0], outs[1]):
         assert torch.equal(a, b)
+
+
+def test_rank_deficient_residual():
+    """A residual of exact rank 1 under a rank-4 solver: codes on a lossless grid plus u v^T small
+    enough to leave every code, scale and zero-point alone, so R = u v^T exactly.  Both sides must
+    drop the three dependent directions (QR of B, then of A) and return A B^T = R."""
+    n = 300
+    w = small_workload(1, 2, 2, n, 2, 64, 0, 4, 71)
+    gc, oc = pu.make_pair(1, 2, 2, 2, 64, 0, 20, n, 1, 4)
+    g = torch.Generator(device="cpu").manual_seed(8)
+    step = 2.0 ** -10
+    k = torch.randint(1, 3, (1, 2, n, 128), generator=g)     # inner codes only, so the perturbed values stay inside the range
+    k[:, :, 0::64, :] = 0                                    # every Key group holds its end points ...
+    k[:, :, 1::64, :] = 3
+    u = torch.randint(-7, 8, (1, 2, n, 1), generator=g).float()   # (3 x, 5 x, 7 x: products that round in fp32)
+    u[:, :, 0::64] = 0                                       # ... in rows the perturbation leaves alone
+    u[:, :, 1::64] = 0
+    vk = torch.randint(1, 3, (1, 2, 1, 128), generator=g).float() * step
+    K = (-1.0 + 0.5 * k.float() + u * vk).to(torch.float16)
+    v = torch.randint(1, 3, (1, 2, n, 128), generator=g)
+    v[..., 0::64] = 0                                        # Value groups run along the channels
+    v[..., 1::64] = 3
+    uv = torch.randint(-7, 8, (1, 2, n, 1), generator=g).float()
+    vv = torch.randint(1, 3, (1, 2, 1, 128), generator=g).float() * step
+    vv[..., 0::64] = 0
+    vv[..., 1::64] = 0
+    V = (-1.0 + 0.5 * v.float() + uv * vv).to(torch.float16)
+    assert torch.equal(K.float(), -1.0 + 0.5 * k.float() + u * vk)      # the construction is exact in fp16
+    ib = gw.make_init_B(w, 4, 0, DEV)
+    pu.compress_both(gc, oc, K.to(DEV), V.to(DEV), 4, 3, ib)
+    rep = pu.compare_components(gc, oc)
+    # the oracle's factors reproduce the rank-1 residual, with three zero columns
+    Lo = np.einsum("bhnr,bhdr->bhnd", oc.K[0].A.astype(np.float64), oc.K[0].Bf.astype(np.float64))
+    assert np.abs(Lo - (u * vk).numpy()).max() <= 2e-3 * step * 14
+    assert (np.abs(oc.K[0].A.astype(np.float64)).sum(axis=2) > 0).sum(axis=-1).max() == 1
+    rep.update(pu.compare_lowrank_product(gc, oc, 0))
+    rep.update(pu.compare_decompress(gc, oc))
+    A, Bf = gc.export_lowrank(0, 0)
+    assert torch.isfinite(A.float()).all() and torch.isfinite(Bf.float()).all()
+    rep.update(pu.compare_attention(gc, oc, gw.make_queries(w, 0, DEV)))
+    say("  ->", rep)
+
+
+def test_seeded_start_matrix():
+    """init_B = NULL: the library draws the start matrices of Algorithm 2 from the seed.  The stored
+    factors must equal, bit for bit, those of a call that is handed the same numbers as an array
+    (the generator's integer formula, mirrored in gear_workloads), and match the oracle run on it."""
+    w = small_workload(B=2, H_kv=3, H_q=3, n=400, bits=2, g=64, ppm=20000, rank=4, seed=91)
+    K = gw.make_keys(w, w.n, 0, DEV)
+    V = gw.make_values(w, w.n, 0, DEV)
+    Kc = gw.make_keys(w, 20, 1, DEV)
+    Vc = gw.make_values(w, 20, 1, DEV)
+    seed, seed_c = 0x1234567890ABCDEF, 7
+    ib = gw.make_init_B_hashed(seed, w.B, w.H_kv, 4, DEV)
+    ibc = gw.make_init_B_hashed(seed_c, w.B, w.H_kv, 3, DEV)
+    assert float(ib.min()) >= -1.0 and float(ib.max()) < 1.0 and abs(float(ib.mean())) < 0.02
+    gc, oc = pu.make_pair(w.B, w.H_kv, w.H_q, 2, 64, 20000, 20, w.n, 1, 4)
+    pu.compress_both(gc, oc, K, V, 4, 3, ib)
+    pu.compress_both(gc, oc, Kc, Vc, 3, 3, ibc)
+    gs, _ = pu.make_pair(w.B, w.H_kv, w.H_q, 2, 64, 20000, 20, w.n, 1, 4)
+    gs.compress(K, V, 4, 3, None, seed=seed)               # prefill: the kernel-per-step path
+    gs.compress(Kc, Vc, 3, 3, None, seed=seed_c)           # chunk: the one-block path
+    for which in (0, 1):
+        for seg in (0, 1):
+            A1, B1 = gc.export_lowrank(which, seg)
+            A2, B2 = gs.export_lowrank(which, seg)
+            assert torch.equal(A1, A2) and torch.equal(B1, B2), (which, seg)
+    rep = pu.compare_lowrank_product(gc, oc, 0)
+    rep.update(pu.compare_decompress(gc, oc))
+    say("  ->", rep)
