@@ -2,7 +2,8 @@
 """Benchmark of the GEAR hot path on one MI355X.
 
 One "step" is one pass of the whole path over one batch of synthetic KV of the
-configured LLaMA-2-7B layer shape (BASELINE config 1 by default):
+headline workload (by default config 4, the Llama-3-8B GQA layer shape: the largest
+configuration that one GPU holds):
   1. gear_compress of the n-token prefill (Filter, Quant, power iteration),
   2. n_b decode iterations: the new token's k/v row is already in its buffer
      slot (the push is the caller writing that row), then gear_decode_attn over
@@ -12,6 +13,10 @@ Decode iterations read cache replicas that hold the prefill segment plus
 --chunks appended chunks (default: half of the flushes of the config's decode
 run, i.e. the cache as it is in the middle of that run) and rotate over three
 replicas, so their reads come from HBM and not from the 256 MB Infinity Cache.
+
+After the timed steps of the headline workload every other configuration gets a
+short run of the same measurement (`per_config`), and the CPU oracle is timed on a
+sample of the headline workload (`cpu_baseline`).
 
 Prints ONE JSON line.  value = KV compress GB/s (fp16 K+V input bytes of the
 prefill / time of its gear_compress call); the decode-attention rate is given
@@ -46,36 +51,20 @@ def compressed_bytes(w, n, rank):
     return codes + sz + lowrank + sparse
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=6)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=1, help="index into gear_workloads.CONFIGS")
-    ap.add_argument("--chunks", type=int, default=-1, help="appended chunks in the caches the decode steps read")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="kept for the profiling commands: the plain streaming kernel over 1 GiB (reads 1 GiB and "
-                         "writes 1 GiB: out = in + 1 on bytes) that the rocprofv3 FETCH_SIZE / WRITE_SIZE readings "
-                         "are scaled by now runs after every timed region")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path would shard over the batch with no "
-              "exchange between GPUs); --gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
+# SURVEY-table bars: bytes the method itself must move -> time at 60 % (compress) / 70 % (decode) of 8 TB/s
+def bar_times(w, in_bytes, comp_bytes, dec_bytes):
+    return {"compress_us_at_60pct": round((in_bytes + comp_bytes) / (0.6 * HBM_PEAK_GBPS * 1e9) * 1e6, 1),
+            "decode_us_at_70pct": round(dec_bytes / (0.7 * HBM_PEAK_GBPS * 1e9) * 1e6, 1)}
 
+
+def measure(w, steps, warmup, chunks, dev):
+    """Runs `warmup` untimed and `steps` timed passes of the whole hot path on workload w.
+    Returns the per-call averages (HIP events on the caller's stream) and the wall time."""
     import torch
     import gear_workloads as gw
     from paper_2403_05527_amd import binding as gb
-
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    gb.load_library()
-    dev = "cuda:0"
-    w = gw.CONFIGS[args.config]
     NREP = 3
-    pre_chunks = args.chunks if args.chunks >= 0 else (w.steps // w.n_b) // 2
+    pre_chunks = chunks if chunks >= 0 else (w.steps // w.n_b) // 2
     max_chunks = max(pre_chunks, 1)
     cfg = gb.make_config(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, w.n_b, w.n, max_chunks,
                          max(w.rank, w.rank_chunk))
@@ -100,9 +89,7 @@ def main():
     chunk_bytes = compressed_bytes(w, w.n_b, w.rank_chunk)
     row_bytes = 2 * w.B * w.H_kv * w.d_h * 2          # one k row + one v row per slab
     qo_bytes = 2 * w.B * w.H_q * w.d_h * 2
-
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    t_comp, t_dec, t_chunk, dec_bytes = [], [], [], []
 
     def step(i, record):
         e0, e1 = ev(), ev()
@@ -124,66 +111,128 @@ def main():
         c1.record()
         return (e0, e1, devs, c0, c1) if record else None
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i, False)
     torch.cuda.synchronize()
     recs = []
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        recs.append(step(args.warmup + i, True))
+    for i in range(steps):
+        recs.append(step(warmup + i, True))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    t_comp, t_dec, t_chunk, dec_bytes = [], [], [], []
     for (e0, e1, devs, c0, c1) in recs:
         t_comp.append(e0.elapsed_time(e1) * 1e-3)
         t_chunk.append(c0.elapsed_time(c1) * 1e-3)
         for (a, b, n_chunks, n_buf) in devs:
             t_dec.append(a.elapsed_time(b) * 1e-3)
             dec_bytes.append(comp_bytes + n_chunks * chunk_bytes + n_buf * row_bytes + qo_bytes)
+    mean = lambda x: sum(x) / len(x)
+    arena_bytes = pre.arena_bytes
+    res = {"w": w, "wall": wall, "tc": mean(t_comp), "td": mean(t_dec), "tchunk": mean(t_chunk),
+           "dec_bytes": mean(dec_bytes), "in_bytes": in_bytes, "comp_bytes": comp_bytes, "pre_chunks": pre_chunks,
+           "arena_bytes": arena_bytes, "sample": (K[:16].cpu(), V[:16].cpu(), ib[:, :16].cpu(), qs[0][:16].cpu())}
+    del pre, reps, K, V, Kb, Vb, qs
+    torch.cuda.empty_cache()
+    return res
 
-    # HBM bytes per decode launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a streaming kernel of
-    # known size); measured offline for the default workload only, see the file for the commands
-    traffic = None
-    tf = os.path.join(ROOT, "profiles", "decode_split_c1_hbm_traffic.txt")
-    if args.config == 1 and args.chunks < 0 and os.path.exists(tf):
+
+def summarize(m):
+    w = m["w"]
+    comp_algo_gbps = (m["in_bytes"] + m["comp_bytes"]) / m["tc"] / 1e9
+    dec_algo_gbps = m["dec_bytes"] / m["td"] / 1e9
+    d = {"workload": w.name, "compress_ms": round(m["tc"] * 1e3, 4), "compress_input_gbps": round(m["in_bytes"] / m["tc"] / 1e9, 1),
+         "compress_frac": round(comp_algo_gbps / HBM_PEAK_GBPS, 4),
+         "chunk_compress_ms": round(m["tchunk"] * 1e3, 4),
+         "decode_attn_us": round(m["td"] * 1e6, 2), "decode_attn_tokens_per_s": round(w.B / m["td"], 1),
+         "decode_frac": round(dec_algo_gbps / HBM_PEAK_GBPS, 4),
+         "decode_loop_tokens_per_s": round(w.B * w.n_b / (w.n_b * m["td"] + m["tchunk"]), 1),
+         "compressed_fraction_algorithmic": round(m["comp_bytes"] / m["in_bytes"], 4),
+         "arena_fraction": round(m["arena_bytes"] / m["in_bytes"], 4)}
+    d.update(bar_times(w, m["in_bytes"], m["comp_bytes"], m["dec_bytes"]))
+    return d
+
+
+def read_traffic(name):
+    """HBM bytes per decode launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a streaming kernel of
+    known size), measured offline per workload; the file gives the commands."""
+    tf = os.path.join(ROOT, "profiles", "decode_split_%s_hbm_traffic.txt" % name)
+    if os.path.exists(tf):
         for line in open(tf):
             if line.startswith("traffic_bytes_per_launch:"):
-                traffic = int(line.split(":")[1])
-    mean = lambda x: sum(x) / len(x)
-    tc, td = mean(t_comp), mean(t_dec)
-    comp_gbps = in_bytes / tc / 1e9
-    comp_algo_gbps = (in_bytes + comp_bytes) / tc / 1e9
-    dec_algo_gbps = mean(dec_bytes) / td / 1e9
+                return int(line.split(":")[1])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="index into gear_workloads.CONFIGS of the headline workload "
+                    "(default: config 4, the largest one-GPU configuration)")
+    ap.add_argument("--chunks", type=int, default=-1, help="appended chunks in the caches the decode steps read")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the short runs of the other configurations")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="kept for the profiling commands: the plain streaming kernel over 1 GiB (reads 1 GiB and "
+                         "writes 1 GiB: out = in + 1 on bytes) that the rocprofv3 FETCH_SIZE / WRITE_SIZE readings "
+                         "are scaled by runs after every timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path would shard over the batch with no "
+              "exchange between GPUs); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import gear_workloads as gw
+    from paper_2403_05527_amd import binding as gb
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    gb.load_library()
+    dev = "cuda:0"
+    w = gw.CONFIGS[args.config]
+    m = measure(w, args.steps, args.warmup, args.chunks, dev)
+    head = summarize(m)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    dec_algo_gbps = m["dec_bytes"] / m["td"] / 1e9
+    comp_algo_gbps = (m["in_bytes"] + m["comp_bytes"]) / m["tc"] / 1e9
     res = {
         "metric": "KV compress GB/s + compressed-KV decode attn tokens/s; % of HBM roofline",
-        "value": round(comp_gbps, 2),
+        "value": round(m["in_bytes"] / m["tc"] / 1e9, 2),
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(wall / args.steps * 1e3, 4),
+        "ms_per_step": round(m["wall"] / args.steps * 1e3, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H_kv": w.H_kv, "H_q": w.H_q, "d_h": w.d_h, "n": w.n,
                    "bits": w.bits, "group": w.group, "outlier_ppm": w.outlier_ppm, "rank": w.rank,
                    "rank_chunk": w.rank_chunk, "n_b": w.n_b, "iters": w.iters,
-                   "chunks_in_decoded_cache": pre_chunks},
-        "compress_ms": round(tc * 1e3, 4),
-        "chunk_compress_ms": round(mean(t_chunk) * 1e3, 4),
-        "decode_attn_us": round(td * 1e6, 2),
-        "decode_attn_tokens_per_s": round(w.B / td, 1),
+                   "chunks_in_decoded_cache": m["pre_chunks"]},
+        "compress_ms": head["compress_ms"],
+        "chunk_compress_ms": head["chunk_compress_ms"],
+        "decode_attn_us": head["decode_attn_us"],
+        "decode_attn_tokens_per_s": head["decode_attn_tokens_per_s"],
         # the streaming loop: n_b decode steps and the flush of the full buffer into a chunk
-        "decode_loop_tokens_per_s": round(w.B * w.n_b / (w.n_b * td + mean(t_chunk)), 1),
+        "decode_loop_tokens_per_s": head["decode_loop_tokens_per_s"],
+        "compressed_fraction_algorithmic": head["compressed_fraction_algorithmic"],
+        "arena_fraction": head["arena_fraction"],
         "roofline": {"bound": "hbm", "kernel": "gear_decode_attn (decode_split_kernel + combine)",
                      "achieved": round(dec_algo_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(dec_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "frac": round(dec_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": read_traffic(w.name) if args.chunks < 0 else None,
                      "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE)",
-                     "algorithmic_bytes_per_launch": int(mean(dec_bytes))},
+                     "algorithmic_bytes_per_launch": int(m["dec_bytes"])},
         "roofline_compress": {"bound": "hbm", "kernel": "gear_compress (all kernels of the call)",
                               "achieved": round(comp_algo_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                              "frac": round(comp_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+                              "frac": round(comp_algo_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                              "algorithmic_bytes_per_call": int(m["in_bytes"] + m["comp_bytes"])},
     }
     # a plain streaming kernel on the same box (out = in + 1 over 1 GiB of bytes: 1 GiB read + 1 GiB written),
     # the practical ceiling next to the nominal peak; --calibrate-copy also uses it to scale the profiler's counters
@@ -199,36 +248,69 @@ def main():
     torch.cuda.synchronize()
     res["roofline"]["measured_stream_gbps"] = round(5 * 2 * (1 << 30) / (s0.elapsed_time(s1) * 1e-3) / 1e9, 1)
     del src, dst
+    torch.cuda.empty_cache()
+    sample = m.pop("sample")
+    if not args.no_per_config:
+        # the other configurations: a short run each (1 warm-up + 3 passes), same measurement
+        per = []
+        for i, wi in enumerate(gw.CONFIGS):
+            if i == 0:
+                continue                              # config 0 is the small parity case (launch-latency bound)
+            if i == args.config:
+                per.append(head)
+                continue
+            mi = measure(wi, 3, 1, -1, dev)
+            mi.pop("sample")
+            per.append(summarize(mi))
+        res["per_config"] = per
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w, K, V, ib, qs[0])
+        res["cpu_baseline"] = cpu_baseline(w, *sample)
     print(json.dumps(res), flush=True)
 
 
-def cpu_baseline(w, K, V, ib, q):
-    """The oracle as it stands, timed on the host cores on ONE batch element
-    (all heads) of the same workload: one compress + two decode reads."""
-    import numpy as np
+def _oracle_pass(args):
+    """One batch element through the oracle: one compress, then `reads` decode reads.  Returns the two times."""
+    w, Kh, Vh, ibh, qh, reads = args
     from threadpoolctl import threadpool_limits
     from oracle import gear_oracle as go
-    Kh = K[:1].cpu().numpy()
-    Vh = V[:1].cpu().numpy()
-    ibh = ib[:, :1].cpu().numpy()
-    qh = q[:1].cpu().numpy()
-    cores = len(os.sched_getaffinity(0))
     with threadpool_limits(limits=1):
         oc = go.OracleCache(1, w.H_kv, w.H_q, w.d_h, w.bits, w.group, w.outlier_ppm)
         t0 = time.perf_counter()
         oc.compress(Kh, Vh, w.rank, w.iters, ibh)
         tc = time.perf_counter() - t0
         t0 = time.perf_counter()
-        for _ in range(2):
+        for _ in range(reads):
             oc.decode_attn(qh)
-        td = (time.perf_counter() - t0) / 2
-    return {"value": round(2 * Kh.nbytes / tc / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        td = (time.perf_counter() - t0) / max(reads, 1)
+    return tc, td
+
+
+def cpu_baseline(w, K, V, ib, q):
+    """The oracle as it stands, timed on the host cores on a sample of whole batch elements of the same
+    workload (all heads; the Value Filter couples them): one element on one thread, then one element per
+    core on all cores at once (numpy releases the interpreter lock inside its array operations; every
+    worker is held to one thread of the numeric libraries)."""
+    from concurrent.futures import ThreadPoolExecutor
+    cores = len(os.sched_getaffinity(0))
+    nb = min(cores, K.shape[0])
+    items = [(w, K[b:b + 1].numpy(), V[b:b + 1].numpy(), ib[:, b:b + 1].numpy(), q[b:b + 1].numpy(), 2) for b in range(nb)]
+    tc1, td1 = _oracle_pass(items[0])
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=nb) as ex:
+        times = list(ex.map(_oracle_pass, items))
+    wall = time.perf_counter() - t0
+    el_bytes = 2 * K[:1].numel() * 2
+    tc_all = sum(t[0] for t in times) / nb            # mean time of a compress while all workers run
+    td_all = sum(t[1] for t in times) / nb
+    return {"value": round(nb * el_bytes / tc_all / 1e9, 5), "unit": "GB/s", "cores": nb, "kind": "oracle",
             "host_cores_available": cores,
-            "decode_attn_tokens_per_s": round(1.0 / td, 3),
-            "sample": "1 of %d batch elements (all %d heads, n=%d): one compress (%.1f s) + 2 decode reads "
-                      "(%.2f s each), numpy oracle pinned to 1 thread" % (w.B, w.H_kv, w.n, tc, td)}
+            "decode_attn_tokens_per_s": round(nb / td_all, 3),
+            "single_thread": {"value": round(el_bytes / tc1 / 1e9, 5), "unit": "GB/s", "cores": 1,
+                              "decode_attn_tokens_per_s": round(1.0 / td1, 3)},
+            "sample": "%d of %d batch elements (all %d KV heads, n=%d), one per worker thread, each one compress + 2 decode "
+                      "reads, numpy oracle with its numeric libraries held to 1 thread per worker: %.1f s wall; before "
+                      "that one element alone on one thread: compress %.1f s, decode read %.2f s"
+                      % (nb, w.B, w.H_kv, w.n, wall, tc1, td1)}
 
 
 if __name__ == "__main__":
