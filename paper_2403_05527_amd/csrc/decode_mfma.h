@@ -135,6 +135,12 @@ __device__ __forceinline__ void val_slot(int t, int& kg, int& idx, int& lg) {
 // LDS layout of one MFMA block (byte offsets into dynamic shared memory)
 // ---------------------------------------------------------------------------
 constexpr int WTOK = 128;  // tokens per wave
+// Row strides of the per-wave LDS arrays, padded by 8 entries: rows (query heads, operand columns)
+// that are read or written by different lanes of one instruction then start in different banks.
+constexpr int SCP = WTOK + 8;   // score / probability plane of one query head (floats)
+constexpr int OSP = D + 8;      // output plane of one query head (floats)
+constexpr int KOP = D + 8;      // Key-side operand column (fp16)
+__host__ __device__ constexpr int vop(int tb) { return tb + 8; }   // Value-side operand row of a tb-token code block (fp16)
 struct MfmaLayout {
   int q, misc;                                 // shared by the four waves
   int bf, bf_v0, bf_cw, bf_vc;                 // B factors: one (K, V) pair for the block, or one per wave (chunks)
@@ -177,15 +183,15 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk0, int 
   }
   L.wave0 = o;
   int w = 0;
-  L.sc = w; w += GQ * WTOK * 4;
+  L.sc = w; w += GQ * SCP * 4;
   L.szk = w; w += (WTOK >> lg) * D * 4;
   L.szv = w; w += WTOK * NG * 4;
   L.ak = w; w += mfma_rows_in_lds<GQ>(odd_rank) ? up16i(WTOK * rk * 2) : 0;
   L.av = w; w += mfma_rows_in_lds<GQ>(odd_rank) ? up16i(WTOK * rv * 2) : 0;
-  L.osp = w; w += GQ * D * 4;
-  int oh = 2 * GQ * D;
-  if (NG * 2 * GQ * TB > oh) oh = NG * 2 * GQ * TB;
+  int oh = 2 * GQ * KOP;
+  if (NG * 2 * GQ * vop(TB) > oh) oh = NG * 2 * GQ * vop(TB);
   L.opnd = w; w += oh * 2;
+  L.osp = L.opnd;   // the output plane (GQ * OSP floats <= the operand area) is written after the last operand was read
   L.qb = w; w += GQ * 8 * 4;
   L.wave_stride = up16i(w);
   L.total = L.wave0 + 4 * L.wave_stride;
@@ -216,10 +222,10 @@ __device__ __forceinline__ void lowrank_key_rows(const uint16_t* Sak, const uint
       else lds_row_f16<R>(Sak + row * R, a);
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
-        float s = Ssc[hq * WTOK + row];
+        float s = Ssc[hq * SCP + row];
 #pragma unroll
         for (int r = 0; r < R; ++r) s += SqB[hq * 8 + r] * a[r];
-        Ssc[hq * WTOK + row] = s;
+        Ssc[hq * SCP + row] = s;
       }
     }
   }
@@ -242,7 +248,7 @@ __device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const ui
       else lds_row_f16<R>(Sav + row * R, a);
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
-        const float p = Ssc[hq * WTOK + row];
+        const float p = Ssc[hq * SCP + row];
 #pragma unroll
         for (int r = 0; r < R; ++r) part[hq][r] += p * a[r];
       }
@@ -308,7 +314,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   uint16_t* Sav = reinterpret_cast<uint16_t*>(wbase + L.av);
   uint16_t* Sbfk = reinterpret_cast<uint16_t*>(smem + L.bf + (shared_b ? 0 : wave * L.bf_cw));   // [128][rk]
   uint16_t* Sbfv = reinterpret_cast<uint16_t*>(smem + L.bf + (shared_b ? L.bf_v0 : wave * L.bf_cw + L.bf_vc));
-  float* Sosp = reinterpret_cast<float*>(wbase + L.osp);            // [GQ][128] this wave's output plane
+  float* Sosp = reinterpret_cast<float*>(wbase + L.osp);            // [GQ][128] this wave's output plane (shares the operand area)
   _Float16* opnd = reinterpret_cast<_Float16*>(wbase + L.opnd);
   float* SqB = reinterpret_cast<float*>(wbase + L.qb);              // [GQ][8] q^T B_K
   const float scale = 0.08838834764831845f;  // 1/sqrt(128)
@@ -434,7 +440,6 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     if (j < n4_bk) reinterpret_cast<uint4*>(Sbfk)[j] = g_bk[j];
     if (j < n4_bv) reinterpret_cast<uint4*>(Sbfv)[j] = g_bv[j];
   }
-  for (int i = lane; i < GQ * D; i += 64) Sosp[i] = 0.0f;
   if (lane < GQ * 8) (&M.wv[wave][0][0])[lane] = 0.0f;
   if (lane < GQ * 4) (&M.pm[wave][0][0])[lane] = 0.0f;
   block_lds_sync();   // q and the B factors are visible to all waves; from here on waves run independently
@@ -497,8 +502,8 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
         const float w = qv * delta * os;
         const _Float16 hi = (_Float16)w;
         const _Float16 lo = (_Float16)(w - (float)hi);
-        dst[(2 * hq) * D] = hi;
-        dst[(2 * hq + 1) * D] = lo;
+        dst[(2 * hq) * KOP] = hi;
+        dst[(2 * hq + 1) * KOP] = lo;
         kb[hq] += qv * mn;
       }
     }
@@ -509,7 +514,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
       uint4 raw = make_uint4(0, 0, 0, 0);
-      if (n16 < 2 * GQ) raw = *reinterpret_cast<const uint4*>(opnd + n16 * D + kg * 32 + jb * 8);
+      if (n16 < 2 * GQ) raw = *reinterpret_cast<const uint4*>(opnd + n16 * KOP + kg * 32 + jb * 8);
       bop[jb] = __builtin_bit_cast(half8, raw);
     }
     // lane group kg receives columns 4 kg .. 4 kg + 3: both parts of query heads 2 kg and 2 kg + 1
@@ -541,8 +546,8 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           }
         }
         // D[col 4*kg + i][token n16]: the hi and lo columns of a query head sit in one lane
-        if (hq0 < GQ) Ssc[hq0 * WTOK + 16 * mt + n16] = (acc[0] + acc[1]) * MFMA_OUT_SCALE + kb0;
-        if (hq1 < GQ) Ssc[hq1 * WTOK + 16 * mt + n16] = (acc[2] + acc[3]) * MFMA_OUT_SCALE + kb1;
+        if (hq0 < GQ) Ssc[hq0 * SCP + 16 * mt + n16] = (acc[0] + acc[1]) * MFMA_OUT_SCALE + kb0;
+        if (hq1 < GQ) Ssc[hq1 * SCP + 16 * mt + n16] = (acc[2] + acc[3]) * MFMA_OUT_SCALE + kb1;
       }
     }
     wave_lds_sync();
@@ -572,10 +577,10 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       for (int hq = 0; hq < GQ; ++hq) {
         const float4 b0 = *reinterpret_cast<const float4*>(&SqB[hq * 8]);       // entries r >= rk are unused (a = 0)
         const float4 b1 = *reinterpret_cast<const float4*>(&SqB[hq * 8 + 4]);
-        float s = Ssc[hq * WTOK + row];
+        float s = Ssc[hq * SCP + row];
         s += b0.x * a[0] + b0.y * a[1] + b0.z * a[2] + b0.w * a[3];
         if (rk > 4) s += b1.x * a[4] + b1.y * a[5] + b1.z * a[6] + b1.w * a[7];
-        Ssc[hq * WTOK + row] = s;
+        Ssc[hq * SCP + row] = s;
       }
     }
     wave_lds_sync();
@@ -601,14 +606,14 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
         for (int hq = 0; hq < GQ; ++hq) a2[hq] += Sq[hq * D + c] * v;
       }
 #pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) Ssc[hq * WTOK + row] += a2[hq];
+      for (int hq = 0; hq < GQ; ++hq) Ssc[hq * SCP + row] += a2[hq];
     }
     wave_lds_sync();
     auto add_k = [&](uint32_t en) {
       const int row = (en & 0xFFFFu) >> 7, c = en & 127u;
       const float v = h2f(en >> 16);
 #pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Ssc[hq * WTOK + row], Sq[hq * D + c] * v);
+      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Ssc[hq * SCP + row], Sq[hq * D + c] * v);
     };
 #pragma unroll
     for (int i = 0; i < SPR; ++i)
@@ -621,17 +626,6 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     wave_lds_sync();
   }
 
-  // fixed outlier slots of the Value channels lane and lane + 64 in the wave's two tiles
-  uint2 ellv[2][2];
-#pragma unroll
-  for (int rep = 0; rep < 2; ++rep)
-#pragma unroll
-    for (int ti = 0; ti < 2; ++ti) {
-      ellv[ti][rep] = make_uint2(0, 0);
-      if (dm.ppm > 0 && ti * TILE < nw)
-        ellv[ti][rep] = *reinterpret_cast<const uint2*>(
-            vs.ell + (((size_t)slab * vs.ntile_cap + tw0 / TILE + ti) * D + lane + 64 * rep) * ELL_V);
-    }
   uint4 avr[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};   // rows lane, lane + 64 of A_V when they are not staged
   if (!rows_lds) {
     const GEAR_BUF_T av = GEAR_BUF_MAKE(g_av, nw * rv * 2);
@@ -658,13 +652,13 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   {
 #pragma unroll
     for (int hq = 0; hq < GQ; ++hq) {
-      const float s0 = lane < nw ? Ssc[hq * WTOK + lane] * scale : -INFINITY;
-      const float s1 = lane + 64 < nw ? Ssc[hq * WTOK + lane + 64] * scale : -INFINITY;
+      const float s0 = lane < nw ? Ssc[hq * SCP + lane] * scale : -INFINITY;
+      const float s1 = lane + 64 < nw ? Ssc[hq * SCP + lane + 64] * scale : -INFINITY;
       const float m = wave_max(fmaxf(s0, s1));
       const float p0 = lane < nw ? __expf(s0 - m) : 0.0f;
       const float p1 = lane + 64 < nw ? __expf(s1 - m) : 0.0f;
-      Ssc[hq * WTOK + lane] = p0;          // rows >= nw hold p = 0
-      Ssc[hq * WTOK + lane + 64] = p1;
+      Ssc[hq * SCP + lane] = p0;          // rows >= nw hold p = 0
+      Ssc[hq * SCP + lane + 64] = p1;
       const float l = wave_sum(p0 + p1);
       if (lane == 0) {
         M.rv[wave] = rv;
@@ -692,7 +686,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     int skg, idx, lg;
     val_slot<BITS>(tl & (TB - 1), skg, idx, lg);
     vrow[k] = tl < TB ? tl : -1;
-    vslot[k] = Gl * 2 * GQ * TB + skg * (TB / 4) + idx;
+    vslot[k] = Gl * 2 * GQ * vop(TB) + skg * (TB / 4) + idx;
     vscale[k] = opscale(lg);
   }
   float pmr[GQ];
@@ -712,12 +706,12 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           _Float16* dst = opnd + vslot[k];
 #pragma unroll
           for (int hq = 0; hq < GQ; ++hq) {
-            const float pv = Ssc[hq * WTOK + row];
+            const float pv = Ssc[hq * SCP + row];
             const float w = pv * ds;
             const _Float16 hi = (_Float16)w;
             const _Float16 lo = (_Float16)(w - (float)hi);
-            dst[(2 * hq) * TB] = hi;
-            dst[(2 * hq + 1) * TB] = lo;
+            dst[(2 * hq) * vop(TB)] = hi;
+            dst[(2 * hq + 1) * vop(TB)] = lo;
             pmr[hq] += pv * mn;
           }
         }
@@ -726,7 +720,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       for (int G = 0; G < NG; ++G) {
         half8 pa0 = __builtin_bit_cast(half8, make_uint4(0, 0, 0, 0)), pa1 = pa0;
         if (n16 < 2 * GQ) {
-          const _Float16* src = opnd + (size_t)(G * 2 * GQ + n16) * TB + kg * (TB / 4);
+          const _Float16* src = opnd + (size_t)(G * 2 * GQ + n16) * vop(TB) + kg * (TB / 4);
           pa0 = __builtin_bit_cast(half8, *reinterpret_cast<const uint4*>(src));
           if (BITS == 2) pa1 = __builtin_bit_cast(half8, *reinterpret_cast<const uint4*>(src + 8));
         }
@@ -749,6 +743,18 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       wave_lds_sync();
     }
   }
+  // fixed outlier slots of the Value channels lane and lane + 64 in the wave's two tiles (requested here: the
+  // reductions and the down-projection below cover their latency, and the registers were needed until now)
+  uint2 ellv[2][2];
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep)
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti) {
+      ellv[ti][rep] = make_uint2(0, 0);
+      if (dm.ppm > 0 && ti * TILE < nw)
+        ellv[ti][rep] = *reinterpret_cast<const uint2*>(
+            vs.ell + (((size_t)slab * vs.ntile_cap + tw0 / TILE + ti) * D + lane + 64 * rep) * ELL_V);
+    }
   // sum_t p_t zero_V[t][G]: lanes with equal lane % NG hold group G's terms; the four rows
   // of 16 lanes add their sums into pm (zero on entry; groups G >= NG stay 0)
 #pragma unroll
@@ -765,8 +771,8 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     const int hq0 = 2 * kg, hq1 = 2 * kg + 1;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      if (hq0 < GQ) Sosp[hq0 * D + 16 * j + n16] = (acc[j][0] + acc[j][1]) * MFMA_OUT_SCALE;
-      if (hq1 < GQ) Sosp[hq1 * D + 16 * j + n16] = (acc[j][2] + acc[j][3]) * MFMA_OUT_SCALE;
+      if (hq0 < GQ) Sosp[hq0 * OSP + 16 * j + n16] = (acc[j][0] + acc[j][1]) * MFMA_OUT_SCALE;
+      if (hq1 < GQ) Sosp[hq1 * OSP + 16 * j + n16] = (acc[j][2] + acc[j][3]) * MFMA_OUT_SCALE;
     }
   }
 
@@ -796,7 +802,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           if (r < rv) {
             const float a = h2f(Sav[row * rv + r]);
 #pragma unroll
-            for (int hq = 0; hq < GQ; ++hq) part[hq][r] += Ssc[hq * WTOK + row] * a;
+            for (int hq = 0; hq < GQ; ++hq) part[hq][r] += Ssc[hq * SCP + row] * a;
           }
         }
       }
@@ -829,18 +835,18 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           const float v = h2f(es[i] >> 16);
           const int row = ti * TILE + (int)(es[i] & 63u);
 #pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * WTOK + row] * v;
+          for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * SCP + row] * v;
         }
       }
 #pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) Sosp[hq * D + c] += a2[hq];
+      for (int hq = 0; hq < GQ; ++hq) Sosp[hq * OSP + c] += a2[hq];
     }
     wave_lds_sync();
     auto add_v = [&](uint32_t en) {
       const int row = (en & 0xFFFFu) >> 7, c = en & 127u;
       const float v = h2f(en >> 16);
 #pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Sosp[hq * D + c], Ssc[hq * WTOK + row] * v);
+      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Sosp[hq * OSP + c], Ssc[hq * SCP + row] * v);
     };
 #pragma unroll
     for (int i = 0; i < SPR; ++i)
@@ -867,7 +873,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       if (mw == -INFINITY) continue;
       const float f = __expf(mw - Mx);
       const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
-      float ow = plane[hq * D + c] + M.pm[w][hq][G];
+      float ow = plane[hq * OSP + c] + M.pm[w][hq][G];
       const uint16_t* bfw = reinterpret_cast<const uint16_t*>(smem + L.bf + (shared_b ? L.bf_v0 : w * L.bf_cw + L.bf_vc));
       const int rvw = GEAR_WAVE_UNIFORM(M.rv[w]);
       const float* wvw = &M.wv[w][hq][0];
