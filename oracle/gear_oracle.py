@@ -18,7 +18,9 @@ arithmetic).  Everything that is not an integer decision (residual, power
 iteration, reconstruction, attention) is computed in fp64 from the *stored*
 fp16 quantities.
 
-Parity pins (tests/test_oracle_*.py): Filter vs brute-force sort; Quant vs the
+Parity pins (tests/test_oracle_*.py): Filter vs brute-force sort (also the
+per-head Value variant); the per-vector grouping vs a hand-computed example and
+Table 1's KCVT KV-size row; Quant vs the
 closed-form error bound of Eq. 2, end-point codes, idempotence and a lossless
 grid; pack vs hand-computed words; SVDSolver vs a full LAPACK SVD (Eckart-Young
 bound, exactness for rank <= r, orthonormality); composite monotonicity;
@@ -78,10 +80,16 @@ def filter_keys(K16: np.ndarray, outlier_ppm: int) -> np.ndarray:
     return np.ascontiguousarray(m)
 
 
-def filter_values(V16: np.ndarray, outlier_ppm: int) -> np.ndarray:
+def filter_values(V16: np.ndarray, outlier_ppm: int, per_head: bool = False) -> np.ndarray:
     """Eq. 4, X = V: the vector is one token's row over all heads' channels,
-    X in R^{n x d} with d = H*d_H (Sec. 2 notation); index j = h*d_H + c."""
+    X in R^{n x d} with d = H*d_H (Sec. 2 notation); index j = h*d_H + c.
+    per_head: the variant that ranks each head's d_H channels of a token on their
+    own (the vector is X_h[t, :], index c), which keeps every head independent."""
     B, H, n, d = V16.shape
+    if per_head:
+        _, kt, kb = outlier_counts(d, outlier_ppm)
+        top, bot = filter_vectors(V16.reshape(B * H * n, d), kt, kb)
+        return (top | bot).reshape(B, H, n, d)
     _, kt, kb = outlier_counts(H * d, outlier_ppm)
     vec = np.ascontiguousarray(V16.transpose(0, 2, 1, 3)).reshape(B * n, H * d)
     top, bot = filter_vectors(vec, kt, kb)
@@ -152,6 +160,20 @@ def quantize_values(Y16: np.ndarray, bits: int, g: int):
     assert d % g == 0
     c, s, z, ties = quantize(Y16.reshape(B, H, n, d // g, g), bits)
     return c.reshape(B, H, n, d), s, z, ties
+
+
+def quantize_values_whole_token(Y16: np.ndarray, bits: int):
+    """The coarse per-vector grouping of the background section ("KCVT"): all Value
+    entries of one token, over every head, form one group of size d = H * d_H.
+    Returns codes [B,H,n,d_H] and scale/zero fp16 [B,H,n,1] (each head carries its
+    token's pair, so the views have the shape of a per-head grouping with g = d_H)."""
+    B, H, n, d = Y16.shape
+    rows = np.ascontiguousarray(Y16.transpose(0, 2, 1, 3)).reshape(B, n, H * d)
+    c, s, z, ties = quantize(rows, bits)
+    codes = np.ascontiguousarray(c.reshape(B, n, H, d).transpose(0, 2, 1, 3))
+    scale = np.ascontiguousarray(np.broadcast_to(s[:, None, :, None], (B, H, n, 1)))
+    zero = np.ascontiguousarray(np.broadcast_to(z[:, None, :, None], (B, H, n, 1)))
+    return codes, scale, zero, ties
 
 
 def dequant_keys(codes, scale, zero, g):
@@ -252,21 +274,31 @@ class Segment:
 
 def compress_tensor(X16: np.ndarray, kind: str, bits: int, g: int, outlier_ppm: int,
                     rank: int, iters: int, init_B: Optional[np.ndarray],
-                    mask: Optional[np.ndarray] = None) -> Segment:
+                    mask: Optional[np.ndarray] = None, v_per_head: bool = False) -> Segment:
     """Algorithm 1, prefill-phase body for one tensor X in {K, V} (the decoding
     phase runs the same body on the buffered tokens):
       S = Filter_s(X); D-hat = Quant_b(X - S); R = X - D-hat - S;
-      L_h = SVDSolver_r(R_h) for every head (and batch element)."""
+      L_h = SVDSolver_r(R_h) for every head (and batch element).
+    g = 0 selects the coarse per-vector grouping (one group per Key channel of the
+    call, one per Value token over all heads)."""
     assert X16.dtype == F16
     B, H, n, d = X16.shape
     if mask is None:       # a caller that holds only some heads passes the support it computed on all
-        mask = (filter_keys if kind == "K" else filter_values)(X16, outlier_ppm) if outlier_ppm > 0 \
-            else np.zeros(X16.shape, bool)
+        if outlier_ppm <= 0:
+            mask = np.zeros(X16.shape, bool)
+        elif kind == "K":
+            mask = filter_keys(X16, outlier_ppm)
+        else:
+            mask = filter_values(X16, outlier_ppm, v_per_head)
     svals = np.where(mask, X16, F16(0))
     Y16 = np.where(mask, F16(0), X16)                       # X - S, exact
     if kind == "K":
-        codes, scale, zero, ties = quantize_keys(Y16, bits, g)
-        Dh = dequant_keys(codes, scale, zero, g)
+        gk = n if g == 0 else g
+        codes, scale, zero, ties = quantize_keys(Y16, bits, gk)
+        Dh = dequant_keys(codes, scale, zero, gk)
+    elif g == 0:
+        codes, scale, zero, ties = quantize_values_whole_token(Y16, bits)
+        Dh = dequant_values(codes, scale, zero, d)
     else:
         codes, scale, zero, ties = quantize_values(Y16, bits, g)
         Dh = dequant_values(codes, scale, zero, g)
@@ -285,9 +317,9 @@ def compress_tensor(X16: np.ndarray, kind: str, bits: int, g: int, outlier_ppm: 
 def reconstruct_segment(seg: Segment, g: int) -> np.ndarray:
     """X-hat = D-hat + A B^T + S in fp64 from the stored (fp16) components."""
     if seg.kind == "K":
-        Dh = dequant_keys(seg.codes, seg.scale, seg.zero, g)
+        Dh = dequant_keys(seg.codes, seg.scale, seg.zero, seg.n if g == 0 else g)
     else:
-        Dh = dequant_values(seg.codes, seg.scale, seg.zero, g)
+        Dh = dequant_values(seg.codes, seg.scale, seg.zero, seg.codes.shape[3] if g == 0 else g)
     L = np.einsum("bhnr,bhdr->bhnd", seg.A.astype(F64), seg.Bf.astype(F64))
     return Dh + L + seg.svals.astype(F64)
 
@@ -296,9 +328,10 @@ class OracleCache:
     """The compressed KV cache of one layer: a list of segments per tensor, in
     append order (prefill first, then one segment per flushed buffer)."""
 
-    def __init__(self, B, H_kv, H_q, d_h, bits, group, outlier_ppm):
+    def __init__(self, B, H_kv, H_q, d_h, bits, group, outlier_ppm, v_per_head=False):
         self.B, self.H_kv, self.H_q, self.d_h = B, H_kv, H_q, d_h
-        self.bits, self.group, self.outlier_ppm = bits, group, outlier_ppm
+        self.bits, self.group, self.outlier_ppm = bits, group, outlier_ppm      # group 0: per-vector groups
+        self.v_per_head = v_per_head
         self.K: List[Segment] = []
         self.V: List[Segment] = []
 
@@ -313,7 +346,8 @@ class OracleCache:
         iK = init_B[0] if rank > 0 else None
         iV = init_B[1] if rank > 0 else None
         self.K.append(compress_tensor(K16, "K", self.bits, self.group, self.outlier_ppm, rank, iters, iK))
-        self.V.append(compress_tensor(V16, "V", self.bits, self.group, self.outlier_ppm, rank, iters, iV, v_mask))
+        self.V.append(compress_tensor(V16, "V", self.bits, self.group, self.outlier_ppm, rank, iters, iV, v_mask,
+                                      self.v_per_head))
 
     def reconstruct(self):
         """(K-hat, V-hat) fp64 [B,H,n_total,d]."""
@@ -353,19 +387,27 @@ class OracleCache:
         return out.astype(F16)
 
 
-def compressed_bytes(n, d_h, H, bits, g, outlier_ppm, rank, index_bytes=2):
+def compressed_bytes(n, d_h, H, bits, g, outlier_ppm, rank, index_bytes=2, v_per_head=False):
     """Byte accounting of one (b, all heads) compressed segment, K + V, against
     its fp16 size (the "KV size" column of Table 1; scale and zero-point in fp16
-    as in the KV-cache-component appendix).  index_bytes is this build's own
+    as in the KV-cache-component appendix).  g = 0: per-vector groups (one pair
+    per Key channel, one per Value token).  index_bytes is this build's own
     choice (the paper's sparse format is "two index vectors and one value
     vector"); it only affects the sparse share."""
     fp16 = 2 * 2 * n * H * d_h
     codes = 2 * n * H * d_h * bits / 8
-    sz_k = 4 * (-(-n // g)) * H * d_h
-    sz_v = 4 * n * H * d_h // g
+    if g == 0:
+        sz_k = 4 * H * d_h
+        sz_v = 4 * n
+    else:
+        sz_k = 4 * (-(-n // g)) * H * d_h
+        sz_v = 4 * n * H * d_h // g
     lowrank = 2 * 2 * (n * rank + d_h * rank) * H
     kv_k, _, _ = outlier_counts(n, outlier_ppm)
-    kv_v, _, _ = outlier_counts(H * d_h, outlier_ppm)
+    if v_per_head:
+        kv_v = H * outlier_counts(d_h, outlier_ppm)[0]
+    else:
+        kv_v, _, _ = outlier_counts(H * d_h, outlier_ppm)
     sparse = (2 + index_bytes) * (kv_k * H * d_h + kv_v * n)
     total = codes + sz_k + sz_v + lowrank + sparse
     return dict(fp16=fp16, codes=codes, scale_zero=sz_k + sz_v, lowrank=lowrank, sparse=sparse,

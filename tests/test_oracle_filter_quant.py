@@ -217,10 +217,78 @@ def test_kv_size_rows_of_table1():
     n_all = spec["avg_tokens"]
     for row in spec["rows"]:
         n = n_all - row["n_b"]
-        g = n if row["per_vector"] else row["g"]
-        acc = go.compressed_bytes(n, 128, 32, row["bits"], g, 0, 0)
-        if row["per_vector"]:      # value groups span the whole token row: one (scale, zero) per token
-            acc["total"] = acc["codes"] + 4 * 32 * 128 + 4 * n
+        acc = go.compressed_bytes(n, 128, 32, row["bits"], 0 if row["per_vector"] else row["g"], 0, 0)
         total = acc["total"] + 2 * 2 * row["n_b"] * 32 * 128      # + fp16 buffer
         pct = 100.0 * total / (2 * 2 * n_all * 32 * 128)
         assert abs(pct - row["kv_size_pct"]) <= row["tol_pct"], (row["name"], pct)
+
+
+# ---- the two variants of the follow-up scope: per-head Value Filter, per-vector groups ----
+def test_filter_values_per_head_vs_brute_force():
+    rng = np.random.default_rng(11)
+    B, H, n, d = 2, 3, 5, 128
+    V = (rng.integers(-20, 21, size=(B, H, n, d)) * 0.25).astype(np.float16)      # many ties
+    V[0, 1, 2, :] = 1.5                                                           # an all-equal vector
+    V[1, 0, 0, ::2] = -0.0
+    for ppm in (20000, 100000, 500000):
+        kv, kt, kb = go.outlier_counts(d, ppm)
+        m = go.filter_values(V, ppm, per_head=True)
+        assert (m.sum(axis=3) == kv).all()
+        for b in range(B):
+            for h in range(H):
+                for t in range(n):
+                    v = [float(x) for x in V[b, h, t]]
+                    top = sorted(range(d), key=lambda i: (-v[i], i))[:kt]
+                    rest = [i for i in range(d) if i not in top]
+                    bot = sorted(rest, key=lambda i: (v[i], i))[:kb]
+                    want = np.zeros(d, bool)
+                    want[top + bot] = True
+                    assert np.array_equal(m[b, h, t], want), (ppm, b, h, t)
+    # the two variants rank different vectors: the per-token one couples the heads
+    assert not np.array_equal(go.filter_values(V, 20000), go.filter_values(V, 20000, per_head=True))
+
+
+def test_per_vector_groups_hand_example():
+    """Per-vector groups by hand: Keys one group per channel over the call's tokens, Values one
+    group per token over both heads.  Values on exact grids, so codes and pairs are known."""
+    # Keys: channel 0 runs 0..3 over 4 tokens (scale 1, zero 0), channel 1 is 2 - 0.5 t (scale 0.5, zero 0.5)
+    K = np.zeros((1, 1, 4, 2), np.float16)
+    K[0, 0, :, 0] = [0, 1, 2, 3]
+    K[0, 0, :, 1] = [2.0, 1.5, 1.0, 0.5]
+    seg = go.compress_tensor(K, "K", 2, 0, 0, 0, 3, None)
+    assert seg.scale.shape == (1, 1, 1, 2) and seg.scale.tolist() == [[[[1.0, 0.5]]]] and seg.zero.tolist() == [[[[0.0, 0.5]]]]
+    assert seg.codes[0, 0, :, 0].tolist() == [0, 1, 2, 3] and seg.codes[0, 0, :, 1].tolist() == [3, 2, 1, 0]
+    assert np.array_equal(go.reconstruct_segment(seg, 0), K.astype(np.float64))
+    # Values: token 0 holds -3..3 over two heads of 2 channels (step 2: scale 2, zero -3), token 1 is constant
+    V = np.zeros((1, 2, 2, 2), np.float16)
+    V[0, 0, 0] = [-3, 1]
+    V[0, 1, 0] = [3, -1]
+    V[0, :, 1] = 0.75
+    seg = go.compress_tensor(V, "V", 2, 0, 0, 0, 3, None)
+    assert seg.scale.shape == (1, 2, 2, 1)
+    assert seg.scale[0, :, 0, 0].tolist() == [2.0, 2.0] and seg.zero[0, :, 0, 0].tolist() == [-3.0, -3.0]
+    assert seg.scale[0, :, 1, 0].tolist() == [0.0, 0.0] and seg.zero[0, :, 1, 0].tolist() == [0.75, 0.75]
+    assert seg.codes[0, 0, 0].tolist() == [0, 2] and seg.codes[0, 1, 0].tolist() == [3, 1]
+    assert np.array_equal(go.reconstruct_segment(seg, 0), V.astype(np.float64))
+
+
+def test_per_vector_groups_error_bound_and_span():
+    """Closed form of Eq. 2 with one group per vector: the scale is (max - min) / (2^b - 1) of the WHOLE
+    Key channel / Value token row (taken here directly from the input), and |y - D| <= scale / 2."""
+    rng = np.random.default_rng(12)
+    B, H, n, d, bits = 2, 3, 70, 128, 4
+    for kind in ("K", "V"):
+        X = rng.standard_normal((B, H, n, d)).astype(np.float16)
+        seg = go.compress_tensor(X, kind, bits, 0, 0, 0, 3, None)
+        x = X.astype(np.float64)
+        if kind == "K":
+            span = x.max(axis=2, keepdims=True) - x.min(axis=2, keepdims=True)            # [B,H,1,d]
+            assert seg.scale.shape == (B, H, 1, d)
+        else:
+            rows = x.transpose(0, 2, 1, 3).reshape(B, n, H * d)
+            span = (rows.max(axis=2) - rows.min(axis=2))[:, None, :, None]                # [B,1,n,1]
+            assert seg.scale.shape == (B, H, n, 1)
+        delta = seg.scale.astype(np.float64)
+        assert np.allclose(delta, np.broadcast_to(span / 15, delta.shape), rtol=2 ** -10, atol=0)
+        err = np.abs(go.reconstruct_segment(seg, 0) - x)
+        assert (err <= np.broadcast_to(delta, err.shape) * (0.5 + 2 ** -9) + 15 * 2 ** -11 * np.broadcast_to(delta, err.shape)).all()
