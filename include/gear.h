@@ -51,14 +51,23 @@ typedef struct gear_config {
   int32_t d_h;           /* head dimension, must be 128                            */
   int32_t bits;          /* b in {2, 4}  (Eq. 2)                                   */
   int32_t group;         /* g in {32, 64, 128}: Keys g tokens of one channel,      */
-                         /* Values g channels of one token                         */
+                         /* Values g channels of one token.  0: the coarse         */
+                         /* per-vector grouping of the paper's background section  */
+                         /* ("KCVT"): one group per Key channel over the tokens of */
+                         /* a call, one per Value token over all H_kv*d_h channels */
   int32_t outlier_ppm;   /* s of Filter_s (Eq. 4) in parts per million of a        */
                          /* vector; 20000 = 2 %, 0 = GEAR-L (no sparse term)       */
   int32_t n_buf_cap;     /* n_b: streaming-buffer capacity, 1..255                 */
   int32_t n_prefill_max; /* capacity of the first (prefill) segment, <= 32768      */
   int32_t n_chunks_max;  /* number of flushed buffers that can be appended, <= 256 */
   int32_t rank_max;      /* largest rank any compress call will use, 0..8          */
+  int32_t flags;         /* GEAR_FLAG_* bits, 0 = the method as the paper states it */
 } gear_config;
+
+/* Filter_s ranks each KV head's d_h channels of a Value token on their own (vector
+ * length d_h, count ceil(s d_h) per head) instead of the token's row over all heads
+ * (Eq. 4 read with X = V in R^{n x d}).  Every head is then independent of the others. */
+#define GEAR_FLAG_V_FILTER_PER_HEAD 1
 
 /* Host-side descriptor of one cache.  Filled by gear_cache_init, advanced by
  * gear_compress.  Treat the fields as read-only. */

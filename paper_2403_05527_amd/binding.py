@@ -22,7 +22,7 @@ EXPORTED = [
 class gear_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "B", "H_kv", "H_q", "d_h", "bits", "group", "outlier_ppm", "n_buf_cap", "n_prefill_max",
-        "n_chunks_max", "rank_max")]
+        "n_chunks_max", "rank_max", "flags")]
 
 
 class gear_cache(ctypes.Structure):
@@ -95,10 +95,13 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+GEAR_FLAG_V_FILTER_PER_HEAD = 1
+
+
 def make_config(B, H_kv, H_q, bits, group, outlier_ppm, n_buf_cap, n_prefill_max, n_chunks_max, rank_max,
-                d_h=128):
+                d_h=128, flags=0):
     return gear_config(B, H_kv, H_q, d_h, bits, group, outlier_ppm, n_buf_cap, n_prefill_max, n_chunks_max,
-                       rank_max)
+                       rank_max, flags)
 
 
 # ---- thin wrappers with the C names ---------------------------------------
@@ -185,6 +188,8 @@ class GearCache:
 
     def n_groups_total(self):
         g = self.cfg.group
+        if g == 0:                                  # per-vector groups: one Key group per segment
+            return (1 if self.cache.n_prefill > 0 else 0) + self.cache.n_chunks
         ng = -(-self.cache.n_prefill // g)
         for j in range(self.cache.n_chunks):
             ng += -(-self.cache.chunk_n[j] // g)
@@ -216,7 +221,7 @@ class GearCache:
         if which == 0:
             shape = (c.B, c.H_kv, self.n_groups_total(), c.d_h)
         else:
-            shape = (c.B, c.H_kv, self.n_total, c.d_h // c.group)
+            shape = (c.B, c.H_kv, self.n_total, c.d_h // (c.group or c.d_h))
         scale = torch.empty(shape, dtype=torch.float16, device=self.device)
         zero = torch.empty(shape, dtype=torch.float16, device=self.device)
         gear_export_codes(self.cache, which, codes, scale, zero)

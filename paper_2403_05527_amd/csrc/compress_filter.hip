@@ -38,7 +38,7 @@ template <int CB>
 __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restrict__ K, int n, int n_pad,
                                                        int nslab, int k_top, int k_bot,
                                                        ThreshPair* __restrict__ thrK, uint32_t* __restrict__ zero,
-                                                       int zero_count) {
+                                                       int zero_count, uint32_t* __restrict__ ksz, int ng_cap, float qmax) {
   GEAR_DYN_LDS(smem_raw);
   // the first kernel of a compress call also clears the call's list counters (the kernels that
   // count run after this one on the stream)
@@ -126,6 +126,36 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
     const Thresh th = n <= 64 ? wave_select_small(src.base, n, k_top, k_bot, active)
                               : wave_select(src, n, k_top, k_bot, hist_all + wave * SELECT_LDS_WORDS, active);
     if (active && lane == 0) thrK[(size_t)slab * D + cb * CB + v] = pack_thresh(th);
+    if (ksz) {
+      // per-vector grouping: the channel's one group of this call spans the whole vector, so its
+      // (scale, zero) come from here: min and max of X - S, i.e. with the outliers counted as 0
+      uint32_t kmn = 0xFFFFu, kmx = 0u;
+      if (active) {
+        const ThreshPair tp = pack_thresh(th);
+        const int nch = (n + 511) >> 9;
+        for (int ch = 0; ch < nch; ++ch) {
+          const uint4 v4 = src(ch);
+          const int base = ch * 512 + lane * 8;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t k = slot16(v4, e), idx = (uint32_t)(base + e);
+            if (base + e < n) {
+              const bool out = ((k << 16) | (0xFFFFu - idx)) >= tp.top || ((k << 16) | idx) < tp.bot;
+              const uint32_t y = out ? 0x8000u : k;
+              kmn = min(kmn, y);
+              kmx = max(kmx, y);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        kmn = min(kmn, (uint32_t)__shfl_xor(kmn, o, 64));
+        kmx = max(kmx, (uint32_t)__shfl_xor(kmx, o, 64));
+      }
+      if (active && lane == 0)
+        ksz[(size_t)slab * ng_cap * D + cb * CB + v] = group_bits(make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), qmax));
+    }
   }
 }
 
@@ -241,10 +271,12 @@ __global__ __launch_bounds__(256, (G <= 64 ? 3 : 2)) void k_quant_kernel(const u
           kmn = a < kmn ? a : kmn;
           kmx = b > kmx ? b : kmx;
         }
-        const GroupQ q = make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), QMAX);
+        // per-vector grouping: the channel's one pair of this segment was found with its thresholds
+        const GroupQ q = dm.kcvt ? load_group(sv.sz[(size_t)slab * sv.ng_cap * D + tid])
+                                 : make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), QMAX);
         gq_mn[gi][tid] = q.mn;
         gq_inv[gi][tid] = q.inv;
-        sv.sz[((size_t)slab * sv.ng_cap + (t0 + gi * G) / G) * D + tid] = group_bits(q);
+        if (!dm.kcvt) sv.sz[((size_t)slab * sv.ng_cap + (t0 + gi * G) / G) * D + tid] = group_bits(q);
       }
     }
   }
@@ -390,7 +422,7 @@ static int k_select_cb(int n_pad, int slabs) {
 
 template <int CB>
 static hipError_t launch_k_select_cb(const uint16_t* K, const Dims& dm, int n, int n_pad, int k_top, int k_bot,
-                                     ThreshPair* thrK, uint32_t* zero, int zero_count, hipStream_t st) {
+                                     ThreshPair* thrK, uint32_t* zero, int zero_count, const SegView& sv, hipStream_t st) {
   constexpr int nw = CB < 4 ? CB : 4;   // waves per block: one vector each per round
   const size_t lds = (size_t)nw * SELECT_LDS_WORDS * sizeof(uint32_t) + (size_t)CB * n_pad * 2;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel<CB>),
@@ -398,22 +430,22 @@ static hipError_t launch_k_select_cb(const uint16_t* K, const Dims& dm, int n, i
   if (e != hipSuccess) return e;
   dim3 grid((D / CB) * dm.B * dm.H);
   hipLaunchKernelGGL(k_select_kernel<CB>, grid, dim3(64 * nw), lds, st, K, n, n_pad, dm.B * dm.H, k_top, k_bot, thrK, zero,
-                     zero_count);
+                     zero_count, dm.kcvt ? sv.sz : (uint32_t*)nullptr, sv.ng_cap, dm.qmax);
   return hipGetLastError();
 }
 
 hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
-                           uint32_t* zero, int zero_count, hipStream_t st) {
+                           uint32_t* zero, int zero_count, const SegView& sv, hipStream_t st) {
   const int n_pad = (n + 7) & ~7;
   switch (k_select_cb(n_pad, dm.B * dm.H)) {
-    case 128: return launch_k_select_cb<128>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
-    case 64: return launch_k_select_cb<64>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
-    case 32: return launch_k_select_cb<32>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
-    case 16: return launch_k_select_cb<16>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
-    case 8: return launch_k_select_cb<8>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
-    case 4: return launch_k_select_cb<4>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
-    case 2: return launch_k_select_cb<2>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
-    default: return launch_k_select_cb<1>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, st);
+    case 128: return launch_k_select_cb<128>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, sv, st);
+    case 64: return launch_k_select_cb<64>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, sv, st);
+    case 32: return launch_k_select_cb<32>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, sv, st);
+    case 16: return launch_k_select_cb<16>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, sv, st);
+    case 8: return launch_k_select_cb<8>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, sv, st);
+    case 4: return launch_k_select_cb<4>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, sv, st);
+    case 2: return launch_k_select_cb<2>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, sv, st);
+    default: return launch_k_select_cb<1>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, sv, st);
   }
 }
 

@@ -23,9 +23,14 @@ struct RegSource {  // the vector lives in the wave's registers
 // grid (ceil(n / (4 * tpw)), B); block 256: tpw tokens per wave, one after another.
 // lane l, chunk ch  <->  head 4*ch + l/16, channels 8*(l%16)..+7, i.e. in-vector index
 // ch*512 + l*8 + e.
+// Under the per-vector grouping (vsz != nullptr) the kernel also leaves the token's (scale, zero):
+// its one Value group spans the whole vector, outliers counted as 0.  per_head: the Filter ranks
+// each head's 128 channels (the 16 lanes of a row) on their own; thresholds are then not stored
+// (the quantization kernel finds them again, they cost less than their round trip).
 template <int NC>
 __global__ __launch_bounds__(256, (NC <= 8 ? 5 : NC <= 10 ? 4 : 2)) void v_select_kernel(const uint16_t* __restrict__ V, int H, int n, int tpw, int k_top,
-                                                       int k_bot, ThreshPair* __restrict__ thrV) {
+                                                       int k_bot, ThreshPair* __restrict__ thrV, uint32_t* __restrict__ vsz,
+                                                       float qmax, int per_head) {
   __shared__ uint32_t hist[4 * SELECT_LDS_WORDS];
   const int b = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -44,9 +49,41 @@ __global__ __launch_bounds__(256, (NC <= 8 ? 5 : NC <= 10 ? 4 : 2)) void v_selec
       const uint4 raw = GEAR_BUF_LOAD16(vb, off0 + (uint32_t)ch * 4u * n * (D * 2));
       x[ch] = make_uint4(key16x2(raw.x), key16x2(raw.y), key16x2(raw.z), key16x2(raw.w));
     }
-    RegSource<NC> src{x};
-    const Thresh th = wave_select(src, N, k_top, k_bot, hist + wave * SELECT_LDS_WORDS, tvalid);
-    if (tvalid && lane == 0) thrV[(size_t)b * n + t] = pack_thresh(th);
+    ThreshPair tp = pack_thresh(thresh_none());
+    if (!per_head) {
+      RegSource<NC> src{x};
+      const Thresh th = wave_select(src, N, k_top, k_bot, hist + wave * SELECT_LDS_WORDS, tvalid);
+      tp = pack_thresh(th);
+      if (tvalid && lane == 0 && thrV) thrV[(size_t)b * n + t] = tp;
+    }
+    if (vsz) {
+      uint32_t kmn = 0xFFFFu, kmx = 0u;
+#pragma unroll
+      for (int ch = 0; ch < NC; ++ch) {
+        const uint32_t kw[4] = {x[ch].x, x[ch].y, x[ch].z, x[ch].w};
+        uint32_t idx0 = (uint32_t)(ch * 512 + lane * 8);          // index in the token's row over all heads
+        if (per_head) {
+          tp = row16_thresholds(kw, oc, k_top, k_bot);            // this head's own thresholds,
+          idx0 = (uint32_t)(oc * 8);                              // on the index inside the head
+        }
+        if (ch * 512 + lane * 8 < N) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t k = (e & 1) ? (kw[e >> 1] >> 16) : (kw[e >> 1] & 0xFFFFu), idx = idx0 + e;
+            const bool out = ((k << 16) | (0xFFFFu - idx)) >= tp.top || ((k << 16) | idx) < tp.bot;
+            const uint32_t y = out ? 0x8000u : k;
+            kmn = min(kmn, y);
+            kmx = max(kmx, y);
+          }
+        }
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        kmn = min(kmn, (uint32_t)__shfl_xor(kmn, o, 64));
+        kmx = max(kmx, (uint32_t)__shfl_xor(kmx, o, 64));
+      }
+      if (tvalid && lane == 0) vsz[(size_t)b * n + t] = group_bits(make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), qmax));
+    }
   }
 }
 
@@ -56,7 +93,8 @@ __global__ __launch_bounds__(256, (NC <= 8 ? 5 : NC <= 10 ? 4 : 2)) void v_selec
 // code bytes read off float mantissas.
 template <int BITS>
 __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict__ V, SegView sv, Dims dm, int n,
-                                                      const ThreshPair* __restrict__ thrV, uint32_t* __restrict__ pool_ctr,
+                                                      const ThreshPair* __restrict__ thrV, const uint32_t* __restrict__ vsz,
+                                                      int k_top, int k_bot, uint32_t* __restrict__ pool_ctr,
                                                       uint16_t* __restrict__ Yout) {
   constexpr int PITCH = 136;  // bytes per staged code row (multiple of 8)
   constexpr float QMAX = (float)((1 << BITS) - 1);
@@ -82,15 +120,26 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
   const GEAR_BUF_T yb = GEAR_BUF_MAKE(Yout ? Yout + (size_t)slab * n * D : nullptr, Yout ? (uint32_t)n * (D * 2) : 0u);
   uint4 xrow[4];
   ThreshPair trow[4];
+  uint32_t gsz[4];   // per-vector grouping: the token's (scale, zero)
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     const int t = t0 + r0 + 16 * k;
     xrow[k] = GEAR_BUF_LOAD16(xb, (uint32_t)t * (D * 2) + oc * 16);   // rows past the end read as 0
     trow[k] = pack_thresh(thresh_none());                             // and have no outliers
-    if (t < n && dm.ppm > 0) trow[k] = thrV[(size_t)b * n + t];
+    if (t < n && dm.ppm > 0 && !dm.vhead) trow[k] = thrV[(size_t)b * n + t];
+    gsz[k] = 0u;
+    if (t < n && dm.kcvt) gsz[k] = vsz[(size_t)b * n + t];
   }
-  // in-vector index of entry e: h*128 + 8*oc + e; the low three bits are e
-  const uint32_t cB0 = (uint32_t)(h * D + oc * 8), cT0 = (0xFFFFu - cB0) & ~7u;
+  if (dm.vhead && dm.ppm > 0) {   // the Filter per head: the row's 16 lanes hold the whole vector
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t kw[4] = {key16x2(xrow[k].x), key16x2(xrow[k].y), key16x2(xrow[k].z), key16x2(xrow[k].w)};
+      const ThreshPair tp = row16_thresholds(kw, oc, k_top, k_bot);
+      if (t0 + r0 + 16 * k < n) trow[k] = tp;
+    }
+  }
+  // in-vector index of entry e: h*128 + 8*oc + e (8*oc + e when the Filter is per head); the low three bits are e
+  const uint32_t cB0 = (uint32_t)((dm.vhead ? 0 : h * D) + oc * 8), cT0 = (0xFFFFu - cB0) & ~7u;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     const int tl = r0 + 16 * k, t = t0 + tl;
@@ -144,7 +193,7 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
       kmx = max(kmx, dpp_u<DPP_MIRROR>(kmx));
     }
     const float lmn = h2f(unkey16(kmn)), lmx = h2f(unkey16(kmx));
-    const GroupQ q = make_group(lmn, lmx, QMAX);
+    const GroupQ q = dm.kcvt ? load_group(gsz[k]) : make_group(lmn, lmx, QMAX);
     uint32_t fc[8];   // bits of code + 2^23
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -247,32 +296,39 @@ __global__ __launch_bounds__(256) void v_quant_kernel(const uint16_t* __restrict
 
 // ------------------------------------------------------------------ launchers
 template <int NC>
-static hipError_t launch_vsel(const uint16_t* V, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrV,
+static hipError_t launch_vsel(const uint16_t* V, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrV, uint32_t* vsz,
                               hipStream_t st) {
   // four tokens per wave, or one when the call has few tokens (a flushed buffer)
   const int tpw = (long long)n * dm.B >= 16384 ? 4 : 1;
   dim3 grid((n + 4 * tpw - 1) / (4 * tpw), dm.B);
-  hipLaunchKernelGGL(v_select_kernel<NC>, grid, dim3(256), 0, st, V, dm.H, n, tpw, k_top, k_bot, thrV);
+  hipLaunchKernelGGL(v_select_kernel<NC>, grid, dim3(256), 0, st, V, dm.H, n, tpw, k_top, k_bot, thrV,
+                     dm.kcvt ? vsz : (uint32_t*)nullptr, dm.qmax, dm.vhead);
   return hipGetLastError();
 }
 
 hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dims& dm, int n, int k_top,
-                                 int k_bot, ThreshPair* thrV, uint32_t* pool_ctr, uint16_t* Yout, hipStream_t st) {
-  if (dm.ppm > 0) {
+                                 int k_bot, ThreshPair* thrV, uint32_t* vsz, uint32_t* pool_ctr, uint16_t* Yout,
+                                 hipStream_t st) {
+  // the pass over whole token rows: thresholds of the per-token Filter, and a token's (scale, zero)
+  // under the per-vector grouping
+  if ((dm.ppm > 0 && !dm.vhead) || dm.kcvt) {
+    const int kt = dm.ppm > 0 ? k_top : 0, kb = dm.ppm > 0 ? k_bot : 0;
     const int nc = (dm.H + 3) / 4;
     hipError_t e;
-    if (nc <= 2) e = launch_vsel<2>(V, dm, n, k_top, k_bot, thrV, st);
-    else if (nc <= 4) e = launch_vsel<4>(V, dm, n, k_top, k_bot, thrV, st);
-    else if (nc <= 8) e = launch_vsel<8>(V, dm, n, k_top, k_bot, thrV, st);
-    else if (nc <= 10) e = launch_vsel<10>(V, dm, n, k_top, k_bot, thrV, st);
-    else e = launch_vsel<16>(V, dm, n, k_top, k_bot, thrV, st);
+    if (nc <= 2) e = launch_vsel<2>(V, dm, n, kt, kb, thrV, vsz, st);
+    else if (nc <= 4) e = launch_vsel<4>(V, dm, n, kt, kb, thrV, vsz, st);
+    else if (nc <= 8) e = launch_vsel<8>(V, dm, n, kt, kb, thrV, vsz, st);
+    else if (nc <= 10) e = launch_vsel<10>(V, dm, n, kt, kb, thrV, vsz, st);
+    else e = launch_vsel<16>(V, dm, n, kt, kb, thrV, vsz, st);
     if (e != hipSuccess) return e;
   }
   dim3 grid((n + TILE - 1) / TILE, dm.B * dm.H);
   if (dm.bits == 2)
-    hipLaunchKernelGGL(v_quant_kernel<2>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, pool_ctr, Yout);
+    hipLaunchKernelGGL(v_quant_kernel<2>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, (const uint32_t*)vsz,
+                       k_top, k_bot, pool_ctr, Yout);
   else
-    hipLaunchKernelGGL(v_quant_kernel<4>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, pool_ctr, Yout);
+    hipLaunchKernelGGL(v_quant_kernel<4>, grid, dim3(256), 0, st, V, sv, dm, n, (const ThreshPair*)thrV, (const uint32_t*)vsz,
+                       k_top, k_bot, pool_ctr, Yout);
   return hipGetLastError();
 }
 

@@ -364,7 +364,8 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
             n4_av = rows_lds ? (nw * rv + 7) >> 3 : 0;
   const bool stage_b = shared_b ? wave == 0 : nw > 0;   // a prefill block's first wave always owns rows
   const int n4_bk = stage_b ? 16 * rk : 0, n4_bv = stage_b ? 16 * rv : 0;   // 128 * rank fp16
-  const uint4* g_szk = reinterpret_cast<const uint4*>(ks.sz + ((size_t)slab * ks.ng_cap + (tw0 >> lg)) * D);
+  // (per-vector grouping: a segment's one Key group, and the wave's 128 rows lie in it)
+  const uint4* g_szk = reinterpret_cast<const uint4*>(ks.sz + ((size_t)slab * ks.ng_cap + (dm.kcvt ? 0 : tw0 >> lg)) * D);
   const uint4* g_szv = reinterpret_cast<const uint4*>(vs.sz + ((size_t)slab * vs.n_cap + tw0) * NG);
   const uint4* g_ak = reinterpret_cast<const uint4*>(ks.A + ((size_t)slab * ks.n_cap + tw0) * rk);
   const uint4* g_av = reinterpret_cast<const uint4*>(vs.A + ((size_t)slab * vs.n_cap + tw0) * rv);

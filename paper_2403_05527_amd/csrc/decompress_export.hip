@@ -32,7 +32,7 @@ __device__ __forceinline__ uint32_t load_code(const SegView& sv, const Dims& dm,
   return (w >> (i * dm.bits)) & cmask;
 }
 __device__ __forceinline__ uint32_t load_sz(const SegView& sv, const Dims& dm, bool is_k, int slab, int t, int c) {
-  if (is_k) return sv.sz[((size_t)slab * sv.ng_cap + t / dm.g) * D + c];
+  if (is_k) return sv.sz[((size_t)slab * sv.ng_cap + key_group(dm, t)) * D + c];
   return sv.sz[((size_t)slab * sv.n_cap + t) * (D / dm.g) + c / dm.g];
 }
 
@@ -103,8 +103,8 @@ __global__ __launch_bounds__(256) void export_codes_kernel(Dims dm, SegView sv, 
     codes[((size_t)slab * n_total + sv.t0 + t) * D + c] = (uint8_t)load_code(sv, dm, is_k, slab, t, c);
     const uint32_t sb = load_sz(sv, dm, is_k, slab, t, c);
     if (is_k) {
-      if (t % dm.g == 0) {
-        const size_t o = ((size_t)slab * ng_total + sv.g0 + t / dm.g) * D + c;
+      if (dm.kcvt ? t == 0 : t % dm.g == 0) {
+        const size_t o = ((size_t)slab * ng_total + sv.g0 + key_group(dm, t)) * D + c;
         scale[o] = (uint16_t)(sb & 0xFFFFu);
         zero[o] = (uint16_t)(sb >> 16);
       }

@@ -26,20 +26,28 @@ struct Region {  // byte offsets of one tensor's arrays inside a segment region
   uint32_t pool_cap;
 };
 
+inline int group_of(const gear_config& c) { return c.group == 0 ? D : c.group; }   // tile-level group size
+// outliers of one Value token over all heads
+inline int v_outliers_per_token(const gear_config& c) {
+  return (c.flags & GEAR_FLAG_V_FILTER_PER_HEAD) ? c.H_kv * outlier_count(D, c.outlier_ppm)
+                                                 : outlier_count((long long)c.H_kv * D, c.outlier_ppm);
+}
+
 Region region_layout(const gear_config& c, bool is_k, int n_cap) {
   Region r;
   const size_t slabs = (size_t)c.B * c.H_kv;
+  const int group = group_of(c);
   const int wpr = D * c.bits / 32, tpw = 32 / c.bits;
   n_cap = (n_cap + 7) & ~7;   // row strides of A, scale/zero and slots stay 16-byte aligned per slab
   r.n_cap = n_cap;
-  r.ng_cap = (n_cap + c.group - 1) / c.group;
+  r.ng_cap = (n_cap + group - 1) / group;
   r.nblk_cap = (n_cap + 4 * tpw - 1) / (4 * tpw);
   r.ntile_cap = (n_cap + TILE - 1) / TILE;
   size_t o = 0;
   r.codes = o;
   o += up(is_k ? slabs * n_cap * wpr * 4 : slabs * (size_t)r.nblk_cap * 2048);
   r.sz = o;
-  o += up((is_k ? slabs * (size_t)r.ng_cap * D * 4 : slabs * (size_t)n_cap * (D / c.group) * 4) + 16);   // readers fetch whole 16-byte pieces
+  o += up((is_k ? slabs * (size_t)r.ng_cap * D * 4 : slabs * (size_t)n_cap * (D / group) * 4) + 16);   // readers fetch whole 16-byte pieces
   r.A = o;
   o += up(slabs * (size_t)n_cap * (c.rank_max > 0 ? c.rank_max : 1) * 2 + 16);
   r.Bf = o;
@@ -54,7 +62,7 @@ Region region_layout(const gear_config& c, bool is_k, int n_cap) {
     o += up(slabs * (size_t)r.pool_cap * 4);
   } else {
     r.pool_cap = (uint32_t)c.H_kv * r.ntile_cap * VPOOL_FIXED +   // reserved regions, then the worst case
-                 (uint32_t)n_cap * outlier_count((long long)c.H_kv * D, c.outlier_ppm);
+                 (uint32_t)n_cap * v_outliers_per_token(c);
     o += up((size_t)c.B * r.pool_cap * 4);
   }
   r.bytes = o;
@@ -81,7 +89,7 @@ ArenaLayout arena_layout(const gear_config& c) {
 }
 
 struct WorkLayout {
-  size_t thrK, thrV, pool_ctr, Bcur, partial, Atmp, cmat, dec, gram, resid, bytes;
+  size_t thrK, thrV, vsz, pool_ctr, Bcur, partial, Atmp, cmat, dec, gram, resid, bytes;
   int gram_strips;
 };
 
@@ -94,6 +102,7 @@ WorkLayout work_layout(const gear_config& c) {
   size_t o = 0;
   w.thrK = o; o += up(slabs * D * sizeof(ThreshPair));
   w.thrV = o; o += up((size_t)c.B * n_max * sizeof(ThreshPair));
+  w.vsz = o; o += up(c.group == 0 ? (size_t)c.B * n_max * 4 : 0);   // per-vector grouping: a Value token's (scale, zero)
   w.pool_ctr = o; o += up((slabs + (size_t)c.B) * 4);   // Key counters per slab, then Value counters per batch
   w.Bcur = o; o += up(slabs * D * R * 4);
   w.partial = o; o += up(slabs * (size_t)npart * (D * R + R * R) * 4);
@@ -120,7 +129,8 @@ int check_config(const gear_config* c) {
   if (!pow2(gq) || gq > 8) return GEAR_EINVAL;
   if (c->d_h != D) return GEAR_EINVAL;
   if (c->bits != 2 && c->bits != 4) return GEAR_EINVAL;
-  if (c->group != 32 && c->group != 64 && c->group != 128) return GEAR_EINVAL;
+  if (c->group != 0 && c->group != 32 && c->group != 64 && c->group != 128) return GEAR_EINVAL;
+  if (c->flags & ~GEAR_FLAG_V_FILTER_PER_HEAD) return GEAR_EINVAL;
   if (c->outlier_ppm < 0 || c->outlier_ppm > 500000) return GEAR_EINVAL;
   if (c->n_buf_cap < 1 || c->n_buf_cap > 255) return GEAR_EINVAL;
   if (c->n_prefill_max < 1 || c->n_prefill_max > 32768) return GEAR_EINVAL;
@@ -135,7 +145,9 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 Dims make_dims(const gear_config& c) {
   Dims d;
   d.B = c.B; d.H = c.H_kv; d.Hq = c.H_q;
-  d.bits = c.bits; d.g = c.group; d.ppm = c.outlier_ppm;
+  d.bits = c.bits; d.g = group_of(c); d.ppm = c.outlier_ppm;
+  d.kcvt = c.group == 0 ? 1 : 0;
+  d.vhead = (c.flags & GEAR_FLAG_V_FILTER_PER_HEAD) ? 1 : 0;
   d.wpr = D * c.bits / 32;
   d.tpw = 32 / c.bits;
   d.qmax = (float)((1 << c.bits) - 1);
@@ -161,7 +173,7 @@ SegView make_view(char* base, const Region& r, int n, int rank, int t0, int g0) 
 // seg 0 = prefill, seg j >= 1 = chunk j-1
 void seg_views(const gear_cache* cache, const ArenaLayout& a, int seg, int n, int rank, SegView* k, SegView* v) {
   char* base = static_cast<char*>(cache->arena);
-  const int g = cache->cfg.group;
+  const int g = cache->cfg.group == 0 ? 1 << 30 : cache->cfg.group;   // per-vector grouping: one Key group per segment
   if (seg == 0) {
     *k = make_view(base + a.off_kp, a.kp, n, rank, 0, 0);
     *v = make_view(base + a.off_vp, a.vp, n, rank, 0, 0);
@@ -181,7 +193,7 @@ int n_segments(const gear_cache* c) { return (c->n_prefill > 0 ? 1 : 0) + c->n_c
 int seg_n(const gear_cache* c, int seg) { return seg == 0 ? c->n_prefill : c->chunk_n[seg - 1]; }
 int seg_rank(const gear_cache* c, int seg) { return seg == 0 ? c->rank_prefill : c->chunk_rank[seg - 1]; }
 int total_groups(const gear_cache* c) {
-  const int g = c->cfg.group;
+  const int g = c->cfg.group == 0 ? 1 << 30 : c->cfg.group;
   int ng = (c->n_prefill + g - 1) / g;
   for (int j = 0; j < c->n_chunks; ++j) ng += (c->chunk_n[j] + g - 1) / g;
   return ng;
@@ -338,9 +350,11 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   uint32_t* pool_ctr = reinterpret_cast<uint32_t*>(ws + w.pool_ctr);
 
   const int kv_k = outlier_count(n, c.outlier_ppm);
-  const int kv_v = outlier_count((long long)c.H_kv * D, c.outlier_ppm);
-  if (c.outlier_ppm > 0) {
-    GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, pool_ctr, c.B * c.H_kv + c.B, st));
+  const bool vhead = (c.flags & GEAR_FLAG_V_FILTER_PER_HEAD) != 0;
+  const int kv_v = outlier_count(vhead ? D : (long long)c.H_kv * D, c.outlier_ppm);   // per Value vector
+  // the Key selection kernel also finds a channel's (scale, zero) under the per-vector grouping
+  if (c.outlier_ppm > 0 || dm.kcvt) {
+    GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, pool_ctr, c.B * c.H_kv + c.B, ks, st));
   }
   // Keys: quantize (leaving Y = X - S in the workspace), then their power iteration;
   // Values reuse the same buffer afterwards.
@@ -350,9 +364,10 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   float* Atmp = reinterpret_cast<float*>(ws + w.Atmp);
   float* cmat = reinterpret_cast<float*>(ws + w.cmat);
   float* gram = reinterpret_cast<float*>(ws + w.gram);
+  uint32_t* vsz = reinterpret_cast<uint32_t*>(ws + w.vsz);
   GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, resid, st));
   if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, ks, dm, n, iters, init_B, seed, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
-  GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, pool_ctr + (size_t)c.B * c.H_kv, resid, st));
+  GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, vsz, pool_ctr + (size_t)c.B * c.H_kv, resid, st));
   if (rank > 0)
     GEAR_HIP(launch_power_iteration(false, resid, vs, dm, n, iters, init_B, seed, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
 
@@ -461,7 +476,7 @@ int gear_export_sparse_coo(const gear_cache* cache, int which, int64_t* nnz, voi
     if (seg == 0 && cache->n_prefill == 0) continue;
     const long long n = seg_n(cache, seg);
     total += which == 0 ? (long long)c.B * c.H_kv * D * outlier_count(n, c.outlier_ppm)
-                        : (long long)c.B * n * outlier_count((long long)c.H_kv * D, c.outlier_ppm);
+                        : (long long)c.B * n * v_outliers_per_token(c);
   }
   *nnz = total;
   if (!lin_index_i64 && !value_f16) return GEAR_OK;   // size query

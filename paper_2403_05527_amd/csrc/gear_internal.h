@@ -102,7 +102,9 @@ struct Thresh {
 struct Dims {
   int B, H, Hq;
   int bits;   // b
-  int g;      // group size
+  int g;      // group size (128 with the per-vector grouping: what the tiles of the Value kernels and of the decode use)
+  int kcvt;   // per-vector grouping: one Key group per segment, one Value group per token over all heads
+  int vhead;  // Filter_s of the Values per head
   int ppm;    // outlier ratio in parts per million
   int wpr;    // 32-bit words per Key code row (128*b/32)
   int tpw;    // tokens per Value code word (32/b)
@@ -156,6 +158,8 @@ struct SegView {
   int t0;        // first token of this segment in the whole cache
   int g0;        // first Key group of this segment in the whole cache
 };
+// Key group of token t of a segment
+__host__ __device__ inline int key_group(const Dims& dm, int t) { return dm.kcvt ? 0 : t / dm.g; }
 
 // ---------------------------------------------------------------------------
 // fp16 helpers (bit patterns travel as integers)

@@ -229,6 +229,57 @@ __device__ __forceinline__ Thresh wave_select_small(const uint16_t* keys, int N,
   return th;
 }
 
+// Max / min of an unsigned value over each row of 16 lanes, in every lane of the row.
+__device__ __forceinline__ uint32_t row16_max_u(uint32_t v) {
+  v = max(v, dpp_u<DPP_XOR1>(v));
+  v = max(v, dpp_u<DPP_XOR2>(v));
+  v = max(v, dpp_u<DPP_HALF_MIRROR>(v));
+  v = max(v, dpp_u<DPP_MIRROR>(v));
+  return v;
+}
+__device__ __forceinline__ uint32_t row16_min_u(uint32_t v) {
+  v = min(v, dpp_u<DPP_XOR1>(v));
+  v = min(v, dpp_u<DPP_XOR2>(v));
+  v = min(v, dpp_u<DPP_HALF_MIRROR>(v));
+  v = min(v, dpp_u<DPP_MIRROR>(v));
+  return v;
+}
+
+// Filter_s thresholds of a vector of 128 entries held by one row of 16 lanes, 8 entries per lane
+// (entry e of lane oc has in-vector index 8 * oc + e): the per-head Value Filter.  kw: the lane's
+// 8 monotone keys, two per word.  The selected sets are the first k_top entries in (value desc,
+// index asc) and the first k_bot of the others in (value asc, index asc), found by taking the
+// row's largest (smallest) composite below (above) the previous one k_top (k_bot) times; the
+// result is the packed predicate of ThreshPair.  All 16 lanes of a row must call together.
+__device__ __forceinline__ ThreshPair row16_thresholds(const uint32_t (&kw)[4], int oc, int k_top, int k_bot) {
+  uint32_t cT[8], cB[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t k = (e & 1) ? (kw[e >> 1] & 0xFFFF0000u) : (kw[e >> 1] << 16);
+    const uint32_t idx = (uint32_t)(8 * oc + e);
+    cT[e] = k | (0xFFFFu - idx);
+    cB[e] = k | idx;
+  }
+  ThreshPair p;
+  p.top = 0xFFFFFFFFu;   // no composite reaches it: no top outliers
+  p.bot = 0u;            // none lies below it: no bottom outliers
+  for (int i = 0; i < k_top; ++i) {   // (the counts are the same in every lane)
+    uint32_t m = 0u;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) m = max(m, cT[e] < p.top ? cT[e] : 0u);
+    p.top = row16_max_u(m);
+  }
+  uint32_t last = 0u;   // composites of finite values are > 0
+  for (int i = 0; i < k_bot; ++i) {
+    uint32_t m = 0xFFFFFFFFu;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) m = min(m, (cT[e] < p.top && cB[e] > last) ? cB[e] : 0xFFFFFFFFu);
+    last = row16_min_u(m);
+  }
+  if (k_bot > 0) p.bot = last + 1u;
+  return p;
+}
+
 constexpr int SELECT_LDS_WORDS = 512;   // LDS words wave_select needs per wave
 
 // A wave with nothing to do passes active = false.  hist: SELECT_LDS_WORDS u32 of LDS private to

@@ -242,7 +242,7 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
   request(0, xv_first, cw_first);   // in flight while the parameters are prepared
 
   if (IS_K) {
-    const int ngb = PT >> lg, grp0 = (pt * PT) >> lg, ng = (n + g - 1) >> lg;
+    const int ngb = (PT >> lg) > 0 ? (PT >> lg) : 1, grp0 = (pt * PT) >> lg, ng = (n + g - 1) >> lg;
     for (int i = tid; i < ngb * D; i += 256) {
       const int gi = grp0 + (i >> 7);
       GroupQ q;
@@ -542,7 +542,7 @@ __global__ __launch_bounds__(256, 2) void pi_gram_kernel(const uint16_t* __restr
   const GEAR_BUF_T pbuf = IS_K ? GEAR_BUF_MAKE(sv.sz + (size_t)slab * sv.ng_cap * D, ((n + g - 1) >> LG) * (D * 4))
                                : GEAR_BUF_MAKE(sv.sz + (((size_t)slab * sv.n_cap) << ngl), (n << ngl) * 4);
   constexpr int GT = 128;                          // tokens per step (32 per wave)
-  constexpr int NGS = IS_K ? (GT >> LG) : 1;       // Key groups per step
+  constexpr int NGS = (IS_K && (GT >> LG) > 0) ? (GT >> LG) : 1;   // Key groups per step
   typedef GramLoads<IS_K, NGS> Loads;
 
   floatx4 acc[GRAM_TILES];
@@ -586,7 +586,7 @@ __global__ __launch_bounds__(256, 2) void pi_gram_kernel(const uint16_t* __restr
       const uint32_t w[4] = {L.xv[k].x, L.xv[k].y, L.xv[k].z, L.xv[k].w};
       float res[8];
       if (IS_K) {
-        if ((16 * k) % (1 << LG) == 0) {   // first rows of a group: its parameters
+        if ((16 * k) % (1 << (LG < 8 ? LG : 8)) == 0) {   // first rows of a group: its parameters
           const int j = (16 * k) >> LG;
           const uint32_t z[8] = {L.pz[j][0].x, L.pz[j][0].y, L.pz[j][0].z, L.pz[j][0].w,
                                  L.pz[j][1].x, L.pz[j][1].y, L.pz[j][1].z, L.pz[j][1].w};
@@ -857,7 +857,8 @@ int pi_gram_strips_max(int n_max, int slabs) {
 template <bool IS_K, int LG>
 static void launch_gram(const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int strip, int nstrips, float* gram,
                         hipStream_t st) {
-  hipLaunchKernelGGL((pi_gram_kernel<IS_K, LG>), dim3(nstrips, dm.B * dm.H), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, strip, gram);
+  // (per-vector grouping: the one Key group of a segment is addressed as a group of 32768 tokens)
+  hipLaunchKernelGGL((pi_gram_kernel<IS_K, LG>), dim3(nstrips, dm.B * dm.H), dim3(256), 0, st, Yf, sv, IS_K ? 1 << LG : dm.g, dm.bits, n, strip, gram);
 }
 
 template <int R>
@@ -866,9 +867,10 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
                          int gram_strips_cap, hipStream_t st) {
   const int slabs = dm.B * dm.H;
   const int npart = (n + PT - 1) / PT;
+  const int g_eff = (is_k && dm.kcvt) ? 32768 : dm.g;   // per-vector grouping: one Key group per segment
   if (npart == 1) {   // a short segment: everything in one block per slab
     if (is_k)
-      hipLaunchKernelGGL((pi_small_kernel<true, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, iters, sb, Bcur, partial, Atmp, cmat);
+      hipLaunchKernelGGL((pi_small_kernel<true, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, iters, sb, Bcur, partial, Atmp, cmat);
     else
       hipLaunchKernelGGL((pi_small_kernel<false, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, iters, sb, Bcur, partial, Atmp, cmat);
     return hipGetLastError();
@@ -880,6 +882,7 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
     nstrips = (n + strip - 1) / strip;
     if (nstrips > gram_strips_cap) return hipErrorInvalidValue;
     if (!is_k) launch_gram<false, 0>(Yf, sv, dm, n, strip, nstrips, gram, st);
+    else if (dm.kcvt) launch_gram<true, 15>(Yf, sv, dm, n, strip, nstrips, gram, st);
     else if (dm.g == 32) launch_gram<true, 5>(Yf, sv, dm, n, strip, nstrips, gram, st);
     else if (dm.g == 64) launch_gram<true, 6>(Yf, sv, dm, n, strip, nstrips, gram, st);
     else launch_gram<true, 7>(Yf, sv, dm, n, strip, nstrips, gram, st);
@@ -899,7 +902,7 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
   {
     const dim3 grid(npart, slabs);
     if (is_k)
-      hipLaunchKernelGGL((pi_sweep_kernel<true, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
+      hipLaunchKernelGGL((pi_sweep_kernel<true, R, true>), grid, dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
     else
       hipLaunchKernelGGL((pi_sweep_kernel<false, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
     hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, 0, sb, sv.rank,

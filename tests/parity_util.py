@@ -15,10 +15,13 @@ def np16(t):
     return t.detach().cpu().numpy()
 
 
-def make_pair(B, H_kv, H_q, bits, group, ppm, n_buf_cap, n_prefill_max, n_chunks_max, rank_max, device="cuda:0"):
-    cfg = gb.make_config(B, H_kv, H_q, bits, group, ppm, n_buf_cap, n_prefill_max, n_chunks_max, rank_max)
+def make_pair(B, H_kv, H_q, bits, group, ppm, n_buf_cap, n_prefill_max, n_chunks_max, rank_max, device="cuda:0",
+              v_per_head=False):
+    """group = 0: the per-vector grouping; v_per_head: Filter_s of the Values per head."""
+    cfg = gb.make_config(B, H_kv, H_q, bits, group, ppm, n_buf_cap, n_prefill_max, n_chunks_max, rank_max,
+                         flags=gb.GEAR_FLAG_V_FILTER_PER_HEAD if v_per_head else 0)
     gc = gb.GearCache(cfg, device)
-    oc = go.OracleCache(B, H_kv, H_q, 128, bits, group, ppm)
+    oc = go.OracleCache(B, H_kv, H_q, 128, bits, group, ppm, v_per_head)
     return gc, oc
 
 

@@ -22,12 +22,12 @@ static void wr(const char* dir, const char* name, const void* v, size_t bytes) {
 #define CK(x) do { int s_ = (x); if (s_ != GEAR_OK) { fprintf(stderr, "%s -> %s\n", #x, gear_strerror(s_)); return 3; } } while (0)
 int main(int argc, char** argv) {
   const char* dir = argv[1];
-  int B, H, Hq, bits, g, ppm, n, rank, nchunks, chunk_n, rank_chunk, n_buf, n_buf_cap, iters;
+  int B, H, Hq, bits, g, ppm, n, rank, nchunks, chunk_n, rank_chunk, n_buf, n_buf_cap, iters, flags = 0;
   char p[512]; snprintf(p, sizeof p, "%s/meta.txt", dir);
   FILE* f = fopen(p, "r");
-  if (fscanf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d", &B, &H, &Hq, &bits, &g, &ppm, &n, &rank, &nchunks, &chunk_n, &rank_chunk, &n_buf, &n_buf_cap, &iters) != 14) return 1;
+  if (fscanf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &B, &H, &Hq, &bits, &g, &ppm, &n, &rank, &nchunks, &chunk_n, &rank_chunk, &n_buf, &n_buf_cap, &iters, &flags) < 14) return 1;
   fclose(f);
-  gear_config cfg{B, H, Hq, 128, bits, g, ppm, n_buf_cap, n, nchunks > 0 ? nchunks : 1, rank > rank_chunk ? rank : rank_chunk};
+  gear_config cfg{B, H, Hq, 128, bits, g, ppm, n_buf_cap, n, nchunks > 0 ? nchunks : 1, rank > rank_chunk ? rank : rank_chunk, flags};
   size_t ab = 0, wb = 0;
   CK(gear_cache_bytes(&cfg, &ab, &wb));
   void* arena = aligned_alloc(256, (ab + 255) / 256 * 256);
@@ -57,9 +57,10 @@ int main(int argc, char** argv) {
   CK(gear_decompress(&cache, Kh, Vh, nullptr));
   wr(dir, "Khat", Kh, hb); wr(dir, "Vhat", Vh, hb);
   // canonical code / scale / zero views, for the bit-exact comparison with the oracle
-  const int ng_tot = (n + g - 1) / g + nchunks * ((chunk_n + g - 1) / g);
+  const int ge = g ? g : 128;   // g = 0: per-vector groups, one Key group per segment, one Value pair per (head, token)
+  const int ng_tot = g ? (n + g - 1) / g + nchunks * ((chunk_n + g - 1) / g) : 1 + nchunks;
   for (int which = 0; which < 2; ++which) {
-    const size_t cb = (size_t)B * H * ntot * 128, sb = which == 0 ? (size_t)B * H * ng_tot * 128 * 2 : (size_t)B * H * ntot * (128 / g) * 2;
+    const size_t cb = (size_t)B * H * ntot * 128, sb = which == 0 ? (size_t)B * H * ng_tot * 128 * 2 : (size_t)B * H * ntot * (128 / ge) * 2;
     void *codes = aligned_alloc(256, (cb + 255) / 256 * 256), *sc = aligned_alloc(256, (sb + 255) / 256 * 256), *ze = aligned_alloc(256, (sb + 255) / 256 * 256);
     CK(gear_export_codes(&cache, which, codes, sc, ze, nullptr));
     wr(dir, which ? "Vcodes" : "Kcodes", codes, cb);

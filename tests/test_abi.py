@@ -28,7 +28,7 @@ def test_exports_every_declared_symbol(lib):
 
 
 def test_struct_sizes_match_header():
-    assert ctypes.sizeof(gb.gear_config) == 11 * 4
+    assert ctypes.sizeof(gb.gear_config) == 12 * 4
     assert ctypes.sizeof(gb.gear_cache) == 48 + 8 + 8 + 16 + 512
 
 
@@ -39,7 +39,7 @@ def good():
 def test_cache_bytes_and_invalid_configs(lib):
     a, w = gb.gear_cache_bytes(good())
     assert a > 0 and w > 0 and a % 256 == 0
-    bad = [dict(bits=3), dict(group=48), dict(d_h=64), dict(H_q=6), dict(H_q=64), dict(n_buf_cap=0),
+    bad = [dict(bits=3), dict(group=48), dict(flags=2), dict(d_h=64), dict(H_q=6), dict(H_q=64), dict(n_buf_cap=0),
            dict(n_buf_cap=300), dict(n_prefill_max=0), dict(n_prefill_max=40000), dict(rank_max=9),
            dict(outlier_ppm=-1), dict(n_chunks_max=257), dict(B=0)]
     for kw in bad:

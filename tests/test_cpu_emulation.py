@@ -60,13 +60,16 @@ def emulator(tmp_path_factory):
     return exe
 
 
-def test_pipeline_under_address_sanitizer(emulator, tmp_path):
-    B, H, Hq, n, bits, g, ppm, rank, n_buf = 1, 4, 8, 290, 2, 64, 20000, 4, 5
+@pytest.mark.parametrize("B,H,Hq,n,bits,g,ppm,rank,n_buf,per_head", [
+    (1, 4, 8, 290, 2, 64, 20000, 4, 5, False),     # the method as stated; n > 256: Gram-matrix power iteration
+    (1, 2, 2, 140, 4, 0, 30000, 2, 3, True),       # per-vector groups and the per-head Value Filter
+])
+def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits, g, ppm, rank, n_buf, per_head):
     w = gw.Workload("emu", B=B, H_kv=H, H_q=Hq, n=n, bits=bits, group=g, outlier_ppm=ppm, rank=rank,
                     rank_chunk=2, n_b=20, steps=1, seed=5)
     d = str(tmp_path)
     a = lambda t: t.numpy()
-    oc = go.OracleCache(B, H, Hq, 128, bits, g, ppm)
+    oc = go.OracleCache(B, H, Hq, 128, bits, g, ppm, per_head)
     K, V, ib = a(gw.make_keys(w, n, 0)), a(gw.make_values(w, n, 0)), a(gw.make_init_B(w, rank, 0))
     for name, x in (("K", K), ("V", V), ("ib", ib)):
         x.tofile(os.path.join(d, name + ".bin"))
@@ -79,7 +82,7 @@ def test_pipeline_under_address_sanitizer(emulator, tmp_path):
     for name, x in (("q", q), ("Kb", Kb), ("Vb", Vb)):
         x.tofile(os.path.join(d, name + ".bin"))
     with open(os.path.join(d, "meta.txt"), "w") as f:
-        f.write(" ".join(str(x) for x in [B, H, Hq, bits, g, ppm, n, rank, 1, 20, 2, n_buf, 20, 3]) + "\n")
+        f.write(" ".join(str(x) for x in [B, H, Hq, bits, g, ppm, n, rank, 1, 20, 2, n_buf, 20, 3, 1 if per_head else 0]) + "\n")
     r = subprocess.run([emulator, d], capture_output=True, text=True, timeout=900,
                        env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0"))
     assert r.returncode == 0, r.stderr[-4000:]

@@ -26,10 +26,10 @@ def small_workload(B, H_kv, H_q, n, bits, g, ppm, rank, seed, nu=4):
                        rank_chunk=2, n_b=20, steps=1, seed=seed, v_nu=nu)
 
 
-def run_case(w, n_chunks=1, chunk_n=20, n_buf=7, iters=3, check_attn=True):
-    say("case", w, "chunks", n_chunks, "chunk_n", chunk_n, "n_buf", n_buf)
+def run_case(w, n_chunks=1, chunk_n=20, n_buf=7, iters=3, check_attn=True, v_per_head=False):
+    say("case", w, "chunks", n_chunks, "chunk_n", chunk_n, "n_buf", n_buf, "v_per_head", v_per_head)
     gc, oc = pu.make_pair(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, max(w.n_b, chunk_n), w.n,
-                          max(n_chunks, 1), max(w.rank, w.rank_chunk))
+                          max(n_chunks, 1), max(w.rank, w.rank_chunk), v_per_head=v_per_head)
     K = gw.make_keys(w, w.n, 0, DEV)
     V = gw.make_values(w, w.n, 0, DEV)
     ib = gw.make_init_B(w, w.rank, 0, DEV)
@@ -262,4 +262,47 @@ def test_seeded_start_matrix():
             assert torch.equal(A1, A2) and torch.equal(B1, B2), (which, seg)
     rep = pu.compare_lowrank_product(gc, oc, 0)
     rep.update(pu.compare_decompress(gc, oc))
+    say("  ->", rep)
+
+
+# ---- the per-head Value Filter and the per-vector grouping ("KCVT") ----
+@pytest.mark.parametrize("bits,ppm,rank", [(4, 20000, 4), (2, 20000, 2), (4, 0, 4), (4, 20000, 0), (2, 50000, 8)])
+def test_per_vector_groups(bits, ppm, rank):
+    """group = 0: one group per Key channel over the tokens of a call, one per Value token over all heads
+    (the paper's 4-bit backbone).  n = 300 takes the kernel-per-step power iteration, the chunks the one-block one."""
+    w = small_workload(B=2, H_kv=4, H_q=8, n=300, bits=bits, g=0, ppm=ppm, rank=rank, seed=300 + bits + rank)
+    rep = run_case(w, n_chunks=2)
+    assert ppm == 0 or (rep["K_nnz"] > 0 and rep["V_nnz"] > 0)
+
+
+@pytest.mark.parametrize("bits,g,ppm,rank", [(2, 64, 20000, 4), (4, 128, 20000, 2), (2, 32, 100000, 4), (4, 0, 20000, 4),
+                                             (2, 0, 300000, 2)])
+def test_value_filter_per_head(bits, g, ppm, rank):
+    """Filter_s ranks every head's 128 channels of a Value token on their own: exactly ceil(s * 128) outliers
+    per (head, token); with g = 0 together with the per-vector grouping."""
+    w = small_workload(B=2, H_kv=3, H_q=6, n=280, bits=bits, g=g, ppm=ppm, rank=rank, seed=400 + bits + rank)
+    run_case(w, n_chunks=1, v_per_head=True)
+    gc, _ = pu.make_pair(2, 3, 6, bits, g, ppm, 20, 280, 1, rank, v_per_head=True)
+    gc.compress(gw.make_keys(w, 280, 0, DEV), gw.make_values(w, 280, 0, DEV), rank, 3, gw.make_init_B(w, rank, 0, DEV))
+    mask, _ = gc.export_sparse(1)
+    assert (mask.sum(dim=3) == -(-ppm * 128 // 1000000)).all()
+
+
+def test_per_vector_groups_ties_and_constants():
+    """Coarse value grid, one constant head, signed zeros, under the per-vector grouping and the per-head Filter."""
+    n = 150
+    w = small_workload(B=1, H_kv=4, H_q=4, n=n, bits=4, g=0, ppm=40000, rank=2, seed=98)
+    gc, oc = pu.make_pair(1, 4, 4, 4, 0, 40000, 20, n, 1, 2, v_per_head=True)
+    g = torch.Generator(device="cpu").manual_seed(15)
+    K = (torch.randint(-6, 7, (1, 4, n, 128), generator=g).float() * 0.5)
+    V = (torch.randint(-3, 4, (1, 4, n, 128), generator=g).float() * 0.25)
+    K[0, 1] = 1.5
+    V[0, 2] = 0.0
+    V[0, 2, ::2] = -0.0
+    K = K.to(torch.float16).to(DEV)
+    V = V.to(torch.float16).to(DEV)
+    pu.compress_both(gc, oc, K, V, 2, 3, gw.make_init_B(w, 2, 0, DEV))
+    rep = pu.compare_components(gc, oc)
+    rep.update(pu.compare_decompress(gc, oc))
+    rep.update(pu.compare_attention(gc, oc, gw.make_queries(w, 0, DEV)))
     say("  ->", rep)
