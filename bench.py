@@ -45,9 +45,13 @@ def compressed_bytes(w, n, rank):
     slabs = w.B * w.H_kv
     d = w.d_h
     codes = 2 * slabs * n * d * w.bits // 8
-    sz = slabs * (4 * (-(-n // w.group)) * d + 4 * n * d // w.group)
+    if w.group == 0:      # per-vector groups: one pair per Key channel, one per Value token over all heads
+        sz = 4 * slabs * d + 4 * w.B * n
+    else:
+        sz = slabs * (4 * (-(-n // w.group)) * d + 4 * n * d // w.group)
     lowrank = 2 * slabs * (2 * n * rank + 2 * d * rank)
-    sparse = 4 * (slabs * d * outlier_count(n, w.outlier_ppm) + w.B * n * outlier_count(w.H_kv * d, w.outlier_ppm))
+    v_out = w.H_kv * outlier_count(d, w.outlier_ppm) if w.v_per_head else outlier_count(w.H_kv * d, w.outlier_ppm)
+    sparse = 4 * (slabs * d * outlier_count(n, w.outlier_ppm) + w.B * n * v_out)
     return codes + sz + lowrank + sparse
 
 
@@ -67,7 +71,7 @@ def measure(w, steps, warmup, chunks, dev):
     pre_chunks = chunks if chunks >= 0 else (w.steps // w.n_b) // 2
     max_chunks = max(pre_chunks, 1)
     cfg = gb.make_config(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, w.n_b, w.n, max_chunks,
-                         max(w.rank, w.rank_chunk))
+                         max(w.rank, w.rank_chunk), flags=gb.GEAR_FLAG_V_FILTER_PER_HEAD if w.v_per_head else 0)
     K = gw.make_keys(w, w.n, 0, dev)
     V = gw.make_values(w, w.n, 0, dev)
     ib = gw.make_init_B(w, w.rank, 0, dev)
@@ -262,6 +266,10 @@ def main():
             mi = measure(wi, 3, 1, -1, dev)
             mi.pop("sample")
             per.append(summarize(mi))
+        for wi in gw.VARIANTS:                        # per-vector groups / per-head Value Filter
+            mi = measure(wi, 3, 1, -1, dev)
+            mi.pop("sample")
+            per.append(summarize(mi))
         res["per_config"] = per
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, *sample)
@@ -274,7 +282,7 @@ def _oracle_pass(args):
     from threadpoolctl import threadpool_limits
     from oracle import gear_oracle as go
     with threadpool_limits(limits=1):
-        oc = go.OracleCache(1, w.H_kv, w.H_q, w.d_h, w.bits, w.group, w.outlier_ppm)
+        oc = go.OracleCache(1, w.H_kv, w.H_q, w.d_h, w.bits, w.group, w.outlier_ppm, w.v_per_head)
         t0 = time.perf_counter()
         oc.compress(Kh, Vh, w.rank, w.iters, ibh)
         tc = time.perf_counter() - t0

@@ -46,6 +46,7 @@ class Workload:
     v_nu: int = 4
     seed: int = 0
     d_h: int = D_HEAD
+    v_per_head: bool = False   # Filter_s of the Values per head (group = 0 selects the per-vector grouping)
 
 
 # The five configurations of the benchmark definition (index = seed base).
@@ -63,6 +64,16 @@ CONFIGS = [
              rank=4, rank_chunk=2, n_b=20, steps=128, seed=4),
     Workload("c4L_llama3_8b_gqa_gearl", B=64, H_kv=8, H_q=32, n=8192, bits=2, group=64, outlier_ppm=0,
              rank=4, rank_chunk=2, n_b=20, steps=128, seed=4),
+]
+
+
+# Variants of the follow-up scope, measured beside the five configurations: the paper's 4-bit backbone
+# (per-vector groups, "KCVT") on the 13B layer shape, and the per-head Value Filter on the 7B layer shape.
+VARIANTS = [
+    Workload("c2_kcvt_4bit", B=32, H_kv=40, H_q=40, n=2048, bits=4, group=0, outlier_ppm=20000,
+             rank=4, rank_chunk=2, n_b=20, steps=128, k_out_channels=6, k_out_scale=(8.0, 25.0), v_nu=3, seed=2),
+    Workload("c1_v_filter_per_head", B=16, H_kv=32, H_q=32, n=4096, bits=2, group=64, outlier_ppm=20000,
+             rank=4, rank_chunk=2, n_b=20, steps=256, seed=1, v_per_head=True),
 ]
 
 
