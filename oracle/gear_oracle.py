@@ -387,6 +387,30 @@ class OracleCache:
         return out.astype(F16)
 
 
+def decode_attn_multi(cache: "OracleCache", q16, K_buf16, V_buf16, n_buf, causal=True):
+    """Eq. 1 for q_len query rows per head (chunked prefill, speculative decoding): the q_len
+    newest tokens are the last q_len of the n_buf buffer rows; every query attends to all
+    compressed rows, and query j (0-based) to buffer rows 0 .. n_buf - q_len + j when causal
+    (to all n_buf rows otherwise).  q16: fp16 [B,H_q,q_len,d] -> fp64 [B,H_q,q_len,d] (unrounded)."""
+    B, Hq, q_len, d = q16.shape
+    assert 1 <= q_len <= n_buf or not causal
+    Kh, Vh = cache.reconstruct() if cache.K else (np.zeros((B, cache.H_kv, 0, d)), np.zeros((B, cache.H_kv, 0, d)))
+    rep = cache.H_q // cache.H_kv
+    out = np.zeros((B, Hq, q_len, d), F64)
+    for j in range(q_len):
+        nb = n_buf - q_len + j + 1 if causal else n_buf
+        Kall = np.concatenate([Kh, K_buf16[:, :, :nb, :].astype(F64)], axis=2)
+        Vall = np.concatenate([Vh, V_buf16[:, :, :nb, :].astype(F64)], axis=2)
+        for b in range(B):
+            for i in range(Hq):
+                h = i // rep
+                s = (Kall[b, h] @ q16[b, i, j].astype(F64)) / np.sqrt(F64(d))
+                p = np.exp(s - s.max())
+                p /= p.sum()
+                out[b, i, j] = p @ Vall[b, h]
+    return out
+
+
 def compressed_bytes(n, d_h, H, bits, g, outlier_ppm, rank, index_bytes=2, v_per_head=False):
     """Byte accounting of one (b, all heads) compressed segment, K + V, against
     its fp16 size (the "KV size" column of Table 1; scale and zero-point in fp16

@@ -245,3 +245,32 @@ def test_streaming_segments_are_independent_compress_calls():
     assert seg.n == 20 and seg.scale.shape[2] == 1          # 20 < g: one short group per channel
     assert seg.mask.sum(axis=2).max() == 1                  # ceil(2% of 20) = 1 per channel (top only)
     assert X.shape == (2, 2, 20, 128)
+
+
+def test_multi_query_read_vs_masked_library_attention():
+    """The multi-query read against torch's attention in fp64 with an explicit mask over
+    [compressed rows | buffer rows], and its q_len = 1 case against the single-query read."""
+    import torch
+    rng = np.random.default_rng(21)
+    B, H, Hq, n, d, n_buf, q_len = 2, 2, 4, 37, 128, 9, 4
+    oc = go.OracleCache(B, H, Hq, d, 4, 64, 20000)
+    K = rng.standard_normal((B, H, n, d)).astype(np.float16)
+    V = rng.standard_normal((B, H, n, d)).astype(np.float16)
+    oc.compress(K, V, 2, 3, rng.uniform(-1, 1, (2, B, H, d, 2)).astype(np.float32))
+    Kb = rng.standard_normal((B, H, 12, d)).astype(np.float16)
+    Vb = rng.standard_normal((B, H, 12, d)).astype(np.float16)
+    q = rng.standard_normal((B, Hq, q_len, d)).astype(np.float16)
+    Kh, Vh = oc.reconstruct()
+    Kall = torch.from_numpy(np.concatenate([Kh, Kb[:, :, :n_buf].astype(np.float64)], axis=2)).repeat_interleave(2, dim=1)
+    Vall = torch.from_numpy(np.concatenate([Vh, Vb[:, :, :n_buf].astype(np.float64)], axis=2)).repeat_interleave(2, dim=1)
+    for causal in (True, False):
+        got = go.decode_attn_multi(oc, q, Kb, Vb, n_buf, causal)
+        mask = torch.ones(q_len, n + n_buf, dtype=torch.bool)
+        if causal:
+            for j in range(q_len):
+                mask[j, n + n_buf - q_len + j + 1:] = False
+        want = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q.astype(np.float64)), Kall, Vall,
+                                                                attn_mask=mask).numpy()
+        assert np.abs(got - want).max() < 1e-12
+    oc.decode_attn(q[:, :, :1], Kb, Vb, n_buf)
+    assert np.abs(go.decode_attn_multi(oc, q[:, :, :1], Kb, Vb, n_buf, True) - oc.last_attn_f64).max() < 1e-15
