@@ -132,10 +132,27 @@ def measure(w, steps, warmup, chunks, dev):
             t_dec.append(a.elapsed_time(b) * 1e-3)
             dec_bytes.append(comp_bytes + n_chunks * chunk_bytes + n_buf * row_bytes + qo_bytes)
     mean = lambda x: sum(x) / len(x)
+    # the multi-query read (q_len rows per head in one pass over the cache), with as many rows as fit the
+    # kernel's eight query columns per KV head; same replicas, same rotation
+    mq = None
+    q_len = 8 // (w.H_q // w.H_kv)
+    if q_len > 1:
+        qm = torch.randn(w.B, w.H_q, q_len, w.d_h, device=dev).to(torch.float16)
+        om = torch.empty_like(qm)
+        for i in range(3):
+            reps[i % NREP].decode_attn_mq(qm, Kb, Vb, w.n_b, True, om)
+        a, b = ev(), ev()
+        a.record()
+        for i in range(12):
+            reps[i % NREP].decode_attn_mq(qm, Kb, Vb, w.n_b, True, om)
+        b.record()
+        torch.cuda.synchronize()
+        tm = a.elapsed_time(b) * 1e-3 / 12
+        mq = {"q_len": q_len, "us": round(tm * 1e6, 2), "query_rows_per_s": round(w.B * q_len / tm, 1)}
     arena_bytes = pre.arena_bytes
     res = {"w": w, "wall": wall, "tc": mean(t_comp), "td": mean(t_dec), "tchunk": mean(t_chunk),
            "dec_bytes": mean(dec_bytes), "in_bytes": in_bytes, "comp_bytes": comp_bytes, "pre_chunks": pre_chunks,
-           "arena_bytes": arena_bytes, "sample": (K[:16].cpu(), V[:16].cpu(), ib[:, :16].cpu(), qs[0][:16].cpu())}
+           "arena_bytes": arena_bytes, "mq": mq, "sample": (K[:16].cpu(), V[:16].cpu(), ib[:, :16].cpu(), qs[0][:16].cpu())}
     del pre, reps, K, V, Kb, Vb, qs
     torch.cuda.empty_cache()
     return res
@@ -154,6 +171,8 @@ def summarize(m):
          "compressed_fraction_algorithmic": round(m["comp_bytes"] / m["in_bytes"], 4),
          "arena_fraction": round(m["arena_bytes"] / m["in_bytes"], 4)}
     d.update(bar_times(w, m["in_bytes"], m["comp_bytes"], m["dec_bytes"]))
+    if m.get("mq"):
+        d["decode_multi_query"] = m["mq"]
     return d
 
 

@@ -141,6 +141,22 @@ int gear_decode_attn(const gear_cache* cache, const void* q, const void* K_buf, 
                      void* stream);
 
 /*
+ * The same read for q_len query rows per head (chunked prefill, speculative decoding): the
+ * packed codes are unpacked once and feed all rows' products.  The q_len newest tokens are the
+ * last q_len of the n_buf buffer rows.  Every query attends to the whole compressed cache;
+ * with causal != 0 query row j (0-based) attends to the buffer rows 0 .. n_buf - q_len + j
+ * (Eq. 1 with the usual causal mask among the new tokens), otherwise to all n_buf rows.
+ * q, out    : device fp16 [B, H_q, q_len, d_h].
+ * q_len     : a power of two with q_len * (H_q / H_kv) <= 8 (longer blocks: several calls);
+ *             causal needs n_buf >= q_len.  Otherwise GEAR_EINVAL.
+ * workspace : the workspace of gear_cache_bytes; GEAR_ECAPACITY if the records of q_len rows do
+ *             not fit behind those of one (they do whenever rank_max > 0).
+ */
+int gear_decode_attn_mq(const gear_cache* cache, const void* q, int32_t q_len, int32_t causal,
+                        const void* K_buf, const void* V_buf, int32_t n_buf, void* out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * gear_decode_attn for callers that cannot allocate device memory or bring a
  * workspace along: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same computation, same kernels and same results as

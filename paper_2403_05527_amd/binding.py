@@ -15,7 +15,7 @@ GEAR_OK, GEAR_EINVAL, GEAR_ECAPACITY, GEAR_EALIGN, GEAR_EHIP = 0, -1, -2, -3, -4
 
 EXPORTED = [
     "gear_cache_bytes", "gear_cache_init", "gear_cache_reset", "gear_compress", "gear_decompress",
-    "gear_decode_attn", "gear_decode_attn_static", "gear_export_codes", "gear_export_sparse", "gear_export_sparse_coo", "gear_export_lowrank", "gear_strerror",
+    "gear_decode_attn", "gear_decode_attn_mq", "gear_decode_attn_static", "gear_export_codes", "gear_export_sparse", "gear_export_sparse_coo", "gear_export_lowrank", "gear_strerror",
 ]
 
 
@@ -64,6 +64,7 @@ def load_library():
     lib.gear_compress.argtypes = [cachep, vp, vp, i32, i32, i32, vp, ctypes.c_uint64, vp, sz, vp]
     lib.gear_decompress.argtypes = [cachep, vp, vp, vp]
     lib.gear_decode_attn.argtypes = [cachep, vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.gear_decode_attn_mq.argtypes = [cachep, vp, i32, i32, vp, vp, i32, vp, vp, sz, vp]
     lib.gear_decode_attn_static.argtypes = [cachep, vp, vp, vp, i32, vp, vp]
     lib.gear_export_codes.argtypes = [cachep, ctypes.c_int, vp, vp, vp, vp]
     lib.gear_export_sparse.argtypes = [cachep, ctypes.c_int, vp, vp, vp]
@@ -140,6 +141,13 @@ def gear_decode_attn(cache, q, K_buf, V_buf, n_buf, out, workspace):
            "gear_decode_attn")
 
 
+def gear_decode_attn_mq(cache, q, causal, K_buf, V_buf, n_buf, out, workspace):
+    _check(load_library().gear_decode_attn_mq(ctypes.byref(cache), _ptr(q), q.shape[2], 1 if causal else 0, _ptr(K_buf),
+                                              _ptr(V_buf), n_buf, _ptr(out), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream()),
+           "gear_decode_attn_mq")
+
+
 def gear_decode_attn_static(cache, q, K_buf, V_buf, n_buf, out):
     _check(load_library().gear_decode_attn_static(ctypes.byref(cache), _ptr(q), _ptr(K_buf), _ptr(V_buf), n_buf,
                                                   _ptr(out), _stream()), "gear_decode_attn_static")
@@ -213,6 +221,12 @@ class GearCache:
         if out is None:
             out = torch.empty_like(q)
         gear_decode_attn(self.cache, q, K_buf, V_buf, n_buf, out, self.workspace)
+        return out
+
+    def decode_attn_mq(self, q, K_buf, V_buf, n_buf, causal=True, out=None):
+        if out is None:
+            out = torch.empty_like(q)
+        gear_decode_attn_mq(self.cache, q, causal, K_buf, V_buf, n_buf, out, self.workspace)
         return out
 
     def export_codes(self, which):

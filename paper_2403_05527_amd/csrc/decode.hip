@@ -29,7 +29,8 @@ __global__ __launch_bounds__(256, ((BITS == 2 && (GQ <= 2 || (GQ == 4 && LG >= 6
                                                               const uint16_t* __restrict__ Kbuf,
                                                               const uint16_t* __restrict__ Vbuf, int n_buf,
                                                               int n_buf_cap, int nsplit, int pp, int rank_cap,
-                                                              int odd_rank, float* __restrict__ partial) {
+                                                              int odd_rank, int q_len, int causal,
+                                                              float* __restrict__ partial) {
   GEAR_DYN_LDS(smem_raw);
   const int slab = blockIdx.y, split = blockIdx.x;
   const int nrec = (int)gridDim.x;
@@ -40,7 +41,7 @@ __global__ __launch_bounds__(256, ((BITS == 2 && (GQ <= 2 || (GQ == 4 && LG >= 6
   const int wave = GEAR_WAVE_UNIFORM((int)(threadIdx.x >> 6));
   if (split == nrec - 1) {
     buffer_block<GQ>(*reinterpret_cast<TailSmem<GQ>*>(smem_raw), qg, Kbuf + (size_t)slab * n_buf_cap * D,
-                     Vbuf + (size_t)slab * n_buf_cap * D, n_buf, rec_base, rec_stride);
+                     Vbuf + (size_t)slab * n_buf_cap * D, n_buf, q_len, causal, rec_base, rec_stride);
     return;
   }
   // one call site: the prefill segment for every wave, or one chunk piece per wave
@@ -104,7 +105,8 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
 template <int BITS, int GQ, int LG>
 static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                                   const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
-                                  int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st) {
+                                  int n_buf_cap, int rank_cap, int q_len, int causal, uint16_t* out, float* partial,
+                                  hipStream_t st) {
   const int nsplit = (k0.n + MFMA_TS - 1) / MFMA_TS;
   const int pp = n_buf_cap > WTOK ? 2 : 1;            // pieces per chunk
   const int ncb = (cs.n_chunks * pp + 3) / 4;
@@ -126,7 +128,7 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
   }
   dim3 grid(nsplit + ncb + 1, dm.B * dm.H);
   hipLaunchKernelGGL((decode_split_kernel<BITS, GQ, LG>), grid, dim3(256), lds, st, dm, k0, v0, cs, q, Kbuf, Vbuf,
-                     n_buf, n_buf_cap, nsplit, pp, rc, odd_rank ? 1 : 0, partial);
+                     n_buf, n_buf_cap, nsplit, pp, rc, odd_rank ? 1 : 0, q_len, causal, partial);
   hipLaunchKernelGGL(decode_combine_kernel, dim3(dm.B * dm.Hq), dim3(128), 0, st, (const float*)partial,
                      nsplit + ncb + 1, out);
   return hipGetLastError();
@@ -135,12 +137,13 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
 template <int BITS>
 static hipError_t launch_decode_b(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                                   const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
-                                  int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st) {
+                                  int n_buf_cap, int rank_cap, int q_len, int causal, uint16_t* out, float* partial,
+                                  hipStream_t st) {
 #define GEAR_DECODE_CASE(GQV)                                                                                          \
   case GQV:                                                                                                            \
-    if (dm.g == 32) return launch_decode_t<BITS, GQV, 5>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st); \
-    if (dm.g == 64) return launch_decode_t<BITS, GQV, 6>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st); \
-    return launch_decode_t<BITS, GQV, 7>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
+    if (dm.g == 32) return launch_decode_t<BITS, GQV, 5>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, q_len, causal, out, partial, st); \
+    if (dm.g == 64) return launch_decode_t<BITS, GQV, 6>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, q_len, causal, out, partial, st); \
+    return launch_decode_t<BITS, GQV, 7>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, q_len, causal, out, partial, st);
   switch (dm.Hq / dm.H) {
     GEAR_DECODE_CASE(1)
     GEAR_DECODE_CASE(2)
@@ -151,11 +154,17 @@ static hipError_t launch_decode_b(const Dims& dm, const SegView& k0, const SegVi
 #undef GEAR_DECODE_CASE
 }
 
-hipError_t launch_decode(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
+// q_len query rows per query head ([B, H_q, q_len, 128]): the rows of the query heads of one KV head lie
+// next to each other, so they are run as (H_q / H) * q_len query columns of that KV head.
+hipError_t launch_decode(const Dims& dm_in, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                          const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
-                         int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st) {
-  if (dm.bits == 2) return launch_decode_b<2>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
-  return launch_decode_b<4>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, out, partial, st);
+                         int n_buf_cap, int rank_cap, int q_len, int causal, uint16_t* out, float* partial,
+                         hipStream_t st) {
+  Dims dm = dm_in;
+  dm.Hq = dm_in.Hq * q_len;
+  if (dm.bits == 2)
+    return launch_decode_b<2>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, q_len, causal, out, partial, st);
+  return launch_decode_b<4>(dm, k0, v0, cs, q, Kbuf, Vbuf, n_buf, n_buf_cap, rank_cap, q_len, causal, out, partial, st);
 }
 
 }  // namespace gear

@@ -36,11 +36,14 @@ __device__ __forceinline__ SegView chunk_view(const SegView& base, uint64_t stri
 }
 
 // Kb, Vb: the slab's buffer rows [n_buf][128] fp16.  Writes the record (m, l, o[128]) of each of
-// the GQ query heads; m = -inf, l = 0 when the buffer is empty.
+// the GQ query columns; m = -inf, l = 0 when a column sees no buffer row.  A column is one query
+// row of one query head: column hq holds query row hq % q_len, and with `causal` that query sees
+// the buffer rows 0 .. n_buf - q_len + hq % q_len only (the q_len newest tokens are the buffer's
+// last q_len rows); q_len = 1: the single-query read, every column sees all n_buf rows.
 template <int GQ>
 __device__ void buffer_block(TailSmem<GQ>& S, const uint16_t* __restrict__ qg, const uint16_t* __restrict__ Kb,
-                             const uint16_t* __restrict__ Vb, int n_buf, float* __restrict__ rec_base,
-                             int rec_stride) {
+                             const uint16_t* __restrict__ Vb, int n_buf, int q_len, int causal,
+                             float* __restrict__ rec_base, int rec_stride) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float scale = 0.08838834764831845f;  // 1/sqrt(128)
   for (int i = tid; i < GQ * D; i += 256) S.q[i / D][i % D] = h2f(qg[i]);
@@ -72,7 +75,8 @@ __device__ void buffer_block(TailSmem<GQ>& S, const uint16_t* __restrict__ qg, c
   float p[GQ];
 #pragma unroll
   for (int hq = 0; hq < GQ; ++hq) {
-    s[hq] = tid < n_buf ? s[hq] * scale : -INFINITY;
+    const int seen = causal ? n_buf - q_len + 1 + (hq & (q_len - 1)) : n_buf;   // q_len is a power of two
+    s[hq] = tid < seen ? s[hq] * scale : -INFINITY;
     const float mx = wave_max(s[hq]);
     if (lane == 0) S.red[hq][wave] = mx;
   }
@@ -80,7 +84,7 @@ __device__ void buffer_block(TailSmem<GQ>& S, const uint16_t* __restrict__ qg, c
 #pragma unroll
   for (int hq = 0; hq < GQ; ++hq) {
     const float m = fmaxf(fmaxf(S.red[hq][0], S.red[hq][1]), fmaxf(S.red[hq][2], S.red[hq][3]));
-    p[hq] = tid < n_buf ? __expf(s[hq] - m) : 0.0f;
+    p[hq] = s[hq] > -INFINITY ? __expf(s[hq] - m) : 0.0f;
     S.sc[hq][tid] = p[hq];
     if (tid == 0) S.stat[hq][0] = m;
   }

@@ -247,7 +247,7 @@ size_t decode_record_bytes(const gear_cache* cache) {
 }
 
 int decode_checked(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf, int32_t n_buf,
-                   void* out, float* partial, void* stream) {
+                   int q_len, int causal, void* out, float* partial, void* stream) {
   const gear_config& c = cache->cfg;
   const ArenaLayout a = arena_layout(c);
   const Dims dm = make_dims(c);
@@ -268,8 +268,8 @@ int decode_checked(const gear_cache* cache, const void* q, const void* K_buf, co
     cs.rank[j] = cache->chunk_rank[j];
   }
   GEAR_HIP(launch_decode(dm, k0, v0, cs, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(K_buf),
-                         static_cast<const uint16_t*>(V_buf), n_buf, c.n_buf_cap, c.rank_max, static_cast<uint16_t*>(out),
-                         partial, static_cast<hipStream_t>(stream)));
+                         static_cast<const uint16_t*>(V_buf), n_buf, c.n_buf_cap, c.rank_max, q_len, causal,
+                         static_cast<uint16_t*>(out), partial, static_cast<hipStream_t>(stream)));
   return GEAR_OK;
 }
 
@@ -409,7 +409,24 @@ int gear_decode_attn(const gear_cache* cache, const void* q, const void* K_buf, 
   if (!aligned16(workspace)) return GEAR_EALIGN;
   const WorkLayout w = work_layout(cache->cfg);
   if (workspace_bytes < w.bytes) return GEAR_ECAPACITY;
-  return decode_checked(cache, q, K_buf, V_buf, n_buf, out,
+  return decode_checked(cache, q, K_buf, V_buf, n_buf, 1, 0, out,
+                        reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dec), stream);
+}
+
+int gear_decode_attn_mq(const gear_cache* cache, const void* q, int32_t q_len, int32_t causal, const void* K_buf,
+                        const void* V_buf, int32_t n_buf, void* out, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  const int rc = check_decode_args(cache, q, K_buf, V_buf, n_buf, out);
+  if (rc) return rc;
+  const gear_config& c = cache->cfg;
+  if (q_len < 1 || !pow2(q_len) || q_len * (c.H_q / c.H_kv) > 8) return GEAR_EINVAL;
+  if (causal && n_buf < q_len) return GEAR_EINVAL;   // the q_len newest tokens are buffer rows
+  if (!workspace) return GEAR_EINVAL;
+  if (!aligned16(workspace)) return GEAR_EALIGN;
+  const WorkLayout w = work_layout(c);
+  // the records of all q_len rows; what follows them in the workspace is scratch of gear_compress
+  if (workspace_bytes < w.bytes || w.dec + decode_record_bytes(cache) * (size_t)q_len > w.bytes) return GEAR_ECAPACITY;
+  return decode_checked(cache, q, K_buf, V_buf, n_buf, q_len, causal ? 1 : 0, out,
                         reinterpret_cast<float*>(static_cast<char*>(workspace) + w.dec), stream);
 }
 
@@ -421,7 +438,7 @@ int gear_decode_attn_static(const gear_cache* cache, const void* q, const void* 
   void* sp = nullptr;
   const int rs = current_device_scratch(&sp);
   if (rs) return rs;
-  return decode_checked(cache, q, K_buf, V_buf, n_buf, out, static_cast<float*>(sp), stream);
+  return decode_checked(cache, q, K_buf, V_buf, n_buf, 1, 0, out, static_cast<float*>(sp), stream);
 }
 
 int gear_export_codes(const gear_cache* cache, int which, void* codes_u8, void* scale_f16, void* zero_f16,

@@ -43,9 +43,12 @@ hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& 
 constexpr int DECODE_TS = 256;           // rows per pass of the chunk / buffer path
 constexpr int DECODE_SPLIT = 512;        // prefill tokens per split block
 constexpr int DECODE_REC = 2 + D;        // floats per partial record: m, l, o[128]
+// q: [B, H_q, q_len, 128]; q_len a power of two with (H_q / H) * q_len <= 8; causal: query row j sees the buffer
+// rows 0 .. n_buf - q_len + j; partial: B * H_q * q_len * (records per row) * DECODE_REC floats
 hipError_t launch_decode(const Dims& dm, const SegView& k0, const SegView& v0, const ChunkSet& cs,
                          const uint16_t* q, const uint16_t* Kbuf, const uint16_t* Vbuf, int n_buf,
-                         int n_buf_cap, int rank_cap, uint16_t* out, float* partial, hipStream_t st);
+                         int n_buf_cap, int rank_cap, int q_len, int causal, uint16_t* out, float* partial,
+                         hipStream_t st);
 
 hipError_t launch_decompress(const Dims& dm, const SegView& ks, const SegView& vs, uint16_t* Kout,
                              uint16_t* Vout, int n_total, hipStream_t st);

@@ -306,3 +306,39 @@ def test_per_vector_groups_ties_and_constants():
     rep.update(pu.compare_decompress(gc, oc))
     rep.update(pu.compare_attention(gc, oc, gw.make_queries(w, 0, DEV)))
     say("  ->", rep)
+
+
+# ---- multi-query read (q_len query rows per head) ----
+@pytest.mark.parametrize("H_kv,H_q,q_len,causal", [(2, 2, 4, True), (2, 2, 8, True), (2, 4, 2, True), (2, 4, 4, False),
+                                                   (1, 4, 2, True), (3, 3, 1, True)])
+def test_multi_query_read(H_kv, H_q, q_len, causal):
+    """q_len query rows per head against the oracle's per-row attention: every row sees the whole compressed
+    cache (prefill + chunks) and, when causal, the buffer rows up to its own token."""
+    w = small_workload(B=2, H_kv=H_kv, H_q=H_q, n=700, bits=2, g=64, ppm=20000, rank=4, seed=500 + q_len + H_q)
+    gc, oc = pu.make_pair(w.B, H_kv, H_q, 2, 64, 20000, 20, w.n, 2, 4)
+    pu.compress_both(gc, oc, gw.make_keys(w, w.n, 0, DEV), gw.make_values(w, w.n, 0, DEV), 4, 3, gw.make_init_B(w, 4, 0, DEV))
+    for j in range(2):
+        pu.compress_both(gc, oc, gw.make_keys(w, 20, 1 + j, DEV), gw.make_values(w, 20, 1 + j, DEV), 2, 3,
+                         gw.make_init_B(w, 2, 1 + j, DEV))
+    Kb, Vb = gw.make_keys(w, 20, 50, DEV), gw.make_values(w, 20, 50, DEV)
+    g = torch.Generator(device="cpu").manual_seed(600 + q_len)
+    q = torch.randn(w.B, H_q, q_len, 128, generator=g).to(torch.float16).to(DEV)
+    for n_buf in (q_len, 13 if q_len <= 13 else 20, 20):
+        out = gc.decode_attn_mq(q, Kb, Vb, n_buf, causal)
+        want = pu.go.decode_attn_multi(oc, pu.np16(q), pu.np16(Kb), pu.np16(Vb), n_buf, causal)
+        rep = pu.check_attention(pu.np16(out), want, "multi-query attention")
+        say("  q_len", q_len, "heads", H_kv, H_q, "causal", causal, "n_buf", n_buf, "->", rep)
+    if q_len == 1:      # one row: the same launch as the single-query entry point
+        assert torch.equal(gc.decode_attn_mq(q, Kb, Vb, 7, True), gc.decode_attn(q, Kb, Vb, 7))
+
+
+def test_multi_query_read_argument_checks():
+    cfg = pu.gb.make_config(1, 2, 8, 2, 64, 0, 20, 64, 1, 0)
+    gc = pu.gb.GearCache(cfg, DEV)
+    gc.compress(torch.zeros(1, 2, 64, 128, dtype=torch.float16, device=DEV), torch.zeros(1, 2, 64, 128, dtype=torch.float16, device=DEV), 0, 3)
+    Kb = torch.zeros(1, 2, 20, 128, dtype=torch.float16, device=DEV)
+    for q_len, n_buf in ((3, 20), (4, 20), (2, 1)):      # not a power of two; 4 heads x 4 rows > 8 columns; fewer buffer rows than queries
+        q = torch.zeros(1, 8, q_len, 128, dtype=torch.float16, device=DEV)
+        with pytest.raises(pu.gb.GearError) as e:
+            gc.decode_attn_mq(q, Kb, Kb, n_buf, True)
+        assert e.value.status == pu.gb.GEAR_EINVAL
