@@ -121,6 +121,19 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
                   int32_t iters, const float* init_B, uint64_t seed, void* workspace,
                   size_t workspace_bytes, void* stream);
 
+/*
+ * gear_compress with the error-reduction (low-rank) term on the n_lowrank most recent tokens of
+ * the call only: the ablation of Sec. 4.3 that recovers the quantization error of the p % most
+ * recent prefill tokens (n_lowrank = ceil(p n / 100)).  SVDSolver runs on the residual rows of
+ * those tokens; the earlier tokens get A = 0, i.e. Filter and Quant only.  n_lowrank = n is
+ * gear_compress; n_lowrank = 0 stores the segment with rank 0.  (The other ablation of that
+ * section, error reduction on the prefill tokens only -- "GEAR-L Prefill" --, needs no entry
+ * point of its own: compress the flushed buffers with rank = 0.)
+ */
+int gear_compress_recent(gear_cache* cache, const void* K, const void* V, int32_t n, int32_t rank,
+                         int32_t iters, const float* init_B, uint64_t seed, int32_t n_lowrank,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* X-hat = D + A B^T + S for every stored token (Algorithm 1, "replace X with
  * D + L + S"), rounded to fp16.  K_out, V_out: device fp16
  * [B, H_kv, n_total, d_h]; either may be NULL. */

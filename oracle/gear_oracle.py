@@ -274,13 +274,16 @@ class Segment:
 
 def compress_tensor(X16: np.ndarray, kind: str, bits: int, g: int, outlier_ppm: int,
                     rank: int, iters: int, init_B: Optional[np.ndarray],
-                    mask: Optional[np.ndarray] = None, v_per_head: bool = False) -> Segment:
+                    mask: Optional[np.ndarray] = None, v_per_head: bool = False,
+                    n_lowrank: Optional[int] = None) -> Segment:
     """Algorithm 1, prefill-phase body for one tensor X in {K, V} (the decoding
     phase runs the same body on the buffered tokens):
       S = Filter_s(X); D-hat = Quant_b(X - S); R = X - D-hat - S;
       L_h = SVDSolver_r(R_h) for every head (and batch element).
     g = 0 selects the coarse per-vector grouping (one group per Key channel of the
-    call, one per Value token over all heads)."""
+    call, one per Value token over all heads).  n_lowrank: the ablation of Sec. 4.3 that
+    applies the low-rank approximation to the n_lowrank most recent tokens only
+    (SVDSolver on their residual rows; the earlier tokens get no low-rank term)."""
     assert X16.dtype == F16
     B, H, n, d = X16.shape
     if mask is None:       # a caller that holds only some heads passes the support it computed on all
@@ -305,11 +308,12 @@ def compress_tensor(X16: np.ndarray, kind: str, bits: int, g: int, outlier_ppm: 
     R = Y16.astype(F64) - Dh                                # = X - D-hat - S
     A16 = np.zeros((B, H, n, rank), F16)
     B16 = np.zeros((B, H, d, rank), F16)
-    if rank > 0:
+    first = 0 if n_lowrank is None else n - n_lowrank
+    if rank > 0 and first < n:
         for b in range(B):
             for h in range(H):
-                A, Bm = svd_solver(R[b, h], init_B[b, h], iters)
-                A16[b, h] = A.astype(F16)
+                A, Bm = svd_solver(R[b, h, first:], init_B[b, h], iters)
+                A16[b, h, first:] = A.astype(F16)
                 B16[b, h] = Bm.astype(F16)
     return Segment(kind, n, codes, scale, zero, mask, svals, A16, B16, ties)
 
@@ -339,15 +343,16 @@ class OracleCache:
     def n_total(self):
         return sum(s.n for s in self.K)
 
-    def compress(self, K16, V16, rank, iters, init_B, v_mask=None):
+    def compress(self, K16, V16, rank, iters, init_B, v_mask=None, n_lowrank=None):
         """Append one segment.  init_B: fp32 [2,B,H,d,rank] (index 0 = K, 1 = V).
         v_mask: optional precomputed support of S for V (used when this cache holds
         a subset of the heads: Filter ranks a Value token across all heads)."""
         iK = init_B[0] if rank > 0 else None
         iV = init_B[1] if rank > 0 else None
-        self.K.append(compress_tensor(K16, "K", self.bits, self.group, self.outlier_ppm, rank, iters, iK))
+        self.K.append(compress_tensor(K16, "K", self.bits, self.group, self.outlier_ppm, rank, iters, iK,
+                                      n_lowrank=n_lowrank))
         self.V.append(compress_tensor(V16, "V", self.bits, self.group, self.outlier_ppm, rank, iters, iV, v_mask,
-                                      self.v_per_head))
+                                      self.v_per_head, n_lowrank))
 
     def reconstruct(self):
         """(K-hat, V-hat) fp64 [B,H,n_total,d]."""

@@ -14,7 +14,7 @@ GEAR_STATIC_SCRATCH_BYTES = 32 << 20
 GEAR_OK, GEAR_EINVAL, GEAR_ECAPACITY, GEAR_EALIGN, GEAR_EHIP = 0, -1, -2, -3, -4
 
 EXPORTED = [
-    "gear_cache_bytes", "gear_cache_init", "gear_cache_reset", "gear_compress", "gear_decompress",
+    "gear_cache_bytes", "gear_cache_init", "gear_cache_reset", "gear_compress", "gear_compress_recent", "gear_decompress",
     "gear_decode_attn", "gear_decode_attn_mq", "gear_decode_attn_static", "gear_export_codes", "gear_export_sparse", "gear_export_sparse_coo", "gear_export_lowrank", "gear_strerror",
 ]
 
@@ -62,6 +62,7 @@ def load_library():
     lib.gear_cache_init.argtypes = [cfgp, vp, sz, cachep]
     lib.gear_cache_reset.argtypes = [cachep]
     lib.gear_compress.argtypes = [cachep, vp, vp, i32, i32, i32, vp, ctypes.c_uint64, vp, sz, vp]
+    lib.gear_compress_recent.argtypes = [cachep, vp, vp, i32, i32, i32, vp, ctypes.c_uint64, i32, vp, sz, vp]
     lib.gear_decompress.argtypes = [cachep, vp, vp, vp]
     lib.gear_decode_attn.argtypes = [cachep, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.gear_decode_attn_mq.argtypes = [cachep, vp, i32, i32, vp, vp, i32, vp, vp, sz, vp]
@@ -128,6 +129,14 @@ def gear_compress(cache, K, V, rank, iters, init_B, workspace, seed=0):
     _check(load_library().gear_compress(ctypes.byref(cache), _ptr(K), _ptr(V), n, rank, iters, _ptr(init_B),
                                         ctypes.c_uint64(seed), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
            "gear_compress")
+
+
+def gear_compress_recent(cache, K, V, rank, iters, init_B, n_lowrank, workspace, seed=0):
+    n = K.shape[2]
+    _check(load_library().gear_compress_recent(ctypes.byref(cache), _ptr(K), _ptr(V), n, rank, iters, _ptr(init_B),
+                                               ctypes.c_uint64(seed), n_lowrank, _ptr(workspace),
+                                               workspace.numel() * workspace.element_size(), _stream()),
+           "gear_compress_recent")
 
 
 def gear_decompress(cache, K_out, V_out):
@@ -206,8 +215,11 @@ class GearCache:
     def reset(self):
         gear_cache_reset(self.cache)
 
-    def compress(self, K, V, rank, iters=3, init_B=None, seed=0):
-        gear_compress(self.cache, K, V, rank, iters, init_B, self.workspace, seed)
+    def compress(self, K, V, rank, iters=3, init_B=None, seed=0, n_lowrank=None):
+        if n_lowrank is None:
+            gear_compress(self.cache, K, V, rank, iters, init_B, self.workspace, seed)
+        else:
+            gear_compress_recent(self.cache, K, V, rank, iters, init_B, n_lowrank, self.workspace, seed)
 
     def decompress(self):
         c = self.cfg

@@ -318,13 +318,17 @@ int gear_cache_reset(gear_cache* cache) {
   return GEAR_OK;
 }
 
-int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, int32_t rank, int32_t iters,
-                  const float* init_B, uint64_t seed, void* workspace, size_t workspace_bytes, void* stream) {
+int gear_compress_recent(gear_cache* cache, const void* K, const void* V, int32_t n, int32_t rank, int32_t iters,
+                         const float* init_B, uint64_t seed, int32_t n_lowrank, void* workspace, size_t workspace_bytes,
+                         void* stream) {
   int rc = check_cache(cache);
   if (rc) return rc;
   const gear_config& c = cache->cfg;
   if (!K || !V || !workspace) return GEAR_EINVAL;
   if (n < 1 || rank < 0 || rank > c.rank_max || iters < 1 || iters > 64) return GEAR_EINVAL;
+  if (n_lowrank < 0 || n_lowrank > n) return GEAR_EINVAL;
+  if (n_lowrank == 0) rank = 0;          // no token takes the low-rank term
+  const int t_lr = n - n_lowrank;
   if (!aligned16(K) || !aligned16(V) || !aligned16(workspace) || (init_B && !aligned16(init_B))) return GEAR_EALIGN;
   const bool first = cache->n_prefill == 0;
   if (first) {
@@ -366,10 +370,10 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   float* gram = reinterpret_cast<float*>(ws + w.gram);
   uint32_t* vsz = reinterpret_cast<uint32_t*>(ws + w.vsz);
   GEAR_HIP(launch_k_quant(Kp, ks, dm, n, thrK, pool_ctr, resid, st));
-  if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, ks, dm, n, iters, init_B, seed, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
+  if (rank > 0) GEAR_HIP(launch_power_iteration(true, resid, ks, dm, n, t_lr, iters, init_B, seed, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
   GEAR_HIP(launch_v_filter_quant(Vp, vs, dm, n, (kv_v + 1) / 2, kv_v / 2, thrV, vsz, pool_ctr + (size_t)c.B * c.H_kv, resid, st));
   if (rank > 0)
-    GEAR_HIP(launch_power_iteration(false, resid, vs, dm, n, iters, init_B, seed, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
+    GEAR_HIP(launch_power_iteration(false, resid, vs, dm, n, t_lr, iters, init_B, seed, Bcur, partial, Atmp, cmat, gram, w.gram_strips, st));
 
   if (first) {
     cache->n_prefill = n;
@@ -381,6 +385,11 @@ int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, in
   }
   cache->n_total += n;
   return GEAR_OK;
+}
+
+int gear_compress(gear_cache* cache, const void* K, const void* V, int32_t n, int32_t rank, int32_t iters,
+                  const float* init_B, uint64_t seed, void* workspace, size_t workspace_bytes, void* stream) {
+  return gear_compress_recent(cache, K, V, n, rank, iters, init_B, seed, n, workspace, workspace_bytes, stream);
 }
 
 int gear_decompress(const gear_cache* cache, void* K_out, void* V_out, void* stream) {

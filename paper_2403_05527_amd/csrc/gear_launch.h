@@ -36,7 +36,8 @@ int pi_padded_rank(int rank);
 int pi_gram_strips_max(int n_max, int slabs);
 // init_B: the whole start array [2 (K, V), B, H, 128, rank] (the launcher takes this tensor's half), or
 // nullptr: the same array is drawn from `seed` (start_entry in gear_internal.h)
-hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
+// t_lr: first token of the segment that takes part in the low-rank term (rows before it get A = 0)
+hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int t_lr, int iters,
                                   const float* init_B, uint64_t seed, float* Bcur, float* partial, float* Atmp, float* cmat,
                                   float* gram, int gram_strips_cap, hipStream_t st);
 

@@ -205,7 +205,7 @@ struct SweepSmem {
 template <bool IS_K, int R, bool LAST>
 __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, int pt, const uint16_t* __restrict__ Y,
                                               const uint32_t* __restrict__ sv_sz, const uint32_t* __restrict__ sv_codes,
-                                              int sv_n_cap, int sv_ng_cap, int g, int bits, int n,
+                                              int sv_n_cap, int sv_ng_cap, int g, int bits, int n, int t_lr,
                                               const float* __restrict__ Bcur, float* __restrict__ partial, int npart,
                                               float* __restrict__ Atmp) {
   float (&red)[4][D * R] = sm.red;
@@ -344,7 +344,8 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
       }
       // Keys: a row past the end has res = -zero-point, not 0; its a_t is dropped instead
       // (Values: the parameters of such rows are 0, so res is)
-      if (IS_K && partial_blk && t >= n) {
+      // rows before t_lr take no part in the low-rank term (error reduction on the most recent tokens only)
+      if ((IS_K && partial_blk && t >= n) || t < t_lr) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) bsel[nb] = 0.0f;
       }
@@ -413,11 +414,11 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
 
 template <bool IS_K, int R, bool LAST>
 __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_kernel(const uint16_t* __restrict__ Y, SegView sv, int g,
-                                                       int bits, int n, const float* __restrict__ Bcur,
+                                                       int bits, int n, int t_lr, const float* __restrict__ Bcur,
                                                        float* __restrict__ partial, int npart,
                                                        float* __restrict__ Atmp) {
   __shared__ SweepSmem<IS_K, R> sm;
-  pi_sweep_body<IS_K, R, LAST>(sm, blockIdx.y, blockIdx.x, Y, sv.sz, sv.codes, sv.n_cap, sv.ng_cap, g, bits, n, Bcur, partial,
+  pi_sweep_body<IS_K, R, LAST>(sm, blockIdx.y, blockIdx.x, Y, sv.sz, sv.codes, sv.n_cap, sv.ng_cap, g, bits, n, t_lr, Bcur, partial,
                                npart, Atmp);
 }
 
@@ -456,7 +457,7 @@ __global__ __launch_bounds__(256) void pi_finish_kernel(const float* __restrict_
 // grid (B*H), block 256.
 template <bool IS_K, int R>
 __global__ __launch_bounds__(256, 1) void pi_small_kernel(const uint16_t* __restrict__ Y, SegView sv, int g, int bits,
-                                                          int n, int iters, StartB sb,
+                                                          int n, int t_lr, int iters, StartB sb,
                                                           float* __restrict__ Bcur, float* __restrict__ partial,
                                                           float* __restrict__ Atmp, float* __restrict__ cmat) {
   __shared__ UpdateSmem<R> um;
@@ -473,10 +474,10 @@ __global__ __launch_bounds__(256, 1) void pi_small_kernel(const uint16_t* __rest
     int off = 0;
     GEAR_PIN_VGPR(off);
     if (last)
-      pi_sweep_body<IS_K, R, true>(ss, slab, 0, Y + off, sv.sz + off, sv.codes + off, sv.n_cap, sv.ng_cap, g, bits, n, Bcur,
+      pi_sweep_body<IS_K, R, true>(ss, slab, 0, Y + off, sv.sz + off, sv.codes + off, sv.n_cap, sv.ng_cap, g, bits, n, t_lr, Bcur,
                                    partial, 1, Atmp);
     else
-      pi_sweep_body<IS_K, R, false>(ss, slab, 0, Y + off, sv.sz + off, sv.codes + off, sv.n_cap, sv.ng_cap, g, bits, n, Bcur,
+      pi_sweep_body<IS_K, R, false>(ss, slab, 0, Y + off, sv.sz + off, sv.codes + off, sv.n_cap, sv.ng_cap, g, bits, n, t_lr, Bcur,
                                     partial, 1, Atmp);
     __syncthreads();
     pi_update_body<R>(um, slab, false, sb, sv.rank, partial, 1, (l == iters - 2) ? 1 : 0, last, Bcur, cmat, sv);
@@ -527,7 +528,7 @@ struct GramLoads {
 
 template <bool IS_K, int LG>   // LG: log2 of the Key group size (Values take the group size at run time)
 __global__ __launch_bounds__(256, 2) void pi_gram_kernel(const uint16_t* __restrict__ Y, SegView sv, int g, int bits, int n,
-                                                         int strip, float* __restrict__ gram_partial) {
+                                                         int t_lr, int strip, float* __restrict__ gram_partial) {
   __shared__ float red[GRAM_FLOATS];
   const int slab = blockIdx.y, sidx = blockIdx.x, nstrips = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -607,7 +608,8 @@ __global__ __launch_bounds__(256, 2) void pi_gram_kernel(const uint16_t* __restr
         }
       }
       // Keys: a row past the end has res = -zero-point, not 0 (Values: the parameters of such rows are 0)
-      if (IS_K && ragged && base + r0 + 16 * k >= n) {
+      // (rows before t_lr take no part in the low-rank term)
+      if ((IS_K && ragged && base + r0 + 16 * k >= n) || base + r0 + 16 * k < t_lr) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) res[e] = 0.0f;
       }
@@ -855,14 +857,14 @@ int pi_gram_strips_max(int n_max, int slabs) {
 }
 
 template <bool IS_K, int LG>
-static void launch_gram(const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int strip, int nstrips, float* gram,
+static void launch_gram(const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int t_lr, int strip, int nstrips, float* gram,
                         hipStream_t st) {
   // (per-vector grouping: the one Key group of a segment is addressed as a group of 32768 tokens)
-  hipLaunchKernelGGL((pi_gram_kernel<IS_K, LG>), dim3(nstrips, dm.B * dm.H), dim3(256), 0, st, Yf, sv, IS_K ? 1 << LG : dm.g, dm.bits, n, strip, gram);
+  hipLaunchKernelGGL((pi_gram_kernel<IS_K, LG>), dim3(nstrips, dm.B * dm.H), dim3(256), 0, st, Yf, sv, IS_K ? 1 << LG : dm.g, dm.bits, n, t_lr, strip, gram);
 }
 
 template <int R>
-static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
+static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int t_lr, int iters,
                          StartB sb, float* Bcur, float* partial, float* Atmp, float* cmat, float* gram,
                          int gram_strips_cap, hipStream_t st) {
   const int slabs = dm.B * dm.H;
@@ -870,9 +872,9 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
   const int g_eff = (is_k && dm.kcvt) ? 32768 : dm.g;   // per-vector grouping: one Key group per segment
   if (npart == 1) {   // a short segment: everything in one block per slab
     if (is_k)
-      hipLaunchKernelGGL((pi_small_kernel<true, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, iters, sb, Bcur, partial, Atmp, cmat);
+      hipLaunchKernelGGL((pi_small_kernel<true, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, t_lr, iters, sb, Bcur, partial, Atmp, cmat);
     else
-      hipLaunchKernelGGL((pi_small_kernel<false, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, iters, sb, Bcur, partial, Atmp, cmat);
+      hipLaunchKernelGGL((pi_small_kernel<false, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, t_lr, iters, sb, Bcur, partial, Atmp, cmat);
     return hipGetLastError();
   }
   // rounds 1 .. L-1: B <- (R^T R)^(L-1) B0 from one pass that forms the Gram matrix; then QR(B)
@@ -881,11 +883,11 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
     const int strip = pi_gram_strip(n, slabs);
     nstrips = (n + strip - 1) / strip;
     if (nstrips > gram_strips_cap) return hipErrorInvalidValue;
-    if (!is_k) launch_gram<false, 0>(Yf, sv, dm, n, strip, nstrips, gram, st);
-    else if (dm.kcvt) launch_gram<true, 15>(Yf, sv, dm, n, strip, nstrips, gram, st);
-    else if (dm.g == 32) launch_gram<true, 5>(Yf, sv, dm, n, strip, nstrips, gram, st);
-    else if (dm.g == 64) launch_gram<true, 6>(Yf, sv, dm, n, strip, nstrips, gram, st);
-    else launch_gram<true, 7>(Yf, sv, dm, n, strip, nstrips, gram, st);
+    if (!is_k) launch_gram<false, 0>(Yf, sv, dm, n, t_lr, strip, nstrips, gram, st);
+    else if (dm.kcvt) launch_gram<true, 15>(Yf, sv, dm, n, t_lr, strip, nstrips, gram, st);
+    else if (dm.g == 32) launch_gram<true, 5>(Yf, sv, dm, n, t_lr, strip, nstrips, gram, st);
+    else if (dm.g == 64) launch_gram<true, 6>(Yf, sv, dm, n, t_lr, strip, nstrips, gram, st);
+    else launch_gram<true, 7>(Yf, sv, dm, n, t_lr, strip, nstrips, gram, st);
   }
   {
     static bool lds_raised = false;   // per kernel instance (R)
@@ -902,9 +904,9 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
   {
     const dim3 grid(npart, slabs);
     if (is_k)
-      hipLaunchKernelGGL((pi_sweep_kernel<true, R, true>), grid, dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
+      hipLaunchKernelGGL((pi_sweep_kernel<true, R, true>), grid, dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, t_lr, (const float*)Bcur, partial, npart, Atmp);
     else
-      hipLaunchKernelGGL((pi_sweep_kernel<false, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, (const float*)Bcur, partial, npart, Atmp);
+      hipLaunchKernelGGL((pi_sweep_kernel<false, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, t_lr, (const float*)Bcur, partial, npart, Atmp);
     hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, 0, sb, sv.rank,
                        (const float*)partial, npart, 0, 1, Bcur, cmat, sv);
   }
@@ -915,16 +917,16 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
 
 int pi_padded_rank(int rank) { return rank <= 2 ? 2 : rank <= 4 ? 4 : 8; }
 
-hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int iters,
+hipError_t launch_power_iteration(bool is_k, const uint16_t* Yf, const SegView& sv, const Dims& dm, int n, int t_lr, int iters,
                                   const float* init_B, uint64_t seed, float* Bcur, float* partial, float* Atmp, float* cmat,
                                   float* gram, int gram_strips_cap, hipStream_t st) {
   // this tensor's part of the [2 (K, V), B, H, 128, rank] start array
   const uint64_t tensor_entries = (uint64_t)dm.B * dm.H * D * sv.rank;
   const StartB sb{init_B ? init_B + (is_k ? 0 : tensor_entries) : nullptr, seed, is_k ? 0 : tensor_entries};
   switch (pi_padded_rank(sv.rank)) {
-    case 2: return run_pi<2>(is_k, Yf, sv, dm, n, iters, sb, Bcur, partial, Atmp, cmat, gram, gram_strips_cap, st);
-    case 4: return run_pi<4>(is_k, Yf, sv, dm, n, iters, sb, Bcur, partial, Atmp, cmat, gram, gram_strips_cap, st);
-    default: return run_pi<8>(is_k, Yf, sv, dm, n, iters, sb, Bcur, partial, Atmp, cmat, gram, gram_strips_cap, st);
+    case 2: return run_pi<2>(is_k, Yf, sv, dm, n, t_lr, iters, sb, Bcur, partial, Atmp, cmat, gram, gram_strips_cap, st);
+    case 4: return run_pi<4>(is_k, Yf, sv, dm, n, t_lr, iters, sb, Bcur, partial, Atmp, cmat, gram, gram_strips_cap, st);
+    default: return run_pi<8>(is_k, Yf, sv, dm, n, t_lr, iters, sb, Bcur, partial, Atmp, cmat, gram, gram_strips_cap, st);
   }
 }
 

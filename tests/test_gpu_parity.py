@@ -342,3 +342,34 @@ def test_multi_query_read_argument_checks():
         with pytest.raises(pu.gb.GearError) as e:
             gc.decode_attn_mq(q, Kb, Kb, n_buf, True)
         assert e.value.status == pu.gb.GEAR_EINVAL
+
+
+# ---- error reduction on part of the tokens (the ablations of Sec. 4.3) ----
+@pytest.mark.parametrize("n,n_lowrank", [(600, 150), (600, 1), (600, 0), (600, 600), (200, 77)])
+def test_low_rank_on_recent_tokens_only(n, n_lowrank):
+    """gear_compress_recent: SVDSolver on the residual rows of the n_lowrank most recent tokens; earlier tokens get
+    A = 0.  n = 600 takes the Gram-matrix path, n = 200 the one-block path."""
+    w = small_workload(B=2, H_kv=2, H_q=4, n=n, bits=2, g=64, ppm=20000, rank=4, seed=700 + n_lowrank)
+    gc, oc = pu.make_pair(2, 2, 4, 2, 64, 20000, 20, n, 1, 4)
+    K, V = gw.make_keys(w, n, 0, DEV), gw.make_values(w, n, 0, DEV)
+    ib = gw.make_init_B(w, 4, 0, DEV)
+    gc.compress(K, V, 4, 3, ib, n_lowrank=n_lowrank)
+    oc.compress(pu.np16(K), pu.np16(V), 4, 3, pu.np16(ib), n_lowrank=n_lowrank)
+    rep = pu.compare_components(gc, oc)
+    rep.update(pu.compare_decompress(gc, oc))
+    if n_lowrank > 0:
+        rep.update(pu.compare_lowrank_product(gc, oc, 0))
+        A, _ = gc.export_lowrank(0, 0)
+        assert not A[:, :, :n - n_lowrank].any()
+    else:
+        assert gc.cache.rank_prefill == 0
+    rep.update(pu.compare_attention(gc, oc, gw.make_queries(w, 0, DEV)))
+    say("  ->", rep)
+
+
+def test_error_reduction_on_prefill_tokens_only():
+    """"GEAR-L Prefill": the flushed buffers are stored with rank 0 and without outliers' help from a low-rank term;
+    the decode kernel then mixes a rank-4 prefill segment with rank-0 chunks."""
+    import dataclasses
+    w = dataclasses.replace(small_workload(B=1, H_kv=4, H_q=8, n=530, bits=2, g=64, ppm=0, rank=4, seed=88), rank_chunk=0)
+    run_case(w, n_chunks=5)

@@ -274,3 +274,32 @@ def test_multi_query_read_vs_masked_library_attention():
         assert np.abs(got - want).max() < 1e-12
     oc.decode_attn(q[:, :, :1], Kb, Vb, n_buf)
     assert np.abs(go.decode_attn_multi(oc, q[:, :, :1], Kb, Vb, n_buf, True) - oc.last_attn_f64).max() < 1e-15
+
+
+def test_low_rank_term_on_the_most_recent_tokens_only():
+    """n_lowrank: codes on a lossless grid plus a rank-1 perturbation u v^T over ALL rows that leaves the
+    quantizer alone, so the residual is exactly u v^T.  The solver run on the recent rows must recover
+    u v^T there (rank 1 <= r is reproduced for any L) and leave the earlier rows without a low-rank term."""
+    rng = np.random.default_rng(31)
+    n, d, m, step = 96, 128, 40, 2.0 ** -10
+    k = rng.integers(1, 3, size=(1, 1, n, d))
+    k[:, :, 0::64, :] = 0
+    k[:, :, 1::64, :] = 3
+    u = rng.integers(-7, 8, size=(1, 1, n, 1)).astype(np.float64)
+    u[:, :, 0::64] = 0
+    u[:, :, 1::64] = 0
+    v = rng.integers(1, 3, size=(1, 1, 1, d)) * step
+    X = (-1.0 + 0.5 * k + u * v).astype(np.float16)
+    assert np.array_equal(X.astype(np.float64), -1.0 + 0.5 * k + u * v)
+    B0 = rng.uniform(-1, 1, (1, 1, d, 3)).astype(np.float32)
+    seg = go.compress_tensor(X, "K", 2, 64, 0, 3, 2, B0, n_lowrank=m)
+    L = np.einsum("bhnr,bhdr->bhnd", seg.A.astype(np.float64), seg.Bf.astype(np.float64))
+    assert not seg.A[:, :, :n - m].any() and np.abs(L[:, :, :n - m]).max() == 0.0
+    assert np.abs(L[:, :, n - m:] - (u * v)[:, :, n - m:]).max() <= 2e-3 * 14 * step
+    Xh = go.reconstruct_segment(seg, 64)
+    assert np.abs(Xh[:, :, :n - m] - (-1.0 + 0.5 * k[:, :, :n - m])).max() == 0.0       # Filter + Quant only
+    # n_lowrank = n is the plain call, n_lowrank = 0 has no low-rank term at all
+    full = go.compress_tensor(X, "K", 2, 64, 0, 3, 2, B0, n_lowrank=n)
+    plain = go.compress_tensor(X, "K", 2, 64, 0, 3, 2, B0)
+    assert np.array_equal(full.A, plain.A) and np.array_equal(full.Bf, plain.Bf)
+    assert not go.compress_tensor(X, "K", 2, 64, 0, 3, 2, B0, n_lowrank=0).A.any()
