@@ -82,10 +82,12 @@ def measure(w, steps, warmup, chunks, dev):
     out = torch.empty_like(qs[0])
     pre = gb.GearCache(cfg, dev)                 # target of the timed prefill compress
     reps = [gb.GearCache(cfg, dev) for _ in range(NREP)]   # caches the decode iterations read
+    n_lr = -(-w.n * w.lowrank_recent_pct // 100)       # prefill tokens that take the low-rank term (all of them by default)
+    n_lr = None if n_lr >= w.n else n_lr
     for r in reps:
-        r.compress(K, V, w.rank, w.iters, ib)
+        r.compress(K, V, w.rank, w.iters, ib, n_lowrank=n_lr)
         for _ in range(pre_chunks):
-            r.compress(Kb, Vb, w.rank_chunk, w.iters, ibc)
+            r.compress(Kb, Vb, w.rank_chunk, w.iters, ibc if w.rank_chunk > 0 else None)
     torch.cuda.synchronize()
 
     in_bytes = 2 * K.numel() * 2
@@ -99,7 +101,7 @@ def measure(w, steps, warmup, chunks, dev):
         e0, e1 = ev(), ev()
         pre.reset()
         e0.record()
-        pre.compress(K, V, w.rank, w.iters, ib)
+        pre.compress(K, V, w.rank, w.iters, ib, n_lowrank=n_lr)
         e1.record()
         devs = []
         for t in range(w.n_b):
@@ -111,7 +113,7 @@ def measure(w, steps, warmup, chunks, dev):
             devs.append((a, b, d.cache.n_chunks, t + 1))
         c0, c1 = ev(), ev()
         c0.record()
-        pre.compress(Kb, Vb, w.rank_chunk, w.iters, ibc)     # the flush: the buffer becomes a chunk of the fresh cache
+        pre.compress(Kb, Vb, w.rank_chunk, w.iters, ibc if w.rank_chunk > 0 else None)     # the flush: the buffer becomes a chunk of the fresh cache
         c1.record()
         return (e0, e1, devs, c0, c1) if record else None
 

@@ -47,6 +47,7 @@ class Workload:
     seed: int = 0
     d_h: int = D_HEAD
     v_per_head: bool = False   # Filter_s of the Values per head (group = 0 selects the per-vector grouping)
+    lowrank_recent_pct: int = 100   # low-rank term on this share of the prefill tokens, the most recent ones
 
 
 # The five configurations of the benchmark definition (index = seed base).
@@ -74,6 +75,12 @@ VARIANTS = [
              rank=4, rank_chunk=2, n_b=20, steps=128, k_out_channels=6, k_out_scale=(8.0, 25.0), v_nu=3, seed=2),
     Workload("c1_v_filter_per_head", B=16, H_kv=32, H_q=32, n=4096, bits=2, group=64, outlier_ppm=20000,
              rank=4, rank_chunk=2, n_b=20, steps=256, seed=1, v_per_head=True),
+    # the ablations on where the error reduction is applied: prefill tokens only (GEAR-L, flushed buffers with
+    # rank 0), and the most recent quarter of the prefill tokens only
+    Workload("c1_gearl_prefill_only", B=16, H_kv=32, H_q=32, n=4096, bits=2, group=64, outlier_ppm=0,
+             rank=4, rank_chunk=0, n_b=20, steps=256, seed=1),
+    Workload("c1_gearl_recent_25pct", B=16, H_kv=32, H_q=32, n=4096, bits=2, group=64, outlier_ppm=0,
+             rank=4, rank_chunk=2, n_b=20, steps=256, seed=1, lowrank_recent_pct=25),
 ]
 
 
