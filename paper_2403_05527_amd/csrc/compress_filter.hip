@@ -159,6 +159,89 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
   }
 }
 
+// ------------------------------------------------------------------ K select, vectors in registers
+// For segments of up to 8192 tokens: a block of eight waves takes eight neighbouring channels, one per
+// wave, and every wave ends up with its whole channel vector in registers (NC chunks of 512 keys, the
+// layout wave_select reads), so LDS only holds the histograms and a staging buffer and the occupancy no
+// longer falls with the segment length.  The vector arrives 1024 tokens at a time: thread tid loads the
+// 16-byte row pieces (8 channels) of rows 2 tid and 2 tid + 1, pairs the two rows' keys of each channel
+// in one word and writes it to stage[channel][tid]; wave w then reads channel w's 1024 keys back as two
+// 16-byte pieces per lane.  The next 1024 tokens' loads are in flight meanwhile.
+// 1-D grid of 16 * B*H blocks of 512 threads, decoded XCD-aware like k_select_kernel.
+template <int NC>
+__global__ __launch_bounds__(512, (NC <= 8 ? 4 : 2)) void k_select_reg_kernel(const uint16_t* __restrict__ K, int n, int nslab,
+                                                                            int k_top, int k_bot, ThreshPair* __restrict__ thrK,
+                                                                            uint32_t* __restrict__ zero, int zero_count,
+                                                                            uint32_t* __restrict__ ksz, int ng_cap, float qmax) {
+  __shared__ uint32_t hist[8 * SELECT_LDS_WORDS];
+  __shared__ __align__(16) uint32_t stage[8][512];
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < zero_count; i += gridDim.x * blockDim.x) zero[i] = 0u;
+  constexpr int ncb = D / 8;
+  int slab, cb;
+  if ((nslab & 7) == 0) {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    cb = j % ncb;
+    slab = (j / ncb) * 8 + xcd;
+  } else {
+    cb = blockIdx.x % ncb;
+    slab = blockIdx.x / ncb;
+  }
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // a view of the column block that ends with its last row: rows past n read as 0
+  const GEAR_BUF_T xb = GEAR_BUF_MAKE(K + (size_t)slab * n * D + cb * 8, (n - 1) * (D * 2) + 16);
+  uint4 x[NC];
+  uint4 ra = GEAR_BUF_LOAD16(xb, (2 * tid) * (D * 2)), rb = GEAR_BUF_LOAD16(xb, (2 * tid + 1) * (D * 2));
+#pragma unroll
+  for (int it = 0; it < NC / 2; ++it) {
+    uint4 na = make_uint4(0, 0, 0, 0), nb = na;
+    if (it + 1 < NC / 2 && (it + 1) * 1024 < n) {   // block-uniform
+      na = GEAR_BUF_LOAD16(xb, ((it + 1) * 1024 + 2 * tid) * (D * 2));
+      nb = GEAR_BUF_LOAD16(xb, ((it + 1) * 1024 + 2 * tid + 1) * (D * 2));
+    }
+    const uint32_t ka[4] = {key16x2(ra.x), key16x2(ra.y), key16x2(ra.z), key16x2(ra.w)};
+    const uint32_t kb[4] = {key16x2(rb.x), key16x2(rb.y), key16x2(rb.z), key16x2(rb.w)};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      stage[2 * j][tid] = GEAR_BYTE_PERM(kb[j], ka[j], 0x05040100u);       // channel 2j of rows 2 tid, 2 tid + 1
+      stage[2 * j + 1][tid] = GEAR_BYTE_PERM(kb[j], ka[j], 0x07060302u);   // channel 2j + 1
+    }
+    block_lds_sync();
+    x[2 * it] = *reinterpret_cast<const uint4*>(&stage[wave][lane * 4]);
+    x[2 * it + 1] = *reinterpret_cast<const uint4*>(&stage[wave][256 + lane * 4]);
+    block_lds_sync();
+    ra = na;
+    rb = nb;
+  }
+  RegSource<NC> src{x};
+  const Thresh th = wave_select(src, n, k_top, k_bot, hist + wave * SELECT_LDS_WORDS, true);
+  const int ch = cb * 8 + wave;
+  if (lane == 0) thrK[(size_t)slab * D + ch] = pack_thresh(th);
+  if (ksz) {   // per-vector grouping: the channel's (scale, zero), outliers counted as 0
+    const ThreshPair tp = pack_thresh(th);
+    uint32_t kmn = 0xFFFFu, kmx = 0u;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const uint32_t kw[4] = {x[c].x, x[c].y, x[c].z, x[c].w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t k = (e & 1) ? (kw[e >> 1] >> 16) : (kw[e >> 1] & 0xFFFFu), idx = (uint32_t)(c * 512 + lane * 8 + e);
+        if ((int)idx < n) {
+          const bool out = ((k << 16) | (0xFFFFu - idx)) >= tp.top || ((k << 16) | idx) < tp.bot;
+          const uint32_t y = out ? 0x8000u : k;
+          kmn = min(kmn, y);
+          kmx = max(kmx, y);
+        }
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      kmn = min(kmn, (uint32_t)__shfl_xor(kmn, o, 64));
+      kmx = max(kmx, (uint32_t)__shfl_xor(kmx, o, 64));
+    }
+    if (lane == 0) ksz[(size_t)slab * ng_cap * D + ch] = group_bits(make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), qmax));
+  }
+}
+
 // ------------------------------------------------------------------ K quant
 // grid (ceil(n/WT), B*H); block 256; WT = max(64, G) tokens per block (G = group size).
 // thread (r0 = tid/16, oc = tid%16) owns channels 8*oc..8*oc+7 of rows
@@ -434,8 +517,20 @@ static hipError_t launch_k_select_cb(const uint16_t* K, const Dims& dm, int n, i
   return hipGetLastError();
 }
 
+template <int NC>
+static hipError_t launch_k_select_reg(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
+                                      uint32_t* zero, int zero_count, const SegView& sv, hipStream_t st) {
+  hipLaunchKernelGGL(k_select_reg_kernel<NC>, dim3((D / 8) * dm.B * dm.H), dim3(512), 0, st, K, n, dm.B * dm.H, k_top, k_bot, thrK,
+                     zero, zero_count, dm.kcvt ? sv.sz : (uint32_t*)nullptr, sv.ng_cap, dm.qmax);
+  return hipGetLastError();
+}
+
 hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
                            uint32_t* zero, int zero_count, const SegView& sv, hipStream_t st) {
+  // segments of 1025 .. 8192 tokens: the channel vectors live in registers
+  if (n > 4096 && n <= 8192) return launch_k_select_reg<16>(K, dm, n, k_top, k_bot, thrK, zero, zero_count, sv, st);
+  if (n > 2048 && n <= 4096) return launch_k_select_reg<8>(K, dm, n, k_top, k_bot, thrK, zero, zero_count, sv, st);
+  if (n > 1024 && n <= 2048) return launch_k_select_reg<4>(K, dm, n, k_top, k_bot, thrK, zero, zero_count, sv, st);
   const int n_pad = (n + 7) & ~7;
   switch (k_select_cb(n_pad, dm.B * dm.H)) {
     case 128: return launch_k_select_cb<128>(K, dm, n, n_pad, k_top, k_bot, thrK, zero, zero_count, sv, st);
