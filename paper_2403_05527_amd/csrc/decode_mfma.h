@@ -198,6 +198,46 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk0, int 
   return L;
 }
 
+// q^T B_K for a rank whose row of B_K is one LDS read (R = 2, 4 or 8), added into SqB[hq * 8 + r]
+// (zero on entry).  Up to four query heads per pass, 64 / heads lanes each (whole rows of 16 lanes):
+// a lane sums its share of the 128 channels for all R ranks at once, the rows of 16 reduce R values
+// together, and the rows of one head meet in an LDS add (in a fixed lane order: the sum does not
+// vary from run to run).
+template <int GQ, int R>
+__device__ __forceinline__ void query_down_projection(const float* Sq, const uint16_t* Sbf, float* SqB, int lane) {
+  constexpr int HP = GQ < 4 ? GQ : 4;   // query heads per pass
+  constexpr int LPH = 64 / HP;          // lanes per head
+  constexpr int CPL = D / LPH;          // channels per lane
+  const int hl = lane / LPH, part = lane % LPH;
+#pragma unroll
+  for (int h0 = 0; h0 < GQ; h0 += HP) {
+    const int hq = h0 + hl;
+    float s[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) s[r] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) {
+      const int c = part + LPH * i;     // the lanes of a head read consecutive channels
+      const float qv = Sq[hq * D + c];
+      float b[R];
+      lds_row_f16<R>(Sbf + c * R, b);
+#pragma unroll
+      for (int r = 0; r < R; ++r) s[r] += qv * b[r];
+    }
+    if constexpr (R == 2) {
+      const float u = row16_sum2(s[0], s[1], lane);
+      if ((lane & 15) < 2) atomicAdd(&SqB[hq * 8 + (lane & 1)], u);
+    } else {
+      const float u = row16_sum4(s[0], s[1], s[2], s[3], lane);
+      if ((lane & 15) < 4) atomicAdd(&SqB[hq * 8 + (lane & 3)], u);
+      if constexpr (R == 8) {
+        const float u2 = row16_sum4(s[4], s[5], s[6], s[7], lane);
+        if ((lane & 15) < 4) atomicAdd(&SqB[hq * 8 + 4 + (lane & 3)], u2);
+      }
+    }
+  }
+}
+
 // Low-rank Key term of the rows lane and lane + 64 for a rank that is one LDS read per row:
 // score[row] += A_K[row] . (q^T B_K).
 // (REGS: the two rows as loaded by the lane itself; otherwise they are read from LDS)
@@ -455,22 +495,28 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     for (int rep = 0; rep < 2; ++rep) ellk[rep] = GEAR_BUF_LOAD16(ebuf, (lane + 64 * rep) * 16);
   }
 
-  // q^T B_K (down-projection of the low-rank Key term).  The GQ * rkp outputs (rkp = rank
-  // rounded up to a power of two) are spread over the 64 lanes, P lanes per output, each
-  // summing 128 / P channels; a butterfly over the P lanes finishes the sums.
+  // q^T B_K (down-projection of the low-rank Key term) into SqB[hq][r]
   if (rk > 0) {
-    const int lrk = rk <= 1 ? 0 : rk <= 2 ? 1 : rk <= 4 ? 2 : 3, rkp = 1 << lrk;
-    constexpr int LGQ = GQ == 1 ? 0 : GQ == 2 ? 1 : GQ == 4 ? 2 : 3;
     for (int i = lane; i < GQ * 8; i += 64) SqB[i] = 0.0f;   // slots r >= rk stay 0
     wave_lds_sync();
-    const int lP = 6 - LGQ - lrk, P = 1 << lP;   // 64 / (GQ * rkp)
-    const int outi = lane >> lP, part = lane & (P - 1);
-    const int hq = outi >> lrk, r = outi & (rkp - 1);
-    float s = 0.0f;
-    if (r < rk)
-      for (int c = part; c < D; c += P) s += Sq[hq * D + c] * h2f(Sbfk[c * rk + r]);
-    for (int o = 1; o < P; o <<= 1) s += __shfl_xor(s, o, 64);
-    if (part == 0) SqB[hq * 8 + r] = s;
+    if (rk == 4) query_down_projection<GQ, 4>(Sq, Sbfk, SqB, lane);
+    else if (rk == 2) query_down_projection<GQ, 2>(Sq, Sbfk, SqB, lane);
+    else if (rk == 8) query_down_projection<GQ, 8>(Sq, Sbfk, SqB, lane);
+    else {
+      // any other rank: the GQ * rkp outputs (rkp = rank rounded up to a power of two) are spread over
+      // the 64 lanes, P lanes per output, each summing 128 / P channels; a butterfly over the P lanes
+      // finishes the sums
+      const int lrk = rk <= 1 ? 0 : rk <= 2 ? 1 : rk <= 4 ? 2 : 3, rkp = 1 << lrk;
+      constexpr int LGQ = GQ == 1 ? 0 : GQ == 2 ? 1 : GQ == 4 ? 2 : 3;
+      const int lP = 6 - LGQ - lrk, P = 1 << lP;   // 64 / (GQ * rkp)
+      const int outi = lane >> lP, part = lane & (P - 1);
+      const int hq = outi >> lrk, r = outi & (rkp - 1);
+      float s = 0.0f;
+      if (r < rk)
+        for (int c = part; c < D; c += P) s += Sq[hq * D + c] * h2f(Sbfk[c * rk + r]);
+      for (int o = 1; o < P; o <<= 1) s += __shfl_xor(s, o, 64);
+      if (part == 0) SqB[hq * 8 + r] = s;
+    }
     wave_lds_sync();
   }
 
@@ -862,41 +908,84 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   block_lds_sync();
 
   // =================== merge the four waves' states, write the record ===================
+  // (an empty wave has m = -inf and weight 0; its plane, pm and wv hold zeros)
+  const bool one_b = shared_b && (rv == 0 || rv == 2 || rv == 4 || rv == 8);   // block-uniform: one B_V, one read per row
   for (int i = tid; i < GQ * D; i += 256) {
     const int hq = i / D, c = i % D, G = c >> lg;
-    float Mx = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) Mx = fmaxf(Mx, M.wstat[w][hq][0]);
-    float o = 0.0f, l = 0.0f;
+    float mw[4], lw[4], f[4];
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float mw = M.wstat[w][hq][0];
-      if (mw == -INFINITY) continue;
-      const float f = __expf(mw - Mx);
-      const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
-      float ow = plane[hq * OSP + c] + M.pm[w][hq][G];
-      const uint16_t* bfw = reinterpret_cast<const uint16_t*>(smem + L.bf + (shared_b ? L.bf_v0 : w * L.bf_cw + L.bf_vc));
-      const int rvw = GEAR_WAVE_UNIFORM(M.rv[w]);
-      const float* wvw = &M.wv[w][hq][0];
-      if (rvw == 4) {
-        float bb[4];
-        lds_row_f16<4>(bfw + c * 4, bb);
+      const float2 st = *reinterpret_cast<const float2*>(&M.wstat[w][hq][0]);
+      mw[w] = st.x;
+      lw[w] = st.y;
+    }
+    const float Mx = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ow += wvw[r] * bb[r];
-      } else if (rvw == 2) {
-        float bb[2];
-        lds_row_f16<2>(bfw + c * 2, bb);
-        ow += wvw[0] * bb[0] + wvw[1] * bb[1];
-      } else if (rvw == 8) {
-        float bb[8];
-        lds_row_f16<8>(bfw + c * 8, bb);
+    for (int w = 0; w < 4; ++w) f[w] = mw[w] == -INFINITY ? 0.0f : __expf(mw[w] - Mx);
+    float o = 0.0f, l = 0.0f;
+    if (one_b) {
+      // sum_w f_w (plane_w + pm_w) + B_V[c] . (sum_w f_w wv_w): every load is independent of the others
+      float t[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) ow += wvw[r] * bb[r];
-      } else {
-        for (int r = 0; r < rvw; ++r) ow += wvw[r] * h2f(bfw[c * rvw + r]);
+      for (int r = 0; r < 8; ++r) t[r] = 0.0f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
+        o += f[w] * (plane[hq * OSP + c] + M.pm[w][hq][G]);
+        l += f[w] * lw[w];
+        if (rv > 0) {
+          const float4 a = *reinterpret_cast<const float4*>(&M.wv[w][hq][0]);
+          t[0] += f[w] * a.x; t[1] += f[w] * a.y; t[2] += f[w] * a.z; t[3] += f[w] * a.w;
+        }
+        if (rv > 4) {
+          const float4 a = *reinterpret_cast<const float4*>(&M.wv[w][hq][4]);
+          t[4] += f[w] * a.x; t[5] += f[w] * a.y; t[6] += f[w] * a.z; t[7] += f[w] * a.w;
+        }
       }
-      o += f * ow;
-      l += f * M.wstat[w][hq][1];
+      if (rv == 4) {
+        float bb[4];
+        lds_row_f16<4>(Sbfv + c * 4, bb);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o += t[r] * bb[r];
+      } else if (rv == 2) {
+        float bb[2];
+        lds_row_f16<2>(Sbfv + c * 2, bb);
+        o += t[0] * bb[0] + t[1] * bb[1];
+      } else if (rv == 8) {
+        float bb[8];
+        lds_row_f16<8>(Sbfv + c * 8, bb);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) o += t[r] * bb[r];
+      }
+    } else {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        if (mw[w] == -INFINITY) continue;
+        const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
+        float ow = plane[hq * OSP + c] + M.pm[w][hq][G];
+        const uint16_t* bfw = reinterpret_cast<const uint16_t*>(smem + L.bf + (shared_b ? L.bf_v0 : w * L.bf_cw + L.bf_vc));
+        const int rvw = GEAR_WAVE_UNIFORM(M.rv[w]);
+        const float* wvw = &M.wv[w][hq][0];
+        if (rvw == 4) {
+          float bb[4];
+          lds_row_f16<4>(bfw + c * 4, bb);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ow += wvw[r] * bb[r];
+        } else if (rvw == 2) {
+          float bb[2];
+          lds_row_f16<2>(bfw + c * 2, bb);
+          ow += wvw[0] * bb[0] + wvw[1] * bb[1];
+        } else if (rvw == 8) {
+          float bb[8];
+          lds_row_f16<8>(bfw + c * 8, bb);
+#pragma unroll
+          for (int r = 0; r < 8; ++r) ow += wvw[r] * bb[r];
+        } else {
+          for (int r = 0; r < rvw; ++r) ow += wvw[r] * h2f(bfw[c * rvw + r]);
+        }
+        o += f[w] * ow;
+        l += f[w] * lw[w];
+      }
     }
     float* rec = rec_base + (size_t)hq * rec_stride;
     rec[2 + c] = o;
