@@ -24,7 +24,7 @@ static_assert(MFMA_TS == DECODE_SPLIT, "split size is part of the workspace layo
 // rows of one chunk, pp pieces per chunk), through the same code as the prefill; the
 // last block: the fp16 streaming-buffer rows.
 template <int BITS, int GQ, int LG>
-__global__ __launch_bounds__(256, ((BITS == 2 && (GQ <= 2 || (GQ == 4 && LG >= 6))) ? 5 : 4)) void decode_split_kernel(Dims dm, SegView k0, SegView v0, ChunkSet cs,
+__global__ __launch_bounds__(256, (GQ == 8 ? 3 : (BITS == 2 && (GQ <= 2 || (GQ == 4 && LG >= 6))) ? 5 : 4)) void decode_split_kernel(Dims dm, SegView k0, SegView v0, ChunkSet cs,
                                                               const uint16_t* __restrict__ q,
                                                               const uint16_t* __restrict__ Kbuf,
                                                               const uint16_t* __restrict__ Vbuf, int n_buf,

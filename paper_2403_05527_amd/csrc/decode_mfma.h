@@ -99,6 +99,36 @@ __device__ __forceinline__ void lds_row_f16(const uint16_t* p, float* a) {
   }
 }
 
+// N consecutive floats in LDS (N = 1, 2, 4 or 8; p aligned to 4 N bytes, to 16 for N = 8): one access, two for N = 8.
+template <int N>
+__device__ __forceinline__ void lds_load_f(const float* p, float (&v)[N]) {
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "a power of two up to 8");
+  if constexpr (N == 1) {
+    v[0] = p[0];
+  } else if constexpr (N == 2) {
+    const float2 t = *reinterpret_cast<const float2*>(p);
+    v[0] = t.x; v[1] = t.y;
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; i += 4) {
+      const float4 t = *reinterpret_cast<const float4*>(p + i);
+      v[i] = t.x; v[i + 1] = t.y; v[i + 2] = t.z; v[i + 3] = t.w;
+    }
+  }
+}
+template <int N>
+__device__ __forceinline__ void lds_store_f(float* p, const float (&v)[N]) {
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "a power of two up to 8");
+  if constexpr (N == 1) {
+    p[0] = v[0];
+  } else if constexpr (N == 2) {
+    *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; i += 4) *reinterpret_cast<float4*>(p + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+  }
+}
+
 // Position of Key channel ch (r = ch % 32 inside lane group ch / 32) in the B
 // operand: fp16 index (0..31) within the lane's 4 k-blocks x 8 slots, and the
 // bit shift of its pair.
@@ -135,17 +165,17 @@ __device__ __forceinline__ void val_slot(int t, int& kg, int& idx, int& lg) {
 // LDS layout of one MFMA block (byte offsets into dynamic shared memory)
 // ---------------------------------------------------------------------------
 constexpr int WTOK = 128;  // tokens per wave
-// Row strides of the per-wave LDS arrays, padded by 8 entries: rows (query heads, operand columns)
-// that are read or written by different lanes of one instruction then start in different banks.
-constexpr int SCP = WTOK + 8;   // score / probability plane of one query head (floats)
-constexpr int OSP = D + 8;      // output plane of one query head (floats)
+// The per-wave float arrays keep the GQ query heads of one row (token, channel) next to each other:
+// q[c][hq], score / probability [row][hq], output plane [c][hq], so one LDS access serves all
+// heads of a row.  The operand columns are padded by 8 entries: columns that are read by
+// different lanes of one instruction then start in different banks.
 constexpr int KOP = D + 8;      // Key-side operand column (fp16)
 __host__ __device__ constexpr int vop(int tb) { return tb + 8; }   // Value-side operand row of a tb-token code block (fp16)
 struct MfmaLayout {
   int q, misc;                                 // shared by the four waves
   int bf, bf_v0, bf_cw, bf_vc;                 // B factors: one (K, V) pair for the block, or one per wave (chunks)
   int wave0, wave_stride;                      // per-wave region
-  int sc, szk, szv, ak, av, osp, opnd, qb;     // offsets inside a wave region
+  int sc, szv, ak, av, osp, opnd, qb;          // offsets inside a wave region
   int total;
 };
 template <int GQ>
@@ -183,15 +213,14 @@ __host__ __device__ inline MfmaLayout mfma_layout(int bits, int g, int rk0, int 
   }
   L.wave0 = o;
   int w = 0;
-  L.sc = w; w += GQ * SCP * 4;
-  L.szk = w; w += (WTOK >> lg) * D * 4;
+  L.sc = w; w += GQ * WTOK * 4;
   L.szv = w; w += WTOK * NG * 4;
   L.ak = w; w += mfma_rows_in_lds<GQ>(odd_rank) ? up16i(WTOK * rk * 2) : 0;
   L.av = w; w += mfma_rows_in_lds<GQ>(odd_rank) ? up16i(WTOK * rv * 2) : 0;
   int oh = 2 * GQ * KOP;
   if (NG * 2 * GQ * vop(TB) > oh) oh = NG * 2 * GQ * vop(TB);
   L.opnd = w; w += oh * 2;
-  L.osp = L.opnd;   // the output plane (GQ * OSP floats <= the operand area) is written after the last operand was read
+  L.osp = L.opnd;   // the output plane (GQ * 128 floats <= the operand area) is written after the last operand was read
   L.qb = w; w += GQ * 8 * 4;
   L.wave_stride = up16i(w);
   L.total = L.wave0 + 4 * L.wave_stride;
@@ -218,7 +247,7 @@ __device__ __forceinline__ void query_down_projection(const float* Sq, const uin
 #pragma unroll
     for (int i = 0; i < CPL; ++i) {
       const int c = part + LPH * i;     // the lanes of a head read consecutive channels
-      const float qv = Sq[hq * D + c];
+      const float qv = Sq[c * GQ + hq];
       float b[R];
       lds_row_f16<R>(Sbf + c * R, b);
 #pragma unroll
@@ -238,8 +267,8 @@ __device__ __forceinline__ void query_down_projection(const float* Sq, const uin
   }
 }
 
-// Low-rank Key term of the rows lane and lane + 64 for a rank that is one LDS read per row:
-// score[row] += A_K[row] . (q^T B_K).
+// Low-rank Key term of the rows lane and lane + 64 (their scores sc[rep][hq] are in registers) for a
+// rank that is one LDS read per row: score[row] += A_K[row] . (q^T B_K).
 // (REGS: the two rows as loaded by the lane itself; otherwise they are read from LDS)
 template <int R>
 __device__ __forceinline__ void reg_row_f16(const uint4& v, float* a) {
@@ -251,8 +280,8 @@ __device__ __forceinline__ void reg_row_f16(const uint4& v, float* a) {
   }
 }
 template <int GQ, int R, bool REGS>
-__device__ __forceinline__ void lowrank_key_rows(const uint16_t* Sak, const uint4 (&regs)[2], const float* SqB, float* Ssc,
-                                                 int lane, int nw) {
+__device__ __forceinline__ void lowrank_key_rows(const uint16_t* Sak, const uint4 (&regs)[2], const float* SqB,
+                                                 float (&sc)[2][GQ], int lane, int nw) {
 #pragma unroll
   for (int rep = 0; rep < 2; ++rep) {
     const int row = lane + 64 * rep;
@@ -262,18 +291,19 @@ __device__ __forceinline__ void lowrank_key_rows(const uint16_t* Sak, const uint
       else lds_row_f16<R>(Sak + row * R, a);
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
-        float s = Ssc[hq * SCP + row];
+        float s = sc[rep][hq];
 #pragma unroll
         for (int r = 0; r < R; ++r) s += SqB[hq * 8 + r] * a[r];
-        Ssc[hq * SCP + row] = s;
+        sc[rep][hq] = s;
       }
     }
   }
 }
-// p^T A_V over the wave's rows for such a rank, added into wv[hq * 8 + r] (zero on entry).
+// p^T A_V over the wave's rows (probabilities pr[rep][hq] of rows lane, lane + 64 in registers) for such a
+// rank, added into wv[hq * 8 + r] (zero on entry).
 template <int GQ, int R, bool REGS>
-__device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const uint4 (&regs)[2], const float* Ssc, float* wv,
-                                                   int lane, int nw) {
+__device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const uint4 (&regs)[2], const float (&pr)[2][GQ],
+                                                   float* wv, int lane, int nw) {
   float part[GQ][R];
 #pragma unroll
   for (int hq = 0; hq < GQ; ++hq)
@@ -288,7 +318,7 @@ __device__ __forceinline__ void lowrank_value_down(const uint16_t* Sav, const ui
       else lds_row_f16<R>(Sav + row * R, a);
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
-        const float p = Ssc[hq * SCP + row];
+        const float p = pr[rep][hq];
 #pragma unroll
         for (int r = 0; r < R; ++r) part[hq][r] += p * a[r];
       }
@@ -344,17 +374,16 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const int rk = ks.rank, rv = vs.rank;
   const MfmaLayout L = mfma_layout<GQ>(BITS, g, rk0, rv0, rc, dm.ppm, odd_rank);
   const bool rows_lds = mfma_rows_in_lds<GQ>(odd_rank);   // compile-time true for fewer than four query heads
-  float* Sq = reinterpret_cast<float*>(smem + L.q);                 // [GQ][128]
+  float* Sq = reinterpret_cast<float*>(smem + L.q);                 // [128][GQ]
   MfmaMisc<GQ>& M = *reinterpret_cast<MfmaMisc<GQ>*>(smem + L.misc);
   unsigned char* wbase = smem + L.wave0 + (size_t)wave * L.wave_stride;
-  float* Ssc = reinterpret_cast<float*>(wbase + L.sc);              // [GQ][128] raw scores, then p
-  uint32_t* Sszk = reinterpret_cast<uint32_t*>(wbase + L.szk);      // [128/g][128]
+  float* Ssc = reinterpret_cast<float*>(wbase + L.sc);              // [128][GQ] raw scores, then p
   uint32_t* Sszv = reinterpret_cast<uint32_t*>(wbase + L.szv);      // [128][NG]
   uint16_t* Sak = reinterpret_cast<uint16_t*>(wbase + L.ak);        // [128][rk]
   uint16_t* Sav = reinterpret_cast<uint16_t*>(wbase + L.av);
   uint16_t* Sbfk = reinterpret_cast<uint16_t*>(smem + L.bf + (shared_b ? 0 : wave * L.bf_cw));   // [128][rk]
   uint16_t* Sbfv = reinterpret_cast<uint16_t*>(smem + L.bf + (shared_b ? L.bf_v0 : wave * L.bf_cw + L.bf_vc));
-  float* Sosp = reinterpret_cast<float*>(wbase + L.osp);            // [GQ][128] this wave's output plane (shares the operand area)
+  float* Sosp = reinterpret_cast<float*>(wbase + L.osp);            // [128][GQ] this wave's output plane (shares the operand area)
   _Float16* opnd = reinterpret_cast<_Float16*>(wbase + L.opnd);
   float* SqB = reinterpret_cast<float*>(wbase + L.qb);              // [GQ][8] q^T B_K
   const float scale = 0.08838834764831845f;  // 1/sqrt(128)
@@ -405,14 +434,22 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const bool stage_b = shared_b ? wave == 0 : nw > 0;   // a prefill block's first wave always owns rows
   const int n4_bk = stage_b ? 16 * rk : 0, n4_bv = stage_b ? 16 * rv : 0;   // 128 * rank fp16
   // (per-vector grouping: a segment's one Key group, and the wave's 128 rows lie in it)
-  const uint4* g_szk = reinterpret_cast<const uint4*>(ks.sz + ((size_t)slab * ks.ng_cap + (dm.kcvt ? 0 : tw0 >> lg)) * D);
+  const uint32_t* g_szk = reinterpret_cast<const uint32_t*>(ks.sz + ((size_t)slab * ks.ng_cap + (dm.kcvt ? 0 : tw0 >> lg)) * D);
   const uint4* g_szv = reinterpret_cast<const uint4*>(vs.sz + ((size_t)slab * vs.n_cap + tw0) * NG);
   const uint4* g_ak = reinterpret_cast<const uint4*>(ks.A + ((size_t)slab * ks.n_cap + tw0) * rk);
   const uint4* g_av = reinterpret_cast<const uint4*>(vs.A + ((size_t)slab * vs.n_cap + tw0) * rv);
   const uint4* g_bk = reinterpret_cast<const uint4*>(ks.Bf + (size_t)slab * D * rk);
   const uint4* g_bv = reinterpret_cast<const uint4*>(vs.Bf + (size_t)slab * D * rv);
   // piece lane of each array; pieces 64.. (g = 32, rank 8) follow after the first
-  const uint4 r_szk = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_szk, n4_szk * 16), lane * 16);
+  // Key (scale, zero) of channels lane and lane + 64 in each of the wave's groups: straight into registers
+  uint32_t szk_r[WTOK >> LG][2];
+  {
+    const GEAR_BUF_T zbuf = GEAR_BUF_MAKE(g_szk, n4_szk * 16);   // groups past the wave's last row read as 0
+#pragma unroll
+    for (int gw = 0; gw < (WTOK >> LG); ++gw)
+#pragma unroll
+      for (int rep = 0; rep < 2; ++rep) szk_r[gw][rep] = GEAR_BUF_LOAD4(zbuf, (gw * D + lane + 64 * rep) * 4);
+  }
   const uint4 r_szv = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_szv, n4_szv * 16), lane * 16);
   const uint4 r_ak = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_ak, n4_ak * 16), lane * 16);
   const uint4 r_av = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_av, n4_av * 16), lane * 16);
@@ -461,20 +498,19 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
     const int i = tid + 256 * k;
-    if (i < GQ * D / 2) {
-      Sq[2 * i] = h2f(qreg[k] & 0xFFFFu);
-      Sq[2 * i + 1] = h2f(qreg[k] >> 16);
+    if (i < GQ * D / 2) {   // channels c, c + 1 of query head hq
+      const int hq = i / (D / 2), c = 2 * (i % (D / 2));
+      Sq[c * GQ + hq] = h2f(qreg[k] & 0xFFFFu);
+      Sq[(c + 1) * GQ + hq] = h2f(qreg[k] >> 16);
     }
   }
-  if (lane < n4_szk) reinterpret_cast<uint4*>(Sszk)[lane] = r_szk;
   if (lane < n4_szv) reinterpret_cast<uint4*>(Sszv)[lane] = r_szv;
   if (lane < n4_ak) reinterpret_cast<uint4*>(Sak)[lane] = r_ak;
   if (lane < n4_av) reinterpret_cast<uint4*>(Sav)[lane] = r_av;
   if (lane < n4_bk) reinterpret_cast<uint4*>(Sbfk)[lane] = r_bk;
   if (lane < n4_bv) reinterpret_cast<uint4*>(Sbfv)[lane] = r_bv;
-  if (n4_szk > 64 || n4_szv > 64 || n4_ak > 64 || n4_av > 64 || n4_bk > 64 || n4_bv > 64) {   // wave-uniform: second pieces
+  if (n4_szv > 64 || n4_ak > 64 || n4_av > 64 || n4_bk > 64 || n4_bv > 64) {   // wave-uniform: second pieces
     const int j = lane + 64;
-    if (j < n4_szk) reinterpret_cast<uint4*>(Sszk)[j] = g_szk[j];
     if (j < n4_szv) reinterpret_cast<uint4*>(Sszv)[j] = g_szv[j];
     if (j < n4_ak) reinterpret_cast<uint4*>(Sak)[j] = g_ak[j];
     if (j < n4_av) reinterpret_cast<uint4*>(Sav)[j] = g_av[j];
@@ -513,7 +549,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       const int hq = outi >> lrk, r = outi & (rkp - 1);
       float s = 0.0f;
       if (r < rk)
-        for (int c = part; c < D; c += P) s += Sq[hq * D + c] * h2f(Sbfk[c * rk + r]);
+        for (int c = part; c < D; c += P) s += Sq[c * GQ + hq] * h2f(Sbfk[c * rk + r]);
       for (int o = 1; o < P; o <<= 1) s += __shfl_xor(s, o, 64);
       if (part == 0) SqB[hq * 8 + r] = s;
     }
@@ -531,6 +567,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     kslot[rep] = (ch >> 5) * 32 + idx;
     kscale[rep] = opscale(lg);
   }
+#pragma unroll
   for (int gw = 0; gw < (WTOK >> lg); ++gw) {
     if (gw * g >= nw) break;                        // wave-uniform
     float kb[GQ];
@@ -539,13 +576,15 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
 #pragma unroll
     for (int rep = 0; rep < 2; ++rep) {
       const int ch = lane + 64 * rep;
-      const uint32_t sb = Sszk[gw * D + ch];
+      const uint32_t sb = szk_r[gw][rep];
       const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
       const float os = kscale[rep];
       _Float16* dst = opnd + kslot[rep];
+      float qh[GQ];
+      lds_load_f<GQ>(Sq + ch * GQ, qh);
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
-        const float qv = Sq[hq * D + ch];
+        const float qv = qh[hq];
         const float w = qv * delta * os;
         const _Float16 hi = (_Float16)w;
         const _Float16 lo = (_Float16)(w - (float)hi);
@@ -593,74 +632,28 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           }
         }
         // D[col 4*kg + i][token n16]: the hi and lo columns of a query head sit in one lane
-        if (hq0 < GQ) Ssc[hq0 * SCP + 16 * mt + n16] = (acc[0] + acc[1]) * MFMA_OUT_SCALE + kb0;
-        if (hq1 < GQ) Ssc[hq1 * SCP + 16 * mt + n16] = (acc[2] + acc[3]) * MFMA_OUT_SCALE + kb1;
+        const float s0 = (acc[0] + acc[1]) * MFMA_OUT_SCALE + kb0, s1 = (acc[2] + acc[3]) * MFMA_OUT_SCALE + kb1;
+        if constexpr (GQ == 1) {
+          if (kg == 0) Ssc[16 * mt + n16] = s0;
+        } else {
+          if (hq0 < GQ) *reinterpret_cast<float2*>(&Ssc[(16 * mt + n16) * GQ + hq0]) = make_float2(s0, s1);
+        }
       }
     }
     wave_lds_sync();
   }
 
-  // low-rank Key term: lane handles rows lane and lane + 64
-  if (rk == 4) {
-    if (rows_lds) lowrank_key_rows<GQ, 4, false>(Sak, akr, SqB, Ssc, lane, nw);
-    else lowrank_key_rows<GQ, 4, true>(Sak, akr, SqB, Ssc, lane, nw);
-    wave_lds_sync();
-  } else if (rk == 2) {
-    if (rows_lds) lowrank_key_rows<GQ, 2, false>(Sak, akr, SqB, Ssc, lane, nw);
-    else lowrank_key_rows<GQ, 2, true>(Sak, akr, SqB, Ssc, lane, nw);
-    wave_lds_sync();
-  } else if (rk == 8) {
-    if (rows_lds) lowrank_key_rows<GQ, 8, false>(Sak, akr, SqB, Ssc, lane, nw);
-    else lowrank_key_rows<GQ, 8, true>(Sak, akr, SqB, Ssc, lane, nw);
-    wave_lds_sync();
-  } else if (rk > 0) {
-#pragma unroll 1
-    for (int rep = 0; rep < 2; ++rep) {
-      const int row = lane + 64 * rep;
-      float a[8];
-#pragma unroll
-      for (int r = 0; r < 8; ++r) a[r] = (r < rk && row < nw) ? h2f(Sak[row * rk + r]) : 0.0f;
-#pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) {
-        const float4 b0 = *reinterpret_cast<const float4*>(&SqB[hq * 8]);       // entries r >= rk are unused (a = 0)
-        const float4 b1 = *reinterpret_cast<const float4*>(&SqB[hq * 8 + 4]);
-        float s = Ssc[hq * SCP + row];
-        s += b0.x * a[0] + b0.y * a[1] + b0.z * a[2] + b0.w * a[3];
-        if (rk > 4) s += b1.x * a[4] + b1.y * a[5] + b1.z * a[6] + b1.w * a[7];
-        Ssc[hq * SCP + row] = s;
-      }
-    }
-    wave_lds_sync();
-  }
-
-  // sparse Key term.  Fixed slots: the lane owns the row, plain adds.  Overflow
-  // entries (rows with more outliers than slots): LDS float adds; those of one wave
-  // are applied in program order and in a fixed lane order inside one instruction,
-  // so the result does not vary from run to run.
-  if (dm.ppm > 0) {
-#pragma unroll
-    for (int rep = 0; rep < 2; ++rep) {
-      const int row = lane + 64 * rep;
-      const uint32_t es[4] = {ellk[rep].x, ellk[rep].y, ellk[rep].z, ellk[rep].w};
-      float a2[GQ];
-#pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
-#pragma unroll
-      for (int i = 0; i < ELL_K; ++i) {
-        const float v = h2f(es[i] >> 16);
-        const int c = es[i] & 127u;
-#pragma unroll
-        for (int hq = 0; hq < GQ; ++hq) a2[hq] += Sq[hq * D + c] * v;
-      }
-#pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) Ssc[hq * SCP + row] += a2[hq];
-    }
-    wave_lds_sync();
+  // Sparse Key term, overflow entries (rows with more outliers than fixed slots): LDS float adds
+  // into the stored scores; those of one wave are applied in program order and in a fixed lane
+  // order inside one instruction, so the result does not vary from run to run.
+  if (dm.ppm > 0 && ck0 + ck1 > 0) {   // wave-uniform
     auto add_k = [&](uint32_t en) {
       const int row = (en & 0xFFFFu) >> 7, c = en & 127u;
       const float v = h2f(en >> 16);
+      float qh[GQ];
+      lds_load_f<GQ>(Sq + c * GQ, qh);
 #pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Ssc[hq * SCP + row], Sq[hq * D + c] * v);
+      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Ssc[row * GQ + hq], qh[hq] * v);
     };
 #pragma unroll
     for (int i = 0; i < SPR; ++i)
@@ -671,6 +664,63 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       add_k(en + (second ? TILE * D : 0));
     }
     wave_lds_sync();
+  }
+
+  // From here the lane owns rows lane and lane + 64: their scores of all query heads stay in
+  // registers through the low-rank term, the fixed outlier slots and the softmax.
+  float sc[2][GQ];
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) lds_load_f<GQ>(Ssc + (lane + 64 * rep) * GQ, sc[rep]);   // rows >= nw: masked below
+
+  // low-rank Key term
+  if (rk == 4) {
+    if (rows_lds) lowrank_key_rows<GQ, 4, false>(Sak, akr, SqB, sc, lane, nw);
+    else lowrank_key_rows<GQ, 4, true>(Sak, akr, SqB, sc, lane, nw);
+  } else if (rk == 2) {
+    if (rows_lds) lowrank_key_rows<GQ, 2, false>(Sak, akr, SqB, sc, lane, nw);
+    else lowrank_key_rows<GQ, 2, true>(Sak, akr, SqB, sc, lane, nw);
+  } else if (rk == 8) {
+    if (rows_lds) lowrank_key_rows<GQ, 8, false>(Sak, akr, SqB, sc, lane, nw);
+    else lowrank_key_rows<GQ, 8, true>(Sak, akr, SqB, sc, lane, nw);
+  } else if (rk > 0) {
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+      const int row = lane + 64 * rep;
+      float a[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) a[r] = (r < rk && row < nw) ? h2f(Sak[row * rk + r]) : 0.0f;
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) {
+        const float4 b0 = *reinterpret_cast<const float4*>(&SqB[hq * 8]);       // entries r >= rk are unused (a = 0)
+        const float4 b1 = *reinterpret_cast<const float4*>(&SqB[hq * 8 + 4]);
+        float s = sc[rep][hq];
+        s += b0.x * a[0] + b0.y * a[1] + b0.z * a[2] + b0.w * a[3];
+        if (rk > 4) s += b1.x * a[4] + b1.y * a[5] + b1.z * a[6] + b1.w * a[7];
+        sc[rep][hq] = s;
+      }
+    }
+  }
+
+  // sparse Key term, fixed slots of the lane's own rows
+  if (dm.ppm > 0) {
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+      const uint32_t es[4] = {ellk[rep].x, ellk[rep].y, ellk[rep].z, ellk[rep].w};
+      float a2[GQ];
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) a2[hq] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < ELL_K; ++i) {
+        const float v = h2f(es[i] >> 16);
+        const int c = es[i] & 127u;
+        float qh[GQ];
+        lds_load_f<GQ>(Sq + c * GQ, qh);
+#pragma unroll
+        for (int hq = 0; hq < GQ; ++hq) a2[hq] += qh[hq] * v;
+      }
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq) sc[rep][hq] += a2[hq];
+    }
   }
 
   uint4 avr[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};   // rows lane, lane + 64 of A_V when they are not staged
@@ -696,16 +746,17 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   }
 
   // =================== this wave's softmax state ===================
+  float pr[2][GQ];   // probabilities of rows lane, lane + 64 (0 for rows >= nw)
   {
 #pragma unroll
     for (int hq = 0; hq < GQ; ++hq) {
-      const float s0 = lane < nw ? Ssc[hq * SCP + lane] * scale : -INFINITY;
-      const float s1 = lane + 64 < nw ? Ssc[hq * SCP + lane + 64] * scale : -INFINITY;
+      const float s0 = lane < nw ? sc[0][hq] * scale : -INFINITY;
+      const float s1 = lane + 64 < nw ? sc[1][hq] * scale : -INFINITY;
       const float m = wave_max(fmaxf(s0, s1));
       const float p0 = lane < nw ? __expf(s0 - m) : 0.0f;
       const float p1 = lane + 64 < nw ? __expf(s1 - m) : 0.0f;
-      Ssc[hq * SCP + lane] = p0;          // rows >= nw hold p = 0
-      Ssc[hq * SCP + lane + 64] = p1;
+      pr[0][hq] = p0;
+      pr[1][hq] = p1;
       const float l = wave_sum(p0 + p1);
       if (lane == 0) {
         M.rv[wave] = rv;
@@ -713,7 +764,53 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
         M.wstat[wave][hq][1] = l;
       }
     }
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) lds_store_f<GQ>(Ssc + (lane + 64 * rep) * GQ, pr[rep]);
     wave_lds_sync();
+  }
+
+  // p^T A_V (down-projection of the low-rank Value term) over the wave's rows; wv starts at 0
+  {
+    float* wv = &M.wv[wave][0][0];
+    if (rv == 4) {
+      if (rows_lds) lowrank_value_down<GQ, 4, false>(Sav, avr, pr, wv, lane, nw);
+      else lowrank_value_down<GQ, 4, true>(Sav, avr, pr, wv, lane, nw);
+    } else if (rv == 2) {
+      if (rows_lds) lowrank_value_down<GQ, 2, false>(Sav, avr, pr, wv, lane, nw);
+      else lowrank_value_down<GQ, 2, true>(Sav, avr, pr, wv, lane, nw);
+    } else if (rv == 8) {
+      if (rows_lds) lowrank_value_down<GQ, 8, false>(Sav, avr, pr, wv, lane, nw);
+      else lowrank_value_down<GQ, 8, true>(Sav, avr, pr, wv, lane, nw);
+    } else if (rv > 0) {
+      float part[GQ][8];
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) part[hq][r] = 0.0f;
+#pragma unroll
+      for (int rep = 0; rep < 2; ++rep) {
+        const int row = lane + 64 * rep;
+        if (row < nw) {
+#pragma unroll
+          for (int r = 0; r < 8; ++r) {
+            if (r < rv) {
+              const float a = h2f(Sav[row * rv + r]);
+#pragma unroll
+              for (int hq = 0; hq < GQ; ++hq) part[hq][r] += pr[rep][hq] * a;
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int hq = 0; hq < GQ; ++hq)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          if (r < rv) {
+            const float s = wave_sum(part[hq][r]);
+            if (lane == 0) wv[hq * 8 + r] = s;
+          }
+        }
+    }
   }
 
   // =================== Value side on the matrix cores ===================
@@ -751,9 +848,11 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
           const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
           const float ds = delta * vscale[k];
           _Float16* dst = opnd + vslot[k];
+          float ph[GQ];
+          lds_load_f<GQ>(Ssc + row * GQ, ph);
 #pragma unroll
           for (int hq = 0; hq < GQ; ++hq) {
-            const float pv = Ssc[hq * SCP + row];
+            const float pv = ph[hq];
             const float w = pv * ds;
             const _Float16 hi = (_Float16)w;
             const _Float16 lo = (_Float16)(w - (float)hi);
@@ -818,52 +917,15 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     const int hq0 = 2 * kg, hq1 = 2 * kg + 1;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      if (hq0 < GQ) Sosp[hq0 * OSP + 16 * j + n16] = (acc[j][0] + acc[j][1]) * MFMA_OUT_SCALE;
-      if (hq1 < GQ) Sosp[hq1 * OSP + 16 * j + n16] = (acc[j][2] + acc[j][3]) * MFMA_OUT_SCALE;
+      const float o0 = (acc[j][0] + acc[j][1]) * MFMA_OUT_SCALE, o1 = (acc[j][2] + acc[j][3]) * MFMA_OUT_SCALE;
+      if constexpr (GQ == 1) {
+        if (kg == 0) Sosp[16 * j + n16] = o0;
+      } else {
+        if (hq0 < GQ) *reinterpret_cast<float2*>(&Sosp[(16 * j + n16) * GQ + hq0]) = make_float2(o0, o1);
+      }
     }
   }
 
-  // p^T A_V (down-projection of the low-rank Value term) over the wave's rows; wv starts at 0
-  float* wv = &M.wv[wave][0][0];
-  if (rv == 4) {
-    if (rows_lds) lowrank_value_down<GQ, 4, false>(Sav, avr, Ssc, wv, lane, nw);
-    else lowrank_value_down<GQ, 4, true>(Sav, avr, Ssc, wv, lane, nw);
-  } else if (rv == 2) {
-    if (rows_lds) lowrank_value_down<GQ, 2, false>(Sav, avr, Ssc, wv, lane, nw);
-    else lowrank_value_down<GQ, 2, true>(Sav, avr, Ssc, wv, lane, nw);
-  } else if (rv == 8) {
-    if (rows_lds) lowrank_value_down<GQ, 8, false>(Sav, avr, Ssc, wv, lane, nw);
-    else lowrank_value_down<GQ, 8, true>(Sav, avr, Ssc, wv, lane, nw);
-  } else if (rv > 0) {
-    float part[GQ][8];
-#pragma unroll
-    for (int hq = 0; hq < GQ; ++hq)
-#pragma unroll
-      for (int r = 0; r < 8; ++r) part[hq][r] = 0.0f;
-#pragma unroll
-    for (int rep = 0; rep < 2; ++rep) {
-      const int row = lane + 64 * rep;
-      if (row < nw) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          if (r < rv) {
-            const float a = h2f(Sav[row * rv + r]);
-#pragma unroll
-            for (int hq = 0; hq < GQ; ++hq) part[hq][r] += Ssc[hq * SCP + row] * a;
-          }
-        }
-      }
-    }
-#pragma unroll
-    for (int hq = 0; hq < GQ; ++hq)
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        if (r < rv) {
-          const float s = wave_sum(part[hq][r]);
-          if (lane == 0) wv[hq * 8 + r] = s;
-        }
-      }
-  }
   wave_lds_sync();
 
   // sparse Value term into this wave's plane.  Fixed slots: the lane owns the channel.
@@ -881,19 +943,26 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
         for (int i = 0; i < ELL_V; ++i) {
           const float v = h2f(es[i] >> 16);
           const int row = ti * TILE + (int)(es[i] & 63u);
+          float ph[GQ];
+          lds_load_f<GQ>(Ssc + row * GQ, ph);
 #pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) a2[hq] += Ssc[hq * SCP + row] * v;
+          for (int hq = 0; hq < GQ; ++hq) a2[hq] += ph[hq] * v;
         }
       }
+      float oh[GQ];
+      lds_load_f<GQ>(Sosp + c * GQ, oh);
 #pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) Sosp[hq * OSP + c] += a2[hq];
+      for (int hq = 0; hq < GQ; ++hq) oh[hq] += a2[hq];
+      lds_store_f<GQ>(Sosp + c * GQ, oh);
     }
     wave_lds_sync();
     auto add_v = [&](uint32_t en) {
       const int row = (en & 0xFFFFu) >> 7, c = en & 127u;
       const float v = h2f(en >> 16);
+      float ph[GQ];
+      lds_load_f<GQ>(Ssc + row * GQ, ph);
 #pragma unroll
-      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Sosp[hq * OSP + c], Ssc[hq * SCP + row] * v);
+      for (int hq = 0; hq < GQ; ++hq) atomicAdd(&Sosp[c * GQ + hq], ph[hq] * v);
     };
 #pragma unroll
     for (int i = 0; i < SPR; ++i)
@@ -911,7 +980,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   // (an empty wave has m = -inf and weight 0; its plane, pm and wv hold zeros)
   const bool one_b = shared_b && (rv == 0 || rv == 2 || rv == 4 || rv == 8);   // block-uniform: one B_V, one read per row
   for (int i = tid; i < GQ * D; i += 256) {
-    const int hq = i / D, c = i % D, G = c >> lg;
+    const int c = i / GQ, hq = i % GQ, G = c >> lg;   // the lanes of a wave read consecutive plane entries
     float mw[4], lw[4], f[4];
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
@@ -931,7 +1000,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
-        o += f[w] * (plane[hq * OSP + c] + M.pm[w][hq][G]);
+        o += f[w] * (plane[c * GQ + hq] + M.pm[w][hq][G]);
         l += f[w] * lw[w];
         if (rv > 0) {
           const float4 a = *reinterpret_cast<const float4*>(&M.wv[w][hq][0]);
@@ -962,7 +1031,7 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       for (int w = 0; w < 4; ++w) {
         if (mw[w] == -INFINITY) continue;
         const float* plane = reinterpret_cast<const float*>(smem + L.wave0 + (size_t)w * L.wave_stride + L.osp);
-        float ow = plane[hq * OSP + c] + M.pm[w][hq][G];
+        float ow = plane[c * GQ + hq] + M.pm[w][hq][G];
         const uint16_t* bfw = reinterpret_cast<const uint16_t*>(smem + L.bf + (shared_b ? L.bf_v0 : w * L.bf_cw + L.bf_vc));
         const int rvw = GEAR_WAVE_UNIFORM(M.rv[w]);
         const float* wvw = &M.wv[w][hq][0];
