@@ -159,6 +159,82 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
   }
 }
 
+// ------------------------------------------------------------------ K select, segments of more than 8192 tokens
+// Such a vector fits neither the registers of a wave nor, eight channels at a time, the LDS of a block, and
+// read one channel at a time from the [token][channel] tensor every 2-byte value costs a whole memory
+// sector.  So the keys are first written channel-major ([slab][channel][stride] u16, stride = n rounded up
+// to 8) into scratch memory, and the selection then reads every vector contiguously, straight from global
+// memory, once per pass: no LDS tile, so the occupancy does not depend on the segment length.
+struct GlobalKeySource {   // one vector stored contiguously in global memory as 16-bit keys
+  static constexpr int kMaxChunks = -1;
+  GEAR_BUF_T buf;          // view of the vector's stride keys; reads past it return 0
+  __device__ __forceinline__ uint4 operator()(int ch) const { return GEAR_BUF_LOAD16(buf, (ch * 64 + lane_id()) * 16); }
+};
+
+// grid (ceil(n / 128), B*H), block 256: thread (rg, oc) takes the 16-byte pieces (8 channels) of rows
+// 8 rg .. 8 rg + 7 of the tile, turns the values into keys, transposes the 8 x 8 block in registers and
+// stores 8 tokens of each of its 8 channels with one 16-byte store.  Rows past n are written as the key of 0.
+__global__ __launch_bounds__(256) void k_transpose_keys_kernel(const uint16_t* __restrict__ K, int n, int stride,
+                                                               uint16_t* __restrict__ KT) {
+  const int slab = blockIdx.y, tid = threadIdx.x, rg = tid >> 4, oc = tid & 15;
+  const int row0 = blockIdx.x * 128 + rg * 8;
+  const GEAR_BUF_T xb = GEAR_BUF_MAKE(K + (size_t)slab * n * D, n * (D * 2));
+  uint32_t w[8][4];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const uint4 t4 = GEAR_BUF_LOAD16(xb, (row0 + k) * (D * 2) + oc * 16);
+    w[k][0] = key16x2(t4.x); w[k][1] = key16x2(t4.y); w[k][2] = key16x2(t4.z); w[k][3] = key16x2(t4.w);
+  }
+  if (row0 >= stride) return;   // (stride is a multiple of 8: the 8 tokens lie inside or outside together)
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int j = c >> 1;
+    const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;   // the high / the low halves of two words
+    const uint4 o = make_uint4(GEAR_BYTE_PERM(w[1][j], w[0][j], sel), GEAR_BYTE_PERM(w[3][j], w[2][j], sel),
+                               GEAR_BYTE_PERM(w[5][j], w[4][j], sel), GEAR_BYTE_PERM(w[7][j], w[6][j], sel));
+    *reinterpret_cast<uint4*>(KT + ((size_t)slab * D + oc * 8 + c) * stride + row0) = o;
+  }
+}
+
+// grid (B*H * 128 / 4), block 256: one wave per channel vector.
+__global__ __launch_bounds__(256) void k_select_long_kernel(const uint16_t* __restrict__ KT, int n, int stride, int k_top,
+                                                            int k_bot, ThreshPair* __restrict__ thrK,
+                                                            uint32_t* __restrict__ zero, int zero_count,
+                                                            uint32_t* __restrict__ ksz, int ng_cap, float qmax) {
+  __shared__ uint32_t hist_all[4 * SELECT_LDS_WORDS];
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < zero_count; i += gridDim.x * blockDim.x) zero[i] = 0u;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int v = blockIdx.x * 4 + wave;   // slab * 128 + channel
+  const GlobalKeySource src{GEAR_BUF_MAKE(KT + (size_t)v * stride, stride * 2)};
+  const Thresh th = wave_select(src, n, k_top, k_bot, hist_all + wave * SELECT_LDS_WORDS, true);
+  if (lane == 0) thrK[v] = pack_thresh(th);
+  if (ksz) {
+    // per-vector grouping: (scale, zero) of the channel's one group, from min and max of X - S
+    uint32_t kmn = 0xFFFFu, kmx = 0u;
+    const ThreshPair tp = pack_thresh(th);
+    for_each_chunk(src, (n + 511) >> 9, [&](int ch, const uint4& v4) {
+      const int base = ch * 512 + lane * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t k = slot16(v4, e), idx = (uint32_t)(base + e);
+        if (base + e < n) {
+          const bool out = ((k << 16) | (0xFFFFu - idx)) >= tp.top || ((k << 16) | idx) < tp.bot;
+          const uint32_t y = out ? 0x8000u : k;
+          kmn = min(kmn, y);
+          kmx = max(kmx, y);
+        }
+      }
+    });
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      kmn = min(kmn, (uint32_t)__shfl_xor(kmn, o, 64));
+      kmx = max(kmx, (uint32_t)__shfl_xor(kmx, o, 64));
+    }
+    if (lane == 0)
+      ksz[(size_t)(v / D) * ng_cap * D + (v % D)] = group_bits(make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), qmax));
+  }
+}
+
 // ------------------------------------------------------------------ K select, vectors in registers
 // For segments of up to 8192 tokens: a block of eight waves takes eight neighbouring channels, one per
 // wave, and every wave ends up with its whole channel vector in registers (NC chunks of 512 keys, the
@@ -526,7 +602,15 @@ static hipError_t launch_k_select_reg(const uint16_t* K, const Dims& dm, int n, 
 }
 
 hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
-                           uint32_t* zero, int zero_count, const SegView& sv, hipStream_t st) {
+                           uint32_t* zero, int zero_count, const SegView& sv, uint16_t* kt_scratch, hipStream_t st) {
+  // segments of more than 8192 tokens: through a channel-major copy of the keys
+  if (n > 8192 && kt_scratch != nullptr) {
+    const int stride = (n + 7) & ~7;
+    hipLaunchKernelGGL(k_transpose_keys_kernel, dim3((n + 127) / 128, dm.B * dm.H), dim3(256), 0, st, K, n, stride, kt_scratch);
+    hipLaunchKernelGGL(k_select_long_kernel, dim3(dm.B * dm.H * (D / 4)), dim3(256), 0, st, (const uint16_t*)kt_scratch, n,
+                       stride, k_top, k_bot, thrK, zero, zero_count, dm.kcvt ? sv.sz : (uint32_t*)nullptr, sv.ng_cap, dm.qmax);
+    return hipGetLastError();
+  }
   // segments of 1025 .. 8192 tokens: the channel vectors live in registers
   if (n > 4096 && n <= 8192) return launch_k_select_reg<16>(K, dm, n, k_top, k_bot, thrK, zero, zero_count, sv, st);
   if (n > 2048 && n <= 4096) return launch_k_select_reg<8>(K, dm, n, k_top, k_bot, thrK, zero, zero_count, sv, st);

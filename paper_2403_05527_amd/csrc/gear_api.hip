@@ -115,7 +115,14 @@ WorkLayout work_layout(const gear_config& c) {
   w.dec = o; o += up((size_t)c.B * c.H_q * (nsplit + ncb + 1) * DECODE_REC * 4);
   w.gram_strips = c.rank_max > 0 && n_max > 256 ? pi_gram_strips_max(n_max, (int)slabs) : 0;
   w.gram = o; o += up(slabs * (size_t)w.gram_strips * 36 * 256 * 4);
-  w.resid = o; o += up(c.rank_max > 0 ? slabs * (size_t)n_max * D * 2 : 0);
+  // the filtered tensor for the low-rank passes; before it is written, the channel-major copy of the
+  // keys of a long Key segment (see launch_k_select) lives in the same place
+  w.resid = o;
+  {
+    const size_t resid = c.rank_max > 0 ? slabs * (size_t)n_max * D * 2 : 0;
+    const size_t kt = c.n_prefill_max > 8192 ? slabs * (size_t)((c.n_prefill_max + 7) & ~7) * D * 2 : 0;
+    o += up(resid > kt ? resid : kt);
+  }
   w.bytes = o;
   return w;
 }
@@ -358,7 +365,8 @@ int gear_compress_recent(gear_cache* cache, const void* K, const void* V, int32_
   const int kv_v = outlier_count(vhead ? D : (long long)c.H_kv * D, c.outlier_ppm);   // per Value vector
   // the Key selection kernel also finds a channel's (scale, zero) under the per-vector grouping
   if (c.outlier_ppm > 0 || dm.kcvt) {
-    GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, pool_ctr, c.B * c.H_kv + c.B, ks, st));
+    GEAR_HIP(launch_k_select(Kp, dm, n, (kv_k + 1) / 2, kv_k / 2, thrK, pool_ctr, c.B * c.H_kv + c.B, ks,
+                             n > 8192 ? reinterpret_cast<uint16_t*>(ws + w.resid) : nullptr, st));
   }
   // Keys: quantize (leaving Y = X - S in the workspace), then their power iteration;
   // Values reuse the same buffer afterwards.

@@ -19,7 +19,7 @@ hipError_t launch_fill_u32(uint32_t* p, uint32_t v, size_t count, hipStream_t st
 // also clears zero[0 .. zero_count) (the list counters of the call); under the per-vector grouping it also writes
 // every channel's (scale, zero) of the segment sv
 hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, int k_bot, ThreshPair* thrK,
-                           uint32_t* zero, int zero_count, const SegView& sv, hipStream_t st);
+                           uint32_t* zero, int zero_count, const SegView& sv, uint16_t* kt_scratch, hipStream_t st);
 // Yout (nullable): [slab][n][128] fp16, Y = X - S (the input with its outliers zeroed), from
 // which the power iteration re-derives the residual R = Y - D-hat.
 hipError_t launch_k_quant(const uint16_t* K, const SegView& sv, const Dims& dm, int n, const ThreshPair* thrK,

@@ -15,12 +15,23 @@ namespace gear {
 // KEYS (key16 of the fp16 bit patterns), two per 32-bit word.
 //   Src::kMaxChunks > 0 : the vector lives in registers; loops are unrolled.
 //   Src::kMaxChunks == 0: runtime loop (vector in LDS).
+//   Src::kMaxChunks < 0 : runtime loop with the loads of several chunks in flight (vector in global memory).
 template <class Src, class F>
 __device__ __forceinline__ void for_each_chunk(const Src& src, int nch, F&& f) {
   if constexpr (Src::kMaxChunks > 0) {
 #pragma unroll
     for (int ch = 0; ch < Src::kMaxChunks; ++ch)
       if (ch < nch) f(ch, src(ch));
+  } else if constexpr (Src::kMaxChunks < 0) {
+    // vector in global memory: eight chunk loads in flight (reads past the vector return defined data)
+    for (int c0 = 0; c0 < nch; c0 += 8) {
+      uint4 v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = src(c0 + i);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (c0 + i < nch) f(c0 + i, v[i]);
+    }
   } else {
     for (int ch = 0; ch < nch; ++ch) f(ch, src(ch));
   }

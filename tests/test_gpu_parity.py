@@ -143,6 +143,33 @@ def test_heavy_ties_and_constant_vectors(n):
     say("  ->", rep)
 
 
+@pytest.mark.parametrize("n,g,ties", [(1100, 64, False), (2500, 64, True), (4101, 128, False), (8192, 64, True),
+                                      (8461, 64, False), (8461, 0, True), (12000, 128, True)])
+def test_key_selection_paths_by_segment_length(n, g, ties):
+    """The Key Filter (Eq. 4 along the token axis) takes a different kernel by segment length: channel vectors
+    in registers (1025 .. 8192 tokens, three sizes) and, beyond, a channel-major copy of the keys read from
+    global memory.  Element-wise against the oracle at ragged lengths; `ties`: values on a coarse grid, so
+    that the threshold value is shared by many entries and the lowest-index rule decides, with one constant head."""
+    bits = 4 if g == 0 else 2
+    w = small_workload(B=1, H_kv=2, H_q=2, n=n, bits=bits, g=g, ppm=20000, rank=2, seed=n + g)
+    say("case key selection", w, "ties", ties)
+    gc, oc = pu.make_pair(1, 2, 2, bits, g, 20000, 20, n, 1, 2)
+    if ties:
+        gen = torch.Generator(device="cpu").manual_seed(n)
+        K = (torch.randint(-6, 7, (1, 2, n, 128), generator=gen).float() * 0.5)
+        K[0, 1, :, :7] = 1.5                             # constant channels
+        K = K.to(torch.float16).to(DEV)
+    else:
+        K = gw.make_keys(w, n, 0, DEV)
+    V = gw.make_values(w, n, 0, DEV)
+    pu.compress_both(gc, oc, K, V, 2, 2, gw.make_init_B(w, 2, 0, DEV))
+    rep = pu.compare_components(gc, oc)
+    rep.update(pu.compare_decompress(gc, oc))
+    rep.update(pu.compare_attention(gc, oc, gw.make_queries(w, 0, DEV)))
+    say("  ->", rep)
+    assert rep["K_nnz"] > 0
+
+
 def test_lossless_grid_reconstructs_input_bit_exact():
     gc, oc = pu.make_pair(1, 2, 2, 2, 64, 0, 20, 128, 1, 4)
     g = torch.Generator(device="cpu").manual_seed(6)
