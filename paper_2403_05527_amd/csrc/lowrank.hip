@@ -41,7 +41,28 @@ __device__ __forceinline__ T block_sum(T v, T* red /* 4 */) {
   return s;
 }
 
-// grid (B*H), block 128: thread c owns row c of the [128 x R] matrix.
+// Sum of a double over the 64 lanes, in every lane: lane exchanges inside rows of 16 (one
+// data-parallel-primitive move per 32-bit half), then the four row sums through scalar reads.
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) {
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = dpp_u<CTRL>((uint32_t)b), hi = dpp_u<CTRL>((uint32_t)(b >> 32));
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ double lane_bcast_d(double v, int lane) {
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), lane);
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ double wave_sum_d(double v) {
+  v += dpp_d<DPP_XOR1>(v);
+  v += dpp_d<DPP_XOR2>(v);
+  v += dpp_d<DPP_HALF_MIRROR>(v);
+  v += dpp_d<DPP_MIRROR>(v);
+  return (lane_bcast_d(v, 0) + lane_bcast_d(v, 16)) + (lane_bcast_d(v, 32) + lane_bcast_d(v, 48));
+}
+// grid (B*H), block 256: thread c < 128 owns row c of the [128 x R] matrix.
 // from_start          : B <- the start matrix (zero-padded to R)
 // else                : B <- sum over `npart` partials ([slab][npart][128*R + R*R])
 // do_orth : replace B by the Q factor of its QR (twice-applied modified
@@ -55,8 +76,8 @@ struct UpdateSmem {
   double C[R][R];
   double cj[R];   // work vector of the one thread that orthonormalises in coefficient space
 };
-// The body runs in a block of 128 threads (its own kernel) or of 256 (the one-block power
-// iteration of short segments, where threads 128.. only take part in the barriers).
+// The body runs in a block of 256 threads: threads 128.. sum the Gram partials of the final round
+// and otherwise only take part in the barriers.
 template <int R>
 __device__ __forceinline__ void pi_update_body(UpdateSmem<R>& sm, int slab, bool from_start, const StartB& sb, int rank,
                                                const float* __restrict__ partial, int npart, int do_orth,
@@ -76,7 +97,23 @@ __device__ __forceinline__ void pi_update_body(UpdateSmem<R>& sm, int slab, bool
       for (int r = 0; r < R; ++r) q[r] = r < rank ? (double)start_b(sb, slab, c, rank, r) : 0.0;
     } else {
       const float* p = partial + (size_t)slab * npart * (D * R + R * R);
-      for (int i = 0; i < npart; ++i) {
+      int i = 0;
+      // long segments (many partials): the loads of eight partials are requested before the first is added
+      // (written as a load loop of its own: an add right after its load makes the compiler wait for every load)
+      if (npart > 16) {
+        for (; i + 8 <= npart; i += 8) {
+          float t[8][R];
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int r = 0; r < R; ++r) t[u][r] = __builtin_nontemporal_load(&p[(size_t)(i + u) * (D * R + R * R) + c * R + r]);
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int r = 0; r < R; ++r) q[r] += (double)t[u][r];
+        }
+      }
+      for (; i < npart; ++i) {
 #pragma unroll
         for (int r = 0; r < R; ++r) q[r] += (double)p[(size_t)i * (D * R + R * R) + c * R + r];
       }
@@ -84,43 +121,58 @@ __device__ __forceinline__ void pi_update_body(UpdateSmem<R>& sm, int slab, bool
   }
 
   if (final_round) {
-    if (c < R * R) {
-      const float* p = partial + (size_t)slab * npart * (D * R + R * R) + D * R;
+    if (c >= D && c < D + R * R) {   // threads 128..: the r x r Gram partials, while threads 0..127 sum theirs
+      const int gi = c - D;
+      const float* p = partial + (size_t)slab * npart * (D * R + R * R) + D * R + gi;
       double s = 0.0;
-      for (int i = 0; i < npart; ++i) s += (double)p[(size_t)i * (D * R + R * R) + c];
-      G[c / R][c % R] = s;
+      int i = 0;
+      for (; i + 8 <= npart; i += 8) {
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = __builtin_nontemporal_load(&p[(size_t)(i + u) * (D * R + R * R)]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (double)t[u];
+      }
+      for (; i < npart; ++i) s += (double)p[(size_t)i * (D * R + R * R)];
+      G[gi / R][gi % R] = s;
     }
     block_lds_sync();
-    if (c == 0) {
-      // Gram-Schmidt in coefficient space: column j of orth(A) is A * C[:, j].
+    if (c < 64) {
+      // Gram-Schmidt in coefficient space: column j of orth(A) is A * C[:, j].  Wave 0 runs it; lane a * R + b
+      // carries the (a, b) term of every quadratic form x^T G y, a sum over the wave finishes it.
+      const int a = c / R, b = c % R;
+      const bool in = c < R * R;
+      const double Gab = in ? G[a][b] : 0.0;
       uint32_t valid = 0;   // bit j: column j is kept
       double* cj = sm.cj;
       for (int j = 0; j < R; ++j) {
-        for (int i = 0; i < R; ++i) cj[i] = (i == j) ? 1.0 : 0.0;
+        if (c < R) cj[c] = (c == j) ? 1.0 : 0.0;
+        wave_lds_sync();
         const double before2 = G[j][j];
         bool ok = before2 > 0.0;
         if (ok) {
           for (int pass = 0; pass < 2; ++pass)
             for (int k = 0; k < j; ++k) {
               if (!((valid >> k) & 1u)) continue;
-              double dot = 0.0;  // q_k^T v = c_k^T G c_j
-              for (int a = 0; a < R; ++a)
-                for (int b = 0; b < R; ++b) dot += C[a][k] * G[a][b] * cj[b];
-              for (int a = 0; a < R; ++a) cj[a] -= dot * C[a][k];
+              const double dot = wave_sum_d(in ? C[a][k] * Gab * cj[b] : 0.0);   // q_k^T v = c_k^T G c_j
+              wave_lds_sync();
+              if (c < R) cj[c] -= dot * C[c][k];
+              wave_lds_sync();
             }
-          double after2 = 0.0;
-          for (int a = 0; a < R; ++a)
-            for (int b = 0; b < R; ++b) after2 += cj[a] * G[a][b] * cj[b];
+          const double after2 = wave_sum_d(in ? cj[a] * Gab * cj[b] : 0.0);
+          wave_lds_sync();
           // (the Gram matrix is a sum of fp32 products: what is left of a dependent column is
           // rounding noise of relative size ~1e-7 in after2, so the cut sits above that)
           if (!(after2 > 1e-6 * before2)) ok = false;
           else {
             const double inv = 1.0 / sqrt(after2);
-            for (int a = 0; a < R; ++a) cj[a] *= inv;
+            if (c < R) cj[c] *= inv;
+            wave_lds_sync();
           }
         }
         if (ok) valid |= 1u << j;
-        for (int a = 0; a < R; ++a) C[a][j] = ok ? cj[a] : 0.0;
+        if (c < R) C[c][j] = ok ? cj[c] : 0.0;
+        wave_lds_sync();
       }
     }
     block_lds_sync();
@@ -171,7 +223,7 @@ __device__ __forceinline__ void pi_update_body(UpdateSmem<R>& sm, int slab, bool
 }
 
 template <int R>
-__global__ __launch_bounds__(128) void pi_update_kernel(int from_start, StartB sb, int rank,
+__global__ __launch_bounds__(256) void pi_update_kernel(int from_start, StartB sb, int rank,
                                                         const float* __restrict__ partial, int npart,
                                                         int do_orth, int final_round,
                                                         float* __restrict__ Bcur, float* __restrict__ cmat,
@@ -692,27 +744,6 @@ struct SolveSmem {
   double part[D][R];   // the upper half block's share of a product
   double red[4 * (R + 1)];
 };
-// Sum of a double over the 64 lanes, in every lane: lane exchanges inside rows of 16 (one
-// data-parallel-primitive move per 32-bit half), then the four row sums through scalar reads.
-template <int CTRL>
-__device__ __forceinline__ double dpp_d(double v) {
-  const uint64_t b = __builtin_bit_cast(uint64_t, v);
-  const uint32_t lo = dpp_u<CTRL>((uint32_t)b), hi = dpp_u<CTRL>((uint32_t)(b >> 32));
-  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
-}
-__device__ __forceinline__ double lane_bcast_d(double v, int lane) {
-  const uint64_t b = __builtin_bit_cast(uint64_t, v);
-  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
-  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), lane);
-  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
-}
-__device__ __forceinline__ double wave_sum_d(double v) {
-  v += dpp_d<DPP_XOR1>(v);
-  v += dpp_d<DPP_XOR2>(v);
-  v += dpp_d<DPP_HALF_MIRROR>(v);
-  v += dpp_d<DPP_MIRROR>(v);
-  return (lane_bcast_d(v, 0) + lane_bcast_d(v, 16)) + (lane_bcast_d(v, 32) + lane_bcast_d(v, 48));
-}
 // Sums of N per-thread values over the block (256 threads), all in every thread: one pair of
 // barriers for the N sums together.
 template <int N>
@@ -907,7 +938,7 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
       hipLaunchKernelGGL((pi_sweep_kernel<true, R, true>), grid, dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, t_lr, (const float*)Bcur, partial, npart, Atmp);
     else
       hipLaunchKernelGGL((pi_sweep_kernel<false, R, true>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, t_lr, (const float*)Bcur, partial, npart, Atmp);
-    hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(128), 0, st, 0, sb, sv.rank,
+    hipLaunchKernelGGL(pi_update_kernel<R>, dim3(slabs), dim3(256), 0, st, 0, sb, sv.rank,
                        (const float*)partial, npart, 0, 1, Bcur, cmat, sv);
   }
   hipLaunchKernelGGL(pi_finish_kernel<R>, dim3((n + 255) / 256, slabs), dim3(256), 0, st, (const float*)Atmp,
