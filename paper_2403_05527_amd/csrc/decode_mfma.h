@@ -75,6 +75,11 @@ struct Codec<4> {
   __device__ static __forceinline__ int lg(int v) { return (v & 1) * 4; }
 };
 
+// Two fp16 values as one 32-bit word (a in the low half).
+__device__ __forceinline__ uint32_t pack_f16x2(_Float16 a, _Float16 b) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+}
+
 // 2^(4 - lg) as a float (operand scale 16 / 2^lg)
 __device__ __forceinline__ float opscale(int lg) { return __uint_as_float((uint32_t)(127 + 4 - lg) << 23); }
 
@@ -441,14 +446,18 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   const uint4* g_bk = reinterpret_cast<const uint4*>(ks.Bf + (size_t)slab * D * rk);
   const uint4* g_bv = reinterpret_cast<const uint4*>(vs.Bf + (size_t)slab * D * rv);
   // piece lane of each array; pieces 64.. (g = 32, rank 8) follow after the first
-  // Key (scale, zero) of channels lane and lane + 64 in each of the wave's groups: straight into registers
+  // The lane builds the Key operand of two channels whose fp16 halves share a 32-bit word of the operand
+  // column (key_slot: channels PD apart inside a block of 2 PD), so every operand store is a whole word.
+  constexpr int PD = (BITS == 2) ? 8 : 4;
+  const int kc0 = (lane / PD) * (2 * PD) + (lane % PD);   // the lane's channels: kc0 and kc0 + PD
+  // their (scale, zero) in each of the wave's groups: straight into registers
   uint32_t szk_r[WTOK >> LG][2];
   {
     const GEAR_BUF_T zbuf = GEAR_BUF_MAKE(g_szk, n4_szk * 16);   // groups past the wave's last row read as 0
 #pragma unroll
     for (int gw = 0; gw < (WTOK >> LG); ++gw)
 #pragma unroll
-      for (int rep = 0; rep < 2; ++rep) szk_r[gw][rep] = GEAR_BUF_LOAD4(zbuf, (gw * D + lane + 64 * rep) * 4);
+      for (int rep = 0; rep < 2; ++rep) szk_r[gw][rep] = GEAR_BUF_LOAD4(zbuf, (gw * D + kc0 + PD * rep) * 4);
   }
   const uint4 r_szv = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_szv, n4_szv * 16), lane * 16);
   const uint4 r_ak = GEAR_BUF_LOAD16(GEAR_BUF_MAKE(g_ak, n4_ak * 16), lane * 16);
@@ -557,40 +566,42 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   }
 
   // =================== Key scores on the matrix cores ===================
-  int kslot[2];     // operand position of channels lane and lane + 64 (same for every group)
-  float kscale[2];
-#pragma unroll
-  for (int rep = 0; rep < 2; ++rep) {
-    const int ch = lane + 64 * rep;
+  int kslot0;       // operand position of channel kc0 (even; kc0 + PD follows it; the same for every group)
+  float kscale;
+  {
     int idx, lg;
-    key_slot<BITS>(ch & 31, idx, lg);
-    kslot[rep] = (ch >> 5) * 32 + idx;
-    kscale[rep] = opscale(lg);
+    key_slot<BITS>(kc0 & 31, idx, lg);
+    kslot0 = (kc0 >> 5) * 32 + idx;
+    kscale = opscale(lg);
   }
 #pragma unroll
   for (int gw = 0; gw < (WTOK >> lg); ++gw) {
     if (gw * g >= nw) break;                        // wave-uniform
     float kb[GQ];
+    uint32_t first[GQ];   // (hi, lo) parts of the first channel's operand
 #pragma unroll
     for (int hq = 0; hq < GQ; ++hq) kb[hq] = 0.0f;
 #pragma unroll
     for (int rep = 0; rep < 2; ++rep) {
-      const int ch = lane + 64 * rep;
+      const int ch = kc0 + PD * rep;
       const uint32_t sb = szk_r[gw][rep];
       const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
-      const float os = kscale[rep];
-      _Float16* dst = opnd + kslot[rep];
       float qh[GQ];
       lds_load_f<GQ>(Sq + ch * GQ, qh);
 #pragma unroll
       for (int hq = 0; hq < GQ; ++hq) {
         const float qv = qh[hq];
-        const float w = qv * delta * os;
+        const float w = qv * delta * kscale;
         const _Float16 hi = (_Float16)w;
         const _Float16 lo = (_Float16)(w - (float)hi);
-        dst[(2 * hq) * KOP] = hi;
-        dst[(2 * hq + 1) * KOP] = lo;
         kb[hq] += qv * mn;
+        if (rep == 0) {
+          first[hq] = pack_f16x2(hi, lo);
+        } else {
+          const uint32_t second = pack_f16x2(hi, lo);
+          *reinterpret_cast<uint32_t*>(opnd + (2 * hq) * KOP + kslot0) = GEAR_BYTE_PERM(second, first[hq], 0x05040100u);
+          *reinterpret_cast<uint32_t*>(opnd + (2 * hq + 1) * KOP + kslot0) = GEAR_BYTE_PERM(second, first[hq], 0x07060302u);
+        }
       }
     }
 #pragma unroll
@@ -817,20 +828,24 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
   floatx4 acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
-  // operand prep: lane handles rows (lane >> lgNG) + k * (64 >> lgNG) of a code block for its own
-  // channel group Gl; positions and scales are the same for every block
+  // operand prep: a lane handles, for its own channel group Gl, pairs of rows of a code block whose fp16
+  // halves share a 32-bit word of the operand row (val_slot: rows VD apart inside a block of 2 VD), so every
+  // operand store is a whole word; positions and scales are the same for every block
   const int lgNG = (NG == 1) ? 0 : (NG == 2) ? 1 : 2;
   const int Gl = lane & (NG - 1);
-  const int tstep = 64 >> lgNG;
-  int vslot[4], vrow[4];
-  float vscale[4];
+  constexpr int VD = (BITS == 2) ? 8 : 4;
+  constexpr int NPAIR = TB / 2;                                    // row pairs of a code block
+  constexpr int KV = (NPAIR * NG + 63) / 64;                       // pairs per lane (1 or 2)
+  int vslot[KV], vrow[KV];
+  float vscale[KV];
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const int tl = (lane >> lgNG) + k * tstep;
+  for (int k = 0; k < KV; ++k) {
+    const int pi = (lane >> lgNG) + k * (64 >> lgNG);              // pair index inside the block
+    const int t0 = (pi / VD) * (2 * VD) + (pi % VD);               // its rows: t0 and t0 + VD
     int skg, idx, lg;
-    val_slot<BITS>(tl & (TB - 1), skg, idx, lg);
-    vrow[k] = tl < TB ? tl : -1;
-    vslot[k] = Gl * 2 * GQ * vop(TB) + skg * (TB / 4) + idx;
+    val_slot<BITS>(t0 & (TB - 1), skg, idx, lg);
+    vrow[k] = pi < NPAIR ? t0 : -1;
+    vslot[k] = Gl * 2 * GQ * vop(TB) + skg * (TB / 4) + idx;       // even
     vscale[k] = opscale(lg);
   }
   float pmr[GQ];
@@ -841,24 +856,33 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
     const int tl0 = bl * TB;                       // first row (inside the wave) of this code block
     if (tl0 < nw) {                                // wave-uniform
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < KV; ++k) {
         if (vrow[k] >= 0) {
-          const int row = tl0 + vrow[k];
-          const uint32_t sb = row < nw ? Sszv[row * NG + Gl] : 0u;
-          const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
-          const float ds = delta * vscale[k];
+          uint32_t first[GQ];   // (hi, lo) parts of the first row's operand
           _Float16* dst = opnd + vslot[k];
-          float ph[GQ];
-          lds_load_f<GQ>(Ssc + row * GQ, ph);
 #pragma unroll
-          for (int hq = 0; hq < GQ; ++hq) {
-            const float pv = ph[hq];
-            const float w = pv * ds;
-            const _Float16 hi = (_Float16)w;
-            const _Float16 lo = (_Float16)(w - (float)hi);
-            dst[(2 * hq) * vop(TB)] = hi;
-            dst[(2 * hq + 1) * vop(TB)] = lo;
-            pmr[hq] += pv * mn;
+          for (int rep = 0; rep < 2; ++rep) {
+            const int row = tl0 + vrow[k] + VD * rep;
+            const uint32_t sb = row < nw ? Sszv[row * NG + Gl] : 0u;
+            const float delta = h2f(sb & 0xFFFFu), mn = h2f(sb >> 16);
+            const float ds = delta * vscale[k];
+            float ph[GQ];
+            lds_load_f<GQ>(Ssc + row * GQ, ph);
+#pragma unroll
+            for (int hq = 0; hq < GQ; ++hq) {
+              const float pv = ph[hq];
+              const float w = pv * ds;
+              const _Float16 hi = (_Float16)w;
+              const _Float16 lo = (_Float16)(w - (float)hi);
+              pmr[hq] += pv * mn;
+              if (rep == 0) {
+                first[hq] = pack_f16x2(hi, lo);
+              } else {
+                const uint32_t second = pack_f16x2(hi, lo);
+                *reinterpret_cast<uint32_t*>(dst + (2 * hq) * vop(TB)) = GEAR_BYTE_PERM(second, first[hq], 0x05040100u);
+                *reinterpret_cast<uint32_t*>(dst + (2 * hq + 1) * vop(TB)) = GEAR_BYTE_PERM(second, first[hq], 0x07060302u);
+              }
+            }
           }
         }
       }

@@ -41,36 +41,55 @@ __device__ __forceinline__ SegView chunk_view(const SegView& base, uint64_t stri
 // the buffer rows 0 .. n_buf - q_len + hq % q_len only (the q_len newest tokens are the buffer's
 // last q_len rows); q_len = 1: the single-query read, every column sees all n_buf rows.
 template <int GQ>
-__device__ void buffer_block(TailSmem<GQ>& S, const uint16_t* __restrict__ qg, const uint16_t* __restrict__ Kb,
+__device__ __forceinline__ void buffer_block(TailSmem<GQ>& S, const uint16_t* __restrict__ qg, const uint16_t* __restrict__ Kb,
                              const uint16_t* __restrict__ Vb, int n_buf, int q_len, int causal,
                              float* __restrict__ rec_base, int rec_stride) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float scale = 0.08838834764831845f;  // 1/sqrt(128)
+  // Scores: thread (row16 = tid / 16, piece = tid % 16) takes the 16-byte piece (8 channels) of rows
+  // row16, row16 + 16, ...; the 16 lanes of a row add their partial dot products.  The loads that do not
+  // depend on the scores are requested before anything waits: q, the pieces of the first two rows, and
+  // the first eight Value rows of the thread's (channel, parity) on the Value side.
+  const int row16 = tid >> 4, piece = tid & 15;
+  auto load_piece = [&](int row) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (row < n_buf) v = reinterpret_cast<const uint4*>(Kb + (size_t)row * D)[piece];
+    return v;
+  };
+  const uint4 kp0 = load_piece(row16), kp1 = load_piece(row16 + 16);
+  const int vc = tid & 127, vhalf = tid >> 7;
+  uint32_t vr0[4];   // two fp16 values per word
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int k = vhalf + 4 * u;
+    uint32_t a = 0, b = 0;
+    if (k < n_buf) a = Vb[(size_t)k * D + vc];
+    if (k + 2 < n_buf) b = Vb[(size_t)(k + 2) * D + vc];
+    vr0[u] = a | (b << 16);
+  }
   for (int i = tid; i < GQ * D; i += 256) S.q[i / D][i % D] = h2f(qg[i]);
-  // ---- scores: thread tid <-> buffer row tid, four 16-byte pieces of the row in flight at a time
+  block_lds_sync();
+  auto row_scores = [&](const uint4& kv, int row) {   // raw scores of `row` into S.sc
+    const uint32_t w[4] = {kv.x, kv.y, kv.z, kv.w};
+    float kf[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) kf[e] = h2f((w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
+#pragma unroll
+    for (int hq = 0; hq < GQ; ++hq) {
+      const float4 a = *reinterpret_cast<const float4*>(&S.q[hq][piece * 8]);   // q of the thread's 8 channels
+      const float4 b = *reinterpret_cast<const float4*>(&S.q[hq][piece * 8 + 4]);
+      float p = a.x * kf[0] + a.y * kf[1] + a.z * kf[2] + a.w * kf[3] + b.x * kf[4] + b.y * kf[5] + b.z * kf[6] + b.w * kf[7];
+      p = row16_sum(p);
+      if (piece == 0 && row < n_buf) S.sc[hq][row] = p;
+    }
+  };
+  row_scores(kp0, row16);
+  row_scores(kp1, row16 + 16);
+  for (int r0 = 32; r0 < n_buf; r0 += 16) row_scores(load_piece(r0 + row16), r0 + row16);
   block_lds_sync();
   float s[GQ];
 #pragma unroll
-  for (int hq = 0; hq < GQ; ++hq) s[hq] = 0.0f;
-#pragma unroll 1
-  for (int i0 = 0; i0 < 16; i0 += 4) {
-    uint4 kr[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      kr[i] = make_uint4(0, 0, 0, 0);
-      if (tid < n_buf) kr[i] = reinterpret_cast<const uint4*>(Kb + (size_t)tid * D)[i0 + i];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t w[4] = {kr[i].x, kr[i].y, kr[i].z, kr[i].w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float kv = h2f((w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
-#pragma unroll
-        for (int hq = 0; hq < GQ; ++hq) s[hq] += S.q[hq][(i0 + i) * 8 + e] * kv;
-      }
-    }
-  }
+  for (int hq = 0; hq < GQ; ++hq) s[hq] = tid < n_buf ? S.sc[hq][tid] : 0.0f;
   // ---- softmax over the buffer rows
   float p[GQ];
 #pragma unroll
@@ -95,8 +114,9 @@ __device__ void buffer_block(TailSmem<GQ>& S, const uint16_t* __restrict__ qg, c
     if (lane == 0) S.red[hq][wave] = sum;
   }
   // ---- Value side: thread (channel c, parity) walks rows parity, parity + 2, ...; 8 rows in flight
+  // (the first eight were requested at the start)
   {
-    const int c = tid & 127, half = tid >> 7;
+    const int c = vc, half = vhalf;
     float o[GQ];
 #pragma unroll
     for (int hq = 0; hq < GQ; ++hq) o[hq] = 0.0f;
@@ -106,7 +126,8 @@ __device__ void buffer_block(TailSmem<GQ>& S, const uint16_t* __restrict__ qg, c
       for (int u = 0; u < 8; ++u) {
         const int k = k0 + 2 * u;
         vr[u] = 0;
-        if (k < n_buf) vr[u] = Vb[(size_t)k * D + c];
+        if (k0 == half) vr[u] = (uint16_t)(vr0[u >> 1] >> ((u & 1) * 16));
+        else if (k < n_buf) vr[u] = Vb[(size_t)k * D + c];
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
