@@ -148,6 +148,12 @@ int gear_decompress(const gear_cache* cache, void* K_out, void* V_out, void* str
  * K_buf,V_buf: device fp16 [B, H_kv, n_buf_cap, d_h]; may be NULL when n_buf == 0.
  * n_buf     : 0..n_buf_cap; n_buf == 0 with an empty cache is GEAR_EINVAL.
  * out       : device fp16 [B, H_q, 1, d_h].
+ * Value range: the products q[c] * scale_K(group, c) and p * scale_V (p <= 1) are fed to
+ *             the matrix cores as fp16 numbers times at most 16, so finite outputs need
+ *             |q[c] * scale_K| < 4094 and scale_V < 4094 for every entry (scale = (max - min)
+ *             / (2^b - 1) of a group: K and V entries of magnitude up to ~1000 with |q| up to
+ *             ~10 are inside).  Inputs beyond that are not detected: the outputs of the heads
+ *             concerned are then inf or NaN and the call still returns GEAR_OK.
  */
 int gear_decode_attn(const gear_cache* cache, const void* q, const void* K_buf, const void* V_buf,
                      int32_t n_buf, void* out, void* workspace, size_t workspace_bytes,

@@ -3,6 +3,7 @@
 //   k_quant_kernel        Key codes, (scale, zero), ordered outlier lists, the filtered input
 //                         Y = X - S for the power iteration
 // (the Value side is in compress_values.hip)
+#include <atomic>
 #include "gear_internal.h"
 #include "gear_select.h"
 #include "gear_launch.h"
@@ -584,9 +585,13 @@ static hipError_t launch_k_select_cb(const uint16_t* K, const Dims& dm, int n, i
                                      ThreshPair* thrK, uint32_t* zero, int zero_count, const SegView& sv, hipStream_t st) {
   constexpr int nw = CB < 4 ? CB : 4;   // waves per block: one vector each per round
   const size_t lds = (size_t)nw * SELECT_LDS_WORDS * sizeof(uint32_t) + (size_t)CB * n_pad * 2;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel<CB>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
+  static std::atomic<size_t> lds_allowed{0};   // per kernel instance (CB): raised when a launch needs more than any before
+  if (lds > lds_allowed.load(std::memory_order_relaxed)) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_kernel<CB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    lds_allowed.store(lds, std::memory_order_relaxed);
+  }
   dim3 grid((D / CB) * dm.B * dm.H);
   hipLaunchKernelGGL(k_select_kernel<CB>, grid, dim3(64 * nw), lds, st, K, n, n_pad, dm.B * dm.H, k_top, k_bot, thrK, zero,
                      zero_count, dm.kcvt ? sv.sz : (uint32_t*)nullptr, sv.ng_cap, dm.qmax);

@@ -10,6 +10,7 @@
 // (decode_mfma.h); the last split index handles the appended chunk segments and
 // the fp16 buffer (decode_tail.h).  Every block writes one partial softmax
 // record (m, l, o) per query head; decode_combine merges the records.
+#include <atomic>
 #include "gear_internal.h"
 #include "gear_launch.h"
 #include "decode_mfma.h"
@@ -119,12 +120,12 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
   for (int j = 0; j < cs.n_chunks; ++j) odd_rank = odd_rank || !one_read(cs.rank[j]);
   size_t lds = (size_t)mfma_layout<GQ>(BITS, dm.g, k0.rank, v0.rank, rc, dm.ppm, odd_rank).total;
   if (lds < sizeof(TailSmem<GQ>)) lds = sizeof(TailSmem<GQ>);
-  static size_t lds_allowed = 0;  // raised once per process and kernel instance
-  if (lds > lds_allowed) {
+  static std::atomic<size_t> lds_allowed{0};  // raised once per process and kernel instance (two threads may both raise it: harmless)
+  if (lds > lds_allowed.load(std::memory_order_relaxed)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_split_kernel<BITS, GQ, LG>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    lds_allowed = lds;
+    lds_allowed.store(lds, std::memory_order_relaxed);
   }
   dim3 grid(nsplit + ncb + 1, dm.B * dm.H);
   hipLaunchKernelGGL((decode_split_kernel<BITS, GQ, LG>), grid, dim3(256), lds, st, dm, k0, v0, cs, q, Kbuf, Vbuf,

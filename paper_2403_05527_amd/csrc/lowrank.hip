@@ -22,6 +22,7 @@
 //                Gram matrix sum_t a_t a_t^T.
 //   pi_finish  : A = a C  (C = the r x r factor), rounded to fp16.
 //   pi_small   : all of the above for a segment of at most 256 tokens, in one block per slab.
+#include <atomic>
 #include "gear_internal.h"
 #include "gear_launch.h"
 
@@ -921,12 +922,12 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
     else launch_gram<true, 7>(Yf, sv, dm, n, t_lr, strip, nstrips, gram, st);
   }
   {
-    static bool lds_raised = false;   // per kernel instance (R)
-    if (!lds_raised) {
+    static std::atomic<bool> lds_raised{false};   // per kernel instance (R); two threads may both raise it: harmless
+    if (!lds_raised.load(std::memory_order_relaxed)) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pi_solve_kernel<R>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SolveSmem<R>));
       if (e != hipSuccess) return e;
-      lds_raised = true;
+      lds_raised.store(true, std::memory_order_relaxed);
     }
   }
   hipLaunchKernelGGL(pi_solve_kernel<R>, dim3(slabs), dim3(256), sizeof(SolveSmem<R>), st, sb, sv.rank, (const float*)gram,

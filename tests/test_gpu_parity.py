@@ -170,6 +170,23 @@ def test_key_selection_paths_by_segment_length(n, g, ties):
     assert rep["K_nnz"] > 0
 
 
+def test_large_magnitudes_inside_the_stated_operand_range():
+    """The read feeds q * scale_K and p * scale_V to the matrix cores as fp16 operands (include/gear.h states
+    the range: |q * scale_K| < 4094).  Keys of magnitude up to 600, Values up to 1500 and |q| up to 9 give products of up to 3600: the outputs must be finite and agree with the oracle (the softmax is then one-hot)."""
+    n = 300
+    w = small_workload(B=1, H_kv=2, H_q=4, n=n, bits=2, g=64, ppm=20000, rank=2, seed=77)
+    gc, oc = pu.make_pair(1, 2, 4, 2, 64, 20000, 20, n, 1, 2)
+    K = (gw.make_keys(w, n, 0, "cpu").float() * 100.0).clamp(-600, 600).to(torch.float16).to(DEV)   # scale_K <= 400
+    V = (gw.make_values(w, n, 0, "cpu").float() * 100.0).clamp(-1500, 1500).to(torch.float16).to(DEV)
+    pu.compress_both(gc, oc, K, V, 2, 3, gw.make_init_B(w, 2, 0, DEV))
+    rep = pu.compare_components(gc, oc)
+    q = (gw.make_queries(w, 0, "cpu").float() * 2.0).clamp(-9, 9).to(torch.float16).to(DEV)               # |q * scale_K| <= 3600
+    out = gc.decode_attn(q, None, None, 0)
+    assert torch.isfinite(out.float()).all()
+    rep.update(pu.compare_attention(gc, oc, q))
+    say("  ->", rep)
+
+
 def test_lossless_grid_reconstructs_input_bit_exact():
     gc, oc = pu.make_pair(1, 2, 2, 2, 64, 0, 20, 128, 1, 4)
     g = torch.Generator(device="cpu").manual_seed(6)
