@@ -888,12 +888,11 @@ __device__ void mfma_block(unsigned char* smem, const Dims& dm, const SegView& k
       }
       wave_lds_sync();
       for (int G = 0; G < NG; ++G) {
-        half8 pa0 = __builtin_bit_cast(half8, make_uint4(0, 0, 0, 0)), pa1 = pa0;
-        if (n16 < 2 * GQ) {
-          const _Float16* src = opnd + (size_t)(G * 2 * GQ + n16) * vop(TB) + kg * (TB / 4);
-          pa0 = __builtin_bit_cast(half8, *reinterpret_cast<const uint4*>(src));
-          if (BITS == 2) pa1 = __builtin_bit_cast(half8, *reinterpret_cast<const uint4*>(src + 8));
-        }
+        // (lanes of the unused columns n16 >= 2 GQ read column 0: their output columns are never looked at)
+        const _Float16* src = opnd + (size_t)(G * 2 * GQ + (n16 < 2 * GQ ? n16 : 0)) * vop(TB) + kg * (TB / 4);
+        const half8 pa0 = __builtin_bit_cast(half8, *reinterpret_cast<const uint4*>(src));
+        half8 pa1 = pa0;
+        if (BITS == 2) pa1 = __builtin_bit_cast(half8, *reinterpret_cast<const uint4*>(src + 8));
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           if ((j >> (lg - 4)) == G) {   // channel tile j (16 channels) lies in group G

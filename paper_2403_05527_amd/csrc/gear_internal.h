@@ -376,14 +376,25 @@ __device__ __forceinline__ float row16_sum2(float v0, float v1, int lane) {
 __device__ __forceinline__ float lane_bcast(float v, int lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
-// Sum / max over the 64 lanes, result in every lane (wave-uniform).
+// Sum / max over the 64 lanes, result in every lane (wave-uniform).  After the sums inside the rows of
+// 16, lane 15 of rows 0 and 2 is added into rows 1 and 3 (row_bcast:15), then lane 31 into rows 2 and 3
+// (row_bcast:31): lane 63 holds (r2 + r3) + (r0 + r1), which one scalar read spreads to the wave.
+constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_rows_f(float old, float v) {   // rows outside ROW_MASK (and lanes without a source) keep `old`
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
   v = row16_sum(v);
-  return (lane_bcast(v, 0) + lane_bcast(v, 16)) + (lane_bcast(v, 32) + lane_bcast(v, 48));
+  v += dpp_rows_f<DPP_ROW_BCAST15, 0xA>(0.0f, v);
+  v += dpp_rows_f<DPP_ROW_BCAST31, 0xC>(0.0f, v);
+  return lane_bcast(v, 63);
 }
 __device__ __forceinline__ float wave_max(float v) {
   v = row16_max(v);
-  return fmaxf(fmaxf(lane_bcast(v, 0), lane_bcast(v, 16)), fmaxf(lane_bcast(v, 32), lane_bcast(v, 48)));
+  v = fmaxf(v, dpp_rows_f<DPP_ROW_BCAST15, 0xA>(-INFINITY, v));
+  v = fmaxf(v, dpp_rows_f<DPP_ROW_BCAST31, 0xC>(-INFINITY, v));
+  return lane_bcast(v, 63);
 }
 template <typename T>
 __device__ __forceinline__ T wave_sum_shfl(T v) {  // generic (integers, doubles)
