@@ -9,6 +9,7 @@
 //                    input Y = X - S for the power iteration
 #include "gear_internal.h"
 #include "gear_select.h"
+#include "gear_select_rows.h"
 #include "gear_launch.h"
 
 namespace gear {
@@ -83,6 +84,58 @@ __global__ __launch_bounds__(256, (NC <= 8 ? 5 : NC <= 10 ? 4 : 2)) void v_selec
         kmx = max(kmx, (uint32_t)__shfl_xor(kmx, o, 64));
       }
       if (tvalid && lane == 0) vsz[(size_t)b * n + t] = group_bits(make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), qmax));
+    }
+  }
+}
+
+// The same thresholds for token rows of at most 1024 entries (up to eight KV heads), four tokens per
+// wave: row r of 16 lanes takes token 4 (4 (blockIdx.x tpw + it) + wave) + r, lane i of the row the
+// 16-byte piece i (channels 8 i .. 8 i + 7) of each head (gear_select_rows.h).  grid (ceil(n / (16 tpw)), B),
+// block 256, 2 KB of LDS per row.  vsz: nullptr unless the per-vector grouping is on.
+__global__ __launch_bounds__(256, 4) void v_select_rows_kernel(const uint16_t* __restrict__ V, int H, int n, int tpw,
+                                                               int k_top, int k_bot, ThreshPair* __restrict__ thrV,
+                                                               uint32_t* __restrict__ vsz, float qmax) {
+  __shared__ __attribute__((aligned(16))) uint32_t hist[16 * SELECT_ROW_LDS_WORDS];
+  const int b = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, row = lane >> 4, i = lane & 15;
+  uint32_t* hrow = hist + (wave * 4 + row) * SELECT_ROW_LDS_WORDS;
+  // a view of the batch element's H * n rows; a lane whose token does not exist reads past it (zeros)
+  const GEAR_BUF_T vb = GEAR_BUF_MAKE(V + (size_t)b * H * n * D, (uint32_t)H * n * (D * 2));
+  for (int it = 0; it < tpw; ++it) {
+    const int t = ((blockIdx.x * tpw + it) * 4 + wave) * 4 + row;
+    const bool tvalid = t < n;
+    const uint32_t off0 = tvalid ? (uint32_t)t * (D * 2) + i * 16 : 0xFFFFFF00u;
+    uint4 x[8];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+      x[h] = make_uint4(0, 0, 0, 0);
+      if (h < H) {
+        const uint4 raw = GEAR_BUF_LOAD16(vb, tvalid ? off0 + (uint32_t)h * n * (D * 2) : off0);
+        x[h] = make_uint4(key16x2(raw.x), key16x2(raw.y), key16x2(raw.z), key16x2(raw.w));
+      }
+    }
+    ThreshPair tp = pack_thresh(thresh_none());
+    if (k_top > 0 || k_bot > 0) {
+      tp = pack_thresh(row_select(x, H, k_top, k_bot, hrow));
+      if (tvalid && i == 0 && thrV) thrV[(size_t)b * n + t] = tp;
+    }
+    if (vsz) {   // per-vector grouping: the token's (scale, zero), outliers counted as 0
+      uint32_t kmn = 0xFFFFu, kmx = 0u;
+#pragma unroll
+      for (int h = 0; h < 8; ++h)
+        if (h < H) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t k = slot16(x[h], e), idx = (uint32_t)(128 * h + 8 * i + e);
+            const bool out = ((k << 16) | (0xFFFFu - idx)) >= tp.top || ((k << 16) | idx) < tp.bot;
+            const uint32_t y = out ? 0x8000u : k;
+            kmn = min(kmn, y);
+            kmx = max(kmx, y);
+          }
+        }
+      kmn = row16_min_u(kmn);
+      kmx = row16_max_u(kmx);
+      if (tvalid && i == 0) vsz[(size_t)b * n + t] = group_bits(make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), qmax));
     }
   }
 }
@@ -315,7 +368,15 @@ hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dim
     const int kt = dm.ppm > 0 ? k_top : 0, kb = dm.ppm > 0 ? k_bot : 0;
     const int nc = (dm.H + 3) / 4;
     hipError_t e;
-    if (nc <= 2) e = launch_vsel<2>(V, dm, n, kt, kb, thrV, vsz, st);
+    const long long tokens = (long long)dm.B * n;
+    // short token rows: four tokens per wave (a flushed buffer has too few tokens to fill the chip that way)
+    if (dm.H <= 8 && !dm.vhead && tokens >= 16384) {
+      const int tpw = tokens >= (1 << 18) ? 4 : tokens >= (1 << 16) ? 2 : 1;   // >= 4096 blocks before a block takes more tokens
+      // (the (scale, zero) array exists only under the per-vector grouping)
+      hipLaunchKernelGGL(v_select_rows_kernel, dim3((n + 16 * tpw - 1) / (16 * tpw), dm.B), dim3(256), 0, st, V, dm.H, n, tpw,
+                         kt, kb, thrV, dm.kcvt ? vsz : (uint32_t*)nullptr, dm.qmax);
+      e = hipGetLastError();
+    } else if (nc <= 2) e = launch_vsel<2>(V, dm, n, kt, kb, thrV, vsz, st);
     else if (nc <= 4) e = launch_vsel<4>(V, dm, n, kt, kb, thrV, vsz, st);
     else if (nc <= 8) e = launch_vsel<8>(V, dm, n, kt, kb, thrV, vsz, st);
     else if (nc <= 10) e = launch_vsel<10>(V, dm, n, kt, kb, thrV, vsz, st);

@@ -123,15 +123,21 @@ inline int dpp_src(int l, int ctrl) {
 inline int dpp(int v, int ctrl) { return (int)(uint32_t)xchg((uint32_t)v, dpp_src(lane(), ctrl)); }
 // with a row mask: rows outside it keep `old`; row_bcast:15 (0x142) gives rows 1..3 lane 15 of the row before,
 // row_bcast:31 (0x143) gives rows 2, 3 lane 31; lanes without a source keep `old`
-inline int dpp_rows(int old, int v, int ctrl, int row_mask) {
-  const int l = lane(), row = l >> 4;
+// row_shl:n (0x101..0x10F): lane i of a row reads lane i + n; row_shr:n (0x111..0x11F): lane i - n; a lane whose
+// source lies outside the row reads 0 with bound_ctrl, else keeps `old`
+inline int dpp_rows(int old, int v, int ctrl, int row_mask, bool bound_ctrl = false) {
+  const int l = lane(), row = l >> 4, i = l & 15;
   int src = l;
-  bool has = ((row_mask >> row) & 1) != 0;
-  if (ctrl == 0x142) { has = has && row >= 1; src = row * 16 - 1; }
-  else if (ctrl == 0x143) { has = has && row >= 2; src = 31; }
+  bool enabled = ((row_mask >> row) & 1) != 0, valid = true;
+  if (ctrl == 0x142) { valid = row >= 1; src = row * 16 - 1; }
+  else if (ctrl == 0x143) { valid = row >= 2; src = 31; }
+  else if (ctrl >= 0x101 && ctrl <= 0x10F) { valid = i + (ctrl & 15) <= 15; src = l + (ctrl & 15); }
+  else if (ctrl >= 0x111 && ctrl <= 0x11F) { valid = i - (ctrl & 15) >= 0; src = l - (ctrl & 15); }
   else src = dpp_src(l, ctrl);
-  const int got = (int)(uint32_t)xchg((uint32_t)v, has ? src : l);
-  return has ? got : old;
+  const int got = (int)(uint32_t)xchg((uint32_t)v, (enabled && valid) ? src : l);
+  if (!enabled) return old;
+  if (!valid) return bound_ctrl ? 0 : old;
+  return got;
 }
 inline int readlane(int v, int l) { return (int)(uint32_t)xchg((uint32_t)v, l); }
 template <typename T>
@@ -200,7 +206,7 @@ inline void launch(dim3 grid, dim3 block, size_t lds, F&& body) {
 }
 }  // namespace simt
 
-#define __builtin_amdgcn_update_dpp(old, src, ctrl, rm, bm, bc) simt::dpp_rows((old), (src), (ctrl), (rm))
+#define __builtin_amdgcn_update_dpp(old, src, ctrl, rm, bm, bc) simt::dpp_rows((old), (src), (ctrl), (rm), (bc))
 #define __builtin_amdgcn_readlane(v, l) simt::readlane((v), (l))
 #define __builtin_amdgcn_fence(...) ((void)0)
 #define __builtin_amdgcn_wave_barrier() simt::wave_barrier()

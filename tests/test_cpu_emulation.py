@@ -63,6 +63,7 @@ def emulator(tmp_path_factory):
 @pytest.mark.parametrize("B,H,Hq,n,bits,g,ppm,rank,n_buf,per_head", [
     (1, 4, 8, 290, 2, 64, 20000, 4, 5, False),     # the method as stated; n > 256: Gram-matrix power iteration
     (1, 2, 2, 140, 4, 0, 30000, 2, 3, True),       # per-vector groups and the per-head Value Filter
+    (1, 8, 8, 70, 2, 64, 20000, 2, 3, False),      # eight KV heads: Value token rows of 1024 entries, four per wave
 ])
 def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits, g, ppm, rank, n_buf, per_head):
     w = gw.Workload("emu", B=B, H_kv=H, H_q=Hq, n=n, bits=bits, group=g, outlier_ppm=ppm, rank=rank,

@@ -170,6 +170,35 @@ def test_key_selection_paths_by_segment_length(n, g, ties):
     assert rep["K_nnz"] > 0
 
 
+@pytest.mark.parametrize("H_kv,g,ties", [(4, 64, False), (8, 64, True), (2, 0, True), (1, 128, False)])
+def test_value_selection_four_token_rows_per_wave(H_kv, g, ties):
+    """With at most eight KV heads and at least 16384 tokens in a call the per-token Value Filter (Eq. 4 over the
+    token's H_kv * 128 entries) runs four tokens per wave, one per row of 16 lanes.  Element-wise against the oracle
+    at a ragged length; `ties`: Values on a coarse grid with constant and signed-zero heads, so that the threshold
+    value is shared by many entries (within one side, and between the top and the bottom side)."""
+    B = 16 // H_kv * 2
+    n = 16384 // B + 37
+    bits = 4 if g == 0 else 2
+    w = small_workload(B=B, H_kv=H_kv, H_q=H_kv, n=n, bits=bits, g=g, ppm=20000, rank=0, seed=900 + H_kv)
+    say("case value rows", w, "ties", ties)
+    gc, oc = pu.make_pair(B, H_kv, H_kv, bits, g, 20000, 20, n, 1, 2)
+    K = gw.make_keys(w, n, 0, DEV)
+    if ties:
+        gen = torch.Generator(device="cpu").manual_seed(n)
+        V = (torch.randint(-3, 4, (B, H_kv, n, 128), generator=gen).float() * 0.25)
+        V[0, 0] = 0.75                                   # constant head
+        V[1, H_kv - 1] = 0.0
+        V[1, H_kv - 1, ::2] = -0.0                       # signed zeros only
+        V = V.to(torch.float16).to(DEV)
+    else:
+        V = gw.make_values(w, n, 0, DEV)
+    pu.compress_both(gc, oc, K, V, 0, 1, None)
+    rep = pu.compare_components(gc, oc)
+    rep.update(pu.compare_decompress(gc, oc))
+    say("  ->", rep)
+    assert rep["V_nnz"] > 0
+
+
 def test_large_magnitudes_inside_the_stated_operand_range():
     """The read feeds q * scale_K and p * scale_V to the matrix cores as fp16 operands (include/gear.h states
     the range: |q * scale_K| < 4094).  Keys of magnitude up to 600, Values up to 1500 and |q| up to 9 give products of up to 3600: the outputs must be finite and agree with the oracle (the softmax is then one-hot)."""
