@@ -243,7 +243,7 @@ __global__ __launch_bounds__(256) void k_select_long_kernel(const uint16_t* __re
 // longer falls with the segment length.  The vector arrives 1024 tokens at a time: thread tid loads the
 // 16-byte row pieces (8 channels) of rows 2 tid and 2 tid + 1, pairs the two rows' keys of each channel
 // in one word and writes it to stage[channel][tid]; wave w then reads channel w's 1024 keys back as two
-// 16-byte pieces per lane.  The next 1024 tokens' loads are in flight meanwhile.
+// 16-byte pieces per lane.  All of a thread's loads are requested at the start.
 // 1-D grid of 16 * B*H blocks of 512 threads, decoded XCD-aware like k_select_kernel.
 template <int NC>
 __global__ __launch_bounds__(512, (NC <= 8 ? 4 : 2)) void k_select_reg_kernel(const uint16_t* __restrict__ K, int n, int nslab,
@@ -266,15 +266,17 @@ __global__ __launch_bounds__(512, (NC <= 8 ? 4 : 2)) void k_select_reg_kernel(co
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   // a view of the column block that ends with its last row: rows past n read as 0
   const GEAR_BUF_T xb = GEAR_BUF_MAKE(K + (size_t)slab * n * D + cb * 8, (n - 1) * (D * 2) + 16);
-  uint4 x[NC];
-  uint4 ra = GEAR_BUF_LOAD16(xb, (2 * tid) * (D * 2)), rb = GEAR_BUF_LOAD16(xb, (2 * tid + 1) * (D * 2));
+  // every row piece of the thread is requested before the first one is used (rows past n read as 0): the
+  // pieces wait in the registers that the finished chunks take over one after another
+  uint4 x[NC], raw[NC];
 #pragma unroll
   for (int it = 0; it < NC / 2; ++it) {
-    uint4 na = make_uint4(0, 0, 0, 0), nb = na;
-    if (it + 1 < NC / 2 && (it + 1) * 1024 < n) {   // block-uniform
-      na = GEAR_BUF_LOAD16(xb, ((it + 1) * 1024 + 2 * tid) * (D * 2));
-      nb = GEAR_BUF_LOAD16(xb, ((it + 1) * 1024 + 2 * tid + 1) * (D * 2));
-    }
+    raw[2 * it] = GEAR_BUF_LOAD16(xb, (it * 1024 + 2 * tid) * (D * 2));
+    raw[2 * it + 1] = GEAR_BUF_LOAD16(xb, (it * 1024 + 2 * tid + 1) * (D * 2));
+  }
+#pragma unroll
+  for (int it = 0; it < NC / 2; ++it) {
+    const uint4 ra = raw[2 * it], rb = raw[2 * it + 1];
     const uint32_t ka[4] = {key16x2(ra.x), key16x2(ra.y), key16x2(ra.z), key16x2(ra.w)};
     const uint32_t kb[4] = {key16x2(rb.x), key16x2(rb.y), key16x2(rb.z), key16x2(rb.w)};
 #pragma unroll
@@ -286,8 +288,6 @@ __global__ __launch_bounds__(512, (NC <= 8 ? 4 : 2)) void k_select_reg_kernel(co
     x[2 * it] = *reinterpret_cast<const uint4*>(&stage[wave][lane * 4]);
     x[2 * it + 1] = *reinterpret_cast<const uint4*>(&stage[wave][256 + lane * 4]);
     block_lds_sync();
-    ra = na;
-    rb = nb;
   }
   RegSource<NC> src{x};
   const Thresh th = wave_select(src, n, k_top, k_bot, hist + wave * SELECT_LDS_WORDS, true);

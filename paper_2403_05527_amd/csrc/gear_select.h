@@ -306,12 +306,17 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
   // ---- level 1: histogram of the high key byte
   for (int i = lane; i < 512; i += 64) hist[i] = 0u;
   wave_lds_sync();
+  // (two copies of the histogram, one for the even and one for the odd lanes: most of a vector falls into a
+  // few bins, and adds of one instruction to one address are applied one after another)
+  uint32_t* hmine = hist + ((lane & 1) << 8);
   for_each_chunk(src, nch, [&](int ch, const uint4& v) {
     const int base = ch * 512 + lane * 8;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      if (base + e < N) atomicAdd(&hist[slot16(v, e) >> 8], 1u);
+      if (base + e < N) atomicAdd(&hmine[slot16(v, e) >> 8], 1u);
   });
+  wave_lds_sync();
+  for (int i = lane; i < 256; i += 64) hist[i] += hist[256 + i];
   wave_lds_sync();
   int bin_t = -1, bin_b = -1;
   uint32_t need_t = 0, need_b = 0;
