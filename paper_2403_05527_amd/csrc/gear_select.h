@@ -333,8 +333,6 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
   wave_lds_sync();
 
   // ---- level 2: histograms of the low key byte inside the two boundary bins
-  // one add per entry and no branch: entries of neither bin (and the padding past N)
-  // add 0
   for (int i = lane; i < 512; i += 64) hist[i] = 0u;
   wave_lds_sync();
   for_each_chunk(src, nch, [&](int ch, const uint4& v) {
@@ -344,8 +342,9 @@ __device__ __forceinline__ Thresh wave_select(const Src& src, int N, int k_top, 
       const uint32_t k = slot16(v, e);
       const int hi = (base + e < N) ? (int)(k >> 8) : -2;
       const bool in_t = hi == bin_t, in_b = hi == bin_b;
-      const uint32_t lo = hi >= 0 ? (k & 255u) : (uint32_t)lane;   // padding: one address per lane, not one for all
-      atomicAdd(&hist[(in_t ? 0u : 256u) + lo], (in_t || in_b) ? 1u : 0u);
+      // (only the few lanes with an entry in a boundary bin take part: the LDS serves an add of 64 lanes to
+      // random bins in ~7 cycles, of a handful of lanes in 2)
+      if (in_t || in_b) atomicAdd(&hist[(in_t ? 0u : 256u) + (k & 255u)], 1u);
     }
   });
   wave_lds_sync();

@@ -171,8 +171,8 @@ __device__ __forceinline__ Thresh row_select(const uint4 (&x)[8], int H, int k_t
   }
   wave_lds_sync();
 
-  // ---- level 2: histograms of the low key byte inside the two boundary bins (one add per entry, no
-  // branch: entries of neither bin add 0)
+  // ---- level 2: histograms of the low key byte inside the two boundary bins (only the lanes with an entry
+  // in one of them take part in an add)
 #pragma unroll
   for (int j = 0; j < 512; j += 64) *reinterpret_cast<uint4*>(hist + j + 4 * i) = make_uint4(0, 0, 0, 0);
   wave_lds_sync();
@@ -184,7 +184,7 @@ __device__ __forceinline__ Thresh row_select(const uint4 (&x)[8], int H, int k_t
         const uint32_t k = slot16(x[h], e);
         const int hi = (int)(k >> 8);
         const bool in_t = hi == bin_t, in_b = hi == bin_b;
-        atomicAdd(&hist[(in_t ? 0u : 256u) + (k & 255u)], (in_t || in_b) ? 1u : 0u);
+        if (in_t || in_b) atomicAdd(&hist[(in_t ? 0u : 256u) + (k & 255u)], 1u);
       }
     }
   wave_lds_sync();
