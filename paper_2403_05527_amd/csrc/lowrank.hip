@@ -63,6 +63,47 @@ __device__ __forceinline__ double wave_sum_d(double v) {
   v += dpp_d<DPP_MIRROR>(v);
   return (lane_bcast_d(v, 0) + lane_bcast_d(v, 16)) + (lane_bcast_d(v, 32) + lane_bcast_d(v, 48));
 }
+// Gram-Schmidt in coefficient space: given the r x r Gram matrix G = A^T A of the columns of some A, finds C
+// with orth(A) = A C (column j of orth(A) is A * C[:, j]; dependent columns get C[:, j] = 0).  Called by the
+// 64 threads c = 0..63 of one wave; lane a * R + b carries the (a, b) term of every quadratic form x^T G y, a
+// sum over the wave finishes it.  G, C, cj: LDS.
+template <int R>
+__device__ __forceinline__ void coeff_orth(double (&G)[R][R], double (&C)[R][R], double* cj, int c) {
+  const int a = c / R, b = c % R;
+  const bool in = c < R * R;
+  const double Gab = in ? G[a][b] : 0.0;
+  uint32_t valid = 0;   // bit j: column j is kept
+  for (int j = 0; j < R; ++j) {
+    if (c < R) cj[c] = (c == j) ? 1.0 : 0.0;
+    wave_lds_sync();
+    const double before2 = G[j][j];
+    bool ok = before2 > 0.0;
+    if (ok) {
+      for (int pass = 0; pass < 2; ++pass)
+        for (int k = 0; k < j; ++k) {
+          if (!((valid >> k) & 1u)) continue;
+          const double dot = wave_sum_d(in ? C[a][k] * Gab * cj[b] : 0.0);   // q_k^T v = c_k^T G c_j
+          wave_lds_sync();
+          if (c < R) cj[c] -= dot * C[c][k];
+          wave_lds_sync();
+        }
+      const double after2 = wave_sum_d(in ? cj[a] * Gab * cj[b] : 0.0);
+      wave_lds_sync();
+      // (the Gram matrix is a sum of fp32 products: what is left of a dependent column is
+      // rounding noise of relative size ~1e-7 in after2, so the cut sits above that)
+      if (!(after2 > 1e-6 * before2)) ok = false;
+      else {
+        const double inv = 1.0 / sqrt(after2);
+        if (c < R) cj[c] *= inv;
+        wave_lds_sync();
+      }
+    }
+    if (ok) valid |= 1u << j;
+    if (c < R) C[c][j] = ok ? cj[c] : 0.0;
+    wave_lds_sync();
+  }
+}
+
 // grid (B*H), block 256: thread c < 128 owns row c of the [128 x R] matrix.
 // from_start          : B <- the start matrix (zero-padded to R)
 // else                : B <- sum over `npart` partials ([slab][npart][128*R + R*R])
@@ -138,44 +179,7 @@ __device__ __forceinline__ void pi_update_body(UpdateSmem<R>& sm, int slab, bool
       G[gi / R][gi % R] = s;
     }
     block_lds_sync();
-    if (c < 64) {
-      // Gram-Schmidt in coefficient space: column j of orth(A) is A * C[:, j].  Wave 0 runs it; lane a * R + b
-      // carries the (a, b) term of every quadratic form x^T G y, a sum over the wave finishes it.
-      const int a = c / R, b = c % R;
-      const bool in = c < R * R;
-      const double Gab = in ? G[a][b] : 0.0;
-      uint32_t valid = 0;   // bit j: column j is kept
-      double* cj = sm.cj;
-      for (int j = 0; j < R; ++j) {
-        if (c < R) cj[c] = (c == j) ? 1.0 : 0.0;
-        wave_lds_sync();
-        const double before2 = G[j][j];
-        bool ok = before2 > 0.0;
-        if (ok) {
-          for (int pass = 0; pass < 2; ++pass)
-            for (int k = 0; k < j; ++k) {
-              if (!((valid >> k) & 1u)) continue;
-              const double dot = wave_sum_d(in ? C[a][k] * Gab * cj[b] : 0.0);   // q_k^T v = c_k^T G c_j
-              wave_lds_sync();
-              if (c < R) cj[c] -= dot * C[c][k];
-              wave_lds_sync();
-            }
-          const double after2 = wave_sum_d(in ? cj[a] * Gab * cj[b] : 0.0);
-          wave_lds_sync();
-          // (the Gram matrix is a sum of fp32 products: what is left of a dependent column is
-          // rounding noise of relative size ~1e-7 in after2, so the cut sits above that)
-          if (!(after2 > 1e-6 * before2)) ok = false;
-          else {
-            const double inv = 1.0 / sqrt(after2);
-            if (c < R) cj[c] *= inv;
-            wave_lds_sync();
-          }
-        }
-        if (ok) valid |= 1u << j;
-        if (c < R) C[c][j] = ok ? cj[c] : 0.0;
-        wave_lds_sync();
-      }
-    }
+    if (c < 64) coeff_orth<R>(G, C, sm.cj, c);
     block_lds_sync();
     double o[R];
 #pragma unroll
@@ -255,12 +259,14 @@ struct SweepSmem {
   __attribute__((aligned(16))) float prm[IS_K ? 2 * (PT / 32) * D : PT * 4 * 4];
 };
 // One block's share of a sweep: rows [pt * PT, pt * PT + PT) of slab `slab`, 256 threads.
-template <bool IS_K, int R, bool LAST>
+// PROJECT: only A = R B is wanted, and it is the final A (B holds the projection matrix of the last round):
+// rows go to the arena as fp16, nothing is accumulated.
+template <bool IS_K, int R, bool LAST, bool PROJECT = false>
 __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, int pt, const uint16_t* __restrict__ Y,
                                               const uint32_t* __restrict__ sv_sz, const uint32_t* __restrict__ sv_codes,
                                               int sv_n_cap, int sv_ng_cap, int g, int bits, int n, int t_lr,
                                               const float* __restrict__ Bcur, float* __restrict__ partial, int npart,
-                                              float* __restrict__ Atmp) {
+                                              float* __restrict__ Atmp, uint16_t* __restrict__ A_out = nullptr, int rank = 0) {
   float (&red)[4][D * R] = sm.red;
   float (&redg)[4][R * R] = sm.redg;
   float* prm = sm.prm;
@@ -402,6 +408,12 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) bsel[nb] = 0.0f;
       }
+      if constexpr (PROJECT) {
+        // lane oc < R holds a_t[oc]
+        const float mine = (NB > 1 && oc >= 4) ? bsel[NB - 1] : bsel[0];
+        if (oc < rank && t < n) A_out[((size_t)slab * sv_n_cap + t) * rank + oc] = (uint16_t)f2h(mine);
+        continue;
+      }
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
@@ -425,6 +437,7 @@ __device__ __forceinline__ void pi_sweep_body(SweepSmem<IS_K, R>& sm, int slab, 
     }
   }
 
+  if constexpr (PROJECT) return;
   // reduce over the 16 row-threads that share a channel octet
 #pragma unroll
   for (int e = 0; e < 8; ++e)
@@ -473,6 +486,16 @@ __global__ __launch_bounds__(256, (R <= 2 ? 4 : R <= 4 ? 3 : 2)) void pi_sweep_k
   __shared__ SweepSmem<IS_K, R> sm;
   pi_sweep_body<IS_K, R, LAST>(sm, blockIdx.y, blockIdx.x, Y, sv.sz, sv.codes, sv.n_cap, sv.ng_cap, g, bits, n, t_lr, Bcur, partial,
                                npart, Atmp);
+}
+
+// The pass of the last round when the Gram matrix exists: A = R W with the projection matrix W that
+// pi_solve_kernel left in Bcur, written to the arena as fp16.  grid (ceil(n / 256), B*H), block 256.
+template <bool IS_K, int R>
+__global__ __launch_bounds__(256, (R <= 4 ? 4 : 3)) void pi_project_kernel(const uint16_t* __restrict__ Y, SegView sv, int g, int bits,
+                                                                         int n, int t_lr, const float* __restrict__ Bcur) {
+  __shared__ SweepSmem<IS_K, R> sm;
+  pi_sweep_body<IS_K, R, false, true>(sm, blockIdx.y, blockIdx.x, Y, sv.sz, sv.codes, sv.n_cap, sv.ng_cap, g, bits, n, t_lr, Bcur,
+                                      nullptr, 0, nullptr, sv.A, sv.rank);
 }
 
 // A = a C for tokens [256 * pt, 256 * pt + 256) of one slab, one token per thread.  Cs: LDS, R * R floats.
@@ -743,7 +766,10 @@ struct SolveSmem {
   float G[D * GP];
   double Bs[D][R];
   double part[D][R];   // the upper half block's share of a product
-  double red[4 * (R + 1)];
+  double red[4 * (R * R > R + 1 ? R * R : R + 1)];
+  double GA[R][R];     // the last round: Gram matrix of A = R B, the factor C of its orthonormalisation
+  double C[R][R];
+  double cj[R];
 };
 // Sums of N per-thread values over the block (256 threads), all in every thread: one pair of
 // barriers for the N sums together.
@@ -777,7 +803,7 @@ __device__ __forceinline__ double rsqrt_d(double x) {
 template <int R>
 __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
                                                        const float* __restrict__ gram_partial, int nstrips, int rounds,
-                                                       float* __restrict__ Bcur) {
+                                                       float* __restrict__ Bcur, int last_round, SegView sv) {
   GEAR_DYN_LDS(smem_raw);
   SolveSmem<R>& sm = *reinterpret_cast<SolveSmem<R>*>(smem_raw);
   const int slab = blockIdx.x, c = threadIdx.x & (D - 1), half = threadIdx.x >> 7;
@@ -869,9 +895,65 @@ __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
     if (!(a2[0] > 1e-24 * before2)) q[j] = 0.0;   // norm after <= 1e-12 * norm before
     else q[j] *= rsqrt_d(a2[0]);
   }
+  if (!last_round) {
+    if (owner) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) Bcur[((size_t)slab * D + c) * R + r] = (float)q[r];
+    }
+    return;
+  }
+  // The last round of Algorithm 2 without another pass over R for B: with A = R B (B orthonormal now),
+  // orth(A) = A C and the round's result B' = R^T orth(A) = (R^T R) B C = G B C, while the r x r Gram matrix
+  // that gives C is A^T A = B^T G B.  What is left for the pass over R is A itself: orth(A) = R (B C), so
+  // the projection matrix W = B C goes to Bcur and B' to the arena.
+  block_lds_sync();
   if (owner) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) Bcur[((size_t)slab * D + c) * R + r] = (float)q[r];
+    for (int r = 0; r < R; ++r) sm.Bs[c][r] = q[r];
+  }
+  block_lds_sync();
+  double pr[R];   // row c of P = G B
+#pragma unroll
+  for (int r = 0; r < R; ++r) pr[r] = 0.0;
+#pragma unroll 8
+  for (int k = 64 * half; k < 64 * half + 64; ++k) {
+    const double gk = (double)sm.G[k * GP + c];
+#pragma unroll
+    for (int r = 0; r < R; ++r) pr[r] += gk * sm.Bs[k][r];
+  }
+  if (!owner) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) sm.part[c][r] = pr[r];
+  }
+  block_lds_sync();
+#pragma unroll
+  for (int r = 0; r < R; ++r) pr[r] = owner ? pr[r] + sm.part[c][r] : 0.0;
+  {
+    double d[R * R];   // B^T P, every entry in every thread
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+#pragma unroll
+      for (int j = 0; j < R; ++j) d[i * R + j] = q[i] * pr[j];
+    block_sum_vec<R * R>(d, sm.red);
+#pragma unroll
+    for (int i = 0; i < R * R; ++i)
+      if ((int)threadIdx.x == i) sm.GA[i / R][i % R] = 0.5 * (d[i] + d[(i % R) * R + i / R]);   // symmetric up to rounding
+  }
+  block_lds_sync();
+  if (threadIdx.x < 64) coeff_orth<R>(sm.GA, sm.C, sm.cj, (int)threadIdx.x);
+  block_lds_sync();
+  if (owner) {
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      double w = 0.0, bo = 0.0;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        w += q[r] * sm.C[r][j];
+        bo += pr[r] * sm.C[r][j];
+      }
+      Bcur[((size_t)slab * D + c) * R + j] = (float)w;
+      if (j < rank) sv.Bf[((size_t)slab * D + c) * sv.rank + j] = (uint16_t)f2h((float)bo);
+    }
   }
 }
 
@@ -931,8 +1013,17 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
     }
   }
   hipLaunchKernelGGL(pi_solve_kernel<R>, dim3(slabs), dim3(256), sizeof(SolveSmem<R>), st, sb, sv.rank, (const float*)gram,
-                     nstrips, iters - 1, Bcur);
-  // the last round: A = R B, orth(A) through its r x r Gram matrix, B = R^T A
+                     nstrips, iters - 1, Bcur, iters > 1 ? 1 : 0, sv);
+  if (iters > 1) {
+    // the last round's B and the factor of orth(A) came out of the Gram matrix; one light pass writes A
+    const dim3 grid(npart, slabs);
+    if (is_k)
+      hipLaunchKernelGGL((pi_project_kernel<true, R>), grid, dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, t_lr, (const float*)Bcur);
+    else
+      hipLaunchKernelGGL((pi_project_kernel<false, R>), grid, dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, t_lr, (const float*)Bcur);
+    return hipGetLastError();
+  }
+  // a single round (no Gram pass): A = R B, orth(A) through its r x r Gram matrix, B = R^T A
   {
     const dim3 grid(npart, slabs);
     if (is_k)
