@@ -766,7 +766,7 @@ struct SolveSmem {
   float G[D * GP];
   double Bs[D][R];
   double part[D][R];   // the upper half block's share of a product
-  double red[4 * (R * R > R + 1 ? R * R : R + 1)];
+  double red[4 * (R + 1)];
   double GA[R][R];     // the last round: Gram matrix of A = R B, the factor C of its orthonormalisation
   double C[R][R];
   double cj[R];
@@ -928,16 +928,27 @@ __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
   block_lds_sync();
 #pragma unroll
   for (int r = 0; r < R; ++r) pr[r] = owner ? pr[r] + sm.part[c][r] : 0.0;
-  {
-    double d[R * R];   // B^T P, every entry in every thread
+  block_lds_sync();
+  if (owner) {   // the whole rows of P, next to those of B in LDS
 #pragma unroll
-    for (int i = 0; i < R; ++i)
-#pragma unroll
-      for (int j = 0; j < R; ++j) d[i * R + j] = q[i] * pr[j];
-    block_sum_vec<R * R>(d, sm.red);
-#pragma unroll
-    for (int i = 0; i < R * R; ++i)
-      if ((int)threadIdx.x == i) sm.GA[i / R][i % R] = 0.5 * (d[i] + d[(i % R) * R + i / R]);   // symmetric up to rounding
+    for (int r = 0; r < R; ++r) sm.part[c][r] = pr[r];
+  }
+  block_lds_sync();
+  if (threadIdx.x < R * R) {   // entry (i, j) of B^T P: one thread each (four running sums)
+    const int i = threadIdx.x / R, j = threadIdx.x % R;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    for (int k = 0; k < D; k += 4) {
+      s0 += sm.Bs[k][i] * sm.part[k][j];
+      s1 += sm.Bs[k + 1][i] * sm.part[k + 1][j];
+      s2 += sm.Bs[k + 2][i] * sm.part[k + 2][j];
+      s3 += sm.Bs[k + 3][i] * sm.part[k + 3][j];
+    }
+    sm.C[i][j] = (s0 + s1) + (s2 + s3);
+  }
+  block_lds_sync();
+  if (threadIdx.x < R * R) {   // symmetric up to rounding
+    const int i = threadIdx.x / R, j = threadIdx.x % R;
+    sm.GA[i][j] = 0.5 * (sm.C[i][j] + sm.C[j][i]);
   }
   block_lds_sync();
   if (threadIdx.x < 64) coeff_orth<R>(sm.GA, sm.C, sm.cj, (int)threadIdx.x);
