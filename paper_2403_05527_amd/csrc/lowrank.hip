@@ -765,7 +765,7 @@ template <int R>
 struct SolveSmem {
   float G[D * GP];
   double Bs[D][R];
-  double part[D][R];   // the upper half block's share of a product
+  float part[D][R];    // the upper half block's share of a product (single precision: with it two blocks fit a CU)
   double red[4 * (R + 1)];
   double GA[R][R];     // the last round: Gram matrix of A = R B, the factor C of its orthonormalisation
   double C[R][R];
@@ -855,7 +855,7 @@ __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
     }
     if (!owner) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) sm.part[c][r] = qn[r];
+      for (int r = 0; r < R; ++r) sm.part[c][r] = (float)qn[r];
     }
     block_lds_sync();
     // keep magnitudes in range between rounds
@@ -923,7 +923,7 @@ __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
   }
   if (!owner) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) sm.part[c][r] = pr[r];
+    for (int r = 0; r < R; ++r) sm.part[c][r] = (float)pr[r];
   }
   block_lds_sync();
 #pragma unroll
@@ -931,7 +931,7 @@ __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
   block_lds_sync();
   if (owner) {   // the whole rows of P, next to those of B in LDS
 #pragma unroll
-    for (int r = 0; r < R; ++r) sm.part[c][r] = pr[r];
+    for (int r = 0; r < R; ++r) sm.part[c][r] = (float)pr[r];
   }
   block_lds_sync();
   if (threadIdx.x < R * R) {   // entry (i, j) of B^T P: one thread each (four running sums)
