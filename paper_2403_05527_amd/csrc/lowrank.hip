@@ -13,6 +13,11 @@
 //                own: they become 128 x 128 x r products on G.
 //   pi_solve   : B <- G^(L-1) B0 (columns rescaled between the products: the span,
 //                hence A B^T, is unchanged), then the QR of B that opens the last round.
+//                With L > 1 the last round comes out of G as well: for A = R Q (Q = that
+//                orthonormal B), A^T A = Q^T G Q gives the r x r factor C with orth(A) = A C,
+//                and the final B = R^T orth(A) = G Q C; the kernel writes B (fp16) and W = Q C.
+//   pi_project : A = R W per token, rounded to fp16: the one pass over R of the last round.
+//   (L = 1 has no Gram pass; its single round runs as sweep + update + finish below.)
 //   pi_update  : B <- start matrix or sum of the sweep partials; column scaling
 //                between rounds (the span, hence A B^T, is unchanged); QR of B
 //                before the last round; after the last round the r x r factor
