@@ -27,6 +27,7 @@
 //                Gram matrix sum_t a_t a_t^T.
 //   pi_finish  : A = a C  (C = the r x r factor), rounded to fp16.
 //   pi_small   : all of the above for a segment of at most 256 tokens, in one block per slab.
+//   pi_tiny    : a segment of at most 64 tokens (a flushed buffer): one block per slab with the residual in LDS.
 #include <atomic>
 #include "gear_internal.h"
 #include "gear_launch.h"
@@ -803,6 +804,36 @@ __device__ __forceinline__ double rsqrt_d(double x) {
   y = y * (1.5 - 0.5 * m * y * y);
   return __builtin_bit_cast(double, __builtin_bit_cast(uint64_t, y) - ((uint64_t)h << 52));   // y * 2^-h
 }
+// QR of B (row c of B in thread c < 128; the other threads of the block hold zeros) by Gram-Schmidt
+// applied twice (the projections of a pass are taken together: one block reduction per pass);
+// dependent columns become 0.  Called by all 256 threads.
+template <int R>
+__device__ __forceinline__ void qr_columns(double (&q)[R], double* red /* 4 * (R + 1) */) {
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    double d[R + 1];
+#pragma unroll
+    for (int i = 0; i < R; ++i) d[i] = i < j ? q[i] * q[j] : 0.0;
+    d[R] = q[j] * q[j];
+    block_sum_vec<R + 1>(d, red);
+    const double before2 = d[R];
+    if (before2 == 0.0) { q[j] = 0.0; continue; }   // block-uniform
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+      if (i < j) q[j] -= d[i] * q[i];
+#pragma unroll
+    for (int i = 0; i < R; ++i) d[i] = i < j ? q[i] * q[j] : 0.0;
+    d[R] = 0.0;
+    block_sum_vec<R + 1>(d, red);
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+      if (i < j) q[j] -= d[i] * q[i];
+    double a2[1] = {q[j] * q[j]};
+    block_sum_vec<1>(a2, red);
+    if (!(a2[0] > 1e-24 * before2)) q[j] = 0.0;   // norm after <= 1e-12 * norm before
+    else q[j] *= rsqrt_d(a2[0]);
+  }
+}
 // grid (B*H), block 256: thread (half = tid / 128, c = tid % 128).  Row c of B belongs to thread
 // (0, c); the upper half of the block helps with the loads of G and with half of every product.
 template <int R>
@@ -874,32 +905,7 @@ __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
 #pragma unroll
     for (int r = 0; r < R; ++r) q[r] = n2[r] > 0.0 ? qn[r] * rsqrt_d(n2[r]) : 0.0;
   }
-  // QR of B by Gram-Schmidt applied twice (the projections of a pass are taken together: one
-  // block reduction per pass); dependent columns become 0.  (The upper half block holds zeros.)
-#pragma unroll
-  for (int j = 0; j < R; ++j) {
-    double d[R + 1];
-#pragma unroll
-    for (int i = 0; i < R; ++i) d[i] = i < j ? q[i] * q[j] : 0.0;
-    d[R] = q[j] * q[j];
-    block_sum_vec<R + 1>(d, sm.red);
-    const double before2 = d[R];
-    if (before2 == 0.0) { q[j] = 0.0; continue; }   // block-uniform
-#pragma unroll
-    for (int i = 0; i < R; ++i)
-      if (i < j) q[j] -= d[i] * q[i];
-#pragma unroll
-    for (int i = 0; i < R; ++i) d[i] = i < j ? q[i] * q[j] : 0.0;
-    d[R] = 0.0;
-    block_sum_vec<R + 1>(d, sm.red);
-#pragma unroll
-    for (int i = 0; i < R; ++i)
-      if (i < j) q[j] -= d[i] * q[i];
-    double a2[1] = {q[j] * q[j]};
-    block_sum_vec<1>(a2, sm.red);
-    if (!(a2[0] > 1e-24 * before2)) q[j] = 0.0;   // norm after <= 1e-12 * norm before
-    else q[j] *= rsqrt_d(a2[0]);
-  }
+  qr_columns<R>(q, sm.red);
   if (!last_round) {
     if (owner) {
 #pragma unroll
@@ -973,6 +979,196 @@ __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
   }
 }
 
+// ------------------------------------------------------------------ segments of at most 64 tokens
+// A flushed streaming buffer (n_b = 20 .. 64 tokens in the paper's settings) is small enough for one
+// block to keep its residual in LDS: the rows are read and the residual derived once, and every round
+// of Algorithm 2 runs out of LDS with a handful of block barriers; nothing goes through the workspace.
+// Same steps and the same precision choices as the kernels above: A = R B and B' = R^T A accumulate in
+// fp32, column scaling, the QR of B and the coefficient-space orth(A) in fp64.
+// grid (B*H), block 256.  Thread (r0 = tid/16, oc = tid%16) derives channels 8*oc..+7 of rows
+// r0 + 16 k and later forms their share of A; thread (half = tid/128, c = tid%128) sums rows
+// [32 half, 32 half + 32) of B'[c][:], thread (0, c) owns row c of B.
+constexpr int TINY_ROWS = 64;
+constexpr int TINY_PITCH = D + 4;   // floats per residual row in LDS (16-byte aligned pieces)
+template <int R>
+struct TinySmem {
+  __attribute__((aligned(16))) float Rs[TINY_ROWS][TINY_PITCH];   // rows >= n are 0
+  __attribute__((aligned(16))) float Bs[D][R];
+  float As[TINY_ROWS][R];
+  float part[D][R];
+  double red[4 * (R + 1)];
+  double GA[R][R];
+  double C[R][R];
+  double cj[R];
+};
+template <bool IS_K, int R>
+__global__ __launch_bounds__(256) void pi_tiny_kernel(const uint16_t* __restrict__ Y, SegView sv, int g, int bits, int n,
+                                                      int t_lr, int iters, StartB sb) {
+  __shared__ TinySmem<R> sm;
+  const int slab = blockIdx.x, tid = threadIdx.x;
+  const int r0 = tid >> 4, oc = tid & 15;
+  const int c = tid & (D - 1), half = tid >> 7;
+  const bool owner = half == 0;
+  const int rank = sv.rank;
+  // ---- the residual, once: R = (Y - zero) - code * scale (Keys: stored codes; Values: the quantizer's sequence)
+  {
+    const int lg = 31 - __clz(g), ngl = 7 - lg;   // (Keys with per-vector groups pass g = 32768: one group)
+    const float qmax = (float)((1 << bits) - 1);
+    const GEAR_BUF_T xbuf = GEAR_BUF_MAKE(Y + (size_t)slab * n * D, n * (D * 2));
+    const GEAR_BUF_T cbuf = GEAR_BUF_MAKE(sv.codes + (size_t)slab * sv.n_cap * (4 * bits), IS_K ? n * (16 * bits) : 0);
+    const GEAR_BUF_T pbuf = IS_K ? GEAR_BUF_MAKE(sv.sz + (size_t)slab * sv.ng_cap * D, ((n + g - 1) >> lg) * (D * 4))
+                                 : GEAR_BUF_MAKE(sv.sz + (((size_t)slab * sv.n_cap) << ngl), (n << ngl) * 4);
+    uint4 xv[4], pz[2][2];
+    uint32_t cw[4], pv[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {   // every load is requested before the first one is used
+      const int t = r0 + 16 * k;
+      xv[k] = GEAR_BUF_LOAD16_NT(xbuf, t * (D * 2) + oc * 16);   // rows past the end read as 0
+      cw[k] = 0u;
+      pv[k] = 0u;
+      if (IS_K) {
+        const int co = t * (16 * bits) + oc * (bits == 4 ? 4 : 2);
+        cw[k] = bits == 4 ? GEAR_BUF_LOAD4(cbuf, co) : GEAR_BUF_LOAD2(cbuf, co);
+      } else {
+        pv[k] = GEAR_BUF_LOAD4(pbuf, ((t << ngl) + ((oc * 8) >> lg)) * 4);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {   // Keys: 64 rows lie in at most two groups (g >= 32)
+      pz[j][0] = make_uint4(0, 0, 0, 0);
+      pz[j][1] = make_uint4(0, 0, 0, 0);
+      if (IS_K) {
+        pz[j][0] = GEAR_BUF_LOAD16(pbuf, (j * D + oc * 8) * 4);
+        pz[j][1] = GEAR_BUF_LOAD16(pbuf, (j * D + oc * 8) * 4 + 16);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int t = r0 + 16 * k;
+      const uint32_t w[4] = {xv[k].x, xv[k].y, xv[k].z, xv[k].w};
+      float res[8];
+      if (IS_K) {
+        const bool second = (t >> lg) != 0;
+        const uint4 z0 = second ? pz[1][0] : pz[0][0], z1 = second ? pz[1][1] : pz[0][1];
+        const uint32_t z[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float y = h2f((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xFFFFu));
+          res[e] = __builtin_fmaf(-(float)GEAR_UBFE(cw[k], e * bits, bits), h2f(z[e] & 0xFFFFu), y - h2f(z[e] >> 16));
+        }
+      } else {
+        const GroupQ q = load_group(pv[k]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float y = h2f((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xFFFFu));
+          res[e] = quant_error(y, q.mn, q.inv, q.delta, qmax);
+        }
+      }
+      if (t >= n || t < t_lr) {   // no such row / a row that takes no part in the low-rank term
+#pragma unroll
+        for (int e = 0; e < 8; ++e) res[e] = 0.0f;
+      }
+      *reinterpret_cast<float4*>(&sm.Rs[t][oc * 8]) = make_float4(res[0], res[1], res[2], res[3]);
+      *reinterpret_cast<float4*>(&sm.Rs[t][oc * 8 + 4]) = make_float4(res[4], res[5], res[6], res[7]);
+    }
+  }
+  double q[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) q[r] = (owner && r < rank) ? (double)start_b(sb, slab, c, rank, r) : 0.0;
+  if (iters == 1) qr_columns<R>(q, sm.red);   // the only round is also the last: B is orthonormalised first
+#pragma unroll 1
+  for (int l = 0; l < iters; ++l) {
+    const bool last = l == iters - 1;
+    block_lds_sync();
+    if (owner) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) sm.Bs[c][r] = (float)q[r];
+    }
+    block_lds_sync();
+    // A = R B: the 16 lanes of a row of lanes hold one token
+    {
+      float bc[8][R];
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int r = 0; r < R; ++r) bc[e][r] = sm.Bs[oc * 8 + e][r];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (16 * k >= n) break;   // block-uniform
+        const int t = r0 + 16 * k;
+        const float4 x0 = *reinterpret_cast<const float4*>(&sm.Rs[t][oc * 8]);
+        const float4 x1 = *reinterpret_cast<const float4*>(&sm.Rs[t][oc * 8 + 4]);
+        const float res[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          float a = 0.0f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) a += res[e] * bc[e][r];
+          a = row16_sum(a);
+          if (oc == 0) sm.As[t][r] = a;
+        }
+      }
+    }
+    block_lds_sync();
+    // B' = R^T A
+    float p[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) p[r] = 0.0f;
+    {
+      const int t_hi = n < 32 * half + 32 ? n : 32 * half + 32;
+      for (int t = 32 * half; t < t_hi; ++t) {
+        const float rv = sm.Rs[t][c];
+#pragma unroll
+        for (int r = 0; r < R; ++r) p[r] += rv * sm.As[t][r];
+      }
+    }
+    if (!owner) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) sm.part[c][r] = p[r];
+    }
+    block_lds_sync();
+    double qn[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) qn[r] = owner ? (double)p[r] + (double)sm.part[c][r] : 0.0;
+    if (!last) {
+      // keep magnitudes in range between rounds (the span, hence A B^T, is unchanged)
+      double n2[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) n2[r] = qn[r] * qn[r];
+      block_sum_vec<R>(n2, sm.red);
+#pragma unroll
+      for (int r = 0; r < R; ++r) q[r] = n2[r] > 0.0 ? qn[r] * rsqrt_d(n2[r]) : 0.0;
+      if (l == iters - 2) qr_columns<R>(q, sm.red);   // the QR of B that opens the last round
+      continue;
+    }
+    // last round: orth(A) = A C from the r x r Gram matrix of A; B = R^T orth(A) = B' C
+    if (tid < R * R) {
+      const int i = tid / R, j = tid % R;
+      double s = 0.0;
+      for (int t = 0; t < n; ++t) s += (double)sm.As[t][i] * (double)sm.As[t][j];
+      sm.GA[i][j] = s;
+    }
+    block_lds_sync();
+    if (tid < 64) coeff_orth<R>(sm.GA, sm.C, sm.cj, tid);
+    block_lds_sync();
+    if (owner) {
+      for (int j = 0; j < rank; ++j) {
+        double bo = 0.0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) bo += qn[r] * sm.C[r][j];
+        sv.Bf[((size_t)slab * D + c) * rank + j] = (uint16_t)f2h((float)bo);
+      }
+    }
+    for (int i = tid; i < n * rank; i += 256) {
+      const int t = i / rank, j = i - t * rank;
+      float a = 0.0f;
+#pragma unroll
+      for (int r = 0; r < R; ++r) a += sm.As[t][r] * (float)sm.C[r][j];
+      sv.A[((size_t)slab * sv.n_cap + t) * rank + j] = (uint16_t)f2h(a);
+    }
+  }
+}
+
 // ------------------------------------------------------------------ host side
 int pi_gram_strip(int n, int slabs) {
   for (int strip = 2048; strip > 512; strip >>= 1)
@@ -1001,6 +1197,13 @@ static hipError_t run_pi(bool is_k, const uint16_t* Yf, const SegView& sv, const
   const int npart = (n + PT - 1) / PT;
   const int g_eff = (is_k && dm.kcvt) ? 32768 : dm.g;   // per-vector grouping: one Key group per segment
   if (npart == 1) {   // a short segment: everything in one block per slab
+    if (n <= TINY_ROWS) {   // (a flushed buffer of the paper's sizes) with its residual resident in LDS
+      if (is_k)
+        hipLaunchKernelGGL((pi_tiny_kernel<true, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, t_lr, iters, sb);
+      else
+        hipLaunchKernelGGL((pi_tiny_kernel<false, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, dm.g, dm.bits, n, t_lr, iters, sb);
+      return hipGetLastError();
+    }
     if (is_k)
       hipLaunchKernelGGL((pi_small_kernel<true, R>), dim3(slabs), dim3(256), 0, st, Yf, sv, g_eff, dm.bits, n, t_lr, iters, sb, Bcur, partial, Atmp, cmat);
     else
