@@ -124,8 +124,7 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
     const int v = it * NW + wave;
     const bool active = v < CB;
     LdsSource src{tile + (size_t)(active ? v : 0) * n_pad, n_pad};
-    const Thresh th = n <= 64 ? wave_select_small(src.base, n, k_top, k_bot, active)
-                              : wave_select(src, n, k_top, k_bot, hist_all + wave * SELECT_LDS_WORDS, active);
+    const Thresh th = wave_select(src, n, k_top, k_bot, hist_all + wave * SELECT_LDS_WORDS, active);
     if (active && lane == 0) thrK[(size_t)slab * D + cb * CB + v] = pack_thresh(th);
     if (ksz) {
       // per-vector grouping: the channel's one group of this call spans the whole vector, so its
@@ -157,6 +156,90 @@ __global__ __launch_bounds__(256) void k_select_kernel(const uint16_t* __restric
       if (active && lane == 0)
         ksz[(size_t)slab * ng_cap * D + cb * CB + v] = group_bits(make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), qmax));
     }
+  }
+}
+
+// ------------------------------------------------------------------ K select, segments of at most 64 tokens
+// A flushed buffer: 128 vectors of n_b entries per slab, of which Filter_s keeps one or two.  One block per
+// slab, one thread per channel; the slab's rows sit in LDS as keys, row-major as they come, and a thread
+// walks down its column.  The selected sets are found by taking the column's largest composite
+// (key, index) below the previous one k_top times, then the smallest above the previous one among the
+// entries outside the top set k_bot times: (k_top + k_bot) n steps per vector instead of a ranking of
+// every entry against every other.  grid (B*H), block 128.
+constexpr int KSEL_TINY_ROWS = 64;
+__global__ __launch_bounds__(128) void k_select_tiny_kernel(const uint16_t* __restrict__ K, int n, int k_top, int k_bot,
+                                                            ThreshPair* __restrict__ thrK, uint32_t* __restrict__ zero,
+                                                            int zero_count, uint32_t* __restrict__ ksz, int ng_cap, float qmax) {
+  __shared__ __attribute__((aligned(16))) uint16_t tile[KSEL_TINY_ROWS * D];
+  // the first kernel of a compress call also clears the call's list counters
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < zero_count; i += gridDim.x * blockDim.x) zero[i] = 0u;
+  const int slab = blockIdx.x, c = threadIdx.x;
+  {
+    const GEAR_BUF_T xb = GEAR_BUF_MAKE(K + (size_t)slab * n * D, n * (D * 2));
+    const int npieces = n * (D / 8);   // 16-byte pieces of the slab's rows
+    for (int p0 = 0; p0 < npieces; p0 += 4 * 128) {
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = GEAR_BUF_LOAD16(xb, (p0 + u * 128 + c) * 16);   // pieces past the end read as 0
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int p = p0 + u * 128 + c;
+        if (p < npieces)
+          *reinterpret_cast<uint4*>(tile + p * 8) = make_uint4(key16x2(v[u].x), key16x2(v[u].y), key16x2(v[u].z), key16x2(v[u].w));
+      }
+    }
+  }
+  block_lds_sync();
+  Thresh th = thresh_none();
+  // composites: (key << 16) | (0xFFFF - index) orders (value desc, index asc) from the top,
+  // (key << 16) | index orders (value asc, index asc) from the bottom; all distinct, and the first kind > 0
+  uint32_t T = 0u;   // composite of the last top entry
+  for (int it = 0; it < k_top; ++it) {
+    uint32_t best = 0u;
+    for (int j = 0; j < n; ++j) {
+      const uint32_t cT = ((uint32_t)tile[j * D + c] << 16) | (0xFFFFu - (uint32_t)j);
+      if ((it == 0 || cT < T) && cT > best) best = cT;
+    }
+    T = best;
+  }
+  if (k_top > 0 && T != 0u) {
+    th.tau_top = T >> 16;
+    th.i_top = (int)(0xFFFFu - (T & 0xFFFFu));
+  }
+  if (k_bot > 0) {
+    uint32_t Bc = 0u;
+    bool found = true;
+    for (int it = 0; it < k_bot && found; ++it) {
+      uint32_t best = 0xFFFFFFFFu;
+      for (int j = 0; j < n; ++j) {
+        const uint32_t key = tile[j * D + c];
+        const bool in_top = k_top > 0 && ((key << 16) | (0xFFFFu - (uint32_t)j)) >= T;
+        const uint32_t cB = (key << 16) | (uint32_t)j;
+        if (!in_top && (it == 0 || cB > Bc) && cB < best) best = cB;
+      }
+      found = best != 0xFFFFFFFFu;
+      Bc = best;
+    }
+    if (found) {
+      th.tau_bot = Bc >> 16;
+      th.i_bot = (int)(Bc & 0xFFFFu);
+      th.l_bot = (k_top > 0 && th.tau_bot == th.tau_top) ? th.i_top : -1;
+    }
+  }
+  const ThreshPair tp = pack_thresh(th);
+  thrK[(size_t)slab * D + c] = tp;
+  if (ksz) {
+    // per-vector grouping: the channel's one group of this call spans the whole vector: min and max of
+    // X - S, i.e. with the outliers counted as 0
+    uint32_t kmn = 0xFFFFu, kmx = 0u;
+    for (int j = 0; j < n; ++j) {
+      const uint32_t k = tile[j * D + c], idx = (uint32_t)j;
+      const bool out = ((k << 16) | (0xFFFFu - idx)) >= tp.top || ((k << 16) | idx) < tp.bot;
+      const uint32_t y = out ? 0x8000u : k;
+      kmn = min(kmn, y);
+      kmx = max(kmx, y);
+    }
+    ksz[(size_t)slab * ng_cap * D + c] = group_bits(make_group(h2f(unkey16(kmn)), h2f(unkey16(kmx)), qmax));
   }
 }
 
@@ -614,6 +697,12 @@ hipError_t launch_k_select(const uint16_t* K, const Dims& dm, int n, int k_top, 
     hipLaunchKernelGGL(k_transpose_keys_kernel, dim3((n + 127) / 128, dm.B * dm.H), dim3(256), 0, st, K, n, stride, kt_scratch);
     hipLaunchKernelGGL(k_select_long_kernel, dim3(dm.B * dm.H * (D / 4)), dim3(256), 0, st, (const uint16_t*)kt_scratch, n,
                        stride, k_top, k_bot, thrK, zero, zero_count, dm.kcvt ? sv.sz : (uint32_t*)nullptr, sv.ng_cap, dm.qmax);
+    return hipGetLastError();
+  }
+  // a flushed buffer: one thread per channel vector
+  if (n <= KSEL_TINY_ROWS) {
+    hipLaunchKernelGGL(k_select_tiny_kernel, dim3(dm.B * dm.H), dim3(128), 0, st, K, n, k_top, k_bot, thrK, zero, zero_count,
+                       dm.kcvt ? sv.sz : (uint32_t*)nullptr, sv.ng_cap, dm.qmax);
     return hipGetLastError();
   }
   // segments of 1025 .. 8192 tokens: the channel vectors live in registers

@@ -204,42 +204,6 @@ __device__ __forceinline__ void find_kth_equal_pair(const Src& src, int N, int n
   wave_lds_sync();
 }
 
-// A vector of at most 64 entries (a flushed buffer's Key channel): lane i takes entry i and
-// finds its rank among the others by comparing with every lane in turn; no LDS, no passes.
-// keys: the vector as 16-bit keys, contiguous.
-__device__ __forceinline__ Thresh wave_select_small(const uint16_t* keys, int N, int k_top, int k_bot, bool active) {
-  const int lane = lane_id();
-  Thresh th = thresh_none();
-  if (!active) return th;                      // wave-uniform
-  const bool valid = lane < N;
-  const uint32_t key = valid ? (uint32_t)keys[lane] : 0u;
-  const uint32_t cT = valid ? ((key << 16) | (0xFFFFu - (uint32_t)lane)) : 0u;   // valid composites are > 0
-  uint32_t rank_t = 0;
-  for (int j = 0; j < N; ++j) rank_t += (uint32_t)__builtin_amdgcn_readlane((int)cT, j) > cT ? 1u : 0u;
-  const bool in_top = valid && rank_t < (uint32_t)k_top;
-  if (k_top > 0) {
-    const unsigned long long bm = __ballot(valid && rank_t == (uint32_t)k_top - 1u);
-    if (bm) {
-      const int L = (int)__ffsll((long long)bm) - 1;
-      th.tau_top = (uint32_t)__builtin_amdgcn_readlane((int)key, L);
-      th.i_top = L;
-    }
-  }
-  if (k_bot > 0) {
-    const uint32_t cB = (valid && !in_top) ? ((key << 16) | (uint32_t)lane) : 0xFFFFFFFFu;
-    uint32_t rank_b = 0;
-    for (int j = 0; j < N; ++j) rank_b += (uint32_t)__builtin_amdgcn_readlane((int)cB, j) < cB ? 1u : 0u;
-    const unsigned long long bm = __ballot(valid && !in_top && rank_b == (uint32_t)k_bot - 1u);
-    if (bm) {
-      const int L = (int)__ffsll((long long)bm) - 1;
-      th.tau_bot = (uint32_t)__builtin_amdgcn_readlane((int)key, L);
-      th.i_bot = L;
-      th.l_bot = (k_top > 0 && th.tau_bot == th.tau_top) ? th.i_top : -1;
-    }
-  }
-  return th;
-}
-
 // Max / min of an unsigned value over each row of 16 lanes, in every lane of the row.
 __device__ __forceinline__ uint32_t row16_max_u(uint32_t v) {
   v = max(v, dpp_u<DPP_XOR1>(v));
