@@ -269,11 +269,20 @@ __device__ __forceinline__ GroupQ make_group(float mn, float mx, float qmax) {
   q.inv = q.delta > 0.0f ? __fdiv_rn(1.0f, q.delta) : 0.0f;
   return q;
 }
+// 1 / d, correctly rounded, for a d > 0 that is an fp16 value (11 significant bits): the hardware's
+// reciprocal estimate (within 1 ulp) refined by one Newton step.  The residual 1 - d r of the estimate
+// is exact in fp32 (12 significant bits after the cancellation) and the step leaves a relative error
+// of about 2^-46, far below the distance (at least 2^-36, relative) of a quotient 2^k / m, m < 2^11,
+// from the nearest rounding boundary: the same float as the IEEE division, in 3 instructions.
+__device__ __forceinline__ float recip_of_half(float d) {
+  const float r = __builtin_amdgcn_rcpf(d);
+  return __builtin_fmaf(__builtin_fmaf(-d, r, 1.0f), r, r);
+}
 __device__ __forceinline__ GroupQ load_group(uint32_t sz_bits) {
   GroupQ q;
   q.delta = h2f(sz_bits & 0xFFFFu);
   q.mn = h2f(sz_bits >> 16);
-  q.inv = q.delta > 0.0f ? __fdiv_rn(1.0f, q.delta) : 0.0f;
+  q.inv = q.delta > 0.0f ? recip_of_half(q.delta) : 0.0f;   // = 1 / delta as the quantizer computed it
   return q;
 }
 __device__ __forceinline__ uint32_t group_bits(const GroupQ& q) {
