@@ -66,21 +66,32 @@ __global__ __launch_bounds__(256, (GQ == 8 ? 3 : (BITS == 2 && (GQ <= 2 || (GQ =
                            rec_base, rec_stride);
 }
 
-// grid (B*H_q), block 128: thread c merges channel c of the row's nrec records.  Lane s of
-// every wave fetches (m, l) of record s, so the weights of up to 64 records come from one
-// round of loads and the weighted sum over the records has no dependent loads in it.
+// grid (B*H_q), block 128: thread c merges channel c of the row's nrec records, 64 records per round.
+// Lane s of every wave fetches (m, l) of record s, and every thread requests its channel of all the
+// round's records before anything is used, so a round costs one load latency (the kernel is a few
+// microseconds of launch and latency; records past the last read as 0 through the buffer view).
 __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __restrict__ partial, int nrec,
                                                              uint16_t* __restrict__ out) {
   const int row = blockIdx.x, c = threadIdx.x, lane = threadIdx.x & 63;
-  const float* rec = partial + (size_t)row * nrec * DECODE_REC;
+  const GEAR_BUF_T rb = GEAR_BUF_MAKE(partial + (size_t)row * nrec * DECODE_REC, nrec * (DECODE_REC * 4));
   float M = -INFINITY, L = 0.0f, o = 0.0f;
   for (int s0 = 0; s0 < nrec; s0 += 64) {
     const int cnt = nrec - s0 < 64 ? nrec - s0 : 64;
-    float m = -INFINITY, l = 0.0f;
-    if (lane < cnt) {
-      m = rec[(size_t)(s0 + lane) * DECODE_REC];
-      l = rec[(size_t)(s0 + lane) * DECODE_REC + 1];
+    const uint2 ml = GEAR_BUF_LOAD8(rb, (s0 + lane) * (DECODE_REC * 4));
+    float v[64];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      if (16 * b < cnt) {   // block-uniform
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+          v[16 * b + u] = __uint_as_float(GEAR_BUF_LOAD4(rb, ((s0 + 16 * b + u) * DECODE_REC + 2 + c) * 4));
+      } else {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[16 * b + u] = 0.0f;
+      }
     }
+    const float m = lane < cnt ? __uint_as_float(ml.x) : -INFINITY;
+    const float l = lane < cnt ? __uint_as_float(ml.y) : 0.0f;
     float Mn = m;
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) Mn = fmaxf(Mn, __shfl_xor(Mn, d, 64));
@@ -91,13 +102,12 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
     L = L * keep + wave_sum_shfl(l * f);
     o *= keep;
     M = Mn;
-    constexpr int UN = 8;
-    for (int j0 = 0; j0 < cnt; j0 += UN) {
-      float v[UN];
 #pragma unroll
-      for (int u = 0; u < UN; ++u) v[u] = (j0 + u < cnt) ? rec[(size_t)(s0 + j0 + u) * DECODE_REC + 2 + c] : 0.0f;
+    for (int b = 0; b < 4; ++b) {
+      if (16 * b < cnt) {
 #pragma unroll
-      for (int u = 0; u < UN; ++u) o += v[u] * __shfl(f, (j0 + u) & 63, 64);
+        for (int u = 0; u < 16; ++u) o += v[16 * b + u] * __shfl(f, 16 * b + u, 64);
+      }
     }
   }
   out[(size_t)row * D + c] = (uint16_t)f2h(o / L);
