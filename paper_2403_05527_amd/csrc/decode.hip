@@ -67,9 +67,12 @@ __global__ __launch_bounds__(256, (GQ == 8 ? 3 : (BITS == 2 && (GQ <= 2 || (GQ =
 }
 
 // grid (B*H_q), block 128: thread c merges channel c of the row's nrec records, 64 records per round.
-// Lane s of every wave fetches (m, l) of record s, and every thread requests its channel of all the
-// round's records before anything is used, so a round costs one load latency (the kernel is a few
-// microseconds of launch and latency; records past the last read as 0 through the buffer view).
+// Lane s of every wave fetches (m, l) of record s, so the weights of up to 64 records come from one
+// round of loads.  WIDE (rows with many records: long contexts at a small batch, where the kernel is a
+// few blocks' latency): a thread requests its channel of all the round's records before anything is
+// used, one load latency per round; otherwise eight at a time (fewer registers: more rows in flight).
+// Records past the last read as 0 through the buffer view.
+template <bool WIDE>
 __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __restrict__ partial, int nrec,
                                                              uint16_t* __restrict__ out) {
   const int row = blockIdx.x, c = threadIdx.x, lane = threadIdx.x & 63;
@@ -78,16 +81,18 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
   for (int s0 = 0; s0 < nrec; s0 += 64) {
     const int cnt = nrec - s0 < 64 ? nrec - s0 : 64;
     const uint2 ml = GEAR_BUF_LOAD8(rb, (s0 + lane) * (DECODE_REC * 4));
-    float v[64];
+    float v[WIDE ? 64 : 1];
+    if constexpr (WIDE) {
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      if (16 * b < cnt) {   // block-uniform
+      for (int b = 0; b < 4; ++b) {
+        if (16 * b < cnt) {   // block-uniform
 #pragma unroll
-        for (int u = 0; u < 16; ++u)
-          v[16 * b + u] = __uint_as_float(GEAR_BUF_LOAD4(rb, ((s0 + 16 * b + u) * DECODE_REC + 2 + c) * 4));
-      } else {
+          for (int u = 0; u < 16; ++u)
+            v[16 * b + u] = __uint_as_float(GEAR_BUF_LOAD4(rb, ((s0 + 16 * b + u) * DECODE_REC + 2 + c) * 4));
+        } else {
 #pragma unroll
-        for (int u = 0; u < 16; ++u) v[16 * b + u] = 0.0f;
+          for (int u = 0; u < 16; ++u) v[16 * b + u] = 0.0f;
+        }
       }
     }
     const float m = lane < cnt ? __uint_as_float(ml.x) : -INFINITY;
@@ -102,11 +107,22 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
     L = L * keep + wave_sum_shfl(l * f);
     o *= keep;
     M = Mn;
+    if constexpr (WIDE) {
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      if (16 * b < cnt) {
+      for (int b = 0; b < 4; ++b) {
+        if (16 * b < cnt) {
 #pragma unroll
-        for (int u = 0; u < 16; ++u) o += v[16 * b + u] * __shfl(f, 16 * b + u, 64);
+          for (int u = 0; u < 16; ++u) o += v[16 * b + u] * __shfl(f, 16 * b + u, 64);
+        }
+      }
+    } else {
+      constexpr int UN = 8;
+      for (int j0 = 0; j0 < cnt; j0 += UN) {
+        float w[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) w[u] = __uint_as_float(GEAR_BUF_LOAD4(rb, ((s0 + j0 + u) * DECODE_REC + 2 + c) * 4));
+#pragma unroll
+        for (int u = 0; u < UN; ++u) o += w[u] * __shfl(f, (j0 + u) & 63, 64);
       }
     }
   }
@@ -140,8 +156,12 @@ static hipError_t launch_decode_t(const Dims& dm, const SegView& k0, const SegVi
   dim3 grid(nsplit + ncb + 1, dm.B * dm.H);
   hipLaunchKernelGGL((decode_split_kernel<BITS, GQ, LG>), grid, dim3(256), lds, st, dm, k0, v0, cs, q, Kbuf, Vbuf,
                      n_buf, n_buf_cap, nsplit, pp, rc, odd_rank ? 1 : 0, q_len, causal, partial);
-  hipLaunchKernelGGL(decode_combine_kernel, dim3(dm.B * dm.Hq), dim3(128), 0, st, (const float*)partial,
-                     nsplit + ncb + 1, out);
+  if (nsplit + ncb + 1 > 32)
+    hipLaunchKernelGGL(decode_combine_kernel<true>, dim3(dm.B * dm.Hq), dim3(128), 0, st, (const float*)partial,
+                       nsplit + ncb + 1, out);
+  else
+    hipLaunchKernelGGL(decode_combine_kernel<false>, dim3(dm.B * dm.Hq), dim3(128), 0, st, (const float*)partial,
+                       nsplit + ncb + 1, out);
   return hipGetLastError();
 }
 
