@@ -804,35 +804,50 @@ __device__ __forceinline__ double rsqrt_d(double x) {
   y = y * (1.5 - 0.5 * m * y * y);
   return __builtin_bit_cast(double, __builtin_bit_cast(uint64_t, y) - ((uint64_t)h << 52));   // y * 2^-h
 }
-// QR of B (row c of B in thread c < 128; the other threads of the block hold zeros) by Gram-Schmidt
-// applied twice (the projections of a pass are taken together: one block reduction per pass);
-// dependent columns become 0.  Called by all 256 threads.
+// QR of B (row c of B in thread c < 128, q; the other threads of the block hold zeros and keep them) by
+// Gram-Schmidt applied twice; dependent columns become 0.  Called by all 256 threads.  The rows go
+// through LDS (Bq) once; then each of the two waves that own rows holds ALL 128 rows, two per lane, and
+// orthonormalises them by itself: every inner product is one reduction over the lanes of a wave, with no
+// barrier and no LDS traffic (the two waves compute the same numbers in the same order and each keeps
+// its own rows).
 template <int R>
-__device__ __forceinline__ void qr_columns(double (&q)[R], double* red /* 4 * (R + 1) */) {
+__device__ __forceinline__ void qr_columns(double (&q)[R], double (*Bq)[R] /* LDS [128][R] */) {
+  const int c = threadIdx.x & (D - 1);
+  const bool owner = threadIdx.x < D;
+  block_lds_sync();
+  if (owner) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) Bq[c][r] = q[r];
+  }
+  block_lds_sync();
+  if (!owner) return;   // (whole waves)
+  const int lane = c & 63;
+  double a[R], b[R];    // rows lane and lane + 64
+#pragma unroll
+  for (int r = 0; r < R; ++r) { a[r] = Bq[lane][r]; b[r] = Bq[lane + 64][r]; }
 #pragma unroll
   for (int j = 0; j < R; ++j) {
-    double d[R + 1];
+    const double before2 = wave_sum_d(a[j] * a[j] + b[j] * b[j]);
+    if (before2 == 0.0) { a[j] = 0.0; b[j] = 0.0; continue; }   // wave-uniform
 #pragma unroll
-    for (int i = 0; i < R; ++i) d[i] = i < j ? q[i] * q[j] : 0.0;
-    d[R] = q[j] * q[j];
-    block_sum_vec<R + 1>(d, red);
-    const double before2 = d[R];
-    if (before2 == 0.0) { q[j] = 0.0; continue; }   // block-uniform
+    for (int pass = 0; pass < 2; ++pass) {
+      double d[R];   // the projections of a pass are taken together (classical Gram-Schmidt, applied twice)
 #pragma unroll
-    for (int i = 0; i < R; ++i)
-      if (i < j) q[j] -= d[i] * q[i];
+      for (int i = 0; i < R; ++i) d[i] = i < j ? wave_sum_d(a[i] * a[j] + b[i] * b[j]) : 0.0;
 #pragma unroll
-    for (int i = 0; i < R; ++i) d[i] = i < j ? q[i] * q[j] : 0.0;
-    d[R] = 0.0;
-    block_sum_vec<R + 1>(d, red);
-#pragma unroll
-    for (int i = 0; i < R; ++i)
-      if (i < j) q[j] -= d[i] * q[i];
-    double a2[1] = {q[j] * q[j]};
-    block_sum_vec<1>(a2, red);
-    if (!(a2[0] > 1e-24 * before2)) q[j] = 0.0;   // norm after <= 1e-12 * norm before
-    else q[j] *= rsqrt_d(a2[0]);
+      for (int i = 0; i < R; ++i)
+        if (i < j) { a[j] -= d[i] * a[i]; b[j] -= d[i] * b[i]; }
+    }
+    const double after2 = wave_sum_d(a[j] * a[j] + b[j] * b[j]);
+    if (!(after2 > 1e-24 * before2)) { a[j] = 0.0; b[j] = 0.0; }   // norm after <= 1e-12 * norm before
+    else {
+      const double inv = rsqrt_d(after2);
+      a[j] *= inv;
+      b[j] *= inv;
+    }
   }
+#pragma unroll
+  for (int r = 0; r < R; ++r) q[r] = c < 64 ? a[r] : b[r];
 }
 // grid (B*H), block 256: thread (half = tid / 128, c = tid % 128).  Row c of B belongs to thread
 // (0, c); the upper half of the block helps with the loads of G and with half of every product.
@@ -905,7 +920,7 @@ __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
 #pragma unroll
     for (int r = 0; r < R; ++r) q[r] = n2[r] > 0.0 ? qn[r] * rsqrt_d(n2[r]) : 0.0;
   }
-  qr_columns<R>(q, sm.red);
+  qr_columns<R>(q, sm.Bs);
   if (!last_round) {
     if (owner) {
 #pragma unroll
@@ -996,6 +1011,7 @@ struct TinySmem {
   __attribute__((aligned(16))) float Bs[D][R];
   float As[TINY_ROWS][R];
   float part[D][R];
+  double Bq[D][R];      // the rows of B for its QR
   double red[4 * (R + 1)];
   double GA[R][R];
   double C[R][R];
@@ -1075,7 +1091,7 @@ __global__ __launch_bounds__(256) void pi_tiny_kernel(const uint16_t* __restrict
   double q[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) q[r] = (owner && r < rank) ? (double)start_b(sb, slab, c, rank, r) : 0.0;
-  if (iters == 1) qr_columns<R>(q, sm.red);   // the only round is also the last: B is orthonormalised first
+  if (iters == 1) qr_columns<R>(q, sm.Bq);   // the only round is also the last: B is orthonormalised first
 #pragma unroll 1
   for (int l = 0; l < iters; ++l) {
     const bool last = l == iters - 1;
@@ -1138,7 +1154,7 @@ __global__ __launch_bounds__(256) void pi_tiny_kernel(const uint16_t* __restrict
       block_sum_vec<R>(n2, sm.red);
 #pragma unroll
       for (int r = 0; r < R; ++r) q[r] = n2[r] > 0.0 ? qn[r] * rsqrt_d(n2[r]) : 0.0;
-      if (l == iters - 2) qr_columns<R>(q, sm.red);   // the QR of B that opens the last round
+      if (l == iters - 2) qr_columns<R>(q, sm.Bq);   // the QR of B that opens the last round
       continue;
     }
     // last round: orth(A) = A C from the r x r Gram matrix of A; B = R^T orth(A) = B' C
@@ -1170,9 +1186,11 @@ __global__ __launch_bounds__(256) void pi_tiny_kernel(const uint16_t* __restrict
 }
 
 // ------------------------------------------------------------------ host side
+// Tokens per strip of the Gram pass: the longest that still gives every resident block slot (two per CU,
+// 512 on the chip) a strip; the solve kernel, one block per slab, then has the fewest partials to add.
 int pi_gram_strip(int n, int slabs) {
   for (int strip = 2048; strip > 512; strip >>= 1)
-    if ((long long)slabs * ((n + strip - 1) / strip) >= 1024) return strip;
+    if ((long long)slabs * ((n + strip - 1) / strip) >= 512) return strip;
   return 512;
 }
 int pi_gram_strips_max(int n_max, int slabs) {
