@@ -69,7 +69,7 @@ __device__ __forceinline__ double wave_sum_d(double v) {
   v += dpp_d<DPP_MIRROR>(v);
   return (lane_bcast_d(v, 0) + lane_bcast_d(v, 16)) + (lane_bcast_d(v, 32) + lane_bcast_d(v, 48));
 }
-// Gram-Schmidt in coefficient space: given the r x r Gram matrix G = A^T A of the columns of some A, finds C
+// Gram-Schmidt (applied twice) in coefficient space: given the r x r Gram matrix G = A^T A of the columns of some A, finds C
 // with orth(A) = A C (column j of orth(A) is A * C[:, j]; dependent columns get C[:, j] = 0).  Called by the
 // 64 threads c = 0..63 of one wave; lane a * R + b carries the (a, b) term of every quadratic form x^T G y, a
 // sum over the wave finishes it.  G, C, cj: LDS.
@@ -85,14 +85,25 @@ __device__ __forceinline__ void coeff_orth(double (&G)[R][R], double (&C)[R][R],
     const double before2 = G[j][j];
     bool ok = before2 > 0.0;
     if (ok) {
-      for (int pass = 0; pass < 2; ++pass)
-        for (int k = 0; k < j; ++k) {
-          if (!((valid >> k) & 1u)) continue;
-          const double dot = wave_sum_d(in ? C[a][k] * Gab * cj[b] : 0.0);   // q_k^T v = c_k^T G c_j
-          wave_lds_sync();
-          if (c < R) cj[c] -= dot * C[c][k];
-          wave_lds_sync();
+      // two passes; the projections of a pass are taken together from the same vector (their reductions
+      // are independent of each other and overlap), then removed together
+      for (int pass = 0; pass < 2; ++pass) {
+        double dot[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+          dot[k] = 0.0;
+          if (k < j && ((valid >> k) & 1u)) dot[k] = wave_sum_d(in ? C[a][k] * Gab * cj[b] : 0.0);   // q_k^T v = c_k^T G c_j
         }
+        wave_lds_sync();
+        if (c < R) {
+          double v = cj[c];
+#pragma unroll
+          for (int k = 0; k < R; ++k)
+            if (k < j) v -= dot[k] * C[c][k];
+          cj[c] = v;
+        }
+        wave_lds_sync();
+      }
       const double after2 = wave_sum_d(in ? cj[a] * Gab * cj[b] : 0.0);
       wave_lds_sync();
       // (the Gram matrix is a sum of fp32 products: what is left of a dependent column is
@@ -909,16 +920,19 @@ __global__ __launch_bounds__(256) void pi_solve_kernel(StartB sb, int rank,
       for (int r = 0; r < R; ++r) sm.part[c][r] = (float)qn[r];
     }
     block_lds_sync();
-    // keep magnitudes in range between rounds
-    double n2[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      qn[r] = owner ? qn[r] + sm.part[c][r] : 0.0;
-      n2[r] = qn[r] * qn[r];
+    for (int r = 0; r < R; ++r) q[r] = owner ? qn[r] + sm.part[c][r] : 0.0;
+    // keep magnitudes in range between rounds (unit columns: the next product stays far inside single
+    // precision, which the upper half block's share passes through); after the last product the QR
+    // below rescales anyway
+    if (l + 1 < rounds) {   // block-uniform
+      double n2[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) n2[r] = q[r] * q[r];
+      block_sum_vec<R>(n2, sm.red);
+#pragma unroll
+      for (int r = 0; r < R; ++r) q[r] = n2[r] > 0.0 ? q[r] * rsqrt_d(n2[r]) : 0.0;
     }
-    block_sum_vec<R>(n2, sm.red);
-#pragma unroll
-    for (int r = 0; r < R; ++r) q[r] = n2[r] > 0.0 ? qn[r] * rsqrt_d(n2[r]) : 0.0;
   }
   qr_columns<R>(q, sm.Bs);
   if (!last_round) {
