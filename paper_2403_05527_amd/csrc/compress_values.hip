@@ -370,7 +370,7 @@ hipError_t launch_v_filter_quant(const uint16_t* V, const SegView& sv, const Dim
     hipError_t e;
     const long long tokens = (long long)dm.B * n;
     // short token rows: four tokens per wave (a flushed buffer has too few tokens to fill the chip that way)
-    if (dm.H <= 8 && !dm.vhead && tokens >= 16384) {
+    if (dm.H <= 8 && !dm.vhead && tokens >= GEAR_ROWS_MIN_TOKENS) {
       const int tpw = tokens >= (1 << 18) ? 4 : tokens >= (1 << 16) ? 2 : 1;   // >= 4096 blocks before a block takes more tokens
       // (the (scale, zero) array exists only under the per-vector grouping)
       hipLaunchKernelGGL(v_select_rows_kernel, dim3((n + 16 * tpw - 1) / (16 * tpw), dm.B), dim3(256), 0, st, V, dm.H, n, tpw,

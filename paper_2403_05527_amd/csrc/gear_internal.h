@@ -55,6 +55,12 @@
 
 // Raw buffer views: a load whose bytes do not all lie below the view's size returns 0,
 // so a ragged tail needs neither a per-lane test nor a 64-bit address per lane.
+// Fewest tokens (B * n) of a call for which the Value selection runs by token rows, four tokens per wave
+// (below that a flushed buffer's few tokens take one wave each).  The CPU stand-in lowers it so that its small
+// cases reach those kernels.
+#ifndef GEAR_ROWS_MIN_TOKENS
+#define GEAR_ROWS_MIN_TOKENS 16384
+#endif
 #ifndef GEAR_BUF_T
 #define GEAR_BUF_T __amdgpu_buffer_rsrc_t
 #define GEAR_BUF_MAKE(p, bytes) \

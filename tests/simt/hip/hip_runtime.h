@@ -212,6 +212,7 @@ inline void launch(dim3 grid, dim3 block, size_t lds, F&& body) {
 #define __builtin_amdgcn_wave_barrier() simt::wave_barrier()
 #define __builtin_amdgcn_rsqf(x) (1.0f / sqrtf(x))
 #define __builtin_amdgcn_rcpf(x) (1.0f / (x))
+#define GEAR_ROWS_MIN_TOKENS 64   // the small emulated cases take the token-row kernels too
 #define __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, x, y, z) \
   __builtin_bit_cast(gear::floatx4, simt::mfma(__builtin_bit_cast(simt::h8, (a)), __builtin_bit_cast(simt::h8, (b)), __builtin_bit_cast(simt::f4, (c))))
 #define __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, x, y, z) \

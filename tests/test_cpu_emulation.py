@@ -64,6 +64,7 @@ def emulator(tmp_path_factory):
     (1, 4, 8, 290, 2, 64, 20000, 4, 5, False),     # the method as stated; n > 256: Gram-matrix power iteration
     (1, 2, 2, 140, 4, 0, 30000, 2, 3, True),       # per-vector groups and the per-head Value Filter
     (1, 8, 8, 70, 2, 64, 20000, 2, 3, False),      # eight KV heads: Value token rows of 1024 entries, four per wave
+    (1, 2, 2, 200, 4, 32, 30000, 2, 3, False),     # two KV heads by the same kernel, 4-bit codes, groups of 32
 ])
 def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits, g, ppm, rank, n_buf, per_head):
     w = gw.Workload("emu", B=B, H_kv=H, H_q=Hq, n=n, bits=bits, group=g, outlier_ppm=ppm, rank=rank,
