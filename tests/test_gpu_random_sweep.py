@@ -53,3 +53,46 @@ def test_random_long_segment(seed):
     w = dataclasses.replace(w, H_q=w.H_kv * r.choice([1, 4]))
     say("random long case", seed)
     run_case(w, **kw)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_multi_query_and_recent_tokens(seed):
+    """Random draws for the two entry points that run_case does not reach: the low-rank term on the most recent
+    tokens of the prefill call only (gear_compress_recent), then q_len query rows per head (gear_decode_attn_mq)
+    over that cache, its chunks and the buffer, with and without the causal rule."""
+    import torch
+
+    import gear_workloads as gw
+    from tests import parity_util as pu
+    from tests.test_gpu_parity import DEV
+
+    r = random.Random(3000 + seed)
+    w, kw = draw(200 + seed)
+    gq = r.choice([1, 2, 4])
+    w = dataclasses.replace(w, H_q=w.H_kv * gq, n=max(w.n, 40), rank=max(w.rank, 1))
+    q_len = r.choice([x for x in (1, 2, 4, 8) if x * gq <= 8])
+    n_lowrank = r.choice([0, 1, w.n // 4, w.n - 1, w.n])
+    n_chunks, chunk_n = kw["n_chunks"], kw["chunk_n"]
+    say("random multi-query case", seed, w, "q_len", q_len, "n_lowrank", n_lowrank, kw)
+    gc, oc = pu.make_pair(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, max(w.n_b, chunk_n, q_len), w.n,
+                          max(n_chunks, 1), max(w.rank, w.rank_chunk), v_per_head=kw["v_per_head"])
+    K, V = gw.make_keys(w, w.n, 0, DEV), gw.make_values(w, w.n, 0, DEV)
+    ib = gw.make_init_B(w, w.rank, 0, DEV)
+    gc.compress(K, V, w.rank, kw["iters"], ib, n_lowrank=n_lowrank)
+    oc.compress(pu.np16(K), pu.np16(V), w.rank, kw["iters"], pu.np16(ib), n_lowrank=n_lowrank)
+    for j in range(n_chunks):
+        pu.compress_both(gc, oc, gw.make_keys(w, chunk_n, 1 + j, DEV), gw.make_values(w, chunk_n, 1 + j, DEV),
+                         w.rank_chunk, kw["iters"], gw.make_init_B(w, w.rank_chunk, 1 + j, DEV))
+    rep = pu.compare_components(gc, oc)
+    rep.update(pu.compare_decompress(gc, oc))
+    if n_lowrank > 0:
+        rep.update(pu.compare_lowrank_product(gc, oc, 0))
+    cap = gc.cfg.n_buf_cap
+    Kb, Vb = gw.make_keys(w, cap, 50, DEV), gw.make_values(w, cap, 50, DEV)
+    g = torch.Generator(device="cpu").manual_seed(4000 + seed)
+    q = torch.randn(w.B, w.H_q, q_len, 128, generator=g).to(torch.float16).to(DEV)
+    for n_buf, causal in ((q_len, True), (r.randint(q_len, cap), True), (r.randint(q_len, cap), False)):
+        out = gc.decode_attn_mq(q, Kb, Vb, n_buf, causal)
+        want = pu.go.decode_attn_multi(oc, pu.np16(q), pu.np16(Kb), pu.np16(Vb), n_buf, causal)
+        rep["mq_%d_%s" % (n_buf, causal)] = pu.check_attention(pu.np16(out), want, "multi-query attention")
+    say("  ->", rep)
