@@ -60,15 +60,17 @@ def emulator(tmp_path_factory):
     return exe
 
 
-@pytest.mark.parametrize("B,H,Hq,n,bits,g,ppm,rank,n_buf,per_head", [
-    (1, 4, 8, 290, 2, 64, 20000, 4, 5, False),     # the method as stated; n > 256: Gram-matrix power iteration
-    (1, 2, 2, 140, 4, 0, 30000, 2, 3, True),       # per-vector groups and the per-head Value Filter
-    (1, 8, 8, 70, 2, 64, 20000, 2, 3, False),      # eight KV heads: Value token rows of 1024 entries, four per wave
-    (1, 2, 2, 200, 4, 32, 30000, 2, 3, False),     # two KV heads by the same kernel, 4-bit codes, groups of 32
+@pytest.mark.parametrize("B,H,Hq,n,bits,g,ppm,rank,n_buf,per_head,chunk_n,n_b", [
+    (1, 4, 8, 290, 2, 64, 20000, 4, 5, False, 20, 20),     # the method as stated; n > 256: Gram-matrix power iteration
+    (1, 2, 2, 140, 4, 0, 30000, 2, 3, True, 20, 20),       # per-vector groups and the per-head Value Filter
+    (1, 8, 8, 70, 2, 64, 20000, 2, 3, False, 20, 20),      # eight KV heads: Value token rows of 1024 entries, four per wave
+    (1, 2, 2, 200, 4, 32, 30000, 2, 3, False, 20, 20),     # two KV heads by the same kernel, 4-bit codes, groups of 32
+    (1, 1, 2, 70, 2, 64, 20000, 2, 255, False, 255, 255),  # the largest streaming buffer: 255 live rows, a flushed
+                                                           # segment of 255 tokens (two 128-row pieces in the decode kernel)
 ])
-def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits, g, ppm, rank, n_buf, per_head):
+def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits, g, ppm, rank, n_buf, per_head, chunk_n, n_b):
     w = gw.Workload("emu", B=B, H_kv=H, H_q=Hq, n=n, bits=bits, group=g, outlier_ppm=ppm, rank=rank,
-                    rank_chunk=2, n_b=20, steps=1, seed=5)
+                    rank_chunk=2, n_b=n_b, steps=1, seed=5)
     d = str(tmp_path)
     a = lambda t: t.numpy()
     oc = go.OracleCache(B, H, Hq, 128, bits, g, ppm, per_head)
@@ -76,15 +78,15 @@ def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits,
     for name, x in (("K", K), ("V", V), ("ib", ib)):
         x.tofile(os.path.join(d, name + ".bin"))
     oc.compress(K, V, rank, 3, ib)
-    Kc, Vc, ibc = a(gw.make_keys(w, 20, 1)), a(gw.make_values(w, 20, 1)), a(gw.make_init_B(w, 2, 1))
+    Kc, Vc, ibc = a(gw.make_keys(w, chunk_n, 1)), a(gw.make_values(w, chunk_n, 1)), a(gw.make_init_B(w, 2, 1))
     for name, x in (("Kc0", Kc), ("Vc0", Vc), ("ibc0", ibc)):
         x.tofile(os.path.join(d, name + ".bin"))
     oc.compress(Kc, Vc, 2, 3, ibc)
-    q, Kb, Vb = a(gw.make_queries(w, 0)), a(gw.make_keys(w, 20, 50)), a(gw.make_values(w, 20, 50))
+    q, Kb, Vb = a(gw.make_queries(w, 0)), a(gw.make_keys(w, n_b, 50)), a(gw.make_values(w, n_b, 50))
     for name, x in (("q", q), ("Kb", Kb), ("Vb", Vb)):
         x.tofile(os.path.join(d, name + ".bin"))
     with open(os.path.join(d, "meta.txt"), "w") as f:
-        f.write(" ".join(str(x) for x in [B, H, Hq, bits, g, ppm, n, rank, 1, 20, 2, n_buf, 20, 3, 1 if per_head else 0]) + "\n")
+        f.write(" ".join(str(x) for x in [B, H, Hq, bits, g, ppm, n, rank, 1, chunk_n, 2, n_buf, n_b, 3, 1 if per_head else 0]) + "\n")
     r = subprocess.run([emulator, d], capture_output=True, text=True, timeout=900,
                        env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0"))
     assert r.returncode == 0, r.stderr[-4000:]

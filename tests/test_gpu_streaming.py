@@ -65,3 +65,48 @@ def test_decode_loop_with_flushes(bits, n_b, steps):
         A1, B1 = gc.export_lowrank(which, 1)
         A2, B2 = gc2.export_lowrank(which, 0)
         assert torch.equal(A1, A2) and torch.equal(B1, B2)
+
+
+def test_maximum_chunk_count():
+    """A cache filled with the largest number of appended segments the descriptor can hold (GEAR_MAX_CHUNKS), of
+    mixed lengths and ranks: components, reconstruction and attention against the oracle; one more compress call is
+    refused on the host."""
+    nmax = pu.gb.GEAR_MAX_CHUNKS
+    w = gw.Workload("maxchunks", B=1, H_kv=2, H_q=4, n=70, bits=2, group=64, outlier_ppm=20000, rank=2,
+                    rank_chunk=2, n_b=8, steps=1, seed=321)
+    print("case", w, flush=True)
+    gc, oc = pu.make_pair(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, w.n_b, w.n, nmax, 2)
+    pu.compress_both(gc, oc, gw.make_keys(w, w.n, 0, DEV), gw.make_values(w, w.n, 0, DEV), 2, 3, gw.make_init_B(w, 2, 0, DEV))
+    for j in range(nmax):
+        nj, rj = 1 + j % w.n_b, j % 3
+        pu.compress_both(gc, oc, gw.make_keys(w, nj, 1 + j, DEV), gw.make_values(w, nj, 1 + j, DEV), rj, 3,
+                         gw.make_init_B(w, rj, 1 + j, DEV))
+    with pytest.raises(pu.gb.GearError) as e:
+        gc.compress(gw.make_keys(w, 1, 999, DEV), gw.make_values(w, 1, 999, DEV), 0, 3)
+    assert e.value.status == pu.gb.GEAR_ECAPACITY
+    rep = pu.compare_components(gc, oc)
+    rep.update(pu.compare_decompress(gc, oc))
+    Kb, Vb = gw.make_keys(w, w.n_b, 50, DEV), gw.make_values(w, w.n_b, 50, DEV)
+    rep.update(pu.compare_attention(gc, oc, gw.make_queries(w, 0, DEV), Kb, Vb, 5))
+    print("  ->", rep, flush=True)
+
+
+def test_maximum_buffer_capacity():
+    """n_b = 255, the largest streaming buffer: 255 live fp16 rows in the decode read, and flushed segments of 255
+    and 129 tokens (two 128-row pieces per chunk in the decode kernel) next to a short one."""
+    w = gw.Workload("maxbuf", B=2, H_kv=2, H_q=4, n=300, bits=4, group=32, outlier_ppm=20000, rank=4,
+                    rank_chunk=2, n_b=255, steps=1, seed=654)
+    print("case", w, flush=True)
+    gc, oc = pu.make_pair(w.B, w.H_kv, w.H_q, w.bits, w.group, w.outlier_ppm, 255, w.n, 3, 4)
+    pu.compress_both(gc, oc, gw.make_keys(w, w.n, 0, DEV), gw.make_values(w, w.n, 0, DEV), 4, 3, gw.make_init_B(w, 4, 0, DEV))
+    for j, nj in enumerate((255, 129, 20)):
+        pu.compress_both(gc, oc, gw.make_keys(w, nj, 1 + j, DEV), gw.make_values(w, nj, 1 + j, DEV), 2, 3,
+                         gw.make_init_B(w, 2, 1 + j, DEV))
+    rep = pu.compare_components(gc, oc)
+    rep.update(pu.compare_decompress(gc, oc))
+    Kb, Vb = gw.make_keys(w, 255, 50, DEV), gw.make_values(w, 255, 50, DEV)
+    q = gw.make_queries(w, 0, DEV)
+    for n_buf in (255, 128, 1):
+        r = pu.compare_attention(gc, oc, q, Kb, Vb, n_buf)
+        rep["attn_bar_used_%d" % n_buf] = r["attn_bar_used"]
+    print("  ->", rep, flush=True)
