@@ -67,6 +67,10 @@ def emulator(tmp_path_factory):
     (1, 2, 2, 200, 4, 32, 30000, 2, 3, False, 20, 20),     # two KV heads by the same kernel, 4-bit codes, groups of 32
     (1, 1, 2, 70, 2, 64, 20000, 2, 255, False, 255, 255),  # the largest streaming buffer: 255 live rows, a flushed
                                                            # segment of 255 tokens (two 128-row pieces in the decode kernel)
+    (1, 2, 8, 1100, 2, 128, 10000, 8, 7, False, 20, 20),   # n > 1024: Key vectors selected in registers; rank 8, four
+                                                           # query heads per KV head, groups of 128
+    (1, 1, 8, 150, 4, 64, 20000, 3, 4, False, 33, 40),     # eight query heads per KV head, a rank that is not one read
+                                                           # (factor rows staged in LDS), a flushed segment of 33 tokens
 ])
 def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits, g, ppm, rank, n_buf, per_head, chunk_n, n_b):
     w = gw.Workload("emu", B=B, H_kv=H, H_q=Hq, n=n, bits=bits, group=g, outlier_ppm=ppm, rank=rank,
