@@ -1,5 +1,5 @@
 // Runs the library's C ABI end to end on the CPU emulation: prefill compress, chunk compresses,
-// decode attention, decompress.  Inputs and outputs are raw files in the directory given as argv[1]
+// decode attention (one and two query rows), decompress, the canonical views.  Inputs and outputs are raw files in the directory given as argv[1]
 // (written and read by tests/test_cpu_emulation.py).
 // Plain C I/O only, so a memory-sanitizer build sees no uninstrumented C++ library code.
 #include <stdio.h>
@@ -66,6 +66,38 @@ int main(int argc, char** argv) {
     wr(dir, which ? "Vcodes" : "Kcodes", codes, cb);
     wr(dir, which ? "Vscale" : "Kscale", sc, sb);
     wr(dir, which ? "Vzero" : "Kzero", ze, sb);
+  }
+  // the sparse matrix S: dense mask + values, and the coordinate form
+  for (int which = 0; which < 2; ++which) {
+    const size_t eb = (size_t)B * H * ntot * 128;
+    void *mask = aligned_alloc(256, (eb + 255) / 256 * 256), *vals = aligned_alloc(256, (2 * eb + 255) / 256 * 256);
+    CK(gear_export_sparse(&cache, which, mask, vals, nullptr));
+    wr(dir, which ? "Vmask" : "Kmask", mask, eb);
+    wr(dir, which ? "Vsvals" : "Ksvals", vals, 2 * eb);
+    int64_t nnz = 0;
+    CK(gear_export_sparse_coo(&cache, which, &nnz, nullptr, nullptr, nullptr, 0, nullptr));   // the count alone
+    void *lin = aligned_alloc(256, ((size_t)nnz * 8 + 255) / 256 * 256 + 256), *cv = aligned_alloc(256, ((size_t)nnz * 2 + 255) / 256 * 256 + 256);
+    CK(gear_export_sparse_coo(&cache, which, &nnz, lin, cv, work, wb, nullptr));
+    wr(dir, which ? "Vcoo_idx" : "Kcoo_idx", lin, (size_t)nnz * 8);
+    wr(dir, which ? "Vcoo_val" : "Kcoo_val", cv, (size_t)nnz * 2);
+  }
+  // the prefill segment's low-rank factors
+  if (rank > 0) {
+    for (int which = 0; which < 2; ++which) {
+      const size_t abytes = (size_t)B * H * n * rank * 2, bbytes = (size_t)B * H * 128 * rank * 2;
+      void *A = aligned_alloc(256, (abytes + 255) / 256 * 256), *Bf = aligned_alloc(256, (bbytes + 255) / 256 * 256);
+      CK(gear_export_lowrank(&cache, which, 0, A, Bf, nullptr));
+      wr(dir, which ? "V_A" : "K_A", A, abytes);
+      wr(dir, which ? "V_B" : "K_B", Bf, bbytes);
+    }
+  }
+  // two query rows per head over the same cache (where the kernel has the columns for them), causal
+  if (2 * (Hq / H) <= 8 && n_buf >= 2) {
+    void* q2 = rd(dir, "q2", -1);
+    void* out2 = aligned_alloc(256, (2 * ob + 255) / 256 * 256);
+    fprintf(stderr, "decode two query rows\n");
+    CK(gear_decode_attn_mq(&cache, q2, 2, 1, Kb, Vb, n_buf, out2, work, wb, nullptr));
+    wr(dir, "out2", out2, 2 * ob);
   }
   fprintf(stderr, "done\n");
   return 0;

@@ -89,6 +89,8 @@ def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits,
     q, Kb, Vb = a(gw.make_queries(w, 0)), a(gw.make_keys(w, n_b, 50)), a(gw.make_values(w, n_b, 50))
     for name, x in (("q", q), ("Kb", Kb), ("Vb", Vb)):
         x.tofile(os.path.join(d, name + ".bin"))
+    q2 = np.stack([q[:, :, 0], a(gw.make_queries(w, 1))[:, :, 0]], axis=2)       # two query rows per head
+    q2.tofile(os.path.join(d, "q2.bin"))
     with open(os.path.join(d, "meta.txt"), "w") as f:
         f.write(" ".join(str(x) for x in [B, H, Hq, bits, g, ppm, n, rank, 1, chunk_n, 2, n_buf, n_b, 3, 1 if per_head else 0]) + "\n")
     r = subprocess.run([emulator, d], capture_output=True, text=True, timeout=900,
@@ -114,3 +116,25 @@ def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits,
         assert np.array_equal(scale.view(np.uint16), o_scale.view(np.uint16)), name
         assert np.array_equal(zero.astype(np.float32), o_zero.astype(np.float32)), name
         assert np.array_equal(codes, o_codes), name
+        # the sparse matrix: support and values bit for bit, as a dense view and in coordinate form
+        o_mask = np.concatenate([s.mask for s in segs], axis=2)
+        o_vals = np.concatenate([s.svals for s in segs], axis=2)
+        mask = np.fromfile(os.path.join(d, name + "mask.bin"), np.uint8).reshape(o_mask.shape).astype(bool)
+        vals = np.fromfile(os.path.join(d, name + "svals.bin"), np.uint16).reshape(o_mask.shape)
+        assert np.array_equal(mask, o_mask), name
+        assert np.array_equal(vals[o_mask], o_vals.view(np.uint16)[o_mask]) and not vals[~o_mask].any(), name
+        want = np.flatnonzero(o_mask)
+        assert np.array_equal(np.fromfile(os.path.join(d, name + "coo_idx.bin"), np.int64), want), name
+        assert np.array_equal(np.fromfile(os.path.join(d, name + "coo_val.bin"), np.uint16),
+                              o_vals.view(np.uint16).reshape(-1)[want]), name
+    # the exported factors of the prefill segment give the oracle's low-rank product (bar of the GPU tests)
+    if rank > 0:
+        for name, seg in (("K", oc.K[0]), ("V", oc.V[0])):
+            A = np.fromfile(os.path.join(d, name + "_A.bin"), np.float16).reshape(B, H, n, rank).astype(np.float64)
+            Bf = np.fromfile(os.path.join(d, name + "_B.bin"), np.float16).reshape(B, H, 128, rank).astype(np.float64)
+            got = A @ np.swapaxes(Bf, -1, -2)
+            want = seg.A.astype(np.float64) @ np.swapaxes(seg.Bf.astype(np.float64), -1, -2)
+            assert np.linalg.norm(got - want) <= pu.LOWRANK_REL_TOL * np.linalg.norm(want), name
+    if 2 * (Hq // H) <= 8 and n_buf >= 2:
+        out2 = np.fromfile(os.path.join(d, "out2.bin"), np.float16).reshape(B, Hq, 2, 128)
+        pu.check_attention(out2, go.decode_attn_multi(oc, q2, Kb, Vb, n_buf, True), "two query rows")
