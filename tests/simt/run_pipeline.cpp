@@ -22,10 +22,10 @@ static void wr(const char* dir, const char* name, const void* v, size_t bytes) {
 #define CK(x) do { int s_ = (x); if (s_ != GEAR_OK) { fprintf(stderr, "%s -> %s\n", #x, gear_strerror(s_)); return 3; } } while (0)
 int main(int argc, char** argv) {
   const char* dir = argv[1];
-  int B, H, Hq, bits, g, ppm, n, rank, nchunks, chunk_n, rank_chunk, n_buf, n_buf_cap, iters, flags = 0;
+  int B, H, Hq, bits, g, ppm, n, rank, nchunks, chunk_n, rank_chunk, n_buf, n_buf_cap, iters, flags = 0, n_lowrank = -1;
   char p[512]; snprintf(p, sizeof p, "%s/meta.txt", dir);
   FILE* f = fopen(p, "r");
-  if (fscanf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &B, &H, &Hq, &bits, &g, &ppm, &n, &rank, &nchunks, &chunk_n, &rank_chunk, &n_buf, &n_buf_cap, &iters, &flags) < 14) return 1;
+  if (fscanf(f, "%d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &B, &H, &Hq, &bits, &g, &ppm, &n, &rank, &nchunks, &chunk_n, &rank_chunk, &n_buf, &n_buf_cap, &iters, &flags, &n_lowrank) < 14) return 1;
   fclose(f);
   gear_config cfg{B, H, Hq, 128, bits, g, ppm, n_buf_cap, n, nchunks > 0 ? nchunks : 1, rank > rank_chunk ? rank : rank_chunk, flags};
   size_t ab = 0, wb = 0;
@@ -39,7 +39,10 @@ int main(int argc, char** argv) {
   CK(gear_cache_init(&cfg, arena, ab, &cache));
   void *K = rd(dir, "K", -1), *V = rd(dir, "V", -1), *ib = rd(dir, "ib", -1);
   fprintf(stderr, "compress prefill n=%d\n", n);
-  CK(gear_compress(&cache, K, V, n, rank, iters, rank ? (const float*)ib : nullptr, 0, work, wb, nullptr));
+  if (n_lowrank >= 0)   // the low-rank term on the most recent n_lowrank tokens of the call only
+    CK(gear_compress_recent(&cache, K, V, n, rank, iters, rank ? (const float*)ib : nullptr, 0, n_lowrank, work, wb, nullptr));
+  else
+    CK(gear_compress(&cache, K, V, n, rank, iters, rank ? (const float*)ib : nullptr, 0, work, wb, nullptr));
   for (int j = 0; j < nchunks; ++j) {
     void *Kc = rd(dir, "Kc", j), *Vc = rd(dir, "Vc", j), *ibc = rd(dir, "ibc", j);
     fprintf(stderr, "compress chunk %d n=%d\n", j, chunk_n);

@@ -60,19 +60,21 @@ def emulator(tmp_path_factory):
     return exe
 
 
-@pytest.mark.parametrize("B,H,Hq,n,bits,g,ppm,rank,n_buf,per_head,chunk_n,n_b", [
-    (1, 4, 8, 290, 2, 64, 20000, 4, 5, False, 20, 20),     # the method as stated; n > 256: Gram-matrix power iteration
-    (1, 2, 2, 140, 4, 0, 30000, 2, 3, True, 20, 20),       # per-vector groups and the per-head Value Filter
-    (1, 8, 8, 70, 2, 64, 20000, 2, 3, False, 20, 20),      # eight KV heads: Value token rows of 1024 entries, four per wave
-    (1, 2, 2, 200, 4, 32, 30000, 2, 3, False, 20, 20),     # two KV heads by the same kernel, 4-bit codes, groups of 32
-    (1, 1, 2, 70, 2, 64, 20000, 2, 255, False, 255, 255),  # the largest streaming buffer: 255 live rows, a flushed
+@pytest.mark.parametrize("B,H,Hq,n,bits,g,ppm,rank,n_buf,per_head,chunk_n,n_b,n_lowrank", [
+    (1, 4, 8, 290, 2, 64, 20000, 4, 5, False, 20, 20, -1),     # the method as stated; n > 256: Gram-matrix power iteration
+    (1, 2, 2, 140, 4, 0, 30000, 2, 3, True, 20, 20, -1),       # per-vector groups and the per-head Value Filter
+    (1, 8, 8, 70, 2, 64, 20000, 2, 3, False, 20, 20, -1),      # eight KV heads: Value token rows of 1024 entries, four per wave
+    (1, 2, 2, 200, 4, 32, 30000, 2, 3, False, 20, 20, -1),     # two KV heads by the same kernel, 4-bit codes, groups of 32
+    (1, 1, 2, 70, 2, 64, 20000, 2, 255, False, 255, 255, -1),  # the largest streaming buffer: 255 live rows, a flushed
                                                            # segment of 255 tokens (two 128-row pieces in the decode kernel)
-    (1, 2, 8, 1100, 2, 128, 10000, 8, 7, False, 20, 20),   # n > 1024: Key vectors selected in registers; rank 8, four
+    (1, 2, 8, 1100, 2, 128, 10000, 8, 7, False, 20, 20, -1),   # n > 1024: Key vectors selected in registers; rank 8, four
                                                            # query heads per KV head, groups of 128
-    (1, 1, 8, 150, 4, 64, 20000, 3, 4, False, 33, 40),     # eight query heads per KV head, a rank that is not one read
+    (1, 1, 8, 150, 4, 64, 20000, 3, 4, False, 33, 40, -1),     # eight query heads per KV head, a rank that is not one read
                                                            # (factor rows staged in LDS), a flushed segment of 33 tokens
+    (1, 2, 4, 330, 2, 64, 20000, 4, 6, False, 20, 20, 100),  # the low-rank term on the last 100 of 330 tokens only
 ])
-def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits, g, ppm, rank, n_buf, per_head, chunk_n, n_b):
+def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits, g, ppm, rank, n_buf, per_head, chunk_n, n_b,
+                                          n_lowrank):
     w = gw.Workload("emu", B=B, H_kv=H, H_q=Hq, n=n, bits=bits, group=g, outlier_ppm=ppm, rank=rank,
                     rank_chunk=2, n_b=n_b, steps=1, seed=5)
     d = str(tmp_path)
@@ -81,7 +83,10 @@ def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits,
     K, V, ib = a(gw.make_keys(w, n, 0)), a(gw.make_values(w, n, 0)), a(gw.make_init_B(w, rank, 0))
     for name, x in (("K", K), ("V", V), ("ib", ib)):
         x.tofile(os.path.join(d, name + ".bin"))
-    oc.compress(K, V, rank, 3, ib)
+    if n_lowrank >= 0:
+        oc.compress(K, V, rank, 3, ib, n_lowrank=n_lowrank)
+    else:
+        oc.compress(K, V, rank, 3, ib)
     Kc, Vc, ibc = a(gw.make_keys(w, chunk_n, 1)), a(gw.make_values(w, chunk_n, 1)), a(gw.make_init_B(w, 2, 1))
     for name, x in (("Kc0", Kc), ("Vc0", Vc), ("ibc0", ibc)):
         x.tofile(os.path.join(d, name + ".bin"))
@@ -92,7 +97,7 @@ def test_pipeline_under_address_sanitizer(emulator, tmp_path, B, H, Hq, n, bits,
     q2 = np.stack([q[:, :, 0], a(gw.make_queries(w, 1))[:, :, 0]], axis=2)       # two query rows per head
     q2.tofile(os.path.join(d, "q2.bin"))
     with open(os.path.join(d, "meta.txt"), "w") as f:
-        f.write(" ".join(str(x) for x in [B, H, Hq, bits, g, ppm, n, rank, 1, chunk_n, 2, n_buf, n_b, 3, 1 if per_head else 0]) + "\n")
+        f.write(" ".join(str(x) for x in [B, H, Hq, bits, g, ppm, n, rank, 1, chunk_n, 2, n_buf, n_b, 3, 1 if per_head else 0, n_lowrank]) + "\n")
     r = subprocess.run([emulator, d], capture_output=True, text=True, timeout=900,
                        env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0"))
     assert r.returncode == 0, r.stderr[-4000:]
